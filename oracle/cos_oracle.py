@@ -1,0 +1,196 @@
+"""ctypes front end of the float64 CPU oracle (``cos_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: the tests, the smoke check and the benchmark's
+CPU-baseline leg may import this module; the product path never does.  The
+module holds no arithmetic of its own: every number comes from the C file.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "cos_oracle.c")
+_LIB = os.path.join(_HERE, "libcos_oracle.so")
+
+DTYPE_F32 = 0
+DTYPE_BF16 = 1
+ENSEMBLE = 0
+CONTRASTIVE = 1
+FLAG_RESIDUAL_FALLBACK = 1
+FLAG_TAIL_CLAMP = 2
+
+
+def build(force: bool = True) -> str:
+    """Compile the oracle with gcc (plain C99, OpenMP over batch rows)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-std=c99", "-O2", "-Wall", "-Wextra", "-fopenmp", "-shared", "-fPIC",
+               "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build(force=False)
+        lib = ctypes.CDLL(_LIB)
+        dp = ctypes.POINTER(ctypes.c_double)
+        ip = ctypes.POINTER(ctypes.c_int32)
+        vp = ctypes.c_void_p
+        ci = ctypes.c_int
+        lib.cos_oracle_row_to_f64.argtypes = [vp, ci, ci, dp]
+        lib.cos_oracle_row_to_f64.restype = None
+        lib.cos_oracle_softmax.argtypes = [dp, ci, dp]
+        lib.cos_oracle_softmax.restype = None
+        lib.cos_oracle_combine_ensemble.argtypes = [dp, dp, ci, ci, dp]
+        lib.cos_oracle_combine_ensemble.restype = None
+        lib.cos_oracle_combine_contrastive.argtypes = [dp, dp, ctypes.c_double, ctypes.c_double, ci, dp]
+        lib.cos_oracle_combine_contrastive.restype = ci
+        lib.cos_oracle_accept.argtypes = [ctypes.c_double, ctypes.c_double, ctypes.c_double, dp]
+        lib.cos_oracle_accept.restype = ci
+        lib.cos_oracle_sample_weights.argtypes = [dp, dp, ci, ci, dp]
+        lib.cos_oracle_sample_weights.restype = ctypes.c_double
+        lib.cos_oracle_inverse_cdf.argtypes = [dp, ci, ctypes.c_double, ctypes.c_double,
+                                               ctypes.POINTER(ci), dp, dp]
+        lib.cos_oracle_inverse_cdf.restype = ci
+        lib.cos_oracle_verify.argtypes = [vp, ci, ci, ci, ci, ci, ip, ip, ci, dp, dp, dp, ip, ip,
+                                          dp, dp, dp, dp, dp, dp, ip, ci, ci]
+        lib.cos_oracle_verify.restype = ci
+        lib.cos_oracle_max_threads.argtypes = []
+        lib.cos_oracle_max_threads.restype = ci
+        _lib = lib
+    return _lib
+
+
+def _dp(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def _ip(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+
+
+def _f64(a):
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+# ---- step functions (one vocabulary row each) -----------------------------
+
+def row_to_f64(row: np.ndarray, dtype: int) -> np.ndarray:
+    """Widen one stored row (float32 array, or uint16 array of bf16 bits)."""
+    row = np.ascontiguousarray(row)
+    assert row.dtype == (np.float32 if dtype == DTYPE_F32 else np.uint16)
+    out = np.empty(row.shape[0], dtype=np.float64)
+    _load().cos_oracle_row_to_f64(row.ctypes.data_as(ctypes.c_void_p), dtype, row.shape[0], _dp(out))
+    return out
+
+
+def softmax(l) -> np.ndarray:
+    l = _f64(l)
+    s = np.empty_like(l)
+    _load().cos_oracle_softmax(_dp(l), l.shape[0], _dp(s))
+    return s
+
+
+def combine_ensemble(s, w) -> np.ndarray:
+    s = _f64(s)
+    w = _f64(w)
+    n, V = s.shape
+    assert w.shape == (n,)
+    r = np.empty(V, dtype=np.float64)
+    _load().cos_oracle_combine_ensemble(_dp(s), _dp(w), n, V, _dp(r))
+    return r
+
+
+def combine_contrastive(l_p, l_q, mu: float, alpha_cd: float):
+    l_p = _f64(l_p)
+    l_q = _f64(l_q)
+    V = l_p.shape[0]
+    r = np.empty(V, dtype=np.float64)
+    count = _load().cos_oracle_combine_contrastive(_dp(l_p), _dp(l_q), mu, alpha_cd, V, _dp(r))
+    return r, count
+
+
+def accept(u: float, r_d: float, q_d: float):
+    ratio = ctypes.c_double()
+    acc = _load().cos_oracle_accept(u, r_d, q_d, ctypes.byref(ratio))
+    return bool(acc), ratio.value
+
+
+def sample_weights(r, q, residual: bool):
+    r = _f64(r)
+    q = _f64(q)
+    f = np.empty_like(r)
+    F = _load().cos_oracle_sample_weights(_dp(r), _dp(q), r.shape[0], int(residual), _dp(f))
+    return f, F
+
+
+def inverse_cdf(f, F: float, u: float):
+    f = _f64(f)
+    clamped = ctypes.c_int()
+    lo = ctypes.c_double()
+    hi = ctypes.c_double()
+    tok = _load().cos_oracle_inverse_cdf(_dp(f), f.shape[0], F, u, ctypes.byref(clamped),
+                                         ctypes.byref(lo), ctypes.byref(hi))
+    return tok, bool(clamped.value), lo.value, hi.value
+
+
+# ---- the whole step --------------------------------------------------------
+
+@dataclass
+class OracleResult:
+    status: int
+    accepted_len: np.ndarray      # [B] int32
+    out_tokens: np.ndarray        # [B][gamma+1] int32
+    r_at_draft: np.ndarray        # [B][gamma] float64 (NaN where never reached)
+    q_at_draft: np.ndarray
+    ratio: np.ndarray
+    sample_mass: np.ndarray       # [B]
+    cdf_lo: np.ndarray            # [B]
+    cdf_hi: np.ndarray            # [B]
+    flags: np.ndarray             # [B] int32
+
+
+def verify(logits: np.ndarray, dtype: int, draft_tokens, proposer_idx, mode: int, weights,
+           u_accept, u_resample, all_positions: bool = False, num_threads: int = 0) -> OracleResult:
+    """Run ``cos_oracle_verify``.
+
+    ``logits`` is a host array of shape [n][B][gamma+1][V]: float32, or uint16
+    holding bf16 bit patterns.
+    """
+    logits = np.ascontiguousarray(logits)
+    assert logits.ndim == 4
+    assert logits.dtype == (np.float32 if dtype == DTYPE_F32 else np.uint16), logits.dtype
+    n, B, g1, V = logits.shape
+    gamma = g1 - 1
+    draft_tokens = np.ascontiguousarray(draft_tokens, dtype=np.int32).reshape(B, gamma)
+    proposer_idx = np.ascontiguousarray(proposer_idx, dtype=np.int32).reshape(B)
+    weights = _f64(weights)
+    u_accept = _f64(u_accept).reshape(B, gamma)
+    u_resample = _f64(u_resample).reshape(B)
+    res = OracleResult(
+        status=0,
+        accepted_len=np.full(B, -7, dtype=np.int32),
+        out_tokens=np.full((B, gamma + 1), -7, dtype=np.int32),
+        r_at_draft=np.empty((B, gamma)), q_at_draft=np.empty((B, gamma)), ratio=np.empty((B, gamma)),
+        sample_mass=np.empty(B), cdf_lo=np.empty(B), cdf_hi=np.empty(B),
+        flags=np.zeros(B, dtype=np.int32))
+    res.status = _load().cos_oracle_verify(
+        logits.ctypes.data_as(ctypes.c_void_p), dtype, n, B, gamma, V,
+        _ip(draft_tokens), _ip(proposer_idx), mode, _dp(weights), _dp(u_accept), _dp(u_resample),
+        _ip(res.accepted_len), _ip(res.out_tokens), _dp(res.r_at_draft), _dp(res.q_at_draft),
+        _dp(res.ratio), _dp(res.sample_mass), _dp(res.cdf_lo), _dp(res.cdf_hi), _ip(res.flags),
+        int(all_positions), int(num_threads))
+    return res
+
+
+def max_threads() -> int:
+    return _load().cos_oracle_max_threads()
