@@ -1,0 +1,155 @@
+"""Benchmark of cos_verify on one MI355X.
+
+A step is one cos_verify call (all of softmax statistics, combine, acceptance
+test, first rejection and the residual/bonus draw) on one batch of synthetic
+logits that is already resident in HBM.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E peak
+
+
+def _traffic_from_profiles(workload: str):
+    """HBM bytes per launch measured with rocprofv3 --pmc (committed summary), or None."""
+    path = os.path.join(ROOT, "profiles", f"cos_verify_{workload}_hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        if line.startswith("traffic_bytes_per_launch:"):
+            return float(line.split(":")[1])
+    return None
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c5", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--batch", type=int, default=0, help="override B (debugging only; changes the workload name)")
+    ap.add_argument("--cpu-rows", type=int, default=-1, help="batch rows the CPU oracle is timed on (-1 = auto, 0 = skip)")
+    ap.add_argument("--chunk-vectors", type=int, default=0, help="tuning knob (0 = library heuristic)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (rows of the batch shard without any exchange; "
+              "see DESIGN.md). Re-run with --gpus 1.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2502_01662_amd import cos_verify as C
+    from paper_2502_01662_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: needs a GPU; there is no CPU path", file=sys.stderr)
+        return 2
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    w = W.WORKLOADS[args.workload]
+    if args.batch:
+        w = w.scaled(B=args.batch, name=f"{w.name}_B{args.batch}")
+    C.load_library()
+    C.cos_tune_set_chunk_vectors(args.chunk_vectors)
+
+    t0 = time.time()
+    # small workloads: rotate over distinct input sets so that the timed calls stream from HBM,
+    # not from the 256 MB memory-side cache
+    nsets = max(1, min(64, int(np.ceil(600e6 / w.logit_bytes)))) if w.logit_bytes < 600e6 else 1
+    sets = [W.generate(w, device=dev, step=s) for s in range(nsets)]
+    torch.cuda.synchronize()
+    gen_s = time.time() - t0
+    dt = C.COS_DTYPE_F32 if w.dtype == "f32" else C.COS_DTYPE_BF16
+    ws = C.allocate_workspace(w.n, w.B, w.gamma, w.V, dt, w.mode, dev)
+    alen = torch.empty(w.B, dtype=torch.int32, device=dev)
+    toks = torch.empty((w.B, w.gamma + 1), dtype=torch.int32, device=dev)
+
+    def step(i):
+        s = sets[i % nsets]
+        C.cos_verify(s["logits"], s["draft_tokens"], s["proposer_idx"], w.mode, w.weights,
+                     s["u_accept"], s["u_resample"], accepted_len=alen, out_tokens=toks, workspace=ws)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    C.cos_profile_enable(min(args.steps, 1024))
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    kernel_ms = [C.cos_profile_kernel_ms(i) for i in range(C.cos_profile_recorded())]
+    C.cos_profile_enable(0)
+    ms_per_step = (t2 - t1) * 1e3 / args.steps
+    kavg = float(np.mean(kernel_ms))
+    value = w.positions / (ms_per_step * 1e-3)
+
+    achieved = w.logit_bytes / (kavg * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": "contrastive_kernel" if w.mode == W.CONTRASTIVE else "ensemble_kernel",
+                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": _traffic_from_profiles(args.workload),
+                "algorithmic_bytes_per_launch": w.logit_bytes, "kernel_avg_ms": round(kavg, 5),
+                "kernel_min_ms": round(float(np.min(kernel_ms)), 5)}
+
+    # ---- CPU baseline: the oracle as it stands, on a bounded sample of the same batch ----
+    cpu = None
+    parity = None
+    cpu_rows = args.cpu_rows
+    if cpu_rows < 0:
+        # ~20 s of single-core work: about 35 ns per logit element the sequential procedure touches
+        per_row = w.n * (w.gamma + 1) * w.V * 35e-9
+        cpu_rows = int(max(1, min(w.B, round(20.0 / per_row))))
+    if cpu_rows > 0:
+        from oracle import cos_oracle as O
+        s = sets[0]
+        rows = np.unique(np.linspace(0, w.B - 1, cpu_rows).round().astype(int))
+        sel = torch.as_tensor(rows, device=dev)
+        lg = W.host_logits(s["logits"][:, sel].contiguous())
+        odt = O.DTYPE_F32 if w.dtype == "f32" else O.DTYPE_BF16
+        hd, hp = s["draft_tokens"][sel].cpu().numpy(), s["proposer_idx"][sel].cpu().numpy()
+        hua, hur = s["u_accept"][sel].cpu().numpy(), s["u_resample"][sel].cpu().numpy()
+        threads = O.max_threads()
+        c0 = time.perf_counter()
+        res = O.verify(lg, odt, hd, hp, w.mode, list(w.weights), hua, hur, all_positions=False, num_threads=threads)
+        c1 = time.perf_counter()
+        assert res.status == 0
+        cpu = {"value": round(len(rows) * w.gamma / (c1 - c0), 2), "unit": "positions/s",
+               "cores": int(min(threads, len(rows))), "kind": "oracle",
+               "sample": f"{len(rows)} of {w.B} batch rows of {w.name} (float64 C oracle, OpenMP over rows, "
+                         f"stops at the first rejection), {c1 - c0:.2f} s wall",
+               "host_cpus": os.cpu_count()}
+        step(0)
+        torch.cuda.synchronize()
+        ga, gt = alen.cpu().numpy()[rows], toks.cpu().numpy()[rows]
+        exact = int(np.sum((ga == res.accepted_len) & np.all(gt == res.out_tokens, axis=1)))
+        parity = {"rows": int(len(rows)), "bit_exact_rows": exact}
+
+    out = {
+        "metric": "verified positions/sec + achieved HBM GB/s of cos_verify (bf16 logits, 1 GPU)",
+        "value": round(value, 1), "unit": "positions/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32",
+        "logit_storage": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "n": w.n, "B": w.B, "gamma": w.gamma, "V": w.V,
+                   "combine": "contrastive" if w.mode == W.CONTRASTIVE else "ensemble", "weights": list(w.weights),
+                   "input_sets_rotated": nsets, "chunk_vectors": args.chunk_vectors},
+        "achieved_hbm_gbs_per_step": round(w.logit_bytes / (ms_per_step * 1e-3) / 1e9, 1),
+        "roofline": roofline, "cpu_baseline": cpu, "parity_sample": parity,
+        "input_generation_s": round(gen_s, 1),
+    }
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

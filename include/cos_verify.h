@@ -1,0 +1,141 @@
+/*
+ * cos_verify.h -- C ABI of the MI355X (gfx950) batched verification step of
+ * Collaborative decoding via Speculation (CoS).
+ *
+ * One call verifies, for B sequences at once, gamma draft tokens per sequence
+ * against the combined distribution r of n collaborating models and emits the
+ * accepted prefix plus one sampled token:
+ *
+ *   s_m   = softmax(l_m)                         Sec. 3.2 (temperature 1)
+ *   r     = sum_m w_m s_m                        Eq. (4), n-model coefficients as
+ *                                                in Sec. 4.1 / Alg. 2, or
+ *   r     = Softmax(l_0 - mu l_1) on the mask    Eq. (5) plus a plausibility mask
+ *           {x : s_0(x) >= alpha_cd max s_0}     (alpha_cd = 0: Eq. (5) exactly)
+ *   q     = s_{proposer_idx[b]}                  the row's current proposer
+ *   accept draft d_j  iff  u_j < min(1, r(d_j)/q(d_j))        Eq. (2) / Eq. (6)
+ *   first rejected position j*: token ~ norm(max(0, r - q))   Sec. 3.1-3.2, App. A.1
+ *   no rejection: j* = gamma, bonus token ~ r at position gamma   Sec. 3.1
+ *   draws are by inverse CDF in ascending token index: the smallest k with
+ *   sum_{x<=k} f(x) > u_resample * sum_x f(x).
+ *
+ * All pointers are plain device or host pointers as stated per argument; the
+ * caller owns every buffer.  Nothing here allocates device memory.  Calls are
+ * asynchronous on the given HIP stream.
+ */
+#ifndef COS_VERIFY_H_
+#define COS_VERIFY_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { COS_DTYPE_F32 = 0, COS_DTYPE_BF16 = 1 } cos_dtype_t;
+
+typedef enum { COS_COMBINE_ENSEMBLE = 0, COS_COMBINE_CONTRASTIVE = 1 } cos_combine_t;
+
+typedef enum {
+  COS_OK = 0,
+  COS_ERR_NULL = -1,        /* a required pointer is NULL */
+  COS_ERR_SHAPE = -2,       /* n, B, gamma or V out of the supported range */
+  COS_ERR_DTYPE = -3,
+  COS_ERR_MODE = -4,        /* unknown combine mode, or contrastive with n != 2 */
+  COS_ERR_WEIGHTS = -5,     /* ensemble: w < 0 or |sum w - 1| > 1e-9; contrastive: mu not finite or alpha_cd outside [0,1] */
+  COS_ERR_WORKSPACE = -6,   /* workspace NULL, misaligned (256 B) or smaller than cos_verify_workspace_bytes() */
+  COS_ERR_ALIGN = -7,       /* logits pointer not aligned to its element size */
+  COS_ERR_LAUNCH = -8,      /* a HIP call failed (no usable GPU, launch error) */
+  COS_ERR_UNSUPPORTED = -9
+} cos_status_t;
+
+/* Supported ranges: 1 <= n <= COS_MAX_MODELS, 1 <= gamma <= COS_MAX_GAMMA,
+ * 1 <= V <= COS_MAX_VOCAB, B >= 0 (B == 0 is a no-op).                      */
+#define COS_MAX_MODELS 8
+#define COS_MAX_GAMMA 31
+#define COS_MAX_VOCAB 1048576
+
+/* Flags written to cos_diag_t.flags. */
+#define COS_FLAG_RESIDUAL_FALLBACK 1 /* residual mass was <= 0 or not finite: token drawn from r instead */
+#define COS_FLAG_TAIL_CLAMP 2        /* rounding left no prefix above u*F: last token with mass taken */
+
+/* Optional per-row diagnostics; every member is a DEVICE pointer or NULL. */
+typedef struct cos_diag_t {
+  double *r_at_draft;  /* [B][gamma]  r(d_{b,j}) for every position (not only up to j*) */
+  double *q_at_draft;  /* [B][gamma]  q(d_{b,j}) */
+  double *sample_mass; /* [B]         F = sum_x f(x) of the sampled position */
+  double *cdf_lo;      /* [B]         normalised CDF just below the drawn token */
+  double *cdf_hi;      /* [B]         normalised CDF just above the drawn token */
+  int32_t *flags;      /* [B]         COS_FLAG_* bits */
+} cos_diag_t;
+
+/* Bytes of device scratch cos_verify needs for this shape (0 on invalid
+ * arguments).  Host-only computation; needs no GPU.                        */
+size_t cos_verify_workspace_bytes(int n, int B, int gamma, int V, cos_dtype_t dt,
+                                  cos_combine_t mode);
+
+/*
+ * The verification step (VERIFY of Alg. 1 / Alg. 2; Eq. (2)-(6), App. A.1).
+ *
+ * logits        DEVICE, [n][B][gamma+1][V] contiguous (V fastest), dtype dt.
+ *               Position gamma is the bonus position.  -inf entries are legal
+ *               (probability 0); NaN or +inf entries give undefined outputs
+ *               but never an out-of-bounds access or a hang.
+ * draft_tokens  DEVICE, [B][gamma] int32, each in [0, V) (caller's contract).
+ * proposer_idx  DEVICE, [B] int32, each in [0, n): whose softmax is q.
+ * combine_mode  ensemble or contrastive.
+ * weights       HOST.  ensemble: w[0..n-1].  contrastive (n must be 2; model 0
+ *               is the expert l^p, model 1 the amateur l^q): weights[0] = mu,
+ *               weights[1] = alpha_cd in [0,1].
+ * u_accept      DEVICE, [B][gamma] float64 in [0,1).
+ * u_resample    DEVICE, [B] float64 in [0,1): used for the one draw of the row
+ *               (residual or bonus).
+ * accepted_len  DEVICE out, [B] int32 in [0, gamma].
+ * out_tokens    DEVICE out, [B][gamma+1] int32: accepted drafts, the drawn
+ *               token at index accepted_len[b], then -1.
+ * workspace     DEVICE scratch, 256-byte aligned, at least
+ *               cos_verify_workspace_bytes() bytes, contents arbitrary on
+ *               entry; two calls that overlap in time need distinct ones.
+ * diag          HOST pointer to a struct of device pointers, or NULL.
+ * hip_stream    hipStream_t (NULL = the default stream).
+ *
+ * Host-side validation only; returns COS_OK once every kernel is enqueued.
+ * Out-of-range tokens or proposer indices are undefined behaviour.
+ */
+cos_status_t cos_verify(const void *logits, cos_dtype_t dt, int n, int B, int gamma, int V,
+                        const int32_t *draft_tokens, const int32_t *proposer_idx,
+                        cos_combine_t combine_mode, const double *weights,
+                        const double *u_accept, const double *u_resample,
+                        int32_t *accepted_len, int32_t *out_tokens, void *workspace,
+                        size_t workspace_bytes, const cos_diag_t *diag, void *hip_stream);
+
+/* Static, NUL-terminated description of a status code. */
+const char *cos_status_string(cos_status_t status);
+
+/* ABI version of this library (bumped on incompatible changes). */
+int cos_verify_version(void);
+
+/*
+ * Optional timing of the streaming kernel (the one that reads every logit),
+ * for benchmarks.  cos_profile_enable(slots) with 1 <= slots <= 1024 makes
+ * each following cos_verify call record a HIP event pair around that kernel
+ * on the call's stream, into slot (call number mod slots); slots == 0 turns
+ * it off.  cos_profile_recorded() is the number of filled slots, and
+ * cos_profile_kernel_ms(i, &ms) waits for slot i's stop event and returns the
+ * elapsed milliseconds.  Process-wide state; not thread-safe; off by default.
+ */
+cos_status_t cos_profile_enable(int slots);
+int cos_profile_recorded(void);
+cos_status_t cos_profile_kernel_ms(int index, float *ms);
+
+/*
+ * Tuning knob for experiments: vectors (16-byte units) of one logit row that
+ * one workgroup of the streaming kernel reduces.  0 restores the built-in
+ * heuristic.  Process-wide; results do not depend on it beyond rounding order.
+ */
+void cos_tune_set_chunk_vectors(int vectors);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* COS_VERIFY_H_ */

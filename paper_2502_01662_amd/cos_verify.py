@@ -1,0 +1,186 @@
+"""Thin ctypes binding of ``libcosverify.so`` (argument marshalling only).
+
+Every step of the verification runs in the HIP kernels behind the C ABI of
+``include/cos_verify.h``; PyTorch only provides device memory and the stream.
+There is no CPU fallback: a missing library or GPU raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional, Sequence
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIBRARY = os.path.join(_PKG, "libcosverify.so")
+
+COS_DTYPE_F32 = 0
+COS_DTYPE_BF16 = 1
+COS_COMBINE_ENSEMBLE = 0
+COS_COMBINE_CONTRASTIVE = 1
+COS_OK = 0
+COS_FLAG_RESIDUAL_FALLBACK = 1
+COS_FLAG_TAIL_CLAMP = 2
+
+
+class CosDiag(ctypes.Structure):
+    _fields_ = [("r_at_draft", ctypes.c_void_p), ("q_at_draft", ctypes.c_void_p),
+                ("sample_mass", ctypes.c_void_p), ("cdf_lo", ctypes.c_void_p),
+                ("cdf_hi", ctypes.c_void_p), ("flags", ctypes.c_void_p)]
+
+
+class CosVerifyError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"cos_verify failed: {message} (status {status})")
+        self.status = status
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load the in-tree library; build it first if it was never built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIBRARY):
+            from .build import build_library
+            build_library()
+        lib = ctypes.CDLL(LIBRARY)
+        vp, ci, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+        lib.cos_verify_workspace_bytes.argtypes = [ci, ci, ci, ci, ci, ci]
+        lib.cos_verify_workspace_bytes.restype = sz
+        lib.cos_verify.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp, ci, ctypes.POINTER(ctypes.c_double),
+                                   vp, vp, vp, vp, vp, sz, ctypes.POINTER(CosDiag), vp]
+        lib.cos_verify.restype = ci
+        lib.cos_status_string.argtypes = [ci]
+        lib.cos_status_string.restype = ctypes.c_char_p
+        lib.cos_verify_version.argtypes = []
+        lib.cos_verify_version.restype = ci
+        lib.cos_profile_enable.argtypes = [ci]
+        lib.cos_profile_enable.restype = ci
+        lib.cos_profile_recorded.argtypes = []
+        lib.cos_profile_recorded.restype = ci
+        lib.cos_profile_kernel_ms.argtypes = [ci, ctypes.POINTER(ctypes.c_float)]
+        lib.cos_profile_kernel_ms.restype = ci
+        lib.cos_tune_set_chunk_vectors.argtypes = [ci]
+        lib.cos_tune_set_chunk_vectors.restype = None
+        _lib = lib
+    return _lib
+
+
+def cos_status_string(status: int) -> str:
+    return load_library().cos_status_string(status).decode()
+
+
+def cos_verify_version() -> int:
+    return load_library().cos_verify_version()
+
+
+def cos_verify_workspace_bytes(n: int, B: int, gamma: int, V: int, dt: int, mode: int) -> int:
+    return load_library().cos_verify_workspace_bytes(n, B, gamma, V, dt, mode)
+
+
+def cos_profile_enable(slots: int) -> None:
+    st = load_library().cos_profile_enable(int(slots))
+    if st != COS_OK:
+        raise CosVerifyError(st, cos_status_string(st))
+
+
+def cos_profile_recorded() -> int:
+    return load_library().cos_profile_recorded()
+
+
+def cos_profile_kernel_ms(index: int) -> float:
+    ms = ctypes.c_float()
+    st = load_library().cos_profile_kernel_ms(int(index), ctypes.byref(ms))
+    if st != COS_OK:
+        raise CosVerifyError(st, cos_status_string(st))
+    return ms.value
+
+
+def cos_tune_set_chunk_vectors(vectors: int) -> None:
+    load_library().cos_tune_set_chunk_vectors(int(vectors))
+
+
+@dataclass
+class Diagnostics:
+    r_at_draft: torch.Tensor
+    q_at_draft: torch.Tensor
+    sample_mass: torch.Tensor
+    cdf_lo: torch.Tensor
+    cdf_hi: torch.Tensor
+    flags: torch.Tensor
+
+    @staticmethod
+    def allocate(B: int, gamma: int, device) -> "Diagnostics":
+        f64 = dict(dtype=torch.float64, device=device)
+        return Diagnostics(torch.zeros((B, gamma), **f64), torch.zeros((B, gamma), **f64),
+                           torch.zeros(B, **f64), torch.zeros(B, **f64), torch.zeros(B, **f64),
+                           torch.zeros(B, dtype=torch.int32, device=device))
+
+    def as_struct(self) -> CosDiag:
+        return CosDiag(self.r_at_draft.data_ptr(), self.q_at_draft.data_ptr(), self.sample_mass.data_ptr(),
+                       self.cdf_lo.data_ptr(), self.cdf_hi.data_ptr(), self.flags.data_ptr())
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return COS_DTYPE_F32
+    if t.dtype == torch.bfloat16:
+        return COS_DTYPE_BF16
+    raise TypeError(f"logits must be float32 or bfloat16, got {t.dtype}")
+
+
+def allocate_workspace(n: int, B: int, gamma: int, V: int, dt: int, mode: int, device) -> torch.Tensor:
+    nbytes = cos_verify_workspace_bytes(n, B, gamma, V, dt, mode)
+    if nbytes == 0:
+        raise CosVerifyError(-2, "unsupported shape")
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+def cos_verify(logits: torch.Tensor, draft_tokens: torch.Tensor, proposer_idx: torch.Tensor,
+               combine_mode: int, weights: Sequence[float], u_accept: torch.Tensor,
+               u_resample: torch.Tensor, accepted_len: Optional[torch.Tensor] = None,
+               out_tokens: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+               diag: Optional[Diagnostics] = None):
+    """Enqueue one verification step on the current stream; returns (accepted_len, out_tokens).
+
+    logits [n][B][gamma+1][V] (float32 or bfloat16), draft_tokens [B][gamma] int32,
+    proposer_idx [B] int32, u_accept [B][gamma] float64, u_resample [B] float64:
+    all contiguous tensors on one GPU.  ``weights`` is a host sequence.
+    """
+    lib = load_library()
+    if not logits.is_cuda:
+        raise CosVerifyError(-8, "logits must live on the GPU: there is no CPU path")
+    n, B, g1, V = logits.shape
+    gamma = g1 - 1
+    dev = logits.device
+    dt = _dtype_code(logits)
+    for name, t, dtype, shape in (("draft_tokens", draft_tokens, torch.int32, (B, gamma)),
+                                  ("proposer_idx", proposer_idx, torch.int32, (B,)),
+                                  ("u_accept", u_accept, torch.float64, (B, gamma)),
+                                  ("u_resample", u_resample, torch.float64, (B,))):
+        if t.dtype != dtype or tuple(t.shape) != shape or not t.is_contiguous() or t.device != dev:
+            raise TypeError(f"{name}: want contiguous {dtype} {shape} on {dev}")
+    if not logits.is_contiguous():
+        raise TypeError("logits must be contiguous")
+    if accepted_len is None:
+        accepted_len = torch.empty(B, dtype=torch.int32, device=dev)
+    if out_tokens is None:
+        out_tokens = torch.empty((B, g1), dtype=torch.int32, device=dev)
+    if workspace is None:
+        workspace = allocate_workspace(n, B, gamma, V, dt, combine_mode, dev)
+    w = (ctypes.c_double * max(len(weights), 1))(*[float(x) for x in weights])
+    dstruct = diag.as_struct() if diag is not None else None
+    stream = torch.cuda.current_stream(dev).cuda_stream
+    with torch.cuda.device(dev):
+        st = lib.cos_verify(logits.data_ptr(), dt, n, B, gamma, V, draft_tokens.data_ptr(),
+                            proposer_idx.data_ptr(), combine_mode, w, u_accept.data_ptr(),
+                            u_resample.data_ptr(), accepted_len.data_ptr(), out_tokens.data_ptr(),
+                            workspace.data_ptr(), workspace.numel(),
+                            ctypes.byref(dstruct) if dstruct is not None else None, stream)
+    if st != COS_OK:
+        raise CosVerifyError(st, cos_status_string(st))
+    return accepted_len, out_tokens

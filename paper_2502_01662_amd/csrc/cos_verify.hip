@@ -1,0 +1,1100 @@
+// cos_verify.hip -- gfx950 kernels and C ABI of the CoS verification step.
+//
+// Structure (one GPU, one HIP stream, no host round trip):
+//
+//   fill kernel         zeroes the per-sequence arrival counters in the workspace
+//   streaming kernel    one workgroup per chunk of one logit row; reads every
+//                       logit exactly once and reduces it to a partial
+//                       (offset, sum 2^(l*log2e - offset)) softmax statistic
+//                       (Sec. 3.2).  Workgroups are ordered sequence-major, so
+//                       a sequence's rows stream through the chip together.
+//   finalize (same      the workgroup that completes a sequence (last arrival on
+//   kernel launch)      its counter) combines the partials in float64, runs the
+//                       acceptance test of Eq. (6) for the gamma drafts, finds the
+//                       first rejection (Sec. 3.1), then re-reads only the n rows
+//                       of that one position -- still resident in the memory-side
+//                       cache -- to build tile sums of f = max(0, r - q)
+//                       (App. A.1) or f = r (bonus), scans them and locates the
+//                       token by inverse CDF.
+//
+// Contrastive mode (Eq. (5) with a plausibility mask) needs the expert row's
+// maximum before anything can be masked, so a row-max kernel runs first.
+//
+// Numerics: per-element work is float32 (v_exp_f32); all offsets are integers
+// in the log2 domain so that rescaling is exact; every cross-lane, cross-wave
+// and cross-workgroup combine, r(d), q(d), the accept decision, tile sums, the
+// scan and the CDF comparison are float64.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+#include <cstdlib>
+
+#include "cos_verify.h"
+
+namespace {
+
+constexpr int kThreads = 256;            // 4 wavefronts of 64 lanes
+constexpr int kWaves = kThreads / 64;
+constexpr int kUnroll = 8;               // 16-byte loads in flight per lane and iteration
+constexpr float kLog2e = 1.44269504088896340736f;
+constexpr int kNoOffset = -(1 << 29);    // "no finite element seen yet"
+constexpr float kMaxOffset = 268435456.0f;  // 2^28: clamp for absurd logits
+constexpr int kMaxSplits = 128;          // upper bound on chunks per row (workspace sizing)
+constexpr int kMaxStatsPerSeq = 256;     // (gamma+1) * statistics per position
+
+// One partial softmax statistic: Z = sum_x 2^(l(x)*log2e - o) over a chunk.
+struct Partial {
+  double Z;
+  int o;
+  int pad;
+};
+
+struct Params {
+  const void* logits;
+  int n, B, gamma, V;
+  const int* draft;
+  const int* proposer;
+  const double* u_accept;
+  const double* u_resample;
+  int* accepted_len;
+  int* out_tokens;
+  // workspace
+  int* counters;      // [B]
+  Partial* partials;  // [B][gamma+1][nstat][S]
+  float* rowmax;      // contrastive: [B][gamma+1][S] partial maxima of the expert row
+  int S;              // chunks per row
+  int cv;             // vectors per chunk
+  int nvec;           // 16-byte vectors per row (last may be partial when unaligned)
+  int ntiles;         // tiles (64 vectors) per row
+  int nstat;          // statistics per position: n (ensemble) or 3 (contrastive)
+  double w[COS_MAX_MODELS];  // ensemble weights; contrastive: w[0] = mu, w[1] = alpha_cd
+  float mu_hi, mu_lo;        // mu split into two floats
+  float thr32;               // smallest float >= ln(alpha_cd)
+  double thr64;              // ln(alpha_cd)
+  cos_diag_t diag;
+  int debug;  // TEMP experiment flags
+};
+
+// ---------------------------------------------------------------------------
+// wavefront primitives
+// ---------------------------------------------------------------------------
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
+
+// max over the 64 lanes, returned wave-uniform.  DPP row shifts reduce each row
+// of 16 lanes into its lane 15, two row broadcasts carry the result to lane 63.
+__device__ __forceinline__ float wave_max(float v) {
+#define COS_DPP_MAX(ctrl, row_mask)                                                        \
+  {                                                                                        \
+    const int t = __builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), ctrl, \
+                                              row_mask, 0xf, false);                      \
+    v = fmaxf(v, __int_as_float(t));                                                       \
+  }
+  COS_DPP_MAX(0x111, 0xf)  // row_shr:1
+  COS_DPP_MAX(0x112, 0xf)  // row_shr:2
+  COS_DPP_MAX(0x114, 0xf)  // row_shr:4
+  COS_DPP_MAX(0x118, 0xf)  // row_shr:8
+  COS_DPP_MAX(0x142, 0xa)  // row_bcast:15 into rows 1 and 3
+  COS_DPP_MAX(0x143, 0xc)  // row_bcast:31 into rows 2 and 3
+#undef COS_DPP_MAX
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+  return v;
+}
+
+__device__ __forceinline__ double wave_inclusive_scan(double v) {
+  const int lane = lane_id();
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const double y = __shfl_up(v, d, 64);
+    if (lane >= d) v += y;
+  }
+  return v;
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// ---------------------------------------------------------------------------
+// 16-byte vector loads of logits, widened to float32
+// ---------------------------------------------------------------------------
+
+template <typename T>
+struct VecOf {
+  static constexpr int N = 16 / sizeof(T);
+};
+
+__device__ __forceinline__ float widen(float x) { return x; }
+__device__ __forceinline__ float widen(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+
+template <typename T>
+__device__ __forceinline__ void unpack(const uint4& raw, float (&x)[VecOf<T>::N]);
+
+template <>
+__device__ __forceinline__ void unpack<float>(const uint4& raw, float (&x)[4]) {
+  x[0] = __uint_as_float(raw.x);
+  x[1] = __uint_as_float(raw.y);
+  x[2] = __uint_as_float(raw.z);
+  x[3] = __uint_as_float(raw.w);
+}
+
+// bf16 is the upper half of a float32; the lower address is the low half-word.
+template <>
+__device__ __forceinline__ void unpack<uint16_t>(const uint4& raw, float (&x)[8]) {
+  x[0] = __uint_as_float(raw.x << 16);
+  x[1] = __uint_as_float(raw.x & 0xffff0000u);
+  x[2] = __uint_as_float(raw.y << 16);
+  x[3] = __uint_as_float(raw.y & 0xffff0000u);
+  x[4] = __uint_as_float(raw.z << 16);
+  x[5] = __uint_as_float(raw.z & 0xffff0000u);
+  x[6] = __uint_as_float(raw.w << 16);
+  x[7] = __uint_as_float(raw.w & 0xffff0000u);
+}
+
+// Vector `vec` of a row.  ALIGNED: the row is 16-byte aligned and V is a
+// multiple of the vector width, so every vector is one full 16-byte load.
+// Otherwise element loads with a bound check; elements past V read as -inf.
+// The caller guarantees 0 <= vec < ceil(V / N).
+template <typename T, bool ALIGNED>
+__device__ __forceinline__ void load_vec(const T* __restrict__ row, int vec, int V,
+                                         float (&x)[VecOf<T>::N]) {
+  constexpr int N = VecOf<T>::N;
+  if constexpr (ALIGNED) {
+    const uint4 raw = *reinterpret_cast<const uint4*>(row + (size_t)vec * N);
+    unpack<T>(raw, x);
+  } else {
+    const int base = vec * N;
+#pragma unroll
+    for (int k = 0; k < N; ++k) x[k] = (base + k < V) ? widen(row[base + k]) : -INFINITY;
+  }
+}
+
+template <typename T>
+__device__ __forceinline__ const T* row_ptr(const Params& p, int m, int b, int j) {
+  const size_t row = ((size_t)m * p.B + b) * (size_t)(p.gamma + 1) + j;
+  return reinterpret_cast<const T*>(p.logits) + row * (size_t)p.V;
+}
+
+// ---------------------------------------------------------------------------
+// streaming softmax statistics (Sec. 3.2)
+// ---------------------------------------------------------------------------
+
+// Running statistic of one wavefront: acc lanes hold sum 2^(l*log2e - o) with a
+// wave-uniform integer offset o >= ceil(max l * log2e) seen so far.
+struct Running {
+  int o;
+  float acc[4];
+};
+
+__device__ __forceinline__ void running_init(Running& r) {
+  r.o = kNoOffset;
+  r.acc[0] = r.acc[1] = r.acc[2] = r.acc[3] = 0.0f;
+}
+
+// Raise the offset to cover a new wave-wide maximum `wm` (wave-uniform).
+// Offsets are integers, so the rescale by 2^(old - new) is exact.
+__device__ __forceinline__ void running_cover(Running& r, float wm) {
+  if (wm > -INFINITY) {
+    float of = ceilf(wm * kLog2e);
+    of = fminf(fmaxf(of, -kMaxOffset), kMaxOffset);
+    const int on = (int)of;
+    if (on > r.o) {
+      const int shift = r.o - on;
+#pragma unroll
+      for (int a = 0; a < 4; ++a) r.acc[a] = ldexpf(r.acc[a], shift);
+      r.o = on;
+    }
+  }
+}
+
+__device__ __forceinline__ double running_total(const Running& r) {
+  const double z = ((double)r.acc[0] + (double)r.acc[1]) + ((double)r.acc[2] + (double)r.acc[3]);
+  return wave_sum(z);
+}
+
+// Statistic of vectors [v0, v1) of one row, per wavefront (all lanes return the
+// wave's values).
+template <typename T, bool ALIGNED>
+__device__ __forceinline__ void chunk_stats(const T* __restrict__ row, int v0, int v1, int V,
+                                            int& o_out, double& z_out) {
+  constexpr int N = VecOf<T>::N;
+  Running run;
+  running_init(run);
+  const int tid = threadIdx.x;
+  for (int base = v0; base < v1; base += kThreads * kUnroll) {
+    float x[kUnroll][N];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const int v = base + u * kThreads + tid;
+      if (v < v1) {
+        load_vec<T, ALIGNED>(row, v, V, x[u]);
+      } else {
+#pragma unroll
+        for (int k = 0; k < N; ++k) x[u][k] = -INFINITY;
+      }
+    }
+    float lm = -INFINITY;
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u)
+#pragma unroll
+      for (int k = 0; k < N; ++k) lm = fmaxf(lm, x[u][k]);
+    running_cover(run, wave_max(lm));
+    const float neg_o = -(float)run.o;
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u)
+#pragma unroll
+      for (int k = 0; k < N; ++k) run.acc[k & 3] += fast_exp2(fmaf(x[u][k], kLog2e, neg_o));
+  }
+  o_out = run.o;
+  z_out = running_total(run);
+}
+
+// Statistics of the wavefronts of a workgroup, combined by thread 0.
+struct WaveStat {
+  double z;
+  int o;
+  int pad;
+};
+
+// ws is [slots][kWaves]; lane 0 of every wavefront publishes its statistic.
+__device__ __forceinline__ void publish_wave_stat(WaveStat* ws, int slot, int o, double z) {
+  const int wave = threadIdx.x >> 6;
+  if (lane_id() == 0) {
+    ws[slot * kWaves + wave].z = z;
+    ws[slot * kWaves + wave].o = o;
+  }
+}
+
+__device__ __forceinline__ Partial block_reduce_slot(const WaveStat* ws, int slot) {
+  int omax = kNoOffset;
+  for (int w = 0; w < kWaves; ++w) {
+    const WaveStat& s = ws[slot * kWaves + w];
+    if (s.z > 0.0 && s.o > omax) omax = s.o;
+  }
+  double z = 0.0;
+  for (int w = 0; w < kWaves; ++w) {
+    const WaveStat& s = ws[slot * kWaves + w];
+    if (s.z > 0.0) z += ldexp(s.z, s.o - omax);
+  }
+  Partial p;
+  p.Z = z;
+  p.o = omax;
+  p.pad = 0;
+  return p;
+}
+
+// Last-arrival test: returns true in every thread of exactly one workgroup per
+// counter, after all `total` workgroups have published their partials.
+__device__ __forceinline__ bool arrive_last(int* counter, int total, int* s_flag, int debug = 0) {
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    if (!(debug & 2)) __threadfence();  // release: this workgroup's partials before the count
+    const int prev = atomicAdd(counter, 1);
+    *s_flag = (prev == total - 1);
+  }
+  __syncthreads();
+  const bool last = *s_flag != 0;
+  if (last) __threadfence();  // acquire: the other workgroups' partials
+  return last;
+}
+
+// ---------------------------------------------------------------------------
+// sampling weights f(x) of one 16-byte vector per model
+// ---------------------------------------------------------------------------
+
+// Ensemble: f = max(0, sum_m a_m 2^(l_m*log2e - K_m)); the a_m carry the
+// ensemble weights, minus one for the proposer when a residual is wanted
+// (App. A.1), times 2^(K_m - log2-sum-exp) so that the K_m are integers.  Each
+// product is rounded before it is added (no fused multiply-add), so that terms
+// of identical models cancel exactly and r == q leaves no residual mass.
+template <int NCAP, int N>
+__device__ __forceinline__ void eval_f_ensemble(const float (&x)[NCAP][N], int n,
+                                                const float* coef, const float* off,
+                                                float (&f)[N]) {
+#pragma unroll
+  for (int k = 0; k < N; ++k) {
+    float s = 0.0f;
+#pragma unroll
+    for (int m = 0; m < NCAP; ++m)
+      if (m < n) s += coef[m] * fast_exp2(fmaf(x[m][k], kLog2e, -off[m]));  // product rounded first
+    f[k] = fmaxf(s, 0.0f);
+  }
+}
+
+// Contrastive logit c = l_0 - mu*l_1 with mu = mu_hi + mu_lo.
+__device__ __forceinline__ float contrast(float l0, float l1, float mu_hi, float mu_lo) {
+  return fmaf(-mu_lo, l1, fmaf(-mu_hi, l1, l0));
+}
+
+// Plausibility mask: l_0 - max l_0 >= ln(alpha_cd), and a finite expert logit.
+// bf16 differences are exact in float32; float32 inputs compare in float64.
+template <typename T>
+__device__ __forceinline__ bool in_mask(float l0, float m0, float thr32, double thr64) {
+  if constexpr (sizeof(T) == 2) {
+    return (l0 > -INFINITY) && (l0 - m0 >= thr32);
+  } else {
+    return (l0 > -INFINITY) && ((double)l0 - (double)m0 >= thr64);
+  }
+}
+
+// Contrastive: r = [mask] coef[0] 2^(c*log2e - off[0]), q = coef[1] 2^(l_pi*log2e - off[1]);
+// f = max(0, r - q) on the mask (coef[1] = 0 for a bonus draw), 0 off it.
+template <typename T, int N>
+__device__ __forceinline__ void eval_f_contrastive(const float (&x0)[N], const float (&x1)[N],
+                                                   int pi, float m0, const Params& p,
+                                                   const float* coef, const float* off,
+                                                   float (&f)[N]) {
+#pragma unroll
+  for (int k = 0; k < N; ++k) {
+    const bool in = in_mask<T>(x0[k], m0, p.thr32, p.thr64);
+    const float c = contrast(x0[k], x1[k], p.mu_hi, p.mu_lo);
+    const float r = coef[0] * fast_exp2(fmaf(c, kLog2e, -off[0]));
+    const float lq = pi ? x1[k] : x0[k];
+    const float q = coef[1] * fast_exp2(fmaf(lq, kLog2e, -off[1]));
+    f[k] = in ? fmaxf(r - q, 0.0f) : 0.0f;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// finalize one sequence (runs in the workgroup that arrived last)
+// ---------------------------------------------------------------------------
+
+struct FinalShared {
+  double lse2[kMaxStatsPerSeq];  // log2-sum-exp2 per (position, statistic)
+  float rowmax[COS_MAX_GAMMA + 1];  // contrastive: expert maximum per position
+  int accept[COS_MAX_GAMMA + 1];
+  float coef[COS_MAX_MODELS];
+  float off[COS_MAX_MODELS];
+  int redo;
+};
+
+template <typename T, bool ALIGNED, int NM, bool CONTRASTIVE>
+__device__ void finalize_sequence(const Params& p, int b, FinalShared& sh, double* tile_sum) {
+  constexpr int N = VecOf<T>::N;
+  constexpr int NCAP = CONTRASTIVE ? 2 : (NM ? NM : COS_MAX_MODELS);
+  const int tid = threadIdx.x;
+  const int lane = lane_id();
+  const int wave = tid >> 6;
+  const int g1 = p.gamma + 1;
+  const int nstat = p.nstat;
+  const int nrows = g1 * nstat;
+  const int n = CONTRASTIVE ? 2 : (NM ? NM : p.n);
+  const int pi = p.proposer[b];
+  const double log2e = (double)kLog2e;
+
+  // 1. combine the chunk partials of every (position, statistic) in float64
+  if (tid < nrows) {
+    const Partial* pp = p.partials + ((size_t)b * nrows + tid) * p.S;
+    int omax = kNoOffset;
+    for (int s = 0; s < p.S; ++s)
+      if (pp[s].Z > 0.0 && pp[s].o > omax) omax = pp[s].o;
+    double z = 0.0;
+    for (int s = 0; s < p.S; ++s)
+      if (pp[s].Z > 0.0) z += ldexp(pp[s].Z, pp[s].o - omax);
+    sh.lse2[tid] = (z > 0.0) ? (double)omax + log2(z) : -INFINITY;
+  }
+  if (CONTRASTIVE && tid < g1) {
+    const float* rm = p.rowmax + ((size_t)b * g1 + tid) * p.S;
+    float m0 = -INFINITY;
+    for (int s = 0; s < p.S; ++s) m0 = fmaxf(m0, rm[s]);
+    sh.rowmax[tid] = m0;
+  }
+  __syncthreads();
+
+  // 2. Eq. (6) for every draft position, in float64
+  if (tid < p.gamma) {
+    const int j = tid;
+    const size_t k = (size_t)b * p.gamma + j;
+    const int d = p.draft[k];
+    double rd = 0.0, qd = 0.0;
+    if constexpr (!CONTRASTIVE) {
+      for (int m = 0; m < n; ++m) {
+        const double l = (double)widen(row_ptr<T>(p, m, b, j)[d]);
+        const double s = exp2(l * log2e - sh.lse2[j * nstat + m]);
+        rd += p.w[m] * s;
+        if (m == pi) qd = s;
+      }
+    } else {
+      const double l0 = (double)widen(row_ptr<T>(p, 0, b, j)[d]);
+      const double l1 = (double)widen(row_ptr<T>(p, 1, b, j)[d]);
+      const bool in = (l0 > -INFINITY) && (l0 - (double)sh.rowmax[j] >= p.thr64);
+      const double c = l0 - p.w[0] * l1;
+      rd = in ? exp2(c * log2e - sh.lse2[j * nstat + 2]) : 0.0;
+      qd = exp2((pi ? l1 : l0) * log2e - sh.lse2[j * nstat + pi]);
+    }
+    double ratio;
+    if (!(rd > 0.0))
+      ratio = 0.0;
+    else if (!(qd > 0.0))
+      ratio = INFINITY;
+    else
+      ratio = rd / qd;
+    const double bound = ratio < 1.0 ? ratio : 1.0;
+    sh.accept[j] = p.u_accept[k] < bound;
+    if (p.diag.r_at_draft) p.diag.r_at_draft[k] = rd;
+    if (p.diag.q_at_draft) p.diag.q_at_draft[k] = qd;
+  }
+  __syncthreads();
+
+  // 3. first rejection (Sec. 3.1)
+  int jstar = p.gamma;
+  for (int j = p.gamma - 1; j >= 0; --j)
+    if (!sh.accept[j]) jstar = j;
+  if (tid == 0) p.accepted_len[b] = jstar;
+  if (tid < g1 && tid != jstar)
+    p.out_tokens[(size_t)b * g1 + tid] = (tid < jstar) ? p.draft[(size_t)b * p.gamma + tid] : -1;
+
+  // 4.-6. tile sums of f at position jstar, scan, inverse CDF
+  bool residual = jstar < p.gamma;
+  int flags = 0;
+  const T* rows[NCAP];
+#pragma unroll
+  for (int m = 0; m < NCAP; ++m) rows[m] = row_ptr<T>(p, m < n ? m : 0, b, jstar);
+  const float m0 = CONTRASTIVE ? sh.rowmax[jstar] : 0.0f;
+
+  for (int attempt = 0; attempt < 2; ++attempt) {
+    // coefficients with integer offsets
+    if (tid < (CONTRASTIVE ? 2 : n)) {
+      double a, lse;
+      if constexpr (!CONTRASTIVE) {
+        a = p.w[tid] - ((residual && tid == pi) ? 1.0 : 0.0);
+        lse = sh.lse2[jstar * nstat + tid];
+      } else {
+        a = (tid == 0) ? 1.0 : (residual ? 1.0 : 0.0);
+        lse = sh.lse2[jstar * nstat + (tid == 0 ? 2 : pi)];
+      }
+      const double K = rint(lse);
+      sh.off[tid] = (float)K;
+      sh.coef[tid] = (float)(a * exp2(K - lse));
+    }
+    if (tid == 0) sh.redo = 0;
+    __syncthreads();
+    float coef[NCAP], off[NCAP];
+#pragma unroll
+    for (int m = 0; m < NCAP; ++m) {
+      coef[m] = (m < n) ? sh.coef[m] : 0.0f;
+      off[m] = (m < n) ? sh.off[m] : 0.0f;
+    }
+
+    // pass 1: one tile = 64 lanes x one 16-byte vector per model
+    for (int tile = wave; tile < p.ntiles; tile += kWaves) {
+      const int vec = tile * 64 + lane;
+      double ls = 0.0;
+      if (vec < p.nvec) {
+        float x[NCAP][N];
+#pragma unroll
+        for (int m = 0; m < NCAP; ++m)
+          if (m < n) load_vec<T, ALIGNED>(rows[m], vec, p.V, x[m]);
+        float f[N];
+        if constexpr (!CONTRASTIVE)
+          eval_f_ensemble<NCAP, N>(x, n, coef, off, f);
+        else
+          eval_f_contrastive<T, N>(x[0], x[1], pi, m0, p, coef, off, f);
+#pragma unroll
+        for (int k = 0; k < N; ++k) ls += (double)f[k];
+      }
+      const double ts = wave_sum(ls);
+      if (lane == 0) tile_sum[tile] = ts;
+    }
+    __syncthreads();
+
+    if (wave == 0) {
+      // scan of the tile sums: each lane owns a contiguous segment
+      const int per = (p.ntiles + 63) / 64;
+      const int t0 = min(lane * per, p.ntiles), t1 = min(t0 + per, p.ntiles);
+      double seg = 0.0;
+      for (int t = t0; t < t1; ++t) seg += tile_sum[t];
+      const double incl = wave_inclusive_scan(seg);
+      const double F = __shfl(incl, 63, 64);
+      const double up = __shfl_up(incl, 1, 64);
+      const double excl = lane ? up : 0.0;
+      const bool bad = !(F > 0.0) || !(F < INFINITY);
+      if (bad && residual && attempt == 0) {
+        if (lane == 0) sh.redo = 1;  // residual has no mass: draw from r itself
+      } else {
+        const double target = p.u_resample[b] * F;
+        // first tile whose inclusive prefix exceeds the target; else the last tile with mass
+        int hit = -1, lastpos = -1;
+        double hit_excl = 0.0, lastpos_excl = 0.0, runsum = excl;
+        for (int t = t0; t < t1; ++t) {
+          const double ts = tile_sum[t];
+          const double nxt = runsum + ts;
+          if (hit < 0 && nxt > target) {
+            hit = t;
+            hit_excl = runsum;
+          }
+          if (ts > 0.0) {
+            lastpos = t;
+            lastpos_excl = runsum;
+          }
+          runsum = nxt;
+        }
+        const unsigned long long hits = __ballot(hit >= 0);
+        const unsigned long long poss = __ballot(lastpos >= 0);
+        bool clamp = false;
+        int tile = 0;
+        double tile_excl = 0.0;
+        if (hits) {
+          const int src = __ffsll((long long)hits) - 1;
+          tile = __shfl(hit, src, 64);
+          tile_excl = __shfl(hit_excl, src, 64);
+        } else {
+          clamp = true;
+          if (poss) {
+            const int src = 63 - __clzll((long long)poss);
+            tile = __shfl(lastpos, src, 64);
+            tile_excl = __shfl(lastpos_excl, src, 64);
+          }
+        }
+
+        // pass 2: the same f values of that one tile, scanned element by element
+        const int vec = tile * 64 + lane;
+        float f[N];
+#pragma unroll
+        for (int k = 0; k < N; ++k) f[k] = 0.0f;
+        if (vec < p.nvec) {
+          float x[NCAP][N];
+#pragma unroll
+          for (int m = 0; m < NCAP; ++m)
+            if (m < n) load_vec<T, ALIGNED>(rows[m], vec, p.V, x[m]);
+          if constexpr (!CONTRASTIVE)
+            eval_f_ensemble<NCAP, N>(x, n, coef, off, f);
+          else
+            eval_f_contrastive<T, N>(x[0], x[1], pi, m0, p, coef, off, f);
+        }
+        double lane_tot = 0.0;
+#pragma unroll
+        for (int k = 0; k < N; ++k) lane_tot += (double)f[k];
+        const double lincl = wave_inclusive_scan(lane_tot);
+        const double lup = __shfl_up(lincl, 1, 64);
+        const double lexcl = tile_excl + (lane ? lup : 0.0);
+        int ksel = -1, klast = -1;
+        double lo_sel = 0.0, hi_sel = 0.0, lo_last = 0.0, hi_last = 0.0, runl = lexcl;
+#pragma unroll
+        for (int k = 0; k < N; ++k) {
+          const double nxt = runl + (double)f[k];
+          if (ksel < 0 && nxt > target) {
+            ksel = k;
+            lo_sel = runl;
+            hi_sel = nxt;
+          }
+          if (f[k] > 0.0f) {
+            klast = k;
+            lo_last = runl;
+            hi_last = nxt;
+          }
+          runl = nxt;
+        }
+        const unsigned long long sel = clamp ? 0ull : __ballot(ksel >= 0);
+        const unsigned long long pos = __ballot(klast >= 0);
+        int src = 0, kk = 0;
+        double lo = 0.0, hi = 0.0;
+        if (sel) {
+          src = __ffsll((long long)sel) - 1;
+          kk = ksel;
+          lo = lo_sel;
+          hi = hi_sel;
+        } else {
+          // rounding left no prefix above the target inside this tile (or tail
+          // clamp): take the last element with mass
+          if (pos) src = 63 - __clzll((long long)pos);
+          kk = klast < 0 ? 0 : klast;
+          lo = lo_last;
+          hi = hi_last;
+          if (clamp) flags |= COS_FLAG_TAIL_CLAMP;
+        }
+        if (lane == src) {
+          int token = (tile * 64 + lane) * N + kk;
+          token = min(max(token, 0), p.V - 1);
+          p.out_tokens[(size_t)b * g1 + jstar] = token;
+          if (p.diag.sample_mass) p.diag.sample_mass[b] = F;
+          if (p.diag.cdf_lo) p.diag.cdf_lo[b] = lo / F;
+          if (p.diag.cdf_hi) p.diag.cdf_hi[b] = hi / F;
+          if (p.diag.flags) p.diag.flags[b] = flags;
+        }
+      }
+    }
+    __syncthreads();
+    if (!sh.redo) break;
+    residual = false;
+    flags |= COS_FLAG_RESIDUAL_FALLBACK;
+    __syncthreads();
+  }
+}
+
+// ---------------------------------------------------------------------------
+// kernels
+// ---------------------------------------------------------------------------
+
+__global__ void __launch_bounds__(kThreads) fill_zero_kernel(int* dst, int count) {
+  const int i = blockIdx.x * kThreads + threadIdx.x;
+  if (i < count) dst[i] = 0;
+}
+
+// Ensemble streaming kernel.  Workgroup index -> (b, j, m, s), b slowest.
+template <typename T, bool ALIGNED, int NM>
+__global__ void __launch_bounds__(kThreads) ensemble_kernel(Params p) {
+  extern __shared__ double tile_sum[];
+  __shared__ WaveStat ws[kWaves];
+  __shared__ FinalShared sh;
+  __shared__ int s_flag;
+
+  const int g1 = p.gamma + 1;
+  const int per_b = g1 * p.n * p.S;
+  const int b = blockIdx.x / per_b;
+  int rem = blockIdx.x - b * per_b;
+  const int j = rem / (p.n * p.S);
+  rem -= j * p.n * p.S;
+  const int m = rem / p.S;
+  const int s = rem - m * p.S;
+
+  const T* row = row_ptr<T>(p, m, b, j);
+  const int v0 = s * p.cv;
+  const int v1 = min(v0 + p.cv, p.nvec);
+  int o;
+  double z;
+  chunk_stats<T, ALIGNED>(row, v0, v1, p.V, o, z);
+  publish_wave_stat(ws, 0, o, z);
+  __syncthreads();
+  if (threadIdx.x == 0)
+    p.partials[(((size_t)b * g1 + j) * p.n + m) * p.S + s] = block_reduce_slot(ws, 0);
+
+  if (arrive_last(p.counters + b, per_b, &s_flag, p.debug) && !(p.debug & 1))
+    finalize_sequence<T, ALIGNED, NM, false>(p, b, sh, tile_sum);
+}
+
+// Contrastive, kernel 1: partial maxima of the expert row (model 0).
+template <typename T, bool ALIGNED>
+__global__ void __launch_bounds__(kThreads) expert_rowmax_kernel(Params p) {
+  constexpr int N = VecOf<T>::N;
+  __shared__ float wmax[kWaves];
+  const int g1 = p.gamma + 1;
+  const int rs = blockIdx.x / p.S;  // b * g1 + j
+  const int s = blockIdx.x - rs * p.S;
+  const int b = rs / g1, j = rs - b * g1;
+  const T* row = row_ptr<T>(p, 0, b, j);
+  const int v0 = s * p.cv;
+  const int v1 = min(v0 + p.cv, p.nvec);
+  float lm = -INFINITY;
+  for (int base = v0; base < v1; base += kThreads * kUnroll) {
+    float x[kUnroll][N];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const int v = base + u * kThreads + threadIdx.x;
+      if (v < v1) {
+        load_vec<T, ALIGNED>(row, v, p.V, x[u]);
+      } else {
+#pragma unroll
+        for (int k = 0; k < N; ++k) x[u][k] = -INFINITY;
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u)
+#pragma unroll
+      for (int k = 0; k < N; ++k) lm = fmaxf(lm, x[u][k]);
+  }
+  const float wm = wave_max(lm);
+  if (lane_id() == 0) wmax[threadIdx.x >> 6] = wm;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float mx = wmax[0];
+    for (int w = 1; w < kWaves; ++w) mx = fmaxf(mx, wmax[w]);
+    p.rowmax[(size_t)rs * p.S + s] = mx;
+  }
+}
+
+// Contrastive, kernel 2.  Workgroup index -> (b, j, s); reads the chunk of both
+// rows once and produces three statistics: the proposer row's softmax sum and
+// the masked sum of 2^(c*log2e - o) (Eq. (5) restricted to the mask).
+template <typename T, bool ALIGNED>
+__global__ void __launch_bounds__(kThreads) contrastive_kernel(Params p) {
+  constexpr int N = VecOf<T>::N;
+  constexpr int U = kUnroll / 2;
+  extern __shared__ double tile_sum[];
+  __shared__ WaveStat ws[2 * kWaves];
+  __shared__ FinalShared sh;
+  __shared__ int s_flag;
+  __shared__ float s_m0[kWaves];
+
+  const int g1 = p.gamma + 1;
+  const int per_b = g1 * p.S;
+  const int b = blockIdx.x / per_b;
+  int rem = blockIdx.x - b * per_b;
+  const int j = rem / p.S;
+  const int s = rem - j * p.S;
+  const int pi = p.proposer[b];
+  const int tid = threadIdx.x;
+
+  // expert maximum of this position from kernel 1's partial maxima
+  {
+    const float* rm = p.rowmax + ((size_t)b * g1 + j) * p.S;
+    float lm = -INFINITY;
+    for (int i = tid; i < p.S; i += kThreads) lm = fmaxf(lm, rm[i]);
+    const float wm = wave_max(lm);
+    if (lane_id() == 0) s_m0[tid >> 6] = wm;
+    __syncthreads();
+  }
+  float m0 = s_m0[0];
+  for (int w = 1; w < kWaves; ++w) m0 = fmaxf(m0, s_m0[w]);
+
+  const T* row0 = row_ptr<T>(p, 0, b, j);
+  const T* row1 = row_ptr<T>(p, 1, b, j);
+  const int v0 = s * p.cv;
+  const int v1 = min(v0 + p.cv, p.nvec);
+  Running rq, rc;  // proposer row; masked contrastive logits
+  running_init(rq);
+  running_init(rc);
+  for (int base = v0; base < v1; base += kThreads * U) {
+    float x0[U][N], x1[U][N];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int v = base + u * kThreads + tid;
+      if (v < v1) {
+        load_vec<T, ALIGNED>(row0, v, p.V, x0[u]);
+        load_vec<T, ALIGNED>(row1, v, p.V, x1[u]);
+      } else {
+#pragma unroll
+        for (int k = 0; k < N; ++k) x0[u][k] = x1[u][k] = -INFINITY;
+      }
+    }
+    // proposer row statistic
+    float lm = -INFINITY;
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int k = 0; k < N; ++k) lm = fmaxf(lm, pi ? x1[u][k] : x0[u][k]);
+    running_cover(rq, wave_max(lm));
+    const float neg_oq = -(float)rq.o;
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int k = 0; k < N; ++k)
+        rq.acc[k & 3] += fast_exp2(fmaf(pi ? x1[u][k] : x0[u][k], kLog2e, neg_oq));
+    // masked contrastive statistic; the mask is sparse, so skip wave-wide when empty
+    float c[U][N];
+    float lmc = -INFINITY;
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int k = 0; k < N; ++k) {
+        const bool in = in_mask<T>(x0[u][k], m0, p.thr32, p.thr64);
+        c[u][k] = in ? contrast(x0[u][k], x1[u][k], p.mu_hi, p.mu_lo) : -INFINITY;
+        lmc = fmaxf(lmc, c[u][k]);
+      }
+    if (__ballot(lmc > -INFINITY)) {
+      running_cover(rc, wave_max(lmc));
+      const float neg_oc = -(float)rc.o;
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int k = 0; k < N; ++k) rc.acc[k & 3] += fast_exp2(fmaf(c[u][k], kLog2e, neg_oc));
+    }
+  }
+  const double zq = running_total(rq);
+  const double zc = running_total(rc);
+  publish_wave_stat(ws, 0, rq.o, zq);
+  publish_wave_stat(ws, 1, rc.o, zc);
+  __syncthreads();
+  if (tid == 0) {
+    Partial* out = p.partials + (((size_t)b * g1 + j) * 3) * p.S;
+    Partial none;
+    none.Z = 0.0;
+    none.o = kNoOffset;
+    none.pad = 0;
+    out[(size_t)pi * p.S + s] = block_reduce_slot(ws, 0);
+    out[(size_t)(1 - pi) * p.S + s] = none;
+    out[(size_t)2 * p.S + s] = block_reduce_slot(ws, 1);
+  }
+
+  if (arrive_last(p.counters + b, per_b, &s_flag))
+    finalize_sequence<T, ALIGNED, 2, true>(p, b, sh, tile_sum);
+}
+
+// ---------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------
+
+int g_chunk_vectors = 0;  // 0 = heuristic
+// Optional event ring around the streaming kernel (benchmarks only).
+constexpr int kMaxProfileSlots = 1024;
+hipEvent_t g_ev_start[kMaxProfileSlots], g_ev_stop[kMaxProfileSlots];
+int g_ev_created = 0;   // event pairs that exist
+int g_ev_slots = 0;     // pairs in use (0 = profiling off)
+int g_ev_recorded = 0;  // calls recorded since the last enable
+
+struct Plan {
+  int nvec, ntiles, S, cv, nstat;
+  size_t off_counters, off_partials, off_rowmax, bytes;
+};
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+bool shape_ok(int n, int B, int gamma, int V) {
+  return n >= 1 && n <= COS_MAX_MODELS && B >= 0 && gamma >= 1 && gamma <= COS_MAX_GAMMA &&
+         V >= 1 && V <= COS_MAX_VOCAB;
+}
+
+// Workspace layout for the largest split count the library may choose.
+void plan_layout(int n, int B, int gamma, int V, cos_dtype_t dt, cos_combine_t mode, int S,
+                 Plan* pl) {
+  const int N = dt == COS_DTYPE_F32 ? 4 : 8;
+  pl->nvec = (V + N - 1) / N;
+  pl->ntiles = (pl->nvec + 63) / 64;
+  pl->nstat = mode == COS_COMBINE_CONTRASTIVE ? 3 : n;
+  const size_t g1 = (size_t)gamma + 1;
+  pl->off_counters = 0;
+  pl->off_partials = align_up((size_t)B * sizeof(int), 256);
+  pl->off_rowmax = pl->off_partials + align_up((size_t)B * g1 * pl->nstat * S * sizeof(Partial), 256);
+  pl->bytes = pl->off_rowmax +
+              (mode == COS_COMBINE_CONTRASTIVE ? align_up((size_t)B * g1 * S * sizeof(float), 256) : 0);
+}
+
+int max_splits(int nvec) {
+  const int s = (nvec + kThreads - 1) / kThreads;
+  return s < kMaxSplits ? (s < 1 ? 1 : s) : kMaxSplits;
+}
+
+// Chunks per row: enough workgroups to fill 256 CUs several times over when the
+// batch is small, at most ~64 KB of one row per workgroup when it is large.
+void choose_split(int rows_total, int nvec, int* S_out, int* cv_out) {
+  int cv;
+  if (g_chunk_vectors > 0) {
+    cv = g_chunk_vectors;
+  } else {
+    const int cap = 4096;  // 64 KB
+    long want_blocks = 4096;
+    long s_want = (want_blocks + rows_total - 1) / (rows_total > 0 ? rows_total : 1);
+    if (s_want < 1) s_want = 1;
+    cv = (int)((nvec + s_want - 1) / s_want);
+    if (cv > cap) cv = cap;
+  }
+  cv = (cv + kThreads - 1) / kThreads * kThreads;
+  if (cv < kThreads) cv = kThreads;
+  int S = (nvec + cv - 1) / cv;
+  const int smax = max_splits(nvec);
+  if (S > smax) {
+    S = smax;
+    cv = (nvec + S - 1) / S;
+    cv = (cv + kThreads - 1) / kThreads * kThreads;
+    S = (nvec + cv - 1) / cv;
+  }
+  *S_out = S;
+  *cv_out = cv;
+}
+
+template <typename T, bool ALIGNED>
+cos_status_t launch_ensemble(const Params& p, size_t lds, hipStream_t st) {
+  const long blocks = (long)p.B * (p.gamma + 1) * p.n * p.S;
+  if (blocks <= 0 || blocks > 0x7fffffffL) return COS_ERR_SHAPE;
+  const dim3 grid((unsigned)blocks), block(kThreads);
+  if constexpr (ALIGNED) {
+    switch (p.n) {
+      case 2: hipLaunchKernelGGL((ensemble_kernel<T, ALIGNED, 2>), grid, block, lds, st, p); break;
+      case 3: hipLaunchKernelGGL((ensemble_kernel<T, ALIGNED, 3>), grid, block, lds, st, p); break;
+      case 4: hipLaunchKernelGGL((ensemble_kernel<T, ALIGNED, 4>), grid, block, lds, st, p); break;
+      default: hipLaunchKernelGGL((ensemble_kernel<T, ALIGNED, 0>), grid, block, lds, st, p); break;
+    }
+  } else {
+    hipLaunchKernelGGL((ensemble_kernel<T, ALIGNED, 0>), grid, block, lds, st, p);
+  }
+  return hipGetLastError() == hipSuccess ? COS_OK : COS_ERR_LAUNCH;
+}
+
+template <typename T, bool ALIGNED>
+cos_status_t launch_contrastive(const Params& p, size_t lds, hipStream_t st, hipEvent_t ev_start) {
+  const long blocks = (long)p.B * (p.gamma + 1) * p.S;
+  if (blocks <= 0 || blocks > 0x7fffffffL) return COS_ERR_SHAPE;
+  const dim3 grid((unsigned)blocks), block(kThreads);
+  hipLaunchKernelGGL((expert_rowmax_kernel<T, ALIGNED>), grid, block, 0, st, p);
+  if (hipGetLastError() != hipSuccess) return COS_ERR_LAUNCH;
+  if (ev_start) (void)hipEventRecord(ev_start, st);
+  hipLaunchKernelGGL((contrastive_kernel<T, ALIGNED>), grid, block, lds, st, p);
+  return hipGetLastError() == hipSuccess ? COS_OK : COS_ERR_LAUNCH;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t cos_verify_workspace_bytes(int n, int B, int gamma, int V, cos_dtype_t dt,
+                                  cos_combine_t mode) {
+  if (!shape_ok(n, B, gamma, V)) return 0;
+  if (dt != COS_DTYPE_F32 && dt != COS_DTYPE_BF16) return 0;
+  if (mode != COS_COMBINE_ENSEMBLE && mode != COS_COMBINE_CONTRASTIVE) return 0;
+  Plan pl;
+  const int N = dt == COS_DTYPE_F32 ? 4 : 8;
+  plan_layout(n, B, gamma, V, dt, mode, max_splits((V + N - 1) / N), &pl);
+  return pl.bytes < 256 ? 256 : pl.bytes;
+}
+
+cos_status_t cos_verify(const void* logits, cos_dtype_t dt, int n, int B, int gamma, int V,
+                        const int32_t* draft_tokens, const int32_t* proposer_idx,
+                        cos_combine_t combine_mode, const double* weights,
+                        const double* u_accept, const double* u_resample,
+                        int32_t* accepted_len, int32_t* out_tokens, void* workspace,
+                        size_t workspace_bytes, const cos_diag_t* diag, void* hip_stream) {
+  // ---- host-side validation (no HIP call before it passes) ----
+  if (!shape_ok(n, B, gamma, V)) return COS_ERR_SHAPE;
+  if (dt != COS_DTYPE_F32 && dt != COS_DTYPE_BF16) return COS_ERR_DTYPE;
+  if (combine_mode != COS_COMBINE_ENSEMBLE && combine_mode != COS_COMBINE_CONTRASTIVE)
+    return COS_ERR_MODE;
+  if (combine_mode == COS_COMBINE_CONTRASTIVE && n != 2) return COS_ERR_MODE;
+  if (!weights) return COS_ERR_NULL;
+  if (combine_mode == COS_COMBINE_ENSEMBLE) {
+    double sum = 0.0;
+    for (int m = 0; m < n; ++m) {
+      if (!(weights[m] >= 0.0) || !std::isfinite(weights[m])) return COS_ERR_WEIGHTS;
+      sum += weights[m];
+    }
+    if (std::fabs(sum - 1.0) > 1e-9) return COS_ERR_WEIGHTS;
+  } else {
+    if (!std::isfinite(weights[0])) return COS_ERR_WEIGHTS;
+    if (!(weights[1] >= 0.0 && weights[1] <= 1.0)) return COS_ERR_WEIGHTS;
+  }
+  if (B == 0) return COS_OK;
+  if (!logits || !draft_tokens || !proposer_idx || !u_accept || !u_resample || !accepted_len ||
+      !out_tokens)
+    return COS_ERR_NULL;
+  const size_t esize = dt == COS_DTYPE_F32 ? 4 : 2;
+  if (reinterpret_cast<uintptr_t>(logits) % esize) return COS_ERR_ALIGN;
+  const size_t need = cos_verify_workspace_bytes(n, B, gamma, V, dt, combine_mode);
+  if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256 || workspace_bytes < need)
+    return COS_ERR_WORKSPACE;
+  if ((size_t)(gamma + 1) * (combine_mode == COS_COMBINE_CONTRASTIVE ? 3 : n) > kMaxStatsPerSeq)
+    return COS_ERR_SHAPE;
+
+  // ---- launch plan ----
+  const int N = dt == COS_DTYPE_F32 ? 4 : 8;
+  const int nvec = (V + N - 1) / N;
+  const int rows_total = (combine_mode == COS_COMBINE_CONTRASTIVE ? 1 : n) * B * (gamma + 1);
+  int S, cv;
+  choose_split(rows_total, nvec, &S, &cv);
+  Plan pl;
+  plan_layout(n, B, gamma, V, dt, combine_mode, S, &pl);
+  if (pl.bytes > workspace_bytes) return COS_ERR_WORKSPACE;
+
+  Params p;
+  p.logits = logits;
+  p.n = n;
+  p.B = B;
+  p.gamma = gamma;
+  p.V = V;
+  p.draft = draft_tokens;
+  p.proposer = proposer_idx;
+  p.u_accept = u_accept;
+  p.u_resample = u_resample;
+  p.accepted_len = accepted_len;
+  p.out_tokens = out_tokens;
+  char* wsb = static_cast<char*>(workspace);
+  p.counters = reinterpret_cast<int*>(wsb + pl.off_counters);
+  p.partials = reinterpret_cast<Partial*>(wsb + pl.off_partials);
+  p.rowmax = reinterpret_cast<float*>(wsb + pl.off_rowmax);
+  p.S = S;
+  p.cv = cv;
+  p.nvec = pl.nvec;
+  p.ntiles = pl.ntiles;
+  p.nstat = pl.nstat;
+  for (int m = 0; m < COS_MAX_MODELS; ++m) p.w[m] = m < n ? weights[m] : 0.0;
+  p.mu_hi = p.mu_lo = 0.0f;
+  p.thr32 = -INFINITY;
+  p.thr64 = -INFINITY;
+  if (combine_mode == COS_COMBINE_CONTRASTIVE) {
+    p.mu_hi = (float)weights[0];
+    p.mu_lo = (float)(weights[0] - (double)p.mu_hi);
+    if (weights[1] > 0.0) {
+      p.thr64 = std::log(weights[1]);
+      float t = (float)p.thr64;  // smallest float >= thr64
+      if ((double)t < p.thr64) t = std::nextafterf(t, INFINITY);
+      p.thr32 = t;
+    }
+  }
+  if (diag) {
+    p.diag = *diag;
+  } else {
+    p.diag.r_at_draft = p.diag.q_at_draft = p.diag.sample_mass = nullptr;
+    p.diag.cdf_lo = p.diag.cdf_hi = nullptr;
+    p.diag.flags = nullptr;
+  }
+
+  p.debug = std::getenv("COS_DEBUG_FLAGS") ? std::atoi(std::getenv("COS_DEBUG_FLAGS")) : 0;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const bool aligned = (reinterpret_cast<uintptr_t>(logits) % 16 == 0) && (V % N == 0);
+  const size_t lds = (size_t)pl.ntiles * sizeof(double);
+  const bool profile = g_ev_slots > 0;
+  const int slot = profile ? g_ev_recorded % g_ev_slots : 0;
+  hipEvent_t ev_start = profile ? g_ev_start[slot] : nullptr;
+
+  hipLaunchKernelGGL(fill_zero_kernel, dim3((B + kThreads - 1) / kThreads), dim3(kThreads), 0, st,
+                     p.counters, B);
+  if (hipGetLastError() != hipSuccess) return COS_ERR_LAUNCH;
+
+  cos_status_t rc;
+  if (combine_mode == COS_COMBINE_ENSEMBLE) {
+    if (profile) (void)hipEventRecord(ev_start, st);
+    if (dt == COS_DTYPE_F32)
+      rc = aligned ? launch_ensemble<float, true>(p, lds, st) : launch_ensemble<float, false>(p, lds, st);
+    else
+      rc = aligned ? launch_ensemble<uint16_t, true>(p, lds, st)
+                   : launch_ensemble<uint16_t, false>(p, lds, st);
+  } else {
+    if (dt == COS_DTYPE_F32)
+      rc = aligned ? launch_contrastive<float, true>(p, lds, st, ev_start)
+                   : launch_contrastive<float, false>(p, lds, st, ev_start);
+    else
+      rc = aligned ? launch_contrastive<uint16_t, true>(p, lds, st, ev_start)
+                   : launch_contrastive<uint16_t, false>(p, lds, st, ev_start);
+  }
+  if (profile) {
+    (void)hipEventRecord(g_ev_stop[slot], st);
+    ++g_ev_recorded;
+  }
+  return rc;
+}
+
+const char* cos_status_string(cos_status_t status) {
+  switch (status) {
+    case COS_OK: return "ok";
+    case COS_ERR_NULL: return "a required pointer is NULL";
+    case COS_ERR_SHAPE: return "n, B, gamma or V outside the supported range";
+    case COS_ERR_DTYPE: return "unknown logits dtype";
+    case COS_ERR_MODE: return "unknown combine mode, or contrastive mode with n != 2";
+    case COS_ERR_WEIGHTS: return "invalid combine weights";
+    case COS_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case COS_ERR_ALIGN: return "logits pointer not aligned to its element size";
+    case COS_ERR_LAUNCH: return "a HIP call failed";
+    case COS_ERR_UNSUPPORTED: return "not supported";
+  }
+  return "unknown status";
+}
+
+int cos_verify_version(void) { return 1; }
+
+cos_status_t cos_profile_enable(int slots) {
+  if (slots < 0 || slots > kMaxProfileSlots) return COS_ERR_SHAPE;
+  while (g_ev_created < slots) {
+    if (hipEventCreate(&g_ev_start[g_ev_created]) != hipSuccess) return COS_ERR_LAUNCH;
+    if (hipEventCreate(&g_ev_stop[g_ev_created]) != hipSuccess) return COS_ERR_LAUNCH;
+    ++g_ev_created;
+  }
+  g_ev_slots = slots;
+  g_ev_recorded = 0;
+  return COS_OK;
+}
+
+int cos_profile_recorded(void) { return g_ev_recorded < g_ev_slots ? g_ev_recorded : g_ev_slots; }
+
+cos_status_t cos_profile_kernel_ms(int index, float* ms) {
+  if (!ms) return COS_ERR_NULL;
+  if (index < 0 || index >= cos_profile_recorded()) return COS_ERR_SHAPE;
+  if (hipEventSynchronize(g_ev_stop[index]) != hipSuccess) return COS_ERR_LAUNCH;
+  if (hipEventElapsedTime(ms, g_ev_start[index], g_ev_stop[index]) != hipSuccess) return COS_ERR_LAUNCH;
+  return COS_OK;
+}
+
+void cos_tune_set_chunk_vectors(int vectors) { g_chunk_vectors = vectors > 0 ? vectors : 0; }
+
+}  // extern "C"

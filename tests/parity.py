@@ -1,0 +1,167 @@
+"""GPU-vs-oracle comparison shared by the GPU tests, the smoke check and the benchmark.
+
+Contract (decisions are integers decided by floating point, so near-ties are
+excused, counted and reported; everything else must be bit-exact):
+
+* accepted_len and out_tokens identical on every row that is not excused;
+* a row is excused when the first differing accept decision has
+  |u - ratio| < 1e-5 (oracle ratio), or when the lengths agree, the drawn token
+  differs, u_resample lies within 1e-6 of the oracle's normalised CDF edge of
+  its token and the GPU token is the neighbouring token with non-zero mass;
+* r(d), q(d) agree to 1e-5 relative (absolute 1e-35 below 1e-30).
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+import torch
+
+from oracle import cos_oracle as O
+from paper_2502_01662_amd import cos_verify as C
+from paper_2502_01662_amd import workloads as W
+
+RATIO_TIE = 1e-5
+CDF_TIE = 1e-6
+PROB_RTOL = 1e-5
+
+
+@dataclass
+class ParityReport:
+    rows: int = 0
+    exact_rows: int = 0
+    excused_accept_ties: int = 0
+    excused_cdf_ties: int = 0
+    failures: List[str] = field(default_factory=list)
+    max_rel_err_r: float = 0.0
+    max_rel_err_q: float = 0.0
+    flag_mismatches: int = 0
+
+    @property
+    def ok(self) -> bool:
+        return not self.failures
+
+    def summary(self) -> Dict:
+        return {"rows": self.rows, "exact_rows": self.exact_rows,
+                "excused_accept_ties": self.excused_accept_ties,
+                "excused_cdf_ties": self.excused_cdf_ties, "failures": len(self.failures),
+                "max_rel_err_r": self.max_rel_err_r, "max_rel_err_q": self.max_rel_err_q}
+
+
+def oracle_dtype(logits: torch.Tensor) -> int:
+    return O.DTYPE_F32 if logits.dtype == torch.float32 else O.DTYPE_BF16
+
+
+def run_gpu(inp: Dict[str, torch.Tensor], mode: int, weights: Sequence[float], with_diag: bool = True):
+    B, gamma = inp["draft_tokens"].shape
+    diag = C.Diagnostics.allocate(B, gamma, inp["logits"].device) if with_diag else None
+    alen, toks = C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], mode, weights,
+                              inp["u_accept"], inp["u_resample"], diag=diag)
+    torch.cuda.synchronize()
+    return alen.cpu().numpy(), toks.cpu().numpy(), diag
+
+
+def run_oracle(inp: Dict[str, torch.Tensor], mode: int, weights: Sequence[float],
+               rows: Optional[Sequence[int]] = None, all_positions: bool = True, num_threads: int = 0):
+    """Oracle on all batch rows, or on the subset ``rows`` (copied to the host first)."""
+    logits = inp["logits"]
+    sel = slice(None) if rows is None else torch.as_tensor(list(rows), device=logits.device)
+    lg = logits[:, sel].contiguous()
+    return lg, O.verify(W.host_logits(lg), oracle_dtype(lg), inp["draft_tokens"][sel].cpu().numpy(),
+                        inp["proposer_idx"][sel].cpu().numpy(), mode, list(weights),
+                        inp["u_accept"][sel].cpu().numpy(), inp["u_resample"][sel].cpu().numpy(),
+                        all_positions=all_positions, num_threads=num_threads)
+
+
+def _rel_err(got: np.ndarray, want: np.ndarray) -> float:
+    big = want >= 1e-30
+    err = 0.0
+    if big.any():
+        err = float(np.max(np.abs(got[big] - want[big]) / want[big]))
+    if (~big).any() and float(np.max(np.abs(got[~big] - want[~big]))) > 1e-35:
+        err = max(err, 1.0)
+    return err
+
+
+def _sample_weights_of_row(host_lg, dtype, b, j, pi, mode, weights, residual):
+    n = host_lg.shape[0]
+    l = [O.row_to_f64(host_lg[m, b, j], dtype) for m in range(n)]
+    s = np.stack([O.softmax(x) for x in l])
+    if mode == O.ENSEMBLE:
+        r = O.combine_ensemble(s, np.asarray(weights, dtype=np.float64))
+    else:
+        r, _ = O.combine_contrastive(l[0], l[1], weights[0], weights[1])
+    return O.sample_weights(r, s[pi], residual)
+
+
+def compare(inp: Dict[str, torch.Tensor], mode: int, weights: Sequence[float], gpu_alen: np.ndarray,
+            gpu_toks: np.ndarray, diag, rows: Optional[Sequence[int]] = None,
+            num_threads: int = 0) -> ParityReport:
+    """Compare GPU outputs with the oracle (on the batch rows ``rows``, default all)."""
+    rep = ParityReport()
+    lg, ora = run_oracle(inp, mode, weights, rows=rows, num_threads=num_threads)
+    assert ora.status == 0, ora.status
+    idx = np.arange(gpu_alen.shape[0]) if rows is None else np.asarray(list(rows))
+    g_alen, g_toks = gpu_alen[idx], gpu_toks[idx]
+    u_acc = inp["u_accept"].cpu().numpy()[idx]
+    u_res = inp["u_resample"].cpu().numpy()[idx]
+    prop = inp["proposer_idx"].cpu().numpy()[idx]
+    gamma = u_acc.shape[1]
+    host_lg = None
+    rep.rows = len(idx)
+    if diag is not None:
+        gr = diag.r_at_draft.cpu().numpy()[idx]
+        gq = diag.q_at_draft.cpu().numpy()[idx]
+        rep.max_rel_err_r = _rel_err(gr, ora.r_at_draft)
+        rep.max_rel_err_q = _rel_err(gq, ora.q_at_draft)
+        if rep.max_rel_err_r > PROB_RTOL:
+            rep.failures.append(f"r(d) relative error {rep.max_rel_err_r:.3e} > {PROB_RTOL}")
+        if rep.max_rel_err_q > PROB_RTOL:
+            rep.failures.append(f"q(d) relative error {rep.max_rel_err_q:.3e} > {PROB_RTOL}")
+        gflags = diag.flags.cpu().numpy()[idx]
+    for i in range(len(idx)):
+        if g_alen[i] == ora.accepted_len[i] and np.array_equal(g_toks[i], ora.out_tokens[i]):
+            rep.exact_rows += 1
+            if diag is not None and (gflags[i] & 1) != (ora.flags[i] & 1):
+                rep.flag_mismatches += 1
+            continue
+        where = f"row {idx[i]}: gpu len {g_alen[i]} tokens {g_toks[i].tolist()} vs oracle len " \
+                f"{ora.accepted_len[i]} tokens {ora.out_tokens[i].tolist()}"
+        if g_alen[i] != ora.accepted_len[i]:
+            j = int(min(g_alen[i], ora.accepted_len[i]))       # first differing decision
+            ratio = ora.ratio[i, j]
+            if j < gamma and abs(u_acc[i, j] - min(1.0, ratio)) < RATIO_TIE and \
+                    np.array_equal(g_toks[i, :j], ora.out_tokens[i, :j]):
+                rep.excused_accept_ties += 1
+            else:
+                rep.failures.append(where + f" (u={u_acc[i, j] if j < gamma else None}, ratio={ratio})")
+            continue
+        j = int(ora.accepted_len[i])
+        if not np.array_equal(np.delete(g_toks[i], j), np.delete(ora.out_tokens[i], j)):
+            rep.failures.append(where + " (prefix or padding differs)")
+            continue
+        edge = min(abs(u_res[i] - ora.cdf_lo[i]), abs(u_res[i] - ora.cdf_hi[i]))
+        if edge >= CDF_TIE:
+            rep.failures.append(where + f" (u_resample {u_res[i]} is {edge:.3e} from the CDF edge)")
+            continue
+        if host_lg is None:
+            host_lg = W.host_logits(lg)
+        residual = j < gamma and not (ora.flags[i] & O.FLAG_RESIDUAL_FALLBACK)
+        f, _ = _sample_weights_of_row(host_lg, oracle_dtype(lg), i, j, int(prop[i]), mode, weights, residual)
+        pos = np.nonzero(f > 0)[0]
+        k = int(np.searchsorted(pos, ora.out_tokens[i, j]))
+        neighbours = {int(pos[k - 1]) if k > 0 else -1, int(pos[k + 1]) if k + 1 < len(pos) else -1}
+        if int(g_toks[i, j]) in neighbours:
+            rep.excused_cdf_ties += 1
+        else:
+            rep.failures.append(where + " (CDF near-tie but the GPU token is not an adjacent token with mass)")
+    return rep
+
+
+def check_workload(w: W.Workload, device: str = "cuda", step: int = 0, rows: Optional[Sequence[int]] = None,
+                   inp: Optional[Dict[str, torch.Tensor]] = None) -> ParityReport:
+    if inp is None:
+        inp = W.generate(w, device=device, step=step)
+    alen, toks, diag = run_gpu(inp, w.mode, w.weights)
+    return compare(inp, w.mode, w.weights, alen, toks, diag, rows=rows)

@@ -1,0 +1,87 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, sizes its workspace, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2502_01662_amd import cos_verify as C
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "cos_verify.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(cos_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = C.load_library()
+    names = _declared_functions()
+    assert {"cos_verify", "cos_verify_workspace_bytes", "cos_status_string", "cos_verify_version"} <= set(names)
+    for name in names:
+        assert hasattr(lib, name), name
+
+
+def test_version_and_status_strings():
+    assert C.cos_verify_version() == 1
+    assert C.cos_status_string(0) == "ok"
+    for code in range(-9, 0):
+        assert C.cos_status_string(code) not in ("ok", "unknown status")
+
+
+def test_workspace_bytes():
+    assert C.cos_verify_workspace_bytes(4, 512, 6, 256000, C.COS_DTYPE_BF16, C.COS_COMBINE_ENSEMBLE) > 0
+    small = C.cos_verify_workspace_bytes(2, 1, 5, 32000, C.COS_DTYPE_F32, C.COS_COMBINE_ENSEMBLE)
+    big = C.cos_verify_workspace_bytes(2, 2, 5, 32000, C.COS_DTYPE_F32, C.COS_COMBINE_ENSEMBLE)
+    assert 0 < small < big
+    assert C.cos_verify_workspace_bytes(0, 1, 5, 32000, 0, 0) == 0            # n < 1
+    assert C.cos_verify_workspace_bytes(9, 1, 5, 32000, 0, 0) == 0            # n > COS_MAX_MODELS
+    assert C.cos_verify_workspace_bytes(2, 1, 0, 32000, 0, 0) == 0            # gamma < 1
+    assert C.cos_verify_workspace_bytes(2, 1, 32, 32000, 0, 0) == 0           # gamma > COS_MAX_GAMMA
+    assert C.cos_verify_workspace_bytes(2, 1, 5, (1 << 20) + 1, 0, 0) == 0    # V > COS_MAX_VOCAB
+    assert C.cos_verify_workspace_bytes(2, 1, 5, 32000, 7, 0) == 0            # dtype
+    assert C.cos_verify_workspace_bytes(2, 1, 5, 32000, 0, 7) == 0            # mode
+
+
+def _call(n=2, B=1, gamma=2, V=16, dt=0, mode=0, weights=(0.5, 0.5), logits=0x1000, draft=0x1000,
+          prop=0x1000, ua=0x1000, ur=0x1000, alen=0x1000, toks=0x1000, ws=0x1000, ws_bytes=1 << 20):
+    """Call cos_verify with fake (never dereferenced) device pointers: validation runs on the host
+    and every case here must be rejected before any HIP call."""
+    lib = C.load_library()
+    w = (ctypes.c_double * len(weights))(*weights)
+    return lib.cos_verify(logits, dt, n, B, gamma, V, draft, prop, mode, w, ua, ur, alen, toks, ws, ws_bytes,
+                          None, None)
+
+
+def test_argument_validation_needs_no_gpu():
+    assert _call(n=0) == -2
+    assert _call(gamma=0) == -2
+    assert _call(V=0) == -2
+    assert _call(B=-1) == -2
+    assert _call(dt=5) == -3
+    assert _call(mode=3) == -4
+    assert _call(mode=1, n=3, weights=(0.5, 0.1, 0.0)) == -4      # contrastive needs n == 2
+    assert _call(weights=(0.5, 0.6)) == -5
+    assert _call(weights=(1.5, -0.5)) == -5
+    assert _call(weights=(float("nan"), 0.5)) == -5
+    assert _call(mode=1, weights=(0.5, 1.5)) == -5                # alpha_cd outside [0,1]
+    assert _call(mode=1, weights=(float("inf"), 0.1)) == -5       # mu not finite
+    assert _call(logits=0) == -1
+    assert _call(draft=0) == -1
+    assert _call(toks=0) == -1
+    assert _call(dt=0, logits=0x1002) == -7                       # float32 logits at a 2-byte address
+    assert _call(ws=0) == -6
+    assert _call(ws=0x1010) == -6                                 # workspace not 256-byte aligned
+    assert _call(ws_bytes=16) == -6
+    assert _call(B=0, logits=0, draft=0) == 0                     # empty batch: a no-op
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    with pytest.raises(C.CosVerifyError):
+        C.cos_verify(torch.zeros((2, 1, 3, 8)), torch.zeros((1, 2), dtype=torch.int32),
+                     torch.zeros(1, dtype=torch.int32), 0, [0.5, 0.5], torch.zeros((1, 2), dtype=torch.float64),
+                     torch.zeros(1, dtype=torch.float64))

@@ -1,0 +1,244 @@
+"""GPU parity: the HIP path behind the C ABI against the float64 oracle, element by element on
+the same seeded inputs.  Bar: accepted_len / out_tokens bit-exact outside counted near-ties
+(|u - ratio| < 1e-5, CDF edge within 1e-6), r(d) and q(d) to 1e-5 relative."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import cos_oracle as O
+from paper_2502_01662_amd import cos_verify as C
+from paper_2502_01662_amd import workloads as W
+from tests import parity as P
+
+pytestmark = pytest.mark.gpu
+
+
+def _report(name, rep):
+    print(f"[parity] {name}: {rep.summary()}", flush=True)
+    assert rep.ok, rep.failures[:5]
+    # excused rows must stay rare
+    assert rep.excused_accept_ties + rep.excused_cdf_ties <= max(2, rep.rows // 50), rep.summary()
+
+
+def _random_inputs(n, B, gamma, V, dtype, seed, std=3.0, device="cuda"):
+    g = torch.Generator(device="cpu").manual_seed(seed)
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    logits = (torch.randn((n, B, gamma + 1, V), generator=g, dtype=torch.float64) * std).to(tdt)
+    return {
+        "logits": logits.to(device),
+        "draft_tokens": torch.randint(0, V, (B, gamma), generator=g, dtype=torch.int32).to(device),
+        "proposer_idx": torch.randint(0, n, (B,), generator=g, dtype=torch.int32).to(device),
+        "u_accept": torch.rand((B, gamma), generator=g, dtype=torch.float64).to(device),
+        "u_resample": torch.rand((B,), generator=g, dtype=torch.float64).to(device),
+    }
+
+
+def _check(name, inp, mode, weights, rows=None):
+    alen, toks, diag = P.run_gpu(inp, mode, weights)
+    rep = P.compare(inp, mode, weights, alen, toks, diag, rows=rows)
+    _report(name, rep)
+    return alen, toks, diag, rep
+
+
+# ---------------------------------------------------------------------------
+# the five workloads
+# ---------------------------------------------------------------------------
+
+def test_c1_ensemble_f32_alternating_proposer():
+    """B=1, gamma=5, V=32000 float32; fresh tensors and the other proposer at every step."""
+    for step in range(12):
+        inp = W.generate(W.C1, device="cuda", step=step)
+        assert int(inp["proposer_idx"][0]) == step % 2
+        _check(f"c1 step {step}", inp, W.C1.mode, W.C1.weights)
+
+
+def test_c2_contrastive_bf16_full():
+    inp = W.generate(W.C2, device="cuda")
+    # the amateur proposes and the mask keeps only a handful of tokens, so almost every first
+    # draft is rejected here: this workload exercises the residual draw, the next one the lengths
+    _check("c2", inp, W.C2.mode, W.C2.weights)
+    inp = W.generate(W.C2.scaled(proposer="const:0"), device="cuda", step=1)
+    alen, _, _, _ = _check("c2, expert proposes", inp, W.C2.mode, W.C2.weights)
+    assert len(set(alen.tolist())) > 1
+
+
+def test_c3_three_model_ensemble_full():
+    inp = W.generate(W.C3, device="cuda")
+    _check("c3", inp, W.C3.mode, W.C3.weights)
+
+
+def test_c4_zipf_reduced_batch():
+    inp = W.generate(W.C4.scaled(B=48), device="cuda")
+    _check("c4 B=48", inp, W.C4.mode, W.C4.weights)
+
+
+def test_c5_four_model_reduced_batch():
+    inp = W.generate(W.C5.scaled(B=24), device="cuda")
+    _check("c5 B=24", inp, W.C5.mode, W.C5.weights)
+
+
+def test_c4_full_size_sampled_rows():
+    """Full B=256 launch (the configuration the benchmark times); the oracle checks a sample of rows."""
+    inp = W.generate(W.C4, device="cuda")
+    rows = list(range(0, 256, 11)) + [255]
+    _check("c4 full, sampled rows", inp, W.C4.mode, W.C4.weights, rows=rows)
+
+
+def test_c5_full_size_sampled_rows():
+    inp = W.generate(W.C5, device="cuda")
+    rows = list(range(0, 512, 23)) + [511]
+    alen, toks, diag, _ = _check("c5 full, sampled rows", inp, W.C5.mode, W.C5.weights, rows=rows)
+    # properties that hold at any size, on every row
+    g = W.C5.gamma
+    assert alen.min() >= 0 and alen.max() <= g
+    drafts = inp["draft_tokens"].cpu().numpy()
+    for b in range(W.C5.B):
+        a = alen[b]
+        assert np.array_equal(toks[b, :a], drafts[b, :a])
+        assert 0 <= toks[b, a] < W.C5.V
+        assert np.all(toks[b, a + 1:] == -1)
+    lo, hi = diag.cdf_lo.cpu().numpy(), diag.cdf_hi.cpu().numpy()
+    u = inp["u_resample"].cpu().numpy()
+    assert np.all(lo <= u + 1e-9) and np.all(u < hi + 1e-9)
+    # Thm 3.2-style sanity on the accept statistics: mean accepted length is plausible and varied
+    assert len(set(alen.tolist())) >= 3
+
+
+# ---------------------------------------------------------------------------
+# shapes: ragged vocabularies, several tiles + a tail, unaligned rows, both dtypes
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("n,B,gamma,V", [
+    (1, 3, 1, 1), (2, 5, 2, 8), (2, 4, 3, 100), (3, 6, 2, 1000), (2, 3, 4, 4099),
+    (5, 4, 2, 2048), (8, 2, 3, 777), (4, 3, 2, 33000), (2, 2, 31, 513), (3, 2, 5, 70001)])
+def test_ensemble_shapes(dtype, n, B, gamma, V):
+    inp = _random_inputs(n, B, gamma, V, dtype, seed=1000 * n + V)
+    w = np.random.default_rng(V).dirichlet(np.ones(n)).tolist()
+    _check(f"ens {dtype} n={n} B={B} g={gamma} V={V}", inp, C.COS_COMBINE_ENSEMBLE, w)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("B,gamma,V,mu,alpha", [
+    (4, 2, 8, 0.5, 0.1), (5, 3, 1000, 0.1, 0.1), (3, 2, 4099, 0.5, 0.0), (4, 4, 33000, 1.0, 0.5),
+    (3, 2, 2048, 0.0, 0.0), (2, 3, 70001, 0.3, 1.0), (6, 1, 513, 0.5, 0.01)])
+def test_contrastive_shapes(dtype, B, gamma, V, mu, alpha):
+    inp = _random_inputs(2, B, gamma, V, dtype, seed=7 * V + B, std=2.0)
+    _check(f"cd {dtype} B={B} g={gamma} V={V} mu={mu} a={alpha}", inp, C.COS_COMBINE_CONTRASTIVE, [mu, alpha])
+
+
+def test_unaligned_base_pointer():
+    """Logits that start 2 bytes (bf16) or 4 bytes (f32) into an allocation: the scalar path."""
+    for dtype, tdt in (("bf16", torch.bfloat16), ("f32", torch.float32)):
+        inp = _random_inputs(2, 3, 2, 1024, dtype, seed=5)
+        flat = torch.empty(inp["logits"].numel() + 1, dtype=tdt, device="cuda")
+        flat[1:] = inp["logits"].reshape(-1)
+        inp["logits"] = flat[1:].view(inp["logits"].shape)
+        assert inp["logits"].data_ptr() % 16 != 0
+        _check(f"unaligned {dtype}", inp, C.COS_COMBINE_ENSEMBLE, [0.3, 0.7])
+
+
+def test_maximum_vocabulary():
+    inp = _random_inputs(2, 1, 1, 1 << 20, "bf16", seed=9)
+    _check("V = 2^20", inp, C.COS_COMBINE_ENSEMBLE, [0.5, 0.5])
+    inp = _random_inputs(2, 1, 1, 1 << 20, "f32", seed=10)
+    _check("V = 2^20 f32", inp, C.COS_COMBINE_CONTRASTIVE, [0.5, 0.1])
+
+
+def test_maximum_gamma_and_models():
+    inp = _random_inputs(8, 2, 31, 640, "bf16", seed=11)
+    _check("n=8 gamma=31", inp, C.COS_COMBINE_ENSEMBLE, [0.125] * 8)
+
+
+# ---------------------------------------------------------------------------
+# degenerate cases of the method
+# ---------------------------------------------------------------------------
+
+def test_empty_batch_is_a_noop():
+    inp = _random_inputs(2, 1, 2, 64, "bf16", seed=1)
+    empty = {k: v[:, :0].contiguous() if k == "logits" else v[:0].contiguous() for k, v in inp.items()}
+    alen, toks = C.cos_verify(empty["logits"], empty["draft_tokens"], empty["proposer_idx"], 0, [0.5, 0.5],
+                              empty["u_accept"], empty["u_resample"])
+    assert alen.numel() == 0 and toks.numel() == 0
+
+
+def test_r_equals_q_accepts_every_draft():
+    inp = _random_inputs(1, 16, 4, 5000, "bf16", seed=21)
+    inp["logits"] = inp["logits"].repeat(3, 1, 1, 1).contiguous()          # three identical models
+    inp["proposer_idx"] = (torch.arange(16, device="cuda") % 3).to(torch.int32)
+    inp["u_accept"][0, :] = float(np.nextafter(1.0, 0.0))
+    alen, _, _, _ = _check("identical models", inp, C.COS_COMBINE_ENSEMBLE, [0.2, 0.5, 0.3])
+    assert np.all(alen == 4)
+    inp2 = _random_inputs(2, 16, 4, 5000, "bf16", seed=22)
+    inp2["proposer_idx"][:] = 1
+    alen, _, _, _ = _check("one-hot on proposer", inp2, C.COS_COMBINE_ENSEMBLE, [0.0, 1.0])
+    assert np.all(alen == 4)
+    inp2["proposer_idx"][:] = 0
+    alen, _, _, _ = _check("cd mu=0 alpha=0", inp2, C.COS_COMBINE_CONTRASTIVE, [0.0, 0.0])
+    assert np.all(alen == 4)
+
+
+def test_residual_without_mass_falls_back_to_r():
+    """Identical models and a draft token of probability zero: rejected, residual mass 0."""
+    inp = _random_inputs(1, 4, 2, 3000, "f32", seed=31)
+    inp["logits"] = inp["logits"].repeat(2, 1, 1, 1).contiguous()
+    inp["draft_tokens"][:, 0] = 7
+    inp["logits"][:, :, 0, 7] = float("-inf")
+    alen, toks, diag, rep = _check("zero residual mass", inp, C.COS_COMBINE_ENSEMBLE, [0.5, 0.5])
+    assert np.all(alen == 0)
+    assert np.all(diag.flags.cpu().numpy() & C.COS_FLAG_RESIDUAL_FALLBACK)
+    assert rep.flag_mismatches == 0
+
+
+def test_minus_inf_logits_and_extreme_uniforms():
+    inp = _random_inputs(2, 8, 3, 4096, "bf16", seed=41)
+    inp["logits"][:, :, :, 100:2100] = float("-inf")                       # whole tiles without mass
+    inp["draft_tokens"].clamp_(max=99)
+    inp["u_resample"][0] = 0.0
+    inp["u_resample"][1] = float(np.nextafter(1.0, 0.0))
+    inp["u_accept"][2, :] = 0.0
+    alen, toks, _, _ = _check("-inf tiles, u=0, u->1", inp, C.COS_COMBINE_ENSEMBLE, [0.4, 0.6])
+    for b in range(8):
+        assert not (100 <= toks[b, alen[b]] < 2100)
+    _check("-inf tiles contrastive", inp, C.COS_COMBINE_CONTRASTIVE, [0.5, 0.1])
+
+
+def test_results_do_not_depend_on_chunking_or_repeat():
+    inp = W.generate(W.C3.scaled(B=6), device="cuda")
+    ref = None
+    for cv in (0, 256, 1024, 8192, 0):
+        C.cos_tune_set_chunk_vectors(cv)
+        try:
+            alen, toks, diag = P.run_gpu(inp, W.C3.mode, W.C3.weights)
+        finally:
+            C.cos_tune_set_chunk_vectors(0)
+        if ref is None:
+            ref = (alen, toks)
+        assert np.array_equal(alen, ref[0]) and np.array_equal(toks, ref[1]), cv
+
+
+def test_workspace_can_be_reused_and_holds_garbage():
+    inp = W.generate(W.C2.scaled(B=4), device="cuda")
+    ws = C.allocate_workspace(2, 4, W.C2.gamma, W.C2.V, C.COS_DTYPE_BF16, W.C2.mode, "cuda")
+    ws.fill_(0xAB)
+    outs = []
+    for _ in range(3):
+        alen, toks = C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], W.C2.mode,
+                                  W.C2.weights, inp["u_accept"], inp["u_resample"], workspace=ws)
+        torch.cuda.synchronize()
+        outs.append((alen.cpu().numpy().copy(), toks.cpu().numpy().copy()))
+    for a, t in outs[1:]:
+        assert np.array_equal(a, outs[0][0]) and np.array_equal(t, outs[0][1])
+    rep = P.compare(inp, W.C2.mode, W.C2.weights, outs[0][0], outs[0][1], None)
+    _report("reused workspace", rep)
+
+
+def test_non_default_stream():
+    inp = W.generate(W.C1, device="cuda")
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        alen, toks = C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], W.C1.mode,
+                                  W.C1.weights, inp["u_accept"], inp["u_resample"])
+    s.synchronize()
+    rep = P.compare(inp, W.C1.mode, W.C1.weights, alen.cpu().numpy(), toks.cpu().numpy(), None)
+    _report("side stream", rep)
