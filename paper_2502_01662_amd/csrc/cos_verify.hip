@@ -2,20 +2,18 @@
 //
 // Structure (one GPU, one HIP stream, no host round trip):
 //
-//   fill kernel         zeroes the per-sequence arrival counters in the workspace
-//   streaming kernel    one workgroup per chunk of one logit row; reads every
-//                       logit exactly once and reduces it to a partial
-//                       (offset, sum 2^(l*log2e - offset)) softmax statistic
-//                       (Sec. 3.2).  Workgroups are ordered sequence-major, so
-//                       a sequence's rows stream through the chip together.
-//   finalize (same      the workgroup that completes a sequence (last arrival on
-//   kernel launch)      its counter) combines the partials in float64, runs the
-//                       acceptance test of Eq. (6) for the gamma drafts, finds the
-//                       first rejection (Sec. 3.1), then re-reads only the n rows
-//                       of that one position -- still resident in the memory-side
-//                       cache -- to build tile sums of f = max(0, r - q)
-//                       (App. A.1) or f = r (bonus), scans them and locates the
-//                       token by inverse CDF.
+//   fill kernel       zeroes the per-sequence arrival counters in the workspace.
+//   streaming kernel  one workgroup per chunk of one logit row; reads every logit
+//                     exactly once and reduces it to a partial softmax statistic
+//                     (offset o, Z = sum 2^(l*log2e - o)), Sec. 3.2.  The workgroup
+//                     that completes a sequence (last arrival on its counter)
+//                     combines the partials in float64, runs the acceptance test
+//                     of Eq. (6) for the gamma drafts, finds the first rejection
+//                     (Sec. 3.1) and leaves a small plan for the draw.
+//   sampling kernel   C workgroups per sequence re-read only the n rows of the one
+//                     position that is sampled and reduce f = max(0, r - q)
+//                     (App. A.1) or f = r (bonus) to tile sums; the last of them
+//                     scans the tile sums and locates the token by inverse CDF.
 //
 // Contrastive mode (Eq. (5) with a plausibility mask) needs the expert row's
 // maximum before anything can be masked, so a row-max kernel runs first.
@@ -24,6 +22,11 @@
 // in the log2 domain so that rescaling is exact; every cross-lane, cross-wave
 // and cross-workgroup combine, r(d), q(d), the accept decision, tile sums, the
 // scan and the CDF comparison are float64.
+//
+// Cross-workgroup hand-off: values another workgroup will read are written with
+// agent-scope atomic stores (write-through), the writer waits for them to
+// complete, then bumps an agent-scope counter; the workgroup that sees the final
+// count reads them back with agent-scope atomic loads.  No cache-wide fences.
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -34,20 +37,30 @@
 
 namespace {
 
-constexpr int kThreads = 256;            // 4 wavefronts of 64 lanes
+constexpr int kThreads = 256;  // 4 wavefronts of 64 lanes
 constexpr int kWaves = kThreads / 64;
-constexpr int kUnroll = 8;               // 16-byte loads in flight per lane and iteration
+constexpr int kUnroll = 8;  // 16-byte loads in flight per lane and iteration
 constexpr float kLog2e = 1.44269504088896340736f;
-constexpr int kNoOffset = -(1 << 29);    // "no finite element seen yet"
+constexpr int kNoOffset = -(1 << 29);       // "no finite element seen yet"
 constexpr float kMaxOffset = 268435456.0f;  // 2^28: clamp for absurd logits
-constexpr int kMaxSplits = 128;          // upper bound on chunks per row (workspace sizing)
-constexpr int kMaxStatsPerSeq = 256;     // (gamma+1) * statistics per position
+constexpr int kMaxSplits = 128;             // upper bound on chunks per row (workspace sizing)
+constexpr int kMaxStatsPerSeq = 256;        // (gamma+1) * statistics per position
+constexpr int kMaxTiles = 4096;             // tiles per row the final scan can hold in LDS
 
 // One partial softmax statistic: Z = sum_x 2^(l(x)*log2e - o) over a chunk.
 struct Partial {
   double Z;
   int o;
   int pad;
+};
+
+// What the streaming kernel leaves for the sampling kernel, per sequence.
+struct SeqPlan {
+  int jstar;     // position that is sampled = accepted_len
+  int residual;  // 1: f = max(0, r - q); 0: f = r (bonus)
+  int pi;        // proposer index
+  float m0;      // contrastive: expert maximum at jstar
+  double lse2[COS_MAX_MODELS];  // log2-sum-exp2 of the statistics at jstar
 };
 
 struct Params {
@@ -60,24 +73,27 @@ struct Params {
   int* accepted_len;
   int* out_tokens;
   // workspace
-  int* counters;      // [B]
+  int* counters;      // [2][B]: arrivals of the streaming kernel, then of the sampling kernel
   Partial* partials;  // [B][gamma+1][nstat][S]
   float* rowmax;      // contrastive: [B][gamma+1][S] partial maxima of the expert row
+  SeqPlan* plans;     // [B]
+  double* tile_sums;  // [B][ntiles]
   int S;              // chunks per row
   int cv;             // vectors per chunk
   int nvec;           // 16-byte vectors per row (last may be partial when unaligned)
   int ntiles;         // tiles (64 vectors) per row
   int nstat;          // statistics per position: n (ensemble) or 3 (contrastive)
+  int C;              // sampling workgroups per sequence
+  int tpc;            // tiles per sampling workgroup
   double w[COS_MAX_MODELS];  // ensemble weights; contrastive: w[0] = mu, w[1] = alpha_cd
   float mu_hi, mu_lo;        // mu split into two floats
   float thr32;               // smallest float >= ln(alpha_cd)
   double thr64;              // ln(alpha_cd)
   cos_diag_t diag;
-  int debug;  // TEMP experiment flags
 };
 
 // ---------------------------------------------------------------------------
-// wavefront primitives
+// wavefront and hand-off primitives
 // ---------------------------------------------------------------------------
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
@@ -118,6 +134,31 @@ __device__ __forceinline__ double wave_inclusive_scan(double v) {
 }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+template <typename U>
+__device__ __forceinline__ void store_agent(U* p, U v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+template <typename U>
+__device__ __forceinline__ U load_agent(const U* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Wait until this wavefront's outstanding stores have completed.
+__device__ __forceinline__ void wait_stores() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// Last-arrival test.  Every wavefront must have called wait_stores() after its
+// hand-off stores.  Returns true in every thread of exactly one workgroup per
+// counter: the one that arrives after all `total` workgroups have published.
+__device__ __forceinline__ bool arrive_last(int* counter, int total, int* s_flag) {
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const int prev = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    *s_flag = (prev == total - 1);
+  }
+  __syncthreads();
+  return *s_flag != 0;
+}
 
 // ---------------------------------------------------------------------------
 // 16-byte vector loads of logits, widened to float32
@@ -173,6 +214,30 @@ __device__ __forceinline__ void load_vec(const T* __restrict__ row, int vec, int
   }
 }
 
+// U vectors per lane starting at `base` (stride kThreads), all loads issued
+// before any use.  GUARDED: vectors at or past v1 read as -inf; their loads are
+// redirected to the in-range vector v1 - 1 so nothing is out of bounds.
+template <typename T, bool ALIGNED, bool GUARDED, int U>
+__device__ __forceinline__ void load_group(const T* __restrict__ row, int base, int v1, int V,
+                                           float (&x)[U][VecOf<T>::N]) {
+  constexpr int N = VecOf<T>::N;
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int v = base + u * kThreads + (int)threadIdx.x;
+    load_vec<T, ALIGNED>(row, GUARDED ? min(v, v1 - 1) : v, V, x[u]);
+  }
+  if constexpr (GUARDED) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int v = base + u * kThreads + (int)threadIdx.x;
+      if (v >= v1) {
+#pragma unroll
+        for (int k = 0; k < N; ++k) x[u][k] = -INFINITY;
+      }
+    }
+  }
+}
+
 template <typename T>
 __device__ __forceinline__ const T* row_ptr(const Params& p, int m, int b, int j) {
   const size_t row = ((size_t)m * p.B + b) * (size_t)(p.gamma + 1) + j;
@@ -216,38 +281,40 @@ __device__ __forceinline__ double running_total(const Running& r) {
   return wave_sum(z);
 }
 
+template <int U, int N>
+__device__ __forceinline__ void running_add(Running& run, const float (&x)[U][N]) {
+  float lm = -INFINITY;
+#pragma unroll
+  for (int u = 0; u < U; ++u)
+#pragma unroll
+    for (int k = 0; k < N; ++k) lm = fmaxf(lm, x[u][k]);
+  running_cover(run, wave_max(lm));
+  const float neg_o = -(float)run.o;
+#pragma unroll
+  for (int u = 0; u < U; ++u)
+#pragma unroll
+    for (int k = 0; k < N; ++k) run.acc[k & 3] += fast_exp2(fmaf(x[u][k], kLog2e, neg_o));
+}
+
 // Statistic of vectors [v0, v1) of one row, per wavefront (all lanes return the
 // wave's values).
 template <typename T, bool ALIGNED>
 __device__ __forceinline__ void chunk_stats(const T* __restrict__ row, int v0, int v1, int V,
                                             int& o_out, double& z_out) {
   constexpr int N = VecOf<T>::N;
+  constexpr int kStep = kThreads * kUnroll;
   Running run;
   running_init(run);
-  const int tid = threadIdx.x;
-  for (int base = v0; base < v1; base += kThreads * kUnroll) {
+  int base = v0;
+  for (; base + kStep <= v1; base += kStep) {
     float x[kUnroll][N];
-#pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-      const int v = base + u * kThreads + tid;
-      if (v < v1) {
-        load_vec<T, ALIGNED>(row, v, V, x[u]);
-      } else {
-#pragma unroll
-        for (int k = 0; k < N; ++k) x[u][k] = -INFINITY;
-      }
-    }
-    float lm = -INFINITY;
-#pragma unroll
-    for (int u = 0; u < kUnroll; ++u)
-#pragma unroll
-      for (int k = 0; k < N; ++k) lm = fmaxf(lm, x[u][k]);
-    running_cover(run, wave_max(lm));
-    const float neg_o = -(float)run.o;
-#pragma unroll
-    for (int u = 0; u < kUnroll; ++u)
-#pragma unroll
-      for (int k = 0; k < N; ++k) run.acc[k & 3] += fast_exp2(fmaf(x[u][k], kLog2e, neg_o));
+    load_group<T, ALIGNED, false, kUnroll>(row, base, v1, V, x);
+    running_add<kUnroll, N>(run, x);
+  }
+  if (base < v1) {
+    float x[kUnroll][N];
+    load_group<T, ALIGNED, true, kUnroll>(row, base, v1, V, x);
+    running_add<kUnroll, N>(run, x);
   }
   o_out = run.o;
   z_out = running_total(run);
@@ -269,7 +336,9 @@ __device__ __forceinline__ void publish_wave_stat(WaveStat* ws, int slot, int o,
   }
 }
 
-__device__ __forceinline__ Partial block_reduce_slot(const WaveStat* ws, int slot) {
+// Thread 0: combine the wavefronts' statistics of one slot and hand the partial
+// to the workgroup that will finish the sequence.
+__device__ __forceinline__ void store_partial(const WaveStat* ws, int slot, Partial* out) {
   int omax = kNoOffset;
   for (int w = 0; w < kWaves; ++w) {
     const WaveStat& s = ws[slot * kWaves + w];
@@ -280,109 +349,32 @@ __device__ __forceinline__ Partial block_reduce_slot(const WaveStat* ws, int slo
     const WaveStat& s = ws[slot * kWaves + w];
     if (s.z > 0.0) z += ldexp(s.z, s.o - omax);
   }
-  Partial p;
-  p.Z = z;
-  p.o = omax;
-  p.pad = 0;
-  return p;
+  store_agent(&out->Z, z);
+  store_agent(&out->o, omax);
 }
 
-// Last-arrival test: returns true in every thread of exactly one workgroup per
-// counter, after all `total` workgroups have published their partials.
-__device__ __forceinline__ bool arrive_last(int* counter, int total, int* s_flag, int debug = 0) {
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    if (!(debug & 2)) __threadfence();  // release: this workgroup's partials before the count
-    const int prev = atomicAdd(counter, 1);
-    *s_flag = (prev == total - 1);
-  }
-  __syncthreads();
-  const bool last = *s_flag != 0;
-  if (last) __threadfence();  // acquire: the other workgroups' partials
-  return last;
+__device__ __forceinline__ void store_empty_partial(Partial* out) {
+  store_agent(&out->Z, 0.0);
+  store_agent(&out->o, kNoOffset);
 }
 
 // ---------------------------------------------------------------------------
-// sampling weights f(x) of one 16-byte vector per model
+// decide one sequence (runs in the workgroup that arrived last on its counter)
 // ---------------------------------------------------------------------------
 
-// Ensemble: f = max(0, sum_m a_m 2^(l_m*log2e - K_m)); the a_m carry the
-// ensemble weights, minus one for the proposer when a residual is wanted
-// (App. A.1), times 2^(K_m - log2-sum-exp) so that the K_m are integers.  Each
-// product is rounded before it is added (no fused multiply-add), so that terms
-// of identical models cancel exactly and r == q leaves no residual mass.
-template <int NCAP, int N>
-__device__ __forceinline__ void eval_f_ensemble(const float (&x)[NCAP][N], int n,
-                                                const float* coef, const float* off,
-                                                float (&f)[N]) {
-#pragma unroll
-  for (int k = 0; k < N; ++k) {
-    float s = 0.0f;
-#pragma unroll
-    for (int m = 0; m < NCAP; ++m)
-      if (m < n) s += coef[m] * fast_exp2(fmaf(x[m][k], kLog2e, -off[m]));  // product rounded first
-    f[k] = fmaxf(s, 0.0f);
-  }
-}
-
-// Contrastive logit c = l_0 - mu*l_1 with mu = mu_hi + mu_lo.
-__device__ __forceinline__ float contrast(float l0, float l1, float mu_hi, float mu_lo) {
-  return fmaf(-mu_lo, l1, fmaf(-mu_hi, l1, l0));
-}
-
-// Plausibility mask: l_0 - max l_0 >= ln(alpha_cd), and a finite expert logit.
-// bf16 differences are exact in float32; float32 inputs compare in float64.
-template <typename T>
-__device__ __forceinline__ bool in_mask(float l0, float m0, float thr32, double thr64) {
-  if constexpr (sizeof(T) == 2) {
-    return (l0 > -INFINITY) && (l0 - m0 >= thr32);
-  } else {
-    return (l0 > -INFINITY) && ((double)l0 - (double)m0 >= thr64);
-  }
-}
-
-// Contrastive: r = [mask] coef[0] 2^(c*log2e - off[0]), q = coef[1] 2^(l_pi*log2e - off[1]);
-// f = max(0, r - q) on the mask (coef[1] = 0 for a bonus draw), 0 off it.
-template <typename T, int N>
-__device__ __forceinline__ void eval_f_contrastive(const float (&x0)[N], const float (&x1)[N],
-                                                   int pi, float m0, const Params& p,
-                                                   const float* coef, const float* off,
-                                                   float (&f)[N]) {
-#pragma unroll
-  for (int k = 0; k < N; ++k) {
-    const bool in = in_mask<T>(x0[k], m0, p.thr32, p.thr64);
-    const float c = contrast(x0[k], x1[k], p.mu_hi, p.mu_lo);
-    const float r = coef[0] * fast_exp2(fmaf(c, kLog2e, -off[0]));
-    const float lq = pi ? x1[k] : x0[k];
-    const float q = coef[1] * fast_exp2(fmaf(lq, kLog2e, -off[1]));
-    f[k] = in ? fmaxf(r - q, 0.0f) : 0.0f;
-  }
-}
-
-// ---------------------------------------------------------------------------
-// finalize one sequence (runs in the workgroup that arrived last)
-// ---------------------------------------------------------------------------
-
-struct FinalShared {
-  double lse2[kMaxStatsPerSeq];  // log2-sum-exp2 per (position, statistic)
+struct DecideShared {
+  double lse2[kMaxStatsPerSeq];     // log2-sum-exp2 per (position, statistic)
   float rowmax[COS_MAX_GAMMA + 1];  // contrastive: expert maximum per position
   int accept[COS_MAX_GAMMA + 1];
-  float coef[COS_MAX_MODELS];
-  float off[COS_MAX_MODELS];
-  int redo;
 };
 
-template <typename T, bool ALIGNED, int NM, bool CONTRASTIVE>
-__device__ void finalize_sequence(const Params& p, int b, FinalShared& sh, double* tile_sum) {
-  constexpr int N = VecOf<T>::N;
-  constexpr int NCAP = CONTRASTIVE ? 2 : (NM ? NM : COS_MAX_MODELS);
+template <typename T, bool CONTRASTIVE>
+__device__ void decide_sequence(const Params& p, int b, DecideShared& sh) {
   const int tid = threadIdx.x;
-  const int lane = lane_id();
-  const int wave = tid >> 6;
   const int g1 = p.gamma + 1;
   const int nstat = p.nstat;
   const int nrows = g1 * nstat;
-  const int n = CONTRASTIVE ? 2 : (NM ? NM : p.n);
+  const int n = p.n;
   const int pi = p.proposer[b];
   const double log2e = (double)kLog2e;
 
@@ -390,14 +382,21 @@ __device__ void finalize_sequence(const Params& p, int b, FinalShared& sh, doubl
   if (tid < nrows) {
     const Partial* pp = p.partials + ((size_t)b * nrows + tid) * p.S;
     int omax = kNoOffset;
-    for (int s = 0; s < p.S; ++s)
-      if (pp[s].Z > 0.0 && pp[s].o > omax) omax = pp[s].o;
-    double z = 0.0;
-    for (int s = 0; s < p.S; ++s)
-      if (pp[s].Z > 0.0) z += ldexp(pp[s].Z, pp[s].o - omax);
-    sh.lse2[tid] = (z > 0.0) ? (double)omax + log2(z) : -INFINITY;
+    for (int s = 0; s < p.S; ++s) {
+      const double z = load_agent(&pp[s].Z);
+      const int o = load_agent(&pp[s].o);
+      if (z > 0.0 && o > omax) omax = o;
+    }
+    double zsum = 0.0;
+    for (int s = 0; s < p.S; ++s) {
+      const double z = load_agent(&pp[s].Z);
+      const int o = load_agent(&pp[s].o);
+      if (z > 0.0) zsum += ldexp(z, o - omax);
+    }
+    sh.lse2[tid] = (zsum > 0.0) ? (double)omax + log2(zsum) : -INFINITY;
   }
   if (CONTRASTIVE && tid < g1) {
+    // written by the row-max kernel, an earlier launch on the same stream
     const float* rm = p.rowmax + ((size_t)b * g1 + tid) * p.S;
     float m0 = -INFINITY;
     for (int s = 0; s < p.S; ++s) m0 = fmaxf(m0, rm[s]);
@@ -440,7 +439,7 @@ __device__ void finalize_sequence(const Params& p, int b, FinalShared& sh, doubl
   }
   __syncthreads();
 
-  // 3. first rejection (Sec. 3.1)
+  // 3. first rejection (Sec. 3.1); the drawn token's slot is filled by the sampling kernel
   int jstar = p.gamma;
   for (int j = p.gamma - 1; j >= 0; --j)
     if (!sh.accept[j]) jstar = j;
@@ -448,182 +447,239 @@ __device__ void finalize_sequence(const Params& p, int b, FinalShared& sh, doubl
   if (tid < g1 && tid != jstar)
     p.out_tokens[(size_t)b * g1 + tid] = (tid < jstar) ? p.draft[(size_t)b * p.gamma + tid] : -1;
 
-  // 4.-6. tile sums of f at position jstar, scan, inverse CDF
-  bool residual = jstar < p.gamma;
-  int flags = 0;
-  const T* rows[NCAP];
-#pragma unroll
-  for (int m = 0; m < NCAP; ++m) rows[m] = row_ptr<T>(p, m < n ? m : 0, b, jstar);
-  const float m0 = CONTRASTIVE ? sh.rowmax[jstar] : 0.0f;
+  // 4. plan for the sampling kernel (read after this launch has ended)
+  SeqPlan* plan = p.plans + b;
+  if (tid == 0) {
+    plan->jstar = jstar;
+    plan->residual = jstar < p.gamma;
+    plan->pi = pi;
+    plan->m0 = CONTRASTIVE ? sh.rowmax[jstar] : 0.0f;
+  }
+  if (tid < nstat) plan->lse2[tid] = sh.lse2[jstar * nstat + tid];
+}
 
-  for (int attempt = 0; attempt < 2; ++attempt) {
-    // coefficients with integer offsets
-    if (tid < (CONTRASTIVE ? 2 : n)) {
+// ---------------------------------------------------------------------------
+// sampling weights f(x) of one 16-byte vector per model
+// ---------------------------------------------------------------------------
+
+// Ensemble: f = max(0, sum_m a_m 2^(l_m*log2e - K_m)); the a_m carry the
+// ensemble weights, minus one for the proposer when a residual is wanted
+// (App. A.1), times 2^(K_m - log2-sum-exp) so that the K_m are integers.  Each
+// product is rounded before it is added (no fused multiply-add), so that terms
+// of identical models cancel exactly and r == q leaves no residual mass.
+template <int NCAP, int N>
+__device__ __forceinline__ void eval_f_ensemble(const float (&x)[NCAP][N], int n,
+                                                const float (&coef)[NCAP], const float (&off)[NCAP],
+                                                float (&f)[N]) {
+#pragma unroll
+  for (int k = 0; k < N; ++k) {
+    float s = 0.0f;
+#pragma unroll
+    for (int m = 0; m < NCAP; ++m)
+      if (m < n) s += coef[m] * fast_exp2(fmaf(x[m][k], kLog2e, -off[m]));
+    f[k] = fmaxf(s, 0.0f);
+  }
+}
+
+// Contrastive logit c = l_0 - mu*l_1 with mu = mu_hi + mu_lo.
+__device__ __forceinline__ float contrast(float l0, float l1, float mu_hi, float mu_lo) {
+  return fmaf(-mu_lo, l1, fmaf(-mu_hi, l1, l0));
+}
+
+// Plausibility mask: l_0 - max l_0 >= ln(alpha_cd), and a finite expert logit.
+// bf16 differences are exact in float32; float32 inputs compare in float64.
+template <typename T>
+__device__ __forceinline__ bool in_mask(float l0, float m0, float thr32, double thr64) {
+  if constexpr (sizeof(T) == 2) {
+    return (l0 > -INFINITY) && (l0 - m0 >= thr32);
+  } else {
+    return (l0 > -INFINITY) && ((double)l0 - (double)m0 >= thr64);
+  }
+}
+
+// Contrastive: r = [mask] coef[0] 2^(c*log2e - off[0]), q = coef[1] 2^(l_pi*log2e - off[1]);
+// f = max(0, r - q) on the mask (coef[1] = 0 for a bonus draw), 0 off it.
+template <typename T, int N>
+__device__ __forceinline__ void eval_f_contrastive(const float (&x0)[N], const float (&x1)[N],
+                                                   int pi, float m0, const Params& p,
+                                                   const float (&coef)[2], const float (&off)[2],
+                                                   float (&f)[N]) {
+#pragma unroll
+  for (int k = 0; k < N; ++k) {
+    const bool in = in_mask<T>(x0[k], m0, p.thr32, p.thr64);
+    const float c = contrast(x0[k], x1[k], p.mu_hi, p.mu_lo);
+    const float r = coef[0] * fast_exp2(fmaf(c, kLog2e, -off[0]));
+    const float lq = pi ? x1[k] : x0[k];
+    const float q = coef[1] * fast_exp2(fmaf(lq, kLog2e, -off[1]));
+    f[k] = in ? fmaxf(r - q, 0.0f) : 0.0f;
+  }
+}
+
+// Coefficients and integer offsets of the sampling weights from a sequence's plan.
+template <int NCAP, bool CONTRASTIVE>
+__device__ __forceinline__ void plan_coefficients(const Params& p, const SeqPlan& plan, bool residual,
+                                                  int n, float (&coef)[NCAP], float (&off)[NCAP]) {
+#pragma unroll
+  for (int m = 0; m < NCAP; ++m) {
+    coef[m] = 0.0f;
+    off[m] = 0.0f;
+    if (m < n) {
       double a, lse;
       if constexpr (!CONTRASTIVE) {
-        a = p.w[tid] - ((residual && tid == pi) ? 1.0 : 0.0);
-        lse = sh.lse2[jstar * nstat + tid];
+        a = p.w[m] - ((residual && m == plan.pi) ? 1.0 : 0.0);
+        lse = plan.lse2[m];
       } else {
-        a = (tid == 0) ? 1.0 : (residual ? 1.0 : 0.0);
-        lse = sh.lse2[jstar * nstat + (tid == 0 ? 2 : pi)];
+        a = (m == 0) ? 1.0 : (residual ? 1.0 : 0.0);
+        lse = plan.lse2[m == 0 ? 2 : plan.pi];
       }
       const double K = rint(lse);
-      sh.off[tid] = (float)K;
-      sh.coef[tid] = (float)(a * exp2(K - lse));
+      off[m] = (float)K;
+      coef[m] = (float)(a * exp2(K - lse));
     }
-    if (tid == 0) sh.redo = 0;
-    __syncthreads();
-    float coef[NCAP], off[NCAP];
-#pragma unroll
-    for (int m = 0; m < NCAP; ++m) {
-      coef[m] = (m < n) ? sh.coef[m] : 0.0f;
-      off[m] = (m < n) ? sh.off[m] : 0.0f;
-    }
-
-    // pass 1: one tile = 64 lanes x one 16-byte vector per model
-    for (int tile = wave; tile < p.ntiles; tile += kWaves) {
-      const int vec = tile * 64 + lane;
-      double ls = 0.0;
-      if (vec < p.nvec) {
-        float x[NCAP][N];
-#pragma unroll
-        for (int m = 0; m < NCAP; ++m)
-          if (m < n) load_vec<T, ALIGNED>(rows[m], vec, p.V, x[m]);
-        float f[N];
-        if constexpr (!CONTRASTIVE)
-          eval_f_ensemble<NCAP, N>(x, n, coef, off, f);
-        else
-          eval_f_contrastive<T, N>(x[0], x[1], pi, m0, p, coef, off, f);
-#pragma unroll
-        for (int k = 0; k < N; ++k) ls += (double)f[k];
-      }
-      const double ts = wave_sum(ls);
-      if (lane == 0) tile_sum[tile] = ts;
-    }
-    __syncthreads();
-
-    if (wave == 0) {
-      // scan of the tile sums: each lane owns a contiguous segment
-      const int per = (p.ntiles + 63) / 64;
-      const int t0 = min(lane * per, p.ntiles), t1 = min(t0 + per, p.ntiles);
-      double seg = 0.0;
-      for (int t = t0; t < t1; ++t) seg += tile_sum[t];
-      const double incl = wave_inclusive_scan(seg);
-      const double F = __shfl(incl, 63, 64);
-      const double up = __shfl_up(incl, 1, 64);
-      const double excl = lane ? up : 0.0;
-      const bool bad = !(F > 0.0) || !(F < INFINITY);
-      if (bad && residual && attempt == 0) {
-        if (lane == 0) sh.redo = 1;  // residual has no mass: draw from r itself
-      } else {
-        const double target = p.u_resample[b] * F;
-        // first tile whose inclusive prefix exceeds the target; else the last tile with mass
-        int hit = -1, lastpos = -1;
-        double hit_excl = 0.0, lastpos_excl = 0.0, runsum = excl;
-        for (int t = t0; t < t1; ++t) {
-          const double ts = tile_sum[t];
-          const double nxt = runsum + ts;
-          if (hit < 0 && nxt > target) {
-            hit = t;
-            hit_excl = runsum;
-          }
-          if (ts > 0.0) {
-            lastpos = t;
-            lastpos_excl = runsum;
-          }
-          runsum = nxt;
-        }
-        const unsigned long long hits = __ballot(hit >= 0);
-        const unsigned long long poss = __ballot(lastpos >= 0);
-        bool clamp = false;
-        int tile = 0;
-        double tile_excl = 0.0;
-        if (hits) {
-          const int src = __ffsll((long long)hits) - 1;
-          tile = __shfl(hit, src, 64);
-          tile_excl = __shfl(hit_excl, src, 64);
-        } else {
-          clamp = true;
-          if (poss) {
-            const int src = 63 - __clzll((long long)poss);
-            tile = __shfl(lastpos, src, 64);
-            tile_excl = __shfl(lastpos_excl, src, 64);
-          }
-        }
-
-        // pass 2: the same f values of that one tile, scanned element by element
-        const int vec = tile * 64 + lane;
-        float f[N];
-#pragma unroll
-        for (int k = 0; k < N; ++k) f[k] = 0.0f;
-        if (vec < p.nvec) {
-          float x[NCAP][N];
-#pragma unroll
-          for (int m = 0; m < NCAP; ++m)
-            if (m < n) load_vec<T, ALIGNED>(rows[m], vec, p.V, x[m]);
-          if constexpr (!CONTRASTIVE)
-            eval_f_ensemble<NCAP, N>(x, n, coef, off, f);
-          else
-            eval_f_contrastive<T, N>(x[0], x[1], pi, m0, p, coef, off, f);
-        }
-        double lane_tot = 0.0;
-#pragma unroll
-        for (int k = 0; k < N; ++k) lane_tot += (double)f[k];
-        const double lincl = wave_inclusive_scan(lane_tot);
-        const double lup = __shfl_up(lincl, 1, 64);
-        const double lexcl = tile_excl + (lane ? lup : 0.0);
-        int ksel = -1, klast = -1;
-        double lo_sel = 0.0, hi_sel = 0.0, lo_last = 0.0, hi_last = 0.0, runl = lexcl;
-#pragma unroll
-        for (int k = 0; k < N; ++k) {
-          const double nxt = runl + (double)f[k];
-          if (ksel < 0 && nxt > target) {
-            ksel = k;
-            lo_sel = runl;
-            hi_sel = nxt;
-          }
-          if (f[k] > 0.0f) {
-            klast = k;
-            lo_last = runl;
-            hi_last = nxt;
-          }
-          runl = nxt;
-        }
-        const unsigned long long sel = clamp ? 0ull : __ballot(ksel >= 0);
-        const unsigned long long pos = __ballot(klast >= 0);
-        int src = 0, kk = 0;
-        double lo = 0.0, hi = 0.0;
-        if (sel) {
-          src = __ffsll((long long)sel) - 1;
-          kk = ksel;
-          lo = lo_sel;
-          hi = hi_sel;
-        } else {
-          // rounding left no prefix above the target inside this tile (or tail
-          // clamp): take the last element with mass
-          if (pos) src = 63 - __clzll((long long)pos);
-          kk = klast < 0 ? 0 : klast;
-          lo = lo_last;
-          hi = hi_last;
-          if (clamp) flags |= COS_FLAG_TAIL_CLAMP;
-        }
-        if (lane == src) {
-          int token = (tile * 64 + lane) * N + kk;
-          token = min(max(token, 0), p.V - 1);
-          p.out_tokens[(size_t)b * g1 + jstar] = token;
-          if (p.diag.sample_mass) p.diag.sample_mass[b] = F;
-          if (p.diag.cdf_lo) p.diag.cdf_lo[b] = lo / F;
-          if (p.diag.cdf_hi) p.diag.cdf_hi[b] = hi / F;
-          if (p.diag.flags) p.diag.flags[b] = flags;
-        }
-      }
-    }
-    __syncthreads();
-    if (!sh.redo) break;
-    residual = false;
-    flags |= COS_FLAG_RESIDUAL_FALLBACK;
-    __syncthreads();
   }
+}
+
+// f of one tile (64 lanes x one vector per model) for this lane; 0 past the row's end.
+template <typename T, bool ALIGNED, int NCAP, bool CONTRASTIVE>
+__device__ __forceinline__ void tile_weights(const Params& p, const T* const (&rows)[NCAP], int n,
+                                             int tile, int pi, float m0, const float (&coef)[NCAP],
+                                             const float (&off)[NCAP], float (&f)[VecOf<T>::N]) {
+  constexpr int N = VecOf<T>::N;
+  const int vec = tile * 64 + lane_id();
+  float x[NCAP][N];
+  const int vc = min(vec, p.nvec - 1);  // keep the load in range; masked below
+#pragma unroll
+  for (int m = 0; m < NCAP; ++m)
+    if (m < n) load_vec<T, ALIGNED>(rows[m], vc, p.V, x[m]);
+  if constexpr (!CONTRASTIVE)
+    eval_f_ensemble<NCAP, N>(x, n, coef, off, f);
+  else
+    eval_f_contrastive<T, N>(x[0], x[1], pi, m0, p, coef, off, f);
+  if (vec >= p.nvec) {
+#pragma unroll
+    for (int k = 0; k < N; ++k) f[k] = 0.0f;
+  }
+}
+
+template <int N>
+__device__ __forceinline__ double lane_mass(const float (&f)[N]) {
+  double s = 0.0;
+#pragma unroll
+  for (int k = 0; k < N; ++k) s += (double)f[k];
+  return s;
+}
+
+// ---------------------------------------------------------------------------
+// final scan + inverse CDF of one sequence (wavefront 0 of the last sampling
+// workgroup); tile_sum holds the ntiles tile sums in LDS.
+// Returns false if the weights have no mass and may_retry is set.
+// ---------------------------------------------------------------------------
+template <typename T, bool ALIGNED, int NCAP, bool CONTRASTIVE>
+__device__ bool draw_token(const Params& p, int b, const SeqPlan& plan, const T* const (&rows)[NCAP],
+                           int n, const float (&coef)[NCAP], const float (&off)[NCAP],
+                           const double* tile_sum, bool may_retry, int flags) {
+  constexpr int N = VecOf<T>::N;
+  const int lane = lane_id();
+  const int g1 = p.gamma + 1;
+  // scan of the tile sums: each lane owns a contiguous segment
+  const int per = (p.ntiles + 63) / 64;
+  const int t0 = min(lane * per, p.ntiles), t1 = min(t0 + per, p.ntiles);
+  double seg = 0.0;
+  for (int t = t0; t < t1; ++t) seg += tile_sum[t];
+  const double incl = wave_inclusive_scan(seg);
+  const double F = __shfl(incl, 63, 64);
+  const double up = __shfl_up(incl, 1, 64);
+  const double excl = lane ? up : 0.0;
+  const bool bad = !(F > 0.0) || !(F < INFINITY);
+  if (bad && may_retry) return false;
+
+  const double target = p.u_resample[b] * F;
+  // first tile whose inclusive prefix exceeds the target; else the last tile with mass
+  int hit = -1, lastpos = -1;
+  double hit_excl = 0.0, lastpos_excl = 0.0, runsum = excl;
+  for (int t = t0; t < t1; ++t) {
+    const double ts = tile_sum[t];
+    const double nxt = runsum + ts;
+    if (hit < 0 && nxt > target) {
+      hit = t;
+      hit_excl = runsum;
+    }
+    if (ts > 0.0) {
+      lastpos = t;
+      lastpos_excl = runsum;
+    }
+    runsum = nxt;
+  }
+  const unsigned long long hits = __ballot(hit >= 0);
+  const unsigned long long poss = __ballot(lastpos >= 0);
+  bool clamp = false;
+  int tile = 0;
+  double tile_excl = 0.0;
+  if (hits) {
+    const int src = __ffsll((long long)hits) - 1;
+    tile = __shfl(hit, src, 64);
+    tile_excl = __shfl(hit_excl, src, 64);
+  } else {
+    clamp = true;
+    if (poss) {
+      const int src = 63 - __clzll((long long)poss);
+      tile = __shfl(lastpos, src, 64);
+      tile_excl = __shfl(lastpos_excl, src, 64);
+    }
+  }
+
+  // the same f values of that one tile, scanned element by element
+  float f[N];
+  tile_weights<T, ALIGNED, NCAP, CONTRASTIVE>(p, rows, n, tile, plan.pi, plan.m0, coef, off, f);
+  const double lane_tot = lane_mass<N>(f);
+  const double lincl = wave_inclusive_scan(lane_tot);
+  const double lup = __shfl_up(lincl, 1, 64);
+  const double lexcl = tile_excl + (lane ? lup : 0.0);
+  int ksel = -1, klast = -1;
+  double lo_sel = 0.0, hi_sel = 0.0, lo_last = 0.0, hi_last = 0.0, runl = lexcl;
+#pragma unroll
+  for (int k = 0; k < N; ++k) {
+    const double nxt = runl + (double)f[k];
+    if (ksel < 0 && nxt > target) {
+      ksel = k;
+      lo_sel = runl;
+      hi_sel = nxt;
+    }
+    if (f[k] > 0.0f) {
+      klast = k;
+      lo_last = runl;
+      hi_last = nxt;
+    }
+    runl = nxt;
+  }
+  const unsigned long long sel = clamp ? 0ull : __ballot(ksel >= 0);
+  const unsigned long long pos = __ballot(klast >= 0);
+  int src = 0, kk = 0;
+  double lo = 0.0, hi = 0.0;
+  if (sel) {
+    src = __ffsll((long long)sel) - 1;
+    kk = ksel;
+    lo = lo_sel;
+    hi = hi_sel;
+  } else {
+    // rounding left no prefix above the target inside this tile (or tail clamp):
+    // take the last element with mass
+    if (pos) src = 63 - __clzll((long long)pos);
+    kk = klast < 0 ? 0 : klast;
+    lo = lo_last;
+    hi = hi_last;
+    if (clamp) flags |= COS_FLAG_TAIL_CLAMP;
+  }
+  if (lane == src) {
+    int token = (tile * 64 + lane) * N + kk;
+    token = min(max(token, 0), p.V - 1);
+    p.out_tokens[(size_t)b * g1 + plan.jstar] = token;
+    if (p.diag.sample_mass) p.diag.sample_mass[b] = F;
+    if (p.diag.cdf_lo) p.diag.cdf_lo[b] = lo / F;
+    if (p.diag.cdf_hi) p.diag.cdf_hi[b] = hi / F;
+    if (p.diag.flags) p.diag.flags[b] = flags;
+  }
+  return true;
 }
 
 // ---------------------------------------------------------------------------
@@ -636,11 +692,10 @@ __global__ void __launch_bounds__(kThreads) fill_zero_kernel(int* dst, int count
 }
 
 // Ensemble streaming kernel.  Workgroup index -> (b, j, m, s), b slowest.
-template <typename T, bool ALIGNED, int NM>
-__global__ void __launch_bounds__(kThreads) ensemble_kernel(Params p) {
-  extern __shared__ double tile_sum[];
+template <typename T, bool ALIGNED>
+__global__ void __launch_bounds__(kThreads) ensemble_stats_kernel(Params p) {
   __shared__ WaveStat ws[kWaves];
-  __shared__ FinalShared sh;
+  __shared__ DecideShared sh;
   __shared__ int s_flag;
 
   const int g1 = p.gamma + 1;
@@ -660,17 +715,18 @@ __global__ void __launch_bounds__(kThreads) ensemble_kernel(Params p) {
   chunk_stats<T, ALIGNED>(row, v0, v1, p.V, o, z);
   publish_wave_stat(ws, 0, o, z);
   __syncthreads();
-  if (threadIdx.x == 0)
-    p.partials[(((size_t)b * g1 + j) * p.n + m) * p.S + s] = block_reduce_slot(ws, 0);
-
-  if (arrive_last(p.counters + b, per_b, &s_flag, p.debug) && !(p.debug & 1))
-    finalize_sequence<T, ALIGNED, NM, false>(p, b, sh, tile_sum);
+  if (threadIdx.x == 0) {
+    store_partial(ws, 0, p.partials + (((size_t)b * g1 + j) * p.n + m) * p.S + s);
+    wait_stores();
+  }
+  if (arrive_last(p.counters + b, per_b, &s_flag)) decide_sequence<T, false>(p, b, sh);
 }
 
 // Contrastive, kernel 1: partial maxima of the expert row (model 0).
 template <typename T, bool ALIGNED>
 __global__ void __launch_bounds__(kThreads) expert_rowmax_kernel(Params p) {
   constexpr int N = VecOf<T>::N;
+  constexpr int kStep = kThreads * kUnroll;
   __shared__ float wmax[kWaves];
   const int g1 = p.gamma + 1;
   const int rs = blockIdx.x / p.S;  // b * g1 + j
@@ -680,18 +736,12 @@ __global__ void __launch_bounds__(kThreads) expert_rowmax_kernel(Params p) {
   const int v0 = s * p.cv;
   const int v1 = min(v0 + p.cv, p.nvec);
   float lm = -INFINITY;
-  for (int base = v0; base < v1; base += kThreads * kUnroll) {
+  for (int base = v0; base < v1; base += kStep) {
     float x[kUnroll][N];
-#pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-      const int v = base + u * kThreads + threadIdx.x;
-      if (v < v1) {
-        load_vec<T, ALIGNED>(row, v, p.V, x[u]);
-      } else {
-#pragma unroll
-        for (int k = 0; k < N; ++k) x[u][k] = -INFINITY;
-      }
-    }
+    if (base + kStep <= v1)
+      load_group<T, ALIGNED, false, kUnroll>(row, base, v1, p.V, x);
+    else
+      load_group<T, ALIGNED, true, kUnroll>(row, base, v1, p.V, x);
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u)
 #pragma unroll
@@ -708,15 +758,15 @@ __global__ void __launch_bounds__(kThreads) expert_rowmax_kernel(Params p) {
 }
 
 // Contrastive, kernel 2.  Workgroup index -> (b, j, s); reads the chunk of both
-// rows once and produces three statistics: the proposer row's softmax sum and
-// the masked sum of 2^(c*log2e - o) (Eq. (5) restricted to the mask).
+// rows once and produces the proposer row's softmax statistic and the masked
+// statistic of the contrastive logits (Eq. (5) restricted to the mask).
 template <typename T, bool ALIGNED>
-__global__ void __launch_bounds__(kThreads) contrastive_kernel(Params p) {
+__global__ void __launch_bounds__(kThreads) contrastive_stats_kernel(Params p) {
   constexpr int N = VecOf<T>::N;
   constexpr int U = kUnroll / 2;
-  extern __shared__ double tile_sum[];
+  constexpr int kStep = kThreads * U;
   __shared__ WaveStat ws[2 * kWaves];
-  __shared__ FinalShared sh;
+  __shared__ DecideShared sh;
   __shared__ int s_flag;
   __shared__ float s_m0[kWaves];
 
@@ -729,7 +779,7 @@ __global__ void __launch_bounds__(kThreads) contrastive_kernel(Params p) {
   const int pi = p.proposer[b];
   const int tid = threadIdx.x;
 
-  // expert maximum of this position from kernel 1's partial maxima
+  // expert maximum of this position from the row-max kernel's partial maxima
   {
     const float* rm = p.rowmax + ((size_t)b * g1 + j) * p.S;
     float lm = -INFINITY;
@@ -748,32 +798,20 @@ __global__ void __launch_bounds__(kThreads) contrastive_kernel(Params p) {
   Running rq, rc;  // proposer row; masked contrastive logits
   running_init(rq);
   running_init(rc);
-  for (int base = v0; base < v1; base += kThreads * U) {
+  for (int base = v0; base < v1; base += kStep) {
     float x0[U][N], x1[U][N];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int v = base + u * kThreads + tid;
-      if (v < v1) {
-        load_vec<T, ALIGNED>(row0, v, p.V, x0[u]);
-        load_vec<T, ALIGNED>(row1, v, p.V, x1[u]);
-      } else {
-#pragma unroll
-        for (int k = 0; k < N; ++k) x0[u][k] = x1[u][k] = -INFINITY;
-      }
+    if (base + kStep <= v1) {
+      load_group<T, ALIGNED, false, U>(row0, base, v1, p.V, x0);
+      load_group<T, ALIGNED, false, U>(row1, base, v1, p.V, x1);
+    } else {
+      load_group<T, ALIGNED, true, U>(row0, base, v1, p.V, x0);
+      load_group<T, ALIGNED, true, U>(row1, base, v1, p.V, x1);
     }
     // proposer row statistic
-    float lm = -INFINITY;
-#pragma unroll
-    for (int u = 0; u < U; ++u)
-#pragma unroll
-      for (int k = 0; k < N; ++k) lm = fmaxf(lm, pi ? x1[u][k] : x0[u][k]);
-    running_cover(rq, wave_max(lm));
-    const float neg_oq = -(float)rq.o;
-#pragma unroll
-    for (int u = 0; u < U; ++u)
-#pragma unroll
-      for (int k = 0; k < N; ++k)
-        rq.acc[k & 3] += fast_exp2(fmaf(pi ? x1[u][k] : x0[u][k], kLog2e, neg_oq));
+    if (pi)
+      running_add<U, N>(rq, x1);
+    else
+      running_add<U, N>(rq, x0);
     // masked contrastive statistic; the mask is sparse, so skip wave-wide when empty
     float c[U][N];
     float lmc = -INFINITY;
@@ -785,14 +823,7 @@ __global__ void __launch_bounds__(kThreads) contrastive_kernel(Params p) {
         c[u][k] = in ? contrast(x0[u][k], x1[u][k], p.mu_hi, p.mu_lo) : -INFINITY;
         lmc = fmaxf(lmc, c[u][k]);
       }
-    if (__ballot(lmc > -INFINITY)) {
-      running_cover(rc, wave_max(lmc));
-      const float neg_oc = -(float)rc.o;
-#pragma unroll
-      for (int u = 0; u < U; ++u)
-#pragma unroll
-        for (int k = 0; k < N; ++k) rc.acc[k & 3] += fast_exp2(fmaf(c[u][k], kLog2e, neg_oc));
-    }
+    if (__ballot(lmc > -INFINITY)) running_add<U, N>(rc, c);
   }
   const double zq = running_total(rq);
   const double zc = running_total(rc);
@@ -801,17 +832,78 @@ __global__ void __launch_bounds__(kThreads) contrastive_kernel(Params p) {
   __syncthreads();
   if (tid == 0) {
     Partial* out = p.partials + (((size_t)b * g1 + j) * 3) * p.S;
-    Partial none;
-    none.Z = 0.0;
-    none.o = kNoOffset;
-    none.pad = 0;
-    out[(size_t)pi * p.S + s] = block_reduce_slot(ws, 0);
-    out[(size_t)(1 - pi) * p.S + s] = none;
-    out[(size_t)2 * p.S + s] = block_reduce_slot(ws, 1);
+    store_partial(ws, 0, out + (size_t)pi * p.S + s);
+    store_empty_partial(out + (size_t)(1 - pi) * p.S + s);
+    store_partial(ws, 1, out + (size_t)2 * p.S + s);
+    wait_stores();
   }
+  if (arrive_last(p.counters + b, per_b, &s_flag)) decide_sequence<T, true>(p, b, sh);
+}
 
-  if (arrive_last(p.counters + b, per_b, &s_flag))
-    finalize_sequence<T, ALIGNED, 2, true>(p, b, sh, tile_sum);
+// Sampling kernel.  Workgroup index -> (b, c): tiles [c*tpc, (c+1)*tpc) of the
+// sampled position's rows -> tile sums; the last workgroup of b draws the token.
+template <typename T, bool ALIGNED, int NM, bool CONTRASTIVE>
+__global__ void __launch_bounds__(kThreads) sample_kernel(Params p) {
+  constexpr int N = VecOf<T>::N;
+  constexpr int NCAP = CONTRASTIVE ? 2 : (NM ? NM : COS_MAX_MODELS);
+  constexpr int TU = NCAP <= 2 ? 4 : (NCAP <= 4 ? 2 : 1);  // tiles in flight per wavefront
+  extern __shared__ double tile_sum[];
+  __shared__ int s_flag;
+
+  const int b = blockIdx.x / p.C;
+  const int c = blockIdx.x - b * p.C;
+  const int lane = lane_id();
+  const int wave = threadIdx.x >> 6;
+  const int n = CONTRASTIVE ? 2 : (NM ? NM : p.n);
+  const SeqPlan plan = p.plans[b];
+  const T* rows[NCAP];
+#pragma unroll
+  for (int m = 0; m < NCAP; ++m) rows[m] = row_ptr<T>(p, m < n ? m : 0, b, plan.jstar);
+  float coef[NCAP], off[NCAP];
+  plan_coefficients<NCAP, CONTRASTIVE>(p, plan, plan.residual != 0, n, coef, off);
+
+  double* sums = p.tile_sums + (size_t)b * p.ntiles;
+  const int tb = c * p.tpc;
+  const int te = min(tb + p.tpc, p.ntiles);
+  for (int t = tb + wave * TU; t < te; t += kWaves * TU) {
+    float f[TU][N];
+#pragma unroll
+    for (int i = 0; i < TU; ++i)
+      tile_weights<T, ALIGNED, NCAP, CONTRASTIVE>(p, rows, n, min(t + i, te - 1), plan.pi, plan.m0,
+                                                  coef, off, f[i]);
+#pragma unroll
+    for (int i = 0; i < TU; ++i) {
+      const double ts = wave_sum(lane_mass<N>(f[i]));
+      if (lane == 0 && t + i < te) store_agent(sums + t + i, ts);
+    }
+  }
+  wait_stores();
+  if (!arrive_last(p.counters + p.B + b, p.C, &s_flag)) return;
+
+  // last workgroup of this sequence: all tile sums are published
+  for (int t = threadIdx.x; t < p.ntiles; t += kThreads) tile_sum[t] = load_agent(sums + t);
+  __syncthreads();
+  bool done = false;
+  if (wave == 0)
+    done = draw_token<T, ALIGNED, NCAP, CONTRASTIVE>(p, b, plan, rows, n, coef, off, tile_sum,
+                                                     plan.residual != 0, 0);
+  if (threadIdx.x == 0) s_flag = done ? 0 : 1;
+  __syncthreads();
+  if (!s_flag) return;
+
+  // The residual has no mass (cannot happen in exact arithmetic): draw from r
+  // itself.  Rare, so this one workgroup recomputes every tile sum.
+  plan_coefficients<NCAP, CONTRASTIVE>(p, plan, false, n, coef, off);
+  for (int t = wave; t < p.ntiles; t += kWaves) {
+    float f[N];
+    tile_weights<T, ALIGNED, NCAP, CONTRASTIVE>(p, rows, n, t, plan.pi, plan.m0, coef, off, f);
+    const double ts = wave_sum(lane_mass<N>(f));
+    if (lane == 0) tile_sum[t] = ts;
+  }
+  __syncthreads();
+  if (wave == 0)
+    draw_token<T, ALIGNED, NCAP, CONTRASTIVE>(p, b, plan, rows, n, coef, off, tile_sum, false,
+                                              COS_FLAG_RESIDUAL_FALLBACK);
 }
 
 // ---------------------------------------------------------------------------
@@ -819,6 +911,7 @@ __global__ void __launch_bounds__(kThreads) contrastive_kernel(Params p) {
 // ---------------------------------------------------------------------------
 
 int g_chunk_vectors = 0;  // 0 = heuristic
+
 // Optional event ring around the streaming kernel (benchmarks only).
 constexpr int kMaxProfileSlots = 1024;
 hipEvent_t g_ev_start[kMaxProfileSlots], g_ev_stop[kMaxProfileSlots];
@@ -827,8 +920,8 @@ int g_ev_slots = 0;     // pairs in use (0 = profiling off)
 int g_ev_recorded = 0;  // calls recorded since the last enable
 
 struct Plan {
-  int nvec, ntiles, S, cv, nstat;
-  size_t off_counters, off_partials, off_rowmax, bytes;
+  int nvec, ntiles, nstat;
+  size_t off_counters, off_partials, off_rowmax, off_plans, off_tiles, bytes;
 };
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -838,7 +931,7 @@ bool shape_ok(int n, int B, int gamma, int V) {
          V >= 1 && V <= COS_MAX_VOCAB;
 }
 
-// Workspace layout for the largest split count the library may choose.
+// Workspace layout for S chunks per row.
 void plan_layout(int n, int B, int gamma, int V, cos_dtype_t dt, cos_combine_t mode, int S,
                  Plan* pl) {
   const int N = dt == COS_DTYPE_F32 ? 4 : 8;
@@ -846,11 +939,18 @@ void plan_layout(int n, int B, int gamma, int V, cos_dtype_t dt, cos_combine_t m
   pl->ntiles = (pl->nvec + 63) / 64;
   pl->nstat = mode == COS_COMBINE_CONTRASTIVE ? 3 : n;
   const size_t g1 = (size_t)gamma + 1;
-  pl->off_counters = 0;
-  pl->off_partials = align_up((size_t)B * sizeof(int), 256);
-  pl->off_rowmax = pl->off_partials + align_up((size_t)B * g1 * pl->nstat * S * sizeof(Partial), 256);
-  pl->bytes = pl->off_rowmax +
-              (mode == COS_COMBINE_CONTRASTIVE ? align_up((size_t)B * g1 * S * sizeof(float), 256) : 0);
+  size_t at = 0;
+  pl->off_counters = at;
+  at += align_up((size_t)2 * B * sizeof(int), 256);
+  pl->off_plans = at;
+  at += align_up((size_t)B * sizeof(SeqPlan), 256);
+  pl->off_tiles = at;
+  at += align_up((size_t)B * pl->ntiles * sizeof(double), 256);
+  pl->off_rowmax = at;
+  if (mode == COS_COMBINE_CONTRASTIVE) at += align_up((size_t)B * g1 * S * sizeof(float), 256);
+  pl->off_partials = at;
+  at += align_up((size_t)B * g1 * pl->nstat * S * sizeof(Partial), 256);
+  pl->bytes = at;
 }
 
 int max_splits(int nvec) {
@@ -866,8 +966,7 @@ void choose_split(int rows_total, int nvec, int* S_out, int* cv_out) {
     cv = g_chunk_vectors;
   } else {
     const int cap = 4096;  // 64 KB
-    long want_blocks = 4096;
-    long s_want = (want_blocks + rows_total - 1) / (rows_total > 0 ? rows_total : 1);
+    long s_want = (4096 + rows_total - 1) / (rows_total > 0 ? rows_total : 1);
     if (s_want < 1) s_want = 1;
     cv = (int)((nvec + s_want - 1) / s_want);
     if (cv > cap) cv = cap;
@@ -886,34 +985,60 @@ void choose_split(int rows_total, int nvec, int* S_out, int* cv_out) {
   *cv_out = cv;
 }
 
-template <typename T, bool ALIGNED>
-cos_status_t launch_ensemble(const Params& p, size_t lds, hipStream_t st) {
-  const long blocks = (long)p.B * (p.gamma + 1) * p.n * p.S;
+// Sampling workgroups per sequence: about 2048 in total, at least 4 tiles each.
+void choose_sampling(int B, int ntiles, int* C_out, int* tpc_out) {
+  int C = (2048 + B - 1) / B;
+  const int cmax = (ntiles + 3) / 4;
+  if (C > cmax) C = cmax;
+  if (C < 1) C = 1;
+  const int tpc = (ntiles + C - 1) / C;
+  *C_out = (ntiles + tpc - 1) / tpc;
+  *tpc_out = tpc;
+}
+
+template <typename T, bool ALIGNED, bool CONTRASTIVE>
+cos_status_t launch_sampling(const Params& p, size_t lds, hipStream_t st) {
+  const long blocks = (long)p.B * p.C;
   if (blocks <= 0 || blocks > 0x7fffffffL) return COS_ERR_SHAPE;
   const dim3 grid((unsigned)blocks), block(kThreads);
-  if constexpr (ALIGNED) {
+  if constexpr (CONTRASTIVE) {
+    hipLaunchKernelGGL((sample_kernel<T, ALIGNED, 2, true>), grid, block, lds, st, p);
+  } else if constexpr (ALIGNED) {
     switch (p.n) {
-      case 2: hipLaunchKernelGGL((ensemble_kernel<T, ALIGNED, 2>), grid, block, lds, st, p); break;
-      case 3: hipLaunchKernelGGL((ensemble_kernel<T, ALIGNED, 3>), grid, block, lds, st, p); break;
-      case 4: hipLaunchKernelGGL((ensemble_kernel<T, ALIGNED, 4>), grid, block, lds, st, p); break;
-      default: hipLaunchKernelGGL((ensemble_kernel<T, ALIGNED, 0>), grid, block, lds, st, p); break;
+      case 1: hipLaunchKernelGGL((sample_kernel<T, true, 1, false>), grid, block, lds, st, p); break;
+      case 2: hipLaunchKernelGGL((sample_kernel<T, true, 2, false>), grid, block, lds, st, p); break;
+      case 3: hipLaunchKernelGGL((sample_kernel<T, true, 3, false>), grid, block, lds, st, p); break;
+      case 4: hipLaunchKernelGGL((sample_kernel<T, true, 4, false>), grid, block, lds, st, p); break;
+      default: hipLaunchKernelGGL((sample_kernel<T, true, 0, false>), grid, block, lds, st, p); break;
     }
   } else {
-    hipLaunchKernelGGL((ensemble_kernel<T, ALIGNED, 0>), grid, block, lds, st, p);
+    hipLaunchKernelGGL((sample_kernel<T, false, 0, false>), grid, block, lds, st, p);
   }
   return hipGetLastError() == hipSuccess ? COS_OK : COS_ERR_LAUNCH;
 }
 
 template <typename T, bool ALIGNED>
-cos_status_t launch_contrastive(const Params& p, size_t lds, hipStream_t st, hipEvent_t ev_start) {
+cos_status_t launch_all(const Params& p, bool contrastive, size_t lds, hipStream_t st,
+                        hipEvent_t ev_start, hipEvent_t ev_stop) {
+  const dim3 block(kThreads);
+  if (!contrastive) {
+    const long blocks = (long)p.B * (p.gamma + 1) * p.n * p.S;
+    if (blocks <= 0 || blocks > 0x7fffffffL) return COS_ERR_SHAPE;
+    if (ev_start) (void)hipEventRecord(ev_start, st);
+    hipLaunchKernelGGL((ensemble_stats_kernel<T, ALIGNED>), dim3((unsigned)blocks), block, 0, st, p);
+    if (ev_stop) (void)hipEventRecord(ev_stop, st);
+    if (hipGetLastError() != hipSuccess) return COS_ERR_LAUNCH;
+    return launch_sampling<T, ALIGNED, false>(p, lds, st);
+  }
   const long blocks = (long)p.B * (p.gamma + 1) * p.S;
   if (blocks <= 0 || blocks > 0x7fffffffL) return COS_ERR_SHAPE;
-  const dim3 grid((unsigned)blocks), block(kThreads);
-  hipLaunchKernelGGL((expert_rowmax_kernel<T, ALIGNED>), grid, block, 0, st, p);
+  hipLaunchKernelGGL((expert_rowmax_kernel<T, ALIGNED>), dim3((unsigned)blocks), block, 0, st, p);
   if (hipGetLastError() != hipSuccess) return COS_ERR_LAUNCH;
   if (ev_start) (void)hipEventRecord(ev_start, st);
-  hipLaunchKernelGGL((contrastive_kernel<T, ALIGNED>), grid, block, lds, st, p);
-  return hipGetLastError() == hipSuccess ? COS_OK : COS_ERR_LAUNCH;
+  hipLaunchKernelGGL((contrastive_stats_kernel<T, ALIGNED>), dim3((unsigned)blocks), block, 0, st, p);
+  if (ev_stop) (void)hipEventRecord(ev_stop, st);
+  if (hipGetLastError() != hipSuccess) return COS_ERR_LAUNCH;
+  return launch_sampling<T, ALIGNED, true>(p, lds, st);
 }
 
 }  // namespace
@@ -942,9 +1067,10 @@ cos_status_t cos_verify(const void* logits, cos_dtype_t dt, int n, int B, int ga
   if (dt != COS_DTYPE_F32 && dt != COS_DTYPE_BF16) return COS_ERR_DTYPE;
   if (combine_mode != COS_COMBINE_ENSEMBLE && combine_mode != COS_COMBINE_CONTRASTIVE)
     return COS_ERR_MODE;
-  if (combine_mode == COS_COMBINE_CONTRASTIVE && n != 2) return COS_ERR_MODE;
+  const bool contrastive = combine_mode == COS_COMBINE_CONTRASTIVE;
+  if (contrastive && n != 2) return COS_ERR_MODE;
   if (!weights) return COS_ERR_NULL;
-  if (combine_mode == COS_COMBINE_ENSEMBLE) {
+  if (!contrastive) {
     double sum = 0.0;
     for (int m = 0; m < n; ++m) {
       if (!(weights[m] >= 0.0) || !std::isfinite(weights[m])) return COS_ERR_WEIGHTS;
@@ -964,18 +1090,17 @@ cos_status_t cos_verify(const void* logits, cos_dtype_t dt, int n, int B, int ga
   const size_t need = cos_verify_workspace_bytes(n, B, gamma, V, dt, combine_mode);
   if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256 || workspace_bytes < need)
     return COS_ERR_WORKSPACE;
-  if ((size_t)(gamma + 1) * (combine_mode == COS_COMBINE_CONTRASTIVE ? 3 : n) > kMaxStatsPerSeq)
-    return COS_ERR_SHAPE;
+  if ((size_t)(gamma + 1) * (contrastive ? 3 : n) > kMaxStatsPerSeq) return COS_ERR_SHAPE;
 
   // ---- launch plan ----
   const int N = dt == COS_DTYPE_F32 ? 4 : 8;
   const int nvec = (V + N - 1) / N;
-  const int rows_total = (combine_mode == COS_COMBINE_CONTRASTIVE ? 1 : n) * B * (gamma + 1);
+  const int rows_total = (contrastive ? 1 : n) * B * (gamma + 1);
   int S, cv;
   choose_split(rows_total, nvec, &S, &cv);
   Plan pl;
   plan_layout(n, B, gamma, V, dt, combine_mode, S, &pl);
-  if (pl.bytes > workspace_bytes) return COS_ERR_WORKSPACE;
+  if (pl.bytes > workspace_bytes || pl.ntiles > kMaxTiles) return COS_ERR_WORKSPACE;
 
   Params p;
   p.logits = logits;
@@ -993,16 +1118,19 @@ cos_status_t cos_verify(const void* logits, cos_dtype_t dt, int n, int B, int ga
   p.counters = reinterpret_cast<int*>(wsb + pl.off_counters);
   p.partials = reinterpret_cast<Partial*>(wsb + pl.off_partials);
   p.rowmax = reinterpret_cast<float*>(wsb + pl.off_rowmax);
+  p.plans = reinterpret_cast<SeqPlan*>(wsb + pl.off_plans);
+  p.tile_sums = reinterpret_cast<double*>(wsb + pl.off_tiles);
   p.S = S;
   p.cv = cv;
   p.nvec = pl.nvec;
   p.ntiles = pl.ntiles;
   p.nstat = pl.nstat;
+  choose_sampling(B, pl.ntiles, &p.C, &p.tpc);
   for (int m = 0; m < COS_MAX_MODELS; ++m) p.w[m] = m < n ? weights[m] : 0.0;
   p.mu_hi = p.mu_lo = 0.0f;
   p.thr32 = -INFINITY;
   p.thr64 = -INFINITY;
-  if (combine_mode == COS_COMBINE_CONTRASTIVE) {
+  if (contrastive) {
     p.mu_hi = (float)weights[0];
     p.mu_lo = (float)(weights[0] - (double)p.mu_hi);
     if (weights[1] > 0.0) {
@@ -1020,38 +1148,26 @@ cos_status_t cos_verify(const void* logits, cos_dtype_t dt, int n, int B, int ga
     p.diag.flags = nullptr;
   }
 
-  p.debug = std::getenv("COS_DEBUG_FLAGS") ? std::atoi(std::getenv("COS_DEBUG_FLAGS")) : 0;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   const bool aligned = (reinterpret_cast<uintptr_t>(logits) % 16 == 0) && (V % N == 0);
   const size_t lds = (size_t)pl.ntiles * sizeof(double);
   const bool profile = g_ev_slots > 0;
   const int slot = profile ? g_ev_recorded % g_ev_slots : 0;
   hipEvent_t ev_start = profile ? g_ev_start[slot] : nullptr;
+  hipEvent_t ev_stop = profile ? g_ev_stop[slot] : nullptr;
 
-  hipLaunchKernelGGL(fill_zero_kernel, dim3((B + kThreads - 1) / kThreads), dim3(kThreads), 0, st,
-                     p.counters, B);
+  hipLaunchKernelGGL(fill_zero_kernel, dim3((2 * B + kThreads - 1) / kThreads), dim3(kThreads), 0,
+                     st, p.counters, 2 * B);
   if (hipGetLastError() != hipSuccess) return COS_ERR_LAUNCH;
 
   cos_status_t rc;
-  if (combine_mode == COS_COMBINE_ENSEMBLE) {
-    if (profile) (void)hipEventRecord(ev_start, st);
-    if (dt == COS_DTYPE_F32)
-      rc = aligned ? launch_ensemble<float, true>(p, lds, st) : launch_ensemble<float, false>(p, lds, st);
-    else
-      rc = aligned ? launch_ensemble<uint16_t, true>(p, lds, st)
-                   : launch_ensemble<uint16_t, false>(p, lds, st);
-  } else {
-    if (dt == COS_DTYPE_F32)
-      rc = aligned ? launch_contrastive<float, true>(p, lds, st, ev_start)
-                   : launch_contrastive<float, false>(p, lds, st, ev_start);
-    else
-      rc = aligned ? launch_contrastive<uint16_t, true>(p, lds, st, ev_start)
-                   : launch_contrastive<uint16_t, false>(p, lds, st, ev_start);
-  }
-  if (profile) {
-    (void)hipEventRecord(g_ev_stop[slot], st);
-    ++g_ev_recorded;
-  }
+  if (dt == COS_DTYPE_F32)
+    rc = aligned ? launch_all<float, true>(p, contrastive, lds, st, ev_start, ev_stop)
+                 : launch_all<float, false>(p, contrastive, lds, st, ev_start, ev_stop);
+  else
+    rc = aligned ? launch_all<uint16_t, true>(p, contrastive, lds, st, ev_start, ev_stop)
+                 : launch_all<uint16_t, false>(p, contrastive, lds, st, ev_start, ev_stop);
+  if (profile) ++g_ev_recorded;
   return rc;
 }
 
