@@ -95,7 +95,7 @@ def main() -> int:
     value = w.positions / (ms_per_step * 1e-3)
 
     achieved = w.logit_bytes / (kavg * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": "contrastive_kernel" if w.mode == W.CONTRASTIVE else "ensemble_kernel",
+    roofline = {"bound": "hbm", "kernel": "contrastive_stats_kernel" if w.mode == W.CONTRASTIVE else "ensemble_stats_kernel",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": _traffic_from_profiles(args.workload),
                 "algorithmic_bytes_per_launch": w.logit_bytes, "kernel_avg_ms": round(kavg, 5),
@@ -106,8 +106,9 @@ def main() -> int:
     parity = None
     cpu_rows = args.cpu_rows
     if cpu_rows < 0:
-        # ~20 s of single-core work: about 35 ns per logit element the sequential procedure touches
-        per_row = w.n * (w.gamma + 1) * w.V * 35e-9
+        # ~20 core-seconds: about 6 ns per logit element, of which the sequential procedure
+        # (it stops at the first rejection) touches roughly half
+        per_row = w.n * (w.gamma + 1) * w.V * 3e-9
         cpu_rows = int(max(1, min(w.B, round(20.0 / per_row))))
     if cpu_rows > 0:
         from oracle import cos_oracle as O

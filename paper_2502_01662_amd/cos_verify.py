@@ -14,7 +14,8 @@ from typing import Optional, Sequence
 import torch
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIBRARY = os.path.join(_PKG, "libcosverify.so")
+# COS_VERIFY_LIBRARY selects another build of the same library (kernel experiments).
+LIBRARY = os.environ.get("COS_VERIFY_LIBRARY") or os.path.join(_PKG, "libcosverify.so")
 
 COS_DTYPE_F32 = 0
 COS_DTYPE_BF16 = 1

@@ -46,6 +46,10 @@ constexpr float kMaxOffset = 268435456.0f;  // 2^28: clamp for absurd logits
 constexpr int kMaxSplits = 128;             // upper bound on chunks per row (workspace sizing)
 constexpr int kMaxStatsPerSeq = 256;        // (gamma+1) * statistics per position
 constexpr int kMaxTiles = 4096;             // tiles per row the final scan can hold in LDS
+// Arrival counters are agent-scope atomics executed at the memory side; one
+// counter per 256 bytes spreads them over the memory channels (packed counters
+// serialise on one channel and slow every stream that crosses it).
+constexpr int kCtrStride = 64;  // ints between two counters
 
 // One partial softmax statistic: Z = sum_x 2^(l(x)*log2e - o) over a chunk.
 struct Partial {
@@ -73,7 +77,7 @@ struct Params {
   int* accepted_len;
   int* out_tokens;
   // workspace
-  int* counters;      // [2][B]: arrivals of the streaming kernel, then of the sampling kernel
+  int* counters;      // [2][B] (stride kCtrStride): arrivals of the streaming, then the sampling kernel
   Partial* partials;  // [B][gamma+1][nstat][S]
   float* rowmax;      // contrastive: [B][gamma+1][S] partial maxima of the expert row
   SeqPlan* plans;     // [B]
@@ -169,6 +173,14 @@ struct VecOf {
   static constexpr int N = 16 / sizeof(T);
 };
 
+// Every logit is read once per pass: 16-byte loads carry the non-temporal hint,
+// which measurably raises the sustained read rate of a streaming kernel here.
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_stream16(const void* p) {
+  const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 __device__ __forceinline__ float widen(float x) { return x; }
 __device__ __forceinline__ float widen(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
 
@@ -205,7 +217,7 @@ __device__ __forceinline__ void load_vec(const T* __restrict__ row, int vec, int
                                          float (&x)[VecOf<T>::N]) {
   constexpr int N = VecOf<T>::N;
   if constexpr (ALIGNED) {
-    const uint4 raw = *reinterpret_cast<const uint4*>(row + (size_t)vec * N);
+    const uint4 raw = load_stream16(row + (size_t)vec * N);
     unpack<T>(raw, x);
   } else {
     const int base = vec * N;
@@ -296,6 +308,96 @@ __device__ __forceinline__ void running_add(Running& run, const float (&x)[U][N]
     for (int k = 0; k < N; ++k) run.acc[k & 3] += fast_exp2(fmaf(x[u][k], kLog2e, neg_o));
 }
 
+// ---- raw-register variant for 16-byte aligned rows -------------------------
+//
+// For bf16 the maximum is taken on the raw bit patterns with packed 16-bit
+// integer maxima: among non-negative floats integer order equals float order,
+// and a pattern with the sign bit set never wins against one without, so
+// whenever the wave-wide result is non-negative it is the true maximum;
+// otherwise (every element negative) the float path below decides.
+
+typedef short short2_t __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ int wave_max_i32(int v) {
+#define COS_DPP_IMAX(ctrl, row_mask) \
+  v = max(v, __builtin_amdgcn_update_dpp(v, v, ctrl, row_mask, 0xf, false));
+  COS_DPP_IMAX(0x111, 0xf)  // row_shr:1
+  COS_DPP_IMAX(0x112, 0xf)  // row_shr:2
+  COS_DPP_IMAX(0x114, 0xf)  // row_shr:4
+  COS_DPP_IMAX(0x118, 0xf)  // row_shr:8
+  COS_DPP_IMAX(0x142, 0xa)  // row_bcast:15 into rows 1 and 3
+  COS_DPP_IMAX(0x143, 0xc)  // row_bcast:31 into rows 2 and 3
+#undef COS_DPP_IMAX
+  return __builtin_amdgcn_readlane(v, 63);
+}
+
+// U raw vectors per lane starting at `base` (stride kThreads); vectors at or
+// past v1 are redirected to the in-range vector v1 - 1 (masked by the caller).
+template <typename T, int U>
+__device__ __forceinline__ void load_raw_group(const T* __restrict__ row, int base, int v1,
+                                               uint4 (&raw)[U]) {
+  const uint4* src = reinterpret_cast<const uint4*>(row);
+#pragma unroll
+  for (int u = 0; u < U; ++u)
+    raw[u] = load_stream16(src + min(base + u * kThreads + (int)threadIdx.x, v1 - 1));
+}
+
+// Replace vectors at or past v1 by -inf (only the last, partial group needs it).
+template <typename T, int U>
+__device__ __forceinline__ void mask_raw_group(int base, int v1, uint4 (&raw)[U]) {
+  const uint32_t ninf = sizeof(T) == 2 ? 0xff80ff80u : 0xff800000u;
+#pragma unroll
+  for (int u = 0; u < U; ++u)
+    if (base + u * kThreads + (int)threadIdx.x >= v1) raw[u] = make_uint4(ninf, ninf, ninf, ninf);
+}
+
+template <typename T, int U>
+__device__ __forceinline__ void running_add_raw(Running& run, const uint4 (&raw)[U]) {
+  constexpr int N = VecOf<T>::N;
+  if constexpr (sizeof(T) == 2) {
+    short2_t m = __builtin_bit_cast(short2_t, raw[0].x);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      m = __builtin_elementwise_max(m, __builtin_bit_cast(short2_t, raw[u].x));
+      m = __builtin_elementwise_max(m, __builtin_bit_cast(short2_t, raw[u].y));
+      m = __builtin_elementwise_max(m, __builtin_bit_cast(short2_t, raw[u].z));
+      m = __builtin_elementwise_max(m, __builtin_bit_cast(short2_t, raw[u].w));
+    }
+    const int wm16 = wave_max_i32(max((int)m.x, (int)m.y));
+    if (wm16 >= 0) {
+      running_cover(run, __uint_as_float((uint32_t)wm16 << 16));
+    } else {
+      float lm = -INFINITY;
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        float x[N];
+        unpack<T>(raw[u], x);
+#pragma unroll
+        for (int k = 0; k < N; ++k) lm = fmaxf(lm, x[k]);
+      }
+      running_cover(run, wave_max(lm));
+    }
+  } else {
+    float lm = -INFINITY;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float x[N];
+      unpack<T>(raw[u], x);
+#pragma unroll
+      for (int k = 0; k < N; ++k) lm = fmaxf(lm, x[k]);
+    }
+    running_cover(run, wave_max(lm));
+  }
+  const float neg_o = -(float)run.o;
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    float x[N];
+    unpack<T>(raw[u], x);
+#pragma unroll
+    for (int k = 0; k < N; ++k) run.acc[k & 3] += fast_exp2(fmaf(x[k], kLog2e, neg_o));
+  }
+}
+
 // Statistic of vectors [v0, v1) of one row, per wavefront (all lanes return the
 // wave's values).
 template <typename T, bool ALIGNED>
@@ -305,16 +407,27 @@ __device__ __forceinline__ void chunk_stats(const T* __restrict__ row, int v0, i
   constexpr int kStep = kThreads * kUnroll;
   Running run;
   running_init(run);
-  int base = v0;
-  for (; base + kStep <= v1; base += kStep) {
-    float x[kUnroll][N];
-    load_group<T, ALIGNED, false, kUnroll>(row, base, v1, V, x);
-    running_add<kUnroll, N>(run, x);
-  }
-  if (base < v1) {
-    float x[kUnroll][N];
-    load_group<T, ALIGNED, true, kUnroll>(row, base, v1, V, x);
-    running_add<kUnroll, N>(run, x);
+  if constexpr (ALIGNED) {
+    // all kUnroll loads of a group are issued before the first use; only the
+    // last group of a chunk can be partial
+    for (int base = v0; base < v1; base += kStep) {
+      uint4 a[kUnroll];
+      load_raw_group<T, kUnroll>(row, base, v1, a);
+      if (base + kStep > v1) mask_raw_group<T, kUnroll>(base, v1, a);
+      running_add_raw<T, kUnroll>(run, a);
+    }
+  } else {
+    int base = v0;
+    for (; base + kStep <= v1; base += kStep) {
+      float x[kUnroll][N];
+      load_group<T, ALIGNED, false, kUnroll>(row, base, v1, V, x);
+      running_add<kUnroll, N>(run, x);
+    }
+    if (base < v1) {
+      float x[kUnroll][N];
+      load_group<T, ALIGNED, true, kUnroll>(row, base, v1, V, x);
+      running_add<kUnroll, N>(run, x);
+    }
   }
   o_out = run.o;
   z_out = running_total(run);
@@ -719,7 +832,7 @@ __global__ void __launch_bounds__(kThreads) ensemble_stats_kernel(Params p) {
     store_partial(ws, 0, p.partials + (((size_t)b * g1 + j) * p.n + m) * p.S + s);
     wait_stores();
   }
-  if (arrive_last(p.counters + b, per_b, &s_flag)) decide_sequence<T, false>(p, b, sh);
+  if (arrive_last(p.counters + (size_t)b * kCtrStride, per_b, &s_flag)) decide_sequence<T, false>(p, b, sh);
 }
 
 // Contrastive, kernel 1: partial maxima of the expert row (model 0).
@@ -763,7 +876,7 @@ __global__ void __launch_bounds__(kThreads) expert_rowmax_kernel(Params p) {
 template <typename T, bool ALIGNED>
 __global__ void __launch_bounds__(kThreads) contrastive_stats_kernel(Params p) {
   constexpr int N = VecOf<T>::N;
-  constexpr int U = kUnroll / 2;
+  constexpr int U = kUnroll >= 2 ? kUnroll / 2 : 1;
   constexpr int kStep = kThreads * U;
   __shared__ WaveStat ws[2 * kWaves];
   __shared__ DecideShared sh;
@@ -837,7 +950,7 @@ __global__ void __launch_bounds__(kThreads) contrastive_stats_kernel(Params p) {
     store_partial(ws, 1, out + (size_t)2 * p.S + s);
     wait_stores();
   }
-  if (arrive_last(p.counters + b, per_b, &s_flag)) decide_sequence<T, true>(p, b, sh);
+  if (arrive_last(p.counters + (size_t)b * kCtrStride, per_b, &s_flag)) decide_sequence<T, true>(p, b, sh);
 }
 
 // Sampling kernel.  Workgroup index -> (b, c): tiles [c*tpc, (c+1)*tpc) of the
@@ -878,7 +991,7 @@ __global__ void __launch_bounds__(kThreads) sample_kernel(Params p) {
     }
   }
   wait_stores();
-  if (!arrive_last(p.counters + p.B + b, p.C, &s_flag)) return;
+  if (!arrive_last(p.counters + (size_t)(p.B + b) * kCtrStride, p.C, &s_flag)) return;
 
   // last workgroup of this sequence: all tile sums are published
   for (int t = threadIdx.x; t < p.ntiles; t += kThreads) tile_sum[t] = load_agent(sums + t);
@@ -941,7 +1054,7 @@ void plan_layout(int n, int B, int gamma, int V, cos_dtype_t dt, cos_combine_t m
   const size_t g1 = (size_t)gamma + 1;
   size_t at = 0;
   pl->off_counters = at;
-  at += align_up((size_t)2 * B * sizeof(int), 256);
+  at += align_up((size_t)2 * B * kCtrStride * sizeof(int), 256);
   pl->off_plans = at;
   at += align_up((size_t)B * sizeof(SeqPlan), 256);
   pl->off_tiles = at;
@@ -958,18 +1071,17 @@ int max_splits(int nvec) {
   return s < kMaxSplits ? (s < 1 ? 1 : s) : kMaxSplits;
 }
 
-// Chunks per row: enough workgroups to fill 256 CUs several times over when the
-// batch is small, at most ~64 KB of one row per workgroup when it is large.
+// Chunks per row.  A workgroup's start-up and hand-off cost is paid per chunk,
+// so chunks are as long as possible: whole rows once there are a few thousand
+// rows, otherwise just enough chunks to fill 256 CUs several times over.
 void choose_split(int rows_total, int nvec, int* S_out, int* cv_out) {
   int cv;
   if (g_chunk_vectors > 0) {
     cv = g_chunk_vectors;
   } else {
-    const int cap = 4096;  // 64 KB
-    long s_want = (4096 + rows_total - 1) / (rows_total > 0 ? rows_total : 1);
+    long s_want = (3072 + rows_total - 1) / (rows_total > 0 ? rows_total : 1);
     if (s_want < 1) s_want = 1;
     cv = (int)((nvec + s_want - 1) / s_want);
-    if (cv > cap) cv = cap;
   }
   cv = (cv + kThreads - 1) / kThreads * kThreads;
   if (cv < kThreads) cv = kThreads;
@@ -1156,8 +1268,9 @@ cos_status_t cos_verify(const void* logits, cos_dtype_t dt, int n, int B, int ga
   hipEvent_t ev_start = profile ? g_ev_start[slot] : nullptr;
   hipEvent_t ev_stop = profile ? g_ev_stop[slot] : nullptr;
 
-  hipLaunchKernelGGL(fill_zero_kernel, dim3((2 * B + kThreads - 1) / kThreads), dim3(kThreads), 0,
-                     st, p.counters, 2 * B);
+  const int nctr = 2 * B * kCtrStride;
+  hipLaunchKernelGGL(fill_zero_kernel, dim3((nctr + kThreads - 1) / kThreads), dim3(kThreads), 0, st,
+                     p.counters, nctr);
   if (hipGetLastError() != hipSuccess) return COS_ERR_LAUNCH;
 
   cos_status_t rc;
