@@ -39,6 +39,7 @@ def main() -> int:
     ap.add_argument("--batch", type=int, default=0, help="override B (debugging only; changes the workload name)")
     ap.add_argument("--cpu-rows", type=int, default=-1, help="batch rows the CPU oracle is timed on (-1 = auto, 0 = skip)")
     ap.add_argument("--chunk-vectors", type=int, default=0, help="tuning knob (0 = library heuristic)")
+    ap.add_argument("--sample-blocks", type=int, default=0, help="tuning knob (0 = library heuristic)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (rows of the batch shard without any exchange; "
@@ -60,6 +61,7 @@ def main() -> int:
         w = w.scaled(B=args.batch, name=f"{w.name}_B{args.batch}")
     C.load_library()
     C.cos_tune_set_chunk_vectors(args.chunk_vectors)
+    C.cos_tune_set_sample_blocks(args.sample_blocks)
 
     t0 = time.time()
     # small workloads: rotate over distinct input sets so that the timed calls stream from HBM,
@@ -143,7 +145,8 @@ def main() -> int:
         "logit_storage": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "n": w.n, "B": w.B, "gamma": w.gamma, "V": w.V,
                    "combine": "contrastive" if w.mode == W.CONTRASTIVE else "ensemble", "weights": list(w.weights),
-                   "input_sets_rotated": nsets, "chunk_vectors": args.chunk_vectors},
+                   "input_sets_rotated": nsets, "chunk_vectors": args.chunk_vectors,
+                   "sample_blocks": args.sample_blocks},
         "achieved_hbm_gbs_per_step": round(w.logit_bytes / (ms_per_step * 1e-3) / 1e9, 1),
         "roofline": roofline, "cpu_baseline": cpu, "parity_sample": parity,
         "input_generation_s": round(gen_s, 1),

@@ -135,6 +135,13 @@ cos_status_t cos_profile_kernel_ms(int index, float *ms);
  */
 void cos_tune_set_chunk_vectors(int vectors);
 
+/*
+ * Tuning knob for experiments: total number of workgroups the sampling kernel
+ * aims for (each sequence gets ceil(blocks / B) of them, at least 4 tiles
+ * each).  0 restores the built-in heuristic.  Process-wide.
+ */
+void cos_tune_set_sample_blocks(int blocks);
+
 #ifdef __cplusplus
 }
 #endif

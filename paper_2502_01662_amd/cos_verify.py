@@ -67,6 +67,8 @@ def load_library() -> ctypes.CDLL:
         lib.cos_profile_kernel_ms.restype = ci
         lib.cos_tune_set_chunk_vectors.argtypes = [ci]
         lib.cos_tune_set_chunk_vectors.restype = None
+        lib.cos_tune_set_sample_blocks.argtypes = [ci]
+        lib.cos_tune_set_sample_blocks.restype = None
         _lib = lib
     return _lib
 
@@ -103,6 +105,10 @@ def cos_profile_kernel_ms(index: int) -> float:
 
 def cos_tune_set_chunk_vectors(vectors: int) -> None:
     load_library().cos_tune_set_chunk_vectors(int(vectors))
+
+
+def cos_tune_set_sample_blocks(blocks: int) -> None:
+    load_library().cos_tune_set_sample_blocks(int(blocks))
 
 
 @dataclass

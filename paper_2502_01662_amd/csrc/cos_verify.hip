@@ -127,6 +127,26 @@ __device__ __forceinline__ double wave_sum(double v) {
   return v;
 }
 
+// Sum over the 64 lanes with DPP moves (no LDS traffic); the total is valid in
+// lane 63 only.
+__device__ __forceinline__ double wave_sum_to_lane63(double v) {
+#define COS_DPP_DSUM(ctrl, row_mask)                                                            \
+  {                                                                                             \
+    const long long bits = __double_as_longlong(v);                                             \
+    const int lo = __builtin_amdgcn_update_dpp(0, (int)bits, ctrl, row_mask, 0xf, false);       \
+    const int hi = __builtin_amdgcn_update_dpp(0, (int)(bits >> 32), ctrl, row_mask, 0xf, false); \
+    v += __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);                        \
+  }
+  COS_DPP_DSUM(0x111, 0xf)  // row_shr:1  (lanes without a source add +0.0)
+  COS_DPP_DSUM(0x112, 0xf)  // row_shr:2
+  COS_DPP_DSUM(0x114, 0xf)  // row_shr:4
+  COS_DPP_DSUM(0x118, 0xf)  // row_shr:8
+  COS_DPP_DSUM(0x142, 0xa)  // row_bcast:15 into rows 1 and 3
+  COS_DPP_DSUM(0x143, 0xc)  // row_bcast:31 into rows 2 and 3
+#undef COS_DPP_DSUM
+  return v;
+}
+
 __device__ __forceinline__ double wave_inclusive_scan(double v) {
   const int lane = lane_id();
 #pragma unroll
@@ -652,26 +672,40 @@ __device__ __forceinline__ void plan_coefficients(const Params& p, const SeqPlan
   }
 }
 
-// f of one tile (64 lanes x one vector per model) for this lane; 0 past the row's end.
-template <typename T, bool ALIGNED, int NCAP, bool CONTRASTIVE>
-__device__ __forceinline__ void tile_weights(const Params& p, const T* const (&rows)[NCAP], int n,
-                                             int tile, int pi, float m0, const float (&coef)[NCAP],
-                                             const float (&off)[NCAP], float (&f)[VecOf<T>::N]) {
-  constexpr int N = VecOf<T>::N;
-  const int vec = tile * 64 + lane_id();
-  float x[NCAP][N];
-  const int vc = min(vec, p.nvec - 1);  // keep the load in range; masked below
+// Raw vectors of one tile (64 lanes x one 16-byte vector per model) for this lane.
+// Tiles past the row's end are redirected to the last vector (masked in tile_eval).
+template <typename T, bool ALIGNED, int NCAP>
+__device__ __forceinline__ void tile_load(const Params& p, const T* const (&rows)[NCAP], int n, int tile,
+                                          float (&x)[NCAP][VecOf<T>::N]) {
+  const int vc = min(tile * 64 + lane_id(), p.nvec - 1);
 #pragma unroll
   for (int m = 0; m < NCAP; ++m)
     if (m < n) load_vec<T, ALIGNED>(rows[m], vc, p.V, x[m]);
+}
+
+// f of the loaded tile for this lane; 0 past the row's end.
+template <typename T, int NCAP, bool CONTRASTIVE>
+__device__ __forceinline__ void tile_eval(const Params& p, const float (&x)[NCAP][VecOf<T>::N], int n,
+                                          int tile, int pi, float m0, const float (&coef)[NCAP],
+                                          const float (&off)[NCAP], float (&f)[VecOf<T>::N]) {
+  constexpr int N = VecOf<T>::N;
   if constexpr (!CONTRASTIVE)
     eval_f_ensemble<NCAP, N>(x, n, coef, off, f);
   else
     eval_f_contrastive<T, N>(x[0], x[1], pi, m0, p, coef, off, f);
-  if (vec >= p.nvec) {
+  if (tile * 64 + lane_id() >= p.nvec) {
 #pragma unroll
     for (int k = 0; k < N; ++k) f[k] = 0.0f;
   }
+}
+
+template <typename T, bool ALIGNED, int NCAP, bool CONTRASTIVE>
+__device__ __forceinline__ void tile_weights(const Params& p, const T* const (&rows)[NCAP], int n,
+                                             int tile, int pi, float m0, const float (&coef)[NCAP],
+                                             const float (&off)[NCAP], float (&f)[VecOf<T>::N]) {
+  float x[NCAP][VecOf<T>::N];
+  tile_load<T, ALIGNED, NCAP>(p, rows, n, tile, x);
+  tile_eval<T, NCAP, CONTRASTIVE>(p, x, n, tile, pi, m0, coef, off, f);
 }
 
 template <int N>
@@ -959,7 +993,7 @@ template <typename T, bool ALIGNED, int NM, bool CONTRASTIVE>
 __global__ void __launch_bounds__(kThreads) sample_kernel(Params p) {
   constexpr int N = VecOf<T>::N;
   constexpr int NCAP = CONTRASTIVE ? 2 : (NM ? NM : COS_MAX_MODELS);
-  constexpr int TU = NCAP <= 2 ? 4 : (NCAP <= 4 ? 2 : 1);  // tiles in flight per wavefront
+  constexpr int TU = NCAP <= 4 ? 4 : 1;  // tiles in flight per wavefront
   extern __shared__ double tile_sum[];
   __shared__ int s_flag;
 
@@ -979,17 +1013,20 @@ __global__ void __launch_bounds__(kThreads) sample_kernel(Params p) {
   const int tb = c * p.tpc;
   const int te = min(tb + p.tpc, p.ntiles);
   for (int t = tb + wave * TU; t < te; t += kWaves * TU) {
-    float f[TU][N];
+    float x[TU][NCAP][N];
 #pragma unroll
-    for (int i = 0; i < TU; ++i)
-      tile_weights<T, ALIGNED, NCAP, CONTRASTIVE>(p, rows, n, min(t + i, te - 1), plan.pi, plan.m0,
-                                                  coef, off, f[i]);
+    for (int i = 0; i < TU; ++i) tile_load<T, ALIGNED, NCAP>(p, rows, n, min(t + i, te - 1), x[i]);
 #pragma unroll
     for (int i = 0; i < TU; ++i) {
-      const double ts = wave_sum(lane_mass<N>(f[i]));
-      if (lane == 0 && t + i < te) store_agent(sums + t + i, ts);
+      float f[N];
+      tile_eval<T, NCAP, CONTRASTIVE>(p, x[i], n, min(t + i, te - 1), plan.pi, plan.m0, coef, off, f);
+      const double ts = wave_sum_to_lane63(lane_mass<N>(f));
+      if (lane == 63 && t + i < te) tile_sum[t + i - tb] = ts;  // staged in LDS
     }
   }
+  __syncthreads();
+  // publish this workgroup's tile sums with coalesced write-through stores
+  for (int i = threadIdx.x; i < te - tb; i += kThreads) store_agent(sums + tb + i, tile_sum[i]);
   wait_stores();
   if (!arrive_last(p.counters + (size_t)(p.B + b) * kCtrStride, p.C, &s_flag)) return;
 
@@ -1024,6 +1061,7 @@ __global__ void __launch_bounds__(kThreads) sample_kernel(Params p) {
 // ---------------------------------------------------------------------------
 
 int g_chunk_vectors = 0;  // 0 = heuristic
+int g_sample_blocks = 0;  // 0 = heuristic
 
 // Optional event ring around the streaming kernel (benchmarks only).
 constexpr int kMaxProfileSlots = 1024;
@@ -1099,7 +1137,8 @@ void choose_split(int rows_total, int nvec, int* S_out, int* cv_out) {
 
 // Sampling workgroups per sequence: about 2048 in total, at least 4 tiles each.
 void choose_sampling(int B, int ntiles, int* C_out, int* tpc_out) {
-  int C = (2048 + B - 1) / B;
+  const int target = g_sample_blocks > 0 ? g_sample_blocks : 2048;
+  int C = (target + B - 1) / B;
   const int cmax = (ntiles + 3) / 4;
   if (C > cmax) C = cmax;
   if (C < 1) C = 1;
@@ -1325,5 +1364,7 @@ cos_status_t cos_profile_kernel_ms(int index, float* ms) {
 }
 
 void cos_tune_set_chunk_vectors(int vectors) { g_chunk_vectors = vectors > 0 ? vectors : 0; }
+
+void cos_tune_set_sample_blocks(int blocks) { g_sample_blocks = blocks > 0 ? blocks : 0; }
 
 }  // extern "C"
