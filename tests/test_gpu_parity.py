@@ -242,3 +242,42 @@ def test_non_default_stream():
     s.synchronize()
     rep = P.compare(inp, W.C1.mode, W.C1.weights, alen.cpu().numpy(), toks.cpu().numpy(), None)
     _report("side stream", rep)
+
+
+def test_hip_graph_capture_and_replay():
+    """The call records no memset node and allocates nothing, so it can be captured; every replay
+    (with eager work and synchronisations in between) must reproduce the eager result."""
+    w = W.C3.scaled(B=8)
+    inp = W.generate(w, device="cuda")
+    dt = C.COS_DTYPE_BF16
+    ws = C.allocate_workspace(w.n, w.B, w.gamma, w.V, dt, w.mode, "cuda")
+    alen = torch.empty(w.B, dtype=torch.int32, device="cuda")
+    toks = torch.empty((w.B, w.gamma + 1), dtype=torch.int32, device="cuda")
+
+    def call():
+        C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], w.mode, w.weights,
+                     inp["u_accept"], inp["u_resample"], accepted_len=alen, out_tokens=toks, workspace=ws)
+
+    call()
+    torch.cuda.synchronize()
+    want = (alen.cpu().numpy().copy(), toks.cpu().numpy().copy())
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        call()                                   # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        call()
+    for i in range(4):
+        alen.fill_(-5)
+        toks.fill_(-5)
+        ws.fill_(i)                              # eager work between replays; garbage in the workspace
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(alen.cpu().numpy(), want[0]), i
+        assert np.array_equal(toks.cpu().numpy(), want[1]), i
+    rep = P.compare(inp, w.mode, w.weights, want[0], want[1], None)
+    _report("graph replay", rep)
