@@ -109,6 +109,41 @@ cos_status_t cos_verify(const void *logits, cos_dtype_t dt, int n, int B, int ga
                         int32_t *accepted_len, int32_t *out_tokens, void *workspace,
                         size_t workspace_bytes, const cos_diag_t *diag, void *hip_stream);
 
+/*
+ * Extensions of the step; every member is optional (0 / NULL = the base step).
+ *
+ * struct_bytes  sizeof(cos_options_t) of the caller (else COS_ERR_UNSUPPORTED).
+ * temperature   T > 0 divides every logit before every softmax (Sec. 4.1 runs
+ *               T = 1; how T enters Eq. (5) is not stated: it divides both l^p
+ *               and l^q, so the mask reads s_0 >= alpha_cd max s_0 at that T).
+ *               0 means 1.  Negative or non-finite: COS_ERR_WEIGHTS.
+ * bonus_idx     DEVICE [B] int32 or NULL.  bonus_idx[b] = v >= 0: when every
+ *               draft of the row is accepted, the extra token is drawn from
+ *               the verifier's own distribution s_v (Sec. 3.1, Sec. 3.3:
+ *               the token the alternate proposal framework hands to the next
+ *               cycle) instead of from r.  The other models' logits at
+ *               position gamma are then ignored (ensemble mode does not even
+ *               read them), so they need not be valid.  -1: drawn from r.
+ * proposer_pos  DEVICE [B][gamma] int32 or NULL: the proposer of every draft
+ *               position (Alg. 2: tokens of one window can come from different
+ *               models); overrides proposer_idx, which must still be valid.
+ */
+typedef struct cos_options_t {
+  size_t struct_bytes;
+  double temperature;
+  const int32_t *bonus_idx;
+  const int32_t *proposer_pos;
+} cos_options_t;
+
+/* cos_verify with extensions; options == NULL is exactly cos_verify. */
+cos_status_t cos_verify_ex(const void *logits, cos_dtype_t dt, int n, int B, int gamma, int V,
+                           const int32_t *draft_tokens, const int32_t *proposer_idx,
+                           cos_combine_t combine_mode, const double *weights,
+                           const double *u_accept, const double *u_resample,
+                           int32_t *accepted_len, int32_t *out_tokens, void *workspace,
+                           size_t workspace_bytes, const cos_diag_t *diag,
+                           const cos_options_t *options, void *hip_stream);
+
 /* Static, NUL-terminated description of a status code. */
 const char *cos_status_string(cos_status_t status);
 

@@ -83,6 +83,22 @@ void cos_oracle_row_to_f64(const void *row, int dtype, int V, double *out) {
   }
 }
 
+/* ---- Sec. 4.1: temperature T > 0 divides the logits before every softmax -- */
+/* (The paper runs T = 1 and T = 0; how T enters Eq. (5) is not stated: here it
+ * divides both l^p and l^q, i.e. every logit, before anything else.)        */
+void cos_oracle_apply_temperature(double *l, int V, double T) {
+  int x;
+  for (x = 0; x < V; ++x) l[x] = l[x] / T;
+}
+
+/* ---- Eq. (7) / App. A.1: acceptance rate alpha = sum_x min(q(x), r(x)) ---- */
+double cos_oracle_acceptance_rate(const double *q, const double *r, int V) {
+  double a = 0.0;
+  int x;
+  for (x = 0; x < V; ++x) a += q[x] < r[x] ? q[x] : r[x];
+  return a;
+}
+
 /* ---- Sec. 3.2: s = softmax(l), temperature 1 --------------------------- */
 /* M = max_x l(x); Z = sum_x exp(l(x) - M); s(x) = exp(l(x) - M) / Z.       */
 void cos_oracle_softmax(const double *l, int V, double *s) {
@@ -254,17 +270,43 @@ static int check_weights(int mode, int n, const double *w) {
  * the batch are independent and each is processed sequentially by one thread,
  * so the result does not depend on the thread count.
  */
-int cos_oracle_verify(const void *logits, int dtype, int n, int B, int gamma,
-                      int V, const int32_t *draft_tokens,
-                      const int32_t *proposer_idx, int mode,
-                      const double *weights, const double *u_accept,
-                      const double *u_resample, int32_t *accepted_len,
-                      int32_t *out_tokens, double *r_at_draft,
-                      double *q_at_draft, double *ratio, double *sample_mass,
-                      double *cdf_lo, double *cdf_hi, int32_t *flags,
-                      int all_positions, int num_threads) {
+/*
+ * Extensions beyond the base step (every member optional):
+ *   temperature    T > 0 (0 or unset = 1): cos_oracle_apply_temperature on every row
+ *   bonus_idx      [B] or NULL: when all gamma drafts are accepted, the extra
+ *                  token is drawn from s_v, v = bonus_idx[b] >= 0 -- the
+ *                  verifier's own distribution, as in Sec. 3.1 / 3.3, for which
+ *                  the other models' logits at position gamma are not needed and
+ *                  not read; -1 (or NULL) draws it from r at position gamma
+ *   proposer_pos   [B][gamma] or NULL: the proposer of each draft position
+ *                  (tokens of one window can come from different models, Alg. 2);
+ *                  overrides proposer_idx
+ *   alpha          out [B][gamma] or NULL: acceptance rate of every evaluated
+ *                  position, Eq. (7) (NaN where never evaluated)
+ */
+typedef struct cos_oracle_options {
+  double temperature;
+  const int32_t *bonus_idx;
+  const int32_t *proposer_pos;
+  double *alpha;
+} cos_oracle_options;
+
+int cos_oracle_verify_ex(const void *logits, int dtype, int n, int B, int gamma,
+                         int V, const int32_t *draft_tokens,
+                         const int32_t *proposer_idx, int mode,
+                         const double *weights, const double *u_accept,
+                         const double *u_resample, int32_t *accepted_len,
+                         int32_t *out_tokens, double *r_at_draft,
+                         double *q_at_draft, double *ratio, double *sample_mass,
+                         double *cdf_lo, double *cdf_hi, int32_t *flags,
+                         int all_positions, int num_threads,
+                         const cos_oracle_options *opt) {
   int status, b, failed = 0;
   size_t esize;
+  const double T = (opt && opt->temperature > 0.0) ? opt->temperature : 1.0;
+  const int32_t *bonus_idx = opt ? opt->bonus_idx : NULL;
+  const int32_t *proposer_pos = opt ? opt->proposer_pos : NULL;
+  double *alpha = opt ? opt->alpha : NULL;
   if (!logits || !draft_tokens || !proposer_idx || !weights || !u_accept ||
       !u_resample || !accepted_len || !out_tokens)
     return ORACLE_ERR_NULL;
@@ -274,12 +316,17 @@ int cos_oracle_verify(const void *logits, int dtype, int n, int B, int gamma,
   status = check_weights(mode, n, weights);
   if (status != ORACLE_OK) return status;
   esize = dtype == ORACLE_DTYPE_F32 ? 4 : 2;
+  if (opt && !(opt->temperature >= 0.0) ) return ORACLE_ERR_WEIGHTS;
   for (b = 0; b < B; ++b) {
     int j;
     if (proposer_idx[b] < 0 || proposer_idx[b] >= n) return ORACLE_ERR_SHAPE;
+    if (bonus_idx && (bonus_idx[b] < -1 || bonus_idx[b] >= n)) return ORACLE_ERR_SHAPE;
     for (j = 0; j < gamma; ++j) {
       int32_t d = draft_tokens[(size_t)b * gamma + j];
       if (d < 0 || d >= V) return ORACLE_ERR_SHAPE;
+      if (proposer_pos && (proposer_pos[(size_t)b * gamma + j] < 0 ||
+                           proposer_pos[(size_t)b * gamma + j] >= n))
+        return ORACLE_ERR_SHAPE;
     }
   }
 #ifdef _OPENMP
@@ -298,44 +345,56 @@ int cos_oracle_verify(const void *logits, int dtype, int n, int B, int gamma,
     }
 #pragma omp for schedule(dynamic, 1)
     for (b = 0; b < B; ++b) {
-      int pi, j, m, jstar, alive, x, clamped = 0, flag = 0, residual, token;
+      int pi, j, m, jstar, alive, x, clamped = 0, flag = 0, residual, token, bonus_from;
       const double *q;
       double F, lo = 0.0, hi = 0.0;
       if (failed) continue;
-      pi = proposer_idx[b];
       alive = 1; /* no draft of this row rejected so far */
       jstar = -1;
-      if (r_at_draft || q_at_draft || ratio)
-        for (j = 0; j < gamma; ++j) {
-          size_t k = (size_t)b * gamma + j;
-          if (r_at_draft) r_at_draft[k] = NAN;
-          if (q_at_draft) q_at_draft[k] = NAN;
-          if (ratio) ratio[k] = NAN;
-        }
+      bonus_from = bonus_idx ? bonus_idx[b] : -1;
+      for (j = 0; j < gamma; ++j) {
+        size_t k = (size_t)b * gamma + j;
+        if (r_at_draft) r_at_draft[k] = NAN;
+        if (q_at_draft) q_at_draft[k] = NAN;
+        if (ratio) ratio[k] = NAN;
+        if (alpha) alpha[k] = NAN;
+      }
       /* positions 0..gamma-1 carry a draft; position gamma is the bonus row */
       for (j = 0; j <= gamma; ++j) {
+        const int verifier_bonus = (j == gamma) && bonus_from >= 0;
         if (!alive && !(all_positions && j < gamma)) break;
         for (m = 0; m < n; ++m) {
           size_t row = ((size_t)m * B + b) * (size_t)(gamma + 1) + j;
           const char *src = (const char *)logits + row * (size_t)V * esize;
+          if (verifier_bonus && m != bonus_from) continue; /* not needed, not read */
           cos_oracle_row_to_f64(src, dtype, V, l + (size_t)m * V);
+          if (T != 1.0) cos_oracle_apply_temperature(l + (size_t)m * V, V, T);
           cos_oracle_softmax(l + (size_t)m * V, V, s + (size_t)m * V);
         }
-        if (mode == ORACLE_ENSEMBLE)
+        if (verifier_bonus) {
+          /* Sec. 3.1 / 3.3: the bonus token follows the verifier's own distribution */
+          memcpy(r, s + (size_t)bonus_from * V, sizeof(double) * (size_t)V);
+        } else if (mode == ORACLE_ENSEMBLE) {
           cos_oracle_combine_ensemble(s, weights, n, V, r);
-        else
+        } else {
           cos_oracle_combine_contrastive(l, l + V, weights[0], weights[1], V, r);
-        q = s + (size_t)pi * V;
+        }
         if (j < gamma) {
           size_t k = (size_t)b * gamma + j;
           int d = draft_tokens[k];
           double rt;
-          int acc = cos_oracle_accept(u_accept[k], r[d], q[d], &rt);
+          int acc;
+          pi = proposer_pos ? proposer_pos[k] : proposer_idx[b];
+          q = s + (size_t)pi * V;
+          acc = cos_oracle_accept(u_accept[k], r[d], q[d], &rt);
           if (r_at_draft) r_at_draft[k] = r[d];
           if (q_at_draft) q_at_draft[k] = q[d];
           if (ratio) ratio[k] = rt;
+          if (alpha) alpha[k] = cos_oracle_acceptance_rate(q, r, V);
           if (!alive) continue; /* diagnostics only: row already decided */
           if (acc) continue;    /* accepted: go on to the next draft */
+        } else {
+          q = r; /* unused: the bonus draw takes f = r */
         }
         /* here j is the first rejected position, or j == gamma (all accepted:
          * bonus token).  r, q hold the distributions of that position.      */
@@ -372,6 +431,22 @@ int cos_oracle_verify(const void *logits, int dtype, int n, int B, int gamma,
     free(f);
   }
   return failed ? ORACLE_ERR_NOMEM : ORACLE_OK;
+}
+
+/* The base step: no extensions. */
+int cos_oracle_verify(const void *logits, int dtype, int n, int B, int gamma,
+                      int V, const int32_t *draft_tokens,
+                      const int32_t *proposer_idx, int mode,
+                      const double *weights, const double *u_accept,
+                      const double *u_resample, int32_t *accepted_len,
+                      int32_t *out_tokens, double *r_at_draft,
+                      double *q_at_draft, double *ratio, double *sample_mass,
+                      double *cdf_lo, double *cdf_hi, int32_t *flags,
+                      int all_positions, int num_threads) {
+  return cos_oracle_verify_ex(logits, dtype, n, B, gamma, V, draft_tokens, proposer_idx, mode,
+                              weights, u_accept, u_resample, accepted_len, out_tokens, r_at_draft,
+                              q_at_draft, ratio, sample_mass, cdf_lo, cdf_hi, flags,
+                              all_positions, num_threads, NULL);
 }
 
 /* number of threads an OpenMP parallel region would use right now */

@@ -10,6 +10,7 @@ import ctypes
 import os
 import subprocess
 from dataclasses import dataclass
+from typing import Optional
 
 import numpy as np
 
@@ -32,6 +33,11 @@ def build(force: bool = True) -> str:
                "-o", _LIB, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
+
+
+class _Options(ctypes.Structure):
+    _fields_ = [("temperature", ctypes.c_double), ("bonus_idx", ctypes.POINTER(ctypes.c_int32)),
+                ("proposer_pos", ctypes.POINTER(ctypes.c_int32)), ("alpha", ctypes.POINTER(ctypes.c_double))]
 
 
 _lib = None
@@ -64,6 +70,12 @@ def _load():
         lib.cos_oracle_verify.argtypes = [vp, ci, ci, ci, ci, ci, ip, ip, ci, dp, dp, dp, ip, ip,
                                           dp, dp, dp, dp, dp, dp, ip, ci, ci]
         lib.cos_oracle_verify.restype = ci
+        lib.cos_oracle_verify_ex.argtypes = lib.cos_oracle_verify.argtypes + [ctypes.POINTER(_Options)]
+        lib.cos_oracle_verify_ex.restype = ci
+        lib.cos_oracle_apply_temperature.argtypes = [dp, ci, ctypes.c_double]
+        lib.cos_oracle_apply_temperature.restype = None
+        lib.cos_oracle_acceptance_rate.argtypes = [dp, dp, ci]
+        lib.cos_oracle_acceptance_rate.restype = ctypes.c_double
         lib.cos_oracle_max_threads.argtypes = []
         lib.cos_oracle_max_threads.restype = ci
         _lib = lib
@@ -91,6 +103,18 @@ def row_to_f64(row: np.ndarray, dtype: int) -> np.ndarray:
     out = np.empty(row.shape[0], dtype=np.float64)
     _load().cos_oracle_row_to_f64(row.ctypes.data_as(ctypes.c_void_p), dtype, row.shape[0], _dp(out))
     return out
+
+
+def apply_temperature(l, T: float) -> np.ndarray:
+    out = _f64(l).copy()
+    _load().cos_oracle_apply_temperature(_dp(out), out.shape[0], T)
+    return out
+
+
+def acceptance_rate(q, r) -> float:
+    q = _f64(q)
+    r = _f64(r)
+    return _load().cos_oracle_acceptance_rate(_dp(q), _dp(r), q.shape[0])
 
 
 def softmax(l) -> np.ndarray:
@@ -157,11 +181,14 @@ class OracleResult:
     cdf_lo: np.ndarray            # [B]
     cdf_hi: np.ndarray            # [B]
     flags: np.ndarray             # [B] int32
+    alpha: Optional[np.ndarray] = None   # [B][gamma] acceptance rates (Eq. 7), NaN where not evaluated
 
 
 def verify(logits: np.ndarray, dtype: int, draft_tokens, proposer_idx, mode: int, weights,
-           u_accept, u_resample, all_positions: bool = False, num_threads: int = 0) -> OracleResult:
-    """Run ``cos_oracle_verify``.
+           u_accept, u_resample, all_positions: bool = False, num_threads: int = 0,
+           temperature: float = 1.0, bonus_idx=None, proposer_pos=None,
+           want_alpha: bool = False) -> OracleResult:
+    """Run ``cos_oracle_verify_ex`` (the base step when no extension is given).
 
     ``logits`` is a host array of shape [n][B][gamma+1][V]: float32, or uint16
     holding bf16 bit patterns.
@@ -183,12 +210,26 @@ def verify(logits: np.ndarray, dtype: int, draft_tokens, proposer_idx, mode: int
         r_at_draft=np.empty((B, gamma)), q_at_draft=np.empty((B, gamma)), ratio=np.empty((B, gamma)),
         sample_mass=np.empty(B), cdf_lo=np.empty(B), cdf_hi=np.empty(B),
         flags=np.zeros(B, dtype=np.int32))
-    res.status = _load().cos_oracle_verify(
+    opt = _Options()
+    opt.temperature = float(temperature)
+    keep = []
+    if bonus_idx is not None:
+        bi = np.ascontiguousarray(bonus_idx, dtype=np.int32).reshape(B)
+        keep.append(bi)
+        opt.bonus_idx = _ip(bi)
+    if proposer_pos is not None:
+        pp = np.ascontiguousarray(proposer_pos, dtype=np.int32).reshape(B, gamma)
+        keep.append(pp)
+        opt.proposer_pos = _ip(pp)
+    if want_alpha:
+        res.alpha = np.empty((B, gamma))
+        opt.alpha = _dp(res.alpha)
+    res.status = _load().cos_oracle_verify_ex(
         logits.ctypes.data_as(ctypes.c_void_p), dtype, n, B, gamma, V,
         _ip(draft_tokens), _ip(proposer_idx), mode, _dp(weights), _dp(u_accept), _dp(u_resample),
         _ip(res.accepted_len), _ip(res.out_tokens), _dp(res.r_at_draft), _dp(res.q_at_draft),
         _dp(res.ratio), _dp(res.sample_mass), _dp(res.cdf_lo), _dp(res.cdf_hi), _ip(res.flags),
-        int(all_positions), int(num_threads))
+        int(all_positions), int(num_threads), ctypes.byref(opt))
     return res
 
 

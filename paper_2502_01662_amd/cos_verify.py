@@ -32,6 +32,11 @@ class CosDiag(ctypes.Structure):
                 ("cdf_hi", ctypes.c_void_p), ("flags", ctypes.c_void_p)]
 
 
+class CosOptions(ctypes.Structure):
+    _fields_ = [("struct_bytes", ctypes.c_size_t), ("temperature", ctypes.c_double),
+                ("bonus_idx", ctypes.c_void_p), ("proposer_pos", ctypes.c_void_p)]
+
+
 class CosVerifyError(RuntimeError):
     def __init__(self, status: int, message: str):
         super().__init__(f"cos_verify failed: {message} (status {status})")
@@ -55,6 +60,10 @@ def load_library() -> ctypes.CDLL:
         lib.cos_verify.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp, ci, ctypes.POINTER(ctypes.c_double),
                                    vp, vp, vp, vp, vp, sz, ctypes.POINTER(CosDiag), vp]
         lib.cos_verify.restype = ci
+        lib.cos_verify_ex.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp, ci, ctypes.POINTER(ctypes.c_double),
+                                      vp, vp, vp, vp, vp, sz, ctypes.POINTER(CosDiag),
+                                      ctypes.POINTER(CosOptions), vp]
+        lib.cos_verify_ex.restype = ci
         lib.cos_status_string.argtypes = [ci]
         lib.cos_status_string.restype = ctypes.c_char_p
         lib.cos_verify_version.argtypes = []
@@ -151,12 +160,15 @@ def cos_verify(logits: torch.Tensor, draft_tokens: torch.Tensor, proposer_idx: t
                combine_mode: int, weights: Sequence[float], u_accept: torch.Tensor,
                u_resample: torch.Tensor, accepted_len: Optional[torch.Tensor] = None,
                out_tokens: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
-               diag: Optional[Diagnostics] = None):
+               diag: Optional[Diagnostics] = None, temperature: float = 1.0,
+               bonus_idx: Optional[torch.Tensor] = None, proposer_pos: Optional[torch.Tensor] = None):
     """Enqueue one verification step on the current stream; returns (accepted_len, out_tokens).
 
     logits [n][B][gamma+1][V] (float32 or bfloat16), draft_tokens [B][gamma] int32,
     proposer_idx [B] int32, u_accept [B][gamma] float64, u_resample [B] float64:
     all contiguous tensors on one GPU.  ``weights`` is a host sequence.
+    Extensions (``cos_verify_ex``): ``temperature``, ``bonus_idx`` [B] int32,
+    ``proposer_pos`` [B][gamma] int32.
     """
     lib = load_library()
     if not logits.is_cuda:
@@ -181,13 +193,23 @@ def cos_verify(logits: torch.Tensor, draft_tokens: torch.Tensor, proposer_idx: t
         workspace = allocate_workspace(n, B, gamma, V, dt, combine_mode, dev)
     w = (ctypes.c_double * max(len(weights), 1))(*[float(x) for x in weights])
     dstruct = diag.as_struct() if diag is not None else None
+    opt = None
+    if temperature != 1.0 or bonus_idx is not None or proposer_pos is not None:
+        for name, t, shape in (("bonus_idx", bonus_idx, (B,)), ("proposer_pos", proposer_pos, (B, gamma))):
+            if t is not None and (t.dtype != torch.int32 or tuple(t.shape) != shape or not t.is_contiguous()
+                                  or t.device != dev):
+                raise TypeError(f"{name}: want contiguous int32 {shape} on {dev}")
+        opt = CosOptions(ctypes.sizeof(CosOptions), float(temperature),
+                         bonus_idx.data_ptr() if bonus_idx is not None else None,
+                         proposer_pos.data_ptr() if proposer_pos is not None else None)
     stream = torch.cuda.current_stream(dev).cuda_stream
     with torch.cuda.device(dev):
-        st = lib.cos_verify(logits.data_ptr(), dt, n, B, gamma, V, draft_tokens.data_ptr(),
-                            proposer_idx.data_ptr(), combine_mode, w, u_accept.data_ptr(),
-                            u_resample.data_ptr(), accepted_len.data_ptr(), out_tokens.data_ptr(),
-                            workspace.data_ptr(), workspace.numel(),
-                            ctypes.byref(dstruct) if dstruct is not None else None, stream)
+        st = lib.cos_verify_ex(logits.data_ptr(), dt, n, B, gamma, V, draft_tokens.data_ptr(),
+                               proposer_idx.data_ptr(), combine_mode, w, u_accept.data_ptr(),
+                               u_resample.data_ptr(), accepted_len.data_ptr(), out_tokens.data_ptr(),
+                               workspace.data_ptr(), workspace.numel(),
+                               ctypes.byref(dstruct) if dstruct is not None else None,
+                               ctypes.byref(opt) if opt is not None else None, stream)
     if st != COS_OK:
         raise CosVerifyError(st, cos_status_string(st))
     return accepted_len, out_tokens

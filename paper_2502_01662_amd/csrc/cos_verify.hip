@@ -62,8 +62,10 @@ struct Partial {
 struct SeqPlan {
   int jstar;     // position that is sampled = accepted_len
   int residual;  // 1: f = max(0, r - q); 0: f = r (bonus)
-  int pi;        // proposer index
+  int pi;        // proposer of the sampled position
+  int bonus;     // >= 0: the bonus token is drawn from this model's softmax alone (jstar == gamma)
   float m0;      // contrastive: expert maximum at jstar
+  int pad;
   double lse2[COS_MAX_MODELS];  // log2-sum-exp2 of the statistics at jstar
 };
 
@@ -72,6 +74,8 @@ struct Params {
   int n, B, gamma, V;
   const int* draft;
   const int* proposer;
+  const int* proposer_pos;  // optional [B][gamma]: proposer of each draft position
+  const int* bonus_idx;     // optional [B]: model the bonus token is drawn from (-1: from r)
   const double* u_accept;
   const double* u_resample;
   int* accepted_len;
@@ -90,9 +94,10 @@ struct Params {
   int C;              // sampling workgroups per sequence
   int tpc;            // tiles per sampling workgroup
   double w[COS_MAX_MODELS];  // ensemble weights; contrastive: w[0] = mu, w[1] = alpha_cd
+  float scale;               // log2(e) / temperature: logits times this are base-2 exponents
   float mu_hi, mu_lo;        // mu split into two floats
-  float thr32;               // smallest float >= ln(alpha_cd)
-  double thr64;              // ln(alpha_cd)
+  float thr32;               // smallest float >= T ln(alpha_cd)
+  double thr64;              // T ln(alpha_cd)
   cos_diag_t diag;
 };
 
@@ -294,9 +299,9 @@ __device__ __forceinline__ void running_init(Running& r) {
 
 // Raise the offset to cover a new wave-wide maximum `wm` (wave-uniform).
 // Offsets are integers, so the rescale by 2^(old - new) is exact.
-__device__ __forceinline__ void running_cover(Running& r, float wm) {
+__device__ __forceinline__ void running_cover(Running& r, float wm, float scale) {
   if (wm > -INFINITY) {
-    float of = ceilf(wm * kLog2e);
+    float of = ceilf(wm * scale);
     of = fminf(fmaxf(of, -kMaxOffset), kMaxOffset);
     const int on = (int)of;
     if (on > r.o) {
@@ -314,18 +319,18 @@ __device__ __forceinline__ double running_total(const Running& r) {
 }
 
 template <int U, int N>
-__device__ __forceinline__ void running_add(Running& run, const float (&x)[U][N]) {
+__device__ __forceinline__ void running_add(Running& run, const float (&x)[U][N], float scale) {
   float lm = -INFINITY;
 #pragma unroll
   for (int u = 0; u < U; ++u)
 #pragma unroll
     for (int k = 0; k < N; ++k) lm = fmaxf(lm, x[u][k]);
-  running_cover(run, wave_max(lm));
+  running_cover(run, wave_max(lm), scale);
   const float neg_o = -(float)run.o;
 #pragma unroll
   for (int u = 0; u < U; ++u)
 #pragma unroll
-    for (int k = 0; k < N; ++k) run.acc[k & 3] += fast_exp2(fmaf(x[u][k], kLog2e, neg_o));
+    for (int k = 0; k < N; ++k) run.acc[k & 3] += fast_exp2(fmaf(x[u][k], scale, neg_o));
 }
 
 // ---- raw-register variant for 16-byte aligned rows -------------------------
@@ -372,7 +377,7 @@ __device__ __forceinline__ void mask_raw_group(int base, int v1, uint4 (&raw)[U]
 }
 
 template <typename T, int U>
-__device__ __forceinline__ void running_add_raw(Running& run, const uint4 (&raw)[U]) {
+__device__ __forceinline__ void running_add_raw(Running& run, const uint4 (&raw)[U], float scale) {
   constexpr int N = VecOf<T>::N;
   if constexpr (sizeof(T) == 2) {
     short2_t m = __builtin_bit_cast(short2_t, raw[0].x);
@@ -385,7 +390,7 @@ __device__ __forceinline__ void running_add_raw(Running& run, const uint4 (&raw)
     }
     const int wm16 = wave_max_i32(max((int)m.x, (int)m.y));
     if (wm16 >= 0) {
-      running_cover(run, __uint_as_float((uint32_t)wm16 << 16));
+      running_cover(run, __uint_as_float((uint32_t)wm16 << 16), scale);
     } else {
       float lm = -INFINITY;
 #pragma unroll
@@ -395,7 +400,7 @@ __device__ __forceinline__ void running_add_raw(Running& run, const uint4 (&raw)
 #pragma unroll
         for (int k = 0; k < N; ++k) lm = fmaxf(lm, x[k]);
       }
-      running_cover(run, wave_max(lm));
+      running_cover(run, wave_max(lm), scale);
     }
   } else {
     float lm = -INFINITY;
@@ -406,7 +411,7 @@ __device__ __forceinline__ void running_add_raw(Running& run, const uint4 (&raw)
 #pragma unroll
       for (int k = 0; k < N; ++k) lm = fmaxf(lm, x[k]);
     }
-    running_cover(run, wave_max(lm));
+    running_cover(run, wave_max(lm), scale);
   }
   const float neg_o = -(float)run.o;
 #pragma unroll
@@ -414,7 +419,7 @@ __device__ __forceinline__ void running_add_raw(Running& run, const uint4 (&raw)
     float x[N];
     unpack<T>(raw[u], x);
 #pragma unroll
-    for (int k = 0; k < N; ++k) run.acc[k & 3] += fast_exp2(fmaf(x[k], kLog2e, neg_o));
+    for (int k = 0; k < N; ++k) run.acc[k & 3] += fast_exp2(fmaf(x[k], scale, neg_o));
   }
 }
 
@@ -422,7 +427,7 @@ __device__ __forceinline__ void running_add_raw(Running& run, const uint4 (&raw)
 // wave's values).
 template <typename T, bool ALIGNED>
 __device__ __forceinline__ void chunk_stats(const T* __restrict__ row, int v0, int v1, int V,
-                                            int& o_out, double& z_out) {
+                                            float scale, int& o_out, double& z_out) {
   constexpr int N = VecOf<T>::N;
   constexpr int kStep = kThreads * kUnroll;
   Running run;
@@ -434,19 +439,19 @@ __device__ __forceinline__ void chunk_stats(const T* __restrict__ row, int v0, i
       uint4 a[kUnroll];
       load_raw_group<T, kUnroll>(row, base, v1, a);
       if (base + kStep > v1) mask_raw_group<T, kUnroll>(base, v1, a);
-      running_add_raw<T, kUnroll>(run, a);
+      running_add_raw<T, kUnroll>(run, a, scale);
     }
   } else {
     int base = v0;
     for (; base + kStep <= v1; base += kStep) {
       float x[kUnroll][N];
       load_group<T, ALIGNED, false, kUnroll>(row, base, v1, V, x);
-      running_add<kUnroll, N>(run, x);
+      running_add<kUnroll, N>(run, x, scale);
     }
     if (base < v1) {
       float x[kUnroll][N];
       load_group<T, ALIGNED, true, kUnroll>(row, base, v1, V, x);
-      running_add<kUnroll, N>(run, x);
+      running_add<kUnroll, N>(run, x, scale);
     }
   }
   o_out = run.o;
@@ -508,8 +513,7 @@ __device__ void decide_sequence(const Params& p, int b, DecideShared& sh) {
   const int nstat = p.nstat;
   const int nrows = g1 * nstat;
   const int n = p.n;
-  const int pi = p.proposer[b];
-  const double log2e = (double)kLog2e;
+  const double log2e = (double)p.scale;  // log2(e) / T, the same constant the streaming kernel used
 
   // 1. combine the chunk partials of every (position, statistic) in float64
   if (tid < nrows) {
@@ -542,6 +546,7 @@ __device__ void decide_sequence(const Params& p, int b, DecideShared& sh) {
     const int j = tid;
     const size_t k = (size_t)b * p.gamma + j;
     const int d = p.draft[k];
+    const int pi = p.proposer_pos ? p.proposer_pos[k] : p.proposer[b];
     double rd = 0.0, qd = 0.0;
     if constexpr (!CONTRASTIVE) {
       for (int m = 0; m < n; ++m) {
@@ -583,10 +588,13 @@ __device__ void decide_sequence(const Params& p, int b, DecideShared& sh) {
   // 4. plan for the sampling kernel (read after this launch has ended)
   SeqPlan* plan = p.plans + b;
   if (tid == 0) {
+    const bool residual = jstar < p.gamma;
     plan->jstar = jstar;
-    plan->residual = jstar < p.gamma;
-    plan->pi = pi;
+    plan->residual = residual;
+    plan->pi = (residual && p.proposer_pos) ? p.proposer_pos[(size_t)b * p.gamma + jstar] : p.proposer[b];
+    plan->bonus = (!residual && p.bonus_idx) ? p.bonus_idx[b] : -1;
     plan->m0 = CONTRASTIVE ? sh.rowmax[jstar] : 0.0f;
+    plan->pad = 0;
   }
   if (tid < nstat) plan->lse2[tid] = sh.lse2[jstar * nstat + tid];
 }
@@ -601,7 +609,7 @@ __device__ void decide_sequence(const Params& p, int b, DecideShared& sh) {
 // product is rounded before it is added (no fused multiply-add), so that terms
 // of identical models cancel exactly and r == q leaves no residual mass.
 template <int NCAP, int N>
-__device__ __forceinline__ void eval_f_ensemble(const float (&x)[NCAP][N], int n,
+__device__ __forceinline__ void eval_f_ensemble(const float (&x)[NCAP][N], int n, float scale,
                                                 const float (&coef)[NCAP], const float (&off)[NCAP],
                                                 float (&f)[N]) {
 #pragma unroll
@@ -609,7 +617,7 @@ __device__ __forceinline__ void eval_f_ensemble(const float (&x)[NCAP][N], int n
     float s = 0.0f;
 #pragma unroll
     for (int m = 0; m < NCAP; ++m)
-      if (m < n) s += coef[m] * fast_exp2(fmaf(x[m][k], kLog2e, -off[m]));
+      if (m < n) s += coef[m] * fast_exp2(fmaf(x[m][k], scale, -off[m]));
     f[k] = fmaxf(s, 0.0f);
   }
 }
@@ -630,21 +638,27 @@ __device__ __forceinline__ bool in_mask(float l0, float m0, float thr32, double 
   }
 }
 
-// Contrastive: r = [mask] coef[0] 2^(c*log2e - off[0]), q = coef[1] 2^(l_pi*log2e - off[1]);
-// f = max(0, r - q) on the mask (coef[1] = 0 for a bonus draw), 0 off it.
+// Contrastive: r = [mask] coef[0] 2^(c*scale - off[0]), q = coef[1] 2^(l_pi*scale - off[1]);
+// f = max(0, r - q) on the mask (coef[1] = 0 for a bonus draw from r), 0 off it.
+// plain >= 0 (the verifier's own bonus token): f = coef[1] 2^(l_plain*scale - off[1]), no mask.
 template <typename T, int N>
 __device__ __forceinline__ void eval_f_contrastive(const float (&x0)[N], const float (&x1)[N],
-                                                   int pi, float m0, const Params& p,
+                                                   int pi, int plain, float m0, const Params& p,
                                                    const float (&coef)[2], const float (&off)[2],
                                                    float (&f)[N]) {
+  const int qsel = plain >= 0 ? plain : pi;
 #pragma unroll
   for (int k = 0; k < N; ++k) {
-    const bool in = in_mask<T>(x0[k], m0, p.thr32, p.thr64);
-    const float c = contrast(x0[k], x1[k], p.mu_hi, p.mu_lo);
-    const float r = coef[0] * fast_exp2(fmaf(c, kLog2e, -off[0]));
-    const float lq = pi ? x1[k] : x0[k];
-    const float q = coef[1] * fast_exp2(fmaf(lq, kLog2e, -off[1]));
-    f[k] = in ? fmaxf(r - q, 0.0f) : 0.0f;
+    const float lq = qsel ? x1[k] : x0[k];
+    const float q = coef[1] * fast_exp2(fmaf(lq, p.scale, -off[1]));
+    if (plain >= 0) {
+      f[k] = q;
+    } else {
+      const bool in = in_mask<T>(x0[k], m0, p.thr32, p.thr64);
+      const float c = contrast(x0[k], x1[k], p.mu_hi, p.mu_lo);
+      const float r = coef[0] * fast_exp2(fmaf(c, p.scale, -off[0]));
+      f[k] = in ? fmaxf(r - q, 0.0f) : 0.0f;
+    }
   }
 }
 
@@ -658,16 +672,19 @@ __device__ __forceinline__ void plan_coefficients(const Params& p, const SeqPlan
     off[m] = 0.0f;
     if (m < n) {
       double a, lse;
+      const bool plain = !residual && plan.bonus >= 0;  // bonus token from one model's softmax alone
       if constexpr (!CONTRASTIVE) {
-        a = p.w[m] - ((residual && m == plan.pi) ? 1.0 : 0.0);
+        a = plain ? (m == plan.bonus ? 1.0 : 0.0) : p.w[m] - ((residual && m == plan.pi) ? 1.0 : 0.0);
         lse = plan.lse2[m];
       } else {
-        a = (m == 0) ? 1.0 : (residual ? 1.0 : 0.0);
-        lse = plan.lse2[m == 0 ? 2 : plan.pi];
+        a = (m == 0) ? 1.0 : ((residual || plain) ? 1.0 : 0.0);
+        lse = plan.lse2[m == 0 ? 2 : (plain ? plan.bonus : plan.pi)];
       }
-      const double K = rint(lse);
-      off[m] = (float)K;
-      coef[m] = (float)(a * exp2(K - lse));
+      if (a != 0.0) {  // a model without weight may have no statistic at all (lse = -inf)
+        const double K = rint(lse);
+        off[m] = (float)K;
+        coef[m] = (float)(a * exp2(K - lse));
+      }
     }
   }
 }
@@ -686,13 +703,14 @@ __device__ __forceinline__ void tile_load(const Params& p, const T* const (&rows
 // f of the loaded tile for this lane; 0 past the row's end.
 template <typename T, int NCAP, bool CONTRASTIVE>
 __device__ __forceinline__ void tile_eval(const Params& p, const float (&x)[NCAP][VecOf<T>::N], int n,
-                                          int tile, int pi, float m0, const float (&coef)[NCAP],
-                                          const float (&off)[NCAP], float (&f)[VecOf<T>::N]) {
+                                          int tile, int pi, int plain, float m0,
+                                          const float (&coef)[NCAP], const float (&off)[NCAP],
+                                          float (&f)[VecOf<T>::N]) {
   constexpr int N = VecOf<T>::N;
   if constexpr (!CONTRASTIVE)
-    eval_f_ensemble<NCAP, N>(x, n, coef, off, f);
+    eval_f_ensemble<NCAP, N>(x, n, p.scale, coef, off, f);
   else
-    eval_f_contrastive<T, N>(x[0], x[1], pi, m0, p, coef, off, f);
+    eval_f_contrastive<T, N>(x[0], x[1], pi, plain, m0, p, coef, off, f);
   if (tile * 64 + lane_id() >= p.nvec) {
 #pragma unroll
     for (int k = 0; k < N; ++k) f[k] = 0.0f;
@@ -701,11 +719,12 @@ __device__ __forceinline__ void tile_eval(const Params& p, const float (&x)[NCAP
 
 template <typename T, bool ALIGNED, int NCAP, bool CONTRASTIVE>
 __device__ __forceinline__ void tile_weights(const Params& p, const T* const (&rows)[NCAP], int n,
-                                             int tile, int pi, float m0, const float (&coef)[NCAP],
-                                             const float (&off)[NCAP], float (&f)[VecOf<T>::N]) {
+                                             int tile, int pi, int plain, float m0,
+                                             const float (&coef)[NCAP], const float (&off)[NCAP],
+                                             float (&f)[VecOf<T>::N]) {
   float x[NCAP][VecOf<T>::N];
   tile_load<T, ALIGNED, NCAP>(p, rows, n, tile, x);
-  tile_eval<T, NCAP, CONTRASTIVE>(p, x, n, tile, pi, m0, coef, off, f);
+  tile_eval<T, NCAP, CONTRASTIVE>(p, x, n, tile, pi, plain, m0, coef, off, f);
 }
 
 template <int N>
@@ -777,7 +796,7 @@ __device__ bool draw_token(const Params& p, int b, const SeqPlan& plan, const T*
 
   // the same f values of that one tile, scanned element by element
   float f[N];
-  tile_weights<T, ALIGNED, NCAP, CONTRASTIVE>(p, rows, n, tile, plan.pi, plan.m0, coef, off, f);
+  tile_weights<T, ALIGNED, NCAP, CONTRASTIVE>(p, rows, n, tile, plan.pi, plan.bonus, plan.m0, coef, off, f);
   const double lane_tot = lane_mass<N>(f);
   const double lincl = wave_inclusive_scan(lane_tot);
   const double lup = __shfl_up(lincl, 1, 64);
@@ -854,17 +873,28 @@ __global__ void __launch_bounds__(kThreads) ensemble_stats_kernel(Params p) {
   const int m = rem / p.S;
   const int s = rem - m * p.S;
 
-  const T* row = row_ptr<T>(p, m, b, j);
-  const int v0 = s * p.cv;
-  const int v1 = min(v0 + p.cv, p.nvec);
-  int o;
-  double z;
-  chunk_stats<T, ALIGNED>(row, v0, v1, p.V, o, z);
-  publish_wave_stat(ws, 0, o, z);
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    store_partial(ws, 0, p.partials + (((size_t)b * g1 + j) * p.n + m) * p.S + s);
-    wait_stores();
+  Partial* out = p.partials + (((size_t)b * g1 + j) * p.n + m) * p.S + s;
+  // With a verifier bonus the other models' logits at the bonus position are
+  // not needed (they may not exist yet) and are not read.
+  const int only = (p.bonus_idx && j == p.gamma) ? p.bonus_idx[b] : -1;
+  if (only >= 0 && m != only) {
+    if (threadIdx.x == 0) {
+      store_empty_partial(out);
+      wait_stores();
+    }
+  } else {
+    const T* row = row_ptr<T>(p, m, b, j);
+    const int v0 = s * p.cv;
+    const int v1 = min(v0 + p.cv, p.nvec);
+    int o;
+    double z;
+    chunk_stats<T, ALIGNED>(row, v0, v1, p.V, p.scale, o, z);
+    publish_wave_stat(ws, 0, o, z);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      store_partial(ws, 0, out);
+      wait_stores();
+    }
   }
   if (arrive_last(p.counters + (size_t)b * kCtrStride, per_b, &s_flag)) decide_sequence<T, false>(p, b, sh);
 }
@@ -923,8 +953,15 @@ __global__ void __launch_bounds__(kThreads) contrastive_stats_kernel(Params p) {
   int rem = blockIdx.x - b * per_b;
   const int j = rem / p.S;
   const int s = rem - j * p.S;
-  const int pi = p.proposer[b];
   const int tid = threadIdx.x;
+  // Whose softmax statistic this position needs: the proposer's at a draft
+  // position; at the bonus position only a verifier bonus needs one at all.
+  int pi = p.proposer[b];
+  if (j < p.gamma) {
+    if (p.proposer_pos) pi = p.proposer_pos[(size_t)b * p.gamma + j];
+  } else if (p.bonus_idx && p.bonus_idx[b] >= 0) {
+    pi = p.bonus_idx[b];
+  }
 
   // expert maximum of this position from the row-max kernel's partial maxima
   {
@@ -956,9 +993,9 @@ __global__ void __launch_bounds__(kThreads) contrastive_stats_kernel(Params p) {
     }
     // proposer row statistic
     if (pi)
-      running_add<U, N>(rq, x1);
+      running_add<U, N>(rq, x1, p.scale);
     else
-      running_add<U, N>(rq, x0);
+      running_add<U, N>(rq, x0, p.scale);
     // masked contrastive statistic; the mask is sparse, so skip wave-wide when empty
     float c[U][N];
     float lmc = -INFINITY;
@@ -970,7 +1007,7 @@ __global__ void __launch_bounds__(kThreads) contrastive_stats_kernel(Params p) {
         c[u][k] = in ? contrast(x0[u][k], x1[u][k], p.mu_hi, p.mu_lo) : -INFINITY;
         lmc = fmaxf(lmc, c[u][k]);
       }
-    if (__ballot(lmc > -INFINITY)) running_add<U, N>(rc, c);
+    if (__ballot(lmc > -INFINITY)) running_add<U, N>(rc, c, p.scale);
   }
   const double zq = running_total(rq);
   const double zc = running_total(rc);
@@ -1003,9 +1040,13 @@ __global__ void __launch_bounds__(kThreads) sample_kernel(Params p) {
   const int wave = threadIdx.x >> 6;
   const int n = CONTRASTIVE ? 2 : (NM ? NM : p.n);
   const SeqPlan plan = p.plans[b];
+  // A verifier bonus reads that one model's row only (the others carry a zero
+  // coefficient and may hold anything, so every slot points at the valid row).
+  const bool one_row = !CONTRASTIVE && plan.residual == 0 && plan.bonus >= 0;
   const T* rows[NCAP];
 #pragma unroll
-  for (int m = 0; m < NCAP; ++m) rows[m] = row_ptr<T>(p, m < n ? m : 0, b, plan.jstar);
+  for (int m = 0; m < NCAP; ++m)
+    rows[m] = row_ptr<T>(p, one_row ? plan.bonus : (m < n ? m : 0), b, plan.jstar);
   float coef[NCAP], off[NCAP];
   plan_coefficients<NCAP, CONTRASTIVE>(p, plan, plan.residual != 0, n, coef, off);
 
@@ -1019,7 +1060,8 @@ __global__ void __launch_bounds__(kThreads) sample_kernel(Params p) {
 #pragma unroll
     for (int i = 0; i < TU; ++i) {
       float f[N];
-      tile_eval<T, NCAP, CONTRASTIVE>(p, x[i], n, min(t + i, te - 1), plan.pi, plan.m0, coef, off, f);
+      tile_eval<T, NCAP, CONTRASTIVE>(p, x[i], n, min(t + i, te - 1), plan.pi, plan.bonus, plan.m0, coef,
+                                      off, f);
       const double ts = wave_sum_to_lane63(lane_mass<N>(f));
       if (lane == 63 && t + i < te) tile_sum[t + i - tb] = ts;  // staged in LDS
     }
@@ -1046,7 +1088,7 @@ __global__ void __launch_bounds__(kThreads) sample_kernel(Params p) {
   plan_coefficients<NCAP, CONTRASTIVE>(p, plan, false, n, coef, off);
   for (int t = wave; t < p.ntiles; t += kWaves) {
     float f[N];
-    tile_weights<T, ALIGNED, NCAP, CONTRASTIVE>(p, rows, n, t, plan.pi, plan.m0, coef, off, f);
+    tile_weights<T, ALIGNED, NCAP, CONTRASTIVE>(p, rows, n, t, plan.pi, plan.bonus, plan.m0, coef, off, f);
     const double ts = wave_sum(lane_mass<N>(f));
     if (lane == 0) tile_sum[t] = ts;
   }
@@ -1213,7 +1255,25 @@ cos_status_t cos_verify(const void* logits, cos_dtype_t dt, int n, int B, int ga
                         const double* u_accept, const double* u_resample,
                         int32_t* accepted_len, int32_t* out_tokens, void* workspace,
                         size_t workspace_bytes, const cos_diag_t* diag, void* hip_stream) {
+  return cos_verify_ex(logits, dt, n, B, gamma, V, draft_tokens, proposer_idx, combine_mode, weights,
+                       u_accept, u_resample, accepted_len, out_tokens, workspace, workspace_bytes,
+                       diag, nullptr, hip_stream);
+}
+
+cos_status_t cos_verify_ex(const void* logits, cos_dtype_t dt, int n, int B, int gamma, int V,
+                           const int32_t* draft_tokens, const int32_t* proposer_idx,
+                           cos_combine_t combine_mode, const double* weights,
+                           const double* u_accept, const double* u_resample,
+                           int32_t* accepted_len, int32_t* out_tokens, void* workspace,
+                           size_t workspace_bytes, const cos_diag_t* diag,
+                           const cos_options_t* options, void* hip_stream) {
   // ---- host-side validation (no HIP call before it passes) ----
+  double temperature = 1.0;
+  if (options) {
+    if (options->struct_bytes != sizeof(cos_options_t)) return COS_ERR_UNSUPPORTED;
+    if (!(options->temperature >= 0.0) || !std::isfinite(options->temperature)) return COS_ERR_WEIGHTS;
+    if (options->temperature > 0.0) temperature = options->temperature;
+  }
   if (!shape_ok(n, B, gamma, V)) return COS_ERR_SHAPE;
   if (dt != COS_DTYPE_F32 && dt != COS_DTYPE_BF16) return COS_ERR_DTYPE;
   if (combine_mode != COS_COMBINE_ENSEMBLE && combine_mode != COS_COMBINE_CONTRASTIVE)
@@ -1261,6 +1321,8 @@ cos_status_t cos_verify(const void* logits, cos_dtype_t dt, int n, int B, int ga
   p.V = V;
   p.draft = draft_tokens;
   p.proposer = proposer_idx;
+  p.proposer_pos = options ? options->proposer_pos : nullptr;
+  p.bonus_idx = options ? options->bonus_idx : nullptr;
   p.u_accept = u_accept;
   p.u_resample = u_resample;
   p.accepted_len = accepted_len;
@@ -1278,6 +1340,7 @@ cos_status_t cos_verify(const void* logits, cos_dtype_t dt, int n, int B, int ga
   p.nstat = pl.nstat;
   choose_sampling(B, pl.ntiles, &p.C, &p.tpc);
   for (int m = 0; m < COS_MAX_MODELS; ++m) p.w[m] = m < n ? weights[m] : 0.0;
+  p.scale = (float)((double)kLog2e / temperature);
   p.mu_hi = p.mu_lo = 0.0f;
   p.thr32 = -INFINITY;
   p.thr64 = -INFINITY;
@@ -1285,7 +1348,8 @@ cos_status_t cos_verify(const void* logits, cos_dtype_t dt, int n, int B, int ga
     p.mu_hi = (float)weights[0];
     p.mu_lo = (float)(weights[0] - (double)p.mu_hi);
     if (weights[1] > 0.0) {
-      p.thr64 = std::log(weights[1]);
+      // (l_0 - max l_0) / T >= ln(alpha_cd)  <=>  l_0 - max l_0 >= T ln(alpha_cd)
+      p.thr64 = temperature * std::log(weights[1]);
       float t = (float)p.thr64;  // smallest float >= thr64
       if ((double)t < p.thr64) t = std::nextafterf(t, INFINITY);
       p.thr32 = t;
@@ -1339,7 +1403,7 @@ const char* cos_status_string(cos_status_t status) {
   return "unknown status";
 }
 
-int cos_verify_version(void) { return 1; }
+int cos_verify_version(void) { return 2; }
 
 cos_status_t cos_profile_enable(int slots) {
   if (slots < 0 || slots > kMaxProfileSlots) return COS_ERR_SHAPE;

@@ -53,11 +53,17 @@ def oracle_dtype(logits: torch.Tensor) -> int:
     return O.DTYPE_F32 if logits.dtype == torch.float32 else O.DTYPE_BF16
 
 
+def _gpu_ext(inp):
+    """Extensions of the step carried in the input dict (all optional)."""
+    return {"temperature": float(inp.get("temperature", 1.0)), "bonus_idx": inp.get("bonus_idx"),
+            "proposer_pos": inp.get("proposer_pos")}
+
+
 def run_gpu(inp: Dict[str, torch.Tensor], mode: int, weights: Sequence[float], with_diag: bool = True):
     B, gamma = inp["draft_tokens"].shape
     diag = C.Diagnostics.allocate(B, gamma, inp["logits"].device) if with_diag else None
     alen, toks = C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], mode, weights,
-                              inp["u_accept"], inp["u_resample"], diag=diag)
+                              inp["u_accept"], inp["u_resample"], diag=diag, **_gpu_ext(inp))
     torch.cuda.synchronize()
     return alen.cpu().numpy(), toks.cpu().numpy(), diag
 
@@ -68,10 +74,15 @@ def run_oracle(inp: Dict[str, torch.Tensor], mode: int, weights: Sequence[float]
     logits = inp["logits"]
     sel = slice(None) if rows is None else torch.as_tensor(list(rows), device=logits.device)
     lg = logits[:, sel].contiguous()
+    bonus = inp.get("bonus_idx")
+    ppos = inp.get("proposer_pos")
     return lg, O.verify(W.host_logits(lg), oracle_dtype(lg), inp["draft_tokens"][sel].cpu().numpy(),
                         inp["proposer_idx"][sel].cpu().numpy(), mode, list(weights),
                         inp["u_accept"][sel].cpu().numpy(), inp["u_resample"][sel].cpu().numpy(),
-                        all_positions=all_positions, num_threads=num_threads)
+                        all_positions=all_positions, num_threads=num_threads,
+                        temperature=float(inp.get("temperature", 1.0)),
+                        bonus_idx=None if bonus is None else bonus[sel].cpu().numpy(),
+                        proposer_pos=None if ppos is None else ppos[sel].cpu().numpy())
 
 
 def _rel_err(got: np.ndarray, want: np.ndarray) -> float:
@@ -84,9 +95,12 @@ def _rel_err(got: np.ndarray, want: np.ndarray) -> float:
     return err
 
 
-def _sample_weights_of_row(host_lg, dtype, b, j, pi, mode, weights, residual):
+def _sample_weights_of_row(host_lg, dtype, b, j, pi, mode, weights, residual, temperature=1.0, bonus=-1):
     n = host_lg.shape[0]
-    l = [O.row_to_f64(host_lg[m, b, j], dtype) for m in range(n)]
+    l = [O.apply_temperature(O.row_to_f64(host_lg[m, b, j], dtype), temperature) for m in range(n)]
+    if bonus >= 0 and not residual:
+        s_v = O.softmax(l[bonus])
+        return s_v, float(s_v.sum())
     s = np.stack([O.softmax(x) for x in l])
     if mode == O.ENSEMBLE:
         r = O.combine_ensemble(s, np.asarray(weights, dtype=np.float64))
@@ -107,6 +121,8 @@ def compare(inp: Dict[str, torch.Tensor], mode: int, weights: Sequence[float], g
     u_acc = inp["u_accept"].cpu().numpy()[idx]
     u_res = inp["u_resample"].cpu().numpy()[idx]
     prop = inp["proposer_idx"].cpu().numpy()[idx]
+    ppos = None if inp.get("proposer_pos") is None else inp["proposer_pos"].cpu().numpy()[idx]
+    bonus = None if inp.get("bonus_idx") is None else inp["bonus_idx"].cpu().numpy()[idx]
     gamma = u_acc.shape[1]
     host_lg = None
     rep.rows = len(idx)
@@ -148,7 +164,10 @@ def compare(inp: Dict[str, torch.Tensor], mode: int, weights: Sequence[float], g
         if host_lg is None:
             host_lg = W.host_logits(lg)
         residual = j < gamma and not (ora.flags[i] & O.FLAG_RESIDUAL_FALLBACK)
-        f, _ = _sample_weights_of_row(host_lg, oracle_dtype(lg), i, j, int(prop[i]), mode, weights, residual)
+        pi = int(prop[i]) if (ppos is None or j >= gamma) else int(ppos[i, j])
+        f, _ = _sample_weights_of_row(host_lg, oracle_dtype(lg), i, j, pi, mode, weights, residual,
+                                      float(inp.get("temperature", 1.0)),
+                                      -1 if bonus is None else int(bonus[i]))
         pos = np.nonzero(f > 0)[0]
         k = int(np.searchsorted(pos, ora.out_tokens[i, j]))
         neighbours = {int(pos[k - 1]) if k > 0 else -1, int(pos[k + 1]) if k + 1 < len(pos) else -1}

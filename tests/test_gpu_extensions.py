@@ -1,0 +1,107 @@
+"""GPU parity of the extensions of the step (cos_verify_ex): temperature, the verifier's own
+bonus token, per-position proposers -- same bar as the base step."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2502_01662_amd import cos_verify as C
+from paper_2502_01662_amd import workloads as W
+from tests import parity as P
+from tests.test_gpu_parity import _check, _random_inputs
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("T", [0.5, 0.7, 1.3, 2.0])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_temperature_ensemble_and_contrastive(T, dtype):
+    inp = _random_inputs(3, 6, 3, 4099, dtype, seed=int(T * 100))
+    inp["temperature"] = T
+    _check(f"ens T={T} {dtype}", inp, C.COS_COMBINE_ENSEMBLE, [0.2, 0.5, 0.3])
+    inp = _random_inputs(2, 6, 3, 33000, dtype, seed=int(T * 100) + 1, std=2.0)
+    inp["temperature"] = T
+    _check(f"cd T={T} {dtype}", inp, C.COS_COMBINE_CONTRASTIVE, [0.5, 0.1])
+
+
+def test_temperature_changes_the_result_and_one_is_the_base_step():
+    w = W.C3.scaled(B=8)
+    inp = W.generate(w, device="cuda")
+    base = P.run_gpu(inp, w.mode, w.weights)
+    inp["temperature"] = 1.0
+    same = P.run_gpu(inp, w.mode, w.weights)
+    assert np.array_equal(base[0], same[0]) and np.array_equal(base[1], same[1])
+    inp["temperature"] = 0.6
+    alen, toks, diag, _ = _check("c3 T=0.6", inp, w.mode, w.weights)
+    assert not np.array_equal(toks, base[1])
+
+
+@pytest.mark.parametrize("mode,weights,n", [(C.COS_COMBINE_ENSEMBLE, [0.5, 0.5], 2),
+                                            (C.COS_COMBINE_ENSEMBLE, [0.5, 0.3, 0.2], 3),
+                                            (C.COS_COMBINE_CONTRASTIVE, [0.5, 0.1], 2)])
+def test_verifier_bonus(mode, weights, n):
+    """Accept everything (identical models would be trivial: use u_accept = 0 on half the rows), draw
+    the bonus from the verifier alone, with NaN where the other models have no logits yet."""
+    B, gamma, V = 12, 3, 5000
+    inp = _random_inputs(n, B, gamma, V, "bf16", seed=77 + n + mode, std=1.5)
+    inp["u_accept"][::2] = 0.0
+    if mode == C.COS_COMBINE_CONTRASTIVE:       # keep the drafts inside the mask so they are accepted at u = 0
+        top = inp["logits"][0, :, :gamma].float().argmax(-1).to(torch.int32)
+        inp["draft_tokens"][::2] = top[::2]
+    bonus = ((inp["proposer_idx"] + 1) % n).to(torch.int32)
+    bonus[1] = -1                                # one row keeps the bonus from r
+    inp["bonus_idx"] = bonus
+    for b in range(B):
+        if int(bonus[b]) >= 0:
+            for m in range(n):
+                if m != int(bonus[b]):
+                    inp["logits"][m, b, gamma] = float("nan")
+    # rows with bonus -1 need valid logits everywhere
+    alen, toks, diag, rep = _check(f"verifier bonus mode={mode} n={n}", inp, mode, weights)
+    assert (alen == gamma).sum() >= B // 2
+    assert np.all(toks[np.arange(B), alen] >= 0)
+
+
+def test_verifier_bonus_only_changes_fully_accepted_rows():
+    inp = _random_inputs(2, 64, 2, 3000, "bf16", seed=5)
+    base = P.run_gpu(inp, C.COS_COMBINE_ENSEMBLE, [0.4, 0.6])
+    inp["bonus_idx"] = (1 - inp["proposer_idx"]).to(torch.int32)
+    alen, toks, diag, _ = _check("bonus vs base", inp, C.COS_COMBINE_ENSEMBLE, [0.4, 0.6])
+    rejected = base[0] < 2
+    assert rejected.any() and (~rejected).any()
+    assert np.array_equal(alen, base[0])
+    assert np.array_equal(toks[rejected], base[1][rejected])
+    assert not np.array_equal(toks[~rejected], base[1][~rejected])
+
+
+@pytest.mark.parametrize("mode,weights,n", [(C.COS_COMBINE_ENSEMBLE, [0.2, 0.5, 0.3], 3),
+                                            (C.COS_COMBINE_CONTRASTIVE, [0.3, 0.05], 2)])
+def test_per_position_proposers(mode, weights, n):
+    B, gamma, V = 24, 4, 8200
+    inp = _random_inputs(n, B, gamma, V, "bf16", seed=31 + n, std=1.5)
+    g = torch.Generator().manual_seed(9)
+    inp["proposer_pos"] = torch.randint(0, n, (B, gamma), generator=g, dtype=torch.int32).cuda()
+    alen, toks, diag, _ = _check(f"per-position proposers mode={mode}", inp, mode, weights)
+    del inp["proposer_pos"]
+    base = P.run_gpu(inp, mode, weights)
+    assert not np.array_equal(base[1], toks)
+
+
+def test_all_extensions_together_on_c5_shape():
+    w = W.C5.scaled(B=16)
+    inp = W.generate(w, device="cuda")
+    g = torch.Generator().manual_seed(3)
+    inp["temperature"] = 0.8
+    inp["proposer_pos"] = torch.randint(0, w.n, (w.B, w.gamma), generator=g, dtype=torch.int32).cuda()
+    inp["bonus_idx"] = torch.randint(-1, w.n, (w.B,), generator=g, dtype=torch.int32).cuda()
+    inp["u_accept"][::3] = 0.0
+    _check("c5 B=16 with every extension", inp, w.mode, w.weights)
+
+
+def test_option_validation():
+    inp = _random_inputs(2, 2, 2, 64, "bf16", seed=1)
+    with pytest.raises(C.CosVerifyError):
+        C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], 0, [0.5, 0.5], inp["u_accept"],
+                     inp["u_resample"], temperature=-1.0)
+    with pytest.raises(C.CosVerifyError):
+        C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], 0, [0.5, 0.5], inp["u_accept"],
+                     inp["u_resample"], temperature=float("nan"))

@@ -1,0 +1,169 @@
+"""Pins of the oracle's extensions: temperature (Sec. 4.1), the verifier's own bonus token
+(Sec. 3.1 / 3.3), per-position proposers (Alg. 2) and the acceptance rate of Eq. (7)."""
+import math
+
+import numpy as np
+import pytest
+from scipy import special, stats
+
+from oracle import cos_oracle as O
+
+
+def _rng(seed):
+    return np.random.default_rng(seed)
+
+
+def _inputs(rng, n, B, gamma, V, std=2.0):
+    logits = (rng.standard_normal((n, B, gamma + 1, V)) * std).astype(np.float32)
+    drafts = rng.integers(0, V, (B, gamma)).astype(np.int32)
+    proposer = rng.integers(0, n, B).astype(np.int32)
+    return logits, drafts, proposer, rng.random((B, gamma)), rng.random(B)
+
+
+# ---- temperature -----------------------------------------------------------
+
+def test_temperature_step_function_and_library_softmax():
+    l = _rng(1).standard_normal(500) * 3
+    for T in (0.5, 0.7, 1.0, 2.0):
+        s = O.softmax(O.apply_temperature(l, T))
+        assert np.allclose(s, special.softmax(l / T), rtol=1e-13)
+    # T -> small sharpens, T -> large flattens
+    assert O.softmax(O.apply_temperature(l, 0.25)).max() > O.softmax(l).max() > O.softmax(O.apply_temperature(l, 4.0)).max()
+
+
+@pytest.mark.parametrize("mode,weights", [(O.ENSEMBLE, [0.3, 0.7]), (O.CONTRASTIVE, [0.5, 0.1])])
+def test_temperature_equals_prescaled_logits(mode, weights):
+    """T = 2 or 1/2 scales float32 logits exactly, so verify(l, T) == verify(l / T, 1) bit for bit."""
+    rng = _rng(2 + mode)
+    logits, drafts, proposer, ua, ur = _inputs(rng, 2, 200, 3, 64)
+    for T in (2.0, 0.5):
+        a = O.verify(logits, O.DTYPE_F32, drafts, proposer, mode, weights, ua, ur, temperature=T)
+        b = O.verify((logits / np.float32(T)).astype(np.float32), O.DTYPE_F32, drafts, proposer, mode, weights, ua, ur)
+        assert a.status == 0 and np.array_equal(a.out_tokens, b.out_tokens) and np.array_equal(a.cdf_hi, b.cdf_hi)
+    c = O.verify(logits, O.DTYPE_F32, drafts, proposer, mode, weights, ua, ur, temperature=1.0)
+    assert not np.array_equal(a.out_tokens, c.out_tokens)            # the temperature matters
+
+
+def test_temperature_contrastive_is_softmax_of_scaled_difference():
+    rng = _rng(4)
+    V, T, mu = 300, 0.7, 0.4
+    lp, lq = rng.standard_normal(V) * 3, rng.standard_normal(V) * 2
+    r, _ = O.combine_contrastive(O.apply_temperature(lp, T), O.apply_temperature(lq, T), mu, 0.0)
+    assert np.allclose(r, special.softmax((lp - mu * lq) / T), rtol=1e-12)
+
+
+# ---- acceptance rate (Eq. 7) -------------------------------------------------
+
+def test_acceptance_rate_closed_form_and_identity():
+    q = np.array([1 / 4, 1 / 2, 1 / 4])
+    r = np.array([4 / 16, 5 / 16, 7 / 16])
+    assert abs(O.acceptance_rate(q, r) - 13 / 16) < 1e-15             # min = (4, 5, 4)/16, by hand
+    rng = _rng(5)
+    for _ in range(10):
+        q = O.softmax(rng.standard_normal(200) * 3)
+        r = O.softmax(rng.standard_normal(200) * 3)
+        assert abs(O.acceptance_rate(q, r) - (1 - 0.5 * np.abs(q - r).sum())) < 1e-12   # Eq. (7)
+        assert abs(O.acceptance_rate(q, q) - 1.0) < 1e-12
+
+
+def test_alpha_output_of_the_whole_step():
+    rng = _rng(6)
+    logits, drafts, proposer, ua, ur = _inputs(rng, 3, 40, 4, 50)
+    w = [0.5, 0.3, 0.2]
+    res = O.verify(logits, O.DTYPE_F32, drafts, proposer, O.ENSEMBLE, w, ua, ur, all_positions=True, want_alpha=True)
+    seq = O.verify(logits, O.DTYPE_F32, drafts, proposer, O.ENSEMBLE, w, ua, ur, want_alpha=True)
+    for b in range(40):
+        for j in range(4):
+            s = np.stack([O.softmax(O.row_to_f64(logits[m, b, j], O.DTYPE_F32)) for m in range(3)])
+            r = O.combine_ensemble(s, np.array(w))
+            want = np.minimum(s[proposer[b]], r).sum()
+            assert abs(res.alpha[b, j] - want) < 1e-12
+            assert res.alpha[b, j] >= w[proposer[b]] - 1e-12            # Thm 3.2
+            if j <= seq.accepted_len[b]:
+                assert seq.alpha[b, j] == res.alpha[b, j]
+            else:
+                assert math.isnan(seq.alpha[b, j])                     # never evaluated
+
+
+# ---- the verifier's own bonus token (Sec. 3.1 / 3.3) --------------------------
+
+def test_verifier_bonus_follows_the_verifiers_distribution_and_ignores_other_rows():
+    rng = _rng(7)
+    n, B, gamma, V = 2, 50_000, 2, 8
+    row = (rng.standard_normal((n, 1, gamma + 1, V)) * 1.5).astype(np.float32)
+    logits = np.ascontiguousarray(np.broadcast_to(row, (n, B, gamma + 1, V))).copy()
+    drafts = rng.integers(0, V, (B, gamma)).astype(np.int32)
+    proposer = np.zeros(B, dtype=np.int32)
+    bonus = np.ones(B, dtype=np.int32)                                 # verifier = model 1
+    ua = np.zeros((B, gamma))                                          # u = 0: every draft with r(d) > 0 is accepted
+    ur = rng.random(B)
+    logits[0, :, gamma, :] = np.nan                                    # the proposer has no logits there yet
+    res = O.verify(logits, O.DTYPE_F32, drafts, proposer, O.ENSEMBLE, [0.5, 0.5], ua, ur, bonus_idx=bonus)
+    assert res.status == 0 and np.all(res.accepted_len == gamma)
+    sv = O.softmax(O.row_to_f64(logits[1, 0, gamma], O.DTYPE_F32))
+    cdf = np.cumsum(sv)
+    want = np.searchsorted(cdf, ur * cdf[-1], side="right")
+    assert np.array_equal(res.out_tokens[:, gamma], want)
+    counts = np.bincount(res.out_tokens[:, gamma], minlength=V)
+    assert stats.chisquare(counts, sv / sv.sum() * B).pvalue > 1e-3
+    # -1 (or no bonus_idx) draws the bonus from r: with NaN rows that poisons the draw, without them not
+    clean = logits.copy()
+    clean[0, :, gamma, :] = row[0, 0, gamma]
+    a = O.verify(clean, O.DTYPE_F32, drafts, proposer, O.ENSEMBLE, [0.5, 0.5], ua, ur, bonus_idx=-np.ones(B, dtype=np.int32))
+    b = O.verify(clean, O.DTYPE_F32, drafts, proposer, O.ENSEMBLE, [0.5, 0.5], ua, ur)
+    assert np.array_equal(a.out_tokens, b.out_tokens)
+    assert not np.array_equal(a.out_tokens[:, gamma], res.out_tokens[:, gamma])
+
+
+def test_verifier_bonus_does_not_change_rejected_rows():
+    rng = _rng(8)
+    logits, drafts, proposer, ua, ur = _inputs(rng, 2, 300, 3, 40)
+    base = O.verify(logits, O.DTYPE_F32, drafts, proposer, O.ENSEMBLE, [0.4, 0.6], ua, ur)
+    vb = O.verify(logits, O.DTYPE_F32, drafts, proposer, O.ENSEMBLE, [0.4, 0.6], ua, ur, bonus_idx=1 - proposer)
+    rejected = base.accepted_len < 3
+    assert rejected.any() and (~rejected).any()
+    assert np.array_equal(base.accepted_len, vb.accepted_len)
+    assert np.array_equal(base.out_tokens[rejected], vb.out_tokens[rejected])
+
+
+# ---- per-position proposers (Alg. 2) -------------------------------------------
+
+def test_per_position_proposers_against_an_independent_rederivation():
+    rng = _rng(9)
+    n, B, gamma, V = 3, 300, 4, 30
+    logits, drafts, proposer, ua, ur = _inputs(rng, n, B, gamma, V)
+    pos = rng.integers(0, n, (B, gamma)).astype(np.int32)
+    w = np.array([0.2, 0.5, 0.3])
+    res = O.verify(logits, O.DTYPE_F32, drafts, proposer, O.ENSEMBLE, w, ua, ur, proposer_pos=pos)
+    sm = special.softmax(logits.astype(np.float64), axis=-1)
+    for b in range(B):
+        alen, tok = gamma, None
+        for j in range(gamma):
+            r = np.tensordot(w, sm[:, b, j], axes=1)
+            q = sm[pos[b, j], b, j]
+            d = drafts[b, j]
+            if not ua[b, j] < min(1.0, r[d] / q[d]):
+                cdf = np.cumsum(np.maximum(r - q, 0.0))
+                alen, tok = j, int(np.searchsorted(cdf, ur[b] * cdf[-1], side="right"))
+                break
+        if tok is None:
+            cdf = np.cumsum(np.tensordot(w, sm[:, b, gamma], axes=1))
+            tok = int(np.searchsorted(cdf, ur[b] * cdf[-1], side="right"))
+        assert res.accepted_len[b] == alen and res.out_tokens[b, alen] == tok
+    # constant per-position proposers are the per-row case
+    same = O.verify(logits, O.DTYPE_F32, drafts, proposer, O.ENSEMBLE, w, ua, ur,
+                    proposer_pos=np.repeat(proposer[:, None], gamma, axis=1))
+    base = O.verify(logits, O.DTYPE_F32, drafts, proposer, O.ENSEMBLE, w, ua, ur)
+    assert np.array_equal(same.out_tokens, base.out_tokens)
+    assert not np.array_equal(res.out_tokens, base.out_tokens)
+
+
+def test_extension_argument_checks():
+    rng = _rng(10)
+    logits, drafts, proposer, ua, ur = _inputs(rng, 2, 4, 2, 10)
+    assert O.verify(logits, O.DTYPE_F32, drafts, proposer, O.ENSEMBLE, [0.5, 0.5], ua, ur,
+                    bonus_idx=np.full(4, 2)).status == -2
+    assert O.verify(logits, O.DTYPE_F32, drafts, proposer, O.ENSEMBLE, [0.5, 0.5], ua, ur,
+                    proposer_pos=np.full((4, 2), -1)).status == -2
+    assert O.verify(logits, O.DTYPE_F32, drafts, proposer, O.ENSEMBLE, [0.5, 0.5], ua, ur,
+                    temperature=-1.0).status == -5
