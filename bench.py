@@ -40,6 +40,8 @@ def main() -> int:
     ap.add_argument("--cpu-rows", type=int, default=-1, help="batch rows the CPU oracle is timed on (-1 = auto, 0 = skip)")
     ap.add_argument("--chunk-vectors", type=int, default=0, help="tuning knob (0 = library heuristic)")
     ap.add_argument("--sample-blocks", type=int, default=0, help="tuning knob (0 = library heuristic)")
+    ap.add_argument("--with-alpha", action="store_true",
+                    help="also compute the acceptance rates of Eq. (7) (an optional output, not the headline step)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (rows of the batch shard without any exchange; "
@@ -75,10 +77,13 @@ def main() -> int:
     alen = torch.empty(w.B, dtype=torch.int32, device=dev)
     toks = torch.empty((w.B, w.gamma + 1), dtype=torch.int32, device=dev)
 
+    alpha = torch.empty((w.B, w.gamma), dtype=torch.float64, device=dev) if args.with_alpha else None
+
     def step(i):
         s = sets[i % nsets]
         C.cos_verify(s["logits"], s["draft_tokens"], s["proposer_idx"], w.mode, w.weights,
-                     s["u_accept"], s["u_resample"], accepted_len=alen, out_tokens=toks, workspace=ws)
+                     s["u_accept"], s["u_resample"], accepted_len=alen, out_tokens=toks, workspace=ws,
+                     alpha=alpha)
 
     for i in range(args.warmup):
         step(i)
@@ -135,7 +140,8 @@ def main() -> int:
         torch.cuda.synchronize()
         ga, gt = alen.cpu().numpy()[rows], toks.cpu().numpy()[rows]
         exact = int(np.sum((ga == res.accepted_len) & np.all(gt == res.out_tokens, axis=1)))
-        parity = {"rows": int(len(rows)), "bit_exact_rows": exact}
+        parity = {"rows": int(len(rows)), "bit_exact_rows": exact,
+                  "accepted_len_histogram": np.bincount(alen.cpu().numpy(), minlength=w.gamma + 1).tolist()}
 
     out = {
         "metric": "verified positions/sec + achieved HBM GB/s of cos_verify (bf16 logits, 1 GPU)",
@@ -146,7 +152,7 @@ def main() -> int:
         "config": {"workload": w.name, "n": w.n, "B": w.B, "gamma": w.gamma, "V": w.V,
                    "combine": "contrastive" if w.mode == W.CONTRASTIVE else "ensemble", "weights": list(w.weights),
                    "input_sets_rotated": nsets, "chunk_vectors": args.chunk_vectors,
-                   "sample_blocks": args.sample_blocks},
+                   "sample_blocks": args.sample_blocks, "acceptance_rate_output": bool(args.with_alpha)},
         "achieved_hbm_gbs_per_step": round(w.logit_bytes / (ms_per_step * 1e-3) / 1e9, 1),
         "roofline": roofline, "cpu_baseline": cpu, "parity_sample": parity,
         "input_generation_s": round(gen_s, 1),

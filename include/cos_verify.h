@@ -127,12 +127,17 @@ cos_status_t cos_verify(const void *logits, cos_dtype_t dt, int n, int B, int ga
  * proposer_pos  DEVICE [B][gamma] int32 or NULL: the proposer of every draft
  *               position (Alg. 2: tokens of one window can come from different
  *               models); overrides proposer_idx, which must still be valid.
+ * alpha         DEVICE out [B][gamma] float64 or NULL: the acceptance rate
+ *               alpha = sum_x min(q(x), r(x)) = 1 - (1/2) sum_x |q(x) - r(x)|
+ *               (Eq. (7), App. A.1) of every draft position.  Costs a second
+ *               read of the draft positions' logits (one more kernel).
  */
 typedef struct cos_options_t {
   size_t struct_bytes;
   double temperature;
   const int32_t *bonus_idx;
   const int32_t *proposer_pos;
+  double *alpha;
 } cos_options_t;
 
 /* cos_verify with extensions; options == NULL is exactly cos_verify. */

@@ -46,6 +46,7 @@ constexpr float kMaxOffset = 268435456.0f;  // 2^28: clamp for absurd logits
 constexpr int kMaxSplits = 128;             // upper bound on chunks per row (workspace sizing)
 constexpr int kMaxStatsPerSeq = 256;        // (gamma+1) * statistics per position
 constexpr int kMaxTiles = 4096;             // tiles per row the final scan can hold in LDS
+constexpr int kMaxAlphaBlocks = 64;         // acceptance-rate workgroups per (sequence, position)
 // Arrival counters are agent-scope atomics executed at the memory side; one
 // counter per 256 bytes spreads them over the memory channels (packed counters
 // serialise on one channel and slow every stream that crosses it).
@@ -86,6 +87,13 @@ struct Params {
   float* rowmax;      // contrastive: [B][gamma+1][S] partial maxima of the expert row
   SeqPlan* plans;     // [B]
   double* tile_sums;  // [B][ntiles]
+  // acceptance-rate output (optional)
+  double* alpha;           // [B][gamma] out, or NULL
+  double* lse_all;         // [B][gamma+1][nstat] log2-sum-exp2 of every position
+  float* rowmax_all;       // contrastive: [B][gamma+1] expert maxima
+  double* alpha_partials;  // [B][gamma][CA]
+  int CA;                  // acceptance-rate workgroups per (sequence, position)
+  int tpa;                 // tiles per acceptance-rate workgroup
   int S;              // chunks per row
   int cv;             // vectors per chunk
   int nvec;           // 16-byte vectors per row (last may be partial when unaligned)
@@ -597,6 +605,10 @@ __device__ void decide_sequence(const Params& p, int b, DecideShared& sh) {
     plan->pad = 0;
   }
   if (tid < nstat) plan->lse2[tid] = sh.lse2[jstar * nstat + tid];
+  if (p.alpha) {
+    if (tid < nrows) p.lse_all[(size_t)b * nrows + tid] = sh.lse2[tid];
+    if (CONTRASTIVE && tid < g1) p.rowmax_all[(size_t)b * g1 + tid] = sh.rowmax[tid];
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -1098,6 +1110,100 @@ __global__ void __launch_bounds__(kThreads) sample_kernel(Params p) {
                                               COS_FLAG_RESIDUAL_FALLBACK);
 }
 
+// Acceptance-rate kernel (optional): alpha = sum_x min(q(x), r(x)) of Eq. (7) for
+// every draft position.  Workgroup index -> (b, j, c); a second full read of the
+// draft positions' rows, with the normalisers the streaming kernel left behind.
+template <typename T, bool ALIGNED, int NM, bool CONTRASTIVE>
+__global__ void __launch_bounds__(kThreads) acceptance_rate_kernel(Params p) {
+  constexpr int N = VecOf<T>::N;
+  constexpr int NCAP = CONTRASTIVE ? 2 : (NM ? NM : COS_MAX_MODELS);
+  __shared__ double wsum[kWaves];
+  __shared__ int s_flag;
+
+  const int per_b = p.gamma * p.CA;
+  const int b = blockIdx.x / per_b;
+  int rem = blockIdx.x - b * per_b;
+  const int j = rem / p.CA;
+  const int c = rem - j * p.CA;
+  const int lane = lane_id();
+  const int wave = threadIdx.x >> 6;
+  const int n = CONTRASTIVE ? 2 : (NM ? NM : p.n);
+  const int g1 = p.gamma + 1;
+  const int pi = p.proposer_pos ? p.proposer_pos[(size_t)b * p.gamma + j] : p.proposer[b];
+  const double* lse = p.lse_all + ((size_t)b * g1 + j) * p.nstat;
+  const float m0 = CONTRASTIVE ? p.rowmax_all[(size_t)b * g1 + j] : 0.0f;
+
+  // r = sum_m cr[m] 2^(l_m*scale - off[m]); q = cq 2^(l_pi*scale - off[pi])   (ensemble)
+  // r = [mask] cr[0] 2^(c*scale - off[0]);  q = cq 2^(l_pi*scale - off[1])    (contrastive)
+  float cr[NCAP], off[NCAP], cq = 0.0f;
+#pragma unroll
+  for (int m = 0; m < NCAP; ++m) {
+    cr[m] = 0.0f;
+    off[m] = 0.0f;
+    if (m < n) {
+      const double l2 = CONTRASTIVE ? lse[m == 0 ? 2 : pi] : lse[m];
+      const double K = rint(l2);
+      const double unit = exp2(K - l2);
+      off[m] = (float)K;
+      if constexpr (CONTRASTIVE) {
+        if (m == 0) cr[0] = (float)unit; else cq = (float)unit;
+      } else {
+        cr[m] = (float)(p.w[m] * unit);
+        if (m == pi) cq = (float)unit;
+      }
+    }
+  }
+  const T* rows[NCAP];
+#pragma unroll
+  for (int m = 0; m < NCAP; ++m) rows[m] = row_ptr<T>(p, m < n ? m : 0, b, j);
+
+  double acc = 0.0;
+  const int tb = c * p.tpa;
+  const int te = min(tb + p.tpa, p.ntiles);
+  for (int t = tb + wave; t < te; t += kWaves) {
+    float x[NCAP][N];
+    tile_load<T, ALIGNED, NCAP>(p, rows, n, t, x);
+    if (t * 64 + lane < p.nvec) {
+#pragma unroll
+      for (int k = 0; k < N; ++k) {
+        float r = 0.0f, q = 0.0f;
+        if constexpr (!CONTRASTIVE) {
+#pragma unroll
+          for (int m = 0; m < NCAP; ++m)
+            if (m < n) {
+              const float e = fast_exp2(fmaf(x[m][k], p.scale, -off[m]));
+              r += cr[m] * e;
+              if (m == pi) q = cq * e;
+            }
+        } else {
+          const bool in = in_mask<T>(x[0][k], m0, p.thr32, p.thr64);
+          const float cc = contrast(x[0][k], x[1][k], p.mu_hi, p.mu_lo);
+          r = in ? cr[0] * fast_exp2(fmaf(cc, p.scale, -off[0])) : 0.0f;
+          q = cq * fast_exp2(fmaf(pi ? x[1][k] : x[0][k], p.scale, -off[1]));
+        }
+        acc += (double)fminf(q, r);
+      }
+    }
+  }
+  const double ws = wave_sum(acc);
+  if (lane == 0) wsum[wave] = ws;
+  __syncthreads();
+  double* parts = p.alpha_partials + ((size_t)b * p.gamma + j) * p.CA;
+  if (threadIdx.x == 0) {
+    double tot = 0.0;
+    for (int w = 0; w < kWaves; ++w) tot += wsum[w];
+    store_agent(parts + c, tot);
+    wait_stores();
+  }
+  int* counter = p.counters + ((size_t)2 * p.B + (size_t)b * p.gamma + j) * kCtrStride;
+  if (!arrive_last(counter, p.CA, &s_flag)) return;
+  if (threadIdx.x == 0) {
+    double tot = 0.0;
+    for (int i = 0; i < p.CA; ++i) tot += load_agent(parts + i);
+    p.alpha[(size_t)b * p.gamma + j] = tot;
+  }
+}
+
 // ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
@@ -1114,7 +1220,8 @@ int g_ev_recorded = 0;  // calls recorded since the last enable
 
 struct Plan {
   int nvec, ntiles, nstat;
-  size_t off_counters, off_partials, off_rowmax, off_plans, off_tiles, bytes;
+  size_t off_counters, off_partials, off_rowmax, off_plans, off_tiles, off_lse_all, off_rowmax_all,
+      off_alpha_partials, bytes;
 };
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -1134,11 +1241,17 @@ void plan_layout(int n, int B, int gamma, int V, cos_dtype_t dt, cos_combine_t m
   const size_t g1 = (size_t)gamma + 1;
   size_t at = 0;
   pl->off_counters = at;
-  at += align_up((size_t)2 * B * kCtrStride * sizeof(int), 256);
+  at += align_up(((size_t)2 * B + (size_t)B * gamma) * kCtrStride * sizeof(int), 256);
   pl->off_plans = at;
   at += align_up((size_t)B * sizeof(SeqPlan), 256);
   pl->off_tiles = at;
   at += align_up((size_t)B * pl->ntiles * sizeof(double), 256);
+  pl->off_lse_all = at;
+  at += align_up((size_t)B * g1 * pl->nstat * sizeof(double), 256);
+  pl->off_rowmax_all = at;
+  at += align_up((size_t)B * g1 * sizeof(float), 256);
+  pl->off_alpha_partials = at;
+  at += align_up((size_t)B * gamma * kMaxAlphaBlocks * sizeof(double), 256);
   pl->off_rowmax = at;
   if (mode == COS_COMBINE_CONTRASTIVE) at += align_up((size_t)B * g1 * S * sizeof(float), 256);
   pl->off_partials = at;
@@ -1210,6 +1323,27 @@ cos_status_t launch_sampling(const Params& p, size_t lds, hipStream_t st) {
   return hipGetLastError() == hipSuccess ? COS_OK : COS_ERR_LAUNCH;
 }
 
+template <typename T, bool ALIGNED, bool CONTRASTIVE>
+cos_status_t launch_acceptance_rate(const Params& p, hipStream_t st) {
+  const long blocks = (long)p.B * p.gamma * p.CA;
+  if (blocks <= 0 || blocks > 0x7fffffffL) return COS_ERR_SHAPE;
+  const dim3 grid((unsigned)blocks), block(kThreads);
+  if constexpr (CONTRASTIVE) {
+    hipLaunchKernelGGL((acceptance_rate_kernel<T, ALIGNED, 2, true>), grid, block, 0, st, p);
+  } else if constexpr (ALIGNED) {
+    switch (p.n) {
+      case 1: hipLaunchKernelGGL((acceptance_rate_kernel<T, true, 1, false>), grid, block, 0, st, p); break;
+      case 2: hipLaunchKernelGGL((acceptance_rate_kernel<T, true, 2, false>), grid, block, 0, st, p); break;
+      case 3: hipLaunchKernelGGL((acceptance_rate_kernel<T, true, 3, false>), grid, block, 0, st, p); break;
+      case 4: hipLaunchKernelGGL((acceptance_rate_kernel<T, true, 4, false>), grid, block, 0, st, p); break;
+      default: hipLaunchKernelGGL((acceptance_rate_kernel<T, true, 0, false>), grid, block, 0, st, p); break;
+    }
+  } else {
+    hipLaunchKernelGGL((acceptance_rate_kernel<T, false, 0, false>), grid, block, 0, st, p);
+  }
+  return hipGetLastError() == hipSuccess ? COS_OK : COS_ERR_LAUNCH;
+}
+
 template <typename T, bool ALIGNED>
 cos_status_t launch_all(const Params& p, bool contrastive, size_t lds, hipStream_t st,
                         hipEvent_t ev_start, hipEvent_t ev_stop) {
@@ -1221,7 +1355,9 @@ cos_status_t launch_all(const Params& p, bool contrastive, size_t lds, hipStream
     hipLaunchKernelGGL((ensemble_stats_kernel<T, ALIGNED>), dim3((unsigned)blocks), block, 0, st, p);
     if (ev_stop) (void)hipEventRecord(ev_stop, st);
     if (hipGetLastError() != hipSuccess) return COS_ERR_LAUNCH;
-    return launch_sampling<T, ALIGNED, false>(p, lds, st);
+    const cos_status_t rc = launch_sampling<T, ALIGNED, false>(p, lds, st);
+    if (rc != COS_OK || !p.alpha) return rc;
+    return launch_acceptance_rate<T, ALIGNED, false>(p, st);
   }
   const long blocks = (long)p.B * (p.gamma + 1) * p.S;
   if (blocks <= 0 || blocks > 0x7fffffffL) return COS_ERR_SHAPE;
@@ -1231,7 +1367,9 @@ cos_status_t launch_all(const Params& p, bool contrastive, size_t lds, hipStream
   hipLaunchKernelGGL((contrastive_stats_kernel<T, ALIGNED>), dim3((unsigned)blocks), block, 0, st, p);
   if (ev_stop) (void)hipEventRecord(ev_stop, st);
   if (hipGetLastError() != hipSuccess) return COS_ERR_LAUNCH;
-  return launch_sampling<T, ALIGNED, true>(p, lds, st);
+  const cos_status_t rc = launch_sampling<T, ALIGNED, true>(p, lds, st);
+  if (rc != COS_OK || !p.alpha) return rc;
+  return launch_acceptance_rate<T, ALIGNED, true>(p, st);
 }
 
 }  // namespace
@@ -1333,6 +1471,20 @@ cos_status_t cos_verify_ex(const void* logits, cos_dtype_t dt, int n, int B, int
   p.rowmax = reinterpret_cast<float*>(wsb + pl.off_rowmax);
   p.plans = reinterpret_cast<SeqPlan*>(wsb + pl.off_plans);
   p.tile_sums = reinterpret_cast<double*>(wsb + pl.off_tiles);
+  p.alpha = options ? options->alpha : nullptr;
+  p.lse_all = reinterpret_cast<double*>(wsb + pl.off_lse_all);
+  p.rowmax_all = reinterpret_cast<float*>(wsb + pl.off_rowmax_all);
+  p.alpha_partials = reinterpret_cast<double*>(wsb + pl.off_alpha_partials);
+  {
+    // about 4096 acceptance-rate workgroups in total, at least 4 tiles each
+    long ca = (4096 + (long)B * gamma - 1) / ((long)B * gamma);
+    const int cmax = (pl.ntiles + 3) / 4;
+    if (ca > cmax) ca = cmax;
+    if (ca > kMaxAlphaBlocks) ca = kMaxAlphaBlocks;
+    if (ca < 1) ca = 1;
+    p.tpa = (pl.ntiles + (int)ca - 1) / (int)ca;
+    p.CA = (pl.ntiles + p.tpa - 1) / p.tpa;
+  }
   p.S = S;
   p.cv = cv;
   p.nvec = pl.nvec;
@@ -1371,7 +1523,7 @@ cos_status_t cos_verify_ex(const void* logits, cos_dtype_t dt, int n, int B, int
   hipEvent_t ev_start = profile ? g_ev_start[slot] : nullptr;
   hipEvent_t ev_stop = profile ? g_ev_stop[slot] : nullptr;
 
-  const int nctr = 2 * B * kCtrStride;
+  const int nctr = (2 * B + B * gamma) * kCtrStride;
   hipLaunchKernelGGL(fill_zero_kernel, dim3((nctr + kThreads - 1) / kThreads), dim3(kThreads), 0, st,
                      p.counters, nctr);
   if (hipGetLastError() != hipSuccess) return COS_ERR_LAUNCH;

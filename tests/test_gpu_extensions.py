@@ -105,3 +105,49 @@ def test_option_validation():
     with pytest.raises(C.CosVerifyError):
         C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], 0, [0.5, 0.5], inp["u_accept"],
                      inp["u_resample"], temperature=float("nan"))
+
+
+@pytest.mark.parametrize("mode,weights,n,dtype", [(C.COS_COMBINE_ENSEMBLE, [0.5, 0.3, 0.2], 3, "bf16"),
+                                                  (C.COS_COMBINE_ENSEMBLE, [0.25] * 4, 4, "f32"),
+                                                  (C.COS_COMBINE_ENSEMBLE, [0.1, 0.2, 0.3, 0.15, 0.25], 5, "bf16"),
+                                                  (C.COS_COMBINE_CONTRASTIVE, [0.5, 0.1], 2, "bf16"),
+                                                  (C.COS_COMBINE_CONTRASTIVE, [0.2, 0.0], 2, "f32")])
+def test_acceptance_rate_output(mode, weights, n, dtype):
+    """alpha = sum min(q, r) per draft position (Eq. 7) against the oracle: float32 terms of relative
+    error ~1e-7 summed in float64, so 1e-6 absolute on a number in [0, 1]."""
+    from oracle import cos_oracle as O
+    B, gamma, V = 10, 3, 20011
+    inp = _random_inputs(n, B, gamma, V, dtype, seed=91 + n, std=1.5)
+    g = torch.Generator().manual_seed(4)
+    inp["proposer_pos"] = torch.randint(0, n, (B, gamma), generator=g, dtype=torch.int32).cuda()
+    inp["temperature"] = 0.9
+    alpha = torch.full((B, gamma), -1.0, dtype=torch.float64, device="cuda")
+    alen, toks = C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], mode, weights,
+                              inp["u_accept"], inp["u_resample"], alpha=alpha, **P._gpu_ext(inp))
+    torch.cuda.synchronize()
+    ora = O.verify(W.host_logits(inp["logits"]), P.oracle_dtype(inp["logits"]), inp["draft_tokens"].cpu().numpy(),
+                   inp["proposer_idx"].cpu().numpy(), mode, weights, inp["u_accept"].cpu().numpy(),
+                   inp["u_resample"].cpu().numpy(), all_positions=True, temperature=0.9,
+                   proposer_pos=inp["proposer_pos"].cpu().numpy(), want_alpha=True)
+    got = alpha.cpu().numpy()
+    err = np.abs(got - ora.alpha).max()
+    print(f"[parity] alpha mode={mode} n={n} {dtype}: max abs err {err:.3e}", flush=True)
+    assert err < 1e-6
+    assert np.array_equal(alen.cpu().numpy(), ora.accepted_len) and np.array_equal(toks.cpu().numpy(), ora.out_tokens)
+    if mode == C.COS_COMBINE_ENSEMBLE:          # Thm 3.2: alpha >= the proposer's weight
+        w = np.asarray(weights)[inp["proposer_pos"].cpu().numpy()]
+        assert np.all(got >= w - 1e-6)
+
+
+def test_acceptance_rate_full_c4_shape():
+    from oracle import cos_oracle as O
+    w = W.C4.scaled(B=32)
+    inp = W.generate(w, device="cuda")
+    alpha = torch.empty((w.B, w.gamma), dtype=torch.float64, device="cuda")
+    C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], w.mode, w.weights,
+                 inp["u_accept"], inp["u_resample"], alpha=alpha)
+    torch.cuda.synchronize()
+    ora = O.verify(W.host_logits(inp["logits"]), O.DTYPE_BF16, inp["draft_tokens"].cpu().numpy(),
+                   inp["proposer_idx"].cpu().numpy(), w.mode, list(w.weights), inp["u_accept"].cpu().numpy(),
+                   inp["u_resample"].cpu().numpy(), all_positions=True, want_alpha=True)
+    assert np.abs(alpha.cpu().numpy() - ora.alpha).max() < 1e-6
