@@ -40,6 +40,9 @@ def main() -> int:
     ap.add_argument("--cpu-rows", type=int, default=-1, help="batch rows the CPU oracle is timed on (-1 = auto, 0 = skip)")
     ap.add_argument("--chunk-vectors", type=int, default=0, help="tuning knob (0 = library heuristic)")
     ap.add_argument("--sample-blocks", type=int, default=0, help="tuning knob (0 = library heuristic)")
+    ap.add_argument("--stop-window", type=int, default=0,
+                    help="verify this many positions per launch and never read past a sequence's first "
+                         "rejection (0 = the headline step: every position read, one launch)")
     ap.add_argument("--with-alpha", action="store_true",
                     help="also compute the acceptance rates of Eq. (7) (an optional output, not the headline step)")
     args = ap.parse_args()
@@ -83,7 +86,7 @@ def main() -> int:
         s = sets[i % nsets]
         C.cos_verify(s["logits"], s["draft_tokens"], s["proposer_idx"], w.mode, w.weights,
                      s["u_accept"], s["u_resample"], accepted_len=alen, out_tokens=toks, workspace=ws,
-                     alpha=alpha)
+                     alpha=alpha, stop_window=args.stop_window)
 
     for i in range(args.warmup):
         step(i)
@@ -107,6 +110,29 @@ def main() -> int:
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": _traffic_from_profiles(args.workload),
                 "algorithmic_bytes_per_launch": w.logit_bytes, "kernel_avg_ms": round(kavg, 5),
                 "kernel_min_ms": round(float(np.min(kernel_ms)), 5)}
+
+    # ---- the same step with stop_window = 1 (opt-in: rows after a sequence's first rejection are
+    # never read, one launch per position): reported beside the headline, never as `value` ----
+    lazy = None
+    if args.stop_window == 0 and not args.with_alpha:
+        def lazy_step(i):
+            s = sets[i % nsets]
+            C.cos_verify(s["logits"], s["draft_tokens"], s["proposer_idx"], w.mode, w.weights,
+                         s["u_accept"], s["u_resample"], accepted_len=alen, out_tokens=toks, workspace=ws,
+                         stop_window=1)
+        for i in range(args.warmup):
+            lazy_step(i)
+        torch.cuda.synchronize()
+        l1 = time.perf_counter()
+        for i in range(args.steps):
+            lazy_step(i)
+        torch.cuda.synchronize()
+        l2 = time.perf_counter()
+        lazy_ms = (l2 - l1) * 1e3 / args.steps
+        lazy = {"ms_per_step": round(lazy_ms, 5), "value": round(w.positions / (lazy_ms * 1e-3), 1),
+                "unit": "positions/s",
+                "note": "identical outputs; logits after a sequence's first rejection are not read, so fewer "
+                        "bytes than the algorithmic count move: not comparable with the HBM roofline"}
 
     # ---- CPU baseline: the oracle as it stands, on a bounded sample of the same batch ----
     cpu = None
@@ -152,9 +178,10 @@ def main() -> int:
         "config": {"workload": w.name, "n": w.n, "B": w.B, "gamma": w.gamma, "V": w.V,
                    "combine": "contrastive" if w.mode == W.CONTRASTIVE else "ensemble", "weights": list(w.weights),
                    "input_sets_rotated": nsets, "chunk_vectors": args.chunk_vectors,
-                   "sample_blocks": args.sample_blocks, "acceptance_rate_output": bool(args.with_alpha)},
+                   "sample_blocks": args.sample_blocks, "acceptance_rate_output": bool(args.with_alpha),
+                   "stop_window": args.stop_window},
         "achieved_hbm_gbs_per_step": round(w.logit_bytes / (ms_per_step * 1e-3) / 1e9, 1),
-        "roofline": roofline, "cpu_baseline": cpu, "parity_sample": parity,
+        "roofline": roofline, "cpu_baseline": cpu, "parity_sample": parity, "stop_window_1": lazy,
         "input_generation_s": round(gen_s, 1),
     }
     print(json.dumps(out), flush=True)

@@ -131,6 +131,14 @@ cos_status_t cos_verify(const void *logits, cos_dtype_t dt, int n, int B, int ga
  *               alpha = sum_x min(q(x), r(x)) = 1 - (1/2) sum_x |q(x) - r(x)|
  *               (Eq. (7), App. A.1) of every draft position.  Costs a second
  *               read of the draft positions' logits (one more kernel).
+ * stop_window   0 (or > gamma): every position of every sequence is read, in
+ *               one streaming launch.  w >= 1: the positions are verified w at
+ *               a time, one streaming launch per window, and a sequence's
+ *               logits after the window of its first rejection are never read
+ *               (Sec. 3.1: they are discarded).  accepted_len and out_tokens
+ *               are identical; diag.r_at_draft / q_at_draft are written only
+ *               for positions that were read; alpha must be NULL
+ *               (COS_ERR_UNSUPPORTED).  Fewer bytes, more launches.
  */
 typedef struct cos_options_t {
   size_t struct_bytes;
@@ -138,6 +146,7 @@ typedef struct cos_options_t {
   const int32_t *bonus_idx;
   const int32_t *proposer_pos;
   double *alpha;
+  int stop_window;
 } cos_options_t;
 
 /* cos_verify with extensions; options == NULL is exactly cos_verify. */

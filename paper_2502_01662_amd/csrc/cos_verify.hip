@@ -82,7 +82,8 @@ struct Params {
   int* accepted_len;
   int* out_tokens;
   // workspace
-  int* counters;      // [2][B] (stride kCtrStride): arrivals of the streaming, then the sampling kernel
+  int* counters;      // (stride kCtrStride) [gamma+1 windows][B] streaming arrivals, [B] sampling
+                      // arrivals, [B][gamma] acceptance-rate arrivals
   Partial* partials;  // [B][gamma+1][nstat][S]
   float* rowmax;      // contrastive: [B][gamma+1][S] partial maxima of the expert row
   SeqPlan* plans;     // [B]
@@ -101,6 +102,9 @@ struct Params {
   int nstat;          // statistics per position: n (ensemble) or 3 (contrastive)
   int C;              // sampling workgroups per sequence
   int tpc;            // tiles per sampling workgroup
+  int j0;             // first position of this launch's window
+  int nj;             // positions in this launch's window (gamma+1: the whole step in one launch)
+  int win;            // window index (selects the arrival counters)
   double w[COS_MAX_MODELS];  // ensemble weights; contrastive: w[0] = mu, w[1] = alpha_cd
   float scale;               // log2(e) / temperature: logits times this are base-2 exponents
   float mu_hi, mu_lo;        // mu split into two floats
@@ -514,18 +518,22 @@ struct DecideShared {
   int accept[COS_MAX_GAMMA + 1];
 };
 
+// Decides the window [j0, j0+nj) of a sequence that no earlier window has
+// decided.  The sequence stays undecided if every draft of the window is
+// accepted and the window does not contain the bonus position.
 template <typename T, bool CONTRASTIVE>
 __device__ void decide_sequence(const Params& p, int b, DecideShared& sh) {
   const int tid = threadIdx.x;
   const int g1 = p.gamma + 1;
   const int nstat = p.nstat;
-  const int nrows = g1 * nstat;
+  const int j0 = p.j0, nj = p.nj;
+  const int nrows = nj * nstat;  // statistics of this window
   const int n = p.n;
   const double log2e = (double)p.scale;  // log2(e) / T, the same constant the streaming kernel used
 
-  // 1. combine the chunk partials of every (position, statistic) in float64
+  // 1. combine the chunk partials of every (position, statistic) of the window in float64
   if (tid < nrows) {
-    const Partial* pp = p.partials + ((size_t)b * nrows + tid) * p.S;
+    const Partial* pp = p.partials + (((size_t)b * g1 + j0) * nstat + tid) * p.S;
     int omax = kNoOffset;
     for (int s = 0; s < p.S; ++s) {
       const double z = load_agent(&pp[s].Z);
@@ -540,18 +548,19 @@ __device__ void decide_sequence(const Params& p, int b, DecideShared& sh) {
     }
     sh.lse2[tid] = (zsum > 0.0) ? (double)omax + log2(zsum) : -INFINITY;
   }
-  if (CONTRASTIVE && tid < g1) {
+  if (CONTRASTIVE && tid < nj) {
     // written by the row-max kernel, an earlier launch on the same stream
-    const float* rm = p.rowmax + ((size_t)b * g1 + tid) * p.S;
+    const float* rm = p.rowmax + ((size_t)b * g1 + j0 + tid) * p.S;
     float m0 = -INFINITY;
     for (int s = 0; s < p.S; ++s) m0 = fmaxf(m0, rm[s]);
     sh.rowmax[tid] = m0;
   }
   __syncthreads();
 
-  // 2. Eq. (6) for every draft position, in float64
-  if (tid < p.gamma) {
-    const int j = tid;
+  // 2. Eq. (6) for every draft position of the window, in float64
+  const int ndraft = min(j0 + nj, p.gamma) - j0;  // draft positions in the window
+  if (tid < ndraft) {
+    const int jj = tid, j = j0 + tid;
     const size_t k = (size_t)b * p.gamma + j;
     const int d = p.draft[k];
     const int pi = p.proposer_pos ? p.proposer_pos[k] : p.proposer[b];
@@ -559,17 +568,17 @@ __device__ void decide_sequence(const Params& p, int b, DecideShared& sh) {
     if constexpr (!CONTRASTIVE) {
       for (int m = 0; m < n; ++m) {
         const double l = (double)widen(row_ptr<T>(p, m, b, j)[d]);
-        const double s = exp2(l * log2e - sh.lse2[j * nstat + m]);
+        const double s = exp2(l * log2e - sh.lse2[jj * nstat + m]);
         rd += p.w[m] * s;
         if (m == pi) qd = s;
       }
     } else {
       const double l0 = (double)widen(row_ptr<T>(p, 0, b, j)[d]);
       const double l1 = (double)widen(row_ptr<T>(p, 1, b, j)[d]);
-      const bool in = (l0 > -INFINITY) && (l0 - (double)sh.rowmax[j] >= p.thr64);
+      const bool in = (l0 > -INFINITY) && (l0 - (double)sh.rowmax[jj] >= p.thr64);
       const double c = l0 - p.w[0] * l1;
-      rd = in ? exp2(c * log2e - sh.lse2[j * nstat + 2]) : 0.0;
-      qd = exp2((pi ? l1 : l0) * log2e - sh.lse2[j * nstat + pi]);
+      rd = in ? exp2(c * log2e - sh.lse2[jj * nstat + 2]) : 0.0;
+      qd = exp2((pi ? l1 : l0) * log2e - sh.lse2[jj * nstat + pi]);
     }
     double ratio;
     if (!(rd > 0.0))
@@ -579,16 +588,23 @@ __device__ void decide_sequence(const Params& p, int b, DecideShared& sh) {
     else
       ratio = rd / qd;
     const double bound = ratio < 1.0 ? ratio : 1.0;
-    sh.accept[j] = p.u_accept[k] < bound;
+    sh.accept[jj] = p.u_accept[k] < bound;
     if (p.diag.r_at_draft) p.diag.r_at_draft[k] = rd;
     if (p.diag.q_at_draft) p.diag.q_at_draft[k] = qd;
   }
   __syncthreads();
+  if (p.alpha) {
+    if (tid < nrows) p.lse_all[((size_t)b * g1 + j0) * nstat + tid] = sh.lse2[tid];
+    if (CONTRASTIVE && tid < nj) p.rowmax_all[(size_t)b * g1 + j0 + tid] = sh.rowmax[tid];
+  }
 
-  // 3. first rejection (Sec. 3.1); the drawn token's slot is filled by the sampling kernel
-  int jstar = p.gamma;
-  for (int j = p.gamma - 1; j >= 0; --j)
-    if (!sh.accept[j]) jstar = j;
+  // 3. first rejection (Sec. 3.1) inside the window; -1: none, and the bonus position is not in it
+  int jstar = (j0 + nj == g1) ? p.gamma : -1;
+  for (int jj = ndraft - 1; jj >= 0; --jj)
+    if (!sh.accept[jj]) jstar = j0 + jj;
+  if (jstar < 0) return;  // undecided: a later window continues
+
+  // the drawn token's slot is filled by the sampling kernel
   if (tid == 0) p.accepted_len[b] = jstar;
   if (tid < g1 && tid != jstar)
     p.out_tokens[(size_t)b * g1 + tid] = (tid < jstar) ? p.draft[(size_t)b * p.gamma + tid] : -1;
@@ -601,14 +617,10 @@ __device__ void decide_sequence(const Params& p, int b, DecideShared& sh) {
     plan->residual = residual;
     plan->pi = (residual && p.proposer_pos) ? p.proposer_pos[(size_t)b * p.gamma + jstar] : p.proposer[b];
     plan->bonus = (!residual && p.bonus_idx) ? p.bonus_idx[b] : -1;
-    plan->m0 = CONTRASTIVE ? sh.rowmax[jstar] : 0.0f;
+    plan->m0 = CONTRASTIVE ? sh.rowmax[jstar - j0] : 0.0f;
     plan->pad = 0;
   }
-  if (tid < nstat) plan->lse2[tid] = sh.lse2[jstar * nstat + tid];
-  if (p.alpha) {
-    if (tid < nrows) p.lse_all[(size_t)b * nrows + tid] = sh.lse2[tid];
-    if (CONTRASTIVE && tid < g1) p.rowmax_all[(size_t)b * g1 + tid] = sh.rowmax[tid];
-  }
+  if (tid < nstat) plan->lse2[tid] = sh.lse2[(jstar - j0) * nstat + tid];
 }
 
 // ---------------------------------------------------------------------------
@@ -864,9 +876,11 @@ __device__ bool draw_token(const Params& p, int b, const SeqPlan& plan, const T*
 // kernels
 // ---------------------------------------------------------------------------
 
-__global__ void __launch_bounds__(kThreads) fill_zero_kernel(int* dst, int count) {
+// Zeroes the arrival counters and marks every sequence undecided.
+__global__ void __launch_bounds__(kThreads) fill_zero_kernel(int* dst, int count, SeqPlan* plans, int B) {
   const int i = blockIdx.x * kThreads + threadIdx.x;
   if (i < count) dst[i] = 0;
+  if (i < B) plans[i].jstar = -1;
 }
 
 // Ensemble streaming kernel.  Workgroup index -> (b, j, m, s), b slowest.
@@ -877,11 +891,13 @@ __global__ void __launch_bounds__(kThreads) ensemble_stats_kernel(Params p) {
   __shared__ int s_flag;
 
   const int g1 = p.gamma + 1;
-  const int per_b = g1 * p.n * p.S;
+  const int per_b = p.nj * p.n * p.S;
   const int b = blockIdx.x / per_b;
+  if (p.plans[b].jstar >= 0) return;  // decided by an earlier window: nothing more is read
   int rem = blockIdx.x - b * per_b;
-  const int j = rem / (p.n * p.S);
-  rem -= j * p.n * p.S;
+  const int jj = rem / (p.n * p.S);
+  rem -= jj * p.n * p.S;
+  const int j = p.j0 + jj;
   const int m = rem / p.S;
   const int s = rem - m * p.S;
 
@@ -908,7 +924,8 @@ __global__ void __launch_bounds__(kThreads) ensemble_stats_kernel(Params p) {
       wait_stores();
     }
   }
-  if (arrive_last(p.counters + (size_t)b * kCtrStride, per_b, &s_flag)) decide_sequence<T, false>(p, b, sh);
+  if (arrive_last(p.counters + ((size_t)p.win * p.B + b) * kCtrStride, per_b, &s_flag))
+    decide_sequence<T, false>(p, b, sh);
 }
 
 // Contrastive, kernel 1: partial maxima of the expert row (model 0).
@@ -918,9 +935,11 @@ __global__ void __launch_bounds__(kThreads) expert_rowmax_kernel(Params p) {
   constexpr int kStep = kThreads * kUnroll;
   __shared__ float wmax[kWaves];
   const int g1 = p.gamma + 1;
-  const int rs = blockIdx.x / p.S;  // b * g1 + j
-  const int s = blockIdx.x - rs * p.S;
-  const int b = rs / g1, j = rs - b * g1;
+  const int ws = blockIdx.x / p.S;  // b * nj + jj
+  const int s = blockIdx.x - ws * p.S;
+  const int b = ws / p.nj, j = p.j0 + (ws - b * p.nj);
+  if (p.plans[b].jstar >= 0) return;  // decided by an earlier window
+  const int rs = b * g1 + j;
   const T* row = row_ptr<T>(p, 0, b, j);
   const int v0 = s * p.cv;
   const int v1 = min(v0 + p.cv, p.nvec);
@@ -960,11 +979,12 @@ __global__ void __launch_bounds__(kThreads) contrastive_stats_kernel(Params p) {
   __shared__ float s_m0[kWaves];
 
   const int g1 = p.gamma + 1;
-  const int per_b = g1 * p.S;
+  const int per_b = p.nj * p.S;
   const int b = blockIdx.x / per_b;
+  if (p.plans[b].jstar >= 0) return;  // decided by an earlier window: nothing more is read
   int rem = blockIdx.x - b * per_b;
-  const int j = rem / p.S;
-  const int s = rem - j * p.S;
+  const int j = p.j0 + rem / p.S;
+  const int s = rem - (j - p.j0) * p.S;
   const int tid = threadIdx.x;
   // Whose softmax statistic this position needs: the proposer's at a draft
   // position; at the bonus position only a verifier bonus needs one at all.
@@ -1033,7 +1053,8 @@ __global__ void __launch_bounds__(kThreads) contrastive_stats_kernel(Params p) {
     store_partial(ws, 1, out + (size_t)2 * p.S + s);
     wait_stores();
   }
-  if (arrive_last(p.counters + (size_t)b * kCtrStride, per_b, &s_flag)) decide_sequence<T, true>(p, b, sh);
+  if (arrive_last(p.counters + ((size_t)p.win * p.B + b) * kCtrStride, per_b, &s_flag))
+    decide_sequence<T, true>(p, b, sh);
 }
 
 // Sampling kernel.  Workgroup index -> (b, c): tiles [c*tpc, (c+1)*tpc) of the
@@ -1082,7 +1103,7 @@ __global__ void __launch_bounds__(kThreads) sample_kernel(Params p) {
   // publish this workgroup's tile sums with coalesced write-through stores
   for (int i = threadIdx.x; i < te - tb; i += kThreads) store_agent(sums + tb + i, tile_sum[i]);
   wait_stores();
-  if (!arrive_last(p.counters + (size_t)(p.B + b) * kCtrStride, p.C, &s_flag)) return;
+  if (!arrive_last(p.counters + ((size_t)(p.gamma + 1) * p.B + b) * kCtrStride, p.C, &s_flag)) return;
 
   // last workgroup of this sequence: all tile sums are published
   for (int t = threadIdx.x; t < p.ntiles; t += kThreads) tile_sum[t] = load_agent(sums + t);
@@ -1195,7 +1216,7 @@ __global__ void __launch_bounds__(kThreads) acceptance_rate_kernel(Params p) {
     store_agent(parts + c, tot);
     wait_stores();
   }
-  int* counter = p.counters + ((size_t)2 * p.B + (size_t)b * p.gamma + j) * kCtrStride;
+  int* counter = p.counters + ((size_t)(p.gamma + 2) * p.B + (size_t)b * p.gamma + j) * kCtrStride;
   if (!arrive_last(counter, p.CA, &s_flag)) return;
   if (threadIdx.x == 0) {
     double tot = 0.0;
@@ -1241,7 +1262,7 @@ void plan_layout(int n, int B, int gamma, int V, cos_dtype_t dt, cos_combine_t m
   const size_t g1 = (size_t)gamma + 1;
   size_t at = 0;
   pl->off_counters = at;
-  at += align_up(((size_t)2 * B + (size_t)B * gamma) * kCtrStride * sizeof(int), 256);
+  at += align_up(((size_t)(gamma + 2) * B + (size_t)B * gamma) * kCtrStride * sizeof(int), 256);
   pl->off_plans = at;
   at += align_up((size_t)B * sizeof(SeqPlan), 256);
   pl->off_tiles = at;
@@ -1344,32 +1365,36 @@ cos_status_t launch_acceptance_rate(const Params& p, hipStream_t st) {
   return hipGetLastError() == hipSuccess ? COS_OK : COS_ERR_LAUNCH;
 }
 
+// All launches of one call after the fill kernel.  `window` positions are
+// verified per streaming launch; sequences decided by an earlier window are
+// skipped by every later one (their workgroups return at once).
 template <typename T, bool ALIGNED>
-cos_status_t launch_all(const Params& p, bool contrastive, size_t lds, hipStream_t st,
+cos_status_t launch_all(Params p, bool contrastive, int window, size_t lds, hipStream_t st,
                         hipEvent_t ev_start, hipEvent_t ev_stop) {
   const dim3 block(kThreads);
-  if (!contrastive) {
-    const long blocks = (long)p.B * (p.gamma + 1) * p.n * p.S;
-    if (blocks <= 0 || blocks > 0x7fffffffL) return COS_ERR_SHAPE;
-    if (ev_start) (void)hipEventRecord(ev_start, st);
-    hipLaunchKernelGGL((ensemble_stats_kernel<T, ALIGNED>), dim3((unsigned)blocks), block, 0, st, p);
-    if (ev_stop) (void)hipEventRecord(ev_stop, st);
-    if (hipGetLastError() != hipSuccess) return COS_ERR_LAUNCH;
-    const cos_status_t rc = launch_sampling<T, ALIGNED, false>(p, lds, st);
-    if (rc != COS_OK || !p.alpha) return rc;
-    return launch_acceptance_rate<T, ALIGNED, false>(p, st);
-  }
-  const long blocks = (long)p.B * (p.gamma + 1) * p.S;
-  if (blocks <= 0 || blocks > 0x7fffffffL) return COS_ERR_SHAPE;
-  hipLaunchKernelGGL((expert_rowmax_kernel<T, ALIGNED>), dim3((unsigned)blocks), block, 0, st, p);
-  if (hipGetLastError() != hipSuccess) return COS_ERR_LAUNCH;
+  const int g1 = p.gamma + 1;
   if (ev_start) (void)hipEventRecord(ev_start, st);
-  hipLaunchKernelGGL((contrastive_stats_kernel<T, ALIGNED>), dim3((unsigned)blocks), block, 0, st, p);
+  p.win = 0;
+  for (int j0 = 0; j0 < g1; j0 += window, ++p.win) {
+    p.j0 = j0;
+    p.nj = (j0 + window <= g1) ? window : g1 - j0;
+    const long blocks = (long)p.B * p.nj * (contrastive ? 1 : p.n) * p.S;
+    if (blocks <= 0 || blocks > 0x7fffffffL) return COS_ERR_SHAPE;
+    const dim3 grid((unsigned)blocks);
+    if (!contrastive) {
+      hipLaunchKernelGGL((ensemble_stats_kernel<T, ALIGNED>), grid, block, 0, st, p);
+    } else {
+      hipLaunchKernelGGL((expert_rowmax_kernel<T, ALIGNED>), grid, block, 0, st, p);
+      hipLaunchKernelGGL((contrastive_stats_kernel<T, ALIGNED>), grid, block, 0, st, p);
+    }
+    if (hipGetLastError() != hipSuccess) return COS_ERR_LAUNCH;
+  }
   if (ev_stop) (void)hipEventRecord(ev_stop, st);
-  if (hipGetLastError() != hipSuccess) return COS_ERR_LAUNCH;
-  const cos_status_t rc = launch_sampling<T, ALIGNED, true>(p, lds, st);
+  cos_status_t rc = contrastive ? launch_sampling<T, ALIGNED, true>(p, lds, st)
+                                : launch_sampling<T, ALIGNED, false>(p, lds, st);
   if (rc != COS_OK || !p.alpha) return rc;
-  return launch_acceptance_rate<T, ALIGNED, true>(p, st);
+  return contrastive ? launch_acceptance_rate<T, ALIGNED, true>(p, st)
+                     : launch_acceptance_rate<T, ALIGNED, false>(p, st);
 }
 
 }  // namespace
@@ -1411,6 +1436,10 @@ cos_status_t cos_verify_ex(const void* logits, cos_dtype_t dt, int n, int B, int
     if (options->struct_bytes != sizeof(cos_options_t)) return COS_ERR_UNSUPPORTED;
     if (!(options->temperature >= 0.0) || !std::isfinite(options->temperature)) return COS_ERR_WEIGHTS;
     if (options->temperature > 0.0) temperature = options->temperature;
+    if (options->stop_window < 0) return COS_ERR_SHAPE;
+    // acceptance rates of positions that were never read do not exist
+    if (options->stop_window > 0 && options->stop_window <= gamma && options->alpha)
+      return COS_ERR_UNSUPPORTED;
   }
   if (!shape_ok(n, B, gamma, V)) return COS_ERR_SHAPE;
   if (dt != COS_DTYPE_F32 && dt != COS_DTYPE_BF16) return COS_ERR_DTYPE;
@@ -1444,7 +1473,9 @@ cos_status_t cos_verify_ex(const void* logits, cos_dtype_t dt, int n, int B, int
   // ---- launch plan ----
   const int N = dt == COS_DTYPE_F32 ? 4 : 8;
   const int nvec = (V + N - 1) / N;
-  const int rows_total = (contrastive ? 1 : n) * B * (gamma + 1);
+  int window = gamma + 1;  // positions per streaming launch
+  if (options && options->stop_window > 0 && options->stop_window < window) window = options->stop_window;
+  const int rows_total = (contrastive ? 1 : n) * B * window;
   int S, cv;
   choose_split(rows_total, nvec, &S, &cv);
   Plan pl;
@@ -1523,18 +1554,21 @@ cos_status_t cos_verify_ex(const void* logits, cos_dtype_t dt, int n, int B, int
   hipEvent_t ev_start = profile ? g_ev_start[slot] : nullptr;
   hipEvent_t ev_stop = profile ? g_ev_stop[slot] : nullptr;
 
-  const int nctr = (2 * B + B * gamma) * kCtrStride;
+  // counters in use: one set per window, the sampling set, and the acceptance-rate set if wanted
+  const int nwin = (gamma + 1 + window - 1) / window;
+  const int nctr = ((p.alpha ? 2 * gamma + 2 : gamma + 2) * B) * kCtrStride;
+  (void)nwin;
   hipLaunchKernelGGL(fill_zero_kernel, dim3((nctr + kThreads - 1) / kThreads), dim3(kThreads), 0, st,
-                     p.counters, nctr);
+                     p.counters, nctr, p.plans, B);
   if (hipGetLastError() != hipSuccess) return COS_ERR_LAUNCH;
 
   cos_status_t rc;
   if (dt == COS_DTYPE_F32)
-    rc = aligned ? launch_all<float, true>(p, contrastive, lds, st, ev_start, ev_stop)
-                 : launch_all<float, false>(p, contrastive, lds, st, ev_start, ev_stop);
+    rc = aligned ? launch_all<float, true>(p, contrastive, window, lds, st, ev_start, ev_stop)
+                 : launch_all<float, false>(p, contrastive, window, lds, st, ev_start, ev_stop);
   else
-    rc = aligned ? launch_all<uint16_t, true>(p, contrastive, lds, st, ev_start, ev_stop)
-                 : launch_all<uint16_t, false>(p, contrastive, lds, st, ev_start, ev_stop);
+    rc = aligned ? launch_all<uint16_t, true>(p, contrastive, window, lds, st, ev_start, ev_stop)
+                 : launch_all<uint16_t, false>(p, contrastive, window, lds, st, ev_start, ev_stop);
   if (profile) ++g_ev_recorded;
   return rc;
 }

@@ -56,7 +56,7 @@ def oracle_dtype(logits: torch.Tensor) -> int:
 def _gpu_ext(inp):
     """Extensions of the step carried in the input dict (all optional)."""
     return {"temperature": float(inp.get("temperature", 1.0)), "bonus_idx": inp.get("bonus_idx"),
-            "proposer_pos": inp.get("proposer_pos")}
+            "proposer_pos": inp.get("proposer_pos"), "stop_window": int(inp.get("stop_window", 0))}
 
 
 def run_gpu(inp: Dict[str, torch.Tensor], mode: int, weights: Sequence[float], with_diag: bool = True):
@@ -129,8 +129,14 @@ def compare(inp: Dict[str, torch.Tensor], mode: int, weights: Sequence[float], g
     if diag is not None:
         gr = diag.r_at_draft.cpu().numpy()[idx]
         gq = diag.q_at_draft.cpu().numpy()[idx]
-        rep.max_rel_err_r = _rel_err(gr, ora.r_at_draft)
-        rep.max_rel_err_q = _rel_err(gq, ora.q_at_draft)
+        want_r, want_q = ora.r_at_draft, ora.q_at_draft
+        w = int(inp.get("stop_window", 0))
+        if 0 < w <= gamma:
+            # only the windows up to the one holding the first rejection are read
+            read = np.arange(gamma)[None, :] < ((np.minimum(g_alen, ora.accepted_len) // w + 1) * w)[:, None]
+            gr, gq, want_r, want_q = gr[read], gq[read], want_r[read], want_q[read]
+        rep.max_rel_err_r = _rel_err(gr, want_r)
+        rep.max_rel_err_q = _rel_err(gq, want_q)
         if rep.max_rel_err_r > PROB_RTOL:
             rep.failures.append(f"r(d) relative error {rep.max_rel_err_r:.3e} > {PROB_RTOL}")
         if rep.max_rel_err_q > PROB_RTOL:

@@ -151,3 +151,62 @@ def test_acceptance_rate_full_c4_shape():
                    inp["proposer_idx"].cpu().numpy(), w.mode, list(w.weights), inp["u_accept"].cpu().numpy(),
                    inp["u_resample"].cpu().numpy(), all_positions=True, want_alpha=True)
     assert np.abs(alpha.cpu().numpy() - ora.alpha).max() < 1e-6
+
+
+# ---------------------------------------------------------------------------
+# stop_window: verify w positions per launch, never read past the first rejection
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("window", [1, 2, 3, 5])
+@pytest.mark.parametrize("name", ["c1", "c2", "c3", "c4", "c5"])
+def test_stop_window_equals_the_one_launch_step(name, window):
+    w = W.WORKLOADS[name]
+    w = w.scaled(B=min(w.B, 12))
+    inp = W.generate(w, device="cuda")
+    base = P.run_gpu(inp, w.mode, w.weights)
+    inp["stop_window"] = window
+    alen, toks, diag, _ = _check(f"{name} stop_window={window}", inp, w.mode, w.weights)
+    assert np.array_equal(alen, base[0]) and np.array_equal(toks, base[1])
+
+
+@pytest.mark.parametrize("mode,weights,n", [(C.COS_COMBINE_ENSEMBLE, [0.2, 0.5, 0.3], 3),
+                                            (C.COS_COMBINE_CONTRASTIVE, [0.3, 0.05], 2)])
+def test_stop_window_never_reads_past_the_first_rejection(mode, weights, n):
+    B, gamma, V = 32, 5, 8200
+    inp = _random_inputs(n, B, gamma, V, "bf16", seed=61 + n, std=1.5)
+    if mode == C.COS_COMBINE_CONTRASTIVE:
+        # drafts at the expert's argmax are accepted, random ones are outside the mask: mix them so
+        # that every accepted length occurs
+        top = inp["logits"][0, :, :gamma].float().argmax(-1).to(torch.int32)
+        cut = (torch.arange(B, device="cuda") % (gamma + 1))[:, None]
+        keep = torch.arange(gamma, device="cuda")[None, :] < cut
+        inp["draft_tokens"] = torch.where(keep, top, inp["draft_tokens"]).contiguous()
+        inp["proposer_idx"][:] = 0
+    base_alen, base_toks, _ = P.run_gpu(inp, mode, weights)
+    assert len(set(base_alen.tolist())) >= 3
+    for window in (1, 2):
+        poisoned = dict(inp)
+        poisoned["logits"] = inp["logits"].clone()
+        for b in range(B):
+            first_unread = (int(base_alen[b]) // window + 1) * window
+            if first_unread <= gamma:
+                poisoned["logits"][:, b, first_unread:] = float("nan")
+        poisoned["stop_window"] = window
+        alen, toks, _ = P.run_gpu(poisoned, mode, weights)
+        assert np.array_equal(alen, base_alen) and np.array_equal(toks, base_toks), window
+
+
+def test_stop_window_with_other_extensions():
+    w = W.C5.scaled(B=16)
+    inp = W.generate(w, device="cuda")
+    g = torch.Generator().manual_seed(3)
+    inp["temperature"] = 0.8
+    inp["proposer_pos"] = torch.randint(0, w.n, (w.B, w.gamma), generator=g, dtype=torch.int32).cuda()
+    inp["bonus_idx"] = torch.randint(-1, w.n, (w.B,), generator=g, dtype=torch.int32).cuda()
+    inp["u_accept"][::3] = 0.0
+    inp["stop_window"] = 2
+    _check("c5 B=16, window 2, every extension", inp, w.mode, w.weights)
+    alpha = torch.empty((w.B, w.gamma), dtype=torch.float64, device="cuda")
+    with pytest.raises(C.CosVerifyError):     # acceptance rates of unread positions do not exist
+        C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], w.mode, w.weights,
+                     inp["u_accept"], inp["u_resample"], alpha=alpha, stop_window=2)
