@@ -181,6 +181,7 @@ cos_status_t cos_profile_kernel_ms(int index, float *ms);
  * Tuning knob for experiments: vectors (16-byte units) of one logit row that
  * one workgroup of the streaming kernel reduces.  0 restores the built-in
  * heuristic.  Process-wide; results do not depend on it beyond rounding order.
+ * cos_verify_workspace_bytes() depends on it: size the workspace after setting it.
  */
 void cos_tune_set_chunk_vectors(int vectors);
 

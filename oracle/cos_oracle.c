@@ -31,6 +31,10 @@
  *                      sum_{x<=k} f(x) > u*F  (the paper names only the
  *                      distribution; the procedure is this build's)
  *
+ *   extensions         cos_oracle_verify_ex: temperature (Sec. 4.1), the
+ *                      verifier's own bonus token (Sec. 3.1 / 3.3), a proposer
+ *                      per draft position (Alg. 2), the acceptance rate of Eq. (7)
+ *
  * Everything is float64; sums run in ascending index order; nothing is
  * blocked, fused or reordered.
  *
@@ -39,7 +43,10 @@
  * Monte Carlo, r == q => all accepted, residual mass = 1 - sum min(q, r) =
  * (1/2) sum |r - q|, Thm 3.2 (alpha >= lambda), lambda = 0 => textbook
  * speculative sampling, P(accepted_len >= k) = prod alpha_j, E[#tokens] of
- * App. A.2, brute-force inverse CDF.  No function here is "parity unpinned".
+ * App. A.2, brute-force inverse CDF; extensions (tests/test_oracle_extension_pins.py):
+ * scipy softmax of l/T and exactly pre-scaled logits, the bonus law s_v by
+ * searchsorted and chi-square, an independent per-position re-derivation, the
+ * hand value 13/16 and Eq. (7) for alpha.  No function here is "parity unpinned".
  */
 #include <math.h>
 #include <stdint.h>

@@ -18,6 +18,11 @@
 // Contrastive mode (Eq. (5) with a plausibility mask) needs the expert row's
 // maximum before anything can be masked, so a row-max kernel runs first.
 //
+// Extensions (cos_verify_ex): temperature, the verifier's own bonus token
+// (Sec. 3.3), per-position proposers (Alg. 2), the acceptance rates of Eq. (7)
+// (one more kernel), and a position window per streaming launch so that logits
+// after a sequence's first rejection are never read.
+//
 // Numerics: per-element work is float32 (v_exp_f32); all offsets are integers
 // in the log2 domain so that rescaling is exact; every cross-lane, cross-wave
 // and cross-workgroup combine, r(d), q(d), the accept decision, tile sums, the
@@ -48,9 +53,9 @@ constexpr int kMaxStatsPerSeq = 256;        // (gamma+1) * statistics per positi
 constexpr int kMaxTiles = 4096;             // tiles per row the final scan can hold in LDS
 constexpr int kMaxAlphaBlocks = 64;         // acceptance-rate workgroups per (sequence, position)
 // Arrival counters are agent-scope atomics executed at the memory side; one
-// counter per 256 bytes spreads them over the memory channels (packed counters
-// serialise on one channel and slow every stream that crosses it).
-constexpr int kCtrStride = 64;  // ints between two counters
+// counter per 128-byte line spreads them over the memory channels (packed
+// counters serialise on one channel and slow every stream that crosses it).
+constexpr int kCtrStride = 32;  // ints between two counters (one 128-byte line each)
 
 // One partial softmax statistic: Z = sum_x 2^(l(x)*log2e - o) over a chunk.
 struct Partial {
@@ -1252,6 +1257,8 @@ bool shape_ok(int n, int B, int gamma, int V) {
          V >= 1 && V <= COS_MAX_VOCAB;
 }
 
+int alpha_blocks(int B, int gamma, int ntiles);
+
 // Workspace layout for S chunks per row.
 void plan_layout(int n, int B, int gamma, int V, cos_dtype_t dt, cos_combine_t mode, int S,
                  Plan* pl) {
@@ -1272,7 +1279,7 @@ void plan_layout(int n, int B, int gamma, int V, cos_dtype_t dt, cos_combine_t m
   pl->off_rowmax_all = at;
   at += align_up((size_t)B * g1 * sizeof(float), 256);
   pl->off_alpha_partials = at;
-  at += align_up((size_t)B * gamma * kMaxAlphaBlocks * sizeof(double), 256);
+  at += align_up((size_t)B * gamma * alpha_blocks(B, gamma, pl->ntiles) * sizeof(double), 256);
   pl->off_rowmax = at;
   if (mode == COS_COMBINE_CONTRASTIVE) at += align_up((size_t)B * g1 * S * sizeof(float), 256);
   pl->off_partials = at;
@@ -1309,6 +1316,17 @@ void choose_split(int rows_total, int nvec, int* S_out, int* cv_out) {
   }
   *S_out = S;
   *cv_out = cv;
+}
+
+// Acceptance-rate workgroups per (sequence, position): about 4096 in total, at
+// least 4 tiles each, at most kMaxAlphaBlocks.
+int alpha_blocks(int B, int gamma, int ntiles) {
+  long ca = (4096 + (long)B * gamma - 1) / ((long)B * gamma > 0 ? (long)B * gamma : 1);
+  const int cmax = (ntiles + 3) / 4;
+  if (ca > cmax) ca = cmax;
+  if (ca > kMaxAlphaBlocks) ca = kMaxAlphaBlocks;
+  if (ca < 1) ca = 1;
+  return (int)ca;
 }
 
 // Sampling workgroups per sequence: about 2048 in total, at least 4 tiles each.
@@ -1406,9 +1424,12 @@ size_t cos_verify_workspace_bytes(int n, int B, int gamma, int V, cos_dtype_t dt
   if (!shape_ok(n, B, gamma, V)) return 0;
   if (dt != COS_DTYPE_F32 && dt != COS_DTYPE_BF16) return 0;
   if (mode != COS_COMBINE_ENSEMBLE && mode != COS_COMBINE_CONTRASTIVE) return 0;
+  // Sized for one-position windows (stop_window = 1), which split rows the most.
   Plan pl;
   const int N = dt == COS_DTYPE_F32 ? 4 : 8;
-  plan_layout(n, B, gamma, V, dt, mode, max_splits((V + N - 1) / N), &pl);
+  int S, cv;
+  choose_split((mode == COS_COMBINE_CONTRASTIVE ? 1 : n) * (B > 0 ? B : 1), (V + N - 1) / N, &S, &cv);
+  plan_layout(n, B, gamma, V, dt, mode, S, &pl);
   return pl.bytes < 256 ? 256 : pl.bytes;
 }
 
@@ -1507,14 +1528,9 @@ cos_status_t cos_verify_ex(const void* logits, cos_dtype_t dt, int n, int B, int
   p.rowmax_all = reinterpret_cast<float*>(wsb + pl.off_rowmax_all);
   p.alpha_partials = reinterpret_cast<double*>(wsb + pl.off_alpha_partials);
   {
-    // about 4096 acceptance-rate workgroups in total, at least 4 tiles each
-    long ca = (4096 + (long)B * gamma - 1) / ((long)B * gamma);
-    const int cmax = (pl.ntiles + 3) / 4;
-    if (ca > cmax) ca = cmax;
-    if (ca > kMaxAlphaBlocks) ca = kMaxAlphaBlocks;
-    if (ca < 1) ca = 1;
-    p.tpa = (pl.ntiles + (int)ca - 1) / (int)ca;
-    p.CA = (pl.ntiles + p.tpa - 1) / p.tpa;
+    const int ca = alpha_blocks(B, gamma, pl.ntiles);
+    p.tpa = (pl.ntiles + ca - 1) / ca;
+    p.CA = (pl.ntiles + p.tpa - 1) / p.tpa;  // <= ca
   }
   p.S = S;
   p.cv = cv;
@@ -1555,9 +1571,7 @@ cos_status_t cos_verify_ex(const void* logits, cos_dtype_t dt, int n, int B, int
   hipEvent_t ev_stop = profile ? g_ev_stop[slot] : nullptr;
 
   // counters in use: one set per window, the sampling set, and the acceptance-rate set if wanted
-  const int nwin = (gamma + 1 + window - 1) / window;
   const int nctr = ((p.alpha ? 2 * gamma + 2 : gamma + 2) * B) * kCtrStride;
-  (void)nwin;
   hipLaunchKernelGGL(fill_zero_kernel, dim3((nctr + kThreads - 1) / kThreads), dim3(kThreads), 0, st,
                      p.counters, nctr, p.plans, B);
   if (hipGetLastError() != hipSuccess) return COS_ERR_LAUNCH;
