@@ -139,6 +139,16 @@ cos_status_t cos_verify(const void *logits, cos_dtype_t dt, int n, int B, int ga
  *               are identical; diag.r_at_draft / q_at_draft are written only
  *               for positions that were read; alpha must be NULL
  *               (COS_ERR_UNSUPPORTED).  Fewer bytes, more launches.
+ * greedy        non-zero: temperature 0 (the T = 0 runs of Sec. 4.1), contrastive
+ *               mode only.  Every softmax is one-hot, so r of Eq. (5) is one-hot
+ *               at a_j = argmax over the mask of l_0 - mu l_1 (ties to the lowest
+ *               index; the mask stays the temperature-1 one, l_0 - max l_0 >=
+ *               ln alpha_cd): draft d_j is accepted iff d_j == a_j, the token at
+ *               the first mismatch -- or the bonus token -- is a_j (with
+ *               bonus_idx[b] = v >= 0: the argmax of l_v alone).  u_accept,
+ *               u_resample, proposer_idx and temperature are not used; diag is
+ *               not written.  Bit-exact against a float64 reference.  Not
+ *               combinable with alpha, proposer_pos or stop_window.
  */
 typedef struct cos_options_t {
   size_t struct_bytes;
@@ -147,6 +157,7 @@ typedef struct cos_options_t {
   const int32_t *proposer_pos;
   double *alpha;
   int stop_window;
+  int greedy;
 } cos_options_t;
 
 /* cos_verify with extensions; options == NULL is exactly cos_verify. */

@@ -171,6 +171,41 @@ int cos_oracle_combine_contrastive(const double *l_p, const double *l_q,
   return count;
 }
 
+/* ---- temperature 0 (greedy decoding, the T = 0 runs of Sec. 4.1) ---------- */
+/* As T -> 0 a softmax becomes one-hot at its largest entry, so r of Eq. (5)
+ * is one-hot at argmax_x (l_p(x) - mu l_q(x)).  The plausibility mask is kept
+ * as defined at temperature 1 (l_p(x) - max l_p >= log(alpha_cd)): at T -> 0 it
+ * would shrink to the expert's argmax and the contrast would do nothing.  Ties
+ * go to the lowest index.  Returns the index, or -1 if the mask is empty
+ * (every expert logit -inf).                                                */
+int cos_oracle_argmax_contrastive(const double *l_p, const double *l_q, double mu,
+                                  double alpha_cd, int V) {
+  double Mp = l_p[0], thr, best = -INFINITY;
+  int x, arg = -1;
+  for (x = 1; x < V; ++x)
+    if (l_p[x] > Mp) Mp = l_p[x];
+  thr = (alpha_cd > 0.0) ? log(alpha_cd) : -INFINITY;
+  for (x = 0; x < V; ++x) {
+    int in = (l_p[x] > -INFINITY) && (l_p[x] - Mp >= thr);
+    if (in) {
+      double c = l_p[x] - mu * l_q[x];
+      if (arg < 0 || c > best) {
+        best = c;
+        arg = x;
+      }
+    }
+  }
+  return arg;
+}
+
+/* argmax of one row, ties to the lowest index */
+int cos_oracle_argmax(const double *l, int V) {
+  int x, arg = 0;
+  for (x = 1; x < V; ++x)
+    if (l[x] > l[arg]) arg = x;
+  return arg;
+}
+
 /* ---- Eq. (6): accept iff u < min(1, r(d)/q(d)) ------------------------- */
 /* q(d) = 0 and r(d) > 0 -> ratio = +inf (accept); r(d) = 0 -> ratio = 0
  * (reject, also when q(d) = 0).  Returns 1 = accept, writes the ratio.      */
@@ -436,6 +471,65 @@ int cos_oracle_verify_ex(const void *logits, int dtype, int n, int B, int gamma,
     free(s);
     free(r);
     free(f);
+  }
+  return failed ? ORACLE_ERR_NOMEM : ORACLE_OK;
+}
+
+/* ---- the step at temperature 0, contrastive mode ---------------------------
+ * r is one-hot at a_j = cos_oracle_argmax_contrastive of position j, so Eq. (6)
+ * accepts d_j iff d_j == a_j whatever q is (r(d) = 0 otherwise), the residual
+ * norm(max(0, r - q)) and its fall-back r are both one-hot at a_j, and the bonus
+ * token is a_gamma -- or, with bonus_idx[b] = v >= 0, the argmax of l_v alone
+ * (Sec. 3.3).  No random numbers are consumed.  weights = (mu, alpha_cd).    */
+int cos_oracle_verify_greedy(const void *logits, int dtype, int B, int gamma, int V,
+                             const int32_t *draft_tokens, const double *weights,
+                             const int32_t *bonus_idx, int32_t *accepted_len,
+                             int32_t *out_tokens, int num_threads) {
+  int b, failed = 0;
+  const int n = 2;
+  size_t esize;
+  if (!logits || !draft_tokens || !weights || !accepted_len || !out_tokens) return ORACLE_ERR_NULL;
+  if (B < 0 || gamma < 1 || V < 1) return ORACLE_ERR_SHAPE;
+  if (dtype != ORACLE_DTYPE_F32 && dtype != ORACLE_DTYPE_BF16) return ORACLE_ERR_DTYPE;
+  if (check_weights(ORACLE_CONTRASTIVE, n, weights) != ORACLE_OK) return ORACLE_ERR_WEIGHTS;
+  esize = dtype == ORACLE_DTYPE_F32 ? 4 : 2;
+#ifdef _OPENMP
+  if (num_threads > 0) omp_set_num_threads(num_threads);
+#endif
+#pragma omp parallel
+  {
+    double *l = (double *)malloc(sizeof(double) * (size_t)n * V);
+    if (!l) {
+#pragma omp atomic write
+      failed = 1;
+    }
+#pragma omp for schedule(dynamic, 1)
+    for (b = 0; b < B; ++b) {
+      int j, m, x, jstar = gamma, token = -1;
+      if (failed) continue;
+      for (j = 0; j <= gamma; ++j) {
+        const int v = (j == gamma && bonus_idx) ? bonus_idx[b] : -1;
+        int a;
+        for (m = 0; m < n; ++m) {
+          size_t row = ((size_t)m * B + b) * (size_t)(gamma + 1) + j;
+          if (v >= 0 && m != v) continue; /* not needed, not read */
+          cos_oracle_row_to_f64((const char *)logits + row * (size_t)V * esize, dtype, V,
+                                l + (size_t)m * V);
+        }
+        a = v >= 0 ? cos_oracle_argmax(l + (size_t)v * V, V)
+                   : cos_oracle_argmax_contrastive(l, l + V, weights[0], weights[1], V);
+        if (j < gamma && draft_tokens[(size_t)b * gamma + j] == a) continue; /* accepted */
+        jstar = j;
+        token = a;
+        break;
+      }
+      accepted_len[b] = jstar;
+      for (x = 0; x <= gamma; ++x) {
+        int32_t *o = out_tokens + (size_t)b * (gamma + 1) + x;
+        *o = x < jstar ? draft_tokens[(size_t)b * gamma + x] : (x == jstar ? token : -1);
+      }
+    }
+    free(l);
   }
   return failed ? ORACLE_ERR_NOMEM : ORACLE_OK;
 }

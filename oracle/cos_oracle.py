@@ -76,6 +76,12 @@ def _load():
         lib.cos_oracle_apply_temperature.restype = None
         lib.cos_oracle_acceptance_rate.argtypes = [dp, dp, ci]
         lib.cos_oracle_acceptance_rate.restype = ctypes.c_double
+        lib.cos_oracle_argmax_contrastive.argtypes = [dp, dp, ctypes.c_double, ctypes.c_double, ci]
+        lib.cos_oracle_argmax_contrastive.restype = ci
+        lib.cos_oracle_argmax.argtypes = [dp, ci]
+        lib.cos_oracle_argmax.restype = ci
+        lib.cos_oracle_verify_greedy.argtypes = [vp, ci, ci, ci, ci, ip, dp, ip, ip, ip, ci]
+        lib.cos_oracle_verify_greedy.restype = ci
         lib.cos_oracle_max_threads.argtypes = []
         lib.cos_oracle_max_threads.restype = ci
         _lib = lib
@@ -231,6 +237,30 @@ def verify(logits: np.ndarray, dtype: int, draft_tokens, proposer_idx, mode: int
         _dp(res.ratio), _dp(res.sample_mass), _dp(res.cdf_lo), _dp(res.cdf_hi), _ip(res.flags),
         int(all_positions), int(num_threads), ctypes.byref(opt))
     return res
+
+
+def argmax_contrastive(l_p, l_q, mu: float, alpha_cd: float) -> int:
+    l_p = _f64(l_p)
+    l_q = _f64(l_q)
+    return _load().cos_oracle_argmax_contrastive(_dp(l_p), _dp(l_q), mu, alpha_cd, l_p.shape[0])
+
+
+def verify_greedy(logits: np.ndarray, dtype: int, draft_tokens, weights, bonus_idx=None, num_threads: int = 0):
+    """Temperature-0 contrastive step; returns (status, accepted_len, out_tokens)."""
+    logits = np.ascontiguousarray(logits)
+    assert logits.ndim == 4 and logits.shape[0] == 2
+    assert logits.dtype == (np.float32 if dtype == DTYPE_F32 else np.uint16), logits.dtype
+    _, B, g1, V = logits.shape
+    gamma = g1 - 1
+    draft_tokens = np.ascontiguousarray(draft_tokens, dtype=np.int32).reshape(B, gamma)
+    weights = _f64(weights)
+    bi = None if bonus_idx is None else np.ascontiguousarray(bonus_idx, dtype=np.int32).reshape(B)
+    alen = np.full(B, -7, dtype=np.int32)
+    toks = np.full((B, gamma + 1), -7, dtype=np.int32)
+    st = _load().cos_oracle_verify_greedy(logits.ctypes.data_as(ctypes.c_void_p), dtype, B, gamma, V,
+                                          _ip(draft_tokens), _dp(weights), _ip(bi) if bi is not None else None,
+                                          _ip(alen), _ip(toks), int(num_threads))
+    return st, alen, toks
 
 
 def max_threads() -> int:

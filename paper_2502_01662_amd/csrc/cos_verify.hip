@@ -1136,6 +1136,133 @@ __global__ void __launch_bounds__(kThreads) sample_kernel(Params p) {
                                               COS_FLAG_RESIDUAL_FALLBACK);
 }
 
+// Temperature 0 (greedy), contrastive mode.  r of Eq. (5) is one-hot at the
+// masked argmax a_j of c = l_0 - mu l_1, so a draft is accepted iff d_j == a_j and
+// the token drawn at the first mismatch (or the bonus token) is a_j itself: one
+// streaming argmax per position, no sampling kernel, no random numbers.  c is
+// evaluated in float64 with a separate multiply and subtract so that every
+// comparison is the one a float64 reference makes; ties go to the lowest index.
+// Workgroup index -> (b, j, s).  With a verifier bonus the bonus position takes
+// the plain argmax of that model's row.
+struct ArgBest {
+  double val;
+  int idx;  // -1: nothing eligible seen
+};
+
+__device__ __forceinline__ void arg_better(ArgBest& a, double val, int idx) {
+  if (idx >= 0 && (a.idx < 0 || val > a.val || (val == a.val && idx < a.idx))) {
+    a.val = val;
+    a.idx = idx;
+  }
+}
+
+template <typename T, bool ALIGNED>
+__global__ void __launch_bounds__(kThreads) greedy_contrastive_kernel(Params p) {
+  constexpr int N = VecOf<T>::N;
+  constexpr int U = 4;
+  constexpr int kStep = kThreads * U;
+  __shared__ ArgBest wbest[kWaves];
+  __shared__ float s_m0[kWaves];
+  __shared__ int s_flag;
+  __shared__ int s_arg[COS_MAX_GAMMA + 1];
+
+  const int g1 = p.gamma + 1;
+  const int per_b = g1 * p.S;
+  const int b = blockIdx.x / per_b;
+  int rem = blockIdx.x - b * per_b;
+  const int j = rem / p.S;
+  const int s = rem - j * p.S;
+  const int tid = threadIdx.x;
+  const int plain = (j == p.gamma && p.bonus_idx) ? p.bonus_idx[b] : -1;
+  const double mu = p.w[0];
+
+  {
+    const float* rm = p.rowmax + ((size_t)b * g1 + j) * p.S;
+    float lm = -INFINITY;
+    for (int i = tid; i < p.S; i += kThreads) lm = fmaxf(lm, rm[i]);
+    const float wm = wave_max(lm);
+    if (lane_id() == 0) s_m0[tid >> 6] = wm;
+    __syncthreads();
+  }
+  float m0 = s_m0[0];
+  for (int w = 1; w < kWaves; ++w) m0 = fmaxf(m0, s_m0[w]);
+
+  const T* row0 = row_ptr<T>(p, 0, b, j);
+  const T* row1 = row_ptr<T>(p, 1, b, j);
+  const int v0 = s * p.cv;
+  const int v1 = min(v0 + p.cv, p.nvec);
+  ArgBest best;
+  best.val = 0.0;
+  best.idx = -1;
+  for (int base = v0; base < v1; base += kStep) {
+    float x0[U][N], x1[U][N];
+    if (base + kStep <= v1) {
+      load_group<T, ALIGNED, false, U>(row0, base, v1, p.V, x0);
+      load_group<T, ALIGNED, false, U>(row1, base, v1, p.V, x1);
+    } else {
+      load_group<T, ALIGNED, true, U>(row0, base, v1, p.V, x0);
+      load_group<T, ALIGNED, true, U>(row1, base, v1, p.V, x1);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int first = (base + u * kThreads + tid) * N;  // element index of x[u][0]
+#pragma unroll
+      for (int k = 0; k < N; ++k) {
+        double val;
+        bool ok;
+        if (plain >= 0) {
+          val = (double)(plain ? x1[u][k] : x0[u][k]);
+          ok = val > -INFINITY || (best.idx < 0 && val == -INFINITY);  // a row of -inf still has an argmax
+        } else {
+          ok = in_mask<T>(x0[u][k], m0, p.thr32, p.thr64);
+          const double prod = mu * (double)x1[u][k];
+          val = (double)x0[u][k] - prod;
+        }
+        if (ok && base + u * kThreads + tid < v1 && first + k < p.V && (best.idx < 0 || val > best.val)) {
+          best.val = val;
+          best.idx = first + k;
+        }
+      }
+    }
+  }
+  // wavefront, then workgroup
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) {
+    const double ov = __shfl_xor(best.val, d, 64);
+    const int oi = __shfl_xor(best.idx, d, 64);
+    arg_better(best, ov, oi);
+  }
+  if (lane_id() == 0) wbest[tid >> 6] = best;
+  __syncthreads();
+  if (tid == 0) {
+    ArgBest bb = wbest[0];
+    for (int w = 1; w < kWaves; ++w) arg_better(bb, wbest[w].val, wbest[w].idx);
+    Partial* out = p.partials + (((size_t)b * g1 + j) * p.nstat) * p.S + s;
+    store_agent(&out->Z, bb.val);
+    store_agent(&out->o, bb.idx);
+    wait_stores();
+  }
+  if (!arrive_last(p.counters + (size_t)b * kCtrStride, per_b, &s_flag)) return;
+
+  // last workgroup of the sequence: argmax of every position, first mismatch, outputs
+  if (tid < g1) {
+    const Partial* pp = p.partials + (((size_t)b * g1 + tid) * p.nstat) * p.S;
+    ArgBest bb;
+    bb.val = 0.0;
+    bb.idx = -1;
+    for (int i = 0; i < p.S; ++i) arg_better(bb, load_agent(&pp[i].Z), load_agent(&pp[i].o));
+    s_arg[tid] = bb.idx;
+  }
+  __syncthreads();
+  int jstar = p.gamma;
+  for (int jj = p.gamma - 1; jj >= 0; --jj)
+    if (p.draft[(size_t)b * p.gamma + jj] != s_arg[jj]) jstar = jj;
+  if (tid == 0) p.accepted_len[b] = jstar;
+  if (tid < g1)
+    p.out_tokens[(size_t)b * g1 + tid] =
+        tid < jstar ? p.draft[(size_t)b * p.gamma + tid] : (tid == jstar ? s_arg[jstar] : -1);
+}
+
 // Acceptance-rate kernel (optional): alpha = sum_x min(q(x), r(x)) of Eq. (7) for
 // every draft position.  Workgroup index -> (b, j, c); a second full read of the
 // draft positions' rows, with the normalisers the streaming kernel left behind.
@@ -1458,6 +1585,12 @@ cos_status_t cos_verify_ex(const void* logits, cos_dtype_t dt, int n, int B, int
     if (!(options->temperature >= 0.0) || !std::isfinite(options->temperature)) return COS_ERR_WEIGHTS;
     if (options->temperature > 0.0) temperature = options->temperature;
     if (options->stop_window < 0) return COS_ERR_SHAPE;
+    if (options->greedy) {
+      // temperature 0: built for the contrastive mode (the paper's T = 0 runs), whole step in one launch
+      if (combine_mode != COS_COMBINE_CONTRASTIVE || options->alpha || options->proposer_pos ||
+          (options->stop_window > 0 && options->stop_window <= gamma))
+        return COS_ERR_UNSUPPORTED;
+    }
     // acceptance rates of positions that were never read do not exist
     if (options->stop_window > 0 && options->stop_window <= gamma && options->alpha)
       return COS_ERR_UNSUPPORTED;
@@ -1575,6 +1708,38 @@ cos_status_t cos_verify_ex(const void* logits, cos_dtype_t dt, int n, int B, int
   hipLaunchKernelGGL(fill_zero_kernel, dim3((nctr + kThreads - 1) / kThreads), dim3(kThreads), 0, st,
                      p.counters, nctr, p.plans, B);
   if (hipGetLastError() != hipSuccess) return COS_ERR_LAUNCH;
+
+  if (options && options->greedy) {
+    p.j0 = 0;
+    p.nj = gamma + 1;
+    p.win = 0;
+    const long blocks = (long)B * (gamma + 1) * S;
+    if (blocks > 0x7fffffffL) return COS_ERR_SHAPE;
+    const dim3 grid((unsigned)blocks), block(kThreads);
+    if (profile) (void)hipEventRecord(ev_start, st);
+    if (dt == COS_DTYPE_F32) {
+      if (aligned) {
+        hipLaunchKernelGGL((expert_rowmax_kernel<float, true>), grid, block, 0, st, p);
+        hipLaunchKernelGGL((greedy_contrastive_kernel<float, true>), grid, block, 0, st, p);
+      } else {
+        hipLaunchKernelGGL((expert_rowmax_kernel<float, false>), grid, block, 0, st, p);
+        hipLaunchKernelGGL((greedy_contrastive_kernel<float, false>), grid, block, 0, st, p);
+      }
+    } else {
+      if (aligned) {
+        hipLaunchKernelGGL((expert_rowmax_kernel<uint16_t, true>), grid, block, 0, st, p);
+        hipLaunchKernelGGL((greedy_contrastive_kernel<uint16_t, true>), grid, block, 0, st, p);
+      } else {
+        hipLaunchKernelGGL((expert_rowmax_kernel<uint16_t, false>), grid, block, 0, st, p);
+        hipLaunchKernelGGL((greedy_contrastive_kernel<uint16_t, false>), grid, block, 0, st, p);
+      }
+    }
+    if (profile) {
+      (void)hipEventRecord(ev_stop, st);
+      ++g_ev_recorded;
+    }
+    return hipGetLastError() == hipSuccess ? COS_OK : COS_ERR_LAUNCH;
+  }
 
   cos_status_t rc;
   if (dt == COS_DTYPE_F32)

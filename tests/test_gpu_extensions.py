@@ -210,3 +210,63 @@ def test_stop_window_with_other_extensions():
     with pytest.raises(C.CosVerifyError):     # acceptance rates of unread positions do not exist
         C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], w.mode, w.weights,
                      inp["u_accept"], inp["u_resample"], alpha=alpha, stop_window=2)
+
+
+# ---------------------------------------------------------------------------
+# temperature 0 (greedy), contrastive mode: bit-exact, no near-tie excuses
+# ---------------------------------------------------------------------------
+
+def _greedy_inputs(B, gamma, V, dtype, seed, mu, alpha):
+    """Random logits; drafts follow the contrastive argmax on a prefix of varying length."""
+    from oracle import cos_oracle as O
+    inp = _random_inputs(2, B, gamma, V, dtype, seed=seed, std=2.0)
+    host = W.host_logits(inp["logits"])
+    odt = P.oracle_dtype(inp["logits"])
+    drafts = inp["draft_tokens"].cpu().numpy().copy()
+    for b in range(B):
+        for j in range(b % (gamma + 1)):
+            drafts[b, j] = O.argmax_contrastive(O.row_to_f64(host[0, b, j], odt), O.row_to_f64(host[1, b, j], odt), mu, alpha)
+    inp["draft_tokens"] = torch.from_numpy(drafts).cuda()
+    return inp, host, odt
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("B,gamma,V,mu,alpha", [(6, 2, 8, 0.5, 0.1), (12, 3, 1000, 0.1, 0.1), (8, 2, 4099, 0.5, 0.0),
+                                                (10, 4, 33000, 1.0, 0.5), (7, 3, 70001, 0.3, 1.0),
+                                                (16, 5, 128256, 0.5, 0.1)])
+def test_greedy_contrastive_is_bit_exact(dtype, B, gamma, V, mu, alpha):
+    from oracle import cos_oracle as O
+    inp, host, odt = _greedy_inputs(B, gamma, V, dtype, seed=V + B, mu=mu, alpha=alpha)
+    for bonus in (None, torch.tensor([(b % 3) - 1 for b in range(B)], dtype=torch.int32).cuda()):
+        alen, toks = C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], C.COS_COMBINE_CONTRASTIVE,
+                                  [mu, alpha], inp["u_accept"], inp["u_resample"], greedy=True, bonus_idx=bonus)
+        torch.cuda.synchronize()
+        st, want_len, want_toks = O.verify_greedy(host, odt, inp["draft_tokens"].cpu().numpy(), [mu, alpha],
+                                                  bonus_idx=None if bonus is None else bonus.cpu().numpy())
+        assert st == 0
+        assert np.array_equal(alen.cpu().numpy(), want_len)
+        assert np.array_equal(toks.cpu().numpy(), want_toks)
+        assert len(set(want_len.tolist())) == min(B, gamma + 1)
+
+
+def test_greedy_ties_go_to_the_lowest_index_and_unsupported_combinations():
+    from oracle import cos_oracle as O
+    B, gamma, V = 4, 2, 5000
+    inp = _random_inputs(2, B, gamma, V, "bf16", seed=3)
+    inp["logits"][:] = 0.0                                   # every token ties
+    inp["logits"][0, :, :, 4000] = 1.0
+    inp["logits"][0, :, :, 77] = 1.0                         # two maxima of c: the lower index wins
+    inp["draft_tokens"][:] = 77
+    alen, toks = C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], C.COS_COMBINE_CONTRASTIVE,
+                              [0.5, 0.0], inp["u_accept"], inp["u_resample"], greedy=True)
+    torch.cuda.synchronize()
+    assert np.all(alen.cpu().numpy() == gamma) and np.all(toks.cpu().numpy() == 77)
+    st, want_len, want_toks = O.verify_greedy(W.host_logits(inp["logits"]), O.DTYPE_BF16,
+                                              inp["draft_tokens"].cpu().numpy(), [0.5, 0.0])
+    assert np.array_equal(toks.cpu().numpy(), want_toks)
+    with pytest.raises(C.CosVerifyError):                    # greedy ensembles are not built
+        C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], C.COS_COMBINE_ENSEMBLE, [0.5, 0.5],
+                     inp["u_accept"], inp["u_resample"], greedy=True)
+    with pytest.raises(C.CosVerifyError):
+        C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], C.COS_COMBINE_CONTRASTIVE, [0.5, 0.0],
+                     inp["u_accept"], inp["u_resample"], greedy=True, stop_window=1)

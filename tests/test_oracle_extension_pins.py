@@ -167,3 +167,68 @@ def test_extension_argument_checks():
                     proposer_pos=np.full((4, 2), -1)).status == -2
     assert O.verify(logits, O.DTYPE_F32, drafts, proposer, O.ENSEMBLE, [0.5, 0.5], ua, ur,
                     temperature=-1.0).status == -5
+
+
+# ---- temperature 0 (greedy), contrastive mode ------------------------------------
+
+def test_greedy_argmax_against_numpy_and_ties():
+    rng = _rng(20)
+    for V in (1, 7, 500):
+        lp, lq = rng.standard_normal(V) * 3, rng.standard_normal(V) * 2
+        for mu, a in ((0.5, 0.0), (0.1, 0.1), (1.0, 0.5), (0.3, 1.0)):
+            c = lp - mu * lq
+            mask = lp - lp.max() >= (np.log(a) if a > 0 else -np.inf)
+            want = int(np.flatnonzero(mask)[np.argmax(c[mask])])
+            assert O.argmax_contrastive(lp, lq, mu, a) == want
+    assert O.argmax_contrastive(np.array([1.0, 5.0, 5.0, 2.0]), np.zeros(4), 0.5, 0.0) == 1     # tie: lowest index
+    assert O.argmax_contrastive(np.array([4.0, 3.0]), np.array([10.0, 0.0]), 0.5, 0.0) == 1     # 4-5 < 3-0
+    assert O.argmax_contrastive(np.array([4.0, 3.0]), np.array([10.0, 0.0]), 0.5, 0.9) == 0     # masked out
+
+
+def test_greedy_step_is_the_small_temperature_limit_without_mask():
+    """With alpha_cd = 0 the greedy step equals the sampled step at a tiny temperature (1e-9), whatever
+    the uniforms (r is numerically one-hot): a pin against the float64 sampler pinned elsewhere."""
+    rng = _rng(21)
+    n, B, gamma, V = 2, 300, 3, 40
+    logits = (rng.standard_normal((n, B, gamma + 1, V)) * 2).astype(np.float32)
+    # drafts: the contrastive argmax on a prefix of random length (accepted), random tokens after it
+    drafts = rng.integers(0, V, (B, gamma)).astype(np.int32)
+    for b in range(B):
+        for j in range(int(rng.integers(0, gamma + 1))):
+            drafts[b, j] = O.argmax_contrastive(logits[0, b, j].astype(np.float64), logits[1, b, j].astype(np.float64), 0.5, 0.0)
+    proposer = np.ones(B, dtype=np.int32)
+    st, alen, toks = O.verify_greedy(logits, O.DTYPE_F32, drafts, [0.5, 0.0])
+    assert st == 0
+    lim = O.verify(logits, O.DTYPE_F32, drafts, proposer, O.CONTRASTIVE, [0.5, 0.0], rng.random((B, gamma)),
+                   rng.random(B), temperature=1e-9)
+    assert np.array_equal(alen, lim.accepted_len) and np.array_equal(toks, lim.out_tokens)
+    assert len(set(alen.tolist())) >= 3
+
+
+def test_greedy_step_brute_force_with_mask_and_verifier_bonus():
+    rng = _rng(22)
+    B, gamma, V = 200, 4, 25
+    logits = (rng.standard_normal((2, B, gamma + 1, V)) * 2).astype(np.float32)
+    mu, a = 0.7, 0.2
+    arg = np.empty((B, gamma + 1), dtype=np.int64)
+    for b in range(B):
+        for j in range(gamma + 1):
+            lp, lq = logits[0, b, j].astype(np.float64), logits[1, b, j].astype(np.float64)
+            c = np.where(lp - lp.max() >= np.log(a), lp - mu * lq, -np.inf)
+            arg[b, j] = int(np.argmax(c))
+    drafts = arg[:, :gamma].astype(np.int32)
+    cut = rng.integers(0, gamma + 1, B)
+    for b in range(B):
+        if cut[b] < gamma:
+            drafts[b, cut[b]] = (drafts[b, cut[b]] + 1) % V
+    bonus = rng.integers(-1, 2, B).astype(np.int32)
+    st, alen, toks = O.verify_greedy(logits, O.DTYPE_F32, drafts, [mu, a], bonus_idx=bonus)
+    assert st == 0 and np.array_equal(alen, cut)
+    for b in range(B):
+        if cut[b] < gamma:
+            assert toks[b, cut[b]] == arg[b, cut[b]]
+        elif bonus[b] >= 0:
+            assert toks[b, gamma] == int(np.argmax(logits[bonus[b], b, gamma]))
+        else:
+            assert toks[b, gamma] == arg[b, gamma]
+        assert np.array_equal(toks[b, :cut[b]], drafts[b, :cut[b]]) and np.all(toks[b, cut[b] + 1:] == -1)
