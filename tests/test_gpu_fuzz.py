@@ -1,0 +1,63 @@
+"""Seeded random sweep of shapes, dtypes, combine modes and extensions: GPU against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2502_01662_amd import cos_verify as C
+from tests import parity as P
+from tests.test_gpu_parity import _random_inputs
+
+pytestmark = pytest.mark.gpu
+
+
+def _case(seed):
+    rng = np.random.default_rng(seed)
+    contrastive = bool(rng.integers(0, 3) == 0)
+    n = 2 if contrastive else int(rng.integers(1, 9))
+    B = int(rng.integers(1, 17))
+    gamma = int(rng.integers(1, 9))
+    V = int(rng.choice([rng.integers(1, 600), rng.integers(600, 9000), 8 * rng.integers(64, 3000), rng.integers(9000, 60000)]))
+    dtype = "bf16" if rng.integers(0, 2) else "f32"
+    std = float(rng.choice([0.5, 1.5, 3.0]))
+    inp = _random_inputs(n, B, gamma, V, dtype, seed=seed, std=std)
+    if rng.integers(0, 4) == 0 and V > 4:                       # some tokens impossible under every model
+        dead = torch.from_numpy(rng.integers(0, V, max(1, V // 7))).cuda()
+        inp["logits"][..., dead] = float("-inf")
+        alive = torch.from_numpy(np.setdiff1d(np.arange(V), dead.cpu().numpy())[:1]).cuda()
+        inp["logits"][..., alive] = 1.0                         # at least one finite logit per row
+    if contrastive:
+        weights = [float(rng.choice([0.0, 0.1, 0.5, 1.0])), float(rng.choice([0.0, 0.05, 0.1, 0.5]))]
+        mode = C.COS_COMBINE_CONTRASTIVE
+        if rng.integers(0, 2):                                   # give acceptance a chance: drafts at the expert's argmax
+            top = inp["logits"][0, :, :gamma].float().argmax(-1).to(torch.int32)
+            keep = torch.from_numpy(rng.integers(0, 2, (B, gamma)).astype(bool)).cuda()
+            inp["draft_tokens"] = torch.where(keep, top, inp["draft_tokens"]).contiguous()
+    else:
+        weights = rng.dirichlet(np.ones(n)).tolist()
+        if rng.integers(0, 5) == 0:
+            weights = [0.0] * n
+            weights[int(rng.integers(0, n))] = 1.0
+        mode = C.COS_COMBINE_ENSEMBLE
+    if rng.integers(0, 2):
+        inp["temperature"] = float(rng.choice([0.5, 0.8, 1.0, 1.7]))
+    if rng.integers(0, 2):
+        inp["proposer_pos"] = torch.from_numpy(rng.integers(0, n, (B, gamma)).astype(np.int32)).cuda()
+    if rng.integers(0, 2):
+        inp["bonus_idx"] = torch.from_numpy(rng.integers(-1, n, B).astype(np.int32)).cuda()
+    if rng.integers(0, 2):
+        inp["stop_window"] = int(rng.integers(1, gamma + 2))
+    if rng.integers(0, 3) == 0:
+        inp["u_accept"][rng.integers(0, B)] = 0.0
+    return inp, mode, weights, dict(n=n, B=B, gamma=gamma, V=V, dtype=dtype, mode=mode,
+                                    ext={k: (v if not torch.is_tensor(v) else "tensor") for k, v in inp.items()
+                                         if k in ("temperature", "proposer_pos", "bonus_idx", "stop_window")})
+
+
+@pytest.mark.parametrize("seed", range(60))
+def test_random_configuration(seed):
+    inp, mode, weights, desc = _case(1000 + seed)
+    alen, toks, diag = P.run_gpu(inp, mode, weights)
+    rep = P.compare(inp, mode, weights, alen, toks, diag)
+    print(f"[fuzz] {desc}: {rep.summary()}", flush=True)
+    assert rep.ok, (desc, rep.failures[:3])
+    assert rep.excused_accept_ties + rep.excused_cdf_ties <= 1, (desc, rep.summary())
