@@ -157,7 +157,15 @@ def main() -> int:
         res = O.verify(lg, odt, hd, hp, w.mode, list(w.weights), hua, hur, all_positions=False, num_threads=threads)
         c1 = time.perf_counter()
         assert res.status == 0
+        # per-core rate: the same oracle on one thread, on a few of those rows
+        few = max(1, min(len(rows), 8))
+        s0 = time.perf_counter()
+        one = O.verify(lg[:, :few], odt, hd[:few], hp[:few], w.mode, list(w.weights), hua[:few], hur[:few],
+                       all_positions=False, num_threads=1)
+        s1 = time.perf_counter()
+        assert one.status == 0
         cpu = {"value": round(len(rows) * w.gamma / (c1 - c0), 2), "unit": "positions/s",
+               "one_core_value": round(few * w.gamma / (s1 - s0), 2),
                "cores": int(min(threads, len(rows))), "kind": "oracle",
                "sample": f"{len(rows)} of {w.B} batch rows of {w.name} (float64 C oracle, OpenMP over rows, "
                          f"stops at the first rejection), {c1 - c0:.2f} s wall",

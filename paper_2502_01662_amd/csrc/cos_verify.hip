@@ -1091,17 +1091,20 @@ __global__ void __launch_bounds__(kThreads) sample_kernel(Params p) {
   double* sums = p.tile_sums + (size_t)b * p.ntiles;
   const int tb = c * p.tpc;
   const int te = min(tb + p.tpc, p.ntiles);
-  for (int t = tb + wave * TU; t < te; t += kWaves * TU) {
+  // wavefront w takes tiles tb + w, tb + w + kWaves, ...; TU of them are in flight at once
+  for (int t = tb + wave; t < te; t += kWaves * TU) {
     float x[TU][NCAP][N];
 #pragma unroll
-    for (int i = 0; i < TU; ++i) tile_load<T, ALIGNED, NCAP>(p, rows, n, min(t + i, te - 1), x[i]);
+    for (int i = 0; i < TU; ++i)
+      tile_load<T, ALIGNED, NCAP>(p, rows, n, min(t + i * kWaves, te - 1), x[i]);
 #pragma unroll
     for (int i = 0; i < TU; ++i) {
+      const int ti = t + i * kWaves;
       float f[N];
-      tile_eval<T, NCAP, CONTRASTIVE>(p, x[i], n, min(t + i, te - 1), plan.pi, plan.bonus, plan.m0, coef,
+      tile_eval<T, NCAP, CONTRASTIVE>(p, x[i], n, min(ti, te - 1), plan.pi, plan.bonus, plan.m0, coef,
                                       off, f);
       const double ts = wave_sum_to_lane63(lane_mass<N>(f));
-      if (lane == 63 && t + i < te) tile_sum[t + i - tb] = ts;  // staged in LDS
+      if (lane == 63 && ti < te) tile_sum[ti - tb] = ts;  // staged in LDS
     }
   }
   __syncthreads();
