@@ -33,7 +33,9 @@
  *
  *   extensions         cos_oracle_verify_ex: temperature (Sec. 4.1), the
  *                      verifier's own bonus token (Sec. 3.1 / 3.3), a proposer
- *                      per draft position (Alg. 2), the acceptance rate of Eq. (7)
+ *                      per draft position (Alg. 2), the acceptance rate of Eq. (7),
+ *                      a draft count per row and verification without an extra
+ *                      token (Alg. 2's VERIFY)
  *
  * Everything is float64; sums run in ascending index order; nothing is
  * blocked, fused or reordered.
@@ -46,7 +48,9 @@
  * App. A.2, brute-force inverse CDF; extensions (tests/test_oracle_extension_pins.py):
  * scipy softmax of l/T and exactly pre-scaled logits, the bonus law s_v by
  * searchsorted and chi-square, an independent per-position re-derivation, the
- * hand value 13/16 and Eq. (7) for alpha.  No function here is "parity unpinned".
+ * hand value 13/16 and Eq. (7) for alpha, rows with fewer drafts and the
+ * no-extra-token mode against the base step on the truncated tensor.  No
+ * function here is "parity unpinned".
  */
 #include <math.h>
 #include <stdint.h>
@@ -325,12 +329,24 @@ static int check_weights(int mode, int n, const double *w) {
  *                  overrides proposer_idx
  *   alpha          out [B][gamma] or NULL: acceptance rate of every evaluated
  *                  position, Eq. (7) (NaN where never evaluated)
+ *   num_drafts     [B] or NULL: row b carries only num_drafts[b] in [0, gamma]
+ *                  drafts (rows of a batch, and the windows Alg. 2 verifies, differ
+ *                  in length); position num_drafts[b] takes the role of position
+ *                  gamma, later positions are never read, accepted_len[b] is in
+ *                  [0, num_drafts[b]]
+ *   no_bonus       != 0: when every draft of a row is accepted nothing is drawn
+ *                  (Alg. 2's VERIFY only tests and resamples; Naive-CoS discards the
+ *                  extra token): out_tokens[b][num_drafts[b]] = -1 and the logits of
+ *                  that position are not read; sample_mass, cdf edges and flags of
+ *                  such a row are 0
  */
 typedef struct cos_oracle_options {
   double temperature;
   const int32_t *bonus_idx;
   const int32_t *proposer_pos;
   double *alpha;
+  const int32_t *num_drafts;
+  int no_bonus;
 } cos_oracle_options;
 
 int cos_oracle_verify_ex(const void *logits, int dtype, int n, int B, int gamma,
@@ -349,6 +365,8 @@ int cos_oracle_verify_ex(const void *logits, int dtype, int n, int B, int gamma,
   const int32_t *bonus_idx = opt ? opt->bonus_idx : NULL;
   const int32_t *proposer_pos = opt ? opt->proposer_pos : NULL;
   double *alpha = opt ? opt->alpha : NULL;
+  const int32_t *num_drafts = opt ? opt->num_drafts : NULL;
+  const int no_bonus = opt ? opt->no_bonus : 0;
   if (!logits || !draft_tokens || !proposer_idx || !weights || !u_accept ||
       !u_resample || !accepted_len || !out_tokens)
     return ORACLE_ERR_NULL;
@@ -363,7 +381,8 @@ int cos_oracle_verify_ex(const void *logits, int dtype, int n, int B, int gamma,
     int j;
     if (proposer_idx[b] < 0 || proposer_idx[b] >= n) return ORACLE_ERR_SHAPE;
     if (bonus_idx && (bonus_idx[b] < -1 || bonus_idx[b] >= n)) return ORACLE_ERR_SHAPE;
-    for (j = 0; j < gamma; ++j) {
+    if (num_drafts && (num_drafts[b] < 0 || num_drafts[b] > gamma)) return ORACLE_ERR_SHAPE;
+    for (j = 0; j < (num_drafts ? num_drafts[b] : gamma); ++j) {
       int32_t d = draft_tokens[(size_t)b * gamma + j];
       if (d < 0 || d >= V) return ORACLE_ERR_SHAPE;
       if (proposer_pos && (proposer_pos[(size_t)b * gamma + j] < 0 ||
@@ -388,6 +407,7 @@ int cos_oracle_verify_ex(const void *logits, int dtype, int n, int B, int gamma,
 #pragma omp for schedule(dynamic, 1)
     for (b = 0; b < B; ++b) {
       int pi, j, m, jstar, alive, x, clamped = 0, flag = 0, residual, token, bonus_from;
+      const int gb = num_drafts ? num_drafts[b] : gamma; /* drafts of this row */
       const double *q;
       double F, lo = 0.0, hi = 0.0;
       if (failed) continue;
@@ -401,10 +421,22 @@ int cos_oracle_verify_ex(const void *logits, int dtype, int n, int B, int gamma,
         if (ratio) ratio[k] = NAN;
         if (alpha) alpha[k] = NAN;
       }
-      /* positions 0..gamma-1 carry a draft; position gamma is the bonus row */
-      for (j = 0; j <= gamma; ++j) {
-        const int verifier_bonus = (j == gamma) && bonus_from >= 0;
-        if (!alive && !(all_positions && j < gamma)) break;
+      /* positions 0..gb-1 carry a draft; position gb is the bonus row */
+      for (j = 0; j <= gb; ++j) {
+        const int verifier_bonus = (j == gb) && bonus_from >= 0;
+        if (!alive && !(all_positions && j < gb)) break;
+        if (j == gb && no_bonus) {
+          /* every draft accepted and no extra token wanted: nothing is read or drawn */
+          accepted_len[b] = gb;
+          for (x = 0; x <= gamma; ++x)
+            out_tokens[(size_t)b * (gamma + 1) + x] =
+                x < gb ? draft_tokens[(size_t)b * gamma + x] : -1;
+          if (sample_mass) sample_mass[b] = 0.0;
+          if (cdf_lo) cdf_lo[b] = 0.0;
+          if (cdf_hi) cdf_hi[b] = 0.0;
+          if (flags) flags[b] = 0;
+          break;
+        }
         for (m = 0; m < n; ++m) {
           size_t row = ((size_t)m * B + b) * (size_t)(gamma + 1) + j;
           const char *src = (const char *)logits + row * (size_t)V * esize;
@@ -421,7 +453,7 @@ int cos_oracle_verify_ex(const void *logits, int dtype, int n, int B, int gamma,
         } else {
           cos_oracle_combine_contrastive(l, l + V, weights[0], weights[1], V, r);
         }
-        if (j < gamma) {
+        if (j < gb) {
           size_t k = (size_t)b * gamma + j;
           int d = draft_tokens[k];
           double rt;
@@ -438,11 +470,11 @@ int cos_oracle_verify_ex(const void *logits, int dtype, int n, int B, int gamma,
         } else {
           q = r; /* unused: the bonus draw takes f = r */
         }
-        /* here j is the first rejected position, or j == gamma (all accepted:
+        /* here j is the first rejected position, or j == gb (all accepted:
          * bonus token).  r, q hold the distributions of that position.      */
         jstar = j;
         alive = 0;
-        residual = jstar < gamma;
+        residual = jstar < gb;
         F = cos_oracle_sample_weights(r, q, V, residual, f);
         if (!(F > 0.0) || !isfinite(F)) {
           /* cannot happen in exact arithmetic: fall back to r itself */
@@ -480,10 +512,12 @@ int cos_oracle_verify_ex(const void *logits, int dtype, int n, int B, int gamma,
  * accepts d_j iff d_j == a_j whatever q is (r(d) = 0 otherwise), the residual
  * norm(max(0, r - q)) and its fall-back r are both one-hot at a_j, and the bonus
  * token is a_gamma -- or, with bonus_idx[b] = v >= 0, the argmax of l_v alone
- * (Sec. 3.3).  No random numbers are consumed.  weights = (mu, alpha_cd).    */
+ * (Sec. 3.3).  No random numbers are consumed.  weights = (mu, alpha_cd).
+ * num_drafts / no_bonus as in cos_oracle_options.                            */
 int cos_oracle_verify_greedy(const void *logits, int dtype, int B, int gamma, int V,
                              const int32_t *draft_tokens, const double *weights,
-                             const int32_t *bonus_idx, int32_t *accepted_len,
+                             const int32_t *bonus_idx, const int32_t *num_drafts,
+                             int no_bonus, int32_t *accepted_len,
                              int32_t *out_tokens, int num_threads) {
   int b, failed = 0;
   const int n = 2;
@@ -493,6 +527,8 @@ int cos_oracle_verify_greedy(const void *logits, int dtype, int B, int gamma, in
   if (dtype != ORACLE_DTYPE_F32 && dtype != ORACLE_DTYPE_BF16) return ORACLE_ERR_DTYPE;
   if (check_weights(ORACLE_CONTRASTIVE, n, weights) != ORACLE_OK) return ORACLE_ERR_WEIGHTS;
   esize = dtype == ORACLE_DTYPE_F32 ? 4 : 2;
+  for (b = 0; b < B; ++b)
+    if (num_drafts && (num_drafts[b] < 0 || num_drafts[b] > gamma)) return ORACLE_ERR_SHAPE;
 #ifdef _OPENMP
   if (num_threads > 0) omp_set_num_threads(num_threads);
 #endif
@@ -505,11 +541,13 @@ int cos_oracle_verify_greedy(const void *logits, int dtype, int B, int gamma, in
     }
 #pragma omp for schedule(dynamic, 1)
     for (b = 0; b < B; ++b) {
-      int j, m, x, jstar = gamma, token = -1;
+      const int gb = num_drafts ? num_drafts[b] : gamma; /* drafts of this row */
+      int j, m, x, jstar = gb, token = -1;
       if (failed) continue;
-      for (j = 0; j <= gamma; ++j) {
-        const int v = (j == gamma && bonus_idx) ? bonus_idx[b] : -1;
+      for (j = 0; j <= gb; ++j) {
+        const int v = (j == gb && bonus_idx) ? bonus_idx[b] : -1;
         int a;
+        if (j == gb && no_bonus) break; /* all accepted, no extra token: nothing read */
         for (m = 0; m < n; ++m) {
           size_t row = ((size_t)m * B + b) * (size_t)(gamma + 1) + j;
           if (v >= 0 && m != v) continue; /* not needed, not read */
@@ -518,7 +556,7 @@ int cos_oracle_verify_greedy(const void *logits, int dtype, int B, int gamma, in
         }
         a = v >= 0 ? cos_oracle_argmax(l + (size_t)v * V, V)
                    : cos_oracle_argmax_contrastive(l, l + V, weights[0], weights[1], V);
-        if (j < gamma && draft_tokens[(size_t)b * gamma + j] == a) continue; /* accepted */
+        if (j < gb && draft_tokens[(size_t)b * gamma + j] == a) continue; /* accepted */
         jstar = j;
         token = a;
         break;

@@ -37,7 +37,8 @@ def build(force: bool = True) -> str:
 
 class _Options(ctypes.Structure):
     _fields_ = [("temperature", ctypes.c_double), ("bonus_idx", ctypes.POINTER(ctypes.c_int32)),
-                ("proposer_pos", ctypes.POINTER(ctypes.c_int32)), ("alpha", ctypes.POINTER(ctypes.c_double))]
+                ("proposer_pos", ctypes.POINTER(ctypes.c_int32)), ("alpha", ctypes.POINTER(ctypes.c_double)),
+                ("num_drafts", ctypes.POINTER(ctypes.c_int32)), ("no_bonus", ctypes.c_int)]
 
 
 _lib = None
@@ -80,7 +81,7 @@ def _load():
         lib.cos_oracle_argmax_contrastive.restype = ci
         lib.cos_oracle_argmax.argtypes = [dp, ci]
         lib.cos_oracle_argmax.restype = ci
-        lib.cos_oracle_verify_greedy.argtypes = [vp, ci, ci, ci, ci, ip, dp, ip, ip, ip, ci]
+        lib.cos_oracle_verify_greedy.argtypes = [vp, ci, ci, ci, ci, ip, dp, ip, ip, ci, ip, ip, ci]
         lib.cos_oracle_verify_greedy.restype = ci
         lib.cos_oracle_max_threads.argtypes = []
         lib.cos_oracle_max_threads.restype = ci
@@ -193,7 +194,7 @@ class OracleResult:
 def verify(logits: np.ndarray, dtype: int, draft_tokens, proposer_idx, mode: int, weights,
            u_accept, u_resample, all_positions: bool = False, num_threads: int = 0,
            temperature: float = 1.0, bonus_idx=None, proposer_pos=None,
-           want_alpha: bool = False) -> OracleResult:
+           want_alpha: bool = False, num_drafts=None, no_bonus: bool = False) -> OracleResult:
     """Run ``cos_oracle_verify_ex`` (the base step when no extension is given).
 
     ``logits`` is a host array of shape [n][B][gamma+1][V]: float32, or uint16
@@ -230,6 +231,11 @@ def verify(logits: np.ndarray, dtype: int, draft_tokens, proposer_idx, mode: int
     if want_alpha:
         res.alpha = np.empty((B, gamma))
         opt.alpha = _dp(res.alpha)
+    if num_drafts is not None:
+        nd = np.ascontiguousarray(num_drafts, dtype=np.int32).reshape(B)
+        keep.append(nd)
+        opt.num_drafts = _ip(nd)
+    opt.no_bonus = int(bool(no_bonus))
     res.status = _load().cos_oracle_verify_ex(
         logits.ctypes.data_as(ctypes.c_void_p), dtype, n, B, gamma, V,
         _ip(draft_tokens), _ip(proposer_idx), mode, _dp(weights), _dp(u_accept), _dp(u_resample),
@@ -245,7 +251,8 @@ def argmax_contrastive(l_p, l_q, mu: float, alpha_cd: float) -> int:
     return _load().cos_oracle_argmax_contrastive(_dp(l_p), _dp(l_q), mu, alpha_cd, l_p.shape[0])
 
 
-def verify_greedy(logits: np.ndarray, dtype: int, draft_tokens, weights, bonus_idx=None, num_threads: int = 0):
+def verify_greedy(logits: np.ndarray, dtype: int, draft_tokens, weights, bonus_idx=None, num_threads: int = 0,
+                  num_drafts=None, no_bonus: bool = False):
     """Temperature-0 contrastive step; returns (status, accepted_len, out_tokens)."""
     logits = np.ascontiguousarray(logits)
     assert logits.ndim == 4 and logits.shape[0] == 2
@@ -255,10 +262,12 @@ def verify_greedy(logits: np.ndarray, dtype: int, draft_tokens, weights, bonus_i
     draft_tokens = np.ascontiguousarray(draft_tokens, dtype=np.int32).reshape(B, gamma)
     weights = _f64(weights)
     bi = None if bonus_idx is None else np.ascontiguousarray(bonus_idx, dtype=np.int32).reshape(B)
+    nd = None if num_drafts is None else np.ascontiguousarray(num_drafts, dtype=np.int32).reshape(B)
     alen = np.full(B, -7, dtype=np.int32)
     toks = np.full((B, gamma + 1), -7, dtype=np.int32)
     st = _load().cos_oracle_verify_greedy(logits.ctypes.data_as(ctypes.c_void_p), dtype, B, gamma, V,
                                           _ip(draft_tokens), _dp(weights), _ip(bi) if bi is not None else None,
+                                          _ip(nd) if nd is not None else None, int(bool(no_bonus)),
                                           _ip(alen), _ip(toks), int(num_threads))
     return st, alen, toks
 

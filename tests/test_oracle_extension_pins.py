@@ -232,3 +232,153 @@ def test_greedy_step_brute_force_with_mask_and_verifier_bonus():
         else:
             assert toks[b, gamma] == arg[b, gamma]
         assert np.array_equal(toks[b, :cut[b]], drafts[b, :cut[b]]) and np.all(toks[b, cut[b] + 1:] == -1)
+
+
+# ---- rows with fewer drafts (num_drafts) and no extra token (no_bonus) -----------------------
+
+def _poison_after(logits, num_drafts, first_unread):
+    """NaN in every position >= num_drafts[b] + first_unread (never read by a correct implementation)."""
+    out = logits.copy()
+    for b, k in enumerate(num_drafts):
+        out[:, b, k + first_unread:, :] = np.nan
+    return out
+
+
+@pytest.mark.parametrize("mode,weights,n", [(O.ENSEMBLE, [0.5, 0.2, 0.3], 3), (O.CONTRASTIVE, [0.5, 0.1], 2)])
+def test_ragged_rows_equal_calls_on_the_truncated_tensor(mode, weights, n):
+    """Row b with K drafts must equal the base step (pinned on its own) on logits[:, b, :K+1] with gamma = K."""
+    rng = _rng(40 + mode)
+    B, gamma, V = 120, 4, 40
+    logits, drafts, proposer, ua, ur = _inputs(rng, n, B, gamma, V, std=1.0)
+    for b in range(B):                       # drafts from the proposer, so that lengths vary
+        for j in range(gamma):
+            s = O.softmax(O.row_to_f64(logits[proposer[b], b, j], O.DTYPE_F32))
+            drafts[b, j] = min(np.searchsorted(np.cumsum(s), rng.random(), side="right"), V - 1)
+    K = rng.integers(0, gamma + 1, B).astype(np.int32)
+    res = O.verify(_poison_after(logits, K, 1), O.DTYPE_F32, drafts, proposer, mode, weights, ua, ur, num_drafts=K)
+    assert res.status == 0
+    seen = set()
+    for b in range(B):
+        k = int(K[b])
+        if k == 0:
+            # nothing to test: one draw from r_0 by the step functions
+            l = [O.row_to_f64(logits[m, b, 0], O.DTYPE_F32) for m in range(n)]
+            if mode == O.ENSEMBLE:
+                r = O.combine_ensemble(np.stack([O.softmax(x) for x in l]), np.array(weights))
+            else:
+                r = O.combine_contrastive(l[0], l[1], weights[0], weights[1])[0]
+            tok = O.inverse_cdf(r, r.sum(), ur[b])[0]
+            assert res.accepted_len[b] == 0 and res.out_tokens[b, 0] == tok and (res.out_tokens[b, 1:] == -1).all()
+            continue
+        one = O.verify(np.ascontiguousarray(logits[:, b:b + 1, :k + 1]), O.DTYPE_F32, drafts[b:b + 1, :k],
+                       proposer[b:b + 1], mode, weights, ua[b:b + 1, :k], ur[b:b + 1])
+        assert one.status == 0
+        assert res.accepted_len[b] == one.accepted_len[0]
+        assert np.array_equal(res.out_tokens[b, :k + 1], one.out_tokens[0])
+        assert (res.out_tokens[b, k + 1:] == -1).all()
+        assert res.sample_mass[b] == one.sample_mass[0] and res.cdf_hi[b] == one.cdf_hi[0]
+        assert res.flags[b] == one.flags[0] == 0
+        assert np.array_equal(res.r_at_draft[b, :k], one.r_at_draft[0], equal_nan=True)
+        assert np.isnan(res.r_at_draft[b, k:]).all()
+        seen.add((k, int(one.accepted_len[0]) == k))
+    assert {(k, True) for k in range(1, gamma + 1)} <= seen            # all-accepted rows of every length occurred
+    assert {(k, False) for k in range(1, gamma + 1)} <= seen
+
+
+def test_ragged_rows_with_a_verifier_bonus():
+    """The verifier's own extra token moves with the row's length: position K, model bonus_idx[b] alone."""
+    rng = _rng(42)
+    B, gamma, V = 150, 3, 25
+    logits, drafts, proposer, ua, ur = _inputs(rng, 2, B, gamma, V, std=0.4)
+    K = rng.integers(1, gamma + 1, B).astype(np.int32)
+    verifier = (1 - proposer).astype(np.int32)
+    poisoned = _poison_after(logits, K, 1)
+    for b in range(B):
+        poisoned[proposer[b], b, K[b]] = np.nan                      # the proposer has no logits at the bonus position
+    res = O.verify(poisoned, O.DTYPE_F32, drafts, proposer, O.ENSEMBLE, [0.5, 0.5], ua, ur, num_drafts=K,
+                   bonus_idx=verifier)
+    assert res.status == 0
+    hit = 0
+    for b in range(B):
+        k = int(K[b])
+        one = O.verify(np.ascontiguousarray(logits[:, b:b + 1, :k + 1]), O.DTYPE_F32, drafts[b:b + 1, :k],
+                       proposer[b:b + 1], O.ENSEMBLE, [0.5, 0.5], ua[b:b + 1, :k], ur[b:b + 1], bonus_idx=verifier[b:b + 1])
+        assert np.array_equal(res.out_tokens[b, :k + 1], one.out_tokens[0]) and res.accepted_len[b] == one.accepted_len[0]
+        if res.accepted_len[b] == k:
+            hit += 1
+            sv = O.softmax(O.row_to_f64(logits[verifier[b], b, k], O.DTYPE_F32))
+            assert res.out_tokens[b, k] == O.inverse_cdf(sv, sv.sum(), ur[b])[0]
+    assert hit > 20
+
+
+def test_no_bonus_only_drops_the_extra_token():
+    rng = _rng(43)
+    B, gamma, V = 200, 3, 30
+    logits, drafts, proposer, ua, ur = _inputs(rng, 2, B, gamma, V, std=0.5)
+    K = rng.integers(0, gamma + 1, B).astype(np.int32)
+    w = [0.6, 0.4]
+    full = O.verify(logits, O.DTYPE_F32, drafts, proposer, O.ENSEMBLE, w, ua, ur, num_drafts=K)
+    nob = O.verify(_poison_after(logits, K, 0), O.DTYPE_F32, drafts, proposer, O.ENSEMBLE, w, ua, ur, num_drafts=K,
+                   no_bonus=True)
+    # (a rejected row stops at a position below K, so the poison is never read)
+    assert full.status == 0 and nob.status == 0
+    assert np.array_equal(full.accepted_len, nob.accepted_len)
+    done = full.accepted_len == K
+    assert done.sum() > 20 and (~done).sum() > 20
+    for b in range(B):
+        if done[b]:
+            assert np.array_equal(nob.out_tokens[b, :K[b]], drafts[b, :K[b]]) and (nob.out_tokens[b, K[b]:] == -1).all()
+            assert nob.sample_mass[b] == 0.0 and nob.flags[b] == 0
+        else:
+            assert np.array_equal(nob.out_tokens[b], full.out_tokens[b])
+            assert nob.sample_mass[b] == full.sample_mass[b]
+    # without num_drafts: the Naive-CoS step (the extra token discarded, Sec. 3.2)
+    a = O.verify(logits, O.DTYPE_F32, drafts, proposer, O.ENSEMBLE, w, ua, ur, no_bonus=True)
+    c = O.verify(logits, O.DTYPE_F32, drafts, proposer, O.ENSEMBLE, w, ua, ur)
+    assert np.array_equal(a.accepted_len, c.accepted_len)
+    assert np.array_equal(a.out_tokens[:, :gamma], c.out_tokens[:, :gamma])
+    assert (a.out_tokens[:, gamma] == -1).all()
+
+
+def test_greedy_ragged_rows_and_no_bonus():
+    rng = _rng(44)
+    B, gamma, V = 150, 4, 12
+    logits = (rng.standard_normal((2, B, gamma + 1, V))).astype(np.float32)
+    w = [0.5, 0.2]
+    drafts = np.zeros((B, gamma), dtype=np.int32)
+    for b in range(B):
+        for j in range(gamma):
+            a = O.argmax_contrastive(logits[0, b, j].astype(np.float64), logits[1, b, j].astype(np.float64), *w)
+            drafts[b, j] = a if rng.random() < 0.7 else (a + 1) % V
+    K = rng.integers(0, gamma + 1, B).astype(np.int32)
+    st, alen, toks = O.verify_greedy(_poison_after(logits, K, 1), O.DTYPE_F32, drafts, w, num_drafts=K)
+    st2, alen2, toks2 = O.verify_greedy(_poison_after(logits, K, 0), O.DTYPE_F32, drafts, w, num_drafts=K, no_bonus=True)
+    st3, alen3, toks3 = O.verify_greedy(logits, O.DTYPE_F32, drafts, w, num_drafts=K, no_bonus=True)
+    assert st == 0 and st2 == 0 and np.array_equal(alen, alen2)
+    assert st3 == 0 and np.array_equal(alen3, alen2) and np.array_equal(toks3, toks2)    # unread means unread
+    for b in range(B):
+        k = int(K[b])
+        if k == 0:
+            a0 = O.argmax_contrastive(logits[0, b, 0].astype(np.float64), logits[1, b, 0].astype(np.float64), *w)
+            assert alen[b] == 0 and toks[b, 0] == a0 and (toks2[b] == -1).all()
+            continue
+        s1, a1, t1 = O.verify_greedy(np.ascontiguousarray(logits[:, b:b + 1, :k + 1]), O.DTYPE_F32, drafts[b:b + 1, :k], w)
+        assert s1 == 0 and alen[b] == a1[0] and np.array_equal(toks[b, :k + 1], t1[0]) and (toks[b, k + 1:] == -1).all()
+        if a1[0] == k:
+            assert np.array_equal(toks2[b, :k], drafts[b, :k]) and (toks2[b, k:] == -1).all()
+        else:
+            assert np.array_equal(toks2[b], toks[b])
+    assert (alen == K).sum() > 10 and (alen < K).sum() > 10
+
+
+def test_num_drafts_argument_checks():
+    rng = _rng(45)
+    logits, drafts, proposer, ua, ur = _inputs(rng, 2, 3, 2, 10)
+    for bad in ([0, 3, 1], [-1, 2, 2]):
+        assert O.verify(logits, O.DTYPE_F32, drafts, proposer, O.ENSEMBLE, [0.5, 0.5], ua, ur,
+                        num_drafts=bad).status == -2
+        assert O.verify_greedy(logits, O.DTYPE_F32, drafts, [0.5, 0.1], num_drafts=bad)[0] == -2
+    # draft tokens beyond a row's length are not looked at
+    drafts2 = drafts.copy()
+    drafts2[0, 1] = 999
+    assert O.verify(logits, O.DTYPE_F32, drafts2, proposer, O.ENSEMBLE, [0.5, 0.5], ua, ur, num_drafts=[1, 2, 2]).status == 0
