@@ -149,6 +149,21 @@ cos_status_t cos_verify(const void *logits, cos_dtype_t dt, int n, int B, int ga
  *               u_resample, proposer_idx and temperature are not used; diag is
  *               not written.  Bit-exact against a float64 reference.  Not
  *               combinable with alpha, proposer_pos or stop_window.
+ * num_drafts    DEVICE [B] int32 or NULL.  Row b carries only num_drafts[b]
+ *               drafts, in [0, gamma] (caller's contract): the rows of a batch,
+ *               and the windows Alg. 2 verifies, differ in length.  Position
+ *               num_drafts[b] takes the role of position gamma (bonus position);
+ *               draft_tokens, u_accept, proposer_pos and logits beyond it are
+ *               never read, accepted_len[b] is in [0, num_drafts[b]], alpha
+ *               and diag.r_at_draft / q_at_draft of positions without a draft
+ *               are NaN.  num_drafts[b] = 0 draws one token from r (or s_v) at
+ *               position 0.
+ * no_bonus      non-zero: when every draft of a row is accepted, nothing is
+ *               drawn (Alg. 2's VERIFY only tests and resamples; Naive-CoS of
+ *               Sec. 3.2 discards the extra token): out_tokens[b][num_drafts[b]]
+ *               = -1 and the logits of that position are not read, so the
+ *               tensor's last position may hold anything.  diag.sample_mass,
+ *               cdf_lo, cdf_hi and flags of such a row are 0.
  */
 typedef struct cos_options_t {
   size_t struct_bytes;
@@ -158,6 +173,8 @@ typedef struct cos_options_t {
   double *alpha;
   int stop_window;
   int greedy;
+  const int32_t *num_drafts;
+  int no_bonus;
 } cos_options_t;
 
 /* cos_verify with extensions; options == NULL is exactly cos_verify. */

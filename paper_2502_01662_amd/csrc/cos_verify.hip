@@ -71,7 +71,7 @@ struct SeqPlan {
   int pi;        // proposer of the sampled position
   int bonus;     // >= 0: the bonus token is drawn from this model's softmax alone (jstar == gamma)
   float m0;      // contrastive: expert maximum at jstar
-  int pad;
+  int skip;      // 1: every draft accepted and no extra token wanted: nothing is sampled
   double lse2[COS_MAX_MODELS];  // log2-sum-exp2 of the statistics at jstar
 };
 
@@ -82,6 +82,8 @@ struct Params {
   const int* proposer;
   const int* proposer_pos;  // optional [B][gamma]: proposer of each draft position
   const int* bonus_idx;     // optional [B]: model the bonus token is drawn from (-1: from r)
+  const int* num_drafts;    // optional [B]: drafts of each row (NULL: gamma everywhere)
+  int no_bonus;             // 1: no extra token when every draft is accepted
   const double* u_accept;
   const double* u_resample;
   int* accepted_len;
@@ -117,6 +119,17 @@ struct Params {
   double thr64;              // T ln(alpha_cd)
   cos_diag_t diag;
 };
+
+// Drafts of row b; position drafts_of(p, b) plays the bonus position's role.
+__device__ __forceinline__ int drafts_of(const Params& p, int b) {
+  return p.num_drafts ? p.num_drafts[b] : p.gamma;
+}
+
+// Positions after the row's bonus position are never read, and neither is the
+// bonus position itself when no extra token is wanted.
+__device__ __forceinline__ bool position_unread(const Params& p, int gb, int j) {
+  return j > gb || (j == gb && p.no_bonus);
+}
 
 // ---------------------------------------------------------------------------
 // wavefront and hand-off primitives
@@ -534,6 +547,7 @@ __device__ void decide_sequence(const Params& p, int b, DecideShared& sh) {
   const int j0 = p.j0, nj = p.nj;
   const int nrows = nj * nstat;  // statistics of this window
   const int n = p.n;
+  const int gb = drafts_of(p, b);
   const double log2e = (double)p.scale;  // log2(e) / T, the same constant the streaming kernel used
 
   // 1. combine the chunk partials of every (position, statistic) of the window in float64
@@ -563,7 +577,11 @@ __device__ void decide_sequence(const Params& p, int b, DecideShared& sh) {
   __syncthreads();
 
   // 2. Eq. (6) for every draft position of the window, in float64
-  const int ndraft = min(j0 + nj, p.gamma) - j0;  // draft positions in the window
+  const int ndraft = max(min(j0 + nj, gb) - j0, 0);  // draft positions in the window
+  if (tid >= ndraft && tid < nj && j0 + tid < p.gamma) {  // no draft here
+    if (p.diag.r_at_draft) p.diag.r_at_draft[(size_t)b * p.gamma + j0 + tid] = NAN;
+    if (p.diag.q_at_draft) p.diag.q_at_draft[(size_t)b * p.gamma + j0 + tid] = NAN;
+  }
   if (tid < ndraft) {
     const int jj = tid, j = j0 + tid;
     const size_t k = (size_t)b * p.gamma + j;
@@ -604,28 +622,35 @@ __device__ void decide_sequence(const Params& p, int b, DecideShared& sh) {
   }
 
   // 3. first rejection (Sec. 3.1) inside the window; -1: none, and the bonus position is not in it
-  int jstar = (j0 + nj == g1) ? p.gamma : -1;
+  int jstar = (j0 + nj > gb) ? gb : -1;
   for (int jj = ndraft - 1; jj >= 0; --jj)
     if (!sh.accept[jj]) jstar = j0 + jj;
   if (jstar < 0) return;  // undecided: a later window continues
 
-  // the drawn token's slot is filled by the sampling kernel
+  // the drawn token's slot is filled by the sampling kernel, unless nothing is drawn
+  const bool skip = p.no_bonus && jstar == gb;
   if (tid == 0) p.accepted_len[b] = jstar;
-  if (tid < g1 && tid != jstar)
+  if (tid < g1 && (tid != jstar || skip))
     p.out_tokens[(size_t)b * g1 + tid] = (tid < jstar) ? p.draft[(size_t)b * p.gamma + tid] : -1;
 
   // 4. plan for the sampling kernel (read after this launch has ended)
   SeqPlan* plan = p.plans + b;
   if (tid == 0) {
-    const bool residual = jstar < p.gamma;
+    const bool residual = jstar < gb;
     plan->jstar = jstar;
     plan->residual = residual;
     plan->pi = (residual && p.proposer_pos) ? p.proposer_pos[(size_t)b * p.gamma + jstar] : p.proposer[b];
     plan->bonus = (!residual && p.bonus_idx) ? p.bonus_idx[b] : -1;
-    plan->m0 = CONTRASTIVE ? sh.rowmax[jstar - j0] : 0.0f;
-    plan->pad = 0;
+    plan->m0 = (CONTRASTIVE && !skip) ? sh.rowmax[jstar - j0] : 0.0f;
+    plan->skip = skip;
+    if (skip) {
+      if (p.diag.sample_mass) p.diag.sample_mass[b] = 0.0;
+      if (p.diag.cdf_lo) p.diag.cdf_lo[b] = 0.0;
+      if (p.diag.cdf_hi) p.diag.cdf_hi[b] = 0.0;
+      if (p.diag.flags) p.diag.flags[b] = 0;
+    }
   }
-  if (tid < nstat) plan->lse2[tid] = sh.lse2[(jstar - j0) * nstat + tid];
+  if (tid < nstat && !skip) plan->lse2[tid] = sh.lse2[(jstar - j0) * nstat + tid];
 }
 
 // ---------------------------------------------------------------------------
@@ -909,8 +934,9 @@ __global__ void __launch_bounds__(kThreads) ensemble_stats_kernel(Params p) {
   Partial* out = p.partials + (((size_t)b * g1 + j) * p.n + m) * p.S + s;
   // With a verifier bonus the other models' logits at the bonus position are
   // not needed (they may not exist yet) and are not read.
-  const int only = (p.bonus_idx && j == p.gamma) ? p.bonus_idx[b] : -1;
-  if (only >= 0 && m != only) {
+  const int gb = drafts_of(p, b);
+  const int only = (p.bonus_idx && j == gb) ? p.bonus_idx[b] : -1;
+  if ((only >= 0 && m != only) || position_unread(p, gb, j)) {
     if (threadIdx.x == 0) {
       store_empty_partial(out);
       wait_stores();
@@ -945,6 +971,10 @@ __global__ void __launch_bounds__(kThreads) expert_rowmax_kernel(Params p) {
   const int b = ws / p.nj, j = p.j0 + (ws - b * p.nj);
   if (p.plans[b].jstar >= 0) return;  // decided by an earlier window
   const int rs = b * g1 + j;
+  if (position_unread(p, drafts_of(p, b), j)) {
+    if (threadIdx.x == 0) p.rowmax[(size_t)rs * p.S + s] = -INFINITY;
+    return;
+  }
   const T* row = row_ptr<T>(p, 0, b, j);
   const int v0 = s * p.cv;
   const int v1 = min(v0 + p.cv, p.nvec);
@@ -993,11 +1023,24 @@ __global__ void __launch_bounds__(kThreads) contrastive_stats_kernel(Params p) {
   const int tid = threadIdx.x;
   // Whose softmax statistic this position needs: the proposer's at a draft
   // position; at the bonus position only a verifier bonus needs one at all.
+  const int gb = drafts_of(p, b);
   int pi = p.proposer[b];
-  if (j < p.gamma) {
+  if (j < gb) {
     if (p.proposer_pos) pi = p.proposer_pos[(size_t)b * p.gamma + j];
   } else if (p.bonus_idx && p.bonus_idx[b] >= 0) {
     pi = p.bonus_idx[b];
+  }
+  if (position_unread(p, gb, j)) {  // uniform over the workgroup
+    if (tid == 0) {
+      Partial* out = p.partials + (((size_t)b * g1 + j) * 3) * p.S + s;
+      store_empty_partial(out);
+      store_empty_partial(out + (size_t)p.S);
+      store_empty_partial(out + (size_t)2 * p.S);
+      wait_stores();
+    }
+    if (arrive_last(p.counters + ((size_t)p.win * p.B + b) * kCtrStride, per_b, &s_flag))
+      decide_sequence<T, true>(p, b, sh);
+    return;
   }
 
   // expert maximum of this position from the row-max kernel's partial maxima
@@ -1078,6 +1121,7 @@ __global__ void __launch_bounds__(kThreads) sample_kernel(Params p) {
   const int wave = threadIdx.x >> 6;
   const int n = CONTRASTIVE ? 2 : (NM ? NM : p.n);
   const SeqPlan plan = p.plans[b];
+  if (plan.skip) return;  // every draft accepted, no extra token: nothing to draw
   // A verifier bonus reads that one model's row only (the others carry a zero
   // coefficient and may hold anything, so every slot points at the valid row).
   const bool one_row = !CONTRASTIVE && plan.residual == 0 && plan.bonus >= 0;
@@ -1176,7 +1220,9 @@ __global__ void __launch_bounds__(kThreads) greedy_contrastive_kernel(Params p) 
   const int j = rem / p.S;
   const int s = rem - j * p.S;
   const int tid = threadIdx.x;
-  const int plain = (j == p.gamma && p.bonus_idx) ? p.bonus_idx[b] : -1;
+  const int gb = drafts_of(p, b);
+  const bool unread = position_unread(p, gb, j);
+  const int plain = (j == gb && p.bonus_idx) ? p.bonus_idx[b] : -1;
   const double mu = p.w[0];
 
   {
@@ -1197,7 +1243,7 @@ __global__ void __launch_bounds__(kThreads) greedy_contrastive_kernel(Params p) 
   ArgBest best;
   best.val = 0.0;
   best.idx = -1;
-  for (int base = v0; base < v1; base += kStep) {
+  for (int base = v0; base < v1 && !unread; base += kStep) {
     float x0[U][N], x1[U][N];
     if (base + kStep <= v1) {
       load_group<T, ALIGNED, false, U>(row0, base, v1, p.V, x0);
@@ -1257,13 +1303,14 @@ __global__ void __launch_bounds__(kThreads) greedy_contrastive_kernel(Params p) 
     s_arg[tid] = bb.idx;
   }
   __syncthreads();
-  int jstar = p.gamma;
-  for (int jj = p.gamma - 1; jj >= 0; --jj)
+  int jstar = gb;
+  for (int jj = gb - 1; jj >= 0; --jj)
     if (p.draft[(size_t)b * p.gamma + jj] != s_arg[jj]) jstar = jj;
+  const bool skip = p.no_bonus && jstar == gb;  // every draft accepted, no extra token
   if (tid == 0) p.accepted_len[b] = jstar;
   if (tid < g1)
     p.out_tokens[(size_t)b * g1 + tid] =
-        tid < jstar ? p.draft[(size_t)b * p.gamma + tid] : (tid == jstar ? s_arg[jstar] : -1);
+        tid < jstar ? p.draft[(size_t)b * p.gamma + tid] : ((tid == jstar && !skip) ? s_arg[jstar] : -1);
 }
 
 // Acceptance-rate kernel (optional): alpha = sum_x min(q(x), r(x)) of Eq. (7) for
@@ -1285,6 +1332,10 @@ __global__ void __launch_bounds__(kThreads) acceptance_rate_kernel(Params p) {
   const int wave = threadIdx.x >> 6;
   const int n = CONTRASTIVE ? 2 : (NM ? NM : p.n);
   const int g1 = p.gamma + 1;
+  if (j >= drafts_of(p, b)) {  // no draft at this position: no acceptance rate
+    if (c == 0 && threadIdx.x == 0) p.alpha[(size_t)b * p.gamma + j] = NAN;
+    return;
+  }
   const int pi = p.proposer_pos ? p.proposer_pos[(size_t)b * p.gamma + j] : p.proposer[b];
   const double* lse = p.lse_all + ((size_t)b * g1 + j) * p.nstat;
   const float m0 = CONTRASTIVE ? p.rowmax_all[(size_t)b * g1 + j] : 0.0f;
@@ -1649,6 +1700,8 @@ cos_status_t cos_verify_ex(const void* logits, cos_dtype_t dt, int n, int B, int
   p.proposer = proposer_idx;
   p.proposer_pos = options ? options->proposer_pos : nullptr;
   p.bonus_idx = options ? options->bonus_idx : nullptr;
+  p.num_drafts = options ? options->num_drafts : nullptr;
+  p.no_bonus = (options && options->no_bonus) ? 1 : 0;
   p.u_accept = u_accept;
   p.u_resample = u_resample;
   p.accepted_len = accepted_len;
@@ -1771,7 +1824,7 @@ const char* cos_status_string(cos_status_t status) {
   return "unknown status";
 }
 
-int cos_verify_version(void) { return 2; }
+int cos_verify_version(void) { return 3; }
 
 cos_status_t cos_profile_enable(int slots) {
   if (slots < 0 || slots > kMaxProfileSlots) return COS_ERR_SHAPE;

@@ -56,7 +56,8 @@ def oracle_dtype(logits: torch.Tensor) -> int:
 def _gpu_ext(inp):
     """Extensions of the step carried in the input dict (all optional)."""
     return {"temperature": float(inp.get("temperature", 1.0)), "bonus_idx": inp.get("bonus_idx"),
-            "proposer_pos": inp.get("proposer_pos"), "stop_window": int(inp.get("stop_window", 0))}
+            "proposer_pos": inp.get("proposer_pos"), "stop_window": int(inp.get("stop_window", 0)),
+            "num_drafts": inp.get("num_drafts"), "no_bonus": bool(inp.get("no_bonus", False))}
 
 
 def run_gpu(inp: Dict[str, torch.Tensor], mode: int, weights: Sequence[float], with_diag: bool = True):
@@ -76,13 +77,16 @@ def run_oracle(inp: Dict[str, torch.Tensor], mode: int, weights: Sequence[float]
     lg = logits[:, sel].contiguous()
     bonus = inp.get("bonus_idx")
     ppos = inp.get("proposer_pos")
+    nd = inp.get("num_drafts")
     return lg, O.verify(W.host_logits(lg), oracle_dtype(lg), inp["draft_tokens"][sel].cpu().numpy(),
                         inp["proposer_idx"][sel].cpu().numpy(), mode, list(weights),
                         inp["u_accept"][sel].cpu().numpy(), inp["u_resample"][sel].cpu().numpy(),
                         all_positions=all_positions, num_threads=num_threads,
                         temperature=float(inp.get("temperature", 1.0)),
                         bonus_idx=None if bonus is None else bonus[sel].cpu().numpy(),
-                        proposer_pos=None if ppos is None else ppos[sel].cpu().numpy())
+                        proposer_pos=None if ppos is None else ppos[sel].cpu().numpy(),
+                        num_drafts=None if nd is None else nd[sel].cpu().numpy(),
+                        no_bonus=bool(inp.get("no_bonus", False)))
 
 
 def _rel_err(got: np.ndarray, want: np.ndarray) -> float:
@@ -124,17 +128,24 @@ def compare(inp: Dict[str, torch.Tensor], mode: int, weights: Sequence[float], g
     ppos = None if inp.get("proposer_pos") is None else inp["proposer_pos"].cpu().numpy()[idx]
     bonus = None if inp.get("bonus_idx") is None else inp["bonus_idx"].cpu().numpy()[idx]
     gamma = u_acc.shape[1]
+    # drafts per row: the row's bonus position takes the role of position gamma
+    ndr = np.full(len(idx), gamma) if inp.get("num_drafts") is None else inp["num_drafts"].cpu().numpy()[idx]
     host_lg = None
     rep.rows = len(idx)
     if diag is not None:
         gr = diag.r_at_draft.cpu().numpy()[idx]
         gq = diag.q_at_draft.cpu().numpy()[idx]
         want_r, want_q = ora.r_at_draft, ora.q_at_draft
+        has_draft = np.arange(gamma)[None, :] < ndr[:, None]
+        read = np.ones_like(has_draft)
         w = int(inp.get("stop_window", 0))
         if 0 < w <= gamma:
-            # only the windows up to the one holding the first rejection are read
+            # only the windows up to the one holding the first rejection are read (and written)
             read = np.arange(gamma)[None, :] < ((np.minimum(g_alen, ora.accepted_len) // w + 1) * w)[:, None]
-            gr, gq, want_r, want_q = gr[read], gq[read], want_r[read], want_q[read]
+        if not (np.isnan(gr[read & ~has_draft]).all() and np.isnan(gq[read & ~has_draft]).all()):
+            rep.failures.append("r(d) / q(d) of a position without a draft is not NaN")
+        has_draft &= read
+        gr, gq, want_r, want_q = gr[has_draft], gq[has_draft], want_r[has_draft], want_q[has_draft]
         rep.max_rel_err_r = _rel_err(gr, want_r)
         rep.max_rel_err_q = _rel_err(gq, want_q)
         if rep.max_rel_err_r > PROB_RTOL:
@@ -153,11 +164,11 @@ def compare(inp: Dict[str, torch.Tensor], mode: int, weights: Sequence[float], g
         if g_alen[i] != ora.accepted_len[i]:
             j = int(min(g_alen[i], ora.accepted_len[i]))       # first differing decision
             ratio = ora.ratio[i, j]
-            if j < gamma and abs(u_acc[i, j] - min(1.0, ratio)) < RATIO_TIE and \
+            if j < ndr[i] and abs(u_acc[i, j] - min(1.0, ratio)) < RATIO_TIE and \
                     np.array_equal(g_toks[i, :j], ora.out_tokens[i, :j]):
                 rep.excused_accept_ties += 1
             else:
-                rep.failures.append(where + f" (u={u_acc[i, j] if j < gamma else None}, ratio={ratio})")
+                rep.failures.append(where + f" (u={u_acc[i, j] if j < ndr[i] else None}, ratio={ratio})")
             continue
         j = int(ora.accepted_len[i])
         if not np.array_equal(np.delete(g_toks[i], j), np.delete(ora.out_tokens[i], j)):
@@ -169,8 +180,8 @@ def compare(inp: Dict[str, torch.Tensor], mode: int, weights: Sequence[float], g
             continue
         if host_lg is None:
             host_lg = W.host_logits(lg)
-        residual = j < gamma and not (ora.flags[i] & O.FLAG_RESIDUAL_FALLBACK)
-        pi = int(prop[i]) if (ppos is None or j >= gamma) else int(ppos[i, j])
+        residual = j < ndr[i] and not (ora.flags[i] & O.FLAG_RESIDUAL_FALLBACK)
+        pi = int(prop[i]) if (ppos is None or j >= ndr[i]) else int(ppos[i, j])
         f, _ = _sample_weights_of_row(host_lg, oracle_dtype(lg), i, j, pi, mode, weights, residual,
                                       float(inp.get("temperature", 1.0)),
                                       -1 if bonus is None else int(bonus[i]))

@@ -270,3 +270,127 @@ def test_greedy_ties_go_to_the_lowest_index_and_unsupported_combinations():
     with pytest.raises(C.CosVerifyError):
         C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], C.COS_COMBINE_CONTRASTIVE, [0.5, 0.0],
                      inp["u_accept"], inp["u_resample"], greedy=True, stop_window=1)
+
+
+# ---------------------------------------------------------------------------
+# rows with fewer drafts (num_drafts) and no extra token (no_bonus): what Alg. 2's VERIFY needs
+# ---------------------------------------------------------------------------
+
+def _ragged_inputs(n, B, gamma, V, dtype, seed, no_bonus, mode):
+    """num_drafts cycles through 0..gamma; half the rows accept every draft (u_accept = 0, drafts
+    inside the mask in contrastive mode); every position a correct kernel never reads holds NaN."""
+    inp = _random_inputs(n, B, gamma, V, dtype, seed=seed, std=1.5)
+    inp["u_accept"][::2] = 0.0
+    if mode == C.COS_COMBINE_CONTRASTIVE:
+        top = inp["logits"][0, :, :gamma].float().argmax(-1).to(torch.int32)
+        inp["draft_tokens"][::2] = top[::2]
+    nd = torch.tensor([(b // 2) % (gamma + 1) for b in range(B)], dtype=torch.int32)
+    for b in range(B):
+        inp["logits"][:, b, int(nd[b]) + (0 if no_bonus else 1):] = float("nan")
+        inp["draft_tokens"][b, int(nd[b]):] = V - 1            # ignored
+        inp["u_accept"][b, int(nd[b]):] = 0.0                  # ignored (would accept if it were read)
+    inp["num_drafts"] = nd.cuda()
+    inp["no_bonus"] = no_bonus
+    return inp, nd.numpy()
+
+
+@pytest.mark.parametrize("no_bonus", [False, True])
+@pytest.mark.parametrize("mode,weights,n,dtype", [(C.COS_COMBINE_ENSEMBLE, [0.5, 0.3, 0.2], 3, "bf16"),
+                                                  (C.COS_COMBINE_ENSEMBLE, [0.4, 0.6], 2, "f32"),
+                                                  (C.COS_COMBINE_CONTRASTIVE, [0.5, 0.1], 2, "bf16"),
+                                                  (C.COS_COMBINE_CONTRASTIVE, [0.3, 0.0], 2, "f32")])
+def test_ragged_rows(mode, weights, n, dtype, no_bonus):
+    B, gamma, V = 24, 5, 6007
+    inp, nd = _ragged_inputs(n, B, gamma, V, dtype, seed=300 + n + mode, no_bonus=no_bonus, mode=mode)
+    alen, toks, diag, rep = _check(f"ragged mode={mode} n={n} {dtype} no_bonus={no_bonus}", inp, mode, weights)
+    assert np.all(alen <= nd)
+    full = alen == nd
+    assert full.sum() >= B // 2 and (~full).sum() >= 2
+    drawn = toks[np.arange(B), alen]
+    if no_bonus:
+        assert np.all(drawn[full] == -1) and np.all(drawn[~full] >= 0)
+        assert np.all(diag.sample_mass.cpu().numpy()[full] == 0.0)
+    else:
+        assert np.all(drawn >= 0)
+
+
+def test_ragged_rows_with_every_other_extension():
+    B, gamma, V, n = 20, 4, 9001, 3
+    inp, nd = _ragged_inputs(n, B, gamma, V, "bf16", seed=321, no_bonus=False, mode=C.COS_COMBINE_ENSEMBLE)
+    g = torch.Generator().manual_seed(8)
+    inp["proposer_pos"] = torch.randint(0, n, (B, gamma), generator=g, dtype=torch.int32).cuda()
+    inp["bonus_idx"] = ((inp["proposer_idx"] + 1) % n).to(torch.int32)
+    inp["temperature"] = 0.8
+    for b in range(B):                                           # only the verifier has logits at the bonus position
+        for m in range(n):
+            if m != int(inp["bonus_idx"][b]):
+                inp["logits"][m, b, int(nd[b])] = float("nan")
+    base = _check("ragged + proposer_pos + verifier bonus + T", inp, C.COS_COMBINE_ENSEMBLE, [0.2, 0.5, 0.3])
+    for w in (1, 2, 3):
+        inp["stop_window"] = w
+        alen, toks, _, _ = _check(f"ragged + all, window {w}", inp, C.COS_COMBINE_ENSEMBLE, [0.2, 0.5, 0.3])
+        assert np.array_equal(alen, base[0]) and np.array_equal(toks, base[1])
+
+
+@pytest.mark.parametrize("window", [1, 2, 4])
+@pytest.mark.parametrize("mode,weights,n", [(C.COS_COMBINE_ENSEMBLE, [0.5, 0.5], 2), (C.COS_COMBINE_CONTRASTIVE, [0.5, 0.1], 2)])
+def test_ragged_rows_no_bonus_in_windows(mode, weights, n, window):
+    inp, nd = _ragged_inputs(n, 18, 5, 4099, "bf16", seed=340 + mode, no_bonus=True, mode=mode)
+    inp["stop_window"] = window
+    alen, toks, _, _ = _check(f"ragged no_bonus window={window} mode={mode}", inp, mode, weights)
+    assert (alen == nd).sum() >= 9
+
+
+def test_ragged_acceptance_rates():
+    from oracle import cos_oracle as O
+    B, gamma, V, n = 12, 4, 12007, 3
+    inp, nd = _ragged_inputs(n, B, gamma, V, "bf16", seed=350, no_bonus=True, mode=C.COS_COMBINE_ENSEMBLE)
+    alpha = torch.full((B, gamma), -1.0, dtype=torch.float64, device="cuda")
+    w = [0.2, 0.5, 0.3]
+    alen, toks = C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], C.COS_COMBINE_ENSEMBLE, w,
+                              inp["u_accept"], inp["u_resample"], alpha=alpha, **P._gpu_ext(inp))
+    torch.cuda.synchronize()
+    ora = O.verify(W.host_logits(inp["logits"]), O.DTYPE_BF16, inp["draft_tokens"].cpu().numpy(),
+                   inp["proposer_idx"].cpu().numpy(), C.COS_COMBINE_ENSEMBLE, w, inp["u_accept"].cpu().numpy(),
+                   inp["u_resample"].cpu().numpy(), all_positions=True, want_alpha=True, num_drafts=nd, no_bonus=True)
+    got = alpha.cpu().numpy()
+    has = np.arange(gamma)[None, :] < nd[:, None]
+    assert np.isnan(got[~has]).all() and np.isnan(ora.alpha[~has]).all()
+    assert np.abs(got[has] - ora.alpha[has]).max() < 1e-6
+    assert np.array_equal(alen.cpu().numpy(), ora.accepted_len) and np.array_equal(toks.cpu().numpy(), ora.out_tokens)
+
+
+@pytest.mark.parametrize("no_bonus", [False, True])
+def test_ragged_greedy(no_bonus):
+    from oracle import cos_oracle as O
+    B, gamma, V, mu, a = 21, 4, 33000, 0.5, 0.1
+    inp, host, odt = _greedy_inputs(B, gamma, V, "bf16", seed=360, mu=mu, alpha=a)
+    nd = np.array([(b * 2) % (gamma + 1) for b in range(B)], dtype=np.int32)
+    for b in range(B):
+        inp["logits"][:, b, int(nd[b]) + (0 if no_bonus else 1):] = float("nan")
+    host = W.host_logits(inp["logits"])
+    alen, toks = C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], C.COS_COMBINE_CONTRASTIVE,
+                              [mu, a], inp["u_accept"], inp["u_resample"], greedy=True,
+                              num_drafts=torch.from_numpy(nd).cuda(), no_bonus=no_bonus)
+    torch.cuda.synchronize()
+    st, want_len, want_toks = O.verify_greedy(host, odt, inp["draft_tokens"].cpu().numpy(), [mu, a], num_drafts=nd,
+                                              no_bonus=no_bonus)
+    assert st == 0
+    assert np.array_equal(alen.cpu().numpy(), want_len) and np.array_equal(toks.cpu().numpy(), want_toks)
+    assert (want_len == nd).sum() >= 4 and (want_len < nd).sum() >= 4
+
+
+def test_ragged_rows_at_the_c5_shape():
+    w = W.C5.scaled(B=24)
+    inp = W.generate(w, device="cuda")
+    nd = torch.tensor([b % (w.gamma + 1) for b in range(w.B)], dtype=torch.int32)
+    for b in range(w.B):
+        inp["logits"][:, b, int(nd[b]):] = float("nan")
+    inp["num_drafts"] = nd.cuda()
+    inp["no_bonus"] = True
+    alen, toks, _, _ = _check("c5 shape, ragged, no bonus", inp, w.mode, w.weights)
+    assert np.all(alen <= nd.numpy())
+    base = W.generate(w, device="cuda")
+    full = P.run_gpu(base, w.mode, w.weights)
+    # a shorter row is a prefix of the full row's verification
+    assert np.array_equal(alen, np.minimum(full[0], nd.numpy()))

@@ -48,12 +48,20 @@ def _case(seed):
         inp["stop_window"] = int(rng.integers(1, gamma + 2))
     if rng.integers(0, 3) == 0:
         inp["u_accept"][rng.integers(0, B)] = 0.0
+    if rng.integers(0, 3) == 0:                                  # rows with fewer drafts; what follows is never read
+        nd = rng.integers(0, gamma + 1, B).astype(np.int32)
+        inp["num_drafts"] = torch.from_numpy(nd).cuda()
+        for b in range(B):
+            inp["logits"][:, b, int(nd[b]) + 1:] = float("nan")
+    if rng.integers(0, 4) == 0:
+        inp["no_bonus"] = True
     return inp, mode, weights, dict(n=n, B=B, gamma=gamma, V=V, dtype=dtype, mode=mode,
                                     ext={k: (v if not torch.is_tensor(v) else "tensor") for k, v in inp.items()
-                                         if k in ("temperature", "proposer_pos", "bonus_idx", "stop_window")})
+                                         if k in ("temperature", "proposer_pos", "bonus_idx", "stop_window",
+                                                  "num_drafts", "no_bonus")})
 
 
-@pytest.mark.parametrize("seed", range(60))
+@pytest.mark.parametrize("seed", range(100))
 def test_random_configuration(seed):
     inp, mode, weights, desc = _case(1000 + seed)
     alen, toks, diag = P.run_gpu(inp, mode, weights)
