@@ -44,6 +44,12 @@ class HashedBigramLM:
         """[B, V] logits of ``model`` after ``contexts`` ([B, L], L >= 2)."""
         return self.tables[model][self.bucket(contexts)]
 
+    def logits_multi(self, models: torch.Tensor, contexts: torch.Tensor) -> torch.Tensor:
+        """[R, V]: logits of ``models[r]`` after ``contexts[r]`` (a different model per row)."""
+        if getattr(self, "_stack", None) is None:
+            self._stack = torch.stack(self.tables)
+        return self._stack[models.to(torch.int64), self.bucket(contexts)]
+
 
 def sample_from_logits(logits: torch.Tensor, u: torch.Tensor) -> torch.Tensor:
     """Eq. (1): one token per row from softmax(logits) by inverse CDF with the uniforms ``u``."""
