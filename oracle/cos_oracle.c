@@ -31,6 +31,8 @@
  *                      sum_{x<=k} f(x) > u*F  (the paper names only the
  *                      distribution; the procedure is this build's)
  *
+ *   logit mix          r = softmax(sum_m beta_m l_m)  (Eq. (3), the logit-level
+ *                      combination C'; decoding-time realignment of Sec. 2)
  *   extensions         cos_oracle_verify_ex: temperature (Sec. 4.1), the
  *                      verifier's own bonus token (Sec. 3.1 / 3.3), a proposer
  *                      per draft position (Alg. 2), the acceptance rate of Eq. (7),
@@ -49,7 +51,8 @@
  * scipy softmax of l/T and exactly pre-scaled logits, the bonus law s_v by
  * searchsorted and chi-square, an independent per-position re-derivation, the
  * hand value 13/16 and Eq. (7) for alpha, rows with fewer drafts and the
- * no-extra-token mode against the base step on the truncated tensor.  No
+ * no-extra-token mode against the base step on the truncated tensor, the logit
+ * mix by a hand example, library softmax and its special cases.  No
  * function here is "parity unpinned".
  */
 #include <math.h>
@@ -61,7 +64,7 @@
 #endif
 
 enum { ORACLE_DTYPE_F32 = 0, ORACLE_DTYPE_BF16 = 1 };
-enum { ORACLE_ENSEMBLE = 0, ORACLE_CONTRASTIVE = 1 };
+enum { ORACLE_ENSEMBLE = 0, ORACLE_CONTRASTIVE = 1, ORACLE_LOGIT_MIX = 2 };
 enum {
   ORACLE_OK = 0,
   ORACLE_ERR_NULL = -1,
@@ -173,6 +176,24 @@ int cos_oracle_combine_contrastive(const double *l_p, const double *l_q,
   }
   for (x = 0; x < V; ++x) r[x] /= Zc;
   return count;
+}
+
+/* ---- Eq. (3), logit level: a linear combination of the models' logits ----- */
+/* c(x) = sum_m beta_m l_m(x), r = softmax(c): the form of decoding-time
+ * realignment (Sec. 2), of logit-level ensembles (beta_m = 1/n), and of Eq. (5)
+ * without its mask (beta = (1, -mu)).  l is [n][V] row-major.  Models with
+ * beta_m == 0 take no part (so their logits may be -inf).  c is summed in
+ * model order.                                                              */
+void cos_oracle_combine_logit_mix(const double *l, const double *beta, int n, int V,
+                                  double *r) {
+  int x, m;
+  for (x = 0; x < V; ++x) {
+    double c = 0.0;
+    for (m = 0; m < n; ++m)
+      if (beta[m] != 0.0) c += beta[m] * l[(size_t)m * V + x];
+    r[x] = c; /* softmax in place below */
+  }
+  cos_oracle_softmax(r, V, r);
 }
 
 /* ---- temperature 0 (greedy decoding, the T = 0 runs of Sec. 4.1) ---------- */
@@ -289,6 +310,11 @@ static int check_weights(int mode, int n, const double *w) {
     if (!(w[1] >= 0.0 && w[1] <= 1.0)) return ORACLE_ERR_WEIGHTS;
     return ORACLE_OK;
   }
+  if (mode == ORACLE_LOGIT_MIX) {
+    for (m = 0; m < n; ++m)
+      if (!isfinite(w[m])) return ORACLE_ERR_WEIGHTS;
+    return ORACLE_OK;
+  }
   return ORACLE_ERR_MODE;
 }
 
@@ -298,7 +324,8 @@ static int check_weights(int mode, int n, const double *w) {
  * draft_tokens  [B][gamma]   proposal tokens (Eq. 1), each in [0, V)
  * proposer_idx  [B]          which model's softmax is q for that row
  * mode/weights  ensemble: w[0..n-1];  contrastive (n == 2, model 0 = expert,
- *               model 1 = amateur): w[0] = mu, w[1] = alpha_cd
+ *               model 1 = amateur): w[0] = mu, w[1] = alpha_cd;  logit mix:
+ *               beta[0..n-1], any finite values
  * u_accept      [B][gamma]   uniforms in [0,1) for Eq. (6)
  * u_resample    [B]          one uniform in [0,1) for the residual or bonus draw
  * accepted_len  out [B]      number of accepted drafts, in [0, gamma]
@@ -450,6 +477,8 @@ int cos_oracle_verify_ex(const void *logits, int dtype, int n, int B, int gamma,
           memcpy(r, s + (size_t)bonus_from * V, sizeof(double) * (size_t)V);
         } else if (mode == ORACLE_ENSEMBLE) {
           cos_oracle_combine_ensemble(s, weights, n, V, r);
+        } else if (mode == ORACLE_LOGIT_MIX) {
+          cos_oracle_combine_logit_mix(l, weights, n, V, r);
         } else {
           cos_oracle_combine_contrastive(l, l + V, weights[0], weights[1], V, r);
         }

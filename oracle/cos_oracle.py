@@ -22,6 +22,7 @@ DTYPE_F32 = 0
 DTYPE_BF16 = 1
 ENSEMBLE = 0
 CONTRASTIVE = 1
+LOGIT_MIX = 2
 FLAG_RESIDUAL_FALLBACK = 1
 FLAG_TAIL_CLAMP = 2
 
@@ -59,6 +60,8 @@ def _load():
         lib.cos_oracle_softmax.restype = None
         lib.cos_oracle_combine_ensemble.argtypes = [dp, dp, ci, ci, dp]
         lib.cos_oracle_combine_ensemble.restype = None
+        lib.cos_oracle_combine_logit_mix.argtypes = [dp, dp, ci, ci, dp]
+        lib.cos_oracle_combine_logit_mix.restype = None
         lib.cos_oracle_combine_contrastive.argtypes = [dp, dp, ctypes.c_double, ctypes.c_double, ci, dp]
         lib.cos_oracle_combine_contrastive.restype = ci
         lib.cos_oracle_accept.argtypes = [ctypes.c_double, ctypes.c_double, ctypes.c_double, dp]
@@ -243,6 +246,17 @@ def verify(logits: np.ndarray, dtype: int, draft_tokens, proposer_idx, mode: int
         _dp(res.ratio), _dp(res.sample_mass), _dp(res.cdf_lo), _dp(res.cdf_hi), _ip(res.flags),
         int(all_positions), int(num_threads), ctypes.byref(opt))
     return res
+
+
+def combine_logit_mix(l, beta):
+    """l [n][V] logits, beta [n]: softmax of the linear combination of the logits."""
+    l = _f64(l)
+    beta = _f64(beta)
+    n, V = l.shape
+    assert beta.shape == (n,)
+    r = np.empty(V)
+    _load().cos_oracle_combine_logit_mix(_dp(l), _dp(beta), n, V, _dp(r))
+    return r
 
 
 def argmax_contrastive(l_p, l_q, mu: float, alpha_cd: float) -> int:

@@ -382,3 +382,62 @@ def test_num_drafts_argument_checks():
     drafts2 = drafts.copy()
     drafts2[0, 1] = 999
     assert O.verify(logits, O.DTYPE_F32, drafts2, proposer, O.ENSEMBLE, [0.5, 0.5], ua, ur, num_drafts=[1, 2, 2]).status == 0
+
+
+# ---- logit-level linear combination (Eq. (3), C' on logits) ------------------------------------
+
+def test_logit_mix_hand_example_library_softmax_and_special_cases():
+    import os
+    from fractions import Fraction
+    g = {}
+    with open(os.path.join(os.path.dirname(__file__), "golden", "logit_mix_hand.txt")) as fh:
+        for line in fh:
+            line = line.split("#")[0].strip()
+            if line:
+                key, vals = line.split(":")
+                g[key.strip()] = np.array([float(Fraction(v)) for v in vals.split()])
+    l = np.log(np.stack([g["p0"], g["p1"]]))
+    assert np.allclose(O.combine_logit_mix(l, g["beta_a"]), g["r_a"], rtol=1e-14)
+    assert np.allclose(O.combine_logit_mix(l, g["beta_b"]), g["r_b"], rtol=1e-14)
+    rng = _rng(60)
+    n, V = 4, 300
+    l = rng.standard_normal((n, V)) * 3
+    beta = np.array([0.7, -0.3, 1.1, 0.25])
+    assert np.allclose(O.combine_logit_mix(l, beta), special.softmax(beta @ l), rtol=1e-12)      # library softmax
+    for m in range(n):                                                                         # one-hot: that model
+        assert np.array_equal(O.combine_logit_mix(l, np.eye(n)[m]), O.softmax(l[m]))
+    # uniform 1/n: the normalised geometric mean of the models' distributions
+    s = np.stack([O.softmax(x) for x in l])
+    geo = np.exp(np.log(s).mean(axis=0))
+    assert np.allclose(O.combine_logit_mix(l, np.full(n, 1 / n)), geo / geo.sum(), rtol=1e-12)
+    # (1, -mu) is Eq. (5) without its mask, bit for bit
+    for mu in (0.1, 0.5, 1.0):
+        assert np.array_equal(O.combine_logit_mix(l[:2], [1.0, -mu]), O.combine_contrastive(l[0], l[1], mu, 0.0)[0])
+    # a model with beta = 0 takes no part, whatever its logits
+    l2 = l.copy()
+    l2[1] = -np.inf
+    assert np.array_equal(O.combine_logit_mix(l2, [0.5, 0.0, 0.2, 0.3]), O.combine_logit_mix(l, [0.5, 0.0, 0.2, 0.3]))
+    # a token one model rules out (positive weight) has probability 0
+    l3 = l.copy()
+    l3[2, 7] = -np.inf
+    assert O.combine_logit_mix(l3, [0.5, 0.1, 0.2, 0.3])[7] == 0.0
+
+
+def test_logit_mix_whole_step_equals_contrastive_without_mask_and_checks_arguments():
+    rng = _rng(61)
+    logits, drafts, proposer, ua, ur = _inputs(rng, 2, 300, 3, 40, std=1.0)
+    a = O.verify(logits, O.DTYPE_F32, drafts, proposer, O.LOGIT_MIX, [1.0, -0.5], ua, ur, all_positions=True, want_alpha=True)
+    b = O.verify(logits, O.DTYPE_F32, drafts, proposer, O.CONTRASTIVE, [0.5, 0.0], ua, ur, all_positions=True, want_alpha=True)
+    assert a.status == 0 and b.status == 0
+    assert np.array_equal(a.out_tokens, b.out_tokens) and np.array_equal(a.r_at_draft, b.r_at_draft)
+    assert np.array_equal(a.alpha, b.alpha) and len(set(a.accepted_len.tolist())) == 4
+    # one-hot on the proposer: r == q, everything accepted; one-hot on the other model: textbook speculative sampling
+    onehot = O.verify(logits, O.DTYPE_F32, drafts, np.zeros(300, dtype=np.int32), O.LOGIT_MIX, [1.0, 0.0], ua, ur)
+    assert np.all(onehot.accepted_len == 3)
+    sd = O.verify(logits, O.DTYPE_F32, drafts, np.zeros(300, dtype=np.int32), O.LOGIT_MIX, [0.0, 1.0], ua, ur)
+    ens = O.verify(logits, O.DTYPE_F32, drafts, np.zeros(300, dtype=np.int32), O.ENSEMBLE, [0.0, 1.0], ua, ur)
+    assert np.array_equal(sd.out_tokens, ens.out_tokens)
+    assert O.verify(logits, O.DTYPE_F32, drafts, proposer, O.LOGIT_MIX, [1.0, float("inf")], ua, ur).status == -5
+    assert O.verify(logits, O.DTYPE_F32, drafts, proposer, 3, [1.0, 0.5], ua, ur).status == -4
+    three = _inputs(rng, 3, 10, 2, 20)
+    assert O.verify(three[0], O.DTYPE_F32, three[1], three[2], O.LOGIT_MIX, [0.5, 0.7, -0.2], three[3], three[4]).status == 0

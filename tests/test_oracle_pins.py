@@ -288,6 +288,8 @@ def _step_dists(logits, b, j, pi, mode, weights):
     s = np.stack([O.softmax(x) for x in l])
     if mode == O.ENSEMBLE:
         r = O.combine_ensemble(s, weights)
+    elif mode == O.LOGIT_MIX:
+        r = O.combine_logit_mix(np.stack(l), weights)
     else:
         r, _ = O.combine_contrastive(l[0], l[1], weights[0], weights[1])
     return s[pi], r
@@ -297,12 +299,15 @@ def _step_dists(logits, b, j, pi, mode, weights):
 # App. A.1: the output law equals r  (pin (a))
 # --------------------------------------------------------------------------
 
-@pytest.mark.parametrize("mode", [O.ENSEMBLE, O.CONTRASTIVE])
+_LAW_WEIGHTS = {O.ENSEMBLE: [0.35, 0.65], O.CONTRASTIVE: [0.5, 0.1], O.LOGIT_MIX: [1.3, -0.4]}
+
+
+@pytest.mark.parametrize("mode", [O.ENSEMBLE, O.CONTRASTIVE, O.LOGIT_MIX])
 def test_output_law_exact_enumeration_V8(mode):
     """P(x) = sum_x' q(x') [a(x') 1{x = x'} + (1 - a(x')) res(x)] must equal r(x)."""
     rng = _rng(41 + mode)
     V, gamma, n = 8, 3, 2
-    weights = np.array([0.35, 0.65]) if mode == O.ENSEMBLE else np.array([0.5, 0.1])
+    weights = np.array(_LAW_WEIGHTS[mode])
     logits = (rng.standard_normal((n, 1, gamma + 1, V)) * 2).astype(np.float32)
     for pi in range(n):
         for j in range(gamma):
@@ -320,13 +325,13 @@ def test_output_law_exact_enumeration_V8(mode):
             assert abs(p_reject - F) < 1e-12         # App. A.1: P(reject) = sum max(r - q, 0)
 
 
-@pytest.mark.parametrize("mode", [O.ENSEMBLE, O.CONTRASTIVE])
+@pytest.mark.parametrize("mode", [O.ENSEMBLE, O.CONTRASTIVE, O.LOGIT_MIX])
 def test_output_law_chi_square_monte_carlo_V8_gamma3(mode):
     """10^6 seeded trials through the full step: tokens at position k (given it was
     reached) follow r_k, and the bonus token follows r_gamma."""
     rng = _rng(51 + mode)
     V, gamma, n, B = 8, 3, 2, 1_000_000
-    weights = np.array([0.4, 0.6]) if mode == O.ENSEMBLE else np.array([0.5, 0.1])
+    weights = np.array({O.ENSEMBLE: [0.4, 0.6], O.CONTRASTIVE: [0.5, 0.1], O.LOGIT_MIX: [0.7, 0.6]}[mode])
     row = (rng.standard_normal((n, 1, gamma + 1, V)) * 1.5).astype(np.float32)
     logits = np.ascontiguousarray(np.broadcast_to(row, (n, B, gamma + 1, V)))
     pi = 1
