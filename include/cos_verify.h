@@ -34,7 +34,18 @@ extern "C" {
 
 typedef enum { COS_DTYPE_F32 = 0, COS_DTYPE_BF16 = 1 } cos_dtype_t;
 
-typedef enum { COS_COMBINE_ENSEMBLE = 0, COS_COMBINE_CONTRASTIVE = 1 } cos_combine_t;
+/* How the models' outputs become the target distribution r (Eq. (3)):
+ *   ENSEMBLE     probability level, Eq. (4): r = sum_m w_m softmax(l_m)
+ *   CONTRASTIVE  logit level, Eq. (5): r = softmax(l_0 - mu l_1) over the
+ *                plausibility mask of the expert (n == 2)
+ *   LOGIT_MIX    logit level, linear: r = softmax(sum_m beta_m l_m) -- the form
+ *                of decoding-time realignment (Sec. 2), of logit-level ensembles
+ *                (beta_m = 1/n) and of Eq. (5) without its mask (beta = (1, -mu)) */
+typedef enum {
+  COS_COMBINE_ENSEMBLE = 0,
+  COS_COMBINE_CONTRASTIVE = 1,
+  COS_COMBINE_LOGIT_MIX = 2
+} cos_combine_t;
 
 typedef enum {
   COS_OK = 0,
@@ -42,7 +53,8 @@ typedef enum {
   COS_ERR_SHAPE = -2,       /* n, B, gamma or V out of the supported range */
   COS_ERR_DTYPE = -3,
   COS_ERR_MODE = -4,        /* unknown combine mode, or contrastive with n != 2 */
-  COS_ERR_WEIGHTS = -5,     /* ensemble: w < 0 or |sum w - 1| > 1e-9; contrastive: mu not finite or alpha_cd outside [0,1] */
+  COS_ERR_WEIGHTS = -5,     /* ensemble: w < 0 or |sum w - 1| > 1e-9; contrastive: mu not finite or alpha_cd outside [0,1];
+                               logit mix: a beta that is not finite */
   COS_ERR_WORKSPACE = -6,   /* workspace NULL, misaligned (256 B) or smaller than cos_verify_workspace_bytes() */
   COS_ERR_ALIGN = -7,       /* logits pointer not aligned to its element size */
   COS_ERR_LAUNCH = -8,      /* a HIP call failed (no usable GPU, launch error) */
@@ -86,7 +98,11 @@ size_t cos_verify_workspace_bytes(int n, int B, int gamma, int V, cos_dtype_t dt
  * combine_mode  ensemble or contrastive.
  * weights       HOST.  ensemble: w[0..n-1].  contrastive (n must be 2; model 0
  *               is the expert l^p, model 1 the amateur l^q): weights[0] = mu,
- *               weights[1] = alpha_cd in [0,1].
+ *               weights[1] = alpha_cd in [0,1].  logit mix: beta[0..n-1], any
+ *               finite values; a model with beta_m = 0 takes no part in r (its
+ *               logits still give q when it proposes); a -inf logit under a
+ *               positive beta_m gives probability 0, under a negative one the
+ *               outputs are undefined.
  * u_accept      DEVICE, [B][gamma] float64 in [0,1).
  * u_resample    DEVICE, [B] float64 in [0,1): used for the one draw of the row
  *               (residual or bonus).

@@ -21,6 +21,7 @@ COS_DTYPE_F32 = 0
 COS_DTYPE_BF16 = 1
 COS_COMBINE_ENSEMBLE = 0
 COS_COMBINE_CONTRASTIVE = 1
+COS_COMBINE_LOGIT_MIX = 2
 COS_OK = 0
 COS_FLAG_RESIDUAL_FALLBACK = 1
 COS_FLAG_TAIL_CLAMP = 2

@@ -57,6 +57,11 @@ constexpr int kMaxAlphaBlocks = 64;         // acceptance-rate workgroups per (s
 // counters serialise on one channel and slow every stream that crosses it).
 constexpr int kCtrStride = 32;  // ints between two counters (one 128-byte line each)
 
+// Combine modes as template arguments.
+constexpr int kEns = 0;  // Eq. (4): r = sum_m w_m softmax(l_m)
+constexpr int kCd = 1;   // Eq. (5) with the plausibility mask
+constexpr int kMix = 2;  // Eq. (3), logit level: r = softmax(sum_m beta_m l_m)
+
 // One partial softmax statistic: Z = sum_x 2^(l(x)*log2e - o) over a chunk.
 struct Partial {
   double Z;
@@ -115,6 +120,7 @@ struct Params {
   double w[COS_MAX_MODELS];  // ensemble weights; contrastive: w[0] = mu, w[1] = alpha_cd
   float scale;               // log2(e) / temperature: logits times this are base-2 exponents
   float mu_hi, mu_lo;        // mu split into two floats
+  float beta_hi[COS_MAX_MODELS], beta_lo[COS_MAX_MODELS];  // logit mix: beta_m split into two floats
   float thr32;               // smallest float >= T ln(alpha_cd)
   double thr64;              // T ln(alpha_cd)
   cos_diag_t diag;
@@ -539,8 +545,9 @@ struct DecideShared {
 // Decides the window [j0, j0+nj) of a sequence that no earlier window has
 // decided.  The sequence stays undecided if every draft of the window is
 // accepted and the window does not contain the bonus position.
-template <typename T, bool CONTRASTIVE>
+template <typename T, int MODE>
 __device__ void decide_sequence(const Params& p, int b, DecideShared& sh) {
+  constexpr bool CONTRASTIVE = MODE == kCd;
   const int tid = threadIdx.x;
   const int g1 = p.gamma + 1;
   const int nstat = p.nstat;
@@ -588,7 +595,15 @@ __device__ void decide_sequence(const Params& p, int b, DecideShared& sh) {
     const int d = p.draft[k];
     const int pi = p.proposer_pos ? p.proposer_pos[k] : p.proposer[b];
     double rd = 0.0, qd = 0.0;
-    if constexpr (!CONTRASTIVE) {
+    if constexpr (MODE == kMix) {
+      // statistic 0: the proposer's row; statistic 1: the mixed logits
+      double c = 0.0;
+      for (int m = 0; m < n; ++m)
+        if (p.w[m] != 0.0) c += p.w[m] * (double)widen(row_ptr<T>(p, m, b, j)[d]);
+      const double lq = (double)widen(row_ptr<T>(p, pi, b, j)[d]);
+      rd = exp2(c * log2e - sh.lse2[jj * nstat + 1]);
+      qd = exp2(lq * log2e - sh.lse2[jj * nstat + 0]);
+    } else if constexpr (MODE == kEns) {
       for (int m = 0; m < n; ++m) {
         const double l = (double)widen(row_ptr<T>(p, m, b, j)[d]);
         const double s = exp2(l * log2e - sh.lse2[jj * nstat + m]);
@@ -716,20 +731,75 @@ __device__ __forceinline__ void eval_f_contrastive(const float (&x0)[N], const f
   }
 }
 
+// Logit mix c = sum_m beta_m l_m with beta_m = hi + lo; models with beta_m == 0
+// take no part.  A -inf logit makes c = -inf (probability 0) instead of the NaN
+// that hi * (-inf) + lo * (-inf) gives when hi and lo differ in sign.
+template <int NCAP>
+__device__ __forceinline__ float mix_one(const Params& p, int n, const float (&l)[NCAP]) {
+  float acc = 0.0f;
+  bool dead = false;
+#pragma unroll
+  for (int m = 0; m < NCAP; ++m)
+    if (m < n && (p.beta_hi[m] != 0.0f || p.beta_lo[m] != 0.0f)) {
+      const bool ninf = l[m] == -INFINITY;
+      dead = dead || ninf;
+      const float v = ninf ? 0.0f : l[m];
+      acc = fmaf(p.beta_lo[m], v, fmaf(p.beta_hi[m], v, acc));
+    }
+  return dead ? -INFINITY : acc;
+}
+
+// Element k of the row of model `sel` (wave-uniform) out of the loaded rows.
+template <int NCAP, int N>
+__device__ __forceinline__ float pick_row(const float (&x)[NCAP][N], int sel, int k) {
+  float v = x[0][k];
+#pragma unroll
+  for (int m = 1; m < NCAP; ++m) v = (m == sel) ? x[m][k] : v;
+  return v;
+}
+
+// Logit mix: r = coef[0] 2^(c*scale - off[0]), q = coef[1] 2^(l_pi*scale - off[1]);
+// f = max(0, r - q) (coef[1] = 0 for a bonus draw from r).
+// plain >= 0 (the verifier's own bonus token): f = coef[1] 2^(l_plain*scale - off[1]).
+template <int NCAP, int N>
+__device__ __forceinline__ void eval_f_mix(const float (&x)[NCAP][N], int n, int pi, int plain,
+                                           const Params& p, const float (&coef)[NCAP],
+                                           const float (&off)[NCAP], float (&f)[N]) {
+  static_assert(NCAP >= 2, "two coefficients");
+  const int qsel = plain >= 0 ? plain : pi;
+#pragma unroll
+  for (int k = 0; k < N; ++k) {
+    const float q = coef[1] * fast_exp2(fmaf(pick_row<NCAP, N>(x, qsel, k), p.scale, -off[1]));
+    if (plain >= 0) {
+      f[k] = q;
+    } else {
+      float l[NCAP];
+#pragma unroll
+      for (int m = 0; m < NCAP; ++m) l[m] = x[m][k];
+      const float r = coef[0] * fast_exp2(fmaf(mix_one<NCAP>(p, n, l), p.scale, -off[0]));
+      f[k] = fmaxf(r - q, 0.0f);
+    }
+  }
+}
+
 // Coefficients and integer offsets of the sampling weights from a sequence's plan.
-template <int NCAP, bool CONTRASTIVE>
+template <int NCAP, int MODE>
 __device__ __forceinline__ void plan_coefficients(const Params& p, const SeqPlan& plan, bool residual,
                                                   int n, float (&coef)[NCAP], float (&off)[NCAP]) {
 #pragma unroll
   for (int m = 0; m < NCAP; ++m) {
     coef[m] = 0.0f;
     off[m] = 0.0f;
-    if (m < n) {
+    if (m < n || (MODE == kMix && m < 2)) {
       double a, lse;
       const bool plain = !residual && plan.bonus >= 0;  // bonus token from one model's softmax alone
-      if constexpr (!CONTRASTIVE) {
+      if constexpr (MODE == kEns) {
         a = plain ? (m == plan.bonus ? 1.0 : 0.0) : p.w[m] - ((residual && m == plan.pi) ? 1.0 : 0.0);
         lse = plan.lse2[m];
+      } else if constexpr (MODE == kMix) {
+        // slot 0: r from the mixed logits (statistic 1); slot 1: q (statistic 0); others unused
+        a = (m == 0) ? (plain ? 0.0 : 1.0) : ((m == 1 && (residual || plain)) ? 1.0 : 0.0);
+        lse = plan.lse2[m == 0 ? 1 : 0];
       } else {
         a = (m == 0) ? 1.0 : ((residual || plain) ? 1.0 : 0.0);
         lse = plan.lse2[m == 0 ? 2 : (plain ? plan.bonus : plan.pi)];
@@ -755,14 +825,16 @@ __device__ __forceinline__ void tile_load(const Params& p, const T* const (&rows
 }
 
 // f of the loaded tile for this lane; 0 past the row's end.
-template <typename T, int NCAP, bool CONTRASTIVE>
+template <typename T, int NCAP, int MODE>
 __device__ __forceinline__ void tile_eval(const Params& p, const float (&x)[NCAP][VecOf<T>::N], int n,
                                           int tile, int pi, int plain, float m0,
                                           const float (&coef)[NCAP], const float (&off)[NCAP],
                                           float (&f)[VecOf<T>::N]) {
   constexpr int N = VecOf<T>::N;
-  if constexpr (!CONTRASTIVE)
+  if constexpr (MODE == kEns)
     eval_f_ensemble<NCAP, N>(x, n, p.scale, coef, off, f);
+  else if constexpr (MODE == kMix)
+    eval_f_mix<NCAP, N>(x, n, pi, plain, p, coef, off, f);
   else
     eval_f_contrastive<T, N>(x[0], x[1], pi, plain, m0, p, coef, off, f);
   if (tile * 64 + lane_id() >= p.nvec) {
@@ -771,14 +843,14 @@ __device__ __forceinline__ void tile_eval(const Params& p, const float (&x)[NCAP
   }
 }
 
-template <typename T, bool ALIGNED, int NCAP, bool CONTRASTIVE>
+template <typename T, bool ALIGNED, int NCAP, int MODE>
 __device__ __forceinline__ void tile_weights(const Params& p, const T* const (&rows)[NCAP], int n,
                                              int tile, int pi, int plain, float m0,
                                              const float (&coef)[NCAP], const float (&off)[NCAP],
                                              float (&f)[VecOf<T>::N]) {
   float x[NCAP][VecOf<T>::N];
   tile_load<T, ALIGNED, NCAP>(p, rows, n, tile, x);
-  tile_eval<T, NCAP, CONTRASTIVE>(p, x, n, tile, pi, plain, m0, coef, off, f);
+  tile_eval<T, NCAP, MODE>(p, x, n, tile, pi, plain, m0, coef, off, f);
 }
 
 template <int N>
@@ -794,7 +866,7 @@ __device__ __forceinline__ double lane_mass(const float (&f)[N]) {
 // workgroup); tile_sum holds the ntiles tile sums in LDS.
 // Returns false if the weights have no mass and may_retry is set.
 // ---------------------------------------------------------------------------
-template <typename T, bool ALIGNED, int NCAP, bool CONTRASTIVE>
+template <typename T, bool ALIGNED, int NCAP, int MODE>
 __device__ bool draw_token(const Params& p, int b, const SeqPlan& plan, const T* const (&rows)[NCAP],
                            int n, const float (&coef)[NCAP], const float (&off)[NCAP],
                            const double* tile_sum, bool may_retry, int flags) {
@@ -850,7 +922,7 @@ __device__ bool draw_token(const Params& p, int b, const SeqPlan& plan, const T*
 
   // the same f values of that one tile, scanned element by element
   float f[N];
-  tile_weights<T, ALIGNED, NCAP, CONTRASTIVE>(p, rows, n, tile, plan.pi, plan.bonus, plan.m0, coef, off, f);
+  tile_weights<T, ALIGNED, NCAP, MODE>(p, rows, n, tile, plan.pi, plan.bonus, plan.m0, coef, off, f);
   const double lane_tot = lane_mass<N>(f);
   const double lincl = wave_inclusive_scan(lane_tot);
   const double lup = __shfl_up(lincl, 1, 64);
@@ -956,7 +1028,7 @@ __global__ void __launch_bounds__(kThreads) ensemble_stats_kernel(Params p) {
     }
   }
   if (arrive_last(p.counters + ((size_t)p.win * p.B + b) * kCtrStride, per_b, &s_flag))
-    decide_sequence<T, false>(p, b, sh);
+    decide_sequence<T, kEns>(p, b, sh);
 }
 
 // Contrastive, kernel 1: partial maxima of the expert row (model 0).
@@ -1039,7 +1111,7 @@ __global__ void __launch_bounds__(kThreads) contrastive_stats_kernel(Params p) {
       wait_stores();
     }
     if (arrive_last(p.counters + ((size_t)p.win * p.B + b) * kCtrStride, per_b, &s_flag))
-      decide_sequence<T, true>(p, b, sh);
+      decide_sequence<T, kCd>(p, b, sh);
     return;
   }
 
@@ -1102,15 +1174,125 @@ __global__ void __launch_bounds__(kThreads) contrastive_stats_kernel(Params p) {
     wait_stores();
   }
   if (arrive_last(p.counters + ((size_t)p.win * p.B + b) * kCtrStride, per_b, &s_flag))
-    decide_sequence<T, true>(p, b, sh);
+    decide_sequence<T, kCd>(p, b, sh);
+}
+
+// Logit mix streaming kernel.  Workgroup index -> (b, j, s); reads the chunk of
+// all n rows once and produces the proposer row's softmax statistic
+// (statistic 0) and the statistic of the mixed logits sum_m beta_m l_m
+// (statistic 1; Eq. (3), logit level).
+template <typename T, bool ALIGNED, int NM>
+__global__ void __launch_bounds__(kThreads) mix_stats_kernel(Params p) {
+  constexpr int N = VecOf<T>::N;
+  constexpr int NCAP = NM ? NM : COS_MAX_MODELS;
+  constexpr int U = NCAP <= 2 ? 4 : (NCAP <= 4 ? 2 : 1);  // vectors per lane and row in flight
+  constexpr int kStep = kThreads * U;
+  __shared__ WaveStat ws[2 * kWaves];
+  __shared__ DecideShared sh;
+  __shared__ int s_flag;
+
+  const int n = NM ? NM : p.n;
+  const int g1 = p.gamma + 1;
+  const int per_b = p.nj * p.S;
+  const int b = blockIdx.x / per_b;
+  if (p.plans[b].jstar >= 0) return;  // decided by an earlier window: nothing more is read
+  int rem = blockIdx.x - b * per_b;
+  const int j = p.j0 + rem / p.S;
+  const int s = rem - (j - p.j0) * p.S;
+  const int tid = threadIdx.x;
+  const int gb = drafts_of(p, b);
+  // Whose softmax statistic this position needs: the proposer's at a draft
+  // position; at the bonus position only a verifier bonus needs one, and then
+  // the mixed logits are not needed.
+  int pi = p.proposer[b];
+  bool plain = false;
+  if (j < gb) {
+    if (p.proposer_pos) pi = p.proposer_pos[(size_t)b * p.gamma + j];
+  } else if (p.bonus_idx && p.bonus_idx[b] >= 0) {
+    pi = p.bonus_idx[b];
+    plain = true;
+  }
+  Partial* out = p.partials + (((size_t)b * g1 + j) * 2) * p.S + s;
+  if (position_unread(p, gb, j)) {  // uniform over the workgroup
+    if (tid == 0) {
+      store_empty_partial(out);
+      store_empty_partial(out + (size_t)p.S);
+      wait_stores();
+    }
+    if (arrive_last(p.counters + ((size_t)p.win * p.B + b) * kCtrStride, per_b, &s_flag))
+      decide_sequence<T, kMix>(p, b, sh);
+    return;
+  }
+
+  const T* rows[NCAP];
+#pragma unroll
+  for (int m = 0; m < NCAP; ++m) rows[m] = row_ptr<T>(p, m < n ? m : 0, b, j);
+  const int v0 = s * p.cv;
+  const int v1 = min(v0 + p.cv, p.nvec);
+  Running rq, rc;  // proposer row; mixed logits
+  running_init(rq);
+  running_init(rc);
+  for (int base = v0; base < v1; base += kStep) {
+    float x[NCAP][U][N];
+    if (base + kStep <= v1) {
+#pragma unroll
+      for (int m = 0; m < NCAP; ++m)
+        if (m < n) load_group<T, ALIGNED, false, U>(rows[m], base, v1, p.V, x[m]);
+    } else {
+#pragma unroll
+      for (int m = 0; m < NCAP; ++m)
+        if (m < n) load_group<T, ALIGNED, true, U>(rows[m], base, v1, p.V, x[m]);
+    }
+    float xq[U][N];
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int k = 0; k < N; ++k) {
+        float v = x[0][u][k];
+#pragma unroll
+        for (int m = 1; m < NCAP; ++m) v = (m == pi) ? x[m][u][k] : v;
+        xq[u][k] = v;
+      }
+    running_add<U, N>(rq, xq, p.scale);
+    if (!plain) {
+      float c[U][N];
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int k = 0; k < N; ++k) {
+          float l[NCAP];
+#pragma unroll
+          for (int m = 0; m < NCAP; ++m) l[m] = x[m][u][k];
+          c[u][k] = mix_one<NCAP>(p, n, l);
+        }
+      running_add<U, N>(rc, c, p.scale);
+    }
+  }
+  const double zq = running_total(rq);
+  const double zc = running_total(rc);
+  publish_wave_stat(ws, 0, rq.o, zq);
+  publish_wave_stat(ws, 1, rc.o, zc);
+  __syncthreads();
+  if (tid == 0) {
+    store_partial(ws, 0, out);
+    if (plain)
+      store_empty_partial(out + (size_t)p.S);
+    else
+      store_partial(ws, 1, out + (size_t)p.S);
+    wait_stores();
+  }
+  if (arrive_last(p.counters + ((size_t)p.win * p.B + b) * kCtrStride, per_b, &s_flag))
+    decide_sequence<T, kMix>(p, b, sh);
 }
 
 // Sampling kernel.  Workgroup index -> (b, c): tiles [c*tpc, (c+1)*tpc) of the
 // sampled position's rows -> tile sums; the last workgroup of b draws the token.
-template <typename T, bool ALIGNED, int NM, bool CONTRASTIVE>
+template <typename T, bool ALIGNED, int NM, int MODE>
 __global__ void __launch_bounds__(kThreads) sample_kernel(Params p) {
   constexpr int N = VecOf<T>::N;
-  constexpr int NCAP = CONTRASTIVE ? 2 : (NM ? NM : COS_MAX_MODELS);
+  constexpr bool CONTRASTIVE = MODE == kCd;
+  // register rows; the logit mix keeps its two coefficients in slots 0 and 1
+  constexpr int NCAP = CONTRASTIVE ? 2 : (NM ? (MODE == kMix && NM < 2 ? 2 : NM) : COS_MAX_MODELS);
   constexpr int TU = NCAP <= 4 ? 4 : 1;  // tiles in flight per wavefront
   extern __shared__ double tile_sum[];
   __shared__ int s_flag;
@@ -1124,13 +1306,13 @@ __global__ void __launch_bounds__(kThreads) sample_kernel(Params p) {
   if (plan.skip) return;  // every draft accepted, no extra token: nothing to draw
   // A verifier bonus reads that one model's row only (the others carry a zero
   // coefficient and may hold anything, so every slot points at the valid row).
-  const bool one_row = !CONTRASTIVE && plan.residual == 0 && plan.bonus >= 0;
+  const bool one_row = MODE == kEns && plan.residual == 0 && plan.bonus >= 0;
   const T* rows[NCAP];
 #pragma unroll
   for (int m = 0; m < NCAP; ++m)
     rows[m] = row_ptr<T>(p, one_row ? plan.bonus : (m < n ? m : 0), b, plan.jstar);
   float coef[NCAP], off[NCAP];
-  plan_coefficients<NCAP, CONTRASTIVE>(p, plan, plan.residual != 0, n, coef, off);
+  plan_coefficients<NCAP, MODE>(p, plan, plan.residual != 0, n, coef, off);
 
   double* sums = p.tile_sums + (size_t)b * p.ntiles;
   const int tb = c * p.tpc;
@@ -1145,7 +1327,7 @@ __global__ void __launch_bounds__(kThreads) sample_kernel(Params p) {
     for (int i = 0; i < TU; ++i) {
       const int ti = t + i * kWaves;
       float f[N];
-      tile_eval<T, NCAP, CONTRASTIVE>(p, x[i], n, min(ti, te - 1), plan.pi, plan.bonus, plan.m0, coef,
+      tile_eval<T, NCAP, MODE>(p, x[i], n, min(ti, te - 1), plan.pi, plan.bonus, plan.m0, coef,
                                       off, f);
       const double ts = wave_sum_to_lane63(lane_mass<N>(f));
       if (lane == 63 && ti < te) tile_sum[ti - tb] = ts;  // staged in LDS
@@ -1162,7 +1344,7 @@ __global__ void __launch_bounds__(kThreads) sample_kernel(Params p) {
   __syncthreads();
   bool done = false;
   if (wave == 0)
-    done = draw_token<T, ALIGNED, NCAP, CONTRASTIVE>(p, b, plan, rows, n, coef, off, tile_sum,
+    done = draw_token<T, ALIGNED, NCAP, MODE>(p, b, plan, rows, n, coef, off, tile_sum,
                                                      plan.residual != 0, 0);
   if (threadIdx.x == 0) s_flag = done ? 0 : 1;
   __syncthreads();
@@ -1170,16 +1352,16 @@ __global__ void __launch_bounds__(kThreads) sample_kernel(Params p) {
 
   // The residual has no mass (cannot happen in exact arithmetic): draw from r
   // itself.  Rare, so this one workgroup recomputes every tile sum.
-  plan_coefficients<NCAP, CONTRASTIVE>(p, plan, false, n, coef, off);
+  plan_coefficients<NCAP, MODE>(p, plan, false, n, coef, off);
   for (int t = wave; t < p.ntiles; t += kWaves) {
     float f[N];
-    tile_weights<T, ALIGNED, NCAP, CONTRASTIVE>(p, rows, n, t, plan.pi, plan.bonus, plan.m0, coef, off, f);
+    tile_weights<T, ALIGNED, NCAP, MODE>(p, rows, n, t, plan.pi, plan.bonus, plan.m0, coef, off, f);
     const double ts = wave_sum(lane_mass<N>(f));
     if (lane == 0) tile_sum[t] = ts;
   }
   __syncthreads();
   if (wave == 0)
-    draw_token<T, ALIGNED, NCAP, CONTRASTIVE>(p, b, plan, rows, n, coef, off, tile_sum, false,
+    draw_token<T, ALIGNED, NCAP, MODE>(p, b, plan, rows, n, coef, off, tile_sum, false,
                                               COS_FLAG_RESIDUAL_FALLBACK);
 }
 
@@ -1316,10 +1498,11 @@ __global__ void __launch_bounds__(kThreads) greedy_contrastive_kernel(Params p) 
 // Acceptance-rate kernel (optional): alpha = sum_x min(q(x), r(x)) of Eq. (7) for
 // every draft position.  Workgroup index -> (b, j, c); a second full read of the
 // draft positions' rows, with the normalisers the streaming kernel left behind.
-template <typename T, bool ALIGNED, int NM, bool CONTRASTIVE>
+template <typename T, bool ALIGNED, int NM, int MODE>
 __global__ void __launch_bounds__(kThreads) acceptance_rate_kernel(Params p) {
   constexpr int N = VecOf<T>::N;
-  constexpr int NCAP = CONTRASTIVE ? 2 : (NM ? NM : COS_MAX_MODELS);
+  constexpr bool CONTRASTIVE = MODE == kCd;
+  constexpr int NCAP = CONTRASTIVE ? 2 : (NM ? (MODE == kMix && NM < 2 ? 2 : NM) : COS_MAX_MODELS);
   __shared__ double wsum[kWaves];
   __shared__ int s_flag;
 
@@ -1342,17 +1525,18 @@ __global__ void __launch_bounds__(kThreads) acceptance_rate_kernel(Params p) {
 
   // r = sum_m cr[m] 2^(l_m*scale - off[m]); q = cq 2^(l_pi*scale - off[pi])   (ensemble)
   // r = [mask] cr[0] 2^(c*scale - off[0]);  q = cq 2^(l_pi*scale - off[1])    (contrastive)
+  // r = cr[0] 2^(mix*scale - off[0]);       q = cq 2^(l_pi*scale - off[1])    (logit mix)
   float cr[NCAP], off[NCAP], cq = 0.0f;
 #pragma unroll
   for (int m = 0; m < NCAP; ++m) {
     cr[m] = 0.0f;
     off[m] = 0.0f;
-    if (m < n) {
-      const double l2 = CONTRASTIVE ? lse[m == 0 ? 2 : pi] : lse[m];
+    if (MODE == kMix ? m < 2 : m < n) {
+      const double l2 = CONTRASTIVE ? lse[m == 0 ? 2 : pi] : (MODE == kMix ? lse[m == 0 ? 1 : 0] : lse[m]);
       const double K = rint(l2);
       const double unit = exp2(K - l2);
       off[m] = (float)K;
-      if constexpr (CONTRASTIVE) {
+      if constexpr (CONTRASTIVE || MODE == kMix) {
         if (m == 0) cr[0] = (float)unit; else cq = (float)unit;
       } else {
         cr[m] = (float)(p.w[m] * unit);
@@ -1374,7 +1558,7 @@ __global__ void __launch_bounds__(kThreads) acceptance_rate_kernel(Params p) {
 #pragma unroll
       for (int k = 0; k < N; ++k) {
         float r = 0.0f, q = 0.0f;
-        if constexpr (!CONTRASTIVE) {
+        if constexpr (MODE == kEns) {
 #pragma unroll
           for (int m = 0; m < NCAP; ++m)
             if (m < n) {
@@ -1382,6 +1566,12 @@ __global__ void __launch_bounds__(kThreads) acceptance_rate_kernel(Params p) {
               r += cr[m] * e;
               if (m == pi) q = cq * e;
             }
+        } else if constexpr (MODE == kMix) {
+          float l[NCAP];
+#pragma unroll
+          for (int m = 0; m < NCAP; ++m) l[m] = x[m][k];
+          r = cr[0] * fast_exp2(fmaf(mix_one<NCAP>(p, n, l), p.scale, -off[0]));
+          q = cq * fast_exp2(fmaf(pick_row<NCAP, N>(x, pi, k), p.scale, -off[1]));
         } else {
           const bool in = in_mask<T>(x[0][k], m0, p.thr32, p.thr64);
           const float cc = contrast(x[0][k], x[1][k], p.mu_hi, p.mu_lo);
@@ -1446,7 +1636,7 @@ void plan_layout(int n, int B, int gamma, int V, cos_dtype_t dt, cos_combine_t m
   const int N = dt == COS_DTYPE_F32 ? 4 : 8;
   pl->nvec = (V + N - 1) / N;
   pl->ntiles = (pl->nvec + 63) / 64;
-  pl->nstat = mode == COS_COMBINE_CONTRASTIVE ? 3 : n;
+  pl->nstat = mode == COS_COMBINE_CONTRASTIVE ? 3 : (mode == COS_COMBINE_LOGIT_MIX ? 2 : n);
   const size_t g1 = (size_t)gamma + 1;
   size_t at = 0;
   pl->off_counters = at;
@@ -1522,53 +1712,71 @@ void choose_sampling(int B, int ntiles, int* C_out, int* tpc_out) {
   *tpc_out = tpc;
 }
 
-template <typename T, bool ALIGNED, bool CONTRASTIVE>
+// Kernels that hold the rows of all n models in registers are specialised for
+// n = 1..4 on the aligned path; everything else takes the generic instance.
+template <typename T, bool ALIGNED, int MODE>
 cos_status_t launch_sampling(const Params& p, size_t lds, hipStream_t st) {
   const long blocks = (long)p.B * p.C;
   if (blocks <= 0 || blocks > 0x7fffffffL) return COS_ERR_SHAPE;
   const dim3 grid((unsigned)blocks), block(kThreads);
-  if constexpr (CONTRASTIVE) {
-    hipLaunchKernelGGL((sample_kernel<T, ALIGNED, 2, true>), grid, block, lds, st, p);
+  if constexpr (MODE == kCd) {
+    hipLaunchKernelGGL((sample_kernel<T, ALIGNED, 2, kCd>), grid, block, lds, st, p);
   } else if constexpr (ALIGNED) {
     switch (p.n) {
-      case 1: hipLaunchKernelGGL((sample_kernel<T, true, 1, false>), grid, block, lds, st, p); break;
-      case 2: hipLaunchKernelGGL((sample_kernel<T, true, 2, false>), grid, block, lds, st, p); break;
-      case 3: hipLaunchKernelGGL((sample_kernel<T, true, 3, false>), grid, block, lds, st, p); break;
-      case 4: hipLaunchKernelGGL((sample_kernel<T, true, 4, false>), grid, block, lds, st, p); break;
-      default: hipLaunchKernelGGL((sample_kernel<T, true, 0, false>), grid, block, lds, st, p); break;
+      case 1: hipLaunchKernelGGL((sample_kernel<T, true, 1, MODE>), grid, block, lds, st, p); break;
+      case 2: hipLaunchKernelGGL((sample_kernel<T, true, 2, MODE>), grid, block, lds, st, p); break;
+      case 3: hipLaunchKernelGGL((sample_kernel<T, true, 3, MODE>), grid, block, lds, st, p); break;
+      case 4: hipLaunchKernelGGL((sample_kernel<T, true, 4, MODE>), grid, block, lds, st, p); break;
+      default: hipLaunchKernelGGL((sample_kernel<T, true, 0, MODE>), grid, block, lds, st, p); break;
     }
   } else {
-    hipLaunchKernelGGL((sample_kernel<T, false, 0, false>), grid, block, lds, st, p);
+    hipLaunchKernelGGL((sample_kernel<T, false, 0, MODE>), grid, block, lds, st, p);
   }
   return hipGetLastError() == hipSuccess ? COS_OK : COS_ERR_LAUNCH;
 }
 
-template <typename T, bool ALIGNED, bool CONTRASTIVE>
+template <typename T, bool ALIGNED, int MODE>
 cos_status_t launch_acceptance_rate(const Params& p, hipStream_t st) {
   const long blocks = (long)p.B * p.gamma * p.CA;
   if (blocks <= 0 || blocks > 0x7fffffffL) return COS_ERR_SHAPE;
   const dim3 grid((unsigned)blocks), block(kThreads);
-  if constexpr (CONTRASTIVE) {
-    hipLaunchKernelGGL((acceptance_rate_kernel<T, ALIGNED, 2, true>), grid, block, 0, st, p);
+  if constexpr (MODE == kCd) {
+    hipLaunchKernelGGL((acceptance_rate_kernel<T, ALIGNED, 2, kCd>), grid, block, 0, st, p);
   } else if constexpr (ALIGNED) {
     switch (p.n) {
-      case 1: hipLaunchKernelGGL((acceptance_rate_kernel<T, true, 1, false>), grid, block, 0, st, p); break;
-      case 2: hipLaunchKernelGGL((acceptance_rate_kernel<T, true, 2, false>), grid, block, 0, st, p); break;
-      case 3: hipLaunchKernelGGL((acceptance_rate_kernel<T, true, 3, false>), grid, block, 0, st, p); break;
-      case 4: hipLaunchKernelGGL((acceptance_rate_kernel<T, true, 4, false>), grid, block, 0, st, p); break;
-      default: hipLaunchKernelGGL((acceptance_rate_kernel<T, true, 0, false>), grid, block, 0, st, p); break;
+      case 1: hipLaunchKernelGGL((acceptance_rate_kernel<T, true, 1, MODE>), grid, block, 0, st, p); break;
+      case 2: hipLaunchKernelGGL((acceptance_rate_kernel<T, true, 2, MODE>), grid, block, 0, st, p); break;
+      case 3: hipLaunchKernelGGL((acceptance_rate_kernel<T, true, 3, MODE>), grid, block, 0, st, p); break;
+      case 4: hipLaunchKernelGGL((acceptance_rate_kernel<T, true, 4, MODE>), grid, block, 0, st, p); break;
+      default: hipLaunchKernelGGL((acceptance_rate_kernel<T, true, 0, MODE>), grid, block, 0, st, p); break;
     }
   } else {
-    hipLaunchKernelGGL((acceptance_rate_kernel<T, false, 0, false>), grid, block, 0, st, p);
+    hipLaunchKernelGGL((acceptance_rate_kernel<T, false, 0, MODE>), grid, block, 0, st, p);
   }
   return hipGetLastError() == hipSuccess ? COS_OK : COS_ERR_LAUNCH;
+}
+
+template <typename T, bool ALIGNED>
+void launch_mix_stats(const Params& p, dim3 grid, hipStream_t st) {
+  const dim3 block(kThreads);
+  if constexpr (ALIGNED) {
+    switch (p.n) {
+      case 1: hipLaunchKernelGGL((mix_stats_kernel<T, true, 1>), grid, block, 0, st, p); break;
+      case 2: hipLaunchKernelGGL((mix_stats_kernel<T, true, 2>), grid, block, 0, st, p); break;
+      case 3: hipLaunchKernelGGL((mix_stats_kernel<T, true, 3>), grid, block, 0, st, p); break;
+      case 4: hipLaunchKernelGGL((mix_stats_kernel<T, true, 4>), grid, block, 0, st, p); break;
+      default: hipLaunchKernelGGL((mix_stats_kernel<T, true, 0>), grid, block, 0, st, p); break;
+    }
+  } else {
+    hipLaunchKernelGGL((mix_stats_kernel<T, false, 0>), grid, block, 0, st, p);
+  }
 }
 
 // All launches of one call after the fill kernel.  `window` positions are
 // verified per streaming launch; sequences decided by an earlier window are
 // skipped by every later one (their workgroups return at once).
 template <typename T, bool ALIGNED>
-cos_status_t launch_all(Params p, bool contrastive, int window, size_t lds, hipStream_t st,
+cos_status_t launch_all(Params p, int mode, int window, size_t lds, hipStream_t st,
                         hipEvent_t ev_start, hipEvent_t ev_stop) {
   const dim3 block(kThreads);
   const int g1 = p.gamma + 1;
@@ -1577,11 +1785,13 @@ cos_status_t launch_all(Params p, bool contrastive, int window, size_t lds, hipS
   for (int j0 = 0; j0 < g1; j0 += window, ++p.win) {
     p.j0 = j0;
     p.nj = (j0 + window <= g1) ? window : g1 - j0;
-    const long blocks = (long)p.B * p.nj * (contrastive ? 1 : p.n) * p.S;
+    const long blocks = (long)p.B * p.nj * (mode == kEns ? p.n : 1) * p.S;
     if (blocks <= 0 || blocks > 0x7fffffffL) return COS_ERR_SHAPE;
     const dim3 grid((unsigned)blocks);
-    if (!contrastive) {
+    if (mode == kEns) {
       hipLaunchKernelGGL((ensemble_stats_kernel<T, ALIGNED>), grid, block, 0, st, p);
+    } else if (mode == kMix) {
+      launch_mix_stats<T, ALIGNED>(p, grid, st);
     } else {
       hipLaunchKernelGGL((expert_rowmax_kernel<T, ALIGNED>), grid, block, 0, st, p);
       hipLaunchKernelGGL((contrastive_stats_kernel<T, ALIGNED>), grid, block, 0, st, p);
@@ -1589,11 +1799,13 @@ cos_status_t launch_all(Params p, bool contrastive, int window, size_t lds, hipS
     if (hipGetLastError() != hipSuccess) return COS_ERR_LAUNCH;
   }
   if (ev_stop) (void)hipEventRecord(ev_stop, st);
-  cos_status_t rc = contrastive ? launch_sampling<T, ALIGNED, true>(p, lds, st)
-                                : launch_sampling<T, ALIGNED, false>(p, lds, st);
+  cos_status_t rc = mode == kEns   ? launch_sampling<T, ALIGNED, kEns>(p, lds, st)
+                    : mode == kMix ? launch_sampling<T, ALIGNED, kMix>(p, lds, st)
+                                   : launch_sampling<T, ALIGNED, kCd>(p, lds, st);
   if (rc != COS_OK || !p.alpha) return rc;
-  return contrastive ? launch_acceptance_rate<T, ALIGNED, true>(p, st)
-                     : launch_acceptance_rate<T, ALIGNED, false>(p, st);
+  return mode == kEns   ? launch_acceptance_rate<T, ALIGNED, kEns>(p, st)
+         : mode == kMix ? launch_acceptance_rate<T, ALIGNED, kMix>(p, st)
+                        : launch_acceptance_rate<T, ALIGNED, kCd>(p, st);
 }
 
 }  // namespace
@@ -1604,12 +1816,13 @@ size_t cos_verify_workspace_bytes(int n, int B, int gamma, int V, cos_dtype_t dt
                                   cos_combine_t mode) {
   if (!shape_ok(n, B, gamma, V)) return 0;
   if (dt != COS_DTYPE_F32 && dt != COS_DTYPE_BF16) return 0;
-  if (mode != COS_COMBINE_ENSEMBLE && mode != COS_COMBINE_CONTRASTIVE) return 0;
+  if (mode != COS_COMBINE_ENSEMBLE && mode != COS_COMBINE_CONTRASTIVE && mode != COS_COMBINE_LOGIT_MIX)
+    return 0;
   // Sized for one-position windows (stop_window = 1), which split rows the most.
   Plan pl;
   const int N = dt == COS_DTYPE_F32 ? 4 : 8;
   int S, cv;
-  choose_split((mode == COS_COMBINE_CONTRASTIVE ? 1 : n) * (B > 0 ? B : 1), (V + N - 1) / N, &S, &cv);
+  choose_split((mode == COS_COMBINE_ENSEMBLE ? n : 1) * (B > 0 ? B : 1), (V + N - 1) / N, &S, &cv);
   plan_layout(n, B, gamma, V, dt, mode, S, &pl);
   return pl.bytes < 256 ? 256 : pl.bytes;
 }
@@ -1651,12 +1864,18 @@ cos_status_t cos_verify_ex(const void* logits, cos_dtype_t dt, int n, int B, int
   }
   if (!shape_ok(n, B, gamma, V)) return COS_ERR_SHAPE;
   if (dt != COS_DTYPE_F32 && dt != COS_DTYPE_BF16) return COS_ERR_DTYPE;
-  if (combine_mode != COS_COMBINE_ENSEMBLE && combine_mode != COS_COMBINE_CONTRASTIVE)
+  if (combine_mode != COS_COMBINE_ENSEMBLE && combine_mode != COS_COMBINE_CONTRASTIVE &&
+      combine_mode != COS_COMBINE_LOGIT_MIX)
     return COS_ERR_MODE;
   const bool contrastive = combine_mode == COS_COMBINE_CONTRASTIVE;
+  const bool mix = combine_mode == COS_COMBINE_LOGIT_MIX;
+  const int mode = contrastive ? kCd : (mix ? kMix : kEns);
   if (contrastive && n != 2) return COS_ERR_MODE;
   if (!weights) return COS_ERR_NULL;
-  if (!contrastive) {
+  if (mix) {
+    for (int m = 0; m < n; ++m)
+      if (!std::isfinite(weights[m])) return COS_ERR_WEIGHTS;
+  } else if (!contrastive) {
     double sum = 0.0;
     for (int m = 0; m < n; ++m) {
       if (!(weights[m] >= 0.0) || !std::isfinite(weights[m])) return COS_ERR_WEIGHTS;
@@ -1676,14 +1895,14 @@ cos_status_t cos_verify_ex(const void* logits, cos_dtype_t dt, int n, int B, int
   const size_t need = cos_verify_workspace_bytes(n, B, gamma, V, dt, combine_mode);
   if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256 || workspace_bytes < need)
     return COS_ERR_WORKSPACE;
-  if ((size_t)(gamma + 1) * (contrastive ? 3 : n) > kMaxStatsPerSeq) return COS_ERR_SHAPE;
+  if ((size_t)(gamma + 1) * (contrastive ? 3 : (mix ? 2 : n)) > kMaxStatsPerSeq) return COS_ERR_SHAPE;
 
   // ---- launch plan ----
   const int N = dt == COS_DTYPE_F32 ? 4 : 8;
   const int nvec = (V + N - 1) / N;
   int window = gamma + 1;  // positions per streaming launch
   if (options && options->stop_window > 0 && options->stop_window < window) window = options->stop_window;
-  const int rows_total = (contrastive ? 1 : n) * B * window;
+  const int rows_total = (mode == kEns ? n : 1) * B * window;
   int S, cv;
   choose_split(rows_total, nvec, &S, &cv);
   Plan pl;
@@ -1730,6 +1949,10 @@ cos_status_t cos_verify_ex(const void* logits, cos_dtype_t dt, int n, int B, int
   for (int m = 0; m < COS_MAX_MODELS; ++m) p.w[m] = m < n ? weights[m] : 0.0;
   p.scale = (float)((double)kLog2e / temperature);
   p.mu_hi = p.mu_lo = 0.0f;
+  for (int m = 0; m < COS_MAX_MODELS; ++m) {
+    p.beta_hi[m] = (mix && m < n) ? (float)weights[m] : 0.0f;
+    p.beta_lo[m] = (mix && m < n) ? (float)(weights[m] - (double)p.beta_hi[m]) : 0.0f;
+  }
   p.thr32 = -INFINITY;
   p.thr64 = -INFINITY;
   if (contrastive) {
@@ -1799,11 +2022,11 @@ cos_status_t cos_verify_ex(const void* logits, cos_dtype_t dt, int n, int B, int
 
   cos_status_t rc;
   if (dt == COS_DTYPE_F32)
-    rc = aligned ? launch_all<float, true>(p, contrastive, window, lds, st, ev_start, ev_stop)
-                 : launch_all<float, false>(p, contrastive, window, lds, st, ev_start, ev_stop);
+    rc = aligned ? launch_all<float, true>(p, mode, window, lds, st, ev_start, ev_stop)
+                 : launch_all<float, false>(p, mode, window, lds, st, ev_start, ev_stop);
   else
-    rc = aligned ? launch_all<uint16_t, true>(p, contrastive, window, lds, st, ev_start, ev_stop)
-                 : launch_all<uint16_t, false>(p, contrastive, window, lds, st, ev_start, ev_stop);
+    rc = aligned ? launch_all<uint16_t, true>(p, mode, window, lds, st, ev_start, ev_stop)
+                 : launch_all<uint16_t, false>(p, mode, window, lds, st, ev_start, ev_stop);
   if (profile) ++g_ev_recorded;
   return rc;
 }

@@ -108,6 +108,8 @@ def _sample_weights_of_row(host_lg, dtype, b, j, pi, mode, weights, residual, te
     s = np.stack([O.softmax(x) for x in l])
     if mode == O.ENSEMBLE:
         r = O.combine_ensemble(s, np.asarray(weights, dtype=np.float64))
+    elif mode == O.LOGIT_MIX:
+        r = O.combine_logit_mix(np.stack(l), np.asarray(weights, dtype=np.float64))
     else:
         r, _ = O.combine_contrastive(l[0], l[1], weights[0], weights[1])
     return O.sample_weights(r, s[pi], residual)

@@ -69,3 +69,27 @@ def test_random_configuration(seed):
     print(f"[fuzz] {desc}: {rep.summary()}", flush=True)
     assert rep.ok, (desc, rep.failures[:3])
     assert rep.excused_accept_ties + rep.excused_cdf_ties <= 1, (desc, rep.summary())
+
+
+@pytest.mark.parametrize("seed", range(50))
+def test_random_logit_mix_configuration(seed):
+    """The same random shapes and extensions with the logit-level linear combination (Eq. (3))."""
+    inp, _, _, desc = _case(5000 + seed)
+    rng = np.random.default_rng(9000 + seed)
+    n = desc["n"]
+    beta = rng.normal(0.0, 0.8, n)
+    beta[rng.integers(0, n)] = float(rng.choice([1.0, 0.5, 1.5]))        # at least one clearly positive weight
+    if n > 1 and rng.integers(0, 3) == 0:
+        beta[rng.integers(0, n)] = 0.0                                   # a model that takes no part
+    if torch.isinf(inp["logits"]).any():
+        beta = np.abs(beta)                                              # -inf logits need non-negative weights
+    if rng.integers(0, 2):                                               # drafts the mix likes, so that some are accepted
+        c = sum(float(beta[m]) * inp["logits"][m, :, :desc["gamma"]].float() for m in range(n) if beta[m] != 0)
+        keep = torch.from_numpy(rng.integers(0, 2, c.shape[:2]).astype(bool)).cuda()
+        inp["draft_tokens"] = torch.where(keep, c.argmax(-1).to(torch.int32), inp["draft_tokens"]).contiguous()
+    desc["mode"], desc["beta"] = C.COS_COMBINE_LOGIT_MIX, beta.round(3).tolist()
+    alen, toks, diag = P.run_gpu(inp, C.COS_COMBINE_LOGIT_MIX, beta.tolist())
+    rep = P.compare(inp, C.COS_COMBINE_LOGIT_MIX, beta.tolist(), alen, toks, diag)
+    print(f"[fuzz] {desc}: {rep.summary()}", flush=True)
+    assert rep.ok, (desc, rep.failures[:3])
+    assert rep.excused_accept_ties + rep.excused_cdf_ties <= 1, (desc, rep.summary())
