@@ -754,7 +754,10 @@ template <int NCAP, int N>
 __device__ __forceinline__ float pick_row(const float (&x)[NCAP][N], int sel, int k) {
   float v = x[0][k];
 #pragma unroll
-  for (int m = 1; m < NCAP; ++m) v = (m == sel) ? x[m][k] : v;
+  for (int m = 1; m < NCAP; ++m) {
+    const float xm = x[m][k];  // read first: a select of values, never of addresses (which would
+    v = (m == sel) ? xm : v;   // force the rows out of registers)
+  }
   return v;
 }
 
@@ -802,7 +805,8 @@ __device__ __forceinline__ void plan_coefficients(const Params& p, const SeqPlan
         lse = plan.lse2[m == 0 ? 1 : 0];
       } else {
         a = (m == 0) ? 1.0 : ((residual || plain) ? 1.0 : 0.0);
-        lse = plan.lse2[m == 0 ? 2 : (plain ? plan.bonus : plan.pi)];
+        const double lse_q0 = plan.lse2[0], lse_q1 = plan.lse2[1];  // values first, then the choice
+        lse = m == 0 ? plan.lse2[2] : ((plain ? plan.bonus : plan.pi) ? lse_q1 : lse_q0);
       }
       if (a != 0.0) {  // a model without weight may have no statistic at all (lse = -inf)
         const double K = rint(lse);
@@ -1250,7 +1254,10 @@ __global__ void __launch_bounds__(kThreads) mix_stats_kernel(Params p) {
       for (int k = 0; k < N; ++k) {
         float v = x[0][u][k];
 #pragma unroll
-        for (int m = 1; m < NCAP; ++m) v = (m == pi) ? x[m][u][k] : v;
+        for (int m = 1; m < NCAP; ++m) {
+          const float xm = x[m][u][k];
+          v = (m == pi) ? xm : v;
+        }
         xq[u][k] = v;
       }
     running_add<U, N>(rq, xq, p.scale);
