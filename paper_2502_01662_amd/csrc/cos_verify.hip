@@ -121,6 +121,7 @@ struct Params {
   float scale;               // log2(e) / temperature: logits times this are base-2 exponents
   float mu_hi, mu_lo;        // mu split into two floats
   float beta_hi[COS_MAX_MODELS], beta_lo[COS_MAX_MODELS];  // logit mix: beta_m split into two floats
+  int masked;                // contrastive: alpha_cd > 0 (else no row-max pass runs and m0 is taken as 0)
   float thr32;               // smallest float >= T ln(alpha_cd)
   double thr64;              // T ln(alpha_cd)
   cos_diag_t diag;
@@ -578,8 +579,8 @@ __device__ void decide_sequence(const Params& p, int b, DecideShared& sh) {
     // written by the row-max kernel, an earlier launch on the same stream
     const float* rm = p.rowmax + ((size_t)b * g1 + j0 + tid) * p.S;
     float m0 = -INFINITY;
-    for (int s = 0; s < p.S; ++s) m0 = fmaxf(m0, rm[s]);
-    sh.rowmax[tid] = m0;
+    for (int s = 0; s < p.S && p.masked; ++s) m0 = fmaxf(m0, rm[s]);
+    sh.rowmax[tid] = p.masked ? m0 : 0.0f;
   }
   __syncthreads();
 
@@ -1123,13 +1124,14 @@ __global__ void __launch_bounds__(kThreads) contrastive_stats_kernel(Params p) {
   {
     const float* rm = p.rowmax + ((size_t)b * g1 + j) * p.S;
     float lm = -INFINITY;
-    for (int i = tid; i < p.S; i += kThreads) lm = fmaxf(lm, rm[i]);
+    for (int i = tid; i < p.S && p.masked; i += kThreads) lm = fmaxf(lm, rm[i]);
     const float wm = wave_max(lm);
     if (lane_id() == 0) s_m0[tid >> 6] = wm;
     __syncthreads();
   }
   float m0 = s_m0[0];
   for (int w = 1; w < kWaves; ++w) m0 = fmaxf(m0, s_m0[w]);
+  if (!p.masked) m0 = 0.0f;  // no mask: every finite expert logit is in
 
   const T* row0 = row_ptr<T>(p, 0, b, j);
   const T* row1 = row_ptr<T>(p, 1, b, j);
@@ -1417,13 +1419,14 @@ __global__ void __launch_bounds__(kThreads) greedy_contrastive_kernel(Params p) 
   {
     const float* rm = p.rowmax + ((size_t)b * g1 + j) * p.S;
     float lm = -INFINITY;
-    for (int i = tid; i < p.S; i += kThreads) lm = fmaxf(lm, rm[i]);
+    for (int i = tid; i < p.S && p.masked; i += kThreads) lm = fmaxf(lm, rm[i]);
     const float wm = wave_max(lm);
     if (lane_id() == 0) s_m0[tid >> 6] = wm;
     __syncthreads();
   }
   float m0 = s_m0[0];
   for (int w = 1; w < kWaves; ++w) m0 = fmaxf(m0, s_m0[w]);
+  if (!p.masked) m0 = 0.0f;  // no mask: every finite expert logit is in
 
   const T* row0 = row_ptr<T>(p, 0, b, j);
   const T* row1 = row_ptr<T>(p, 1, b, j);
@@ -1800,7 +1803,8 @@ cos_status_t launch_all(Params p, int mode, int window, size_t lds, hipStream_t 
     } else if (mode == kMix) {
       launch_mix_stats<T, ALIGNED>(p, grid, st);
     } else {
-      hipLaunchKernelGGL((expert_rowmax_kernel<T, ALIGNED>), grid, block, 0, st, p);
+      // alpha_cd = 0 is Eq. (5) as printed: no mask, so no pass for the expert maxima
+      if (p.masked) hipLaunchKernelGGL((expert_rowmax_kernel<T, ALIGNED>), grid, block, 0, st, p);
       hipLaunchKernelGGL((contrastive_stats_kernel<T, ALIGNED>), grid, block, 0, st, p);
     }
     if (hipGetLastError() != hipSuccess) return COS_ERR_LAUNCH;
@@ -1962,6 +1966,7 @@ cos_status_t cos_verify_ex(const void* logits, cos_dtype_t dt, int n, int B, int
   }
   p.thr32 = -INFINITY;
   p.thr64 = -INFINITY;
+  p.masked = (contrastive && weights[1] > 0.0) ? 1 : 0;
   if (contrastive) {
     p.mu_hi = (float)weights[0];
     p.mu_lo = (float)(weights[0] - (double)p.mu_hi);
@@ -2005,18 +2010,18 @@ cos_status_t cos_verify_ex(const void* logits, cos_dtype_t dt, int n, int B, int
     if (profile) (void)hipEventRecord(ev_start, st);
     if (dt == COS_DTYPE_F32) {
       if (aligned) {
-        hipLaunchKernelGGL((expert_rowmax_kernel<float, true>), grid, block, 0, st, p);
+        if (p.masked) hipLaunchKernelGGL((expert_rowmax_kernel<float, true>), grid, block, 0, st, p);
         hipLaunchKernelGGL((greedy_contrastive_kernel<float, true>), grid, block, 0, st, p);
       } else {
-        hipLaunchKernelGGL((expert_rowmax_kernel<float, false>), grid, block, 0, st, p);
+        if (p.masked) hipLaunchKernelGGL((expert_rowmax_kernel<float, false>), grid, block, 0, st, p);
         hipLaunchKernelGGL((greedy_contrastive_kernel<float, false>), grid, block, 0, st, p);
       }
     } else {
       if (aligned) {
-        hipLaunchKernelGGL((expert_rowmax_kernel<uint16_t, true>), grid, block, 0, st, p);
+        if (p.masked) hipLaunchKernelGGL((expert_rowmax_kernel<uint16_t, true>), grid, block, 0, st, p);
         hipLaunchKernelGGL((greedy_contrastive_kernel<uint16_t, true>), grid, block, 0, st, p);
       } else {
-        hipLaunchKernelGGL((expert_rowmax_kernel<uint16_t, false>), grid, block, 0, st, p);
+        if (p.masked) hipLaunchKernelGGL((expert_rowmax_kernel<uint16_t, false>), grid, block, 0, st, p);
         hipLaunchKernelGGL((greedy_contrastive_kernel<uint16_t, false>), grid, block, 0, st, p);
       }
     }

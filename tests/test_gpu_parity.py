@@ -233,6 +233,37 @@ def test_workspace_can_be_reused_and_holds_garbage():
     _report("reused workspace", rep)
 
 
+def test_contrastive_without_mask_needs_no_expert_maxima():
+    """alpha_cd = 0 (Eq. (5) as printed) runs no pass for the expert maxima: a workspace full of NaN bit
+    patterns must not matter, with the acceptance rates and at temperature 0 as well."""
+    from oracle import cos_oracle as O
+    B, gamma, V = 6, 3, 33000
+    inp = _random_inputs(2, B, gamma, V, "bf16", seed=71, std=2.0)
+    top = (inp["logits"][0, :, :gamma].float() - 0.5 * inp["logits"][1, :, :gamma].float()).argmax(-1).to(torch.int32)
+    inp["draft_tokens"][::2] = top[::2]
+    ws = C.allocate_workspace(2, B, gamma, V, C.COS_DTYPE_BF16, C.COS_COMBINE_CONTRASTIVE, "cuda")
+    ws.fill_(0xFF)
+    diag = C.Diagnostics.allocate(B, gamma, "cuda")
+    alpha = torch.empty((B, gamma), dtype=torch.float64, device="cuda")
+    alen, toks = C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], C.COS_COMBINE_CONTRASTIVE,
+                              [0.5, 0.0], inp["u_accept"], inp["u_resample"], workspace=ws, diag=diag, alpha=alpha)
+    torch.cuda.synchronize()
+    rep = P.compare(inp, C.COS_COMBINE_CONTRASTIVE, [0.5, 0.0], alen.cpu().numpy(), toks.cpu().numpy(), diag)
+    _report("contrastive, no mask, poisoned workspace", rep)
+    assert len(set(alen.cpu().numpy().tolist())) >= 2
+    ora = O.verify(W.host_logits(inp["logits"]), O.DTYPE_BF16, inp["draft_tokens"].cpu().numpy(),
+                   inp["proposer_idx"].cpu().numpy(), O.CONTRASTIVE, [0.5, 0.0], inp["u_accept"].cpu().numpy(),
+                   inp["u_resample"].cpu().numpy(), all_positions=True, want_alpha=True)
+    assert np.abs(alpha.cpu().numpy() - ora.alpha).max() < 1e-6
+    ws.fill_(0xFF)
+    alen, toks = C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], C.COS_COMBINE_CONTRASTIVE,
+                              [0.5, 0.0], inp["u_accept"], inp["u_resample"], workspace=ws, greedy=True)
+    torch.cuda.synchronize()
+    st, want_len, want_toks = O.verify_greedy(W.host_logits(inp["logits"]), O.DTYPE_BF16,
+                                              inp["draft_tokens"].cpu().numpy(), [0.5, 0.0])
+    assert st == 0 and np.array_equal(alen.cpu().numpy(), want_len) and np.array_equal(toks.cpu().numpy(), want_toks)
+
+
 def test_non_default_stream():
     inp = W.generate(W.C1, device="cuda")
     s = torch.cuda.Stream()
