@@ -558,22 +558,42 @@ __device__ void decide_sequence(const Params& p, int b, DecideShared& sh) {
   const int gb = drafts_of(p, b);
   const double log2e = (double)p.scale;  // log2(e) / T, the same constant the streaming kernel used
 
-  // 1. combine the chunk partials of every (position, statistic) of the window in float64
-  if (tid < nrows) {
-    const Partial* pp = p.partials + (((size_t)b * g1 + j0) * nstat + tid) * p.S;
-    int omax = kNoOffset;
-    for (int s = 0; s < p.S; ++s) {
-      const double z = load_agent(&pp[s].Z);
-      const int o = load_agent(&pp[s].o);
-      if (z > 0.0 && o > omax) omax = o;
+  // 1. combine the chunk partials of every (position, statistic) of the window in float64.
+  //    A group of G lanes (a power of two >= S, at most a wavefront) shares the S partials of
+  //    one statistic, so that a row cut into many chunks (small batches) costs a few dependent
+  //    loads, not S of them; with whole rows (S = 1) it is one thread per statistic.
+  {
+    int G = 1;
+    while (G < p.S && G < 64) G <<= 1;
+    const int per_pass = kThreads / G;
+    const int gl = tid & (G - 1);
+    for (int r0 = 0; r0 < nrows; r0 += per_pass) {  // uniform trip count: every lane shuffles
+      const int r = r0 + tid / G;
+      int omax = kNoOffset;
+      double zsum = 0.0;  // sum of Z 2^(o - omax) over the partials seen by this lane
+      if (r < nrows) {
+        const Partial* pp = p.partials + (((size_t)b * g1 + j0) * nstat + r) * p.S;
+        for (int s = gl; s < p.S; s += G) {
+          const double z = load_agent(&pp[s].Z);
+          const int o = load_agent(&pp[s].o);
+          if (z > 0.0) {
+            if (o > omax) {
+              zsum = ldexp(zsum, omax - o);  // exact: a power of two
+              omax = o;
+            }
+            zsum += ldexp(z, o - omax);
+          }
+        }
+      }
+      for (int d = G >> 1; d >= 1; d >>= 1) {
+        const int oo = __shfl_xor(omax, d, 64);
+        const double zz = __shfl_xor(zsum, d, 64);
+        const int om = max(omax, oo);
+        zsum = (zsum > 0.0 ? ldexp(zsum, omax - om) : 0.0) + (zz > 0.0 ? ldexp(zz, oo - om) : 0.0);
+        omax = om;
+      }
+      if (r < nrows && gl == 0) sh.lse2[r] = (zsum > 0.0) ? (double)omax + log2(zsum) : -INFINITY;
     }
-    double zsum = 0.0;
-    for (int s = 0; s < p.S; ++s) {
-      const double z = load_agent(&pp[s].Z);
-      const int o = load_agent(&pp[s].o);
-      if (z > 0.0) zsum += ldexp(z, o - omax);
-    }
-    sh.lse2[tid] = (zsum > 0.0) ? (double)omax + log2(zsum) : -INFINITY;
   }
   if (CONTRASTIVE && tid < nj) {
     // written by the row-max kernel, an earlier launch on the same stream
@@ -1684,6 +1704,8 @@ void choose_split(int rows_total, int nvec, int* S_out, int* cv_out) {
     long s_want = (3072 + rows_total - 1) / (rows_total > 0 ? rows_total : 1);
     if (s_want < 1) s_want = 1;
     cv = (int)((nvec + s_want - 1) / s_want);
+    // never less than one full group of loads per thread: shorter chunks only add hand-offs
+    if (cv < kThreads * kUnroll) cv = kThreads * kUnroll;
   }
   cv = (cv + kThreads - 1) / kThreads * kThreads;
   if (cv < kThreads) cv = kThreads;
