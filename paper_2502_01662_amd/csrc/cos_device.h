@@ -1,0 +1,342 @@
+// cos_device.h -- constants, the structures shared by the kernels, wavefront and
+// hand-off primitives, logit loads and the logit-level combinations (gfx950).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+
+#include "cos_verify.h"
+
+namespace {
+
+
+constexpr int kThreads = 256;  // 4 wavefronts of 64 lanes
+constexpr int kWaves = kThreads / 64;
+constexpr int kUnroll = 8;  // 16-byte loads in flight per lane and iteration
+constexpr float kLog2e = 1.44269504088896340736f;
+constexpr int kNoOffset = -(1 << 29);       // "no finite element seen yet"
+constexpr float kMaxOffset = 268435456.0f;  // 2^28: clamp for absurd logits
+constexpr int kMaxSplits = 128;             // upper bound on chunks per row (workspace sizing)
+constexpr int kMaxStatsPerSeq = 256;        // (gamma+1) * statistics per position
+constexpr int kMaxTiles = 4096;             // tiles per row the final scan can hold in LDS
+constexpr int kMaxAlphaBlocks = 64;         // acceptance-rate workgroups per (sequence, position)
+// Arrival counters are agent-scope atomics executed at the memory side; one
+// counter per 128-byte line spreads them over the memory channels (packed
+// counters serialise on one channel and slow every stream that crosses it).
+constexpr int kCtrStride = 32;  // ints between two counters (one 128-byte line each)
+
+// Combine modes as template arguments.
+constexpr int kEns = 0;  // Eq. (4): r = sum_m w_m softmax(l_m)
+constexpr int kCd = 1;   // Eq. (5) with the plausibility mask
+constexpr int kMix = 2;  // Eq. (3), logit level: r = softmax(sum_m beta_m l_m)
+
+// One partial softmax statistic: Z = sum_x 2^(l(x)*log2e - o) over a chunk.
+struct Partial {
+  double Z;
+  int o;
+  int pad;
+};
+
+// What the streaming kernel leaves for the sampling kernel, per sequence.
+struct SeqPlan {
+  int jstar;     // position that is sampled = accepted_len
+  int residual;  // 1: f = max(0, r - q); 0: f = r (bonus)
+  int pi;        // proposer of the sampled position
+  int bonus;     // >= 0: the bonus token is drawn from this model's softmax alone (jstar == gamma)
+  float m0;      // contrastive: expert maximum at jstar
+  int skip;      // 1: every draft accepted and no extra token wanted: nothing is sampled
+  double lse2[COS_MAX_MODELS];  // log2-sum-exp2 of the statistics at jstar
+};
+
+struct Params {
+  const void* logits;
+  int n, B, gamma, V;
+  const int* draft;
+  const int* proposer;
+  const int* proposer_pos;  // optional [B][gamma]: proposer of each draft position
+  const int* bonus_idx;     // optional [B]: model the bonus token is drawn from (-1: from r)
+  const int* num_drafts;    // optional [B]: drafts of each row (NULL: gamma everywhere)
+  int no_bonus;             // 1: no extra token when every draft is accepted
+  const double* u_accept;
+  const double* u_resample;
+  int* accepted_len;
+  int* out_tokens;
+  // workspace
+  int* counters;      // (stride kCtrStride) [gamma+1 windows][B] streaming arrivals, [B] sampling
+                      // arrivals, [B][gamma] acceptance-rate arrivals
+  Partial* partials;  // [B][gamma+1][nstat][S]
+  float* rowmax;      // contrastive: [B][gamma+1][S] partial maxima of the expert row
+  SeqPlan* plans;     // [B]
+  double* tile_sums;  // [B][ntiles]
+  // acceptance-rate output (optional)
+  double* alpha;           // [B][gamma] out, or NULL
+  double* lse_all;         // [B][gamma+1][nstat] log2-sum-exp2 of every position
+  float* rowmax_all;       // contrastive: [B][gamma+1] expert maxima
+  double* alpha_partials;  // [B][gamma][CA]
+  int CA;                  // acceptance-rate workgroups per (sequence, position)
+  int tpa;                 // tiles per acceptance-rate workgroup
+  int S;              // chunks per row
+  int cv;             // vectors per chunk
+  int nvec;           // 16-byte vectors per row (last may be partial when unaligned)
+  int ntiles;         // tiles (64 vectors) per row
+  int nstat;          // statistics per position: n (ensemble) or 3 (contrastive)
+  int C;              // sampling workgroups per sequence
+  int tpc;            // tiles per sampling workgroup
+  int j0;             // first position of this launch's window
+  int nj;             // positions in this launch's window (gamma+1: the whole step in one launch)
+  int win;            // window index (selects the arrival counters)
+  double w[COS_MAX_MODELS];  // ensemble weights; contrastive: w[0] = mu, w[1] = alpha_cd
+  float scale;               // log2(e) / temperature: logits times this are base-2 exponents
+  float mu_hi, mu_lo;        // mu split into two floats
+  float beta_hi[COS_MAX_MODELS], beta_lo[COS_MAX_MODELS];  // logit mix: beta_m split into two floats
+  int masked;                // contrastive: alpha_cd > 0 (else no row-max pass runs and m0 is taken as 0)
+  float thr32;               // smallest float >= T ln(alpha_cd)
+  double thr64;              // T ln(alpha_cd)
+  cos_diag_t diag;
+};
+
+// Drafts of row b; position drafts_of(p, b) plays the bonus position's role.
+__device__ __forceinline__ int drafts_of(const Params& p, int b) {
+  return p.num_drafts ? p.num_drafts[b] : p.gamma;
+}
+
+// Positions after the row's bonus position are never read, and neither is the
+// bonus position itself when no extra token is wanted.
+__device__ __forceinline__ bool position_unread(const Params& p, int gb, int j) {
+  return j > gb || (j == gb && p.no_bonus);
+}
+
+// ---------------------------------------------------------------------------
+// wavefront and hand-off primitives
+// ---------------------------------------------------------------------------
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
+
+// max over the 64 lanes, returned wave-uniform.  DPP row shifts reduce each row
+// of 16 lanes into its lane 15, two row broadcasts carry the result to lane 63.
+__device__ __forceinline__ float wave_max(float v) {
+#define COS_DPP_MAX(ctrl, row_mask)                                                        \
+  {                                                                                        \
+    const int t = __builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), ctrl, \
+                                              row_mask, 0xf, false);                      \
+    v = fmaxf(v, __int_as_float(t));                                                       \
+  }
+  COS_DPP_MAX(0x111, 0xf)  // row_shr:1
+  COS_DPP_MAX(0x112, 0xf)  // row_shr:2
+  COS_DPP_MAX(0x114, 0xf)  // row_shr:4
+  COS_DPP_MAX(0x118, 0xf)  // row_shr:8
+  COS_DPP_MAX(0x142, 0xa)  // row_bcast:15 into rows 1 and 3
+  COS_DPP_MAX(0x143, 0xc)  // row_bcast:31 into rows 2 and 3
+#undef COS_DPP_MAX
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+  return v;
+}
+
+// Sum over the 64 lanes with DPP moves (no LDS traffic); the total is valid in
+// lane 63 only.
+__device__ __forceinline__ double wave_sum_to_lane63(double v) {
+#define COS_DPP_DSUM(ctrl, row_mask)                                                            \
+  {                                                                                             \
+    const long long bits = __double_as_longlong(v);                                             \
+    const int lo = __builtin_amdgcn_update_dpp(0, (int)bits, ctrl, row_mask, 0xf, false);       \
+    const int hi = __builtin_amdgcn_update_dpp(0, (int)(bits >> 32), ctrl, row_mask, 0xf, false); \
+    v += __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);                        \
+  }
+  COS_DPP_DSUM(0x111, 0xf)  // row_shr:1  (lanes without a source add +0.0)
+  COS_DPP_DSUM(0x112, 0xf)  // row_shr:2
+  COS_DPP_DSUM(0x114, 0xf)  // row_shr:4
+  COS_DPP_DSUM(0x118, 0xf)  // row_shr:8
+  COS_DPP_DSUM(0x142, 0xa)  // row_bcast:15 into rows 1 and 3
+  COS_DPP_DSUM(0x143, 0xc)  // row_bcast:31 into rows 2 and 3
+#undef COS_DPP_DSUM
+  return v;
+}
+
+__device__ __forceinline__ double wave_inclusive_scan(double v) {
+  const int lane = lane_id();
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const double y = __shfl_up(v, d, 64);
+    if (lane >= d) v += y;
+  }
+  return v;
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+template <typename U>
+__device__ __forceinline__ void store_agent(U* p, U v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+template <typename U>
+__device__ __forceinline__ U load_agent(const U* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Wait until this wavefront's outstanding stores have completed.
+__device__ __forceinline__ void wait_stores() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// Last-arrival test.  Every wavefront must have called wait_stores() after its
+// hand-off stores.  Returns true in every thread of exactly one workgroup per
+// counter: the one that arrives after all `total` workgroups have published.
+__device__ __forceinline__ bool arrive_last(int* counter, int total, int* s_flag) {
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const int prev = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    *s_flag = (prev == total - 1);
+  }
+  __syncthreads();
+  return *s_flag != 0;
+}
+
+// ---------------------------------------------------------------------------
+// 16-byte vector loads of logits, widened to float32
+// ---------------------------------------------------------------------------
+
+template <typename T>
+struct VecOf {
+  static constexpr int N = 16 / sizeof(T);
+};
+
+// Every logit is read once per pass: 16-byte loads carry the non-temporal hint,
+// which measurably raises the sustained read rate of a streaming kernel here.
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_stream16(const void* p) {
+  const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+__device__ __forceinline__ float widen(float x) { return x; }
+__device__ __forceinline__ float widen(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+
+template <typename T>
+__device__ __forceinline__ void unpack(const uint4& raw, float (&x)[VecOf<T>::N]);
+
+template <>
+__device__ __forceinline__ void unpack<float>(const uint4& raw, float (&x)[4]) {
+  x[0] = __uint_as_float(raw.x);
+  x[1] = __uint_as_float(raw.y);
+  x[2] = __uint_as_float(raw.z);
+  x[3] = __uint_as_float(raw.w);
+}
+
+// bf16 is the upper half of a float32; the lower address is the low half-word.
+template <>
+__device__ __forceinline__ void unpack<uint16_t>(const uint4& raw, float (&x)[8]) {
+  x[0] = __uint_as_float(raw.x << 16);
+  x[1] = __uint_as_float(raw.x & 0xffff0000u);
+  x[2] = __uint_as_float(raw.y << 16);
+  x[3] = __uint_as_float(raw.y & 0xffff0000u);
+  x[4] = __uint_as_float(raw.z << 16);
+  x[5] = __uint_as_float(raw.z & 0xffff0000u);
+  x[6] = __uint_as_float(raw.w << 16);
+  x[7] = __uint_as_float(raw.w & 0xffff0000u);
+}
+
+// Vector `vec` of a row.  ALIGNED: the row is 16-byte aligned and V is a
+// multiple of the vector width, so every vector is one full 16-byte load.
+// Otherwise element loads with a bound check; elements past V read as -inf.
+// The caller guarantees 0 <= vec < ceil(V / N).
+template <typename T, bool ALIGNED>
+__device__ __forceinline__ void load_vec(const T* __restrict__ row, int vec, int V,
+                                         float (&x)[VecOf<T>::N]) {
+  constexpr int N = VecOf<T>::N;
+  if constexpr (ALIGNED) {
+    const uint4 raw = load_stream16(row + (size_t)vec * N);
+    unpack<T>(raw, x);
+  } else {
+    const int base = vec * N;
+#pragma unroll
+    for (int k = 0; k < N; ++k) x[k] = (base + k < V) ? widen(row[base + k]) : -INFINITY;
+  }
+}
+
+// U vectors per lane starting at `base` (stride kThreads), all loads issued
+// before any use.  GUARDED: vectors at or past v1 read as -inf; their loads are
+// redirected to the in-range vector v1 - 1 so nothing is out of bounds.
+template <typename T, bool ALIGNED, bool GUARDED, int U>
+__device__ __forceinline__ void load_group(const T* __restrict__ row, int base, int v1, int V,
+                                           float (&x)[U][VecOf<T>::N]) {
+  constexpr int N = VecOf<T>::N;
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int v = base + u * kThreads + (int)threadIdx.x;
+    load_vec<T, ALIGNED>(row, GUARDED ? min(v, v1 - 1) : v, V, x[u]);
+  }
+  if constexpr (GUARDED) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int v = base + u * kThreads + (int)threadIdx.x;
+      if (v >= v1) {
+#pragma unroll
+        for (int k = 0; k < N; ++k) x[u][k] = -INFINITY;
+      }
+    }
+  }
+}
+
+template <typename T>
+__device__ __forceinline__ const T* row_ptr(const Params& p, int m, int b, int j) {
+  const size_t row = ((size_t)m * p.B + b) * (size_t)(p.gamma + 1) + j;
+  return reinterpret_cast<const T*>(p.logits) + row * (size_t)p.V;
+}
+
+
+// ---------------------------------------------------------------------------
+// logit-level combinations shared by the streaming and the sampling kernels
+// ---------------------------------------------------------------------------
+
+// Contrastive logit c = l_0 - mu*l_1 with mu = mu_hi + mu_lo.
+__device__ __forceinline__ float contrast(float l0, float l1, float mu_hi, float mu_lo) {
+  return fmaf(-mu_lo, l1, fmaf(-mu_hi, l1, l0));
+}
+
+// Plausibility mask: l_0 - max l_0 >= ln(alpha_cd), and a finite expert logit.
+// bf16 differences are exact in float32; float32 inputs compare in float64.
+template <typename T>
+__device__ __forceinline__ bool in_mask(float l0, float m0, float thr32, double thr64) {
+  if constexpr (sizeof(T) == 2) {
+    return (l0 > -INFINITY) && (l0 - m0 >= thr32);
+  } else {
+    return (l0 > -INFINITY) && ((double)l0 - (double)m0 >= thr64);
+  }
+}
+
+// Logit mix c = sum_m beta_m l_m with beta_m = hi + lo; models with beta_m == 0
+// take no part.  A -inf logit makes c = -inf (probability 0) instead of the NaN
+// that hi * (-inf) + lo * (-inf) gives when hi and lo differ in sign.
+template <int NCAP>
+__device__ __forceinline__ float mix_one(const Params& p, int n, const float (&l)[NCAP]) {
+  float acc = 0.0f;
+  bool dead = false;
+#pragma unroll
+  for (int m = 0; m < NCAP; ++m)
+    if (m < n && (p.beta_hi[m] != 0.0f || p.beta_lo[m] != 0.0f)) {
+      const bool ninf = l[m] == -INFINITY;
+      dead = dead || ninf;
+      const float v = ninf ? 0.0f : l[m];
+      acc = fmaf(p.beta_lo[m], v, fmaf(p.beta_hi[m], v, acc));
+    }
+  return dead ? -INFINITY : acc;
+}
+
+// Element k of the row of model `sel` (wave-uniform) out of the loaded rows.
+template <int NCAP, int N>
+__device__ __forceinline__ float pick_row(const float (&x)[NCAP][N], int sel, int k) {
+  float v = x[0][k];
+#pragma unroll
+  for (int m = 1; m < NCAP; ++m) {
+    const float xm = x[m][k];  // read first: a select of values, never of addresses (which would
+    v = (m == sel) ? xm : v;   // force the rows out of registers)
+  }
+  return v;
+}
+
+}  // namespace

@@ -1,0 +1,459 @@
+// cos_sample.h -- the sampling weights f = max(0, r - q) or r (App. A.1), the tile
+// sums, the inverse-CDF draw, and the acceptance-rate kernel (Eq. (7)).
+#pragma once
+
+#include "cos_device.h"
+
+namespace {
+
+// ---------------------------------------------------------------------------
+// sampling weights f(x) of one 16-byte vector per model
+// ---------------------------------------------------------------------------
+
+// Ensemble: f = max(0, sum_m a_m 2^(l_m*log2e - K_m)); the a_m carry the
+// ensemble weights, minus one for the proposer when a residual is wanted
+// (App. A.1), times 2^(K_m - log2-sum-exp) so that the K_m are integers.  Each
+// product is rounded before it is added (no fused multiply-add), so that terms
+// of identical models cancel exactly and r == q leaves no residual mass.
+template <int NCAP, int N>
+__device__ __forceinline__ void eval_f_ensemble(const float (&x)[NCAP][N], int n, float scale,
+                                                const float (&coef)[NCAP], const float (&off)[NCAP],
+                                                float (&f)[N]) {
+#pragma unroll
+  for (int k = 0; k < N; ++k) {
+    float s = 0.0f;
+#pragma unroll
+    for (int m = 0; m < NCAP; ++m)
+      if (m < n) s += coef[m] * fast_exp2(fmaf(x[m][k], scale, -off[m]));
+    f[k] = fmaxf(s, 0.0f);
+  }
+}
+
+// Contrastive: r = [mask] coef[0] 2^(c*scale - off[0]), q = coef[1] 2^(l_pi*scale - off[1]);
+// f = max(0, r - q) on the mask (coef[1] = 0 for a bonus draw from r), 0 off it.
+// plain >= 0 (the verifier's own bonus token): f = coef[1] 2^(l_plain*scale - off[1]), no mask.
+template <typename T, int N>
+__device__ __forceinline__ void eval_f_contrastive(const float (&x0)[N], const float (&x1)[N],
+                                                   int pi, int plain, float m0, const Params& p,
+                                                   const float (&coef)[2], const float (&off)[2],
+                                                   float (&f)[N]) {
+  const int qsel = plain >= 0 ? plain : pi;
+#pragma unroll
+  for (int k = 0; k < N; ++k) {
+    const float lq = qsel ? x1[k] : x0[k];
+    const float q = coef[1] * fast_exp2(fmaf(lq, p.scale, -off[1]));
+    if (plain >= 0) {
+      f[k] = q;
+    } else {
+      const bool in = in_mask<T>(x0[k], m0, p.thr32, p.thr64);
+      const float c = contrast(x0[k], x1[k], p.mu_hi, p.mu_lo);
+      const float r = coef[0] * fast_exp2(fmaf(c, p.scale, -off[0]));
+      f[k] = in ? fmaxf(r - q, 0.0f) : 0.0f;
+    }
+  }
+}
+
+// Logit mix: r = coef[0] 2^(c*scale - off[0]), q = coef[1] 2^(l_pi*scale - off[1]);
+// f = max(0, r - q) (coef[1] = 0 for a bonus draw from r).
+// plain >= 0 (the verifier's own bonus token): f = coef[1] 2^(l_plain*scale - off[1]).
+template <int NCAP, int N>
+__device__ __forceinline__ void eval_f_mix(const float (&x)[NCAP][N], int n, int pi, int plain,
+                                           const Params& p, const float (&coef)[NCAP],
+                                           const float (&off)[NCAP], float (&f)[N]) {
+  static_assert(NCAP >= 2, "two coefficients");
+  const int qsel = plain >= 0 ? plain : pi;
+#pragma unroll
+  for (int k = 0; k < N; ++k) {
+    const float q = coef[1] * fast_exp2(fmaf(pick_row<NCAP, N>(x, qsel, k), p.scale, -off[1]));
+    if (plain >= 0) {
+      f[k] = q;
+    } else {
+      float l[NCAP];
+#pragma unroll
+      for (int m = 0; m < NCAP; ++m) l[m] = x[m][k];
+      const float r = coef[0] * fast_exp2(fmaf(mix_one<NCAP>(p, n, l), p.scale, -off[0]));
+      f[k] = fmaxf(r - q, 0.0f);
+    }
+  }
+}
+
+// Coefficients and integer offsets of the sampling weights from a sequence's plan.
+template <int NCAP, int MODE>
+__device__ __forceinline__ void plan_coefficients(const Params& p, const SeqPlan& plan, bool residual,
+                                                  int n, float (&coef)[NCAP], float (&off)[NCAP]) {
+#pragma unroll
+  for (int m = 0; m < NCAP; ++m) {
+    coef[m] = 0.0f;
+    off[m] = 0.0f;
+    if (m < n || (MODE == kMix && m < 2)) {
+      double a, lse;
+      const bool plain = !residual && plan.bonus >= 0;  // bonus token from one model's softmax alone
+      if constexpr (MODE == kEns) {
+        a = plain ? (m == plan.bonus ? 1.0 : 0.0) : p.w[m] - ((residual && m == plan.pi) ? 1.0 : 0.0);
+        lse = plan.lse2[m];
+      } else if constexpr (MODE == kMix) {
+        // slot 0: r from the mixed logits (statistic 1); slot 1: q (statistic 0); others unused
+        a = (m == 0) ? (plain ? 0.0 : 1.0) : ((m == 1 && (residual || plain)) ? 1.0 : 0.0);
+        lse = plan.lse2[m == 0 ? 1 : 0];
+      } else {
+        a = (m == 0) ? 1.0 : ((residual || plain) ? 1.0 : 0.0);
+        const double lse_q0 = plan.lse2[0], lse_q1 = plan.lse2[1];  // values first, then the choice
+        lse = m == 0 ? plan.lse2[2] : ((plain ? plan.bonus : plan.pi) ? lse_q1 : lse_q0);
+      }
+      if (a != 0.0) {  // a model without weight may have no statistic at all (lse = -inf)
+        const double K = rint(lse);
+        off[m] = (float)K;
+        coef[m] = (float)(a * exp2(K - lse));
+      }
+    }
+  }
+}
+
+// Raw vectors of one tile (64 lanes x one 16-byte vector per model) for this lane.
+// Tiles past the row's end are redirected to the last vector (masked in tile_eval).
+template <typename T, bool ALIGNED, int NCAP>
+__device__ __forceinline__ void tile_load(const Params& p, const T* const (&rows)[NCAP], int n, int tile,
+                                          float (&x)[NCAP][VecOf<T>::N]) {
+  const int vc = min(tile * 64 + lane_id(), p.nvec - 1);
+#pragma unroll
+  for (int m = 0; m < NCAP; ++m)
+    if (m < n) load_vec<T, ALIGNED>(rows[m], vc, p.V, x[m]);
+}
+
+// f of the loaded tile for this lane; 0 past the row's end.
+template <typename T, int NCAP, int MODE>
+__device__ __forceinline__ void tile_eval(const Params& p, const float (&x)[NCAP][VecOf<T>::N], int n,
+                                          int tile, int pi, int plain, float m0,
+                                          const float (&coef)[NCAP], const float (&off)[NCAP],
+                                          float (&f)[VecOf<T>::N]) {
+  constexpr int N = VecOf<T>::N;
+  if constexpr (MODE == kEns)
+    eval_f_ensemble<NCAP, N>(x, n, p.scale, coef, off, f);
+  else if constexpr (MODE == kMix)
+    eval_f_mix<NCAP, N>(x, n, pi, plain, p, coef, off, f);
+  else
+    eval_f_contrastive<T, N>(x[0], x[1], pi, plain, m0, p, coef, off, f);
+  if (tile * 64 + lane_id() >= p.nvec) {
+#pragma unroll
+    for (int k = 0; k < N; ++k) f[k] = 0.0f;
+  }
+}
+
+template <typename T, bool ALIGNED, int NCAP, int MODE>
+__device__ __forceinline__ void tile_weights(const Params& p, const T* const (&rows)[NCAP], int n,
+                                             int tile, int pi, int plain, float m0,
+                                             const float (&coef)[NCAP], const float (&off)[NCAP],
+                                             float (&f)[VecOf<T>::N]) {
+  float x[NCAP][VecOf<T>::N];
+  tile_load<T, ALIGNED, NCAP>(p, rows, n, tile, x);
+  tile_eval<T, NCAP, MODE>(p, x, n, tile, pi, plain, m0, coef, off, f);
+}
+
+template <int N>
+__device__ __forceinline__ double lane_mass(const float (&f)[N]) {
+  double s = 0.0;
+#pragma unroll
+  for (int k = 0; k < N; ++k) s += (double)f[k];
+  return s;
+}
+
+// ---------------------------------------------------------------------------
+// final scan + inverse CDF of one sequence (wavefront 0 of the last sampling
+// workgroup); tile_sum holds the ntiles tile sums in LDS.
+// Returns false if the weights have no mass and may_retry is set.
+// ---------------------------------------------------------------------------
+template <typename T, bool ALIGNED, int NCAP, int MODE>
+__device__ bool draw_token(const Params& p, int b, const SeqPlan& plan, const T* const (&rows)[NCAP],
+                           int n, const float (&coef)[NCAP], const float (&off)[NCAP],
+                           const double* tile_sum, bool may_retry, int flags) {
+  constexpr int N = VecOf<T>::N;
+  const int lane = lane_id();
+  const int g1 = p.gamma + 1;
+  // scan of the tile sums: each lane owns a contiguous segment
+  const int per = (p.ntiles + 63) / 64;
+  const int t0 = min(lane * per, p.ntiles), t1 = min(t0 + per, p.ntiles);
+  double seg = 0.0;
+  for (int t = t0; t < t1; ++t) seg += tile_sum[t];
+  const double incl = wave_inclusive_scan(seg);
+  const double F = __shfl(incl, 63, 64);
+  const double up = __shfl_up(incl, 1, 64);
+  const double excl = lane ? up : 0.0;
+  const bool bad = !(F > 0.0) || !(F < INFINITY);
+  if (bad && may_retry) return false;
+
+  const double target = p.u_resample[b] * F;
+  // first tile whose inclusive prefix exceeds the target; else the last tile with mass
+  int hit = -1, lastpos = -1;
+  double hit_excl = 0.0, lastpos_excl = 0.0, runsum = excl;
+  for (int t = t0; t < t1; ++t) {
+    const double ts = tile_sum[t];
+    const double nxt = runsum + ts;
+    if (hit < 0 && nxt > target) {
+      hit = t;
+      hit_excl = runsum;
+    }
+    if (ts > 0.0) {
+      lastpos = t;
+      lastpos_excl = runsum;
+    }
+    runsum = nxt;
+  }
+  const unsigned long long hits = __ballot(hit >= 0);
+  const unsigned long long poss = __ballot(lastpos >= 0);
+  bool clamp = false;
+  int tile = 0;
+  double tile_excl = 0.0;
+  if (hits) {
+    const int src = __ffsll((long long)hits) - 1;
+    tile = __shfl(hit, src, 64);
+    tile_excl = __shfl(hit_excl, src, 64);
+  } else {
+    clamp = true;
+    if (poss) {
+      const int src = 63 - __clzll((long long)poss);
+      tile = __shfl(lastpos, src, 64);
+      tile_excl = __shfl(lastpos_excl, src, 64);
+    }
+  }
+
+  // the same f values of that one tile, scanned element by element
+  float f[N];
+  tile_weights<T, ALIGNED, NCAP, MODE>(p, rows, n, tile, plan.pi, plan.bonus, plan.m0, coef, off, f);
+  const double lane_tot = lane_mass<N>(f);
+  const double lincl = wave_inclusive_scan(lane_tot);
+  const double lup = __shfl_up(lincl, 1, 64);
+  const double lexcl = tile_excl + (lane ? lup : 0.0);
+  int ksel = -1, klast = -1;
+  double lo_sel = 0.0, hi_sel = 0.0, lo_last = 0.0, hi_last = 0.0, runl = lexcl;
+#pragma unroll
+  for (int k = 0; k < N; ++k) {
+    const double nxt = runl + (double)f[k];
+    if (ksel < 0 && nxt > target) {
+      ksel = k;
+      lo_sel = runl;
+      hi_sel = nxt;
+    }
+    if (f[k] > 0.0f) {
+      klast = k;
+      lo_last = runl;
+      hi_last = nxt;
+    }
+    runl = nxt;
+  }
+  const unsigned long long sel = clamp ? 0ull : __ballot(ksel >= 0);
+  const unsigned long long pos = __ballot(klast >= 0);
+  int src = 0, kk = 0;
+  double lo = 0.0, hi = 0.0;
+  if (sel) {
+    src = __ffsll((long long)sel) - 1;
+    kk = ksel;
+    lo = lo_sel;
+    hi = hi_sel;
+  } else {
+    // rounding left no prefix above the target inside this tile (or tail clamp):
+    // take the last element with mass
+    if (pos) src = 63 - __clzll((long long)pos);
+    kk = klast < 0 ? 0 : klast;
+    lo = lo_last;
+    hi = hi_last;
+    if (clamp) flags |= COS_FLAG_TAIL_CLAMP;
+  }
+  if (lane == src) {
+    int token = (tile * 64 + lane) * N + kk;
+    token = min(max(token, 0), p.V - 1);
+    p.out_tokens[(size_t)b * g1 + plan.jstar] = token;
+    if (p.diag.sample_mass) p.diag.sample_mass[b] = F;
+    if (p.diag.cdf_lo) p.diag.cdf_lo[b] = lo / F;
+    if (p.diag.cdf_hi) p.diag.cdf_hi[b] = hi / F;
+    if (p.diag.flags) p.diag.flags[b] = flags;
+  }
+  return true;
+}
+
+// Sampling kernel.  Workgroup index -> (b, c): tiles [c*tpc, (c+1)*tpc) of the
+// sampled position's rows -> tile sums; the last workgroup of b draws the token.
+template <typename T, bool ALIGNED, int NM, int MODE>
+__global__ void __launch_bounds__(kThreads) sample_kernel(Params p) {
+  constexpr int N = VecOf<T>::N;
+  constexpr bool CONTRASTIVE = MODE == kCd;
+  // register rows; the logit mix keeps its two coefficients in slots 0 and 1
+  constexpr int NCAP = CONTRASTIVE ? 2 : (NM ? (MODE == kMix && NM < 2 ? 2 : NM) : COS_MAX_MODELS);
+  constexpr int TU = NCAP <= 4 ? 4 : 1;  // tiles in flight per wavefront
+  extern __shared__ double tile_sum[];
+  __shared__ int s_flag;
+
+  const int b = blockIdx.x / p.C;
+  const int c = blockIdx.x - b * p.C;
+  const int lane = lane_id();
+  const int wave = threadIdx.x >> 6;
+  const int n = CONTRASTIVE ? 2 : (NM ? NM : p.n);
+  const SeqPlan plan = p.plans[b];
+  if (plan.skip) return;  // every draft accepted, no extra token: nothing to draw
+  // A verifier bonus reads that one model's row only (the others carry a zero
+  // coefficient and may hold anything, so every slot points at the valid row).
+  const bool one_row = MODE == kEns && plan.residual == 0 && plan.bonus >= 0;
+  const T* rows[NCAP];
+#pragma unroll
+  for (int m = 0; m < NCAP; ++m)
+    rows[m] = row_ptr<T>(p, one_row ? plan.bonus : (m < n ? m : 0), b, plan.jstar);
+  float coef[NCAP], off[NCAP];
+  plan_coefficients<NCAP, MODE>(p, plan, plan.residual != 0, n, coef, off);
+
+  double* sums = p.tile_sums + (size_t)b * p.ntiles;
+  const int tb = c * p.tpc;
+  const int te = min(tb + p.tpc, p.ntiles);
+  // wavefront w takes tiles tb + w, tb + w + kWaves, ...; TU of them are in flight at once
+  for (int t = tb + wave; t < te; t += kWaves * TU) {
+    float x[TU][NCAP][N];
+#pragma unroll
+    for (int i = 0; i < TU; ++i)
+      tile_load<T, ALIGNED, NCAP>(p, rows, n, min(t + i * kWaves, te - 1), x[i]);
+#pragma unroll
+    for (int i = 0; i < TU; ++i) {
+      const int ti = t + i * kWaves;
+      float f[N];
+      tile_eval<T, NCAP, MODE>(p, x[i], n, min(ti, te - 1), plan.pi, plan.bonus, plan.m0, coef,
+                                      off, f);
+      const double ts = wave_sum_to_lane63(lane_mass<N>(f));
+      if (lane == 63 && ti < te) tile_sum[ti - tb] = ts;  // staged in LDS
+    }
+  }
+  __syncthreads();
+  // publish this workgroup's tile sums with coalesced write-through stores
+  for (int i = threadIdx.x; i < te - tb; i += kThreads) store_agent(sums + tb + i, tile_sum[i]);
+  wait_stores();
+  if (!arrive_last(p.counters + ((size_t)(p.gamma + 1) * p.B + b) * kCtrStride, p.C, &s_flag)) return;
+
+  // last workgroup of this sequence: all tile sums are published
+  for (int t = threadIdx.x; t < p.ntiles; t += kThreads) tile_sum[t] = load_agent(sums + t);
+  __syncthreads();
+  bool done = false;
+  if (wave == 0)
+    done = draw_token<T, ALIGNED, NCAP, MODE>(p, b, plan, rows, n, coef, off, tile_sum,
+                                                     plan.residual != 0, 0);
+  if (threadIdx.x == 0) s_flag = done ? 0 : 1;
+  __syncthreads();
+  if (!s_flag) return;
+
+  // The residual has no mass (cannot happen in exact arithmetic): draw from r
+  // itself.  Rare, so this one workgroup recomputes every tile sum.
+  plan_coefficients<NCAP, MODE>(p, plan, false, n, coef, off);
+  for (int t = wave; t < p.ntiles; t += kWaves) {
+    float f[N];
+    tile_weights<T, ALIGNED, NCAP, MODE>(p, rows, n, t, plan.pi, plan.bonus, plan.m0, coef, off, f);
+    const double ts = wave_sum(lane_mass<N>(f));
+    if (lane == 0) tile_sum[t] = ts;
+  }
+  __syncthreads();
+  if (wave == 0)
+    draw_token<T, ALIGNED, NCAP, MODE>(p, b, plan, rows, n, coef, off, tile_sum, false,
+                                              COS_FLAG_RESIDUAL_FALLBACK);
+}
+
+// Acceptance-rate kernel (optional): alpha = sum_x min(q(x), r(x)) of Eq. (7) for
+// every draft position.  Workgroup index -> (b, j, c); a second full read of the
+// draft positions' rows, with the normalisers the streaming kernel left behind.
+template <typename T, bool ALIGNED, int NM, int MODE>
+__global__ void __launch_bounds__(kThreads) acceptance_rate_kernel(Params p) {
+  constexpr int N = VecOf<T>::N;
+  constexpr bool CONTRASTIVE = MODE == kCd;
+  constexpr int NCAP = CONTRASTIVE ? 2 : (NM ? (MODE == kMix && NM < 2 ? 2 : NM) : COS_MAX_MODELS);
+  __shared__ double wsum[kWaves];
+  __shared__ int s_flag;
+
+  const int per_b = p.gamma * p.CA;
+  const int b = blockIdx.x / per_b;
+  int rem = blockIdx.x - b * per_b;
+  const int j = rem / p.CA;
+  const int c = rem - j * p.CA;
+  const int lane = lane_id();
+  const int wave = threadIdx.x >> 6;
+  const int n = CONTRASTIVE ? 2 : (NM ? NM : p.n);
+  const int g1 = p.gamma + 1;
+  if (j >= drafts_of(p, b)) {  // no draft at this position: no acceptance rate
+    if (c == 0 && threadIdx.x == 0) p.alpha[(size_t)b * p.gamma + j] = NAN;
+    return;
+  }
+  const int pi = p.proposer_pos ? p.proposer_pos[(size_t)b * p.gamma + j] : p.proposer[b];
+  const double* lse = p.lse_all + ((size_t)b * g1 + j) * p.nstat;
+  const float m0 = CONTRASTIVE ? p.rowmax_all[(size_t)b * g1 + j] : 0.0f;
+
+  // r = sum_m cr[m] 2^(l_m*scale - off[m]); q = cq 2^(l_pi*scale - off[pi])   (ensemble)
+  // r = [mask] cr[0] 2^(c*scale - off[0]);  q = cq 2^(l_pi*scale - off[1])    (contrastive)
+  // r = cr[0] 2^(mix*scale - off[0]);       q = cq 2^(l_pi*scale - off[1])    (logit mix)
+  float cr[NCAP], off[NCAP], cq = 0.0f;
+#pragma unroll
+  for (int m = 0; m < NCAP; ++m) {
+    cr[m] = 0.0f;
+    off[m] = 0.0f;
+    if (MODE == kMix ? m < 2 : m < n) {
+      const double l2 = CONTRASTIVE ? lse[m == 0 ? 2 : pi] : (MODE == kMix ? lse[m == 0 ? 1 : 0] : lse[m]);
+      const double K = rint(l2);
+      const double unit = exp2(K - l2);
+      off[m] = (float)K;
+      if constexpr (CONTRASTIVE || MODE == kMix) {
+        if (m == 0) cr[0] = (float)unit; else cq = (float)unit;
+      } else {
+        cr[m] = (float)(p.w[m] * unit);
+        if (m == pi) cq = (float)unit;
+      }
+    }
+  }
+  const T* rows[NCAP];
+#pragma unroll
+  for (int m = 0; m < NCAP; ++m) rows[m] = row_ptr<T>(p, m < n ? m : 0, b, j);
+
+  double acc = 0.0;
+  const int tb = c * p.tpa;
+  const int te = min(tb + p.tpa, p.ntiles);
+  for (int t = tb + wave; t < te; t += kWaves) {
+    float x[NCAP][N];
+    tile_load<T, ALIGNED, NCAP>(p, rows, n, t, x);
+    if (t * 64 + lane < p.nvec) {
+#pragma unroll
+      for (int k = 0; k < N; ++k) {
+        float r = 0.0f, q = 0.0f;
+        if constexpr (MODE == kEns) {
+#pragma unroll
+          for (int m = 0; m < NCAP; ++m)
+            if (m < n) {
+              const float e = fast_exp2(fmaf(x[m][k], p.scale, -off[m]));
+              r += cr[m] * e;
+              if (m == pi) q = cq * e;
+            }
+        } else if constexpr (MODE == kMix) {
+          float l[NCAP];
+#pragma unroll
+          for (int m = 0; m < NCAP; ++m) l[m] = x[m][k];
+          r = cr[0] * fast_exp2(fmaf(mix_one<NCAP>(p, n, l), p.scale, -off[0]));
+          q = cq * fast_exp2(fmaf(pick_row<NCAP, N>(x, pi, k), p.scale, -off[1]));
+        } else {
+          const bool in = in_mask<T>(x[0][k], m0, p.thr32, p.thr64);
+          const float cc = contrast(x[0][k], x[1][k], p.mu_hi, p.mu_lo);
+          r = in ? cr[0] * fast_exp2(fmaf(cc, p.scale, -off[0])) : 0.0f;
+          q = cq * fast_exp2(fmaf(pi ? x[1][k] : x[0][k], p.scale, -off[1]));
+        }
+        acc += (double)fminf(q, r);
+      }
+    }
+  }
+  const double ws = wave_sum(acc);
+  if (lane == 0) wsum[wave] = ws;
+  __syncthreads();
+  double* parts = p.alpha_partials + ((size_t)b * p.gamma + j) * p.CA;
+  if (threadIdx.x == 0) {
+    double tot = 0.0;
+    for (int w = 0; w < kWaves; ++w) tot += wsum[w];
+    store_agent(parts + c, tot);
+    wait_stores();
+  }
+  int* counter = p.counters + ((size_t)(p.gamma + 2) * p.B + (size_t)b * p.gamma + j) * kCtrStride;
+  if (!arrive_last(counter, p.CA, &s_flag)) return;
+  if (threadIdx.x == 0) {
+    double tot = 0.0;
+    for (int i = 0; i < p.CA; ++i) tot += load_agent(parts + i);
+    p.alpha[(size_t)b * p.gamma + j] = tot;
+  }
+}
+
+}  // namespace

@@ -1,0 +1,827 @@
+// cos_stats.h -- the streaming kernels: softmax statistics of every logit row
+// (Sec. 3.2), the decision of a sequence (Eq. (6), Sec. 3.1) by the workgroup that
+// completes it, and the temperature-0 argmax kernel.
+#pragma once
+
+#include "cos_device.h"
+
+namespace {
+
+// ---------------------------------------------------------------------------
+// streaming softmax statistics (Sec. 3.2)
+// ---------------------------------------------------------------------------
+
+// Running statistic of one wavefront: acc lanes hold sum 2^(l*log2e - o) with a
+// wave-uniform integer offset o >= ceil(max l * log2e) seen so far.
+struct Running {
+  int o;
+  float acc[4];
+};
+
+__device__ __forceinline__ void running_init(Running& r) {
+  r.o = kNoOffset;
+  r.acc[0] = r.acc[1] = r.acc[2] = r.acc[3] = 0.0f;
+}
+
+// Raise the offset to cover a new wave-wide maximum `wm` (wave-uniform).
+// Offsets are integers, so the rescale by 2^(old - new) is exact.
+__device__ __forceinline__ void running_cover(Running& r, float wm, float scale) {
+  if (wm > -INFINITY) {
+    float of = ceilf(wm * scale);
+    of = fminf(fmaxf(of, -kMaxOffset), kMaxOffset);
+    const int on = (int)of;
+    if (on > r.o) {
+      const int shift = r.o - on;
+#pragma unroll
+      for (int a = 0; a < 4; ++a) r.acc[a] = ldexpf(r.acc[a], shift);
+      r.o = on;
+    }
+  }
+}
+
+__device__ __forceinline__ double running_total(const Running& r) {
+  const double z = ((double)r.acc[0] + (double)r.acc[1]) + ((double)r.acc[2] + (double)r.acc[3]);
+  return wave_sum(z);
+}
+
+template <int U, int N>
+__device__ __forceinline__ void running_add(Running& run, const float (&x)[U][N], float scale) {
+  float lm = -INFINITY;
+#pragma unroll
+  for (int u = 0; u < U; ++u)
+#pragma unroll
+    for (int k = 0; k < N; ++k) lm = fmaxf(lm, x[u][k]);
+  running_cover(run, wave_max(lm), scale);
+  const float neg_o = -(float)run.o;
+#pragma unroll
+  for (int u = 0; u < U; ++u)
+#pragma unroll
+    for (int k = 0; k < N; ++k) run.acc[k & 3] += fast_exp2(fmaf(x[u][k], scale, neg_o));
+}
+
+// ---- raw-register variant for 16-byte aligned rows -------------------------
+//
+// For bf16 the maximum is taken on the raw bit patterns with packed 16-bit
+// integer maxima: among non-negative floats integer order equals float order,
+// and a pattern with the sign bit set never wins against one without, so
+// whenever the wave-wide result is non-negative it is the true maximum;
+// otherwise (every element negative) the float path below decides.
+
+typedef short short2_t __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ int wave_max_i32(int v) {
+#define COS_DPP_IMAX(ctrl, row_mask) \
+  v = max(v, __builtin_amdgcn_update_dpp(v, v, ctrl, row_mask, 0xf, false));
+  COS_DPP_IMAX(0x111, 0xf)  // row_shr:1
+  COS_DPP_IMAX(0x112, 0xf)  // row_shr:2
+  COS_DPP_IMAX(0x114, 0xf)  // row_shr:4
+  COS_DPP_IMAX(0x118, 0xf)  // row_shr:8
+  COS_DPP_IMAX(0x142, 0xa)  // row_bcast:15 into rows 1 and 3
+  COS_DPP_IMAX(0x143, 0xc)  // row_bcast:31 into rows 2 and 3
+#undef COS_DPP_IMAX
+  return __builtin_amdgcn_readlane(v, 63);
+}
+
+// U raw vectors per lane starting at `base` (stride kThreads); vectors at or
+// past v1 are redirected to the in-range vector v1 - 1 (masked by the caller).
+template <typename T, int U>
+__device__ __forceinline__ void load_raw_group(const T* __restrict__ row, int base, int v1,
+                                               uint4 (&raw)[U]) {
+  const uint4* src = reinterpret_cast<const uint4*>(row);
+#pragma unroll
+  for (int u = 0; u < U; ++u)
+    raw[u] = load_stream16(src + min(base + u * kThreads + (int)threadIdx.x, v1 - 1));
+}
+
+// Replace vectors at or past v1 by -inf (only the last, partial group needs it).
+template <typename T, int U>
+__device__ __forceinline__ void mask_raw_group(int base, int v1, uint4 (&raw)[U]) {
+  const uint32_t ninf = sizeof(T) == 2 ? 0xff80ff80u : 0xff800000u;
+#pragma unroll
+  for (int u = 0; u < U; ++u)
+    if (base + u * kThreads + (int)threadIdx.x >= v1) raw[u] = make_uint4(ninf, ninf, ninf, ninf);
+}
+
+template <typename T, int U>
+__device__ __forceinline__ void running_add_raw(Running& run, const uint4 (&raw)[U], float scale) {
+  constexpr int N = VecOf<T>::N;
+  if constexpr (sizeof(T) == 2) {
+    short2_t m = __builtin_bit_cast(short2_t, raw[0].x);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      m = __builtin_elementwise_max(m, __builtin_bit_cast(short2_t, raw[u].x));
+      m = __builtin_elementwise_max(m, __builtin_bit_cast(short2_t, raw[u].y));
+      m = __builtin_elementwise_max(m, __builtin_bit_cast(short2_t, raw[u].z));
+      m = __builtin_elementwise_max(m, __builtin_bit_cast(short2_t, raw[u].w));
+    }
+    const int wm16 = wave_max_i32(max((int)m.x, (int)m.y));
+    if (wm16 >= 0) {
+      running_cover(run, __uint_as_float((uint32_t)wm16 << 16), scale);
+    } else {
+      float lm = -INFINITY;
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        float x[N];
+        unpack<T>(raw[u], x);
+#pragma unroll
+        for (int k = 0; k < N; ++k) lm = fmaxf(lm, x[k]);
+      }
+      running_cover(run, wave_max(lm), scale);
+    }
+  } else {
+    float lm = -INFINITY;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float x[N];
+      unpack<T>(raw[u], x);
+#pragma unroll
+      for (int k = 0; k < N; ++k) lm = fmaxf(lm, x[k]);
+    }
+    running_cover(run, wave_max(lm), scale);
+  }
+  const float neg_o = -(float)run.o;
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    float x[N];
+    unpack<T>(raw[u], x);
+#pragma unroll
+    for (int k = 0; k < N; ++k) run.acc[k & 3] += fast_exp2(fmaf(x[k], scale, neg_o));
+  }
+}
+
+// Statistic of vectors [v0, v1) of one row, per wavefront (all lanes return the
+// wave's values).
+template <typename T, bool ALIGNED>
+__device__ __forceinline__ void chunk_stats(const T* __restrict__ row, int v0, int v1, int V,
+                                            float scale, int& o_out, double& z_out) {
+  constexpr int N = VecOf<T>::N;
+  constexpr int kStep = kThreads * kUnroll;
+  Running run;
+  running_init(run);
+  if constexpr (ALIGNED) {
+    // all kUnroll loads of a group are issued before the first use; only the
+    // last group of a chunk can be partial
+    for (int base = v0; base < v1; base += kStep) {
+      uint4 a[kUnroll];
+      load_raw_group<T, kUnroll>(row, base, v1, a);
+      if (base + kStep > v1) mask_raw_group<T, kUnroll>(base, v1, a);
+      running_add_raw<T, kUnroll>(run, a, scale);
+    }
+  } else {
+    int base = v0;
+    for (; base + kStep <= v1; base += kStep) {
+      float x[kUnroll][N];
+      load_group<T, ALIGNED, false, kUnroll>(row, base, v1, V, x);
+      running_add<kUnroll, N>(run, x, scale);
+    }
+    if (base < v1) {
+      float x[kUnroll][N];
+      load_group<T, ALIGNED, true, kUnroll>(row, base, v1, V, x);
+      running_add<kUnroll, N>(run, x, scale);
+    }
+  }
+  o_out = run.o;
+  z_out = running_total(run);
+}
+
+// Statistics of the wavefronts of a workgroup, combined by thread 0.
+struct WaveStat {
+  double z;
+  int o;
+  int pad;
+};
+
+// ws is [slots][kWaves]; lane 0 of every wavefront publishes its statistic.
+__device__ __forceinline__ void publish_wave_stat(WaveStat* ws, int slot, int o, double z) {
+  const int wave = threadIdx.x >> 6;
+  if (lane_id() == 0) {
+    ws[slot * kWaves + wave].z = z;
+    ws[slot * kWaves + wave].o = o;
+  }
+}
+
+// Thread 0: combine the wavefronts' statistics of one slot and hand the partial
+// to the workgroup that will finish the sequence.
+__device__ __forceinline__ void store_partial(const WaveStat* ws, int slot, Partial* out) {
+  int omax = kNoOffset;
+  for (int w = 0; w < kWaves; ++w) {
+    const WaveStat& s = ws[slot * kWaves + w];
+    if (s.z > 0.0 && s.o > omax) omax = s.o;
+  }
+  double z = 0.0;
+  for (int w = 0; w < kWaves; ++w) {
+    const WaveStat& s = ws[slot * kWaves + w];
+    if (s.z > 0.0) z += ldexp(s.z, s.o - omax);
+  }
+  store_agent(&out->Z, z);
+  store_agent(&out->o, omax);
+}
+
+__device__ __forceinline__ void store_empty_partial(Partial* out) {
+  store_agent(&out->Z, 0.0);
+  store_agent(&out->o, kNoOffset);
+}
+
+// ---------------------------------------------------------------------------
+// decide one sequence (runs in the workgroup that arrived last on its counter)
+// ---------------------------------------------------------------------------
+
+struct DecideShared {
+  double lse2[kMaxStatsPerSeq];     // log2-sum-exp2 per (position, statistic)
+  float rowmax[COS_MAX_GAMMA + 1];  // contrastive: expert maximum per position
+  int accept[COS_MAX_GAMMA + 1];
+};
+
+// Decides the window [j0, j0+nj) of a sequence that no earlier window has
+// decided.  The sequence stays undecided if every draft of the window is
+// accepted and the window does not contain the bonus position.
+template <typename T, int MODE>
+__device__ void decide_sequence(const Params& p, int b, DecideShared& sh) {
+  constexpr bool CONTRASTIVE = MODE == kCd;
+  const int tid = threadIdx.x;
+  const int g1 = p.gamma + 1;
+  const int nstat = p.nstat;
+  const int j0 = p.j0, nj = p.nj;
+  const int nrows = nj * nstat;  // statistics of this window
+  const int n = p.n;
+  const int gb = drafts_of(p, b);
+  const double log2e = (double)p.scale;  // log2(e) / T, the same constant the streaming kernel used
+
+  // 1. combine the chunk partials of every (position, statistic) of the window in float64.
+  //    A group of G lanes (a power of two >= S, at most a wavefront) shares the S partials of
+  //    one statistic, so that a row cut into many chunks (small batches) costs a few dependent
+  //    loads, not S of them; with whole rows (S = 1) it is one thread per statistic.
+  {
+    int G = 1;
+    while (G < p.S && G < 64) G <<= 1;
+    const int per_pass = kThreads / G;
+    const int gl = tid & (G - 1);
+    for (int r0 = 0; r0 < nrows; r0 += per_pass) {  // uniform trip count: every lane shuffles
+      const int r = r0 + tid / G;
+      int omax = kNoOffset;
+      double zsum = 0.0;  // sum of Z 2^(o - omax) over the partials seen by this lane
+      if (r < nrows) {
+        const Partial* pp = p.partials + (((size_t)b * g1 + j0) * nstat + r) * p.S;
+        for (int s = gl; s < p.S; s += G) {
+          const double z = load_agent(&pp[s].Z);
+          const int o = load_agent(&pp[s].o);
+          if (z > 0.0) {
+            if (o > omax) {
+              zsum = ldexp(zsum, omax - o);  // exact: a power of two
+              omax = o;
+            }
+            zsum += ldexp(z, o - omax);
+          }
+        }
+      }
+      for (int d = G >> 1; d >= 1; d >>= 1) {
+        const int oo = __shfl_xor(omax, d, 64);
+        const double zz = __shfl_xor(zsum, d, 64);
+        const int om = max(omax, oo);
+        zsum = (zsum > 0.0 ? ldexp(zsum, omax - om) : 0.0) + (zz > 0.0 ? ldexp(zz, oo - om) : 0.0);
+        omax = om;
+      }
+      if (r < nrows && gl == 0) sh.lse2[r] = (zsum > 0.0) ? (double)omax + log2(zsum) : -INFINITY;
+    }
+  }
+  if (CONTRASTIVE && tid < nj) {
+    // written by the row-max kernel, an earlier launch on the same stream
+    const float* rm = p.rowmax + ((size_t)b * g1 + j0 + tid) * p.S;
+    float m0 = -INFINITY;
+    for (int s = 0; s < p.S && p.masked; ++s) m0 = fmaxf(m0, rm[s]);
+    sh.rowmax[tid] = p.masked ? m0 : 0.0f;
+  }
+  __syncthreads();
+
+  // 2. Eq. (6) for every draft position of the window, in float64
+  const int ndraft = max(min(j0 + nj, gb) - j0, 0);  // draft positions in the window
+  if (tid >= ndraft && tid < nj && j0 + tid < p.gamma) {  // no draft here
+    if (p.diag.r_at_draft) p.diag.r_at_draft[(size_t)b * p.gamma + j0 + tid] = NAN;
+    if (p.diag.q_at_draft) p.diag.q_at_draft[(size_t)b * p.gamma + j0 + tid] = NAN;
+  }
+  if (tid < ndraft) {
+    const int jj = tid, j = j0 + tid;
+    const size_t k = (size_t)b * p.gamma + j;
+    const int d = p.draft[k];
+    const int pi = p.proposer_pos ? p.proposer_pos[k] : p.proposer[b];
+    double rd = 0.0, qd = 0.0;
+    if constexpr (MODE == kMix) {
+      // statistic 0: the proposer's row; statistic 1: the mixed logits
+      double c = 0.0;
+      for (int m = 0; m < n; ++m)
+        if (p.w[m] != 0.0) c += p.w[m] * (double)widen(row_ptr<T>(p, m, b, j)[d]);
+      const double lq = (double)widen(row_ptr<T>(p, pi, b, j)[d]);
+      rd = exp2(c * log2e - sh.lse2[jj * nstat + 1]);
+      qd = exp2(lq * log2e - sh.lse2[jj * nstat + 0]);
+    } else if constexpr (MODE == kEns) {
+      for (int m = 0; m < n; ++m) {
+        const double l = (double)widen(row_ptr<T>(p, m, b, j)[d]);
+        const double s = exp2(l * log2e - sh.lse2[jj * nstat + m]);
+        rd += p.w[m] * s;
+        if (m == pi) qd = s;
+      }
+    } else {
+      const double l0 = (double)widen(row_ptr<T>(p, 0, b, j)[d]);
+      const double l1 = (double)widen(row_ptr<T>(p, 1, b, j)[d]);
+      const bool in = (l0 > -INFINITY) && (l0 - (double)sh.rowmax[jj] >= p.thr64);
+      const double c = l0 - p.w[0] * l1;
+      rd = in ? exp2(c * log2e - sh.lse2[jj * nstat + 2]) : 0.0;
+      qd = exp2((pi ? l1 : l0) * log2e - sh.lse2[jj * nstat + pi]);
+    }
+    double ratio;
+    if (!(rd > 0.0))
+      ratio = 0.0;
+    else if (!(qd > 0.0))
+      ratio = INFINITY;
+    else
+      ratio = rd / qd;
+    const double bound = ratio < 1.0 ? ratio : 1.0;
+    sh.accept[jj] = p.u_accept[k] < bound;
+    if (p.diag.r_at_draft) p.diag.r_at_draft[k] = rd;
+    if (p.diag.q_at_draft) p.diag.q_at_draft[k] = qd;
+  }
+  __syncthreads();
+  if (p.alpha) {
+    if (tid < nrows) p.lse_all[((size_t)b * g1 + j0) * nstat + tid] = sh.lse2[tid];
+    if (CONTRASTIVE && tid < nj) p.rowmax_all[(size_t)b * g1 + j0 + tid] = sh.rowmax[tid];
+  }
+
+  // 3. first rejection (Sec. 3.1) inside the window; -1: none, and the bonus position is not in it
+  int jstar = (j0 + nj > gb) ? gb : -1;
+  for (int jj = ndraft - 1; jj >= 0; --jj)
+    if (!sh.accept[jj]) jstar = j0 + jj;
+  if (jstar < 0) return;  // undecided: a later window continues
+
+  // the drawn token's slot is filled by the sampling kernel, unless nothing is drawn
+  const bool skip = p.no_bonus && jstar == gb;
+  if (tid == 0) p.accepted_len[b] = jstar;
+  if (tid < g1 && (tid != jstar || skip))
+    p.out_tokens[(size_t)b * g1 + tid] = (tid < jstar) ? p.draft[(size_t)b * p.gamma + tid] : -1;
+
+  // 4. plan for the sampling kernel (read after this launch has ended)
+  SeqPlan* plan = p.plans + b;
+  if (tid == 0) {
+    const bool residual = jstar < gb;
+    plan->jstar = jstar;
+    plan->residual = residual;
+    plan->pi = (residual && p.proposer_pos) ? p.proposer_pos[(size_t)b * p.gamma + jstar] : p.proposer[b];
+    plan->bonus = (!residual && p.bonus_idx) ? p.bonus_idx[b] : -1;
+    plan->m0 = (CONTRASTIVE && !skip) ? sh.rowmax[jstar - j0] : 0.0f;
+    plan->skip = skip;
+    if (skip) {
+      if (p.diag.sample_mass) p.diag.sample_mass[b] = 0.0;
+      if (p.diag.cdf_lo) p.diag.cdf_lo[b] = 0.0;
+      if (p.diag.cdf_hi) p.diag.cdf_hi[b] = 0.0;
+      if (p.diag.flags) p.diag.flags[b] = 0;
+    }
+  }
+  if (tid < nstat && !skip) plan->lse2[tid] = sh.lse2[(jstar - j0) * nstat + tid];
+}
+
+// ---------------------------------------------------------------------------
+// kernels
+// ---------------------------------------------------------------------------
+
+// Zeroes the arrival counters and marks every sequence undecided.
+__global__ void __launch_bounds__(kThreads) fill_zero_kernel(int* dst, int count, SeqPlan* plans, int B) {
+  const int i = blockIdx.x * kThreads + threadIdx.x;
+  if (i < count) dst[i] = 0;
+  if (i < B) plans[i].jstar = -1;
+}
+
+// Ensemble streaming kernel.  Workgroup index -> (b, j, m, s), b slowest.
+template <typename T, bool ALIGNED>
+__global__ void __launch_bounds__(kThreads) ensemble_stats_kernel(Params p) {
+  __shared__ WaveStat ws[kWaves];
+  __shared__ DecideShared sh;
+  __shared__ int s_flag;
+
+  const int g1 = p.gamma + 1;
+  const int per_b = p.nj * p.n * p.S;
+  const int b = blockIdx.x / per_b;
+  if (p.plans[b].jstar >= 0) return;  // decided by an earlier window: nothing more is read
+  int rem = blockIdx.x - b * per_b;
+  const int jj = rem / (p.n * p.S);
+  rem -= jj * p.n * p.S;
+  const int j = p.j0 + jj;
+  const int m = rem / p.S;
+  const int s = rem - m * p.S;
+
+  Partial* out = p.partials + (((size_t)b * g1 + j) * p.n + m) * p.S + s;
+  // With a verifier bonus the other models' logits at the bonus position are
+  // not needed (they may not exist yet) and are not read.
+  const int gb = drafts_of(p, b);
+  const int only = (p.bonus_idx && j == gb) ? p.bonus_idx[b] : -1;
+  if ((only >= 0 && m != only) || position_unread(p, gb, j)) {
+    if (threadIdx.x == 0) {
+      store_empty_partial(out);
+      wait_stores();
+    }
+  } else {
+    const T* row = row_ptr<T>(p, m, b, j);
+    const int v0 = s * p.cv;
+    const int v1 = min(v0 + p.cv, p.nvec);
+    int o;
+    double z;
+    chunk_stats<T, ALIGNED>(row, v0, v1, p.V, p.scale, o, z);
+    publish_wave_stat(ws, 0, o, z);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      store_partial(ws, 0, out);
+      wait_stores();
+    }
+  }
+  if (arrive_last(p.counters + ((size_t)p.win * p.B + b) * kCtrStride, per_b, &s_flag))
+    decide_sequence<T, kEns>(p, b, sh);
+}
+
+// Contrastive, kernel 1: partial maxima of the expert row (model 0).
+template <typename T, bool ALIGNED>
+__global__ void __launch_bounds__(kThreads) expert_rowmax_kernel(Params p) {
+  constexpr int N = VecOf<T>::N;
+  constexpr int kStep = kThreads * kUnroll;
+  __shared__ float wmax[kWaves];
+  const int g1 = p.gamma + 1;
+  const int ws = blockIdx.x / p.S;  // b * nj + jj
+  const int s = blockIdx.x - ws * p.S;
+  const int b = ws / p.nj, j = p.j0 + (ws - b * p.nj);
+  if (p.plans[b].jstar >= 0) return;  // decided by an earlier window
+  const int rs = b * g1 + j;
+  if (position_unread(p, drafts_of(p, b), j)) {
+    if (threadIdx.x == 0) p.rowmax[(size_t)rs * p.S + s] = -INFINITY;
+    return;
+  }
+  const T* row = row_ptr<T>(p, 0, b, j);
+  const int v0 = s * p.cv;
+  const int v1 = min(v0 + p.cv, p.nvec);
+  float lm = -INFINITY;
+  for (int base = v0; base < v1; base += kStep) {
+    float x[kUnroll][N];
+    if (base + kStep <= v1)
+      load_group<T, ALIGNED, false, kUnroll>(row, base, v1, p.V, x);
+    else
+      load_group<T, ALIGNED, true, kUnroll>(row, base, v1, p.V, x);
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u)
+#pragma unroll
+      for (int k = 0; k < N; ++k) lm = fmaxf(lm, x[u][k]);
+  }
+  const float wm = wave_max(lm);
+  if (lane_id() == 0) wmax[threadIdx.x >> 6] = wm;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float mx = wmax[0];
+    for (int w = 1; w < kWaves; ++w) mx = fmaxf(mx, wmax[w]);
+    p.rowmax[(size_t)rs * p.S + s] = mx;
+  }
+}
+
+// Contrastive, kernel 2.  Workgroup index -> (b, j, s); reads the chunk of both
+// rows once and produces the proposer row's softmax statistic and the masked
+// statistic of the contrastive logits (Eq. (5) restricted to the mask).
+template <typename T, bool ALIGNED>
+__global__ void __launch_bounds__(kThreads) contrastive_stats_kernel(Params p) {
+  constexpr int N = VecOf<T>::N;
+  constexpr int U = kUnroll >= 2 ? kUnroll / 2 : 1;
+  constexpr int kStep = kThreads * U;
+  __shared__ WaveStat ws[2 * kWaves];
+  __shared__ DecideShared sh;
+  __shared__ int s_flag;
+  __shared__ float s_m0[kWaves];
+
+  const int g1 = p.gamma + 1;
+  const int per_b = p.nj * p.S;
+  const int b = blockIdx.x / per_b;
+  if (p.plans[b].jstar >= 0) return;  // decided by an earlier window: nothing more is read
+  int rem = blockIdx.x - b * per_b;
+  const int j = p.j0 + rem / p.S;
+  const int s = rem - (j - p.j0) * p.S;
+  const int tid = threadIdx.x;
+  // Whose softmax statistic this position needs: the proposer's at a draft
+  // position; at the bonus position only a verifier bonus needs one at all.
+  const int gb = drafts_of(p, b);
+  int pi = p.proposer[b];
+  if (j < gb) {
+    if (p.proposer_pos) pi = p.proposer_pos[(size_t)b * p.gamma + j];
+  } else if (p.bonus_idx && p.bonus_idx[b] >= 0) {
+    pi = p.bonus_idx[b];
+  }
+  if (position_unread(p, gb, j)) {  // uniform over the workgroup
+    if (tid == 0) {
+      Partial* out = p.partials + (((size_t)b * g1 + j) * 3) * p.S + s;
+      store_empty_partial(out);
+      store_empty_partial(out + (size_t)p.S);
+      store_empty_partial(out + (size_t)2 * p.S);
+      wait_stores();
+    }
+    if (arrive_last(p.counters + ((size_t)p.win * p.B + b) * kCtrStride, per_b, &s_flag))
+      decide_sequence<T, kCd>(p, b, sh);
+    return;
+  }
+
+  // expert maximum of this position from the row-max kernel's partial maxima
+  {
+    const float* rm = p.rowmax + ((size_t)b * g1 + j) * p.S;
+    float lm = -INFINITY;
+    for (int i = tid; i < p.S && p.masked; i += kThreads) lm = fmaxf(lm, rm[i]);
+    const float wm = wave_max(lm);
+    if (lane_id() == 0) s_m0[tid >> 6] = wm;
+    __syncthreads();
+  }
+  float m0 = s_m0[0];
+  for (int w = 1; w < kWaves; ++w) m0 = fmaxf(m0, s_m0[w]);
+  if (!p.masked) m0 = 0.0f;  // no mask: every finite expert logit is in
+
+  const T* row0 = row_ptr<T>(p, 0, b, j);
+  const T* row1 = row_ptr<T>(p, 1, b, j);
+  const int v0 = s * p.cv;
+  const int v1 = min(v0 + p.cv, p.nvec);
+  Running rq, rc;  // proposer row; masked contrastive logits
+  running_init(rq);
+  running_init(rc);
+  for (int base = v0; base < v1; base += kStep) {
+    float x0[U][N], x1[U][N];
+    if (base + kStep <= v1) {
+      load_group<T, ALIGNED, false, U>(row0, base, v1, p.V, x0);
+      load_group<T, ALIGNED, false, U>(row1, base, v1, p.V, x1);
+    } else {
+      load_group<T, ALIGNED, true, U>(row0, base, v1, p.V, x0);
+      load_group<T, ALIGNED, true, U>(row1, base, v1, p.V, x1);
+    }
+    // proposer row statistic
+    if (pi)
+      running_add<U, N>(rq, x1, p.scale);
+    else
+      running_add<U, N>(rq, x0, p.scale);
+    // masked contrastive statistic; the mask is sparse, so skip wave-wide when empty
+    float c[U][N];
+    float lmc = -INFINITY;
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int k = 0; k < N; ++k) {
+        const bool in = in_mask<T>(x0[u][k], m0, p.thr32, p.thr64);
+        c[u][k] = in ? contrast(x0[u][k], x1[u][k], p.mu_hi, p.mu_lo) : -INFINITY;
+        lmc = fmaxf(lmc, c[u][k]);
+      }
+    if (__ballot(lmc > -INFINITY)) running_add<U, N>(rc, c, p.scale);
+  }
+  const double zq = running_total(rq);
+  const double zc = running_total(rc);
+  publish_wave_stat(ws, 0, rq.o, zq);
+  publish_wave_stat(ws, 1, rc.o, zc);
+  __syncthreads();
+  if (tid == 0) {
+    Partial* out = p.partials + (((size_t)b * g1 + j) * 3) * p.S;
+    store_partial(ws, 0, out + (size_t)pi * p.S + s);
+    store_empty_partial(out + (size_t)(1 - pi) * p.S + s);
+    store_partial(ws, 1, out + (size_t)2 * p.S + s);
+    wait_stores();
+  }
+  if (arrive_last(p.counters + ((size_t)p.win * p.B + b) * kCtrStride, per_b, &s_flag))
+    decide_sequence<T, kCd>(p, b, sh);
+}
+
+// Logit mix streaming kernel.  Workgroup index -> (b, j, s); reads the chunk of
+// all n rows once and produces the proposer row's softmax statistic
+// (statistic 0) and the statistic of the mixed logits sum_m beta_m l_m
+// (statistic 1; Eq. (3), logit level).
+template <typename T, bool ALIGNED, int NM>
+__global__ void __launch_bounds__(kThreads) mix_stats_kernel(Params p) {
+  constexpr int N = VecOf<T>::N;
+  constexpr int NCAP = NM ? NM : COS_MAX_MODELS;
+  constexpr int U = NCAP <= 2 ? 4 : (NCAP <= 4 ? 2 : 1);  // vectors per lane and row in flight
+  constexpr int kStep = kThreads * U;
+  __shared__ WaveStat ws[2 * kWaves];
+  __shared__ DecideShared sh;
+  __shared__ int s_flag;
+
+  const int n = NM ? NM : p.n;
+  const int g1 = p.gamma + 1;
+  const int per_b = p.nj * p.S;
+  const int b = blockIdx.x / per_b;
+  if (p.plans[b].jstar >= 0) return;  // decided by an earlier window: nothing more is read
+  int rem = blockIdx.x - b * per_b;
+  const int j = p.j0 + rem / p.S;
+  const int s = rem - (j - p.j0) * p.S;
+  const int tid = threadIdx.x;
+  const int gb = drafts_of(p, b);
+  // Whose softmax statistic this position needs: the proposer's at a draft
+  // position; at the bonus position only a verifier bonus needs one, and then
+  // the mixed logits are not needed.
+  int pi = p.proposer[b];
+  bool plain = false;
+  if (j < gb) {
+    if (p.proposer_pos) pi = p.proposer_pos[(size_t)b * p.gamma + j];
+  } else if (p.bonus_idx && p.bonus_idx[b] >= 0) {
+    pi = p.bonus_idx[b];
+    plain = true;
+  }
+  Partial* out = p.partials + (((size_t)b * g1 + j) * 2) * p.S + s;
+  if (position_unread(p, gb, j)) {  // uniform over the workgroup
+    if (tid == 0) {
+      store_empty_partial(out);
+      store_empty_partial(out + (size_t)p.S);
+      wait_stores();
+    }
+    if (arrive_last(p.counters + ((size_t)p.win * p.B + b) * kCtrStride, per_b, &s_flag))
+      decide_sequence<T, kMix>(p, b, sh);
+    return;
+  }
+
+  const T* rows[NCAP];
+#pragma unroll
+  for (int m = 0; m < NCAP; ++m) rows[m] = row_ptr<T>(p, m < n ? m : 0, b, j);
+  const int v0 = s * p.cv;
+  const int v1 = min(v0 + p.cv, p.nvec);
+  Running rq, rc;  // proposer row; mixed logits
+  running_init(rq);
+  running_init(rc);
+  for (int base = v0; base < v1; base += kStep) {
+    float x[NCAP][U][N];
+    if (base + kStep <= v1) {
+#pragma unroll
+      for (int m = 0; m < NCAP; ++m)
+        if (m < n) load_group<T, ALIGNED, false, U>(rows[m], base, v1, p.V, x[m]);
+    } else {
+#pragma unroll
+      for (int m = 0; m < NCAP; ++m)
+        if (m < n) load_group<T, ALIGNED, true, U>(rows[m], base, v1, p.V, x[m]);
+    }
+    float xq[U][N];
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int k = 0; k < N; ++k) {
+        float v = x[0][u][k];
+#pragma unroll
+        for (int m = 1; m < NCAP; ++m) {
+          const float xm = x[m][u][k];
+          v = (m == pi) ? xm : v;
+        }
+        xq[u][k] = v;
+      }
+    running_add<U, N>(rq, xq, p.scale);
+    if (!plain) {
+      float c[U][N];
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int k = 0; k < N; ++k) {
+          float l[NCAP];
+#pragma unroll
+          for (int m = 0; m < NCAP; ++m) l[m] = x[m][u][k];
+          c[u][k] = mix_one<NCAP>(p, n, l);
+        }
+      running_add<U, N>(rc, c, p.scale);
+    }
+  }
+  const double zq = running_total(rq);
+  const double zc = running_total(rc);
+  publish_wave_stat(ws, 0, rq.o, zq);
+  publish_wave_stat(ws, 1, rc.o, zc);
+  __syncthreads();
+  if (tid == 0) {
+    store_partial(ws, 0, out);
+    if (plain)
+      store_empty_partial(out + (size_t)p.S);
+    else
+      store_partial(ws, 1, out + (size_t)p.S);
+    wait_stores();
+  }
+  if (arrive_last(p.counters + ((size_t)p.win * p.B + b) * kCtrStride, per_b, &s_flag))
+    decide_sequence<T, kMix>(p, b, sh);
+}
+
+// Temperature 0 (greedy), contrastive mode.  r of Eq. (5) is one-hot at the
+// masked argmax a_j of c = l_0 - mu l_1, so a draft is accepted iff d_j == a_j and
+// the token drawn at the first mismatch (or the bonus token) is a_j itself: one
+// streaming argmax per position, no sampling kernel, no random numbers.  c is
+// evaluated in float64 with a separate multiply and subtract so that every
+// comparison is the one a float64 reference makes; ties go to the lowest index.
+// Workgroup index -> (b, j, s).  With a verifier bonus the bonus position takes
+// the plain argmax of that model's row.
+struct ArgBest {
+  double val;
+  int idx;  // -1: nothing eligible seen
+};
+
+__device__ __forceinline__ void arg_better(ArgBest& a, double val, int idx) {
+  if (idx >= 0 && (a.idx < 0 || val > a.val || (val == a.val && idx < a.idx))) {
+    a.val = val;
+    a.idx = idx;
+  }
+}
+
+template <typename T, bool ALIGNED>
+__global__ void __launch_bounds__(kThreads) greedy_contrastive_kernel(Params p) {
+  constexpr int N = VecOf<T>::N;
+  constexpr int U = 4;
+  constexpr int kStep = kThreads * U;
+  __shared__ ArgBest wbest[kWaves];
+  __shared__ float s_m0[kWaves];
+  __shared__ int s_flag;
+  __shared__ int s_arg[COS_MAX_GAMMA + 1];
+
+  const int g1 = p.gamma + 1;
+  const int per_b = g1 * p.S;
+  const int b = blockIdx.x / per_b;
+  int rem = blockIdx.x - b * per_b;
+  const int j = rem / p.S;
+  const int s = rem - j * p.S;
+  const int tid = threadIdx.x;
+  const int gb = drafts_of(p, b);
+  const bool unread = position_unread(p, gb, j);
+  const int plain = (j == gb && p.bonus_idx) ? p.bonus_idx[b] : -1;
+  const double mu = p.w[0];
+
+  {
+    const float* rm = p.rowmax + ((size_t)b * g1 + j) * p.S;
+    float lm = -INFINITY;
+    for (int i = tid; i < p.S && p.masked; i += kThreads) lm = fmaxf(lm, rm[i]);
+    const float wm = wave_max(lm);
+    if (lane_id() == 0) s_m0[tid >> 6] = wm;
+    __syncthreads();
+  }
+  float m0 = s_m0[0];
+  for (int w = 1; w < kWaves; ++w) m0 = fmaxf(m0, s_m0[w]);
+  if (!p.masked) m0 = 0.0f;  // no mask: every finite expert logit is in
+
+  const T* row0 = row_ptr<T>(p, 0, b, j);
+  const T* row1 = row_ptr<T>(p, 1, b, j);
+  const int v0 = s * p.cv;
+  const int v1 = min(v0 + p.cv, p.nvec);
+  ArgBest best;
+  best.val = 0.0;
+  best.idx = -1;
+  for (int base = v0; base < v1 && !unread; base += kStep) {
+    float x0[U][N], x1[U][N];
+    if (base + kStep <= v1) {
+      load_group<T, ALIGNED, false, U>(row0, base, v1, p.V, x0);
+      load_group<T, ALIGNED, false, U>(row1, base, v1, p.V, x1);
+    } else {
+      load_group<T, ALIGNED, true, U>(row0, base, v1, p.V, x0);
+      load_group<T, ALIGNED, true, U>(row1, base, v1, p.V, x1);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int first = (base + u * kThreads + tid) * N;  // element index of x[u][0]
+#pragma unroll
+      for (int k = 0; k < N; ++k) {
+        double val;
+        bool ok;
+        if (plain >= 0) {
+          val = (double)(plain ? x1[u][k] : x0[u][k]);
+          ok = val > -INFINITY || (best.idx < 0 && val == -INFINITY);  // a row of -inf still has an argmax
+        } else {
+          ok = in_mask<T>(x0[u][k], m0, p.thr32, p.thr64);
+          const double prod = mu * (double)x1[u][k];
+          val = (double)x0[u][k] - prod;
+        }
+        if (ok && base + u * kThreads + tid < v1 && first + k < p.V && (best.idx < 0 || val > best.val)) {
+          best.val = val;
+          best.idx = first + k;
+        }
+      }
+    }
+  }
+  // wavefront, then workgroup
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) {
+    const double ov = __shfl_xor(best.val, d, 64);
+    const int oi = __shfl_xor(best.idx, d, 64);
+    arg_better(best, ov, oi);
+  }
+  if (lane_id() == 0) wbest[tid >> 6] = best;
+  __syncthreads();
+  if (tid == 0) {
+    ArgBest bb = wbest[0];
+    for (int w = 1; w < kWaves; ++w) arg_better(bb, wbest[w].val, wbest[w].idx);
+    Partial* out = p.partials + (((size_t)b * g1 + j) * p.nstat) * p.S + s;
+    store_agent(&out->Z, bb.val);
+    store_agent(&out->o, bb.idx);
+    wait_stores();
+  }
+  if (!arrive_last(p.counters + (size_t)b * kCtrStride, per_b, &s_flag)) return;
+
+  // last workgroup of the sequence: argmax of every position, first mismatch, outputs
+  if (tid < g1) {
+    const Partial* pp = p.partials + (((size_t)b * g1 + tid) * p.nstat) * p.S;
+    ArgBest bb;
+    bb.val = 0.0;
+    bb.idx = -1;
+    for (int i = 0; i < p.S; ++i) arg_better(bb, load_agent(&pp[i].Z), load_agent(&pp[i].o));
+    s_arg[tid] = bb.idx;
+  }
+  __syncthreads();
+  int jstar = gb;
+  for (int jj = gb - 1; jj >= 0; --jj)
+    if (p.draft[(size_t)b * p.gamma + jj] != s_arg[jj]) jstar = jj;
+  const bool skip = p.no_bonus && jstar == gb;  // every draft accepted, no extra token
+  if (tid == 0) p.accepted_len[b] = jstar;
+  if (tid < g1)
+    p.out_tokens[(size_t)b * g1 + tid] =
+        tid < jstar ? p.draft[(size_t)b * p.gamma + tid] : ((tid == jstar && !skip) ? s_arg[jstar] : -1);
+}
+
+}  // namespace
