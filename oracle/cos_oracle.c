@@ -63,7 +63,7 @@
 #include <omp.h>
 #endif
 
-enum { ORACLE_DTYPE_F32 = 0, ORACLE_DTYPE_BF16 = 1 };
+enum { ORACLE_DTYPE_F32 = 0, ORACLE_DTYPE_BF16 = 1, ORACLE_DTYPE_F16 = 2 };
 enum { ORACLE_ENSEMBLE = 0, ORACLE_CONTRASTIVE = 1, ORACLE_LOGIT_MIX = 2 };
 enum {
   ORACLE_OK = 0,
@@ -86,11 +86,28 @@ static double bf16_to_f64(uint16_t h) {
   return (double)f;
 }
 
+/* IEEE binary16: 1 sign, 5 exponent (bias 15), 10 fraction bits.  Every value
+ * is a small integer times a power of two, so the float64 below is exact. */
+static double f16_to_f64(uint16_t h) {
+  const int sign = h >> 15, e = (h >> 10) & 0x1f, frac = h & 0x3ff;
+  double v;
+  if (e == 0)
+    v = ldexp((double)frac, -24); /* zero and subnormals: frac * 2^-24 */
+  else if (e == 31)
+    v = frac ? NAN : INFINITY;
+  else
+    v = ldexp((double)(1024 + frac), e - 25); /* (1 + frac/1024) * 2^(e-15) */
+  return sign ? -v : v;
+}
+
 void cos_oracle_row_to_f64(const void *row, int dtype, int V, double *out) {
   int x;
   if (dtype == ORACLE_DTYPE_F32) {
     const float *p = (const float *)row;
     for (x = 0; x < V; ++x) out[x] = (double)p[x];
+  } else if (dtype == ORACLE_DTYPE_F16) {
+    const uint16_t *p = (const uint16_t *)row;
+    for (x = 0; x < V; ++x) out[x] = f16_to_f64(p[x]);
   } else {
     const uint16_t *p = (const uint16_t *)row;
     for (x = 0; x < V; ++x) out[x] = bf16_to_f64(p[x]);
@@ -320,7 +337,7 @@ static int check_weights(int mode, int n, const double *w) {
 
 /* ---- the whole verification step, one call per batch -------------------- */
 /*
- * logits        host, [n][B][gamma+1][V] contiguous, dtype f32 or bf16
+ * logits        host, [n][B][gamma+1][V] contiguous, dtype f32, bf16 or f16 (IEEE binary16)
  * draft_tokens  [B][gamma]   proposal tokens (Eq. 1), each in [0, V)
  * proposer_idx  [B]          which model's softmax is q for that row
  * mode/weights  ensemble: w[0..n-1];  contrastive (n == 2, model 0 = expert,
@@ -398,7 +415,7 @@ int cos_oracle_verify_ex(const void *logits, int dtype, int n, int B, int gamma,
       !u_resample || !accepted_len || !out_tokens)
     return ORACLE_ERR_NULL;
   if (n < 1 || B < 0 || gamma < 1 || V < 1) return ORACLE_ERR_SHAPE;
-  if (dtype != ORACLE_DTYPE_F32 && dtype != ORACLE_DTYPE_BF16)
+  if (dtype != ORACLE_DTYPE_F32 && dtype != ORACLE_DTYPE_BF16 && dtype != ORACLE_DTYPE_F16)
     return ORACLE_ERR_DTYPE;
   status = check_weights(mode, n, weights);
   if (status != ORACLE_OK) return status;
@@ -553,7 +570,8 @@ int cos_oracle_verify_greedy(const void *logits, int dtype, int B, int gamma, in
   size_t esize;
   if (!logits || !draft_tokens || !weights || !accepted_len || !out_tokens) return ORACLE_ERR_NULL;
   if (B < 0 || gamma < 1 || V < 1) return ORACLE_ERR_SHAPE;
-  if (dtype != ORACLE_DTYPE_F32 && dtype != ORACLE_DTYPE_BF16) return ORACLE_ERR_DTYPE;
+  if (dtype != ORACLE_DTYPE_F32 && dtype != ORACLE_DTYPE_BF16 && dtype != ORACLE_DTYPE_F16)
+    return ORACLE_ERR_DTYPE;
   if (check_weights(ORACLE_CONTRASTIVE, n, weights) != ORACLE_OK) return ORACLE_ERR_WEIGHTS;
   esize = dtype == ORACLE_DTYPE_F32 ? 4 : 2;
   for (b = 0; b < B; ++b)

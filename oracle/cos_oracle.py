@@ -20,6 +20,7 @@ _LIB = os.path.join(_HERE, "libcos_oracle.so")
 
 DTYPE_F32 = 0
 DTYPE_BF16 = 1
+DTYPE_F16 = 2
 ENSEMBLE = 0
 CONTRASTIVE = 1
 LOGIT_MIX = 2
@@ -107,7 +108,7 @@ def _f64(a):
 # ---- step functions (one vocabulary row each) -----------------------------
 
 def row_to_f64(row: np.ndarray, dtype: int) -> np.ndarray:
-    """Widen one stored row (float32 array, or uint16 array of bf16 bits)."""
+    """Widen one stored row (float32 array, or uint16 array of bf16 / binary16 bits)."""
     row = np.ascontiguousarray(row)
     assert row.dtype == (np.float32 if dtype == DTYPE_F32 else np.uint16)
     out = np.empty(row.shape[0], dtype=np.float64)
@@ -205,7 +206,7 @@ def verify(logits: np.ndarray, dtype: int, draft_tokens, proposer_idx, mode: int
     """
     logits = np.ascontiguousarray(logits)
     assert logits.ndim == 4
-    assert logits.dtype == (np.float32 if dtype == DTYPE_F32 else np.uint16), logits.dtype
+    assert logits.dtype == (np.float32 if dtype == DTYPE_F32 else np.uint16), logits.dtype   # 16-bit formats as raw bits
     n, B, g1, V = logits.shape
     gamma = g1 - 1
     draft_tokens = np.ascontiguousarray(draft_tokens, dtype=np.int32).reshape(B, gamma)
@@ -270,7 +271,7 @@ def verify_greedy(logits: np.ndarray, dtype: int, draft_tokens, weights, bonus_i
     """Temperature-0 contrastive step; returns (status, accepted_len, out_tokens)."""
     logits = np.ascontiguousarray(logits)
     assert logits.ndim == 4 and logits.shape[0] == 2
-    assert logits.dtype == (np.float32 if dtype == DTYPE_F32 else np.uint16), logits.dtype
+    assert logits.dtype == (np.float32 if dtype == DTYPE_F32 else np.uint16), logits.dtype   # 16-bit formats as raw bits
     _, B, g1, V = logits.shape
     gamma = g1 - 1
     draft_tokens = np.ascontiguousarray(draft_tokens, dtype=np.int32).reshape(B, gamma)

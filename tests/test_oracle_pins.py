@@ -55,6 +55,37 @@ def _read_golden(name):
 # storage formats
 # --------------------------------------------------------------------------
 
+def test_f16_widening_every_bit_pattern_against_numpy():
+    """IEEE binary16 -> float64 is exact: all 65536 patterns against numpy's float16 (NaNs as NaNs)."""
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    got = O.row_to_f64(bits, O.DTYPE_F16)
+    want = bits.view(np.float16).astype(np.float64)
+    nan = np.isnan(want)
+    assert np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got[~nan], want[~nan])
+    assert np.array_equal(np.signbit(got[~nan]), np.signbit(want[~nan]))          # -0.0 keeps its sign
+    known = np.array([0x3C00, 0xC000, 0x7BFF, 0x0001, 0x0400, 0x3555, 0xFC00], dtype=np.uint16)
+    assert np.array_equal(O.row_to_f64(known, O.DTYPE_F16),
+                          np.array([1.0, -2.0, 65504.0, 2.0 ** -24, 2.0 ** -14, 0.333251953125, -np.inf]))
+
+
+def test_f16_logits_through_the_whole_step_equal_their_float32_copies():
+    """binary16 -> float32 is exact, so the same values stored as float32 must give the same result."""
+    rng = _rng(17)
+    n, B, gamma, V = 2, 50, 3, 64
+    h = (rng.standard_normal((n, B, gamma + 1, V)) * 2).astype(np.float16)
+    drafts = rng.integers(0, V, (B, gamma)).astype(np.int32)
+    proposer = rng.integers(0, n, B).astype(np.int32)
+    ua, ur = rng.random((B, gamma)), rng.random(B)
+    for mode, w in ((O.ENSEMBLE, [0.3, 0.7]), (O.CONTRASTIVE, [0.5, 0.1])):
+        a = O.verify(h.view(np.uint16), O.DTYPE_F16, drafts, proposer, mode, w, ua, ur, all_positions=True)
+        b = O.verify(h.astype(np.float32), O.DTYPE_F32, drafts, proposer, mode, w, ua, ur, all_positions=True)
+        assert a.status == 0 and b.status == 0
+        assert np.array_equal(a.out_tokens, b.out_tokens) and np.array_equal(a.r_at_draft, b.r_at_draft)
+        assert np.array_equal(a.cdf_hi, b.cdf_hi)
+    assert O.verify(h.view(np.uint16), 3, drafts, proposer, O.ENSEMBLE, [0.3, 0.7], ua, ur).status == -3
+
+
 def test_bf16_widening_known_patterns():
     bits = np.array([0x3F80, 0xC000, 0x0000, 0x8000, 0x7F80, 0xFF80, 0x3DCD, 0x4049], dtype=np.uint16)
     want = np.array([1.0, -2.0, 0.0, -0.0, np.inf, -np.inf, 0.10009765625, 3.140625])
