@@ -32,7 +32,8 @@
 extern "C" {
 #endif
 
-typedef enum { COS_DTYPE_F32 = 0, COS_DTYPE_BF16 = 1 } cos_dtype_t;
+/* Storage format of the logits: float32, bfloat16, or IEEE binary16 (half). */
+typedef enum { COS_DTYPE_F32 = 0, COS_DTYPE_BF16 = 1, COS_DTYPE_F16 = 2 } cos_dtype_t;
 
 /* How the models' outputs become the target distribution r (Eq. (3)):
  *   ENSEMBLE     probability level, Eq. (4): r = sum_m w_m softmax(l_m)

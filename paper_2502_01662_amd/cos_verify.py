@@ -19,6 +19,7 @@ LIBRARY = os.environ.get("COS_VERIFY_LIBRARY") or os.path.join(_PKG, "libcosveri
 
 COS_DTYPE_F32 = 0
 COS_DTYPE_BF16 = 1
+COS_DTYPE_F16 = 2
 COS_COMBINE_ENSEMBLE = 0
 COS_COMBINE_CONTRASTIVE = 1
 COS_COMBINE_LOGIT_MIX = 2
@@ -149,7 +150,9 @@ def _dtype_code(t: torch.Tensor) -> int:
         return COS_DTYPE_F32
     if t.dtype == torch.bfloat16:
         return COS_DTYPE_BF16
-    raise TypeError(f"logits must be float32 or bfloat16, got {t.dtype}")
+    if t.dtype == torch.float16:
+        return COS_DTYPE_F16
+    raise TypeError(f"logits must be float32, bfloat16 or float16, got {t.dtype}")
 
 
 def allocate_workspace(n: int, B: int, gamma: int, V: int, dt: int, mode: int, device) -> torch.Tensor:

@@ -215,6 +215,27 @@ __device__ __forceinline__ uint4 load_stream16(const void* p) {
 
 __device__ __forceinline__ float widen(float x) { return x; }
 __device__ __forceinline__ float widen(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+__device__ __forceinline__ float widen(_Float16 h) { return (float)h; }
+
+// Storage types: float, uint16_t = bfloat16 bit patterns, _Float16 = IEEE binary16.
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+template <typename T>
+struct IsBf16 {
+  static constexpr bool value = false;
+};
+template <>
+struct IsBf16<uint16_t> {
+  static constexpr bool value = true;
+};
+
+// A 16-bit pattern (a non-negative value of T) as float32.
+template <typename T>
+__device__ __forceinline__ float raw16_to_float(int bits) {
+  if constexpr (IsBf16<T>::value)
+    return __uint_as_float((uint32_t)bits << 16);
+  else
+    return (float)__builtin_bit_cast(_Float16, (uint16_t)bits);
+}
 
 template <typename T>
 __device__ __forceinline__ void unpack(const uint4& raw, float (&x)[VecOf<T>::N]);
@@ -238,6 +259,21 @@ __device__ __forceinline__ void unpack<uint16_t>(const uint4& raw, float (&x)[8]
   x[5] = __uint_as_float(raw.z & 0xffff0000u);
   x[6] = __uint_as_float(raw.w << 16);
   x[7] = __uint_as_float(raw.w & 0xffff0000u);
+}
+
+// binary16 -> float32 is exact (v_cvt_f32_f16).
+template <>
+__device__ __forceinline__ void unpack<_Float16>(const uint4& raw, float (&x)[8]) {
+  const half2_t a = __builtin_bit_cast(half2_t, raw.x), b = __builtin_bit_cast(half2_t, raw.y);
+  const half2_t c = __builtin_bit_cast(half2_t, raw.z), d = __builtin_bit_cast(half2_t, raw.w);
+  x[0] = (float)a.x;
+  x[1] = (float)a.y;
+  x[2] = (float)b.x;
+  x[3] = (float)b.y;
+  x[4] = (float)c.x;
+  x[5] = (float)c.y;
+  x[6] = (float)d.x;
+  x[7] = (float)d.y;
 }
 
 // Vector `vec` of a row.  ALIGNED: the row is 16-byte aligned and V is a
@@ -299,10 +335,10 @@ __device__ __forceinline__ float contrast(float l0, float l1, float mu_hi, float
 }
 
 // Plausibility mask: l_0 - max l_0 >= ln(alpha_cd), and a finite expert logit.
-// bf16 differences are exact in float32; float32 inputs compare in float64.
+// bf16 differences are exact in float32; float32 and binary16 inputs compare in float64.
 template <typename T>
 __device__ __forceinline__ bool in_mask(float l0, float m0, float thr32, double thr64) {
-  if constexpr (sizeof(T) == 2) {
+  if constexpr (IsBf16<T>::value) {
     return (l0 > -INFINITY) && (l0 - m0 >= thr32);
   } else {
     return (l0 > -INFINITY) && ((double)l0 - (double)m0 >= thr64);

@@ -61,7 +61,8 @@ __device__ __forceinline__ void running_add(Running& run, const float (&x)[U][N]
 
 // ---- raw-register variant for 16-byte aligned rows -------------------------
 //
-// For bf16 the maximum is taken on the raw bit patterns with packed 16-bit
+// For the 16-bit formats (bf16, binary16: both sign-magnitude) the maximum is taken on
+// the raw bit patterns with packed 16-bit
 // integer maxima: among non-negative floats integer order equals float order,
 // and a pattern with the sign bit set never wins against one without, so
 // whenever the wave-wide result is non-negative it is the true maximum;
@@ -96,7 +97,7 @@ __device__ __forceinline__ void load_raw_group(const T* __restrict__ row, int ba
 // Replace vectors at or past v1 by -inf (only the last, partial group needs it).
 template <typename T, int U>
 __device__ __forceinline__ void mask_raw_group(int base, int v1, uint4 (&raw)[U]) {
-  const uint32_t ninf = sizeof(T) == 2 ? 0xff80ff80u : 0xff800000u;
+  const uint32_t ninf = sizeof(T) == 4 ? 0xff800000u : (IsBf16<T>::value ? 0xff80ff80u : 0xfc00fc00u);
 #pragma unroll
   for (int u = 0; u < U; ++u)
     if (base + u * kThreads + (int)threadIdx.x >= v1) raw[u] = make_uint4(ninf, ninf, ninf, ninf);
@@ -116,7 +117,7 @@ __device__ __forceinline__ void running_add_raw(Running& run, const uint4 (&raw)
     }
     const int wm16 = wave_max_i32(max((int)m.x, (int)m.y));
     if (wm16 >= 0) {
-      running_cover(run, __uint_as_float((uint32_t)wm16 << 16), scale);
+      running_cover(run, raw16_to_float<T>(wm16), scale);
     } else {
       float lm = -INFINITY;
 #pragma unroll

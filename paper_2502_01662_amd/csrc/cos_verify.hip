@@ -266,7 +266,7 @@ extern "C" {
 size_t cos_verify_workspace_bytes(int n, int B, int gamma, int V, cos_dtype_t dt,
                                   cos_combine_t mode) {
   if (!shape_ok(n, B, gamma, V)) return 0;
-  if (dt != COS_DTYPE_F32 && dt != COS_DTYPE_BF16) return 0;
+  if (dt != COS_DTYPE_F32 && dt != COS_DTYPE_BF16 && dt != COS_DTYPE_F16) return 0;
   if (mode != COS_COMBINE_ENSEMBLE && mode != COS_COMBINE_CONTRASTIVE && mode != COS_COMBINE_LOGIT_MIX)
     return 0;
   // Sized for one-position windows (stop_window = 1), which split rows the most.
@@ -314,7 +314,7 @@ cos_status_t cos_verify_ex(const void* logits, cos_dtype_t dt, int n, int B, int
       return COS_ERR_UNSUPPORTED;
   }
   if (!shape_ok(n, B, gamma, V)) return COS_ERR_SHAPE;
-  if (dt != COS_DTYPE_F32 && dt != COS_DTYPE_BF16) return COS_ERR_DTYPE;
+  if (dt != COS_DTYPE_F32 && dt != COS_DTYPE_BF16 && dt != COS_DTYPE_F16) return COS_ERR_DTYPE;
   if (combine_mode != COS_COMBINE_ENSEMBLE && combine_mode != COS_COMBINE_CONTRASTIVE &&
       combine_mode != COS_COMBINE_LOGIT_MIX)
     return COS_ERR_MODE;
@@ -456,7 +456,15 @@ cos_status_t cos_verify_ex(const void* logits, cos_dtype_t dt, int n, int B, int
         if (p.masked) hipLaunchKernelGGL((expert_rowmax_kernel<float, false>), grid, block, 0, st, p);
         hipLaunchKernelGGL((greedy_contrastive_kernel<float, false>), grid, block, 0, st, p);
       }
-    } else {
+    } else if (dt == COS_DTYPE_F16) {
+      if (aligned) {
+        if (p.masked) hipLaunchKernelGGL((expert_rowmax_kernel<_Float16, true>), grid, block, 0, st, p);
+        hipLaunchKernelGGL((greedy_contrastive_kernel<_Float16, true>), grid, block, 0, st, p);
+      } else {
+        if (p.masked) hipLaunchKernelGGL((expert_rowmax_kernel<_Float16, false>), grid, block, 0, st, p);
+        hipLaunchKernelGGL((greedy_contrastive_kernel<_Float16, false>), grid, block, 0, st, p);
+      }
+} else {
       if (aligned) {
         if (p.masked) hipLaunchKernelGGL((expert_rowmax_kernel<uint16_t, true>), grid, block, 0, st, p);
         hipLaunchKernelGGL((greedy_contrastive_kernel<uint16_t, true>), grid, block, 0, st, p);
@@ -476,6 +484,9 @@ cos_status_t cos_verify_ex(const void* logits, cos_dtype_t dt, int n, int B, int
   if (dt == COS_DTYPE_F32)
     rc = aligned ? launch_all<float, true>(p, mode, window, lds, st, ev_start, ev_stop)
                  : launch_all<float, false>(p, mode, window, lds, st, ev_start, ev_stop);
+  else if (dt == COS_DTYPE_F16)
+    rc = aligned ? launch_all<_Float16, true>(p, mode, window, lds, st, ev_start, ev_stop)
+                 : launch_all<_Float16, false>(p, mode, window, lds, st, ev_start, ev_stop);
   else
     rc = aligned ? launch_all<uint16_t, true>(p, mode, window, lds, st, ev_start, ev_stop)
                  : launch_all<uint16_t, false>(p, mode, window, lds, st, ev_start, ev_stop);

@@ -164,8 +164,8 @@ def generate(w: Workload, device: str = "cpu", step: int = 0,
 
 
 def host_logits(logits: torch.Tensor):
-    """Host view for the oracle: float32 array, or uint16 array of bf16 bits."""
+    """Host view for the oracle: float32 array, or uint16 array of bf16 / float16 bits."""
     t = logits.detach().cpu().contiguous()
-    if t.dtype == torch.bfloat16:
+    if t.dtype in (torch.bfloat16, torch.float16):
         return t.view(torch.int16).numpy().view("uint16")
     return t.numpy()

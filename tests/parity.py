@@ -50,7 +50,7 @@ class ParityReport:
 
 
 def oracle_dtype(logits: torch.Tensor) -> int:
-    return O.DTYPE_F32 if logits.dtype == torch.float32 else O.DTYPE_BF16
+    return {torch.float32: O.DTYPE_F32, torch.bfloat16: O.DTYPE_BF16, torch.float16: O.DTYPE_F16}[logits.dtype]
 
 
 def _gpu_ext(inp):

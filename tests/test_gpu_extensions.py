@@ -13,7 +13,7 @@ pytestmark = pytest.mark.gpu
 
 
 @pytest.mark.parametrize("T", [0.5, 0.7, 1.3, 2.0])
-@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("dtype", ["bf16", "f32", "f16"])
 def test_temperature_ensemble_and_contrastive(T, dtype):
     inp = _random_inputs(3, 6, 3, 4099, dtype, seed=int(T * 100))
     inp["temperature"] = T
@@ -230,7 +230,7 @@ def _greedy_inputs(B, gamma, V, dtype, seed, mu, alpha):
     return inp, host, odt
 
 
-@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("dtype", ["bf16", "f32", "f16"])
 @pytest.mark.parametrize("B,gamma,V,mu,alpha", [(6, 2, 8, 0.5, 0.1), (12, 3, 1000, 0.1, 0.1), (8, 2, 4099, 0.5, 0.0),
                                                 (10, 4, 33000, 1.0, 0.5), (7, 3, 70001, 0.3, 1.0),
                                                 (16, 5, 128256, 0.5, 0.1)])

@@ -93,3 +93,16 @@ def test_random_logit_mix_configuration(seed):
     print(f"[fuzz] {desc}: {rep.summary()}", flush=True)
     assert rep.ok, (desc, rep.failures[:3])
     assert rep.excused_accept_ties + rep.excused_cdf_ties <= 1, (desc, rep.summary())
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_float16_configuration(seed):
+    """The same random shapes, modes and extensions with IEEE binary16 logits."""
+    inp, mode, weights, desc = _case(7000 + seed)
+    inp["logits"] = inp["logits"].to(torch.float16)                # -inf and NaN poison survive the conversion
+    desc["dtype"] = "f16"
+    alen, toks, diag = P.run_gpu(inp, mode, weights)
+    rep = P.compare(inp, mode, weights, alen, toks, diag)
+    print(f"[fuzz] {desc}: {rep.summary()}", flush=True)
+    assert rep.ok, (desc, rep.failures[:3])
+    assert rep.excused_accept_ties + rep.excused_cdf_ties <= 1, (desc, rep.summary())

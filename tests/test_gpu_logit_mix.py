@@ -23,7 +23,7 @@ def _likely_drafts(inp, beta, every=2):
     inp["draft_tokens"][::every] = c.argmax(-1).to(torch.int32)[::every]
 
 
-@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("dtype", ["bf16", "f32", "f16"])
 @pytest.mark.parametrize("n,B,gamma,V", [(1, 3, 2, 777), (2, 6, 3, 4099), (2, 4, 2, 33000), (3, 5, 4, 8192), (4, 4, 3, 20011),
                                          (5, 3, 2, 6000), (8, 2, 3, 2048), (3, 2, 31, 513), (2, 3, 2, 70001)])
 def test_logit_mix_shapes(dtype, n, B, gamma, V):

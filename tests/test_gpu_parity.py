@@ -22,7 +22,7 @@ def _report(name, rep):
 
 def _random_inputs(n, B, gamma, V, dtype, seed, std=3.0, device="cuda"):
     g = torch.Generator(device="cpu").manual_seed(seed)
-    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    tdt = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[dtype]
     logits = (torch.randn((n, B, gamma + 1, V), generator=g, dtype=torch.float64) * std).to(tdt)
     return {
         "logits": logits.to(device),
@@ -108,7 +108,7 @@ def test_c5_full_size_sampled_rows():
 # shapes: ragged vocabularies, several tiles + a tail, unaligned rows, both dtypes
 # ---------------------------------------------------------------------------
 
-@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("dtype", ["bf16", "f32", "f16"])
 @pytest.mark.parametrize("n,B,gamma,V", [
     (1, 3, 1, 1), (2, 5, 2, 8), (2, 4, 3, 100), (3, 6, 2, 1000), (2, 3, 4, 4099),
     (5, 4, 2, 2048), (8, 2, 3, 777), (4, 3, 2, 33000), (2, 2, 31, 513), (3, 2, 5, 70001)])
@@ -118,7 +118,7 @@ def test_ensemble_shapes(dtype, n, B, gamma, V):
     _check(f"ens {dtype} n={n} B={B} g={gamma} V={V}", inp, C.COS_COMBINE_ENSEMBLE, w)
 
 
-@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("dtype", ["bf16", "f32", "f16"])
 @pytest.mark.parametrize("B,gamma,V,mu,alpha", [
     (4, 2, 8, 0.5, 0.1), (5, 3, 1000, 0.1, 0.1), (3, 2, 4099, 0.5, 0.0), (4, 4, 33000, 1.0, 0.5),
     (3, 2, 2048, 0.0, 0.0), (2, 3, 70001, 0.3, 1.0), (6, 1, 513, 0.5, 0.01)])
@@ -262,6 +262,20 @@ def test_contrastive_without_mask_needs_no_expert_maxima():
     st, want_len, want_toks = O.verify_greedy(W.host_logits(inp["logits"]), O.DTYPE_BF16,
                                               inp["draft_tokens"].cpu().numpy(), [0.5, 0.0])
     assert st == 0 and np.array_equal(alen.cpu().numpy(), want_len) and np.array_equal(toks.cpu().numpy(), want_toks)
+
+
+def test_float16_workload_shapes():
+    """The c3 and c2 recipes stored as IEEE binary16 (values re-rounded from the bf16 tensors)."""
+    for w in (W.C3.scaled(B=8), W.C2.scaled(B=8), W.C4.scaled(B=8)):
+        inp = W.generate(w, device="cuda")
+        inp["logits"] = inp["logits"].to(torch.float16)
+        alen, toks, diag, rep = _check(f"{w.name} as float16", inp, w.mode, w.weights)
+        assert rep.exact_rows + rep.excused_accept_ties + rep.excused_cdf_ties == w.B
+    big = _random_inputs(2, 2, 2, 1 << 20, "f16", seed=77, std=2.0)        # maximum vocabulary
+    _check("float16, V = 2^20", big, C.COS_COMBINE_ENSEMBLE, [0.5, 0.5])
+    neg = _random_inputs(2, 3, 2, 4096, "f16", seed=78, std=0.5)
+    neg["logits"] -= 20.0                                                  # every logit negative: the float path of the maximum
+    _check("float16, all negative", neg, C.COS_COMBINE_ENSEMBLE, [0.5, 0.5])
 
 
 def test_non_default_stream():
