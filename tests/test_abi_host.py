@@ -42,6 +42,11 @@ def test_workspace_bytes():
     assert C.cos_verify_workspace_bytes(2, 1, 0, 32000, 0, 0) == 0            # gamma < 1
     assert C.cos_verify_workspace_bytes(2, 1, 32, 32000, 0, 0) == 0           # gamma > COS_MAX_GAMMA
     assert C.cos_verify_workspace_bytes(2, 1, 5, (1 << 20) + 1, 0, 0) == 0    # V > COS_MAX_VOCAB
+    for dt in (C.COS_DTYPE_F32, C.COS_DTYPE_BF16, C.COS_DTYPE_F16):          # every format, every mode
+        for mode, n in ((C.COS_COMBINE_ENSEMBLE, 3), (C.COS_COMBINE_CONTRASTIVE, 2), (C.COS_COMBINE_LOGIT_MIX, 3)):
+            assert C.cos_verify_workspace_bytes(n, 4, 5, 32000, dt, mode) >= 256
+    assert C.cos_verify_workspace_bytes(2, 4, 5, 32000, C.COS_DTYPE_F16, 0) == \
+        C.cos_verify_workspace_bytes(2, 4, 5, 32000, C.COS_DTYPE_BF16, 0)    # both are 2-byte formats
     assert C.cos_verify_workspace_bytes(2, 1, 5, 32000, 7, 0) == 0            # dtype
     assert C.cos_verify_workspace_bytes(2, 1, 5, 32000, 0, 7) == 0            # mode
 
@@ -63,6 +68,9 @@ def test_argument_validation_needs_no_gpu():
     assert _call(B=-1) == -2
     assert _call(dt=5) == -3
     assert _call(mode=3) == -4
+    assert _call(mode=2, weights=(1.5, -0.5)) not in (-4, -5)     # logit mix: any finite weights ...
+    assert _call(mode=2, weights=(1.5, float("inf"))) == -5       # ... but finite
+    assert _call(dt=2, logits=0x1001) == -7                       # binary16 logits at an odd address
     assert _call(mode=1, n=3, weights=(0.5, 0.1, 0.0)) == -4      # contrastive needs n == 2
     assert _call(weights=(0.5, 0.6)) == -5
     assert _call(weights=(1.5, -0.5)) == -5
@@ -85,3 +93,30 @@ def test_binding_refuses_cpu_tensors():
         C.cos_verify(torch.zeros((2, 1, 3, 8)), torch.zeros((1, 2), dtype=torch.int32),
                      torch.zeros(1, dtype=torch.int32), 0, [0.5, 0.5], torch.zeros((1, 2), dtype=torch.float64),
                      torch.zeros(1, dtype=torch.float64))
+
+
+class _Options(ctypes.Structure):
+    _fields_ = C.CosOptions._fields_
+
+
+def _call_ex(opt, mode=0, weights=(0.5, 0.5), gamma=2):
+    lib = C.load_library()
+    w = (ctypes.c_double * len(weights))(*weights)
+    return lib.cos_verify_ex(0x1000, 0, 2, 1, gamma, 16, 0x1000, 0x1000, mode, w, 0x1000, 0x1000, 0x1000, 0x1000,
+                             0x1000, 16, None, ctypes.byref(opt), None)     # workspace too small: -6 if all else passes
+
+
+def test_option_validation_needs_no_gpu():
+    size = ctypes.sizeof(C.CosOptions)
+    ok = C.CosOptions(size, 0.0, None, None, None, 0, 0, None, 0)
+    assert _call_ex(ok) == -6                                               # options accepted, workspace rejected
+    assert _call_ex(C.CosOptions(size - 8, 0.0, None, None, None, 0, 0, None, 0)) == -9      # another ABI's struct
+    assert _call_ex(C.CosOptions(size, -1.0, None, None, None, 0, 0, None, 0)) == -5         # temperature < 0
+    assert _call_ex(C.CosOptions(size, float("nan"), None, None, None, 0, 0, None, 0)) == -5
+    assert _call_ex(C.CosOptions(size, 0.0, None, None, None, -1, 0, None, 0)) == -2         # stop_window < 0
+    assert _call_ex(C.CosOptions(size, 0.0, None, None, None, 0, 1, None, 0)) == -9          # greedy ensemble
+    assert _call_ex(C.CosOptions(size, 0.0, None, None, None, 0, 1, None, 0), mode=2) == -9  # greedy logit mix
+    assert _call_ex(C.CosOptions(size, 0.0, None, None, None, 0, 1, None, 0), mode=1, weights=(0.5, 0.1)) == -6
+    assert _call_ex(C.CosOptions(size, 0.0, None, None, 0x1000, 1, 0, None, 0)) == -9        # alpha with windows
+    assert _call_ex(C.CosOptions(size, 0.0, None, None, 0x1000, 5, 0, None, 0)) == -6        # window > gamma: one launch
+    assert _call_ex(C.CosOptions(size, 0.0, None, None, None, 0, 0, 0x1000, 1)) == -6        # ragged, no bonus
