@@ -43,8 +43,9 @@ def main() -> int:
     ap.add_argument("--stop-window", type=int, default=0,
                     help="verify this many positions per launch and never read past a sequence's first "
                          "rejection (0 = the headline step: every position read, one launch)")
-    ap.add_argument("--skip-extras", action="store_true",
-                    help="time the headline step only (no stop_window_1 leg): what the profiler summaries use")
+    ap.add_argument("--extras", action="store_true",
+                    help="also time the same step with stop_window = 1 (reported beside the headline as stop_window_1)")
+    ap.add_argument("--skip-extras", action="store_true", help="accepted for older command lines; the default now")
     ap.add_argument("--with-alpha", action="store_true",
                     help="also compute the acceptance rates of Eq. (7) (an optional output, not the headline step)")
     args = ap.parse_args()
@@ -116,7 +117,7 @@ def main() -> int:
     # ---- the same step with stop_window = 1 (opt-in: rows after a sequence's first rejection are
     # never read, one launch per position): reported beside the headline, never as `value` ----
     lazy = None
-    if args.stop_window == 0 and not args.with_alpha and not args.skip_extras:
+    if args.extras and args.stop_window == 0 and not args.with_alpha:
         def lazy_step(i):
             s = sets[i % nsets]
             C.cos_verify(s["logits"], s["draft_tokens"], s["proposer_idx"], w.mode, w.weights,
