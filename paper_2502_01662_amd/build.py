@@ -11,6 +11,8 @@ INCLUDE = os.path.join(_ROOT, "include")
 LIBRARY = os.path.join(_PKG, "libcosverify.so")
 PROBE_SOURCE = os.path.join(_PKG, "csrc", "hbm_probe.hip")
 PROBE = os.path.join(_PKG, "hbm_probe")
+DRIVER_SOURCE = os.path.join(_PKG, "csrc", "cos_verify_driver.hip")
+DRIVER = os.path.join(_PKG, "cos_verify_driver")
 
 # -packed-fp32-ops off: packed float32 instructions are never emitted.
 # -ffp-contract=off: fused multiply-adds only where the source says fmaf, so
@@ -39,6 +41,19 @@ def build_probe(verbose: bool = False) -> str:
     return PROBE
 
 
+def build_driver(verbose: bool = False) -> str:
+    """The plain C++ caller of the C ABI (timing and profiler runs without Python in the process)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
+           "-packed-fp32-ops", "-I", INCLUDE, "-o", DRIVER, DRIVER_SOURCE, "-L", _PKG, "-lcosverify",
+           "-Wl,-rpath,$ORIGIN"]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    return DRIVER
+
+
 if __name__ == "__main__":
     print(build_library(verbose=True))
     print(build_probe(verbose=True))
+    print(build_driver(verbose=True))
