@@ -120,3 +120,14 @@ def test_option_validation_needs_no_gpu():
     assert _call_ex(C.CosOptions(size, 0.0, None, None, 0x1000, 1, 0, None, 0)) == -9        # alpha with windows
     assert _call_ex(C.CosOptions(size, 0.0, None, None, 0x1000, 5, 0, None, 0)) == -6        # window > gamma: one launch
     assert _call_ex(C.CosOptions(size, 0.0, None, None, None, 0, 0, 0x1000, 1)) == -6        # ragged, no bonus
+
+
+def test_cpp_driver_links_the_library_and_validates_its_arguments():
+    """The plain C++ caller is built with the library; bad arguments end it before any GPU call."""
+    import subprocess
+    from paper_2502_01662_amd import build as B
+    if not os.path.exists(B.DRIVER):
+        B.build_driver()
+    assert subprocess.run([B.DRIVER, "0"], capture_output=True).returncode == 2              # n = 0
+    assert subprocess.run([B.DRIVER, "2", "1", "2", "16", "int8"], capture_output=True).returncode == 2
+    assert subprocess.run([B.DRIVER, "2", "1", "2", "16", "bf16", "vote"], capture_output=True).returncode == 2
