@@ -329,9 +329,20 @@ __device__ __forceinline__ const T* row_ptr(const Params& p, int m, int b, int j
 // logit-level combinations shared by the streaming and the sampling kernels
 // ---------------------------------------------------------------------------
 
-// Contrastive logit c = l_0 - mu*l_1 with mu = mu_hi + mu_lo.
-__device__ __forceinline__ float contrast(float l0, float l1, float mu_hi, float mu_lo) {
-  return fmaf(-mu_lo, l1, fmaf(-mu_hi, l1, l0));
+// Logit-level combinations are evaluated on logits shifted by a per-row reference (the row's
+// first element, 0 if that is not finite): a softmax does not see a shift, and the float32
+// result then rounds at the scale of the logits' spread, not of their magnitude.
+template <typename T>
+__device__ __forceinline__ float row_reference(const T* row) {
+  const float v = widen(row[0]);
+  return (fabsf(v) < INFINITY) ? v : 0.0f;  // false for NaN as well
+}
+
+// Contrastive logit c = (l_0 - ref_0) - mu*(l_1 - ref_1) with mu = mu_hi + mu_lo.
+__device__ __forceinline__ float contrast(float l0, float l1, float mu_hi, float mu_lo, float ref0,
+                                          float ref1) {
+  const float d1 = l1 - ref1;
+  return fmaf(-mu_lo, d1, fmaf(-mu_hi, d1, l0 - ref0));
 }
 
 // Plausibility mask: l_0 - max l_0 >= ln(alpha_cd), and a finite expert logit.
@@ -345,11 +356,12 @@ __device__ __forceinline__ bool in_mask(float l0, float m0, float thr32, double 
   }
 }
 
-// Logit mix c = sum_m beta_m l_m with beta_m = hi + lo; models with beta_m == 0
+// Logit mix c = sum_m beta_m (l_m - ref_m) with beta_m = hi + lo; models with beta_m == 0
 // take no part.  A -inf logit makes c = -inf (probability 0) instead of the NaN
 // that hi * (-inf) + lo * (-inf) gives when hi and lo differ in sign.
 template <int NCAP>
-__device__ __forceinline__ float mix_one(const Params& p, int n, const float (&l)[NCAP]) {
+__device__ __forceinline__ float mix_one(const Params& p, int n, const float (&l)[NCAP],
+                                         const float (&ref)[NCAP]) {
   float acc = 0.0f;
   bool dead = false;
 #pragma unroll
@@ -357,7 +369,7 @@ __device__ __forceinline__ float mix_one(const Params& p, int n, const float (&l
     if (m < n && (p.beta_hi[m] != 0.0f || p.beta_lo[m] != 0.0f)) {
       const bool ninf = l[m] == -INFINITY;
       dead = dead || ninf;
-      const float v = ninf ? 0.0f : l[m];
+      const float v = ninf ? 0.0f : l[m] - ref[m];
       acc = fmaf(p.beta_lo[m], v, fmaf(p.beta_hi[m], v, acc));
     }
   return dead ? -INFINITY : acc;

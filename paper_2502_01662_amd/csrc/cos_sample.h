@@ -36,17 +36,17 @@ template <typename T, int N>
 __device__ __forceinline__ void eval_f_contrastive(const float (&x0)[N], const float (&x1)[N],
                                                    int pi, int plain, float m0, const Params& p,
                                                    const float (&coef)[2], const float (&off)[2],
-                                                   float (&f)[N]) {
+                                                   const float (&ref)[2], float (&f)[N]) {
   const int qsel = plain >= 0 ? plain : pi;
 #pragma unroll
   for (int k = 0; k < N; ++k) {
-    const float lq = qsel ? x1[k] : x0[k];
+    const float lq = qsel ? x1[k] - ref[1] : x0[k] - ref[0];
     const float q = coef[1] * fast_exp2(fmaf(lq, p.scale, -off[1]));
     if (plain >= 0) {
       f[k] = q;
     } else {
       const bool in = in_mask<T>(x0[k], m0, p.thr32, p.thr64);
-      const float c = contrast(x0[k], x1[k], p.mu_hi, p.mu_lo);
+      const float c = contrast(x0[k], x1[k], p.mu_hi, p.mu_lo, ref[0], ref[1]);
       const float r = coef[0] * fast_exp2(fmaf(c, p.scale, -off[0]));
       f[k] = in ? fmaxf(r - q, 0.0f) : 0.0f;
     }
@@ -59,19 +59,23 @@ __device__ __forceinline__ void eval_f_contrastive(const float (&x0)[N], const f
 template <int NCAP, int N>
 __device__ __forceinline__ void eval_f_mix(const float (&x)[NCAP][N], int n, int pi, int plain,
                                            const Params& p, const float (&coef)[NCAP],
-                                           const float (&off)[NCAP], float (&f)[N]) {
+                                           const float (&off)[NCAP], const float (&ref)[NCAP],
+                                           float (&f)[N]) {
   static_assert(NCAP >= 2, "two coefficients");
   const int qsel = plain >= 0 ? plain : pi;
+  float refq = ref[0];
+#pragma unroll
+  for (int m = 1; m < NCAP; ++m) refq = (m == qsel) ? ref[m] : refq;
 #pragma unroll
   for (int k = 0; k < N; ++k) {
-    const float q = coef[1] * fast_exp2(fmaf(pick_row<NCAP, N>(x, qsel, k), p.scale, -off[1]));
+    const float q = coef[1] * fast_exp2(fmaf(pick_row<NCAP, N>(x, qsel, k) - refq, p.scale, -off[1]));
     if (plain >= 0) {
       f[k] = q;
     } else {
       float l[NCAP];
 #pragma unroll
       for (int m = 0; m < NCAP; ++m) l[m] = x[m][k];
-      const float r = coef[0] * fast_exp2(fmaf(mix_one<NCAP>(p, n, l), p.scale, -off[0]));
+      const float r = coef[0] * fast_exp2(fmaf(mix_one<NCAP>(p, n, l, ref), p.scale, -off[0]));
       f[k] = fmaxf(r - q, 0.0f);
     }
   }
@@ -125,14 +129,14 @@ template <typename T, int NCAP, int MODE>
 __device__ __forceinline__ void tile_eval(const Params& p, const float (&x)[NCAP][VecOf<T>::N], int n,
                                           int tile, int pi, int plain, float m0,
                                           const float (&coef)[NCAP], const float (&off)[NCAP],
-                                          float (&f)[VecOf<T>::N]) {
+                                          const float (&ref)[NCAP], float (&f)[VecOf<T>::N]) {
   constexpr int N = VecOf<T>::N;
   if constexpr (MODE == kEns)
     eval_f_ensemble<NCAP, N>(x, n, p.scale, coef, off, f);
   else if constexpr (MODE == kMix)
-    eval_f_mix<NCAP, N>(x, n, pi, plain, p, coef, off, f);
+    eval_f_mix<NCAP, N>(x, n, pi, plain, p, coef, off, ref, f);
   else
-    eval_f_contrastive<T, N>(x[0], x[1], pi, plain, m0, p, coef, off, f);
+    eval_f_contrastive<T, N>(x[0], x[1], pi, plain, m0, p, coef, off, ref, f);
   if (tile * 64 + lane_id() >= p.nvec) {
 #pragma unroll
     for (int k = 0; k < N; ++k) f[k] = 0.0f;
@@ -143,10 +147,10 @@ template <typename T, bool ALIGNED, int NCAP, int MODE>
 __device__ __forceinline__ void tile_weights(const Params& p, const T* const (&rows)[NCAP], int n,
                                              int tile, int pi, int plain, float m0,
                                              const float (&coef)[NCAP], const float (&off)[NCAP],
-                                             float (&f)[VecOf<T>::N]) {
+                                             const float (&ref)[NCAP], float (&f)[VecOf<T>::N]) {
   float x[NCAP][VecOf<T>::N];
   tile_load<T, ALIGNED, NCAP>(p, rows, n, tile, x);
-  tile_eval<T, NCAP, MODE>(p, x, n, tile, pi, plain, m0, coef, off, f);
+  tile_eval<T, NCAP, MODE>(p, x, n, tile, pi, plain, m0, coef, off, ref, f);
 }
 
 template <int N>
@@ -165,7 +169,7 @@ __device__ __forceinline__ double lane_mass(const float (&f)[N]) {
 template <typename T, bool ALIGNED, int NCAP, int MODE>
 __device__ bool draw_token(const Params& p, int b, const SeqPlan& plan, const T* const (&rows)[NCAP],
                            int n, const float (&coef)[NCAP], const float (&off)[NCAP],
-                           const double* tile_sum, bool may_retry, int flags) {
+                           const float (&ref)[NCAP], const double* tile_sum, bool may_retry, int flags) {
   constexpr int N = VecOf<T>::N;
   const int lane = lane_id();
   const int g1 = p.gamma + 1;
@@ -218,7 +222,7 @@ __device__ bool draw_token(const Params& p, int b, const SeqPlan& plan, const T*
 
   // the same f values of that one tile, scanned element by element
   float f[N];
-  tile_weights<T, ALIGNED, NCAP, MODE>(p, rows, n, tile, plan.pi, plan.bonus, plan.m0, coef, off, f);
+  tile_weights<T, ALIGNED, NCAP, MODE>(p, rows, n, tile, plan.pi, plan.bonus, plan.m0, coef, off, ref, f);
   const double lane_tot = lane_mass<N>(f);
   const double lincl = wave_inclusive_scan(lane_tot);
   const double lup = __shfl_up(lincl, 1, 64);
@@ -298,6 +302,9 @@ __global__ void __launch_bounds__(kThreads) sample_kernel(Params p) {
     rows[m] = row_ptr<T>(p, one_row ? plan.bonus : (m < n ? m : 0), b, plan.jstar);
   float coef[NCAP], off[NCAP];
   plan_coefficients<NCAP, MODE>(p, plan, plan.residual != 0, n, coef, off);
+  float ref[NCAP];  // per-row reference of the logit-level combinations (unused by the ensemble)
+#pragma unroll
+  for (int m = 0; m < NCAP; ++m) ref[m] = (MODE != kEns && m < n) ? row_reference<T>(rows[m]) : 0.0f;
 
   double* sums = p.tile_sums + (size_t)b * p.ntiles;
   const int tb = c * p.tpc;
@@ -313,7 +320,7 @@ __global__ void __launch_bounds__(kThreads) sample_kernel(Params p) {
       const int ti = t + i * kWaves;
       float f[N];
       tile_eval<T, NCAP, MODE>(p, x[i], n, min(ti, te - 1), plan.pi, plan.bonus, plan.m0, coef,
-                                      off, f);
+                               off, ref, f);
       const double ts = wave_sum_to_lane63(lane_mass<N>(f));
       if (lane == 63 && ti < te) tile_sum[ti - tb] = ts;  // staged in LDS
     }
@@ -329,7 +336,7 @@ __global__ void __launch_bounds__(kThreads) sample_kernel(Params p) {
   __syncthreads();
   bool done = false;
   if (wave == 0)
-    done = draw_token<T, ALIGNED, NCAP, MODE>(p, b, plan, rows, n, coef, off, tile_sum,
+    done = draw_token<T, ALIGNED, NCAP, MODE>(p, b, plan, rows, n, coef, off, ref, tile_sum,
                                                      plan.residual != 0, 0);
   if (threadIdx.x == 0) s_flag = done ? 0 : 1;
   __syncthreads();
@@ -340,13 +347,13 @@ __global__ void __launch_bounds__(kThreads) sample_kernel(Params p) {
   plan_coefficients<NCAP, MODE>(p, plan, false, n, coef, off);
   for (int t = wave; t < p.ntiles; t += kWaves) {
     float f[N];
-    tile_weights<T, ALIGNED, NCAP, MODE>(p, rows, n, t, plan.pi, plan.bonus, plan.m0, coef, off, f);
+    tile_weights<T, ALIGNED, NCAP, MODE>(p, rows, n, t, plan.pi, plan.bonus, plan.m0, coef, off, ref, f);
     const double ts = wave_sum(lane_mass<N>(f));
     if (lane == 0) tile_sum[t] = ts;
   }
   __syncthreads();
   if (wave == 0)
-    draw_token<T, ALIGNED, NCAP, MODE>(p, b, plan, rows, n, coef, off, tile_sum, false,
+    draw_token<T, ALIGNED, NCAP, MODE>(p, b, plan, rows, n, coef, off, ref, tile_sum, false,
                                               COS_FLAG_RESIDUAL_FALLBACK);
 }
 
@@ -402,6 +409,12 @@ __global__ void __launch_bounds__(kThreads) acceptance_rate_kernel(Params p) {
   const T* rows[NCAP];
 #pragma unroll
   for (int m = 0; m < NCAP; ++m) rows[m] = row_ptr<T>(p, m < n ? m : 0, b, j);
+  float ref[NCAP];
+#pragma unroll
+  for (int m = 0; m < NCAP; ++m) ref[m] = (MODE != kEns && m < n) ? row_reference<T>(rows[m]) : 0.0f;
+  float refq = ref[0];  // the proposer row's reference
+#pragma unroll
+  for (int m = 1; m < NCAP; ++m) refq = (m == pi) ? ref[m] : refq;
 
   double acc = 0.0;
   const int tb = c * p.tpa;
@@ -425,13 +438,13 @@ __global__ void __launch_bounds__(kThreads) acceptance_rate_kernel(Params p) {
           float l[NCAP];
 #pragma unroll
           for (int m = 0; m < NCAP; ++m) l[m] = x[m][k];
-          r = cr[0] * fast_exp2(fmaf(mix_one<NCAP>(p, n, l), p.scale, -off[0]));
-          q = cq * fast_exp2(fmaf(pick_row<NCAP, N>(x, pi, k), p.scale, -off[1]));
+          r = cr[0] * fast_exp2(fmaf(mix_one<NCAP>(p, n, l, ref), p.scale, -off[0]));
+          q = cq * fast_exp2(fmaf(pick_row<NCAP, N>(x, pi, k) - refq, p.scale, -off[1]));
         } else {
           const bool in = in_mask<T>(x[0][k], m0, p.thr32, p.thr64);
-          const float cc = contrast(x[0][k], x[1][k], p.mu_hi, p.mu_lo);
+          const float cc = contrast(x[0][k], x[1][k], p.mu_hi, p.mu_lo, ref[0], ref[1]);
           r = in ? cr[0] * fast_exp2(fmaf(cc, p.scale, -off[0])) : 0.0f;
-          q = cq * fast_exp2(fmaf(pi ? x[1][k] : x[0][k], p.scale, -off[1]));
+          q = cq * fast_exp2(fmaf((pi ? x[1][k] : x[0][k]) - refq, p.scale, -off[1]));
         }
         acc += (double)fminf(q, r);
       }

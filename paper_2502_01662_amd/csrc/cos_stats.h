@@ -308,10 +308,14 @@ __device__ void decide_sequence(const Params& p, int b, DecideShared& sh) {
     double rd = 0.0, qd = 0.0;
     if constexpr (MODE == kMix) {
       // statistic 0: the proposer's row; statistic 1: the mixed logits
-      double c = 0.0;
+      double c = 0.0;  // on logits shifted by the row references, as the statistic was
       for (int m = 0; m < n; ++m)
-        if (p.w[m] != 0.0) c += p.w[m] * (double)widen(row_ptr<T>(p, m, b, j)[d]);
-      const double lq = (double)widen(row_ptr<T>(p, pi, b, j)[d]);
+        if (p.w[m] != 0.0) {
+          const T* row = row_ptr<T>(p, m, b, j);
+          c += p.w[m] * ((double)widen(row[d]) - (double)row_reference<T>(row));
+        }
+      const T* rowq = row_ptr<T>(p, pi, b, j);
+      const double lq = (double)widen(rowq[d]) - (double)row_reference<T>(rowq);
       rd = exp2(c * log2e - sh.lse2[jj * nstat + 1]);
       qd = exp2(lq * log2e - sh.lse2[jj * nstat + 0]);
     } else if constexpr (MODE == kEns) {
@@ -325,9 +329,12 @@ __device__ void decide_sequence(const Params& p, int b, DecideShared& sh) {
       const double l0 = (double)widen(row_ptr<T>(p, 0, b, j)[d]);
       const double l1 = (double)widen(row_ptr<T>(p, 1, b, j)[d]);
       const bool in = (l0 > -INFINITY) && (l0 - (double)sh.rowmax[jj] >= p.thr64);
-      const double c = l0 - p.w[0] * l1;
+      // on logits shifted by the row references, as both statistics were
+      const double d0 = l0 - (double)row_reference<T>(row_ptr<T>(p, 0, b, j));
+      const double d1 = l1 - (double)row_reference<T>(row_ptr<T>(p, 1, b, j));
+      const double c = d0 - p.w[0] * d1;
       rd = in ? exp2(c * log2e - sh.lse2[jj * nstat + 2]) : 0.0;
-      qd = exp2((pi ? l1 : l0) * log2e - sh.lse2[jj * nstat + pi]);
+      qd = exp2((pi ? d1 : d0) * log2e - sh.lse2[jj * nstat + pi]);
     }
     double ratio;
     if (!(rd > 0.0))
@@ -535,6 +542,7 @@ __global__ void __launch_bounds__(kThreads) contrastive_stats_kernel(Params p) {
 
   const T* row0 = row_ptr<T>(p, 0, b, j);
   const T* row1 = row_ptr<T>(p, 1, b, j);
+  const float ref0 = row_reference<T>(row0), ref1 = row_reference<T>(row1);
   const int v0 = s * p.cv;
   const int v1 = min(v0 + p.cv, p.nvec);
   Running rq, rc;  // proposer row; masked contrastive logits
@@ -549,11 +557,17 @@ __global__ void __launch_bounds__(kThreads) contrastive_stats_kernel(Params p) {
       load_group<T, ALIGNED, true, U>(row0, base, v1, p.V, x0);
       load_group<T, ALIGNED, true, U>(row1, base, v1, p.V, x1);
     }
-    // proposer row statistic
-    if (pi)
-      running_add<U, N>(rq, x1, p.scale);
-    else
-      running_add<U, N>(rq, x0, p.scale);
+    // proposer row statistic, on the shifted logits like the contrastive one: with mu = 0 and
+    // the expert proposing, r and q then see the very same numbers and cancel exactly
+    {
+      float xq[U][N];
+      const float refq = pi ? ref1 : ref0;
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int k = 0; k < N; ++k) xq[u][k] = (pi ? x1[u][k] : x0[u][k]) - refq;
+      running_add<U, N>(rq, xq, p.scale);
+    }
     // masked contrastive statistic; the mask is sparse, so skip wave-wide when empty
     float c[U][N];
     float lmc = -INFINITY;
@@ -562,7 +576,7 @@ __global__ void __launch_bounds__(kThreads) contrastive_stats_kernel(Params p) {
 #pragma unroll
       for (int k = 0; k < N; ++k) {
         const bool in = in_mask<T>(x0[u][k], m0, p.thr32, p.thr64);
-        c[u][k] = in ? contrast(x0[u][k], x1[u][k], p.mu_hi, p.mu_lo) : -INFINITY;
+        c[u][k] = in ? contrast(x0[u][k], x1[u][k], p.mu_hi, p.mu_lo, ref0, ref1) : -INFINITY;
         lmc = fmaxf(lmc, c[u][k]);
       }
     if (__ballot(lmc > -INFINITY)) running_add<U, N>(rc, c, p.scale);
@@ -633,6 +647,9 @@ __global__ void __launch_bounds__(kThreads) mix_stats_kernel(Params p) {
   const T* rows[NCAP];
 #pragma unroll
   for (int m = 0; m < NCAP; ++m) rows[m] = row_ptr<T>(p, m < n ? m : 0, b, j);
+  float ref[NCAP];
+#pragma unroll
+  for (int m = 0; m < NCAP; ++m) ref[m] = m < n ? row_reference<T>(rows[m]) : 0.0f;
   const int v0 = s * p.cv;
   const int v1 = min(v0 + p.cv, p.nvec);
   Running rq, rc;  // proposer row; mixed logits
@@ -650,6 +667,9 @@ __global__ void __launch_bounds__(kThreads) mix_stats_kernel(Params p) {
         if (m < n) load_group<T, ALIGNED, true, U>(rows[m], base, v1, p.V, x[m]);
     }
     float xq[U][N];
+    float refq = ref[0];
+#pragma unroll
+    for (int m = 1; m < NCAP; ++m) refq = (m == pi) ? ref[m] : refq;
 #pragma unroll
     for (int u = 0; u < U; ++u)
 #pragma unroll
@@ -660,7 +680,7 @@ __global__ void __launch_bounds__(kThreads) mix_stats_kernel(Params p) {
           const float xm = x[m][u][k];
           v = (m == pi) ? xm : v;
         }
-        xq[u][k] = v;
+        xq[u][k] = v - refq;  // shifted like the mixed logits: a one-hot mix on the proposer cancels exactly
       }
     running_add<U, N>(rq, xq, p.scale);
     if (!plain) {
@@ -672,7 +692,7 @@ __global__ void __launch_bounds__(kThreads) mix_stats_kernel(Params p) {
           float l[NCAP];
 #pragma unroll
           for (int m = 0; m < NCAP; ++m) l[m] = x[m][u][k];
-          c[u][k] = mix_one<NCAP>(p, n, l);
+          c[u][k] = mix_one<NCAP>(p, n, l, ref);
         }
       running_add<U, N>(rc, c, p.scale);
     }

@@ -127,3 +127,21 @@ def test_logit_mix_at_the_c5_shape_and_argument_checks():
     with pytest.raises(C.CosVerifyError):                    # temperature 0 is built for Eq. (5) only
         C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], MIX, beta, inp["u_accept"],
                      inp["u_resample"], greedy=True)
+
+
+@pytest.mark.parametrize("dtype,shift", [("f32", 0.0), ("f32", 500.0), ("bf16", 0.0), ("f16", 0.0)])
+def test_logit_level_modes_cancel_exactly_when_r_equals_q(dtype, shift):
+    """A one-hot mix on the proposer (or contrastive mu = 0 with the expert proposing) makes r == q;
+    a draft token of probability zero is still rejected, and the residual then has no mass at all:
+    the kernels must see exactly zero (and draw from r, flagged), not rounding noise."""
+    inp = _random_inputs(2, 6, 2, 3000, dtype, seed=33, std=2.0)
+    if shift:
+        inp["logits"] = (inp["logits"].double() + shift).to(inp["logits"].dtype)
+    inp["proposer_idx"][:] = 0
+    inp["draft_tokens"][:, 0] = 7
+    inp["logits"][:, :, 0, 7] = float("-inf")
+    for name, mode, w in (("mix one-hot", MIX, [1.0, 0.0]), ("contrastive mu=0", C.COS_COMBINE_CONTRASTIVE, [0.0, 0.0])):
+        alen, toks, diag, rep = _check(f"{name}, zero residual mass, {dtype} shift {shift}", inp, mode, w)
+        assert np.all(alen == 0)
+        assert np.all(diag.flags.cpu().numpy() & C.COS_FLAG_RESIDUAL_FALLBACK)
+        assert rep.flag_mismatches == 0

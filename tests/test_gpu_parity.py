@@ -278,6 +278,22 @@ def test_float16_workload_shapes():
     _check("float16, all negative", neg, C.COS_COMBINE_ENSEMBLE, [0.5, 0.5])
 
 
+@pytest.mark.parametrize("shift", [1000.0, -1000.0, 30000.0])
+def test_large_common_offset_of_the_logits(shift):
+    """Softmax is shift-invariant; float32 logits far from zero must not cost accuracy (the integer
+    offsets in the log2 domain absorb the shift exactly)."""
+    inp = _random_inputs(3, 6, 3, 20011, "f32", seed=90, std=2.5)
+    inp["logits"] = (inp["logits"].double() + shift).float()
+    top = inp["logits"][:, :, :3].float().mean(0).argmax(-1).to(torch.int32)
+    inp["draft_tokens"][::2] = top[::2]
+    alen, toks, diag, rep = _check(f"f32 logits shifted by {shift}", inp, C.COS_COMBINE_ENSEMBLE, [0.5, 0.3, 0.2])
+    assert len(set(alen.tolist())) >= 2
+    cd = {k: (v[:2].contiguous() if k == "logits" else v) for k, v in inp.items()}
+    cd["proposer_idx"] = cd["proposer_idx"] % 2
+    _check(f"f32 logits shifted by {shift}, contrastive", cd, C.COS_COMBINE_CONTRASTIVE, [0.5, 0.1])
+    _check(f"f32 logits shifted by {shift}, mix", inp, C.COS_COMBINE_LOGIT_MIX, [0.8, 0.5, -0.3])
+
+
 def test_non_default_stream():
     inp = W.generate(W.C1, device="cuda")
     s = torch.cuda.Stream()
