@@ -294,6 +294,31 @@ def test_large_common_offset_of_the_logits(shift):
     _check(f"f32 logits shifted by {shift}, mix", inp, C.COS_COMBINE_LOGIT_MIX, [0.8, 0.5, -0.3])
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32", "f16"])
+def test_nan_and_plus_inf_logits_leave_outputs_in_range(dtype):
+    """NaN and +inf logits have no defined result, but every call must finish and every integer it
+    writes must be a legal one (no index is ever derived from a floating-point value)."""
+    n, B, gamma, V = 2, 8, 3, 5000
+    for poison in (float("nan"), float("inf")):
+        inp = _random_inputs(n, B, gamma, V, dtype, seed=95)
+        inp["logits"][0, 0] = poison                       # a whole row group
+        inp["logits"][1, 1, 1, 17] = poison                # single elements
+        inp["logits"][0, 2, :, ::3] = poison
+        inp["logits"][:, 3] = poison                       # everything of one sequence
+        for mode, w, kw in ((C.COS_COMBINE_ENSEMBLE, [0.5, 0.5], {}), (C.COS_COMBINE_CONTRASTIVE, [0.5, 0.1], {}),
+                            (C.COS_COMBINE_LOGIT_MIX, [1.2, -0.2], {}), (C.COS_COMBINE_CONTRASTIVE, [0.5, 0.1], {"greedy": True}),
+                            (C.COS_COMBINE_ENSEMBLE, [0.5, 0.5], {"stop_window": 1})):
+            alpha = torch.zeros((B, gamma), dtype=torch.float64, device="cuda") if not kw else None
+            alen, toks = C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], mode, w,
+                                      inp["u_accept"], inp["u_resample"], alpha=alpha, **kw)
+            torch.cuda.synchronize()
+            a, t = alen.cpu().numpy(), toks.cpu().numpy()
+            assert np.all((a >= 0) & (a <= gamma)), (poison, mode, kw, a)
+            assert np.all((t >= -1) & (t < V)), (poison, mode, kw)
+            clean = [4, 5, 6, 7]                           # untouched sequences still verify normally
+            assert np.all(t[clean, a[clean]] >= 0) and np.all(t[clean, :1] >= 0)
+
+
 def test_non_default_stream():
     inp = W.generate(W.C1, device="cuda")
     s = torch.cuda.Stream()
