@@ -18,6 +18,7 @@ constexpr int kUnroll = 8;  // 16-byte loads in flight per lane and iteration
 constexpr float kLog2e = 1.44269504088896340736f;
 constexpr int kNoOffset = -(1 << 29);       // "no finite element seen yet"
 constexpr float kMaxOffset = 268435456.0f;  // 2^28: clamp for absurd logits
+constexpr float kOffNever = 1.0e30f;         // offset of a term that must evaluate to 0
 constexpr int kMaxSplits = 128;             // upper bound on chunks per row (workspace sizing)
 constexpr int kMaxStatsPerSeq = 256;        // (gamma+1) * statistics per position
 constexpr int kMaxTiles = 4096;             // tiles per row the final scan can hold in LDS

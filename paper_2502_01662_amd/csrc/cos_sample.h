@@ -87,8 +87,11 @@ __device__ __forceinline__ void plan_coefficients(const Params& p, const SeqPlan
                                                   int n, float (&coef)[NCAP], float (&off)[NCAP]) {
 #pragma unroll
   for (int m = 0; m < NCAP; ++m) {
+    // A term without weight must vanish whatever its logits are: with the offset far up,
+    // 2^(l*scale - off) is 0 for every finite l (with offset 0 a large logit would overflow
+    // to +inf, and 0 * inf would poison the sum).
     coef[m] = 0.0f;
-    off[m] = 0.0f;
+    off[m] = kOffNever;
     if (m < n || (MODE == kMix && m < 2)) {
       double a, lse;
       const bool plain = !residual && plan.bonus >= 0;  // bonus token from one model's softmax alone

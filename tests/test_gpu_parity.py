@@ -319,6 +319,29 @@ def test_nan_and_plus_inf_logits_leave_outputs_in_range(dtype):
             assert np.all(t[clean, a[clean]] >= 0) and np.all(t[clean, :1] >= 0)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("std", [0.0, 1e-3, 25.0])
+def test_flat_and_very_peaked_distributions(dtype, std):
+    """std = 0: every token equally likely (the draw is floor(u V)); std = 25: one or two tokens hold
+    all the mass and most probabilities underflow float32."""
+    n, B, gamma, V = 3, 10, 3, 30011
+    inp = _random_inputs(n, B, gamma, V, dtype, seed=97, std=std)
+    c = sum(inp["logits"][m, :, :gamma].float() for m in range(n))
+    inp["draft_tokens"][::2] = c.argmax(-1).to(torch.int32)[::2]
+    for mode, w in ((C.COS_COMBINE_ENSEMBLE, [0.5, 0.3, 0.2]), (C.COS_COMBINE_LOGIT_MIX, [0.6, 0.5, -0.1]),
+                    (C.COS_COMBINE_ENSEMBLE, [0.0, 1.0, 0.0]), (C.COS_COMBINE_LOGIT_MIX, [0.0, 1.0, 0.0])):
+        alen, toks, diag, rep = _check(f"std={std} {dtype} mode={mode} w={w}", inp, mode, w)
+    cd = {k: (v[:2].contiguous() if k == "logits" else v) for k, v in inp.items()}
+    cd["proposer_idx"] = cd["proposer_idx"] % 2
+    _check(f"std={std} {dtype} contrastive", cd, C.COS_COMBINE_CONTRASTIVE, [0.5, 0.1])
+    if std == 0.0:
+        # uniform r = q: everything accepted, the bonus token is floor(u V)
+        alen, toks, _, _ = _check("flat, ensemble", inp, C.COS_COMBINE_ENSEMBLE, [0.5, 0.3, 0.2])
+        assert np.all(alen == gamma)
+        want = np.floor(inp["u_resample"].cpu().numpy() * V).astype(np.int64)
+        assert np.all(np.abs(toks[:, gamma] - want) <= 1)
+
+
 def test_non_default_stream():
     inp = W.generate(W.C1, device="cuda")
     s = torch.cuda.Stream()
