@@ -71,6 +71,8 @@ typedef enum {
 /* Flags written to cos_diag_t.flags. */
 #define COS_FLAG_RESIDUAL_FALLBACK 1 /* residual mass was <= 0 or not finite: token drawn from r instead */
 #define COS_FLAG_TAIL_CLAMP 2        /* rounding left no prefix above u*F: last token with mass taken */
+#define COS_FLAG_RESIDUAL_REFINED 4  /* the residual had little mass (r close to q) and was re-evaluated in
+                                        its difference form q (r/q - 1); not an error */
 
 /* Optional per-row diagnostics; every member is a DEVICE pointer or NULL. */
 typedef struct cos_diag_t {
@@ -181,6 +183,17 @@ cos_status_t cos_verify(const void *logits, cos_dtype_t dt, int n, int B, int ga
  *               = -1 and the logits of that position are not read, so the
  *               tensor's last position may hold anything.  diag.sample_mass,
  *               cdf_lo, cdf_hi and flags of such a row are 0.
+ * refine_residual  non-zero: a residual max(0, r - q) whose mass is below 1/32 (r
+ *               close to q: an acceptance rate above 97 %) is evaluated once more in
+ *               its difference form q (r/q - 1) by one workgroup of the sequence
+ *               (flag COS_FLAG_RESIDUAL_REFINED).  The plain float32 evaluation
+ *               carries an absolute error of ~1e-7 of each probability, i.e. ~1e-7 / F
+ *               of the residual distribution with mass F: statistically irrelevant (such
+ *               a residual is drawn from with probability F), but with F below ~1e-2 the
+ *               drawn token can differ from a float64 reference for u_resample not near
+ *               any CDF edge.  With this option it agrees down to F ~ 1e-3 (then the
+ *               ~1e-7 accuracy of the float32 normalisers is the limit).  Costs about
+ *               1.5 % of the step (a second variant of the sampling kernel).
  */
 typedef struct cos_options_t {
   size_t struct_bytes;
@@ -192,6 +205,7 @@ typedef struct cos_options_t {
   int greedy;
   const int32_t *num_drafts;
   int no_bonus;
+  int refine_residual;
 } cos_options_t;
 
 /* cos_verify with extensions; options == NULL is exactly cos_verify. */

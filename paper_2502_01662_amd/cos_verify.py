@@ -26,6 +26,7 @@ COS_COMBINE_LOGIT_MIX = 2
 COS_OK = 0
 COS_FLAG_RESIDUAL_FALLBACK = 1
 COS_FLAG_TAIL_CLAMP = 2
+COS_FLAG_RESIDUAL_REFINED = 4
 
 
 class CosDiag(ctypes.Structure):
@@ -38,7 +39,7 @@ class CosOptions(ctypes.Structure):
     _fields_ = [("struct_bytes", ctypes.c_size_t), ("temperature", ctypes.c_double),
                 ("bonus_idx", ctypes.c_void_p), ("proposer_pos", ctypes.c_void_p), ("alpha", ctypes.c_void_p),
                 ("stop_window", ctypes.c_int), ("greedy", ctypes.c_int),
-                ("num_drafts", ctypes.c_void_p), ("no_bonus", ctypes.c_int)]
+                ("num_drafts", ctypes.c_void_p), ("no_bonus", ctypes.c_int), ("refine_residual", ctypes.c_int)]
 
 
 class CosVerifyError(RuntimeError):
@@ -169,7 +170,7 @@ def cos_verify(logits: torch.Tensor, draft_tokens: torch.Tensor, proposer_idx: t
                diag: Optional[Diagnostics] = None, temperature: float = 1.0,
                bonus_idx: Optional[torch.Tensor] = None, proposer_pos: Optional[torch.Tensor] = None,
                alpha: Optional[torch.Tensor] = None, stop_window: int = 0, greedy: bool = False,
-               num_drafts: Optional[torch.Tensor] = None, no_bonus: bool = False):
+               num_drafts: Optional[torch.Tensor] = None, no_bonus: bool = False, refine_residual: bool = False):
     """Enqueue one verification step on the current stream; returns (accepted_len, out_tokens).
 
     logits [n][B][gamma+1][V] (float32 or bfloat16), draft_tokens [B][gamma] int32,
@@ -179,7 +180,8 @@ def cos_verify(logits: torch.Tensor, draft_tokens: torch.Tensor, proposer_idx: t
     ``proposer_pos`` [B][gamma] int32, ``alpha`` [B][gamma] float64 (output: acceptance rates),
     ``stop_window`` (positions per streaming launch; later positions of a rejected sequence are not read),
     ``greedy`` (temperature 0, contrastive mode), ``num_drafts`` [B] int32 (drafts per row, each in
-    [0, gamma]), ``no_bonus`` (no extra token when every draft of a row is accepted).
+    [0, gamma]), ``no_bonus`` (no extra token when every draft of a row is accepted), ``refine_residual``
+    (residuals of little mass are evaluated once more in their difference form).
     """
     lib = load_library()
     if not logits.is_cuda:
@@ -209,7 +211,7 @@ def cos_verify(logits: torch.Tensor, draft_tokens: torch.Tensor, proposer_idx: t
                               or not alpha.is_contiguous() or alpha.device != dev):
         raise TypeError(f"alpha: want contiguous float64 {(B, gamma)} on {dev}")
     if (temperature != 1.0 or bonus_idx is not None or proposer_pos is not None or alpha is not None
-            or stop_window or greedy or num_drafts is not None or no_bonus):
+            or stop_window or greedy or num_drafts is not None or no_bonus or refine_residual):
         for name, t, shape in (("bonus_idx", bonus_idx, (B,)), ("proposer_pos", proposer_pos, (B, gamma)),
                                ("num_drafts", num_drafts, (B,))):
             if t is not None and (t.dtype != torch.int32 or tuple(t.shape) != shape or not t.is_contiguous()
@@ -219,7 +221,8 @@ def cos_verify(logits: torch.Tensor, draft_tokens: torch.Tensor, proposer_idx: t
                          bonus_idx.data_ptr() if bonus_idx is not None else None,
                          proposer_pos.data_ptr() if proposer_pos is not None else None,
                          alpha.data_ptr() if alpha is not None else None, int(stop_window), int(greedy),
-                         num_drafts.data_ptr() if num_drafts is not None else None, int(bool(no_bonus)))
+                         num_drafts.data_ptr() if num_drafts is not None else None, int(bool(no_bonus)),
+                         int(bool(refine_residual)))
     stream = torch.cuda.current_stream(dev).cuda_stream
     with torch.cuda.device(dev):
         st = lib.cos_verify_ex(logits.data_ptr(), dt, n, B, gamma, V, draft_tokens.data_ptr(),

@@ -81,6 +81,135 @@ __device__ __forceinline__ void eval_f_mix(const float (&x)[NCAP][N], int n, int
   }
 }
 
+// ---------------------------------------------------------------------------
+// the residual in its difference form, for r close to q
+// ---------------------------------------------------------------------------
+//
+// max(0, r - q) evaluated term by term rounds each softmax value to float32 on its
+// own: an absolute error of ~1e-7 of the value, harmless unless r - q is a small
+// fraction of it everywhere, i.e. unless the residual mass F = 1 - alpha is small.
+// Then the last workgroup of the sequence evaluates the residual once more as
+//   ensemble:     q(x) * sum_{m != pi} w_m (2^delta_m - 1),  delta_m = log2(s_m(x) / s_pi(x))
+//   logit level:  q(x) * (2^delta - 1),                      delta   = log2(r(x) / q(x))
+// (the ensemble form uses sum_m w_m = 1), whose error is relative to the small
+// differences themselves.
+
+// What the difference form needs beside the plain coefficients.
+template <int NCAP>
+struct Refine {
+  float coef_q, off_q;  // q(x) = coef_q 2^(l_pi(x)*scale - off_q)
+  float w[NCAP];        // ensemble: w_m (0 for the proposer); logit level: unused
+  float dlse[NCAP];     // ensemble: lse2_m - lse2_pi; logit level: slot 0 = lse2_r - lse2_q
+  float wsum_m1;        // sum of the weights - 1 (ensemble: within 1e-9 of zero, kept so the form is
+                        // exact; logit mix: sum_m beta_m - 1)
+};
+
+// 2^d - 1 for |d| <= 1 with an error relative to the result.
+__device__ __forceinline__ float exp2m1(float d) {
+  const float y = d * 0.69314718055994531f;
+  const float poly =
+      y * fmaf(y, fmaf(y, fmaf(y, fmaf(y, fmaf(y, 1.0f / 720.0f, 1.0f / 120.0f), 1.0f / 24.0f), 1.0f / 6.0f), 0.5f), 1.0f);
+  return fabsf(y) < 0.125f ? poly : fast_exp2(d) - 1.0f;
+}
+
+template <int NCAP, int MODE>
+__device__ __forceinline__ void plan_refine(const Params& p, const SeqPlan& plan, int n, Refine<NCAP>& rf) {
+  double lq;  // log2-sum-exp2 of the proposer's row
+  rf.wsum_m1 = 0.0f;
+  if constexpr (MODE == kEns) {
+    lq = plan.lse2[0];
+    double wsum = 0.0;
+#pragma unroll
+    for (int m = 1; m < NCAP; ++m) {
+      const double v = plan.lse2[m];  // value first, then the choice: no indexed access
+      lq = (m == plan.pi) ? v : lq;
+    }
+#pragma unroll
+    for (int m = 0; m < NCAP; ++m) {
+      const bool on = m < n && m != plan.pi && p.w[m] != 0.0;
+      rf.w[m] = on ? (float)p.w[m] : 0.0f;
+      rf.dlse[m] = on ? (float)(plan.lse2[m] - lq) : 0.0f;
+      if (m < n) wsum += p.w[m];
+    }
+    rf.wsum_m1 = (float)(wsum - 1.0);
+  } else if constexpr (MODE == kMix) {
+    lq = plan.lse2[0];
+    double bsum = 0.0;
+#pragma unroll
+    for (int m = 0; m < NCAP; ++m) {
+      rf.w[m] = rf.dlse[m] = 0.0f;
+      if (m < n) bsum += p.w[m];
+    }
+    rf.wsum_m1 = (float)(bsum - 1.0);  // sum_m beta_m - 1
+    rf.dlse[0] = (float)(plan.lse2[1] - lq);
+  } else {
+    const double l0 = plan.lse2[0], l1 = plan.lse2[1];
+    lq = plan.pi ? l1 : l0;
+#pragma unroll
+    for (int m = 0; m < NCAP; ++m) rf.w[m] = rf.dlse[m] = 0.0f;
+    rf.dlse[0] = (float)(plan.lse2[2] - lq);
+  }
+  const double K = rint(lq);
+  rf.off_q = (float)K;
+  rf.coef_q = (float)exp2(K - lq);
+}
+
+// The residual of one vector in its difference form.  `plainf` is the term-by-term
+// value, kept wherever the difference form does not apply (q(x) = 0, or a ratio
+// beyond a factor of two, where nothing cancels).  A term whose numerator is 0
+// (a -inf logit, a token outside the mask) has delta = -inf and 2^delta - 1 = -1
+// without any special case.
+template <typename T, int NCAP, int N, int MODE>
+__device__ __forceinline__ void eval_f_refined(const Params& p, const float (&x)[NCAP][N], int n, int pi,
+                                               float m0, const float (&ref)[NCAP], const Refine<NCAP>& rf,
+                                               const float (&plainf)[N], float (&f)[N]) {
+  float refq = ref[0];
+#pragma unroll
+  for (int m = 1; m < NCAP; ++m) refq = (m == pi) ? ref[m] : refq;
+#pragma unroll
+  for (int k = 0; k < N; ++k) {
+    const float lp = pick_row<NCAP, N>(x, pi, k);
+    const float q = rf.coef_q * fast_exp2(fmaf(lp - refq, p.scale, -rf.off_q));
+    float acc = rf.wsum_m1;
+    float far = 0.0f;  // largest finite |delta| of this element
+    if constexpr (MODE == kEns) {
+#pragma unroll
+      for (int m = 0; m < NCAP; ++m)
+        if (m < n && rf.w[m] != 0.0f) {
+          const float d = fmaf(x[m][k] - lp, p.scale, -rf.dlse[m]);
+          far = fmaxf(far, d == -INFINITY ? 0.0f : fabsf(d));
+          acc = fmaf(rf.w[m], exp2m1(d), acc);
+        }
+    } else {
+      // c(x) - l_pi(x) on the shifted logits, from differences between the models so that it
+      // rounds at their scale: sum_m beta_m (v_m - v_pi) + (sum_m beta_m - 1) v_pi
+      const float vp = lp - refq;
+      float cd;
+      if constexpr (MODE == kMix) {
+        cd = rf.wsum_m1 * vp;
+        bool dead = false;
+#pragma unroll
+        for (int m = 0; m < NCAP; ++m)
+          if (m < n && (p.beta_hi[m] != 0.0f || p.beta_lo[m] != 0.0f)) {
+            dead = dead || x[m][k] == -INFINITY;
+            const float dv = (x[m][k] - ref[m]) - vp;
+            cd = fmaf(p.beta_lo[m], dv, fmaf(p.beta_hi[m], dv, cd));
+          }
+        cd = dead ? -INFINITY : cd;
+      } else {
+        const float v1 = x[1][k] - ref[1];
+        cd = fmaf(-p.mu_lo, v1, fmaf(-p.mu_hi, v1, (x[0][k] - ref[0]) - vp));
+        cd = in_mask<T>(x[0][k], m0, p.thr32, p.thr64) ? cd : -INFINITY;
+      }
+      const float d = fmaf(cd, p.scale, -rf.dlse[0]);
+      far = d == -INFINITY ? 0.0f : fabsf(d);
+      acc = exp2m1(d);
+    }
+    // (NaN in `far` -- q(x) = 0 -- fails the comparison and keeps the plain value)
+    f[k] = (far <= 1.0f) ? fmaxf(q * acc, 0.0f) : plainf[k];
+  }
+}
+
 // Coefficients and integer offsets of the sampling weights from a sequence's plan.
 template <int NCAP, int MODE>
 __device__ __forceinline__ void plan_coefficients(const Params& p, const SeqPlan& plan, bool residual,
@@ -132,7 +261,8 @@ template <typename T, int NCAP, int MODE>
 __device__ __forceinline__ void tile_eval(const Params& p, const float (&x)[NCAP][VecOf<T>::N], int n,
                                           int tile, int pi, int plain, float m0,
                                           const float (&coef)[NCAP], const float (&off)[NCAP],
-                                          const float (&ref)[NCAP], float (&f)[VecOf<T>::N]) {
+                                          const float (&ref)[NCAP], float (&f)[VecOf<T>::N],
+                                          bool refined, const Refine<NCAP>& rf) {
   constexpr int N = VecOf<T>::N;
   if constexpr (MODE == kEns)
     eval_f_ensemble<NCAP, N>(x, n, p.scale, coef, off, f);
@@ -140,6 +270,12 @@ __device__ __forceinline__ void tile_eval(const Params& p, const float (&x)[NCAP
     eval_f_mix<NCAP, N>(x, n, pi, plain, p, coef, off, ref, f);
   else
     eval_f_contrastive<T, N>(x[0], x[1], pi, plain, m0, p, coef, off, ref, f);
+  if (refined) {  // wave-uniform: the residual once more, in its difference form
+    float g[N];
+    eval_f_refined<T, NCAP, N, MODE>(p, x, n, pi, m0, ref, rf, f, g);
+#pragma unroll
+    for (int k = 0; k < N; ++k) f[k] = g[k];
+  }
   if (tile * 64 + lane_id() >= p.nvec) {
 #pragma unroll
     for (int k = 0; k < N; ++k) f[k] = 0.0f;
@@ -150,10 +286,11 @@ template <typename T, bool ALIGNED, int NCAP, int MODE>
 __device__ __forceinline__ void tile_weights(const Params& p, const T* const (&rows)[NCAP], int n,
                                              int tile, int pi, int plain, float m0,
                                              const float (&coef)[NCAP], const float (&off)[NCAP],
-                                             const float (&ref)[NCAP], float (&f)[VecOf<T>::N]) {
+                                             const float (&ref)[NCAP], float (&f)[VecOf<T>::N],
+                                             bool refined, const Refine<NCAP>& rf) {
   float x[NCAP][VecOf<T>::N];
   tile_load<T, ALIGNED, NCAP>(p, rows, n, tile, x);
-  tile_eval<T, NCAP, MODE>(p, x, n, tile, pi, plain, m0, coef, off, ref, f);
+  tile_eval<T, NCAP, MODE>(p, x, n, tile, pi, plain, m0, coef, off, ref, f, refined, rf);
 }
 
 template <int N>
@@ -167,12 +304,17 @@ __device__ __forceinline__ double lane_mass(const float (&f)[N]) {
 // ---------------------------------------------------------------------------
 // final scan + inverse CDF of one sequence (wavefront 0 of the last sampling
 // workgroup); tile_sum holds the ntiles tile sums in LDS.
-// Returns false if the weights have no mass and may_retry is set.
+// Returns kDrawn, or without drawing: kNoMass if the weights have no mass and
+// may_retry is set, kLittleMass if their mass is below refine_below.
 // ---------------------------------------------------------------------------
+constexpr int kDrawn = 0, kNoMass = 1, kLittleMass = 2;
+constexpr double kRefineBelow = 1.0 / 32.0;  // residual mass under which the difference form is used
+
 template <typename T, bool ALIGNED, int NCAP, int MODE>
-__device__ bool draw_token(const Params& p, int b, const SeqPlan& plan, const T* const (&rows)[NCAP],
-                           int n, const float (&coef)[NCAP], const float (&off)[NCAP],
-                           const float (&ref)[NCAP], const double* tile_sum, bool may_retry, int flags) {
+__device__ int draw_token(const Params& p, int b, const SeqPlan& plan, const T* const (&rows)[NCAP],
+                          int n, const float (&coef)[NCAP], const float (&off)[NCAP],
+                          const float (&ref)[NCAP], const double* tile_sum, bool may_retry, int flags,
+                          double refine_below, bool refined, const Refine<NCAP>& rf) {
   constexpr int N = VecOf<T>::N;
   const int lane = lane_id();
   const int g1 = p.gamma + 1;
@@ -186,7 +328,8 @@ __device__ bool draw_token(const Params& p, int b, const SeqPlan& plan, const T*
   const double up = __shfl_up(incl, 1, 64);
   const double excl = lane ? up : 0.0;
   const bool bad = !(F > 0.0) || !(F < INFINITY);
-  if (bad && may_retry) return false;
+  if (bad && may_retry) return kNoMass;
+  if (!bad && F < refine_below) return kLittleMass;
 
   const double target = p.u_resample[b] * F;
   // first tile whose inclusive prefix exceeds the target; else the last tile with mass
@@ -225,7 +368,8 @@ __device__ bool draw_token(const Params& p, int b, const SeqPlan& plan, const T*
 
   // the same f values of that one tile, scanned element by element
   float f[N];
-  tile_weights<T, ALIGNED, NCAP, MODE>(p, rows, n, tile, plan.pi, plan.bonus, plan.m0, coef, off, ref, f);
+  tile_weights<T, ALIGNED, NCAP, MODE>(p, rows, n, tile, plan.pi, plan.bonus, plan.m0, coef, off, ref, f,
+                                       refined, rf);
   const double lane_tot = lane_mass<N>(f);
   const double lincl = wave_inclusive_scan(lane_tot);
   const double lup = __shfl_up(lincl, 1, 64);
@@ -274,12 +418,14 @@ __device__ bool draw_token(const Params& p, int b, const SeqPlan& plan, const T*
     if (p.diag.cdf_hi) p.diag.cdf_hi[b] = hi / F;
     if (p.diag.flags) p.diag.flags[b] = flags;
   }
-  return true;
+  return kDrawn;
 }
 
 // Sampling kernel.  Workgroup index -> (b, c): tiles [c*tpc, (c+1)*tpc) of the
 // sampled position's rows -> tile sums; the last workgroup of b draws the token.
-template <typename T, bool ALIGNED, int NM, int MODE>
+// REFINE: the variant that can re-evaluate a residual of little mass in its difference form
+// (a kernel of its own because that rare path costs the streaming loop scalar registers).
+template <typename T, bool ALIGNED, int NM, int MODE, bool REFINE>
 __global__ void __launch_bounds__(kThreads) sample_kernel(Params p) {
   constexpr int N = VecOf<T>::N;
   constexpr bool CONTRASTIVE = MODE == kCd;
@@ -288,6 +434,9 @@ __global__ void __launch_bounds__(kThreads) sample_kernel(Params p) {
   constexpr int TU = NCAP <= 4 ? 4 : 1;  // tiles in flight per wavefront
   extern __shared__ double tile_sum[];
   __shared__ int s_flag;
+  // parameters of the rarely used difference form: kept in LDS, not in scalar registers, which
+  // the streaming loop below needs for itself
+  __shared__ Refine<NCAP> s_rf;
 
   const int b = blockIdx.x / p.C;
   const int c = blockIdx.x - b * p.C;
@@ -309,6 +458,7 @@ __global__ void __launch_bounds__(kThreads) sample_kernel(Params p) {
 #pragma unroll
   for (int m = 0; m < NCAP; ++m) ref[m] = (MODE != kEns && m < n) ? row_reference<T>(rows[m]) : 0.0f;
 
+  const Refine<NCAP> no_refine = {};  // the plain, term-by-term evaluation
   double* sums = p.tile_sums + (size_t)b * p.ntiles;
   const int tb = c * p.tpc;
   const int te = min(tb + p.tpc, p.ntiles);
@@ -323,7 +473,7 @@ __global__ void __launch_bounds__(kThreads) sample_kernel(Params p) {
       const int ti = t + i * kWaves;
       float f[N];
       tile_eval<T, NCAP, MODE>(p, x[i], n, min(ti, te - 1), plan.pi, plan.bonus, plan.m0, coef,
-                               off, ref, f);
+                               off, ref, f, false, no_refine);
       const double ts = wave_sum_to_lane63(lane_mass<N>(f));
       if (lane == 63 && ti < te) tile_sum[ti - tb] = ts;  // staged in LDS
     }
@@ -337,27 +487,57 @@ __global__ void __launch_bounds__(kThreads) sample_kernel(Params p) {
   // last workgroup of this sequence: all tile sums are published
   for (int t = threadIdx.x; t < p.ntiles; t += kThreads) tile_sum[t] = load_agent(sums + t);
   __syncthreads();
-  bool done = false;
+  const bool residual = plan.residual != 0;
+  int status = kDrawn;
   if (wave == 0)
-    done = draw_token<T, ALIGNED, NCAP, MODE>(p, b, plan, rows, n, coef, off, ref, tile_sum,
-                                                     plan.residual != 0, 0);
-  if (threadIdx.x == 0) s_flag = done ? 0 : 1;
+    status = draw_token<T, ALIGNED, NCAP, MODE>(p, b, plan, rows, n, coef, off, ref, tile_sum, residual, 0,
+                                                (REFINE && residual) ? kRefineBelow : 0.0, false, no_refine);
+  if (threadIdx.x == 0) s_flag = status;
   __syncthreads();
-  if (!s_flag) return;
+  status = s_flag;
+  if (status == kDrawn) return;
+  __syncthreads();  // s_flag is written again below
+
+  if (REFINE && status == kLittleMass) {
+    // r is close to q: this one workgroup evaluates the residual of the whole row once more,
+    // in its difference form, and draws from that
+    if (threadIdx.x == 0) {
+      // read the plan again rather than keeping its normalisers in registers across the
+      // streaming loop above, which every sequence runs
+      const SeqPlan again = p.plans[b];
+      plan_refine<NCAP, MODE>(p, again, n, s_rf);
+    }
+    __syncthreads();
+    const Refine<NCAP>& rf = s_rf;
+    for (int t = wave; t < p.ntiles; t += kWaves) {
+      float f[N];
+      tile_weights<T, ALIGNED, NCAP, MODE>(p, rows, n, t, plan.pi, plan.bonus, plan.m0, coef, off, ref, f, true, rf);
+      const double ts = wave_sum(lane_mass<N>(f));
+      if (lane == 0) tile_sum[t] = ts;
+    }
+    __syncthreads();
+    if (wave == 0)
+      status = draw_token<T, ALIGNED, NCAP, MODE>(p, b, plan, rows, n, coef, off, ref, tile_sum, true,
+                                                  COS_FLAG_RESIDUAL_REFINED, 0.0, true, rf);
+    if (threadIdx.x == 0) s_flag = status;
+    __syncthreads();
+    if (s_flag == kDrawn) return;
+  }
 
   // The residual has no mass (cannot happen in exact arithmetic): draw from r
   // itself.  Rare, so this one workgroup recomputes every tile sum.
   plan_coefficients<NCAP, MODE>(p, plan, false, n, coef, off);
   for (int t = wave; t < p.ntiles; t += kWaves) {
     float f[N];
-    tile_weights<T, ALIGNED, NCAP, MODE>(p, rows, n, t, plan.pi, plan.bonus, plan.m0, coef, off, ref, f);
+    tile_weights<T, ALIGNED, NCAP, MODE>(p, rows, n, t, plan.pi, plan.bonus, plan.m0, coef, off, ref, f, false,
+                                         no_refine);
     const double ts = wave_sum(lane_mass<N>(f));
     if (lane == 0) tile_sum[t] = ts;
   }
   __syncthreads();
   if (wave == 0)
     draw_token<T, ALIGNED, NCAP, MODE>(p, b, plan, rows, n, coef, off, ref, tile_sum, false,
-                                              COS_FLAG_RESIDUAL_FALLBACK);
+                                       COS_FLAG_RESIDUAL_FALLBACK, 0.0, false, no_refine);
 }
 
 // Acceptance-rate kernel (optional): alpha = sum_x min(q(x), r(x)) of Eq. (7) for

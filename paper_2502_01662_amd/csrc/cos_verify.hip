@@ -164,25 +164,31 @@ void choose_sampling(int B, int ntiles, int* C_out, int* tpc_out) {
 
 // Kernels that hold the rows of all n models in registers are specialised for
 // n = 1..4 on the aligned path; everything else takes the generic instance.
-template <typename T, bool ALIGNED, int MODE>
-cos_status_t launch_sampling(const Params& p, size_t lds, hipStream_t st) {
+template <typename T, bool ALIGNED, int MODE, bool REFINE>
+cos_status_t launch_sampling_variant(const Params& p, size_t lds, hipStream_t st) {
   const long blocks = (long)p.B * p.C;
   if (blocks <= 0 || blocks > 0x7fffffffL) return COS_ERR_SHAPE;
   const dim3 grid((unsigned)blocks), block(kThreads);
   if constexpr (MODE == kCd) {
-    hipLaunchKernelGGL((sample_kernel<T, ALIGNED, 2, kCd>), grid, block, lds, st, p);
+    hipLaunchKernelGGL((sample_kernel<T, ALIGNED, 2, kCd, REFINE>), grid, block, lds, st, p);
   } else if constexpr (ALIGNED) {
     switch (p.n) {
-      case 1: hipLaunchKernelGGL((sample_kernel<T, true, 1, MODE>), grid, block, lds, st, p); break;
-      case 2: hipLaunchKernelGGL((sample_kernel<T, true, 2, MODE>), grid, block, lds, st, p); break;
-      case 3: hipLaunchKernelGGL((sample_kernel<T, true, 3, MODE>), grid, block, lds, st, p); break;
-      case 4: hipLaunchKernelGGL((sample_kernel<T, true, 4, MODE>), grid, block, lds, st, p); break;
-      default: hipLaunchKernelGGL((sample_kernel<T, true, 0, MODE>), grid, block, lds, st, p); break;
+      case 1: hipLaunchKernelGGL((sample_kernel<T, true, 1, MODE, REFINE>), grid, block, lds, st, p); break;
+      case 2: hipLaunchKernelGGL((sample_kernel<T, true, 2, MODE, REFINE>), grid, block, lds, st, p); break;
+      case 3: hipLaunchKernelGGL((sample_kernel<T, true, 3, MODE, REFINE>), grid, block, lds, st, p); break;
+      case 4: hipLaunchKernelGGL((sample_kernel<T, true, 4, MODE, REFINE>), grid, block, lds, st, p); break;
+      default: hipLaunchKernelGGL((sample_kernel<T, true, 0, MODE, REFINE>), grid, block, lds, st, p); break;
     }
   } else {
-    hipLaunchKernelGGL((sample_kernel<T, false, 0, MODE>), grid, block, lds, st, p);
+    hipLaunchKernelGGL((sample_kernel<T, false, 0, MODE, REFINE>), grid, block, lds, st, p);
   }
   return hipGetLastError() == hipSuccess ? COS_OK : COS_ERR_LAUNCH;
+}
+
+template <typename T, bool ALIGNED, int MODE>
+cos_status_t launch_sampling(const Params& p, size_t lds, hipStream_t st) {
+  return p.refine ? launch_sampling_variant<T, ALIGNED, MODE, true>(p, lds, st)
+                  : launch_sampling_variant<T, ALIGNED, MODE, false>(p, lds, st);
 }
 
 template <typename T, bool ALIGNED, int MODE>
@@ -372,6 +378,7 @@ cos_status_t cos_verify_ex(const void* logits, cos_dtype_t dt, int n, int B, int
   p.bonus_idx = options ? options->bonus_idx : nullptr;
   p.num_drafts = options ? options->num_drafts : nullptr;
   p.no_bonus = (options && options->no_bonus) ? 1 : 0;
+  p.refine = (options && options->refine_residual) ? 1 : 0;
   p.u_accept = u_accept;
   p.u_resample = u_resample;
   p.accepted_len = accepted_len;
@@ -510,7 +517,7 @@ const char* cos_status_string(cos_status_t status) {
   return "unknown status";
 }
 
-int cos_verify_version(void) { return 3; }
+int cos_verify_version(void) { return 4; }
 
 cos_status_t cos_profile_enable(int slots) {
   if (slots < 0 || slots > kMaxProfileSlots) return COS_ERR_SHAPE;

@@ -394,3 +394,53 @@ def test_ragged_rows_at_the_c5_shape():
     full = P.run_gpu(base, w.mode, w.weights)
     # a shorter row is a prefix of the full row's verification
     assert np.array_equal(alen, np.minimum(full[0], nd.numpy()))
+
+
+# ---------------------------------------------------------------------------
+# refine_residual: r close to q (acceptance rates above 97 %), rejection forced
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("mode,weights,n,noise", [(C.COS_COMBINE_ENSEMBLE, [0.5, 0.5], 2, 0.03),
+                                                  (C.COS_COMBINE_ENSEMBLE, [0.5, 0.5], 2, 0.003),
+                                                  (C.COS_COMBINE_ENSEMBLE, [0.4, 0.35, 0.25], 3, 0.03),
+                                                  (C.COS_COMBINE_ENSEMBLE, [0.4, 0.35, 0.25], 3, 0.003),
+                                                  (C.COS_COMBINE_CONTRASTIVE, [0.002, 0.0], 2, 0.03),   # mu -> 0: r -> softmax(l_0)
+                                                  (C.COS_COMBINE_LOGIT_MIX, [0.5, 0.5], 2, 0.03)])
+def test_residual_of_nearly_identical_models(mode, weights, n, noise):
+    """Models that differ by a little noise: the residual mass is 1e-2 ... 1e-4 of a probability, far
+    below what term-by-term float32 resolves; with refine_residual every drawn token must still be
+    the float64 reference's (u_accept -> 1 forces the rejections that never happen otherwise).
+    Residual masses of ~1e-2 (noise 0.03) in every mode, ~1e-3 for ensembles, whose normalisers'
+    rounding errors are correlated between nearly identical rows; below that the ~1e-7 accuracy of the
+    float32 normalisers themselves is the limit."""
+    B, gamma, V = 256, 2, 32000
+    inp = _random_inputs(1, B, gamma, V, "f32", seed=5, std=2.5)
+    g = torch.Generator().manual_seed(3)
+    base = inp["logits"][0].double().cpu()
+    inp["logits"] = torch.stack([(base + torch.randn(base.shape, generator=g, dtype=torch.float64) * noise).float()
+                                 for _ in range(n)]).cuda()
+    inp["proposer_idx"] = torch.zeros(B, dtype=torch.int32).cuda()
+    inp["u_accept"][:] = 1.0 - 1e-12
+    # the proposer's favourite token: a slightly flatter r gives it less than q does, so it is rejected
+    inp["draft_tokens"][:, 0] = inp["logits"][0, :, 0].argmax(-1).to(torch.int32)
+    diag = C.Diagnostics.allocate(B, gamma, "cuda")
+    alen, toks = C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], mode, weights,
+                              inp["u_accept"], inp["u_resample"], diag=diag, refine_residual=True)
+    torch.cuda.synchronize()
+    rep = P.compare(inp, mode, weights, alen.cpu().numpy(), toks.cpu().numpy(), diag)
+    flags = diag.flags.cpu().numpy()
+    print(f"[parity] nearly identical models, noise {noise}, mode {mode}: {rep.summary()}, refined "
+          f"{int((flags & C.COS_FLAG_RESIDUAL_REFINED != 0).sum())}/{B}, median F {np.median(diag.sample_mass.cpu().numpy()):.2e}", flush=True)
+    assert rep.ok, rep.failures[:3]
+    assert (flags & C.COS_FLAG_RESIDUAL_REFINED != 0).sum() > B // 4
+    assert rep.excused_accept_ties + rep.excused_cdf_ties <= 3
+
+
+def test_refine_residual_changes_nothing_when_the_residual_has_mass():
+    w = W.C3.scaled(B=16)
+    inp = W.generate(w, device="cuda")
+    a = P.run_gpu(inp, w.mode, w.weights)
+    alen, toks = C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], w.mode, w.weights,
+                              inp["u_accept"], inp["u_resample"], refine_residual=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(a[0], alen.cpu().numpy()) and np.array_equal(a[1], toks.cpu().numpy())

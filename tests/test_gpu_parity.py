@@ -342,6 +342,41 @@ def test_flat_and_very_peaked_distributions(dtype, std):
         assert np.all(np.abs(toks[:, gamma] - want) <= 1)
 
 
+def test_many_sequences_of_a_tiny_vocabulary():
+    """Thousands of rows of ten tokens: one partial vector per row, the grid is all hand-off."""
+    inp = _random_inputs(2, 4096, 2, 10, "f32", seed=98, std=1.0)
+    alen, toks, diag, rep = _check("B=4096 V=10", inp, C.COS_COMBINE_ENSEMBLE, [0.5, 0.5])
+    assert len(set(alen.tolist())) == 3
+    inp = _random_inputs(2, 3000, 1, 8, "bf16", seed=99, std=1.0)
+    _check("B=3000 V=8 contrastive", inp, C.COS_COMBINE_CONTRASTIVE, [0.5, 0.1])
+
+
+def test_draft_the_proposer_thinks_impossible_is_accepted_when_r_allows_it():
+    """q(d) = 0 < r(d): the ratio is +inf, accepted whatever u is; r(d) = q(d) = 0: rejected."""
+    n, B, gamma, V = 2, 8, 2, 4096
+    inp = _random_inputs(n, B, gamma, V, "bf16", seed=100, std=1.5)
+    inp["proposer_idx"][:] = 0
+    inp["draft_tokens"][:, 0] = 11
+    inp["logits"][0, :, 0, 11] = float("-inf")               # the proposer rules token 11 out at position 0
+    inp["logits"][1, 4:, 0, 11] = float("-inf")              # ... and for half the rows the other model does too
+    inp["u_accept"][:, 0] = float(np.nextafter(1.0, 0.0))
+    alen, toks, diag, rep = _check("q(d) = 0", inp, C.COS_COMBINE_ENSEMBLE, [0.5, 0.5])
+    assert np.all(alen[:4] >= 1) and np.all(alen[4:] == 0)
+    assert np.all(diag.q_at_draft.cpu().numpy()[:, 0] == 0.0)
+    assert np.all(toks[4:, 0] != 11)                         # a token of probability zero is never drawn
+
+
+@pytest.mark.parametrize("T", [0.05, 20.0])
+def test_extreme_temperatures(T):
+    for mode, w, n in ((C.COS_COMBINE_ENSEMBLE, [0.5, 0.3, 0.2], 3), (C.COS_COMBINE_CONTRASTIVE, [0.5, 0.1], 2),
+                       (C.COS_COMBINE_LOGIT_MIX, [0.7, 0.6, -0.3], 3)):
+        inp = _random_inputs(n, 8, 3, 20011, "bf16", seed=101 + n, std=2.0)
+        c = inp["logits"][0, :, :3].float()
+        inp["draft_tokens"][::2] = c.argmax(-1).to(torch.int32)[::2]
+        inp["temperature"] = T
+        _check(f"T={T} mode={mode}", inp, mode, w)
+
+
 def test_non_default_stream():
     inp = W.generate(W.C1, device="cuda")
     s = torch.cuda.Stream()
