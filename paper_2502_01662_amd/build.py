@@ -21,6 +21,17 @@ HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-value"]
 
 
+def library_is_stale() -> bool:
+    """True if the library is missing or older than any of its sources (kernels, headers, the ABI)."""
+    if not os.path.exists(LIBRARY):
+        return True
+    built = os.path.getmtime(LIBRARY)
+    csrc = os.path.join(_PKG, "csrc")
+    deps = [os.path.join(csrc, f) for f in os.listdir(csrc) if f.startswith("cos_") and f != "cos_verify_driver.hip"]
+    deps.append(os.path.join(INCLUDE, "cos_verify.h"))
+    return any(os.path.getmtime(d) > built for d in deps)
+
+
 def build_library(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [hipcc, *HIPCC_FLAGS, "-I", INCLUDE, "-o", LIBRARY, *SOURCES]
