@@ -55,8 +55,8 @@ def load_library() -> ctypes.CDLL:
     """Load the in-tree library; build it first if it was never built."""
     global _lib
     if _lib is None:
-        from .build import build_library, library_is_stale
-        if library_is_stale():      # never built, or older than its sources
+        if not os.path.exists(LIBRARY):   # only if nothing is built: a built library is used as it is
+            from .build import build_library
             build_library()
         lib = ctypes.CDLL(LIBRARY)
         vp, ci, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
