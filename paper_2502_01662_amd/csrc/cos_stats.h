@@ -248,6 +248,29 @@ __device__ void decide_sequence(const Params& p, int b, DecideShared& sh) {
   const int gb = drafts_of(p, b);
   const double log2e = (double)p.scale;  // log2(e) / T, the same constant the streaming kernel used
 
+  // 0. The loads that do not depend on the statistics go out first, so that their latency
+  //    (draft token, then the n logits at it) overlaps the combine of step 1.
+  const int ndraft = max(min(j0 + nj, gb) - j0, 0);  // draft positions in the window
+  int d = 0, pi = 0;
+  double u_acc = 0.0;
+  double lgat[COS_MAX_MODELS], rgat[COS_MAX_MODELS];  // logits at the draft token; row references
+#pragma unroll
+  for (int m = 0; m < COS_MAX_MODELS; ++m) lgat[m] = rgat[m] = 0.0;
+  if (tid < ndraft) {
+    const int j = j0 + tid;
+    const size_t k = (size_t)b * p.gamma + j;
+    d = p.draft[k];
+    pi = p.proposer_pos ? p.proposer_pos[k] : p.proposer[b];
+    u_acc = p.u_accept[k];
+#pragma unroll
+    for (int m = 0; m < COS_MAX_MODELS; ++m)
+      if (m < n) {
+        const T* row = row_ptr<T>(p, m, b, j);
+        lgat[m] = (double)widen(row[d]);
+        if constexpr (MODE != kEns) rgat[m] = (double)row_reference<T>(row);
+      }
+  }
+
   // 1. combine the chunk partials of every (position, statistic) of the window in float64.
   //    A group of G lanes (a power of two >= S, at most a wavefront) shares the S partials of
   //    one statistic, so that a row cut into many chunks (small batches) costs a few dependent
@@ -295,43 +318,41 @@ __device__ void decide_sequence(const Params& p, int b, DecideShared& sh) {
   __syncthreads();
 
   // 2. Eq. (6) for every draft position of the window, in float64
-  const int ndraft = max(min(j0 + nj, gb) - j0, 0);  // draft positions in the window
   if (tid >= ndraft && tid < nj && j0 + tid < p.gamma) {  // no draft here
     if (p.diag.r_at_draft) p.diag.r_at_draft[(size_t)b * p.gamma + j0 + tid] = NAN;
     if (p.diag.q_at_draft) p.diag.q_at_draft[(size_t)b * p.gamma + j0 + tid] = NAN;
   }
   if (tid < ndraft) {
-    const int jj = tid, j = j0 + tid;
-    const size_t k = (size_t)b * p.gamma + j;
-    const int d = p.draft[k];
-    const int pi = p.proposer_pos ? p.proposer_pos[k] : p.proposer[b];
+    const int jj = tid;
+    const size_t k = (size_t)b * p.gamma + j0 + tid;
     double rd = 0.0, qd = 0.0;
     if constexpr (MODE == kMix) {
-      // statistic 0: the proposer's row; statistic 1: the mixed logits
-      double c = 0.0;  // on logits shifted by the row references, as the statistic was
-      for (int m = 0; m < n; ++m)
-        if (p.w[m] != 0.0) {
-          const T* row = row_ptr<T>(p, m, b, j);
-          c += p.w[m] * ((double)widen(row[d]) - (double)row_reference<T>(row));
+      // statistic 0: the proposer's row; statistic 1: the mixed logits; both on logits
+      // shifted by the row references, as the statistics were
+      double c = 0.0, lq = 0.0;
+#pragma unroll
+      for (int m = 0; m < COS_MAX_MODELS; ++m)
+        if (m < n) {
+          const double v = lgat[m] - rgat[m];
+          if (p.w[m] != 0.0) c += p.w[m] * v;
+          lq = (m == pi) ? v : lq;
         }
-      const T* rowq = row_ptr<T>(p, pi, b, j);
-      const double lq = (double)widen(rowq[d]) - (double)row_reference<T>(rowq);
       rd = exp2(c * log2e - sh.lse2[jj * nstat + 1]);
       qd = exp2(lq * log2e - sh.lse2[jj * nstat + 0]);
     } else if constexpr (MODE == kEns) {
-      for (int m = 0; m < n; ++m) {
-        const double l = (double)widen(row_ptr<T>(p, m, b, j)[d]);
-        const double s = exp2(l * log2e - sh.lse2[jj * nstat + m]);
-        rd += p.w[m] * s;
-        if (m == pi) qd = s;
-      }
+#pragma unroll
+      for (int m = 0; m < COS_MAX_MODELS; ++m)
+        if (m < n) {
+          const double s = exp2(lgat[m] * log2e - sh.lse2[jj * nstat + m]);
+          rd += p.w[m] * s;
+          qd = (m == pi) ? s : qd;
+        }
     } else {
-      const double l0 = (double)widen(row_ptr<T>(p, 0, b, j)[d]);
-      const double l1 = (double)widen(row_ptr<T>(p, 1, b, j)[d]);
+      const double l0 = lgat[0], l1 = lgat[1];
       const bool in = (l0 > -INFINITY) && (l0 - (double)sh.rowmax[jj] >= p.thr64);
       // on logits shifted by the row references, as both statistics were
-      const double d0 = l0 - (double)row_reference<T>(row_ptr<T>(p, 0, b, j));
-      const double d1 = l1 - (double)row_reference<T>(row_ptr<T>(p, 1, b, j));
+      const double d0 = l0 - rgat[0];
+      const double d1 = l1 - rgat[1];
       const double c = d0 - p.w[0] * d1;
       rd = in ? exp2(c * log2e - sh.lse2[jj * nstat + 2]) : 0.0;
       qd = exp2((pi ? d1 : d0) * log2e - sh.lse2[jj * nstat + pi]);
@@ -344,7 +365,7 @@ __device__ void decide_sequence(const Params& p, int b, DecideShared& sh) {
     else
       ratio = rd / qd;
     const double bound = ratio < 1.0 ? ratio : 1.0;
-    sh.accept[jj] = p.u_accept[k] < bound;
+    sh.accept[jj] = u_acc < bound;
     if (p.diag.r_at_draft) p.diag.r_at_draft[k] = rd;
     if (p.diag.q_at_draft) p.diag.q_at_draft[k] = qd;
   }
