@@ -138,6 +138,40 @@ def test_unaligned_base_pointer():
         _check(f"unaligned {dtype}", inp, C.COS_COMBINE_ENSEMBLE, [0.3, 0.7])
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32", "f16"])
+def test_unaligned_base_pointer_and_odd_vocabulary_in_every_mode(dtype):
+    """The element-wise path of every kernel: a base pointer off the 16-byte grid, a vocabulary that is
+    not a multiple of the vector width, more than four models, every extension that has a kernel."""
+    tdt = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[dtype]
+    for n, mode, w in ((5, C.COS_COMBINE_ENSEMBLE, [0.3, 0.2, 0.2, 0.2, 0.1]), (2, C.COS_COMBINE_CONTRASTIVE, [0.5, 0.1]),
+                       (3, C.COS_COMBINE_LOGIT_MIX, [0.8, 0.5, -0.3]), (6, C.COS_COMBINE_LOGIT_MIX, [0.3, 0.2, 0.2, 0.1, 0.1, 0.1])):
+        inp = _random_inputs(n, 5, 3, 3001, dtype, seed=50 + n, std=1.5)
+        c = inp["logits"][0, :, :3].float()
+        inp["draft_tokens"][::2] = c.argmax(-1).to(torch.int32)[::2]
+        flat = torch.empty(inp["logits"].numel() + 3, dtype=tdt, device="cuda")
+        flat[3:] = inp["logits"].reshape(-1)
+        inp["logits"] = flat[3:].view(inp["logits"].shape)
+        assert inp["logits"].data_ptr() % 16 != 0
+        _check(f"unaligned {dtype} n={n} mode={mode}", inp, mode, w)
+        alpha = torch.empty((5, 3), dtype=torch.float64, device="cuda")
+        C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], mode, w, inp["u_accept"],
+                     inp["u_resample"], alpha=alpha, refine_residual=True)
+        torch.cuda.synchronize()
+        a = alpha.cpu().numpy()
+        assert np.all((a > 0) & (a <= 1 + 1e-9))
+    greedy = _random_inputs(2, 5, 3, 3001, dtype, seed=57, std=1.5)
+    flat = torch.empty(greedy["logits"].numel() + 1, dtype=tdt, device="cuda")
+    flat[1:] = greedy["logits"].reshape(-1)
+    greedy["logits"] = flat[1:].view(greedy["logits"].shape)
+    from oracle import cos_oracle as O
+    alen, toks = C.cos_verify(greedy["logits"], greedy["draft_tokens"], greedy["proposer_idx"], C.COS_COMBINE_CONTRASTIVE,
+                              [0.5, 0.1], greedy["u_accept"], greedy["u_resample"], greedy=True)
+    torch.cuda.synchronize()
+    st, want_len, want_toks = O.verify_greedy(W.host_logits(greedy["logits"]), P.oracle_dtype(greedy["logits"]),
+                                              greedy["draft_tokens"].cpu().numpy(), [0.5, 0.1])
+    assert st == 0 and np.array_equal(alen.cpu().numpy(), want_len) and np.array_equal(toks.cpu().numpy(), want_toks)
+
+
 def test_maximum_vocabulary():
     inp = _random_inputs(2, 1, 1, 1 << 20, "bf16", seed=9)
     _check("V = 2^20", inp, C.COS_COMBINE_ENSEMBLE, [0.5, 0.5])
@@ -147,7 +181,42 @@ def test_maximum_vocabulary():
 
 def test_maximum_gamma_and_models():
     inp = _random_inputs(8, 2, 31, 640, "bf16", seed=11)
-    _check("n=8 gamma=31", inp, C.COS_COMBINE_ENSEMBLE, [0.125] * 8)
+    base = _check("n=8 gamma=31", inp, C.COS_COMBINE_ENSEMBLE, [0.125] * 8)
+    # identical models: all 31 drafts accepted, also one position (of 32) per launch
+    same = _random_inputs(1, 3, 31, 640, "bf16", seed=12)
+    same["logits"] = same["logits"].repeat(8, 1, 1, 1).contiguous()
+    for window in (0, 1, 5):
+        same["stop_window"] = window
+        alen, toks, _, _ = _check(f"n=8 gamma=31 identical models, window {window}", same, C.COS_COMBINE_ENSEMBLE, [0.125] * 8)
+        assert np.all(alen == 31)
+    for window in (1, 7):
+        inp["stop_window"] = window
+        alen, toks, _, _ = _check(f"n=8 gamma=31 window {window}", inp, C.COS_COMBINE_ENSEMBLE, [0.125] * 8)
+        assert np.array_equal(alen, base[0]) and np.array_equal(toks, base[1])
+
+
+def test_two_streams_with_their_own_workspaces_overlap():
+    """Calls that overlap in time need distinct workspaces, and with them they do not disturb each other."""
+    w = W.C3.scaled(B=16)
+    a_in, b_in = W.generate(w, device="cuda", step=0), W.generate(w, device="cuda", step=1)
+    want_a, want_b = P.run_gpu(a_in, w.mode, w.weights), P.run_gpu(b_in, w.mode, w.weights)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    ws1 = C.allocate_workspace(w.n, w.B, w.gamma, w.V, C.COS_DTYPE_BF16, w.mode, "cuda")
+    ws2 = C.allocate_workspace(w.n, w.B, w.gamma, w.V, C.COS_DTYPE_BF16, w.mode, "cuda")
+    torch.cuda.synchronize()
+    outs = []
+    for _ in range(5):
+        with torch.cuda.stream(s1):
+            ra = C.cos_verify(a_in["logits"], a_in["draft_tokens"], a_in["proposer_idx"], w.mode, w.weights,
+                              a_in["u_accept"], a_in["u_resample"], workspace=ws1)
+        with torch.cuda.stream(s2):
+            rb = C.cos_verify(b_in["logits"], b_in["draft_tokens"], b_in["proposer_idx"], w.mode, w.weights,
+                              b_in["u_accept"], b_in["u_resample"], workspace=ws2)
+        outs.append((ra, rb))
+    torch.cuda.synchronize()
+    for ra, rb in outs:
+        assert np.array_equal(ra[0].cpu().numpy(), want_a[0]) and np.array_equal(ra[1].cpu().numpy(), want_a[1])
+        assert np.array_equal(rb[0].cpu().numpy(), want_b[0]) and np.array_equal(rb[1].cpu().numpy(), want_b[1])
 
 
 # ---------------------------------------------------------------------------
