@@ -215,6 +215,20 @@ __device__ __forceinline__ uint4 load_stream16(const void* p) {
   return make_uint4(v.x, v.y, v.z, v.w);
 }
 
+// The same 16 bytes from an address that is only aligned to the element: one
+// global_load_dwordx4 as well (unaligned access is enabled for compute on this GPU).
+template <typename T>
+__device__ __forceinline__ uint4 load_stream16_unaligned(const T* p) {
+  typedef u32x4_t __attribute__((aligned(2))) u32x4_a2;
+  typedef u32x4_t __attribute__((aligned(4))) u32x4_a4;
+  u32x4_t v;
+  if constexpr (sizeof(T) == 2)
+    v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_a2*>(p));
+  else
+    v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_a4*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 __device__ __forceinline__ float widen(float x) { return x; }
 __device__ __forceinline__ float widen(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
 __device__ __forceinline__ float widen(_Float16 h) { return (float)h; }
@@ -280,7 +294,9 @@ __device__ __forceinline__ void unpack<_Float16>(const uint4& raw, float (&x)[8]
 
 // Vector `vec` of a row.  ALIGNED: the row is 16-byte aligned and V is a
 // multiple of the vector width, so every vector is one full 16-byte load.
-// Otherwise element loads with a bound check; elements past V read as -inf.
+// Otherwise rows start anywhere (an odd vocabulary): a vector that lies inside
+// the row is still one 16-byte load, from an element-aligned address; only the
+// row's last, partial vector is read element by element, past V as -inf.
 // The caller guarantees 0 <= vec < ceil(V / N).
 template <typename T, bool ALIGNED>
 __device__ __forceinline__ void load_vec(const T* __restrict__ row, int vec, int V,
@@ -291,8 +307,13 @@ __device__ __forceinline__ void load_vec(const T* __restrict__ row, int vec, int
     unpack<T>(raw, x);
   } else {
     const int base = vec * N;
+    if (base + N <= V) {
+      const uint4 raw = load_stream16_unaligned<T>(row + base);
+      unpack<T>(raw, x);
+    } else {
 #pragma unroll
-    for (int k = 0; k < N; ++k) x[k] = (base + k < V) ? widen(row[base + k]) : -INFINITY;
+      for (int k = 0; k < N; ++k) x[k] = (base + k < V) ? widen(row[base + k]) : -INFINITY;
+    }
   }
 }
 
