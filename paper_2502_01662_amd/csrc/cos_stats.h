@@ -85,13 +85,38 @@ __device__ __forceinline__ int wave_max_i32(int v) {
 
 // U raw vectors per lane starting at `base` (stride kThreads); vectors at or
 // past v1 are redirected to the in-range vector v1 - 1 (masked by the caller).
-template <typename T, int U>
+template <typename T, bool ALIGNED, int U>
 __device__ __forceinline__ void load_raw_group(const T* __restrict__ row, int base, int v1,
                                                uint4 (&raw)[U]) {
-  const uint4* src = reinterpret_cast<const uint4*>(row);
+  constexpr int N = VecOf<T>::N;
 #pragma unroll
-  for (int u = 0; u < U; ++u)
-    raw[u] = load_stream16(src + min(base + u * kThreads + (int)threadIdx.x, v1 - 1));
+  for (int u = 0; u < U; ++u) {
+    const size_t v = (size_t)min(base + u * kThreads + (int)threadIdx.x, v1 - 1);
+    raw[u] = ALIGNED ? load_stream16(row + v * N) : load_stream16_unaligned<T>(row + v * N);
+  }
+}
+
+// The last, partial vector of a row whose length is not a multiple of the vector
+// width: its elements one by one, the rest of the vector -inf.
+template <typename T>
+__device__ __forceinline__ uint4 load_tail_raw(const T* __restrict__ row, int first, int V) {
+  constexpr int N = VecOf<T>::N;
+  uint32_t w[4];
+  if constexpr (sizeof(T) == 4) {
+#pragma unroll
+    for (int k = 0; k < N; ++k)
+      w[k] = (first + k < V) ? __float_as_uint(widen(row[first + k])) : 0xff800000u;
+  } else {
+    const uint32_t ninf = IsBf16<T>::value ? 0xff80u : 0xfc00u;
+    const uint16_t* bits = reinterpret_cast<const uint16_t*>(row);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const uint32_t lo = (first + 2 * k < V) ? bits[first + 2 * k] : ninf;
+      const uint32_t hi = (first + 2 * k + 1 < V) ? bits[first + 2 * k + 1] : ninf;
+      w[k] = lo | (hi << 16);
+    }
+  }
+  return make_uint4(w[0], w[1], w[2], w[3]);
 }
 
 // Replace vectors at or past v1 by -inf (only the last, partial group needs it).
@@ -159,27 +184,22 @@ __device__ __forceinline__ void chunk_stats(const T* __restrict__ row, int v0, i
   constexpr int kStep = kThreads * kUnroll;
   Running run;
   running_init(run);
-  if constexpr (ALIGNED) {
-    // all kUnroll loads of a group are issued before the first use; only the
-    // last group of a chunk can be partial
-    for (int base = v0; base < v1; base += kStep) {
-      uint4 a[kUnroll];
-      load_raw_group<T, kUnroll>(row, base, v1, a);
-      if (base + kStep > v1) mask_raw_group<T, kUnroll>(base, v1, a);
-      running_add_raw<T, kUnroll>(run, a, scale);
-    }
-  } else {
-    int base = v0;
-    for (; base + kStep <= v1; base += kStep) {
-      float x[kUnroll][N];
-      load_group<T, ALIGNED, false, kUnroll>(row, base, v1, V, x);
-      running_add<kUnroll, N>(run, x, scale);
-    }
-    if (base < v1) {
-      float x[kUnroll][N];
-      load_group<T, ALIGNED, true, kUnroll>(row, base, v1, V, x);
-      running_add<kUnroll, N>(run, x, scale);
-    }
+  // vectors that lie inside the row; an odd vocabulary leaves one partial vector at its end
+  const int vfull = ALIGNED ? v1 : min(v1, V / N);
+  // all kUnroll loads of a group are issued before the first use; only the
+  // last group of a chunk can be partial
+  for (int base = v0; base < vfull; base += kStep) {
+    uint4 a[kUnroll];
+    load_raw_group<T, ALIGNED, kUnroll>(row, base, vfull, a);
+    if (base + kStep > vfull) mask_raw_group<T, kUnroll>(base, vfull, a);
+    running_add_raw<T, kUnroll>(run, a, scale);
+  }
+  if (!ALIGNED && v1 > vfull && threadIdx.x < 64) {
+    // the partial vector belongs to this chunk: lane 0 of the first wavefront brings it in
+    uint4 a[1];
+    const uint32_t ninf = sizeof(T) == 4 ? 0xff800000u : (IsBf16<T>::value ? 0xff80ff80u : 0xfc00fc00u);
+    a[0] = threadIdx.x == 0 ? load_tail_raw<T>(row, vfull * N, V) : make_uint4(ninf, ninf, ninf, ninf);
+    running_add_raw<T, 1>(run, a, scale);
   }
   o_out = run.o;
   z_out = running_total(run);

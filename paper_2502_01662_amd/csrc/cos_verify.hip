@@ -163,7 +163,7 @@ void choose_sampling(int B, int ntiles, int* C_out, int* tpc_out) {
 }
 
 // Kernels that hold the rows of all n models in registers are specialised for
-// n = 1..4 on the aligned path; everything else takes the generic instance.
+// n = 1..4; more models take the generic instance.
 template <typename T, bool ALIGNED, int MODE, bool REFINE>
 cos_status_t launch_sampling_variant(const Params& p, size_t lds, hipStream_t st) {
   const long blocks = (long)p.B * p.C;
@@ -171,16 +171,14 @@ cos_status_t launch_sampling_variant(const Params& p, size_t lds, hipStream_t st
   const dim3 grid((unsigned)blocks), block(kThreads);
   if constexpr (MODE == kCd) {
     hipLaunchKernelGGL((sample_kernel<T, ALIGNED, 2, kCd, REFINE>), grid, block, lds, st, p);
-  } else if constexpr (ALIGNED) {
-    switch (p.n) {
-      case 1: hipLaunchKernelGGL((sample_kernel<T, true, 1, MODE, REFINE>), grid, block, lds, st, p); break;
-      case 2: hipLaunchKernelGGL((sample_kernel<T, true, 2, MODE, REFINE>), grid, block, lds, st, p); break;
-      case 3: hipLaunchKernelGGL((sample_kernel<T, true, 3, MODE, REFINE>), grid, block, lds, st, p); break;
-      case 4: hipLaunchKernelGGL((sample_kernel<T, true, 4, MODE, REFINE>), grid, block, lds, st, p); break;
-      default: hipLaunchKernelGGL((sample_kernel<T, true, 0, MODE, REFINE>), grid, block, lds, st, p); break;
-    }
   } else {
-    hipLaunchKernelGGL((sample_kernel<T, false, 0, MODE, REFINE>), grid, block, lds, st, p);
+    switch (p.n) {
+      case 1: hipLaunchKernelGGL((sample_kernel<T, ALIGNED, 1, MODE, REFINE>), grid, block, lds, st, p); break;
+      case 2: hipLaunchKernelGGL((sample_kernel<T, ALIGNED, 2, MODE, REFINE>), grid, block, lds, st, p); break;
+      case 3: hipLaunchKernelGGL((sample_kernel<T, ALIGNED, 3, MODE, REFINE>), grid, block, lds, st, p); break;
+      case 4: hipLaunchKernelGGL((sample_kernel<T, ALIGNED, 4, MODE, REFINE>), grid, block, lds, st, p); break;
+      default: hipLaunchKernelGGL((sample_kernel<T, ALIGNED, 0, MODE, REFINE>), grid, block, lds, st, p); break;
+    }
   }
   return hipGetLastError() == hipSuccess ? COS_OK : COS_ERR_LAUNCH;
 }
@@ -198,16 +196,14 @@ cos_status_t launch_acceptance_rate(const Params& p, hipStream_t st) {
   const dim3 grid((unsigned)blocks), block(kThreads);
   if constexpr (MODE == kCd) {
     hipLaunchKernelGGL((acceptance_rate_kernel<T, ALIGNED, 2, kCd>), grid, block, 0, st, p);
-  } else if constexpr (ALIGNED) {
-    switch (p.n) {
-      case 1: hipLaunchKernelGGL((acceptance_rate_kernel<T, true, 1, MODE>), grid, block, 0, st, p); break;
-      case 2: hipLaunchKernelGGL((acceptance_rate_kernel<T, true, 2, MODE>), grid, block, 0, st, p); break;
-      case 3: hipLaunchKernelGGL((acceptance_rate_kernel<T, true, 3, MODE>), grid, block, 0, st, p); break;
-      case 4: hipLaunchKernelGGL((acceptance_rate_kernel<T, true, 4, MODE>), grid, block, 0, st, p); break;
-      default: hipLaunchKernelGGL((acceptance_rate_kernel<T, true, 0, MODE>), grid, block, 0, st, p); break;
-    }
   } else {
-    hipLaunchKernelGGL((acceptance_rate_kernel<T, false, 0, MODE>), grid, block, 0, st, p);
+    switch (p.n) {
+      case 1: hipLaunchKernelGGL((acceptance_rate_kernel<T, ALIGNED, 1, MODE>), grid, block, 0, st, p); break;
+      case 2: hipLaunchKernelGGL((acceptance_rate_kernel<T, ALIGNED, 2, MODE>), grid, block, 0, st, p); break;
+      case 3: hipLaunchKernelGGL((acceptance_rate_kernel<T, ALIGNED, 3, MODE>), grid, block, 0, st, p); break;
+      case 4: hipLaunchKernelGGL((acceptance_rate_kernel<T, ALIGNED, 4, MODE>), grid, block, 0, st, p); break;
+      default: hipLaunchKernelGGL((acceptance_rate_kernel<T, ALIGNED, 0, MODE>), grid, block, 0, st, p); break;
+    }
   }
   return hipGetLastError() == hipSuccess ? COS_OK : COS_ERR_LAUNCH;
 }
@@ -215,16 +211,12 @@ cos_status_t launch_acceptance_rate(const Params& p, hipStream_t st) {
 template <typename T, bool ALIGNED>
 void launch_mix_stats(const Params& p, dim3 grid, hipStream_t st) {
   const dim3 block(kThreads);
-  if constexpr (ALIGNED) {
-    switch (p.n) {
-      case 1: hipLaunchKernelGGL((mix_stats_kernel<T, true, 1>), grid, block, 0, st, p); break;
-      case 2: hipLaunchKernelGGL((mix_stats_kernel<T, true, 2>), grid, block, 0, st, p); break;
-      case 3: hipLaunchKernelGGL((mix_stats_kernel<T, true, 3>), grid, block, 0, st, p); break;
-      case 4: hipLaunchKernelGGL((mix_stats_kernel<T, true, 4>), grid, block, 0, st, p); break;
-      default: hipLaunchKernelGGL((mix_stats_kernel<T, true, 0>), grid, block, 0, st, p); break;
-    }
-  } else {
-    hipLaunchKernelGGL((mix_stats_kernel<T, false, 0>), grid, block, 0, st, p);
+  switch (p.n) {
+    case 1: hipLaunchKernelGGL((mix_stats_kernel<T, ALIGNED, 1>), grid, block, 0, st, p); break;
+    case 2: hipLaunchKernelGGL((mix_stats_kernel<T, ALIGNED, 2>), grid, block, 0, st, p); break;
+    case 3: hipLaunchKernelGGL((mix_stats_kernel<T, ALIGNED, 3>), grid, block, 0, st, p); break;
+    case 4: hipLaunchKernelGGL((mix_stats_kernel<T, ALIGNED, 4>), grid, block, 0, st, p); break;
+    default: hipLaunchKernelGGL((mix_stats_kernel<T, ALIGNED, 0>), grid, block, 0, st, p); break;
   }
 }
 
