@@ -6,7 +6,8 @@ import subprocess
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_PKG)
-SOURCES = [os.path.join(_PKG, "csrc", "cos_verify.hip")]
+SOURCES = [os.path.join(_PKG, "csrc", f) for f in
+           ("cos_verify.hip", "cos_kernels_bf16.hip", "cos_kernels_f32.hip", "cos_kernels_f16.hip")]
 INCLUDE = os.path.join(_ROOT, "include")
 LIBRARY = os.path.join(_PKG, "libcosverify.so")
 PROBE_SOURCE = os.path.join(_PKG, "csrc", "hbm_probe.hip")
@@ -33,8 +34,25 @@ def library_is_stale() -> bool:
 
 
 def build_library(verbose: bool = False) -> str:
+    """Compile the host side of the ABI and one translation unit of kernels per logit format
+    (in parallel: they are independent), then link the shared library."""
+    from concurrent.futures import ThreadPoolExecutor
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, "-I", INCLUDE, "-o", LIBRARY, *SOURCES]
+    objdir = os.path.join(_PKG, "_build")
+    os.makedirs(objdir, exist_ok=True)
+    compile_flags = [f for f in HIPCC_FLAGS if f != "-shared"]
+
+    def compile_one(src: str) -> str:
+        obj = os.path.join(objdir, os.path.basename(src) + ".o")
+        cmd = [hipcc, *compile_flags, "-c", "-I", INCLUDE, "-o", obj, src]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.run(cmd, check=True)
+        return obj
+
+    with ThreadPoolExecutor(max_workers=len(SOURCES)) as pool:
+        objects = list(pool.map(compile_one, SOURCES))
+    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIBRARY, *objects]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)

@@ -9,7 +9,8 @@
 
 #include "cos_verify.h"
 
-namespace {
+// Constants and structures shared by the host side and the kernels' translation units.
+namespace cosv {
 
 
 constexpr int kThreads = 256;  // 4 wavefronts of 64 lanes
@@ -98,6 +99,30 @@ struct Params {
   double thr64;              // T ln(alpha_cd)
   cos_diag_t diag;
 };
+
+// How one call is launched: filled in by the host side of the ABI, consumed by the
+// per-format translation units (cos_kernels_*.hip), which hold the kernels.
+struct LaunchPlan {
+  int mode;         // kEns, kCd or kMix
+  int window;       // positions per streaming launch
+  int greedy;       // temperature 0 (contrastive mode): one argmax kernel instead
+  int aligned;      // every row starts on a 16-byte boundary and V is a multiple of the vector width
+  int counters;     // arrival counters (ints, with their stride) the fill kernel clears
+  size_t lds;       // dynamic LDS of the sampling kernel (one double per tile)
+  hipStream_t stream;
+  hipEvent_t ev_start, ev_stop;  // optional: recorded around the streaming launches
+};
+
+// Enqueue every kernel of one call for logits stored as float32 / bfloat16 / binary16.
+cos_status_t run_f32(const Params& p, const LaunchPlan& lp);
+cos_status_t run_bf16(const Params& p, const LaunchPlan& lp);
+cos_status_t run_f16(const Params& p, const LaunchPlan& lp);
+
+}  // namespace cosv
+
+using namespace cosv;
+
+namespace {
 
 // Drafts of row b; position drafts_of(p, b) plays the bonus position's role.
 __device__ __forceinline__ int drafts_of(const Params& p, int b) {

@@ -1,0 +1,135 @@
+// cos_launch.h -- launches of one call, per storage format T.  Included by the
+// translation units that instantiate the kernels for one format each
+// (cos_kernels_f32.hip, cos_kernels_bf16.hip, cos_kernels_f16.hip), so that the
+// formats compile in parallel.
+#pragma once
+
+#include "cos_device.h"
+#include "cos_stats.h"
+#include "cos_sample.h"
+
+namespace {
+
+// Kernels that hold the rows of all n models in registers are specialised for
+// n = 1..4; more models take the generic instance.
+template <typename T, bool ALIGNED, int MODE, bool REFINE>
+cos_status_t launch_sampling_variant(const Params& p, size_t lds, hipStream_t st) {
+  const long blocks = (long)p.B * p.C;
+  if (blocks <= 0 || blocks > 0x7fffffffL) return COS_ERR_SHAPE;
+  const dim3 grid((unsigned)blocks), block(kThreads);
+  if constexpr (MODE == kCd) {
+    hipLaunchKernelGGL((sample_kernel<T, ALIGNED, 2, kCd, REFINE>), grid, block, lds, st, p);
+  } else {
+    switch (p.n) {
+      case 1: hipLaunchKernelGGL((sample_kernel<T, ALIGNED, 1, MODE, REFINE>), grid, block, lds, st, p); break;
+      case 2: hipLaunchKernelGGL((sample_kernel<T, ALIGNED, 2, MODE, REFINE>), grid, block, lds, st, p); break;
+      case 3: hipLaunchKernelGGL((sample_kernel<T, ALIGNED, 3, MODE, REFINE>), grid, block, lds, st, p); break;
+      case 4: hipLaunchKernelGGL((sample_kernel<T, ALIGNED, 4, MODE, REFINE>), grid, block, lds, st, p); break;
+      default: hipLaunchKernelGGL((sample_kernel<T, ALIGNED, 0, MODE, REFINE>), grid, block, lds, st, p); break;
+    }
+  }
+  return hipGetLastError() == hipSuccess ? COS_OK : COS_ERR_LAUNCH;
+}
+
+template <typename T, bool ALIGNED, int MODE>
+cos_status_t launch_sampling(const Params& p, size_t lds, hipStream_t st) {
+  return p.refine ? launch_sampling_variant<T, ALIGNED, MODE, true>(p, lds, st)
+                  : launch_sampling_variant<T, ALIGNED, MODE, false>(p, lds, st);
+}
+
+template <typename T, bool ALIGNED, int MODE>
+cos_status_t launch_acceptance_rate(const Params& p, hipStream_t st) {
+  const long blocks = (long)p.B * p.gamma * p.CA;
+  if (blocks <= 0 || blocks > 0x7fffffffL) return COS_ERR_SHAPE;
+  const dim3 grid((unsigned)blocks), block(kThreads);
+  if constexpr (MODE == kCd) {
+    hipLaunchKernelGGL((acceptance_rate_kernel<T, ALIGNED, 2, kCd>), grid, block, 0, st, p);
+  } else {
+    switch (p.n) {
+      case 1: hipLaunchKernelGGL((acceptance_rate_kernel<T, ALIGNED, 1, MODE>), grid, block, 0, st, p); break;
+      case 2: hipLaunchKernelGGL((acceptance_rate_kernel<T, ALIGNED, 2, MODE>), grid, block, 0, st, p); break;
+      case 3: hipLaunchKernelGGL((acceptance_rate_kernel<T, ALIGNED, 3, MODE>), grid, block, 0, st, p); break;
+      case 4: hipLaunchKernelGGL((acceptance_rate_kernel<T, ALIGNED, 4, MODE>), grid, block, 0, st, p); break;
+      default: hipLaunchKernelGGL((acceptance_rate_kernel<T, ALIGNED, 0, MODE>), grid, block, 0, st, p); break;
+    }
+  }
+  return hipGetLastError() == hipSuccess ? COS_OK : COS_ERR_LAUNCH;
+}
+
+template <typename T, bool ALIGNED>
+void launch_mix_stats(const Params& p, dim3 grid, hipStream_t st) {
+  const dim3 block(kThreads);
+  switch (p.n) {
+    case 1: hipLaunchKernelGGL((mix_stats_kernel<T, ALIGNED, 1>), grid, block, 0, st, p); break;
+    case 2: hipLaunchKernelGGL((mix_stats_kernel<T, ALIGNED, 2>), grid, block, 0, st, p); break;
+    case 3: hipLaunchKernelGGL((mix_stats_kernel<T, ALIGNED, 3>), grid, block, 0, st, p); break;
+    case 4: hipLaunchKernelGGL((mix_stats_kernel<T, ALIGNED, 4>), grid, block, 0, st, p); break;
+    default: hipLaunchKernelGGL((mix_stats_kernel<T, ALIGNED, 0>), grid, block, 0, st, p); break;
+  }
+}
+
+// All launches of one call after the fill kernel.  `window` positions are
+// verified per streaming launch; sequences decided by an earlier window are
+// skipped by every later one (their workgroups return at once).
+template <typename T, bool ALIGNED>
+cos_status_t launch_all(Params p, int mode, int window, size_t lds, hipStream_t st,
+                        hipEvent_t ev_start, hipEvent_t ev_stop) {
+  const dim3 block(kThreads);
+  const int g1 = p.gamma + 1;
+  if (ev_start) (void)hipEventRecord(ev_start, st);
+  p.win = 0;
+  for (int j0 = 0; j0 < g1; j0 += window, ++p.win) {
+    p.j0 = j0;
+    p.nj = (j0 + window <= g1) ? window : g1 - j0;
+    const long blocks = (long)p.B * p.nj * (mode == kEns ? p.n : 1) * p.S;
+    if (blocks <= 0 || blocks > 0x7fffffffL) return COS_ERR_SHAPE;
+    const dim3 grid((unsigned)blocks);
+    if (mode == kEns) {
+      hipLaunchKernelGGL((ensemble_stats_kernel<T, ALIGNED>), grid, block, 0, st, p);
+    } else if (mode == kMix) {
+      launch_mix_stats<T, ALIGNED>(p, grid, st);
+    } else {
+      // alpha_cd = 0 is Eq. (5) as printed: no mask, so no pass for the expert maxima
+      if (p.masked) hipLaunchKernelGGL((expert_rowmax_kernel<T, ALIGNED>), grid, block, 0, st, p);
+      hipLaunchKernelGGL((contrastive_stats_kernel<T, ALIGNED>), grid, block, 0, st, p);
+    }
+    if (hipGetLastError() != hipSuccess) return COS_ERR_LAUNCH;
+  }
+  if (ev_stop) (void)hipEventRecord(ev_stop, st);
+  cos_status_t rc = mode == kEns   ? launch_sampling<T, ALIGNED, kEns>(p, lds, st)
+                    : mode == kMix ? launch_sampling<T, ALIGNED, kMix>(p, lds, st)
+                                   : launch_sampling<T, ALIGNED, kCd>(p, lds, st);
+  if (rc != COS_OK || !p.alpha) return rc;
+  return mode == kEns   ? launch_acceptance_rate<T, ALIGNED, kEns>(p, st)
+         : mode == kMix ? launch_acceptance_rate<T, ALIGNED, kMix>(p, st)
+                        : launch_acceptance_rate<T, ALIGNED, kCd>(p, st);
+}
+
+// Temperature 0, contrastive mode: the expert maxima (only with a mask), then one argmax kernel.
+template <typename T, bool ALIGNED>
+cos_status_t launch_greedy(Params p, const LaunchPlan& lp) {
+  p.j0 = 0;
+  p.nj = p.gamma + 1;
+  p.win = 0;
+  const long blocks = (long)p.B * (p.gamma + 1) * p.S;
+  if (blocks <= 0 || blocks > 0x7fffffffL) return COS_ERR_SHAPE;
+  const dim3 grid((unsigned)blocks), block(kThreads);
+  if (lp.ev_start) (void)hipEventRecord(lp.ev_start, lp.stream);
+  if (p.masked) hipLaunchKernelGGL((expert_rowmax_kernel<T, ALIGNED>), grid, block, 0, lp.stream, p);
+  hipLaunchKernelGGL((greedy_contrastive_kernel<T, ALIGNED>), grid, block, 0, lp.stream, p);
+  if (lp.ev_stop) (void)hipEventRecord(lp.ev_stop, lp.stream);
+  return hipGetLastError() == hipSuccess ? COS_OK : COS_ERR_LAUNCH;
+}
+
+// Everything one call enqueues: the fill kernel, then the kernels of the mode.
+template <typename T>
+cos_status_t run_kernels(const Params& p, const LaunchPlan& lp) {
+  hipLaunchKernelGGL(fill_zero_kernel, dim3((lp.counters + kThreads - 1) / kThreads), dim3(kThreads), 0,
+                     lp.stream, p.counters, lp.counters, p.plans, p.B);
+  if (hipGetLastError() != hipSuccess) return COS_ERR_LAUNCH;
+  if (lp.greedy) return lp.aligned ? launch_greedy<T, true>(p, lp) : launch_greedy<T, false>(p, lp);
+  return lp.aligned ? launch_all<T, true>(p, lp.mode, lp.window, lp.lds, lp.stream, lp.ev_start, lp.ev_stop)
+                    : launch_all<T, false>(p, lp.mode, lp.window, lp.lds, lp.stream, lp.ev_start, lp.ev_stop);
+}
+
+}  // namespace

@@ -1,7 +1,9 @@
 // cos_verify.hip -- C ABI and host side of the CoS verification step for gfx950.
-// The kernels live in the headers beside this file: cos_device.h (structures,
+// The kernels live in the headers beside this file -- cos_device.h (structures,
 // wavefront and hand-off primitives, loads), cos_stats.h (streaming kernels and
-// the decision of a sequence), cos_sample.h (sampling and acceptance-rate kernels).
+// the decision of a sequence), cos_sample.h (sampling and acceptance-rate
+// kernels), cos_launch.h (their launches) -- and are instantiated once per logit
+// format in cos_kernels_f32.hip, cos_kernels_bf16.hip and cos_kernels_f16.hip.
 //
 // Structure (one GPU, one HIP stream, no host round trip):
 //
@@ -44,8 +46,6 @@
 #include "cos_verify.h"
 
 #include "cos_device.h"
-#include "cos_stats.h"
-#include "cos_sample.h"
 
 namespace {
 
@@ -160,101 +160,6 @@ void choose_sampling(int B, int ntiles, int* C_out, int* tpc_out) {
   const int tpc = (ntiles + C - 1) / C;
   *C_out = (ntiles + tpc - 1) / tpc;
   *tpc_out = tpc;
-}
-
-// Kernels that hold the rows of all n models in registers are specialised for
-// n = 1..4; more models take the generic instance.
-template <typename T, bool ALIGNED, int MODE, bool REFINE>
-cos_status_t launch_sampling_variant(const Params& p, size_t lds, hipStream_t st) {
-  const long blocks = (long)p.B * p.C;
-  if (blocks <= 0 || blocks > 0x7fffffffL) return COS_ERR_SHAPE;
-  const dim3 grid((unsigned)blocks), block(kThreads);
-  if constexpr (MODE == kCd) {
-    hipLaunchKernelGGL((sample_kernel<T, ALIGNED, 2, kCd, REFINE>), grid, block, lds, st, p);
-  } else {
-    switch (p.n) {
-      case 1: hipLaunchKernelGGL((sample_kernel<T, ALIGNED, 1, MODE, REFINE>), grid, block, lds, st, p); break;
-      case 2: hipLaunchKernelGGL((sample_kernel<T, ALIGNED, 2, MODE, REFINE>), grid, block, lds, st, p); break;
-      case 3: hipLaunchKernelGGL((sample_kernel<T, ALIGNED, 3, MODE, REFINE>), grid, block, lds, st, p); break;
-      case 4: hipLaunchKernelGGL((sample_kernel<T, ALIGNED, 4, MODE, REFINE>), grid, block, lds, st, p); break;
-      default: hipLaunchKernelGGL((sample_kernel<T, ALIGNED, 0, MODE, REFINE>), grid, block, lds, st, p); break;
-    }
-  }
-  return hipGetLastError() == hipSuccess ? COS_OK : COS_ERR_LAUNCH;
-}
-
-template <typename T, bool ALIGNED, int MODE>
-cos_status_t launch_sampling(const Params& p, size_t lds, hipStream_t st) {
-  return p.refine ? launch_sampling_variant<T, ALIGNED, MODE, true>(p, lds, st)
-                  : launch_sampling_variant<T, ALIGNED, MODE, false>(p, lds, st);
-}
-
-template <typename T, bool ALIGNED, int MODE>
-cos_status_t launch_acceptance_rate(const Params& p, hipStream_t st) {
-  const long blocks = (long)p.B * p.gamma * p.CA;
-  if (blocks <= 0 || blocks > 0x7fffffffL) return COS_ERR_SHAPE;
-  const dim3 grid((unsigned)blocks), block(kThreads);
-  if constexpr (MODE == kCd) {
-    hipLaunchKernelGGL((acceptance_rate_kernel<T, ALIGNED, 2, kCd>), grid, block, 0, st, p);
-  } else {
-    switch (p.n) {
-      case 1: hipLaunchKernelGGL((acceptance_rate_kernel<T, ALIGNED, 1, MODE>), grid, block, 0, st, p); break;
-      case 2: hipLaunchKernelGGL((acceptance_rate_kernel<T, ALIGNED, 2, MODE>), grid, block, 0, st, p); break;
-      case 3: hipLaunchKernelGGL((acceptance_rate_kernel<T, ALIGNED, 3, MODE>), grid, block, 0, st, p); break;
-      case 4: hipLaunchKernelGGL((acceptance_rate_kernel<T, ALIGNED, 4, MODE>), grid, block, 0, st, p); break;
-      default: hipLaunchKernelGGL((acceptance_rate_kernel<T, ALIGNED, 0, MODE>), grid, block, 0, st, p); break;
-    }
-  }
-  return hipGetLastError() == hipSuccess ? COS_OK : COS_ERR_LAUNCH;
-}
-
-template <typename T, bool ALIGNED>
-void launch_mix_stats(const Params& p, dim3 grid, hipStream_t st) {
-  const dim3 block(kThreads);
-  switch (p.n) {
-    case 1: hipLaunchKernelGGL((mix_stats_kernel<T, ALIGNED, 1>), grid, block, 0, st, p); break;
-    case 2: hipLaunchKernelGGL((mix_stats_kernel<T, ALIGNED, 2>), grid, block, 0, st, p); break;
-    case 3: hipLaunchKernelGGL((mix_stats_kernel<T, ALIGNED, 3>), grid, block, 0, st, p); break;
-    case 4: hipLaunchKernelGGL((mix_stats_kernel<T, ALIGNED, 4>), grid, block, 0, st, p); break;
-    default: hipLaunchKernelGGL((mix_stats_kernel<T, ALIGNED, 0>), grid, block, 0, st, p); break;
-  }
-}
-
-// All launches of one call after the fill kernel.  `window` positions are
-// verified per streaming launch; sequences decided by an earlier window are
-// skipped by every later one (their workgroups return at once).
-template <typename T, bool ALIGNED>
-cos_status_t launch_all(Params p, int mode, int window, size_t lds, hipStream_t st,
-                        hipEvent_t ev_start, hipEvent_t ev_stop) {
-  const dim3 block(kThreads);
-  const int g1 = p.gamma + 1;
-  if (ev_start) (void)hipEventRecord(ev_start, st);
-  p.win = 0;
-  for (int j0 = 0; j0 < g1; j0 += window, ++p.win) {
-    p.j0 = j0;
-    p.nj = (j0 + window <= g1) ? window : g1 - j0;
-    const long blocks = (long)p.B * p.nj * (mode == kEns ? p.n : 1) * p.S;
-    if (blocks <= 0 || blocks > 0x7fffffffL) return COS_ERR_SHAPE;
-    const dim3 grid((unsigned)blocks);
-    if (mode == kEns) {
-      hipLaunchKernelGGL((ensemble_stats_kernel<T, ALIGNED>), grid, block, 0, st, p);
-    } else if (mode == kMix) {
-      launch_mix_stats<T, ALIGNED>(p, grid, st);
-    } else {
-      // alpha_cd = 0 is Eq. (5) as printed: no mask, so no pass for the expert maxima
-      if (p.masked) hipLaunchKernelGGL((expert_rowmax_kernel<T, ALIGNED>), grid, block, 0, st, p);
-      hipLaunchKernelGGL((contrastive_stats_kernel<T, ALIGNED>), grid, block, 0, st, p);
-    }
-    if (hipGetLastError() != hipSuccess) return COS_ERR_LAUNCH;
-  }
-  if (ev_stop) (void)hipEventRecord(ev_stop, st);
-  cos_status_t rc = mode == kEns   ? launch_sampling<T, ALIGNED, kEns>(p, lds, st)
-                    : mode == kMix ? launch_sampling<T, ALIGNED, kMix>(p, lds, st)
-                                   : launch_sampling<T, ALIGNED, kCd>(p, lds, st);
-  if (rc != COS_OK || !p.alpha) return rc;
-  return mode == kEns   ? launch_acceptance_rate<T, ALIGNED, kEns>(p, st)
-         : mode == kMix ? launch_acceptance_rate<T, ALIGNED, kMix>(p, st)
-                        : launch_acceptance_rate<T, ALIGNED, kCd>(p, st);
 }
 
 }  // namespace
@@ -434,61 +339,19 @@ cos_status_t cos_verify_ex(const void* logits, cos_dtype_t dt, int n, int B, int
   hipEvent_t ev_stop = profile ? g_ev_stop[slot] : nullptr;
 
   // counters in use: one set per window, the sampling set, and the acceptance-rate set if wanted
-  const int nctr = ((p.alpha ? 2 * gamma + 2 : gamma + 2) * B) * kCtrStride;
-  hipLaunchKernelGGL(fill_zero_kernel, dim3((nctr + kThreads - 1) / kThreads), dim3(kThreads), 0, st,
-                     p.counters, nctr, p.plans, B);
-  if (hipGetLastError() != hipSuccess) return COS_ERR_LAUNCH;
-
-  if (options && options->greedy) {
-    p.j0 = 0;
-    p.nj = gamma + 1;
-    p.win = 0;
-    const long blocks = (long)B * (gamma + 1) * S;
-    if (blocks > 0x7fffffffL) return COS_ERR_SHAPE;
-    const dim3 grid((unsigned)blocks), block(kThreads);
-    if (profile) (void)hipEventRecord(ev_start, st);
-    if (dt == COS_DTYPE_F32) {
-      if (aligned) {
-        if (p.masked) hipLaunchKernelGGL((expert_rowmax_kernel<float, true>), grid, block, 0, st, p);
-        hipLaunchKernelGGL((greedy_contrastive_kernel<float, true>), grid, block, 0, st, p);
-      } else {
-        if (p.masked) hipLaunchKernelGGL((expert_rowmax_kernel<float, false>), grid, block, 0, st, p);
-        hipLaunchKernelGGL((greedy_contrastive_kernel<float, false>), grid, block, 0, st, p);
-      }
-    } else if (dt == COS_DTYPE_F16) {
-      if (aligned) {
-        if (p.masked) hipLaunchKernelGGL((expert_rowmax_kernel<_Float16, true>), grid, block, 0, st, p);
-        hipLaunchKernelGGL((greedy_contrastive_kernel<_Float16, true>), grid, block, 0, st, p);
-      } else {
-        if (p.masked) hipLaunchKernelGGL((expert_rowmax_kernel<_Float16, false>), grid, block, 0, st, p);
-        hipLaunchKernelGGL((greedy_contrastive_kernel<_Float16, false>), grid, block, 0, st, p);
-      }
-} else {
-      if (aligned) {
-        if (p.masked) hipLaunchKernelGGL((expert_rowmax_kernel<uint16_t, true>), grid, block, 0, st, p);
-        hipLaunchKernelGGL((greedy_contrastive_kernel<uint16_t, true>), grid, block, 0, st, p);
-      } else {
-        if (p.masked) hipLaunchKernelGGL((expert_rowmax_kernel<uint16_t, false>), grid, block, 0, st, p);
-        hipLaunchKernelGGL((greedy_contrastive_kernel<uint16_t, false>), grid, block, 0, st, p);
-      }
-    }
-    if (profile) {
-      (void)hipEventRecord(ev_stop, st);
-      ++g_ev_recorded;
-    }
-    return hipGetLastError() == hipSuccess ? COS_OK : COS_ERR_LAUNCH;
-  }
-
-  cos_status_t rc;
-  if (dt == COS_DTYPE_F32)
-    rc = aligned ? launch_all<float, true>(p, mode, window, lds, st, ev_start, ev_stop)
-                 : launch_all<float, false>(p, mode, window, lds, st, ev_start, ev_stop);
-  else if (dt == COS_DTYPE_F16)
-    rc = aligned ? launch_all<_Float16, true>(p, mode, window, lds, st, ev_start, ev_stop)
-                 : launch_all<_Float16, false>(p, mode, window, lds, st, ev_start, ev_stop);
-  else
-    rc = aligned ? launch_all<uint16_t, true>(p, mode, window, lds, st, ev_start, ev_stop)
-                 : launch_all<uint16_t, false>(p, mode, window, lds, st, ev_start, ev_stop);
+  LaunchPlan lp;
+  lp.mode = mode;
+  lp.window = window;
+  lp.greedy = (options && options->greedy) ? 1 : 0;
+  lp.aligned = aligned ? 1 : 0;
+  lp.counters = ((p.alpha ? 2 * gamma + 2 : gamma + 2) * B) * kCtrStride;
+  lp.lds = lds;
+  lp.stream = st;
+  lp.ev_start = ev_start;
+  lp.ev_stop = ev_stop;
+  const cos_status_t rc = dt == COS_DTYPE_F32   ? run_f32(p, lp)
+                          : dt == COS_DTYPE_F16 ? run_f16(p, lp)
+                                                : run_bf16(p, lp);
   if (profile) ++g_ev_recorded;
   return rc;
 }
