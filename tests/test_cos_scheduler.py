@@ -34,6 +34,8 @@ def _exact_joint_law(lm, ctx0, mode, weights, depth):
         l = [lm.logits(m, c)[0].to(torch.float64).numpy() for m in range(lm.n_models)]
         if mode == O.ENSEMBLE:
             return O.combine_ensemble(np.stack([O.softmax(x) for x in l]), np.asarray(weights, dtype=np.float64))
+        if mode == O.LOGIT_MIX:
+            return O.combine_logit_mix(np.stack(l), np.asarray(weights, dtype=np.float64))
         return O.combine_contrastive(l[0], l[1], weights[0], weights[1])[0]
 
     def rec(ctx, prob, toks):
@@ -50,6 +52,7 @@ def _exact_joint_law(lm, ctx0, mode, weights, depth):
 
 
 @pytest.mark.parametrize("n,gammas,mode,weights", [(3, (2, 1, 1), O.ENSEMBLE, [0.5, 0.3, 0.2]),
+                                                  (3, (1, 2, 1), O.LOGIT_MIX, [0.6, 0.5, -0.1]),
                                                   (3, (1, 1, 1), O.ENSEMBLE, [0.2, 0.2, 0.6]),
                                                   (2, (2, 2), O.CONTRASTIVE, [0.5, 0.05]),
                                                   (4, (1, 2, 1, 1), O.ENSEMBLE, [0.25, 0.25, 0.25, 0.25])])
@@ -137,7 +140,8 @@ def test_argument_checks():
 @pytest.mark.gpu
 @pytest.mark.parametrize("n,gammas,mode,weights", [(3, (3, 2, 1), O.ENSEMBLE, [0.5, 0.3, 0.2]),
                                                   (2, (2, 3), O.CONTRASTIVE, [0.5, 0.1]),
-                                                  (4, (1, 1, 2, 1), O.ENSEMBLE, [0.4, 0.3, 0.2, 0.1])])
+                                                  (4, (1, 1, 2, 1), O.ENSEMBLE, [0.4, 0.3, 0.2, 0.1]),
+                                                  (3, (2, 1, 2), O.LOGIT_MIX, [0.5, 0.4, 0.1])])
 def test_gpu_driver_matches_oracle_driver_token_for_token(n, gammas, mode, weights):
     from paper_2502_01662_amd import cos_verify as C
     V, B = 4096, 40

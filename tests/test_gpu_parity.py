@@ -420,6 +420,21 @@ def test_many_sequences_of_a_tiny_vocabulary():
     _check("B=3000 V=8 contrastive", inp, C.COS_COMBINE_CONTRASTIVE, [0.5, 0.1])
 
 
+def test_large_batch_all_modes():
+    """Eight thousand sequences: the counters, plans and partials of a large batch."""
+    n, B, gamma, V = 2, 8192, 3, 1024
+    inp = _random_inputs(n, B, gamma, V, "bf16", seed=102, std=1.5)
+    c = inp["logits"][0, :, :gamma].float()
+    inp["draft_tokens"][::2] = c.argmax(-1).to(torch.int32)[::2]
+    for mode, w in ((C.COS_COMBINE_ENSEMBLE, [0.5, 0.5]), (C.COS_COMBINE_CONTRASTIVE, [0.5, 0.1]),
+                    (C.COS_COMBINE_LOGIT_MIX, [1.2, -0.2])):
+        alen, toks, diag, rep = _check(f"B=8192 mode={mode}", inp, mode, w)
+        assert len(set(alen.tolist())) == gamma + 1
+        assert rep.excused_accept_ties + rep.excused_cdf_ties <= 8
+    inp["stop_window"] = 2
+    _check("B=8192 ensemble, windows of 2", inp, C.COS_COMBINE_ENSEMBLE, [0.5, 0.5])
+
+
 def test_draft_the_proposer_thinks_impossible_is_accepted_when_r_allows_it():
     """q(d) = 0 < r(d): the ratio is +inf, accepted whatever u is; r(d) = q(d) = 0: rejected."""
     n, B, gamma, V = 2, 8, 2, 4096
