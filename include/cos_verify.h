@@ -10,7 +10,8 @@
  *   r     = sum_m w_m s_m                        Eq. (4), n-model coefficients as
  *                                                in Sec. 4.1 / Alg. 2, or
  *   r     = Softmax(l_0 - mu l_1) on the mask    Eq. (5) plus a plausibility mask
- *           {x : s_0(x) >= alpha_cd max s_0}     (alpha_cd = 0: Eq. (5) exactly)
+ *           {x : s_0(x) >= alpha_cd max s_0}     (alpha_cd = 0: Eq. (5) exactly), or
+ *   r     = Softmax(sum_m beta_m l_m)            Eq. (3) at the logit level, linear
  *   q     = s_{proposer_idx[b]}                  the row's current proposer
  *   accept draft d_j  iff  u_j < min(1, r(d_j)/q(d_j))        Eq. (2) / Eq. (6)
  *   first rejected position j*: token ~ norm(max(0, r - q))   Sec. 3.1-3.2, App. A.1
@@ -98,7 +99,7 @@ size_t cos_verify_workspace_bytes(int n, int B, int gamma, int V, cos_dtype_t dt
  *               but never an out-of-bounds access or a hang.
  * draft_tokens  DEVICE, [B][gamma] int32, each in [0, V) (caller's contract).
  * proposer_idx  DEVICE, [B] int32, each in [0, n): whose softmax is q.
- * combine_mode  ensemble or contrastive.
+ * combine_mode  ensemble, contrastive or logit mix (see cos_combine_t).
  * weights       HOST.  ensemble: w[0..n-1].  contrastive (n must be 2; model 0
  *               is the expert l^p, model 1 the amateur l^q): weights[0] = mu,
  *               weights[1] = alpha_cd in [0,1].  logit mix: beta[0..n-1], any

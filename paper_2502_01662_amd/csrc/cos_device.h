@@ -67,7 +67,7 @@ struct Params {
   int* accepted_len;
   int* out_tokens;
   // workspace
-  int* counters;      // (stride kCtrStride) [gamma+1 windows][B] streaming arrivals, [B] sampling
+  int* counters;      // (stride kCtrStride) [nwin windows][B] streaming arrivals, [B] sampling
                       // arrivals, [B][gamma] acceptance-rate arrivals
   Partial* partials;  // [B][gamma+1][nstat][S]
   float* rowmax;      // contrastive: [B][gamma+1][S] partial maxima of the expert row
@@ -90,6 +90,7 @@ struct Params {
   int j0;             // first position of this launch's window
   int nj;             // positions in this launch's window (gamma+1: the whole step in one launch)
   int win;            // window index (selects the arrival counters)
+  int nwin;           // streaming launches of the call = sets of streaming arrival counters
   double w[COS_MAX_MODELS];  // ensemble weights; contrastive: w[0] = mu, w[1] = alpha_cd
   float scale;               // log2(e) / temperature: logits times this are base-2 exponents
   float mu_hi, mu_lo;        // mu split into two floats

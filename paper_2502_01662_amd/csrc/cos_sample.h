@@ -482,7 +482,7 @@ __global__ void __launch_bounds__(kThreads) sample_kernel(Params p) {
   // publish this workgroup's tile sums with coalesced write-through stores
   for (int i = threadIdx.x; i < te - tb; i += kThreads) store_agent(sums + tb + i, tile_sum[i]);
   wait_stores();
-  if (!arrive_last(p.counters + ((size_t)(p.gamma + 1) * p.B + b) * kCtrStride, p.C, &s_flag)) return;
+  if (!arrive_last(p.counters + ((size_t)p.nwin * p.B + b) * kCtrStride, p.C, &s_flag)) return;
 
   // last workgroup of this sequence: all tile sums are published
   for (int t = threadIdx.x; t < p.ntiles; t += kThreads) tile_sum[t] = load_agent(sums + t);
@@ -643,7 +643,7 @@ __global__ void __launch_bounds__(kThreads) acceptance_rate_kernel(Params p) {
     store_agent(parts + c, tot);
     wait_stores();
   }
-  int* counter = p.counters + ((size_t)(p.gamma + 2) * p.B + (size_t)b * p.gamma + j) * kCtrStride;
+  int* counter = p.counters + ((size_t)(p.nwin + 1) * p.B + (size_t)b * p.gamma + j) * kCtrStride;
   if (!arrive_last(counter, p.CA, &s_flag)) return;
   if (threadIdx.x == 0) {
     double tot = 0.0;

@@ -318,9 +318,9 @@ __device__ void decide_sequence(const Params& p, int b, DecideShared& sh) {
           }
         }
       }
-      for (int d = G >> 1; d >= 1; d >>= 1) {
-        const int oo = __shfl_xor(omax, d, 64);
-        const double zz = __shfl_xor(zsum, d, 64);
+      for (int span = G >> 1; span >= 1; span >>= 1) {
+        const int oo = __shfl_xor(omax, span, 64);
+        const double zz = __shfl_xor(zsum, span, 64);
         const int om = max(omax, oo);
         zsum = (zsum > 0.0 ? ldexp(zsum, omax - om) : 0.0) + (zz > 0.0 ? ldexp(zz, oo - om) : 0.0);
         omax = om;
@@ -448,7 +448,7 @@ __global__ void __launch_bounds__(kThreads) ensemble_stats_kernel(Params p) {
   const int g1 = p.gamma + 1;
   const int per_b = p.nj * p.n * p.S;
   const int b = blockIdx.x / per_b;
-  if (p.plans[b].jstar >= 0) return;  // decided by an earlier window: nothing more is read
+  if (p.win > 0 && p.plans[b].jstar >= 0) return;  // decided by an earlier window: nothing more is read
   int rem = blockIdx.x - b * per_b;
   const int jj = rem / (p.n * p.S);
   rem -= jj * p.n * p.S;
@@ -494,7 +494,7 @@ __global__ void __launch_bounds__(kThreads) expert_rowmax_kernel(Params p) {
   const int ws = blockIdx.x / p.S;  // b * nj + jj
   const int s = blockIdx.x - ws * p.S;
   const int b = ws / p.nj, j = p.j0 + (ws - b * p.nj);
-  if (p.plans[b].jstar >= 0) return;  // decided by an earlier window
+  if (p.win > 0 && p.plans[b].jstar >= 0) return;  // decided by an earlier window
   const int rs = b * g1 + j;
   if (position_unread(p, drafts_of(p, b), j)) {
     if (threadIdx.x == 0) p.rowmax[(size_t)rs * p.S + s] = -INFINITY;
@@ -541,7 +541,7 @@ __global__ void __launch_bounds__(kThreads) contrastive_stats_kernel(Params p) {
   const int g1 = p.gamma + 1;
   const int per_b = p.nj * p.S;
   const int b = blockIdx.x / per_b;
-  if (p.plans[b].jstar >= 0) return;  // decided by an earlier window: nothing more is read
+  if (p.win > 0 && p.plans[b].jstar >= 0) return;  // decided by an earlier window: nothing more is read
   int rem = blockIdx.x - b * per_b;
   const int j = p.j0 + rem / p.S;
   const int s = rem - (j - p.j0) * p.S;
@@ -656,7 +656,7 @@ __global__ void __launch_bounds__(kThreads) mix_stats_kernel(Params p) {
   const int g1 = p.gamma + 1;
   const int per_b = p.nj * p.S;
   const int b = blockIdx.x / per_b;
-  if (p.plans[b].jstar >= 0) return;  // decided by an earlier window: nothing more is read
+  if (p.win > 0 && p.plans[b].jstar >= 0) return;  // decided by an earlier window: nothing more is read
   int rem = blockIdx.x - b * per_b;
   const int j = p.j0 + rem / p.S;
   const int s = rem - (j - p.j0) * p.S;

@@ -21,7 +21,9 @@
 //                     scans the tile sums and locates the token by inverse CDF.
 //
 // Contrastive mode (Eq. (5) with a plausibility mask) needs the expert row's
-// maximum before anything can be masked, so a row-max kernel runs first.
+// maximum before anything can be masked, so a row-max kernel runs first.  The
+// logit-level modes (contrastive, logit mix) stream the rows of all models of a
+// position together, since their statistic is of a combination of the rows.
 //
 // Extensions (cos_verify_ex): temperature, the verifier's own bonus token
 // (Sec. 3.3), per-position proposers (Alg. 2), the acceptance rates of Eq. (7)
@@ -295,6 +297,7 @@ cos_status_t cos_verify_ex(const void* logits, cos_dtype_t dt, int n, int B, int
     p.tpa = (pl.ntiles + ca - 1) / ca;
     p.CA = (pl.ntiles + p.tpa - 1) / p.tpa;  // <= ca
   }
+  p.nwin = (gamma + 1 + window - 1) / window;
   p.S = S;
   p.cv = cv;
   p.nvec = pl.nvec;
@@ -338,13 +341,13 @@ cos_status_t cos_verify_ex(const void* logits, cos_dtype_t dt, int n, int B, int
   hipEvent_t ev_start = profile ? g_ev_start[slot] : nullptr;
   hipEvent_t ev_stop = profile ? g_ev_stop[slot] : nullptr;
 
-  // counters in use: one set per window, the sampling set, and the acceptance-rate set if wanted
+  // counters in use: one set per streaming launch, the sampling set, and the acceptance-rate sets if wanted
   LaunchPlan lp;
   lp.mode = mode;
   lp.window = window;
   lp.greedy = (options && options->greedy) ? 1 : 0;
   lp.aligned = aligned ? 1 : 0;
-  lp.counters = ((p.alpha ? 2 * gamma + 2 : gamma + 2) * B) * kCtrStride;
+  lp.counters = ((p.nwin + 1 + (p.alpha ? gamma : 0)) * B) * kCtrStride;
   lp.lds = lds;
   lp.stream = st;
   lp.ev_start = ev_start;
