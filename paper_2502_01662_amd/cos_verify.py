@@ -173,7 +173,7 @@ def cos_verify(logits: torch.Tensor, draft_tokens: torch.Tensor, proposer_idx: t
                num_drafts: Optional[torch.Tensor] = None, no_bonus: bool = False, refine_residual: bool = False):
     """Enqueue one verification step on the current stream; returns (accepted_len, out_tokens).
 
-    logits [n][B][gamma+1][V] (float32 or bfloat16), draft_tokens [B][gamma] int32,
+    logits [n][B][gamma+1][V] (float32, bfloat16 or float16), draft_tokens [B][gamma] int32,
     proposer_idx [B] int32, u_accept [B][gamma] float64, u_resample [B] float64:
     all contiguous tensors on one GPU.  ``weights`` is a host sequence.
     Extensions (``cos_verify_ex``): ``temperature``, ``bonus_idx`` [B] int32,
@@ -202,9 +202,25 @@ def cos_verify(logits: torch.Tensor, draft_tokens: torch.Tensor, proposer_idx: t
         accepted_len = torch.empty(B, dtype=torch.int32, device=dev)
     if out_tokens is None:
         out_tokens = torch.empty((B, g1), dtype=torch.int32, device=dev)
+    for name, t, shape in (("accepted_len", accepted_len, (B,)), ("out_tokens", out_tokens, (B, g1))):
+        if t.dtype != torch.int32 or tuple(t.shape) != shape or not t.is_contiguous() or t.device != dev:
+            raise TypeError(f"{name}: want contiguous int32 {shape} on {dev}")
     if workspace is None:
         workspace = allocate_workspace(n, B, gamma, V, dt, combine_mode, dev)
+    elif workspace.dtype != torch.uint8 or not workspace.is_contiguous() or workspace.device != dev:
+        raise TypeError(f"workspace: want a contiguous uint8 tensor on {dev}")
+    # the library reads n weights (two in contrastive mode) from this host array
+    wanted = 2 if combine_mode == COS_COMBINE_CONTRASTIVE else n
+    if len(weights) != wanted:
+        raise CosVerifyError(-5, f"{wanted} weights wanted for this mode, got {len(weights)}")
     w = (ctypes.c_double * max(len(weights), 1))(*[float(x) for x in weights])
+    if diag is not None:
+        for name, shape, dtype in (("r_at_draft", (B, gamma), torch.float64), ("q_at_draft", (B, gamma), torch.float64),
+                                   ("sample_mass", (B,), torch.float64), ("cdf_lo", (B,), torch.float64),
+                                   ("cdf_hi", (B,), torch.float64), ("flags", (B,), torch.int32)):
+            t = getattr(diag, name)
+            if t.dtype != dtype or tuple(t.shape) != shape or not t.is_contiguous() or t.device != dev:
+                raise TypeError(f"diag.{name}: want contiguous {dtype} {shape} on {dev}")
     dstruct = diag.as_struct() if diag is not None else None
     opt = None
     if alpha is not None and (alpha.dtype != torch.float64 or tuple(alpha.shape) != (B, gamma)

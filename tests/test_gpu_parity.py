@@ -231,6 +231,31 @@ def test_empty_batch_is_a_noop():
     assert alen.numel() == 0 and toks.numel() == 0
 
 
+def test_binding_checks_what_the_library_cannot():
+    # the C side reads n weights from a host array and writes through the output pointers it is given:
+    # lengths, shapes, dtypes and devices are the binding's to check
+    inp = _random_inputs(2, 3, 2, 64, "bf16", seed=2)
+    args = (inp["logits"], inp["draft_tokens"], inp["proposer_idx"])
+    us = (inp["u_accept"], inp["u_resample"])
+    with pytest.raises(C.CosVerifyError):
+        C.cos_verify(*args, C.COS_COMBINE_ENSEMBLE, [1.0], *us)                   # one weight for two models
+    with pytest.raises(C.CosVerifyError):
+        C.cos_verify(*args, C.COS_COMBINE_CONTRASTIVE, [0.5, 0.1, 0.0], *us)      # contrastive takes (mu, alpha_cd)
+    with pytest.raises(TypeError):
+        C.cos_verify(*args, 0, [0.5, 0.5], *us, accepted_len=torch.empty(2, dtype=torch.int32, device="cuda"))
+    with pytest.raises(TypeError):
+        C.cos_verify(*args, 0, [0.5, 0.5], *us, out_tokens=torch.empty((3, 3), dtype=torch.int64, device="cuda"))
+    with pytest.raises(TypeError):
+        C.cos_verify(*args, 0, [0.5, 0.5], *us, workspace=torch.empty(1 << 20, dtype=torch.float32, device="cuda"))
+    with pytest.raises(TypeError):
+        C.cos_verify(*args, 0, [0.5, 0.5], *us, diag=C.Diagnostics.allocate(2, 2, "cuda"))   # for another batch
+    with pytest.raises(TypeError):
+        C.cos_verify(inp["logits"].transpose(0, 1), inp["draft_tokens"], inp["proposer_idx"], 0, [0.5, 0.5], *us)
+    alen, toks = C.cos_verify(*args, 0, [0.5, 0.5], *us)     # and the well-formed call still goes through
+    torch.cuda.synchronize()
+    assert alen.shape == (3,) and toks.shape == (3, 3)
+
+
 def test_r_equals_q_accepts_every_draft():
     inp = _random_inputs(1, 16, 4, 5000, "bf16", seed=21)
     inp["logits"] = inp["logits"].repeat(3, 1, 1, 1).contiguous()          # three identical models
