@@ -240,6 +240,25 @@ int cos_oracle_argmax_contrastive(const double *l_p, const double *l_q, double m
   return arg;
 }
 
+/* Temperature 0 of the logit-level linear combination (Eq. (3)): the softmax of
+ * c(x) = sum_m beta_m l_m(x) becomes one-hot at the largest c(x), ties to the
+ * lowest index.  c is summed exactly as cos_oracle_combine_logit_mix sums it
+ * (model order, models with beta_m = 0 left out).  l is [n][V].              */
+int cos_oracle_argmax_logit_mix(const double *l, const double *beta, int n, int V) {
+  double best = -INFINITY;
+  int x, m, arg = -1;
+  for (x = 0; x < V; ++x) {
+    double c = 0.0;
+    for (m = 0; m < n; ++m)
+      if (beta[m] != 0.0) c += beta[m] * l[(size_t)m * V + x];
+    if (arg < 0 || c > best) {
+      best = c;
+      arg = x;
+    }
+  }
+  return arg;
+}
+
 /* argmax of one row, ties to the lowest index */
 int cos_oracle_argmax(const double *l, int V) {
   int x, arg = 0;
@@ -553,29 +572,33 @@ int cos_oracle_verify_ex(const void *logits, int dtype, int n, int B, int gamma,
   return failed ? ORACLE_ERR_NOMEM : ORACLE_OK;
 }
 
-/* ---- the step at temperature 0, contrastive mode ---------------------------
- * r is one-hot at a_j = cos_oracle_argmax_contrastive of position j, so Eq. (6)
- * accepts d_j iff d_j == a_j whatever q is (r(d) = 0 otherwise), the residual
- * norm(max(0, r - q)) and its fall-back r are both one-hot at a_j, and the bonus
- * token is a_gamma -- or, with bonus_idx[b] = v >= 0, the argmax of l_v alone
- * (Sec. 3.3).  No random numbers are consumed.  weights = (mu, alpha_cd).
- * num_drafts / no_bonus as in cos_oracle_options.                            */
-int cos_oracle_verify_greedy(const void *logits, int dtype, int B, int gamma, int V,
-                             const int32_t *draft_tokens, const double *weights,
-                             const int32_t *bonus_idx, const int32_t *num_drafts,
-                             int no_bonus, int32_t *accepted_len,
-                             int32_t *out_tokens, int num_threads) {
+/* ---- the step at temperature 0, logit-level modes --------------------------
+ * r is one-hot at a_j -- cos_oracle_argmax_contrastive (mode contrastive, n = 2,
+ * weights = (mu, alpha_cd)) or cos_oracle_argmax_logit_mix (mode logit mix,
+ * weights = beta[0..n-1]) of position j -- so Eq. (6) accepts d_j iff d_j == a_j
+ * whatever q is (r(d) = 0 otherwise), the residual norm(max(0, r - q)) and its
+ * fall-back r are both one-hot at a_j, and the bonus token is a_gamma -- or, with
+ * bonus_idx[b] = v >= 0, the argmax of l_v alone (Sec. 3.3).  No random numbers
+ * are consumed.  num_drafts / no_bonus as in cos_oracle_options.              */
+int cos_oracle_verify_greedy_mode(const void *logits, int dtype, int n, int B, int gamma, int V,
+                                  const int32_t *draft_tokens, int mode, const double *weights,
+                                  const int32_t *bonus_idx, const int32_t *num_drafts,
+                                  int no_bonus, int32_t *accepted_len,
+                                  int32_t *out_tokens, int num_threads) {
   int b, failed = 0;
-  const int n = 2;
   size_t esize;
   if (!logits || !draft_tokens || !weights || !accepted_len || !out_tokens) return ORACLE_ERR_NULL;
-  if (B < 0 || gamma < 1 || V < 1) return ORACLE_ERR_SHAPE;
+  if (n < 1 || B < 0 || gamma < 1 || V < 1) return ORACLE_ERR_SHAPE;
   if (dtype != ORACLE_DTYPE_F32 && dtype != ORACLE_DTYPE_BF16 && dtype != ORACLE_DTYPE_F16)
     return ORACLE_ERR_DTYPE;
-  if (check_weights(ORACLE_CONTRASTIVE, n, weights) != ORACLE_OK) return ORACLE_ERR_WEIGHTS;
+  if (mode != ORACLE_CONTRASTIVE && mode != ORACLE_LOGIT_MIX) return ORACLE_ERR_MODE;
+  if (mode == ORACLE_CONTRASTIVE && n != 2) return ORACLE_ERR_MODE;
+  if (check_weights(mode, n, weights) != ORACLE_OK) return ORACLE_ERR_WEIGHTS;
   esize = dtype == ORACLE_DTYPE_F32 ? 4 : 2;
-  for (b = 0; b < B; ++b)
+  for (b = 0; b < B; ++b) {
     if (num_drafts && (num_drafts[b] < 0 || num_drafts[b] > gamma)) return ORACLE_ERR_SHAPE;
+    if (bonus_idx && bonus_idx[b] >= n) return ORACLE_ERR_SHAPE;
+  }
 #ifdef _OPENMP
   if (num_threads > 0) omp_set_num_threads(num_threads);
 #endif
@@ -601,8 +624,12 @@ int cos_oracle_verify_greedy(const void *logits, int dtype, int B, int gamma, in
           cos_oracle_row_to_f64((const char *)logits + row * (size_t)V * esize, dtype, V,
                                 l + (size_t)m * V);
         }
-        a = v >= 0 ? cos_oracle_argmax(l + (size_t)v * V, V)
-                   : cos_oracle_argmax_contrastive(l, l + V, weights[0], weights[1], V);
+        if (v >= 0)
+          a = cos_oracle_argmax(l + (size_t)v * V, V);
+        else if (mode == ORACLE_CONTRASTIVE)
+          a = cos_oracle_argmax_contrastive(l, l + V, weights[0], weights[1], V);
+        else
+          a = cos_oracle_argmax_logit_mix(l, weights, n, V);
         if (j < gb && draft_tokens[(size_t)b * gamma + j] == a) continue; /* accepted */
         jstar = j;
         token = a;
@@ -617,6 +644,17 @@ int cos_oracle_verify_greedy(const void *logits, int dtype, int B, int gamma, in
     free(l);
   }
   return failed ? ORACLE_ERR_NOMEM : ORACLE_OK;
+}
+
+/* The contrastive mode of the above (n = 2, weights = (mu, alpha_cd)). */
+int cos_oracle_verify_greedy(const void *logits, int dtype, int B, int gamma, int V,
+                             const int32_t *draft_tokens, const double *weights,
+                             const int32_t *bonus_idx, const int32_t *num_drafts,
+                             int no_bonus, int32_t *accepted_len,
+                             int32_t *out_tokens, int num_threads) {
+  return cos_oracle_verify_greedy_mode(logits, dtype, 2, B, gamma, V, draft_tokens,
+                                       ORACLE_CONTRASTIVE, weights, bonus_idx, num_drafts,
+                                       no_bonus, accepted_len, out_tokens, num_threads);
 }
 
 /* The base step: no extensions. */

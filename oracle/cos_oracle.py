@@ -85,8 +85,10 @@ def _load():
         lib.cos_oracle_argmax_contrastive.restype = ci
         lib.cos_oracle_argmax.argtypes = [dp, ci]
         lib.cos_oracle_argmax.restype = ci
-        lib.cos_oracle_verify_greedy.argtypes = [vp, ci, ci, ci, ci, ip, dp, ip, ip, ci, ip, ip, ci]
-        lib.cos_oracle_verify_greedy.restype = ci
+        lib.cos_oracle_verify_greedy_mode.argtypes = [vp, ci, ci, ci, ci, ci, ip, ci, dp, ip, ip, ci, ip, ip, ci]
+        lib.cos_oracle_verify_greedy_mode.restype = ci
+        lib.cos_oracle_argmax_logit_mix.argtypes = [dp, dp, ci, ci]
+        lib.cos_oracle_argmax_logit_mix.restype = ci
         lib.cos_oracle_max_threads.argtypes = []
         lib.cos_oracle_max_threads.restype = ci
         _lib = lib
@@ -266,24 +268,35 @@ def argmax_contrastive(l_p, l_q, mu: float, alpha_cd: float) -> int:
     return _load().cos_oracle_argmax_contrastive(_dp(l_p), _dp(l_q), mu, alpha_cd, l_p.shape[0])
 
 
+def argmax_logit_mix(l, beta) -> int:
+    """Temperature 0 of the logit mix: index of the largest sum_m beta_m l_m (ties to the lowest index)."""
+    l = _f64(l)
+    beta = _f64(beta)
+    n, V = l.shape
+    assert beta.shape == (n,)
+    return _load().cos_oracle_argmax_logit_mix(_dp(l), _dp(beta), n, V)
+
+
 def verify_greedy(logits: np.ndarray, dtype: int, draft_tokens, weights, bonus_idx=None, num_threads: int = 0,
-                  num_drafts=None, no_bonus: bool = False):
-    """Temperature-0 contrastive step; returns (status, accepted_len, out_tokens)."""
+                  num_drafts=None, no_bonus: bool = False, mode: int = CONTRASTIVE):
+    """Temperature-0 step of a logit-level mode (contrastive, or logit mix); returns (status, accepted_len, out_tokens)."""
     logits = np.ascontiguousarray(logits)
-    assert logits.ndim == 4 and logits.shape[0] == 2
+    assert logits.ndim == 4
     assert logits.dtype == (np.float32 if dtype == DTYPE_F32 else np.uint16), logits.dtype   # 16-bit formats as raw bits
-    _, B, g1, V = logits.shape
+    n, B, g1, V = logits.shape
     gamma = g1 - 1
     draft_tokens = np.ascontiguousarray(draft_tokens, dtype=np.int32).reshape(B, gamma)
     weights = _f64(weights)
+    assert weights.shape[0] >= (2 if mode == CONTRASTIVE else n)
     bi = None if bonus_idx is None else np.ascontiguousarray(bonus_idx, dtype=np.int32).reshape(B)
     nd = None if num_drafts is None else np.ascontiguousarray(num_drafts, dtype=np.int32).reshape(B)
     alen = np.full(B, -7, dtype=np.int32)
     toks = np.full((B, gamma + 1), -7, dtype=np.int32)
-    st = _load().cos_oracle_verify_greedy(logits.ctypes.data_as(ctypes.c_void_p), dtype, B, gamma, V,
-                                          _ip(draft_tokens), _dp(weights), _ip(bi) if bi is not None else None,
-                                          _ip(nd) if nd is not None else None, int(bool(no_bonus)),
-                                          _ip(alen), _ip(toks), int(num_threads))
+    st = _load().cos_oracle_verify_greedy_mode(logits.ctypes.data_as(ctypes.c_void_p), dtype, n, B, gamma, V,
+                                               _ip(draft_tokens), int(mode), _dp(weights),
+                                               _ip(bi) if bi is not None else None,
+                                               _ip(nd) if nd is not None else None, int(bool(no_bonus)),
+                                               _ip(alen), _ip(toks), int(num_threads))
     return st, alen, toks
 
 

@@ -55,9 +55,12 @@ def load_library() -> ctypes.CDLL:
     """Load the in-tree library; build it first if it was never built."""
     global _lib
     if _lib is None:
+        from .build import build_library, library_is_stale
         if not os.path.exists(LIBRARY):   # only if nothing is built: a built library is used as it is
-            from .build import build_library
             build_library()
+        elif "COS_VERIFY_LIBRARY" not in os.environ and library_is_stale():
+            import warnings
+            warnings.warn("libcosverify.so is older than its sources: run `python paper_2502_01662_amd/build.py`")
         lib = ctypes.CDLL(LIBRARY)
         vp, ci, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
         lib.cos_verify_workspace_bytes.argtypes = [ci, ci, ci, ci, ci, ci]

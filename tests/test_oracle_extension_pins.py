@@ -441,3 +441,80 @@ def test_logit_mix_whole_step_equals_contrastive_without_mask_and_checks_argumen
     assert O.verify(logits, O.DTYPE_F32, drafts, proposer, 3, [1.0, 0.5], ua, ur).status == -4
     three = _inputs(rng, 3, 10, 2, 20)
     assert O.verify(three[0], O.DTYPE_F32, three[1], three[2], O.LOGIT_MIX, [0.5, 0.7, -0.2], three[3], three[4]).status == 0
+
+
+# ---- temperature 0 (greedy), logit mix -------------------------------------------
+
+def test_greedy_logit_mix_argmax_against_numpy_and_special_cases():
+    rng = _rng(40)
+    for n, V in ((1, 9), (2, 300), (3, 41), (5, 1000)):
+        l = rng.standard_normal((n, V)) * 3
+        beta = rng.normal(0.0, 0.8, n)
+        beta[0] = 1.0
+        assert O.argmax_logit_mix(l, beta) == int(np.argmax((beta[:, None] * l).sum(0)))
+        one = np.zeros(n)
+        one[n - 1] = 2.5                                         # one-hot mix: that model's argmax
+        assert O.argmax_logit_mix(l, one) == int(np.argmax(l[n - 1]))
+    lp, lq = rng.standard_normal(200) * 3, rng.standard_normal(200) * 2
+    assert O.argmax_logit_mix(np.stack([lp, lq]), [1.0, -0.5]) == O.argmax_contrastive(lp, lq, 0.5, 0.0)  # Eq. (5), no mask
+    assert O.argmax_logit_mix(np.array([[1.0, 5.0, 5.0, 2.0], [0.0, 0.0, 0.0, 0.0]]), [1.0, 1.0]) == 1     # tie: lowest index
+    assert O.argmax_logit_mix(np.array([[4.0, 3.0], [10.0, 0.0]]), [1.0, -0.5]) == 1                        # 4-5 < 3-0
+    assert O.argmax_logit_mix(np.array([[4.0, 3.0], [10.0, 0.0]]), [1.0, 0.0]) == 0                         # beta = 0: no part
+    assert O.argmax_logit_mix(np.array([[4.0, 3.0], [np.nan, 0.0]]), [1.0, 0.0]) == 0                       # ... not even its NaN
+
+
+def test_greedy_logit_mix_step_is_the_small_temperature_limit():
+    """The greedy step equals the sampled logit-mix step at a tiny temperature (1e-9), whatever the
+    uniforms and the proposers: a pin against the float64 sampler that is pinned elsewhere."""
+    rng = _rng(41)
+    n, B, gamma, V = 3, 300, 3, 40
+    beta = [0.9, 0.6, -0.4]
+    logits = (rng.standard_normal((n, B, gamma + 1, V)) * 2).astype(np.float32)
+    drafts = rng.integers(0, V, (B, gamma)).astype(np.int32)
+    for b in range(B):
+        for j in range(int(rng.integers(0, gamma + 1))):      # an accepted prefix of random length
+            drafts[b, j] = O.argmax_logit_mix(logits[:, b, j].astype(np.float64), beta)
+    st, alen, toks = O.verify_greedy(logits, O.DTYPE_F32, drafts, beta, mode=O.LOGIT_MIX)
+    assert st == 0
+    lim = O.verify(logits, O.DTYPE_F32, drafts, rng.integers(0, n, B).astype(np.int32), O.LOGIT_MIX, beta,
+                   rng.random((B, gamma)), rng.random(B), temperature=1e-9)
+    assert np.array_equal(alen, lim.accepted_len) and np.array_equal(toks, lim.out_tokens)
+    assert len(set(alen.tolist())) >= 3
+
+
+def test_greedy_logit_mix_brute_force_with_verifier_bonus_ragged_rows_and_no_bonus():
+    rng = _rng(42)
+    n, B, gamma, V = 4, 200, 4, 25
+    beta = np.array([1.0, 0.5, 0.0, -0.3])
+    logits = (rng.standard_normal((n, B, gamma + 1, V)) * 2).astype(np.float32)
+    arg = np.argmax(np.einsum("m,mbjv->bjv", beta, logits.astype(np.float64)), axis=-1)
+    K = rng.integers(0, gamma + 1, B).astype(np.int32)          # drafts per row
+    drafts = arg[:, :gamma].astype(np.int32)
+    cut = np.array([rng.integers(0, k + 1) for k in K])          # first mismatch (== K[b]: none)
+    for b in range(B):
+        if cut[b] < K[b]:
+            drafts[b, cut[b]] = (drafts[b, cut[b]] + 1) % V
+    bonus = rng.integers(-1, n, B).astype(np.int32)
+    poisoned = logits.copy()
+    for b in range(B):
+        poisoned[:, b, K[b] + 1:] = np.nan                        # never read
+    st, alen, toks = O.verify_greedy(poisoned, O.DTYPE_F32, drafts, beta, bonus_idx=bonus, num_drafts=K, mode=O.LOGIT_MIX)
+    assert st == 0 and np.array_equal(alen, cut)
+    for b in range(B):
+        assert np.array_equal(toks[b, :cut[b]], drafts[b, :cut[b]]) and np.all(toks[b, cut[b] + 1:] == -1)
+        if cut[b] < K[b] or bonus[b] < 0:
+            assert toks[b, cut[b]] == arg[b, cut[b]]
+        else:
+            assert toks[b, cut[b]] == int(np.argmax(logits[bonus[b], b, K[b]]))
+    for b in range(B):
+        poisoned[:, b, K[b]:] = np.nan                            # without the extra token not even that position
+    st2, alen2, toks2 = O.verify_greedy(poisoned, O.DTYPE_F32, drafts, beta, num_drafts=K, no_bonus=True, mode=O.LOGIT_MIX)
+    assert st2 == 0 and np.array_equal(alen2, cut)
+    full = cut == K
+    assert np.all(toks2[full, :][np.arange(full.sum()), K[full]] == -1)
+    assert np.array_equal(toks2[~full], toks[~full])
+    # argument checks
+    assert O.verify_greedy(logits, O.DTYPE_F32, drafts, [1.0, np.inf, 0.0, 0.0], mode=O.LOGIT_MIX)[0] == -5
+    assert O.verify_greedy(logits, O.DTYPE_F32, drafts, beta, mode=O.ENSEMBLE)[0] == -4
+    assert O.verify_greedy(logits, O.DTYPE_F32, drafts, [0.5, 0.1], mode=O.CONTRASTIVE)[0] == -4   # contrastive needs n == 2
+    assert O.verify_greedy(logits, O.DTYPE_F32, drafts, beta, bonus_idx=np.full(B, n), mode=O.LOGIT_MIX)[0] == -2
