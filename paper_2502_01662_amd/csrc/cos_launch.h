@@ -105,7 +105,8 @@ cos_status_t launch_all(Params p, int mode, int window, size_t lds, hipStream_t 
                         : launch_acceptance_rate<T, ALIGNED, kCd>(p, st);
 }
 
-// Temperature 0, contrastive mode: the expert maxima (only with a mask), then one argmax kernel.
+// Temperature 0, logit-level modes: the expert maxima (contrastive with a mask only), then one
+// argmax kernel.
 template <typename T, bool ALIGNED>
 cos_status_t launch_greedy(Params p, const LaunchPlan& lp) {
   p.j0 = 0;
@@ -115,8 +116,18 @@ cos_status_t launch_greedy(Params p, const LaunchPlan& lp) {
   if (blocks <= 0 || blocks > 0x7fffffffL) return COS_ERR_SHAPE;
   const dim3 grid((unsigned)blocks), block(kThreads);
   if (lp.ev_start) (void)hipEventRecord(lp.ev_start, lp.stream);
-  if (p.masked) hipLaunchKernelGGL((expert_rowmax_kernel<T, ALIGNED>), grid, block, 0, lp.stream, p);
-  hipLaunchKernelGGL((greedy_contrastive_kernel<T, ALIGNED>), grid, block, 0, lp.stream, p);
+  if (lp.mode == kMix) {
+    switch (p.n) {
+      case 1: hipLaunchKernelGGL((greedy_mix_kernel<T, ALIGNED, 1>), grid, block, 0, lp.stream, p); break;
+      case 2: hipLaunchKernelGGL((greedy_mix_kernel<T, ALIGNED, 2>), grid, block, 0, lp.stream, p); break;
+      case 3: hipLaunchKernelGGL((greedy_mix_kernel<T, ALIGNED, 3>), grid, block, 0, lp.stream, p); break;
+      case 4: hipLaunchKernelGGL((greedy_mix_kernel<T, ALIGNED, 4>), grid, block, 0, lp.stream, p); break;
+      default: hipLaunchKernelGGL((greedy_mix_kernel<T, ALIGNED, 0>), grid, block, 0, lp.stream, p); break;
+    }
+  } else {
+    if (p.masked) hipLaunchKernelGGL((expert_rowmax_kernel<T, ALIGNED>), grid, block, 0, lp.stream, p);
+    hipLaunchKernelGGL((greedy_contrastive_kernel<T, ALIGNED>), grid, block, 0, lp.stream, p);
+  }
   if (lp.ev_stop) (void)hipEventRecord(lp.ev_stop, lp.stream);
   return hipGetLastError() == hipSuccess ? COS_OK : COS_ERR_LAUNCH;
 }

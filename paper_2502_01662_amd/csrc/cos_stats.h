@@ -755,14 +755,14 @@ __global__ void __launch_bounds__(kThreads) mix_stats_kernel(Params p) {
     decide_sequence<T, kMix>(p, b, sh);
 }
 
-// Temperature 0 (greedy), contrastive mode.  r of Eq. (5) is one-hot at the
-// masked argmax a_j of c = l_0 - mu l_1, so a draft is accepted iff d_j == a_j and
-// the token drawn at the first mismatch (or the bonus token) is a_j itself: one
-// streaming argmax per position, no sampling kernel, no random numbers.  c is
-// evaluated in float64 with a separate multiply and subtract so that every
-// comparison is the one a float64 reference makes; ties go to the lowest index.
-// Workgroup index -> (b, j, s).  With a verifier bonus the bonus position takes
-// the plain argmax of that model's row.
+// Temperature 0 (greedy), logit-level modes.  r is one-hot at a_j -- the masked
+// argmax of c = l_0 - mu l_1 (Eq. (5)), or the argmax of c = sum_m beta_m l_m
+// (Eq. (3), linear) -- so a draft is accepted iff d_j == a_j and the token drawn at
+// the first mismatch (or the bonus token) is a_j itself: one streaming argmax per
+// position, no sampling kernel, no random numbers.  c is evaluated in float64 with
+// separate multiplies and adds so that every comparison is the one a float64
+// reference makes; ties go to the lowest index.  Workgroup index -> (b, j, s).
+// With a verifier bonus the bonus position takes the plain argmax of that model's row.
 struct ArgBest {
   double val;
   int idx;  // -1: nothing eligible seen
@@ -773,6 +773,64 @@ __device__ __forceinline__ void arg_better(ArgBest& a, double val, int idx) {
     a.val = val;
     a.idx = idx;
   }
+}
+
+// One lane's candidate: element `idx` with value `val` is taken if eligible, in
+// range and larger than what the lane holds (ascending idx per lane, so strict).
+__device__ __forceinline__ void arg_take(ArgBest& best, double val, int idx, bool eligible) {
+  if (eligible && (best.idx < 0 || val > best.val)) {
+    best.val = val;
+    best.idx = idx;
+  }
+}
+
+// A value of a plain row (or of a mix) is eligible unless it is NaN; a row of -inf
+// still has an argmax, its first element.
+__device__ __forceinline__ bool arg_plain_ok(const ArgBest& best, double val) {
+  return val > -INFINITY || (best.idx < 0 && val == -INFINITY);
+}
+
+// Lanes -> wavefront -> workgroup -> the chunk's partial, then the arrival.  The
+// workgroup that completes the sequence takes the argmax of every position, finds
+// the first mismatch and writes the outputs.
+__device__ __forceinline__ void greedy_finish(const Params& p, int b, int gb, ArgBest best, Partial* out,
+                                              int per_b, ArgBest* wbest, int* s_flag, int* s_arg) {
+  const int tid = threadIdx.x;
+  const int g1 = p.gamma + 1;
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) {
+    const double ov = __shfl_xor(best.val, d, 64);
+    const int oi = __shfl_xor(best.idx, d, 64);
+    arg_better(best, ov, oi);
+  }
+  if (lane_id() == 0) wbest[tid >> 6] = best;
+  __syncthreads();
+  if (tid == 0) {
+    ArgBest bb = wbest[0];
+    for (int w = 1; w < kWaves; ++w) arg_better(bb, wbest[w].val, wbest[w].idx);
+    store_agent(&out->Z, bb.val);
+    store_agent(&out->o, bb.idx);
+    wait_stores();
+  }
+  if (!arrive_last(p.counters + (size_t)b * kCtrStride, per_b, s_flag)) return;
+
+  if (tid < g1) {
+    const Partial* pp = p.partials + (((size_t)b * g1 + tid) * p.nstat) * p.S;
+    ArgBest bb;
+    bb.val = 0.0;
+    bb.idx = -1;
+    for (int i = 0; i < p.S; ++i) arg_better(bb, load_agent(&pp[i].Z), load_agent(&pp[i].o));
+    s_arg[tid] = bb.idx;
+  }
+  __syncthreads();
+  int jstar = gb;
+  for (int jj = gb - 1; jj >= 0; --jj)
+    if (p.draft[(size_t)b * p.gamma + jj] != s_arg[jj]) jstar = jj;
+  const bool skip = p.no_bonus && jstar == gb;  // every draft accepted, no extra token
+  if (tid == 0) p.accepted_len[b] = jstar;
+  if (tid < g1)
+    p.out_tokens[(size_t)b * g1 + tid] =
+        tid < jstar ? p.draft[(size_t)b * p.gamma + tid] : ((tid == jstar && !skip) ? s_arg[jstar] : -1);
 }
 
 template <typename T, bool ALIGNED>
@@ -828,62 +886,97 @@ __global__ void __launch_bounds__(kThreads) greedy_contrastive_kernel(Params p) 
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int first = (base + u * kThreads + tid) * N;  // element index of x[u][0]
+      const bool inside = base + u * kThreads + tid < v1;
 #pragma unroll
       for (int k = 0; k < N; ++k) {
         double val;
         bool ok;
         if (plain >= 0) {
           val = (double)(plain ? x1[u][k] : x0[u][k]);
-          ok = val > -INFINITY || (best.idx < 0 && val == -INFINITY);  // a row of -inf still has an argmax
+          ok = arg_plain_ok(best, val);
         } else {
           ok = in_mask<T>(x0[u][k], m0, p.thr32, p.thr64);
           const double prod = mu * (double)x1[u][k];
           val = (double)x0[u][k] - prod;
         }
-        if (ok && base + u * kThreads + tid < v1 && first + k < p.V && (best.idx < 0 || val > best.val)) {
-          best.val = val;
-          best.idx = first + k;
-        }
+        arg_take(best, val, first + k, ok && inside && first + k < p.V);
       }
     }
   }
-  // wavefront, then workgroup
-#pragma unroll
-  for (int d = 32; d >= 1; d >>= 1) {
-    const double ov = __shfl_xor(best.val, d, 64);
-    const int oi = __shfl_xor(best.idx, d, 64);
-    arg_better(best, ov, oi);
-  }
-  if (lane_id() == 0) wbest[tid >> 6] = best;
-  __syncthreads();
-  if (tid == 0) {
-    ArgBest bb = wbest[0];
-    for (int w = 1; w < kWaves; ++w) arg_better(bb, wbest[w].val, wbest[w].idx);
-    Partial* out = p.partials + (((size_t)b * g1 + j) * p.nstat) * p.S + s;
-    store_agent(&out->Z, bb.val);
-    store_agent(&out->o, bb.idx);
-    wait_stores();
-  }
-  if (!arrive_last(p.counters + (size_t)b * kCtrStride, per_b, &s_flag)) return;
+  Partial* out = p.partials + (((size_t)b * g1 + j) * p.nstat) * p.S + s;
+  greedy_finish(p, b, gb, best, out, per_b, wbest, &s_flag, s_arg);
+}
 
-  // last workgroup of the sequence: argmax of every position, first mismatch, outputs
-  if (tid < g1) {
-    const Partial* pp = p.partials + (((size_t)b * g1 + tid) * p.nstat) * p.S;
-    ArgBest bb;
-    bb.val = 0.0;
-    bb.idx = -1;
-    for (int i = 0; i < p.S; ++i) arg_better(bb, load_agent(&pp[i].Z), load_agent(&pp[i].o));
-    s_arg[tid] = bb.idx;
+// The same for the logit mix: one workgroup reads the chunk of all n rows.
+template <typename T, bool ALIGNED, int NM>
+__global__ void __launch_bounds__(kThreads) greedy_mix_kernel(Params p) {
+  constexpr int N = VecOf<T>::N;
+  constexpr int NCAP = NM ? NM : COS_MAX_MODELS;
+  constexpr int U = NCAP <= 2 ? 4 : (NCAP <= 4 ? 2 : 1);  // vectors per lane and row in flight
+  constexpr int kStep = kThreads * U;
+  __shared__ ArgBest wbest[kWaves];
+  __shared__ int s_flag;
+  __shared__ int s_arg[COS_MAX_GAMMA + 1];
+
+  const int n = NM ? NM : p.n;
+  const int g1 = p.gamma + 1;
+  const int per_b = g1 * p.S;
+  const int b = blockIdx.x / per_b;
+  int rem = blockIdx.x - b * per_b;
+  const int j = rem / p.S;
+  const int s = rem - j * p.S;
+  const int tid = threadIdx.x;
+  const int gb = drafts_of(p, b);
+  const bool unread = position_unread(p, gb, j);
+  const int plain = (j == gb && p.bonus_idx) ? p.bonus_idx[b] : -1;
+  // a verifier bonus reads that model's row only (slot 0); the others need not be valid
+  const int nload = plain >= 0 ? 1 : n;
+
+  const T* rows[NCAP];
+#pragma unroll
+  for (int m = 0; m < NCAP; ++m) rows[m] = row_ptr<T>(p, plain >= 0 ? plain : (m < n ? m : 0), b, j);
+  const int v0 = s * p.cv;
+  const int v1 = min(v0 + p.cv, p.nvec);
+  ArgBest best;
+  best.val = 0.0;
+  best.idx = -1;
+  for (int base = v0; base < v1 && !unread; base += kStep) {
+    float x[NCAP][U][N];
+    if (base + kStep <= v1) {
+#pragma unroll
+      for (int m = 0; m < NCAP; ++m)
+        if (m < nload) load_group<T, ALIGNED, false, U>(rows[m], base, v1, p.V, x[m]);
+    } else {
+#pragma unroll
+      for (int m = 0; m < NCAP; ++m)
+        if (m < nload) load_group<T, ALIGNED, true, U>(rows[m], base, v1, p.V, x[m]);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int first = (base + u * kThreads + tid) * N;  // element index of x[.][u][0]
+      const bool inside = base + u * kThreads + tid < v1;
+#pragma unroll
+      for (int k = 0; k < N; ++k) {
+        double val;
+        if (plain >= 0) {
+          val = (double)x[0][u][k];
+        } else {
+          // sum_m beta_m l_m in model order, each product rounded on its own, models without
+          // weight left out: the float64 reference's operations
+          val = 0.0;
+#pragma unroll
+          for (int m = 0; m < NCAP; ++m)
+            if (m < n && p.w[m] != 0.0) {
+              const double prod = p.w[m] * (double)x[m][u][k];
+              val = val + prod;
+            }
+        }
+        arg_take(best, val, first + k, arg_plain_ok(best, val) && inside && first + k < p.V);
+      }
+    }
   }
-  __syncthreads();
-  int jstar = gb;
-  for (int jj = gb - 1; jj >= 0; --jj)
-    if (p.draft[(size_t)b * p.gamma + jj] != s_arg[jj]) jstar = jj;
-  const bool skip = p.no_bonus && jstar == gb;  // every draft accepted, no extra token
-  if (tid == 0) p.accepted_len[b] = jstar;
-  if (tid < g1)
-    p.out_tokens[(size_t)b * g1 + tid] =
-        tid < jstar ? p.draft[(size_t)b * p.gamma + tid] : ((tid == jstar && !skip) ? s_arg[jstar] : -1);
+  Partial* out = p.partials + (((size_t)b * g1 + j) * p.nstat) * p.S + s;
+  greedy_finish(p, b, gb, best, out, per_b, wbest, &s_flag, s_arg);
 }
 
 }  // namespace

@@ -4,6 +4,7 @@ import numpy as np
 import pytest
 import torch
 
+from oracle import cos_oracle as O
 from paper_2502_01662_amd import cos_verify as C
 from paper_2502_01662_amd import workloads as W
 from tests import parity as P
@@ -124,9 +125,9 @@ def test_logit_mix_at_the_c5_shape_and_argument_checks():
                      inp["u_accept"], inp["u_resample"])
     with pytest.raises(C.CosVerifyError):
         C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], 3, beta, inp["u_accept"], inp["u_resample"])
-    with pytest.raises(C.CosVerifyError):                    # temperature 0 is built for Eq. (5) only
+    with pytest.raises(C.CosVerifyError):                    # temperature 0 has no acceptance rates to report
         C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], MIX, beta, inp["u_accept"],
-                     inp["u_resample"], greedy=True)
+                     inp["u_resample"], greedy=True, alpha=torch.empty((w.B, w.gamma), dtype=torch.float64, device="cuda"))
 
 
 @pytest.mark.parametrize("dtype,shift", [("f32", 0.0), ("f32", 500.0), ("bf16", 0.0), ("f16", 0.0)])
@@ -145,3 +146,92 @@ def test_logit_level_modes_cancel_exactly_when_r_equals_q(dtype, shift):
         assert np.all(alen == 0)
         assert np.all(diag.flags.cpu().numpy() & C.COS_FLAG_RESIDUAL_FALLBACK)
         assert rep.flag_mismatches == 0
+
+
+# ---------------------------------------------------------------------------
+# temperature 0 (greedy) of the logit mix: bit-exact, no near-tie excuses
+# ---------------------------------------------------------------------------
+
+def _greedy_mix_inputs(n, B, gamma, V, dtype, seed, beta, std=2.0):
+    """Random logits; drafts follow the argmax of the mix on a prefix of varying length."""
+    inp = _random_inputs(n, B, gamma, V, dtype, seed=seed, std=std)
+    host = W.host_logits(inp["logits"])
+    odt = P.oracle_dtype(inp["logits"])
+    drafts = inp["draft_tokens"].cpu().numpy().copy()
+    for b in range(B):
+        for j in range(b % (gamma + 1)):
+            drafts[b, j] = O.argmax_logit_mix(np.stack([O.row_to_f64(host[m, b, j], odt) for m in range(n)]), beta)
+    inp["draft_tokens"] = torch.from_numpy(drafts).cuda()
+    return inp, host, odt
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32", "f16"])
+@pytest.mark.parametrize("n,B,gamma,V,beta", [(1, 5, 2, 9, [1.7]), (2, 12, 3, 1000, [1.0, -0.5]), (3, 8, 2, 4099, [0.5, 0.3, 0.2]),
+                                              (4, 10, 4, 33000, [0.9, 0.0, -0.3, 0.4]), (5, 7, 3, 70001, [0.2] * 5),
+                                              (2, 16, 5, 128256, [1.5, -0.5]), (8, 6, 2, 20000, [0.3, 0.1, -0.2, 0.0, 0.5, 0.1, 0.1, 0.1])])
+def test_greedy_logit_mix_is_bit_exact(dtype, n, B, gamma, V, beta):
+    inp, host, odt = _greedy_mix_inputs(n, B, gamma, V, dtype, seed=V + B, beta=beta)
+    for bonus in (None, torch.tensor([(b % (n + 1)) - 1 for b in range(B)], dtype=torch.int32).cuda()):
+        if bonus is not None:                                 # with a verifier bonus the other rows are never read
+            for b in range(B):
+                if int(bonus[b]) >= 0:
+                    for m in range(n):
+                        if m != int(bonus[b]):
+                            inp["logits"][m, b, gamma] = float("nan")
+            host = W.host_logits(inp["logits"])
+        alen, toks = C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], MIX, beta,
+                                  inp["u_accept"], inp["u_resample"], greedy=True, bonus_idx=bonus)
+        torch.cuda.synchronize()
+        st, want_len, want_toks = O.verify_greedy(host, odt, inp["draft_tokens"].cpu().numpy(), beta, mode=O.LOGIT_MIX,
+                                                  bonus_idx=None if bonus is None else bonus.cpu().numpy())
+        assert st == 0
+        assert np.array_equal(alen.cpu().numpy(), want_len)
+        assert np.array_equal(toks.cpu().numpy(), want_toks)
+        assert len(set(want_len.tolist())) == min(B, gamma + 1)
+
+
+@pytest.mark.parametrize("no_bonus", [False, True])
+def test_greedy_logit_mix_ragged_rows_odd_vocabulary_and_minus_inf(no_bonus):
+    n, B, gamma, V, beta = 3, 21, 4, 33001, [0.6, 0.3, 0.4]
+    inp, _, _ = _greedy_mix_inputs(n, B, gamma, V, "bf16", seed=77, beta=beta)
+    inp["logits"][:, :, :, 5::7] = float("-inf")              # impossible tokens (non-negative weights)
+    inp, host, odt = inp, W.host_logits(inp["logits"]), O.DTYPE_BF16
+    drafts = inp["draft_tokens"].cpu().numpy().copy()
+    for b in range(B):
+        for j in range(b % (gamma + 1)):
+            drafts[b, j] = O.argmax_logit_mix(np.stack([O.row_to_f64(host[m, b, j], odt) for m in range(n)]), beta)
+    inp["draft_tokens"] = torch.from_numpy(drafts).cuda()
+    nd = np.array([(b * 2) % (gamma + 1) for b in range(B)], dtype=np.int32)
+    for b in range(B):
+        inp["logits"][:, b, int(nd[b]) + (0 if no_bonus else 1):] = float("nan")
+    host = W.host_logits(inp["logits"])
+    alen, toks = C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], MIX, beta, inp["u_accept"],
+                              inp["u_resample"], greedy=True, num_drafts=torch.from_numpy(nd).cuda(), no_bonus=no_bonus)
+    torch.cuda.synchronize()
+    st, want_len, want_toks = O.verify_greedy(host, odt, drafts, beta, num_drafts=nd, no_bonus=no_bonus, mode=O.LOGIT_MIX)
+    assert st == 0
+    assert np.array_equal(alen.cpu().numpy(), want_len) and np.array_equal(toks.cpu().numpy(), want_toks)
+    assert (want_len == nd).sum() >= 4 and (want_len < nd).sum() >= 4
+
+
+def test_greedy_logit_mix_ties_and_the_contrastive_special_case():
+    B, gamma, V = 4, 2, 5000
+    inp = _random_inputs(2, B, gamma, V, "bf16", seed=3)
+    inp["logits"][:] = 0.0                                   # every token ties
+    inp["logits"][0, :, :, 4000] = 1.0
+    inp["logits"][0, :, :, 77] = 1.0                         # two maxima: the lower index wins
+    inp["draft_tokens"][:] = 77
+    alen, toks = C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], MIX, [1.0, -0.5],
+                              inp["u_accept"], inp["u_resample"], greedy=True)
+    torch.cuda.synchronize()
+    assert np.all(alen.cpu().numpy() == gamma) and np.all(toks.cpu().numpy() == 77)
+    # beta = (1, -mu) is Eq. (5) without its mask: the two greedy kernels agree
+    inp = _random_inputs(2, 9, 3, 50000, "f32", seed=8, std=2.5)
+    top = inp["logits"][0].double() - 0.5 * inp["logits"][1].double()
+    inp["draft_tokens"][::2] = top[::2, :3].argmax(-1).to(torch.int32)
+    a1, t1 = C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], MIX, [1.0, -0.5],
+                          inp["u_accept"], inp["u_resample"], greedy=True)
+    a2, t2 = C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], C.COS_COMBINE_CONTRASTIVE, [0.5, 0.0],
+                          inp["u_accept"], inp["u_resample"], greedy=True)
+    torch.cuda.synchronize()
+    assert torch.equal(a1, a2) and torch.equal(t1, t2) and int(a1.max()) == 3
