@@ -106,3 +106,44 @@ def test_random_float16_configuration(seed):
     print(f"[fuzz] {desc}: {rep.summary()}", flush=True)
     assert rep.ok, (desc, rep.failures[:3])
     assert rep.excused_accept_ties + rep.excused_cdf_ties <= 1, (desc, rep.summary())
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_greedy_configuration(seed):
+    """Temperature 0 of the logit-level modes on the same random shapes: bit-exact, nothing excused."""
+    from oracle import cos_oracle as O
+    from paper_2502_01662_amd import workloads as W
+    inp, mode, weights, desc = _case(11000 + seed)
+    rng = np.random.default_rng(12000 + seed)
+    n, B, gamma, V = desc["n"], desc["B"], desc["gamma"], desc["V"]
+    if mode != C.COS_COMBINE_CONTRASTIVE:                         # an ensemble case: take its shape for a logit mix
+        mode = C.COS_COMBINE_LOGIT_MIX
+        weights = rng.normal(0.0, 0.8, n)
+        weights[rng.integers(0, n)] = 1.0
+        if torch.isinf(inp["logits"]).any():
+            weights = np.abs(weights)
+        weights = weights.tolist()
+    host, odt = W.host_logits(inp["logits"]), P.oracle_dtype(inp["logits"])
+    drafts = inp["draft_tokens"].cpu().numpy().copy()
+    for b in range(B):                                            # an accepted prefix of random length
+        for j in range(int(rng.integers(0, gamma + 1))):
+            rows = [O.row_to_f64(host[m, b, j], odt) for m in range(n)]
+            if np.isnan(rows[0]).any():
+                break                                             # poisoned: beyond this row's drafts
+            drafts[b, j] = (O.argmax_contrastive(rows[0], rows[1], weights[0], weights[1])
+                            if mode == C.COS_COMBINE_CONTRASTIVE else O.argmax_logit_mix(np.stack(rows), weights))
+    inp["draft_tokens"] = torch.from_numpy(drafts).cuda()
+    nd, bonus = inp.get("num_drafts"), inp.get("bonus_idx")
+    alen, toks = C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], mode, weights, inp["u_accept"],
+                              inp["u_resample"], greedy=True, bonus_idx=bonus, num_drafts=nd,
+                              no_bonus=bool(inp.get("no_bonus", False)))
+    torch.cuda.synchronize()
+    st, want_len, want_toks = O.verify_greedy(host, odt, drafts, weights, mode=mode,
+                                              bonus_idx=None if bonus is None else bonus.cpu().numpy(),
+                                              num_drafts=None if nd is None else nd.cpu().numpy(),
+                                              no_bonus=bool(inp.get("no_bonus", False)))
+    desc["mode"] = mode
+    print(f"[fuzz] greedy {desc}: accepted lengths {np.bincount(want_len, minlength=gamma + 1).tolist()}", flush=True)
+    assert st == 0
+    assert np.array_equal(alen.cpu().numpy(), want_len), desc
+    assert np.array_equal(toks.cpu().numpy(), want_toks), desc
