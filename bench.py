@@ -40,6 +40,9 @@ def main() -> int:
     ap.add_argument("--cpu-rows", type=int, default=-1, help="batch rows the CPU oracle is timed on (-1 = auto, 0 = skip)")
     ap.add_argument("--chunk-vectors", type=int, default=0, help="tuning knob (0 = library heuristic)")
     ap.add_argument("--sample-blocks", type=int, default=0, help="tuning knob (0 = library heuristic)")
+    ap.add_argument("--tail-sequences", type=int, default=-1,
+                    help="tuning knob: sequences at the end of the grid with shorter chunks (-1 = library heuristic)")
+    ap.add_argument("--tail-factor", type=int, default=4, help="tuning knob: how many times shorter")
     ap.add_argument("--stop-window", type=int, default=0,
                     help="verify this many positions per launch and never read past a sequence's first "
                          "rejection (0 = the headline step: every position read, one launch)")
@@ -70,6 +73,7 @@ def main() -> int:
     C.load_library()
     C.cos_tune_set_chunk_vectors(args.chunk_vectors)
     C.cos_tune_set_sample_blocks(args.sample_blocks)
+    C.cos_tune_set_tail(args.tail_sequences, args.tail_factor)
 
     t0 = time.time()
     # small workloads: rotate over distinct input sets so that the timed calls stream from HBM,
@@ -202,7 +206,7 @@ def main() -> int:
         "config": {"workload": w.name, "n": w.n, "B": w.B, "gamma": w.gamma, "V": w.V,
                    "combine": "contrastive" if w.mode == W.CONTRASTIVE else "ensemble", "weights": list(w.weights),
                    "input_sets_rotated": nsets, "chunk_vectors": args.chunk_vectors,
-                   "sample_blocks": args.sample_blocks, "acceptance_rate_output": bool(args.with_alpha),
+                   "sample_blocks": args.sample_blocks, "tail_sequences": args.tail_sequences, "tail_factor": args.tail_factor, "acceptance_rate_output": bool(args.with_alpha),
                    "stop_window": args.stop_window},
         "achieved_hbm_gbs_per_step": round(w.logit_bytes / (ms_per_step * 1e-3) / 1e9, 1),
         "roofline": roofline, "cpu_baseline": cpu, "parity_sample": parity, "stop_window_1": lazy,

@@ -254,6 +254,15 @@ void cos_tune_set_chunk_vectors(int vectors);
  */
 void cos_tune_set_sample_blocks(int blocks);
 
+/*
+ * Tuning knob for experiments: the rows of the last `sequences` sequences of a streaming
+ * launch are cut into `factor` times more chunks than the others (they run while
+ * the GPU drains, where short chunks finish sooner).  sequences < 0 restores the
+ * built-in heuristic, 0 or factor <= 1 turns it off.  Process-wide;
+ * cos_verify_workspace_bytes() depends on it.
+ */
+void cos_tune_set_tail(int sequences, int factor);
+
 #ifdef __cplusplus
 }
 #endif

@@ -86,6 +86,8 @@ def load_library() -> ctypes.CDLL:
         lib.cos_tune_set_chunk_vectors.restype = None
         lib.cos_tune_set_sample_blocks.argtypes = [ci]
         lib.cos_tune_set_sample_blocks.restype = None
+        lib.cos_tune_set_tail.argtypes = [ci, ci]
+        lib.cos_tune_set_tail.restype = None
         _lib = lib
     return _lib
 
@@ -147,6 +149,10 @@ class Diagnostics:
     def as_struct(self) -> CosDiag:
         return CosDiag(self.r_at_draft.data_ptr(), self.q_at_draft.data_ptr(), self.sample_mass.data_ptr(),
                        self.cdf_lo.data_ptr(), self.cdf_hi.data_ptr(), self.flags.data_ptr())
+
+
+def cos_tune_set_tail(sequences: int, factor: int) -> None:
+    load_library().cos_tune_set_tail(int(sequences), int(factor))
 
 
 def _dtype_code(t: torch.Tensor) -> int:

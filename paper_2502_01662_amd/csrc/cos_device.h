@@ -80,8 +80,11 @@ struct Params {
   double* alpha_partials;  // [B][gamma][CA]
   int CA;                  // acceptance-rate workgroups per (sequence, position)
   int tpa;                 // tiles per acceptance-rate workgroup
-  int S;              // chunks per row
-  int cv;             // vectors per chunk
+  int S;              // stride of the per-chunk arrays: the larger of Sh and St
+  int Sh, cvh;        // sequences before b_tail: chunks per row, vectors per chunk
+  int St, cvt;        // sequences from b_tail on (the end of the grid, which runs while the GPU drains):
+                      // more and shorter chunks
+  int b_tail;         // first sequence cut the second way (B: none)
   int nvec;           // 16-byte vectors per row (last may be partial when unaligned)
   int ntiles;         // tiles (64 vectors) per row
   int nstat;          // statistics per position: n (ensemble) or 3 (contrastive)
@@ -129,6 +132,35 @@ namespace {
 __device__ __forceinline__ int drafts_of(const Params& p, int b) {
   return p.num_drafts ? p.num_drafts[b] : p.gamma;
 }
+
+// Where a streaming workgroup works: its sequence, its index among that sequence's
+// workgroups, and how the sequence's rows are cut.  The grid lists the sequences in
+// order, rows_per_b rows each, every row cut into S chunks.
+struct Place {
+  int b, rem, S, cv, per_b;
+};
+__device__ __forceinline__ Place place_of(const Params& p, int rows_per_b) {
+  Place pl;
+  const int per_head = rows_per_b * p.Sh;
+  const int head = p.b_tail * per_head;
+  if ((int)blockIdx.x < head) {
+    pl.S = p.Sh;
+    pl.cv = p.cvh;
+    pl.per_b = per_head;
+    pl.b = blockIdx.x / per_head;
+    pl.rem = blockIdx.x - pl.b * per_head;
+  } else {
+    const int i = blockIdx.x - head;
+    pl.S = p.St;
+    pl.cv = p.cvt;
+    pl.per_b = rows_per_b * p.St;
+    const int bb = i / pl.per_b;
+    pl.b = p.b_tail + bb;
+    pl.rem = i - bb * pl.per_b;
+  }
+  return pl;
+}
+__device__ __forceinline__ int splits_of(const Params& p, int b) { return b < p.b_tail ? p.Sh : p.St; }
 
 // Positions after the row's bonus position are never read, and neither is the
 // bonus position itself when no extra token is wanted.

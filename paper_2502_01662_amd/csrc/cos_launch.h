@@ -68,6 +68,12 @@ void launch_mix_stats(const Params& p, dim3 grid, hipStream_t st) {
   }
 }
 
+// Workgroups of a streaming launch: rows_per_b rows per sequence, cut into Sh chunks for the
+// sequences before b_tail and into St for the rest.
+inline long stream_blocks(const Params& p, int rows_per_b) {
+  return ((long)p.b_tail * p.Sh + (long)(p.B - p.b_tail) * p.St) * rows_per_b;
+}
+
 // All launches of one call after the fill kernel.  `window` positions are
 // verified per streaming launch; sequences decided by an earlier window are
 // skipped by every later one (their workgroups return at once).
@@ -81,7 +87,7 @@ cos_status_t launch_all(Params p, int mode, int window, size_t lds, hipStream_t 
   for (int j0 = 0; j0 < g1; j0 += window, ++p.win) {
     p.j0 = j0;
     p.nj = (j0 + window <= g1) ? window : g1 - j0;
-    const long blocks = (long)p.B * p.nj * (mode == kEns ? p.n : 1) * p.S;
+    const long blocks = stream_blocks(p, p.nj * (mode == kEns ? p.n : 1));
     if (blocks <= 0 || blocks > 0x7fffffffL) return COS_ERR_SHAPE;
     const dim3 grid((unsigned)blocks);
     if (mode == kEns) {
@@ -112,7 +118,7 @@ cos_status_t launch_greedy(Params p, const LaunchPlan& lp) {
   p.j0 = 0;
   p.nj = p.gamma + 1;
   p.win = 0;
-  const long blocks = (long)p.B * (p.gamma + 1) * p.S;
+  const long blocks = stream_blocks(p, p.gamma + 1);
   if (blocks <= 0 || blocks > 0x7fffffffL) return COS_ERR_SHAPE;
   const dim3 grid((unsigned)blocks), block(kThreads);
   if (lp.ev_start) (void)hipEventRecord(lp.ev_start, lp.stream);

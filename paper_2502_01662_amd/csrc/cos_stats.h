@@ -266,6 +266,7 @@ __device__ void decide_sequence(const Params& p, int b, DecideShared& sh) {
   const int nrows = nj * nstat;  // statistics of this window
   const int n = p.n;
   const int gb = drafts_of(p, b);
+  const int Sb = splits_of(p, b);        // chunks per row of this sequence
   const double log2e = (double)p.scale;  // log2(e) / T, the same constant the streaming kernel used
 
   // 0. The loads that do not depend on the statistics go out first, so that their latency
@@ -297,7 +298,7 @@ __device__ void decide_sequence(const Params& p, int b, DecideShared& sh) {
   //    loads, not S of them; with whole rows (S = 1) it is one thread per statistic.
   {
     int G = 1;
-    while (G < p.S && G < 64) G <<= 1;
+    while (G < Sb && G < 64) G <<= 1;
     const int per_pass = kThreads / G;
     const int gl = tid & (G - 1);
     for (int r0 = 0; r0 < nrows; r0 += per_pass) {  // uniform trip count: every lane shuffles
@@ -306,7 +307,7 @@ __device__ void decide_sequence(const Params& p, int b, DecideShared& sh) {
       double zsum = 0.0;  // sum of Z 2^(o - omax) over the partials seen by this lane
       if (r < nrows) {
         const Partial* pp = p.partials + (((size_t)b * g1 + j0) * nstat + r) * p.S;
-        for (int s = gl; s < p.S; s += G) {
+        for (int s = gl; s < Sb; s += G) {
           const double z = load_agent(&pp[s].Z);
           const int o = load_agent(&pp[s].o);
           if (z > 0.0) {
@@ -332,7 +333,7 @@ __device__ void decide_sequence(const Params& p, int b, DecideShared& sh) {
     // written by the row-max kernel, an earlier launch on the same stream
     const float* rm = p.rowmax + ((size_t)b * g1 + j0 + tid) * p.S;
     float m0 = -INFINITY;
-    for (int s = 0; s < p.S && p.masked; ++s) m0 = fmaxf(m0, rm[s]);
+    for (int s = 0; s < Sb && p.masked; ++s) m0 = fmaxf(m0, rm[s]);
     sh.rowmax[tid] = p.masked ? m0 : 0.0f;
   }
   __syncthreads();
@@ -446,15 +447,15 @@ __global__ void __launch_bounds__(kThreads) ensemble_stats_kernel(Params p) {
   __shared__ int s_flag;
 
   const int g1 = p.gamma + 1;
-  const int per_b = p.nj * p.n * p.S;
-  const int b = blockIdx.x / per_b;
+  const Place pl = place_of(p, p.nj * p.n);
+  const int b = pl.b, per_b = pl.per_b;
   if (p.win > 0 && p.plans[b].jstar >= 0) return;  // decided by an earlier window: nothing more is read
-  int rem = blockIdx.x - b * per_b;
-  const int jj = rem / (p.n * p.S);
-  rem -= jj * p.n * p.S;
+  int rem = pl.rem;
+  const int jj = rem / (p.n * pl.S);
+  rem -= jj * p.n * pl.S;
   const int j = p.j0 + jj;
-  const int m = rem / p.S;
-  const int s = rem - m * p.S;
+  const int m = rem / pl.S;
+  const int s = rem - m * pl.S;
 
   Partial* out = p.partials + (((size_t)b * g1 + j) * p.n + m) * p.S + s;
   // With a verifier bonus the other models' logits at the bonus position are
@@ -468,8 +469,8 @@ __global__ void __launch_bounds__(kThreads) ensemble_stats_kernel(Params p) {
     }
   } else {
     const T* row = row_ptr<T>(p, m, b, j);
-    const int v0 = s * p.cv;
-    const int v1 = min(v0 + p.cv, p.nvec);
+    const int v0 = s * pl.cv;
+    const int v1 = min(v0 + pl.cv, p.nvec);
     int o;
     double z;
     chunk_stats<T, ALIGNED>(row, v0, v1, p.V, p.scale, o, z);
@@ -491,9 +492,10 @@ __global__ void __launch_bounds__(kThreads) expert_rowmax_kernel(Params p) {
   constexpr int kStep = kThreads * kUnroll;
   __shared__ float wmax[kWaves];
   const int g1 = p.gamma + 1;
-  const int ws = blockIdx.x / p.S;  // b * nj + jj
-  const int s = blockIdx.x - ws * p.S;
-  const int b = ws / p.nj, j = p.j0 + (ws - b * p.nj);
+  const Place pl = place_of(p, p.nj);
+  const int b = pl.b;
+  const int j = p.j0 + pl.rem / pl.S;
+  const int s = pl.rem - (j - p.j0) * pl.S;
   if (p.win > 0 && p.plans[b].jstar >= 0) return;  // decided by an earlier window
   const int rs = b * g1 + j;
   if (position_unread(p, drafts_of(p, b), j)) {
@@ -501,8 +503,8 @@ __global__ void __launch_bounds__(kThreads) expert_rowmax_kernel(Params p) {
     return;
   }
   const T* row = row_ptr<T>(p, 0, b, j);
-  const int v0 = s * p.cv;
-  const int v1 = min(v0 + p.cv, p.nvec);
+  const int v0 = s * pl.cv;
+  const int v1 = min(v0 + pl.cv, p.nvec);
   float lm = -INFINITY;
   for (int base = v0; base < v1; base += kStep) {
     float x[kUnroll][N];
@@ -539,12 +541,11 @@ __global__ void __launch_bounds__(kThreads) contrastive_stats_kernel(Params p) {
   __shared__ float s_m0[kWaves];
 
   const int g1 = p.gamma + 1;
-  const int per_b = p.nj * p.S;
-  const int b = blockIdx.x / per_b;
+  const Place pl = place_of(p, p.nj);
+  const int b = pl.b, per_b = pl.per_b;
   if (p.win > 0 && p.plans[b].jstar >= 0) return;  // decided by an earlier window: nothing more is read
-  int rem = blockIdx.x - b * per_b;
-  const int j = p.j0 + rem / p.S;
-  const int s = rem - (j - p.j0) * p.S;
+  const int j = p.j0 + pl.rem / pl.S;
+  const int s = pl.rem - (j - p.j0) * pl.S;
   const int tid = threadIdx.x;
   // Whose softmax statistic this position needs: the proposer's at a draft
   // position; at the bonus position only a verifier bonus needs one at all.
@@ -572,7 +573,7 @@ __global__ void __launch_bounds__(kThreads) contrastive_stats_kernel(Params p) {
   {
     const float* rm = p.rowmax + ((size_t)b * g1 + j) * p.S;
     float lm = -INFINITY;
-    for (int i = tid; i < p.S && p.masked; i += kThreads) lm = fmaxf(lm, rm[i]);
+    for (int i = tid; i < pl.S && p.masked; i += kThreads) lm = fmaxf(lm, rm[i]);
     const float wm = wave_max(lm);
     if (lane_id() == 0) s_m0[tid >> 6] = wm;
     __syncthreads();
@@ -584,8 +585,8 @@ __global__ void __launch_bounds__(kThreads) contrastive_stats_kernel(Params p) {
   const T* row0 = row_ptr<T>(p, 0, b, j);
   const T* row1 = row_ptr<T>(p, 1, b, j);
   const float ref0 = row_reference<T>(row0), ref1 = row_reference<T>(row1);
-  const int v0 = s * p.cv;
-  const int v1 = min(v0 + p.cv, p.nvec);
+  const int v0 = s * pl.cv;
+  const int v1 = min(v0 + pl.cv, p.nvec);
   Running rq, rc;  // proposer row; masked contrastive logits
   running_init(rq);
   running_init(rc);
@@ -654,12 +655,11 @@ __global__ void __launch_bounds__(kThreads) mix_stats_kernel(Params p) {
 
   const int n = NM ? NM : p.n;
   const int g1 = p.gamma + 1;
-  const int per_b = p.nj * p.S;
-  const int b = blockIdx.x / per_b;
+  const Place pl = place_of(p, p.nj);
+  const int b = pl.b, per_b = pl.per_b;
   if (p.win > 0 && p.plans[b].jstar >= 0) return;  // decided by an earlier window: nothing more is read
-  int rem = blockIdx.x - b * per_b;
-  const int j = p.j0 + rem / p.S;
-  const int s = rem - (j - p.j0) * p.S;
+  const int j = p.j0 + pl.rem / pl.S;
+  const int s = pl.rem - (j - p.j0) * pl.S;
   const int tid = threadIdx.x;
   const int gb = drafts_of(p, b);
   // Whose softmax statistic this position needs: the proposer's at a draft
@@ -691,8 +691,8 @@ __global__ void __launch_bounds__(kThreads) mix_stats_kernel(Params p) {
   float ref[NCAP];
 #pragma unroll
   for (int m = 0; m < NCAP; ++m) ref[m] = m < n ? row_reference<T>(rows[m]) : 0.0f;
-  const int v0 = s * p.cv;
-  const int v1 = min(v0 + p.cv, p.nvec);
+  const int v0 = s * pl.cv;
+  const int v1 = min(v0 + pl.cv, p.nvec);
   Running rq, rc;  // proposer row; mixed logits
   running_init(rq);
   running_init(rc);
@@ -816,10 +816,11 @@ __device__ __forceinline__ void greedy_finish(const Params& p, int b, int gb, Ar
 
   if (tid < g1) {
     const Partial* pp = p.partials + (((size_t)b * g1 + tid) * p.nstat) * p.S;
+    const int Sb = splits_of(p, b);
     ArgBest bb;
     bb.val = 0.0;
     bb.idx = -1;
-    for (int i = 0; i < p.S; ++i) arg_better(bb, load_agent(&pp[i].Z), load_agent(&pp[i].o));
+    for (int i = 0; i < Sb; ++i) arg_better(bb, load_agent(&pp[i].Z), load_agent(&pp[i].o));
     s_arg[tid] = bb.idx;
   }
   __syncthreads();
@@ -844,11 +845,10 @@ __global__ void __launch_bounds__(kThreads) greedy_contrastive_kernel(Params p) 
   __shared__ int s_arg[COS_MAX_GAMMA + 1];
 
   const int g1 = p.gamma + 1;
-  const int per_b = g1 * p.S;
-  const int b = blockIdx.x / per_b;
-  int rem = blockIdx.x - b * per_b;
-  const int j = rem / p.S;
-  const int s = rem - j * p.S;
+  const Place pl = place_of(p, g1);
+  const int b = pl.b, per_b = pl.per_b;
+  const int j = pl.rem / pl.S;
+  const int s = pl.rem - j * pl.S;
   const int tid = threadIdx.x;
   const int gb = drafts_of(p, b);
   const bool unread = position_unread(p, gb, j);
@@ -858,7 +858,7 @@ __global__ void __launch_bounds__(kThreads) greedy_contrastive_kernel(Params p) 
   {
     const float* rm = p.rowmax + ((size_t)b * g1 + j) * p.S;
     float lm = -INFINITY;
-    for (int i = tid; i < p.S && p.masked; i += kThreads) lm = fmaxf(lm, rm[i]);
+    for (int i = tid; i < pl.S && p.masked; i += kThreads) lm = fmaxf(lm, rm[i]);
     const float wm = wave_max(lm);
     if (lane_id() == 0) s_m0[tid >> 6] = wm;
     __syncthreads();
@@ -869,8 +869,8 @@ __global__ void __launch_bounds__(kThreads) greedy_contrastive_kernel(Params p) 
 
   const T* row0 = row_ptr<T>(p, 0, b, j);
   const T* row1 = row_ptr<T>(p, 1, b, j);
-  const int v0 = s * p.cv;
-  const int v1 = min(v0 + p.cv, p.nvec);
+  const int v0 = s * pl.cv;
+  const int v1 = min(v0 + pl.cv, p.nvec);
   ArgBest best;
   best.val = 0.0;
   best.idx = -1;
@@ -920,11 +920,10 @@ __global__ void __launch_bounds__(kThreads) greedy_mix_kernel(Params p) {
 
   const int n = NM ? NM : p.n;
   const int g1 = p.gamma + 1;
-  const int per_b = g1 * p.S;
-  const int b = blockIdx.x / per_b;
-  int rem = blockIdx.x - b * per_b;
-  const int j = rem / p.S;
-  const int s = rem - j * p.S;
+  const Place pl = place_of(p, g1);
+  const int b = pl.b, per_b = pl.per_b;
+  const int j = pl.rem / pl.S;
+  const int s = pl.rem - j * pl.S;
   const int tid = threadIdx.x;
   const int gb = drafts_of(p, b);
   const bool unread = position_unread(p, gb, j);
@@ -935,8 +934,8 @@ __global__ void __launch_bounds__(kThreads) greedy_mix_kernel(Params p) {
   const T* rows[NCAP];
 #pragma unroll
   for (int m = 0; m < NCAP; ++m) rows[m] = row_ptr<T>(p, plain >= 0 ? plain : (m < n ? m : 0), b, j);
-  const int v0 = s * p.cv;
-  const int v1 = min(v0 + p.cv, p.nvec);
+  const int v0 = s * pl.cv;
+  const int v1 = min(v0 + pl.cv, p.nvec);
   ArgBest best;
   best.val = 0.0;
   best.idx = -1;

@@ -57,6 +57,8 @@ namespace {
 
 int g_chunk_vectors = 0;  // 0 = heuristic
 int g_sample_blocks = 0;  // 0 = heuristic
+int g_tail_sequences = -1;  // sequences at the end of the grid with shorter chunks (-1 = heuristic, 0 = none)
+int g_tail_factor = 4;      // how many times shorter
 
 // Optional event ring around the streaming kernel (benchmarks only).
 constexpr int kMaxProfileSlots = 1024;
@@ -141,6 +143,52 @@ void choose_split(int rows_total, int nvec, int* S_out, int* cv_out) {
   *cv_out = cv;
 }
 
+// The end of the grid.  While the GPU drains, the workgroups still running no longer share the
+// memory system with a full machine, but one workgroup cannot use what is freed: it streams at the
+// rate its own loads in flight allow, a few times its share of the full machine.  The last whole-row
+// workgroups therefore run alone for tens of microseconds.  The rows of the last sequences -- about
+// as many workgroups as are resident at once -- are cut into shorter chunks, so that the drain is
+// short; everywhere else chunks stay long (a workgroup's start-up and hand-off are paid per chunk).
+// Measured: half a generation of resident workgroups, cut four times finer, is about the optimum
+// (0.6 % of the streaming kernel at 14336 rows of 512 KB, 3 % at 4608 rows of 256 KB, 5 % at 960 rows).
+void choose_tail(int B, int rows_per_b, int nvec, int Sh, int cvh, int* b_tail, int* St, int* cvt) {
+  *b_tail = B;
+  *St = Sh;
+  *cvt = cvh;
+  constexpr long kResident = 1536;  // workgroups the streaming kernels keep resident (6 per CU)
+  const long per_b = (long)rows_per_b * Sh;
+  long K = g_tail_sequences;
+  if (K < 0) K = ((long)B * per_b >= 2 * kResident) ? (kResident / 2 + per_b - 1) / per_b : 0;
+  if (K <= 0 || g_tail_factor <= 1) return;
+  if (K > B) K = B;
+  const int smax = max_splits(nvec);
+  long s_want = (long)Sh * g_tail_factor;
+  if (s_want > smax) s_want = smax;
+  int cv = (int)((nvec + s_want - 1) / s_want);
+  // one full group of loads per thread, as everywhere (unless the chunk length is dictated)
+  const int cv_min = g_chunk_vectors > 0 ? kThreads : kThreads * kUnroll;
+  if (cv < cv_min) cv = cv_min;
+  cv = (cv + kThreads - 1) / kThreads * kThreads;
+  const int S = (nvec + cv - 1) / cv;
+  if (S <= Sh) return;
+  *b_tail = B - (int)K;
+  *St = S;
+  *cvt = cv;
+}
+
+// Chunking of one streaming launch over `window` positions.
+struct Split {
+  int Sh, cvh, St, cvt, b_tail, stride;
+};
+Split split_for(int n, int B, int window, int nvec, bool ensemble) {
+  Split sp;
+  const int rows_per_b = (ensemble ? n : 1) * window;
+  choose_split(rows_per_b * (B > 0 ? B : 1), nvec, &sp.Sh, &sp.cvh);
+  choose_tail(B, rows_per_b, nvec, sp.Sh, sp.cvh, &sp.b_tail, &sp.St, &sp.cvt);
+  sp.stride = sp.St > sp.Sh ? sp.St : sp.Sh;
+  return sp;
+}
+
 // Acceptance-rate workgroups per (sequence, position): about 4096 in total, at
 // least 4 tiles each, at most kMaxAlphaBlocks.
 int alpha_blocks(int B, int gamma, int ntiles) {
@@ -152,7 +200,9 @@ int alpha_blocks(int B, int gamma, int ntiles) {
   return (int)ca;
 }
 
-// Sampling workgroups per sequence: about 2048 in total, at least 4 tiles each.
+// Sampling workgroups per sequence: about 2048 in total, at least 4 tiles each.  (Finer
+// workgroups at the end of this grid, as choose_tail makes them for the streaming kernels, were
+// measured and do not pay: the kernel is short and its workgroups are nearly all resident at once.)
 void choose_sampling(int B, int ntiles, int* C_out, int* tpc_out) {
   const int target = g_sample_blocks > 0 ? g_sample_blocks : 2048;
   int C = (target + B - 1) / B;
@@ -174,11 +224,15 @@ size_t cos_verify_workspace_bytes(int n, int B, int gamma, int V, cos_dtype_t dt
   if (dt != COS_DTYPE_F32 && dt != COS_DTYPE_BF16 && dt != COS_DTYPE_F16) return 0;
   if (mode != COS_COMBINE_ENSEMBLE && mode != COS_COMBINE_CONTRASTIVE && mode != COS_COMBINE_LOGIT_MIX)
     return 0;
-  // Sized for one-position windows (stop_window = 1), which split rows the most.
+  // Sized for the window length that cuts rows into the most chunks (one position per launch, as a
+  // rule; every length is tried, there are at most gamma + 1).
   Plan pl;
   const int N = dt == COS_DTYPE_F32 ? 4 : 8;
-  int S, cv;
-  choose_split((mode == COS_COMBINE_ENSEMBLE ? n : 1) * (B > 0 ? B : 1), (V + N - 1) / N, &S, &cv);
+  int S = 1;
+  for (int window = 1; window <= gamma + 1; ++window) {
+    const Split sp = split_for(n, B, window, (V + N - 1) / N, mode == COS_COMBINE_ENSEMBLE);
+    if (sp.stride > S) S = sp.stride;
+  }
   plan_layout(n, B, gamma, V, dt, mode, S, &pl);
   return pl.bytes < 256 ? 256 : pl.bytes;
 }
@@ -260,11 +314,9 @@ cos_status_t cos_verify_ex(const void* logits, cos_dtype_t dt, int n, int B, int
   const int nvec = (V + N - 1) / N;
   int window = gamma + 1;  // positions per streaming launch
   if (options && options->stop_window > 0 && options->stop_window < window) window = options->stop_window;
-  const int rows_total = (mode == kEns ? n : 1) * B * window;
-  int S, cv;
-  choose_split(rows_total, nvec, &S, &cv);
+  const Split sp = split_for(n, B, window, nvec, mode == kEns);
   Plan pl;
-  plan_layout(n, B, gamma, V, dt, combine_mode, S, &pl);
+  plan_layout(n, B, gamma, V, dt, combine_mode, sp.stride, &pl);
   if (pl.bytes > workspace_bytes || pl.ntiles > kMaxTiles) return COS_ERR_WORKSPACE;
 
   Params p;
@@ -300,8 +352,12 @@ cos_status_t cos_verify_ex(const void* logits, cos_dtype_t dt, int n, int B, int
     p.CA = (pl.ntiles + p.tpa - 1) / p.tpa;  // <= ca
   }
   p.nwin = (gamma + 1 + window - 1) / window;
-  p.S = S;
-  p.cv = cv;
+  p.S = sp.stride;
+  p.Sh = sp.Sh;
+  p.cvh = sp.cvh;
+  p.St = sp.St;
+  p.cvt = sp.cvt;
+  p.b_tail = sp.b_tail;
   p.nvec = pl.nvec;
   p.ntiles = pl.ntiles;
   p.nstat = pl.nstat;
@@ -404,5 +460,10 @@ cos_status_t cos_profile_kernel_ms(int index, float* ms) {
 void cos_tune_set_chunk_vectors(int vectors) { g_chunk_vectors = vectors > 0 ? vectors : 0; }
 
 void cos_tune_set_sample_blocks(int blocks) { g_sample_blocks = blocks > 0 ? blocks : 0; }
+
+void cos_tune_set_tail(int sequences, int factor) {
+  g_tail_sequences = sequences < 0 ? -1 : sequences;
+  g_tail_factor = factor > 1 ? factor : 1;
+}
 
 }  // extern "C"

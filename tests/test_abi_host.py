@@ -132,3 +132,23 @@ def test_cpp_driver_links_the_library_and_validates_its_arguments():
     assert subprocess.run([B.DRIVER, "0"], capture_output=True).returncode == 2              # n = 0
     assert subprocess.run([B.DRIVER, "2", "1", "2", "16", "int8"], capture_output=True).returncode == 2
     assert subprocess.run([B.DRIVER, "2", "1", "2", "16", "bf16", "vote"], capture_output=True).returncode == 2
+
+
+def test_workspace_bytes_follow_the_tail_knob():
+    """Shorter chunks for the last sequences need more room for chunk partials: the size function and the
+    call must agree on it (the call rejects a workspace sized before the knob was turned)."""
+    shape = (2, 2048, 4, 128256, C.COS_DTYPE_BF16, C.COS_COMBINE_ENSEMBLE)   # whole rows per workgroup without the knob
+    try:
+        C.cos_tune_set_tail(0, 1)
+        plain = C.cos_verify_workspace_bytes(*shape)
+        C.cos_tune_set_tail(8, 16)
+        finer = C.cos_verify_workspace_bytes(*shape)
+        assert finer > plain > 0
+        lib = C.load_library()
+        w = (ctypes.c_double * 2)(0.5, 0.5)
+        call = lambda nbytes: lib.cos_verify(0x1000, 1, 2, 2048, 4, 128256, 0x1000, 0x1000, 0, w, 0x1000, 0x1000,
+                                             0x1000, 0x1000, 0x1000, nbytes, None, None)
+        assert call(plain) == -6                                 # too small for this setting: rejected on the host
+    finally:
+        C.cos_tune_set_tail(-1, 4)
+    assert C.cos_verify_workspace_bytes(*shape) >= plain

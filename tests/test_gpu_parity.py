@@ -311,6 +311,41 @@ def test_results_do_not_depend_on_chunking_or_repeat():
         assert np.array_equal(alen, ref[0]) and np.array_equal(toks, ref[1]), cv
 
 
+@pytest.mark.parametrize("mode,weights,n", [(C.COS_COMBINE_ENSEMBLE, [0.5, 0.3, 0.2], 3),
+                                            (C.COS_COMBINE_CONTRASTIVE, [0.5, 0.1], 2),
+                                            (C.COS_COMBINE_LOGIT_MIX, [0.8, 0.5, -0.3], 3)])
+def test_shorter_chunks_for_the_last_sequences_of_the_grid(mode, weights, n):
+    """The rows of the last sequences of a streaming launch are cut into more chunks than the others
+    (they run while the GPU drains).  Any number of such sequences and any factor give the oracle's
+    outputs: none, a few, all of them, with one-position windows and at temperature 0 as well."""
+    B, gamma, V = 40, 3, 33000
+    inp = _random_inputs(n, B, gamma, V, "bf16", seed=910 + n, std=2.0)
+    if mode != C.COS_COMBINE_ENSEMBLE:                          # drafts the combination likes, so that lengths vary
+        c = inp["logits"][0, :, :gamma].float() - (0.5 if mode == C.COS_COMBINE_CONTRASTIVE else 0.0) * inp["logits"][1, :, :gamma].float()
+        inp["draft_tokens"][::2] = c.argmax(-1).to(torch.int32)[::2]
+    ref = None
+    try:
+        C.cos_tune_set_chunk_vectors(1024)                      # several chunks per row at this small size
+        for seqs, factor in ((0, 1), (3, 8), (7, 2), (17, 4), (40, 3), (100, 16), (-1, 4)):
+            C.cos_tune_set_tail(seqs, factor)
+            for window in (0, 1):
+                inp["stop_window"] = window
+                alen, toks, _, _ = _check(f"tail {seqs} x{factor}, window {window}, mode {mode}", inp, mode, weights)
+                if ref is None:
+                    ref = (alen, toks)
+                assert np.array_equal(alen, ref[0]) and np.array_equal(toks, ref[1]), (seqs, factor, window)
+            if mode != C.COS_COMBINE_ENSEMBLE:
+                a, t = C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], mode, weights,
+                                    inp["u_accept"], inp["u_resample"], greedy=True)
+                torch.cuda.synchronize()
+                st, wl, wt = O.verify_greedy(W.host_logits(inp["logits"]), O.DTYPE_BF16, inp["draft_tokens"].cpu().numpy(),
+                                             weights, mode=mode)
+                assert st == 0 and np.array_equal(a.cpu().numpy(), wl) and np.array_equal(t.cpu().numpy(), wt), (seqs, factor)
+    finally:
+        C.cos_tune_set_tail(-1, 4)
+        C.cos_tune_set_chunk_vectors(0)
+
+
 def test_workspace_can_be_reused_and_holds_garbage():
     inp = W.generate(W.C2.scaled(B=4), device="cuda")
     ws = C.allocate_workspace(2, 4, W.C2.gamma, W.C2.V, C.COS_DTYPE_BF16, W.C2.mode, "cuda")
