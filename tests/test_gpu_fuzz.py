@@ -147,3 +147,25 @@ def test_random_greedy_configuration(seed):
     assert st == 0
     assert np.array_equal(alen.cpu().numpy(), want_len), desc
     assert np.array_equal(toks.cpu().numpy(), want_toks), desc
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_configuration_with_random_chunking(seed):
+    """The same random cases with the launch shape drawn at random as well: chunk length, and how many
+    of the last sequences of the grid get how much shorter chunks.  Outputs must not depend on it."""
+    inp, mode, weights, desc = _case(15000 + seed)
+    rng = np.random.default_rng(16000 + seed)
+    if mode == C.COS_COMBINE_ENSEMBLE and rng.integers(0, 2):
+        mode, weights = C.COS_COMBINE_LOGIT_MIX, np.abs(rng.normal(0.5, 0.5, desc["n"])).tolist()
+    knobs = (int(rng.choice([0, 256, 512, 1024, 2048])), int(rng.integers(0, desc["B"] + 2)), int(rng.choice([1, 2, 3, 4, 8, 16])))
+    try:
+        C.cos_tune_set_chunk_vectors(knobs[0])
+        C.cos_tune_set_tail(knobs[1], knobs[2])
+        alen, toks, diag = P.run_gpu(inp, mode, weights)
+    finally:
+        C.cos_tune_set_chunk_vectors(0)
+        C.cos_tune_set_tail(-1, 4)
+    rep = P.compare(inp, mode, weights, alen, toks, diag)
+    print(f"[fuzz] chunking {knobs} {desc}: {rep.summary()}", flush=True)
+    assert rep.ok, (desc, knobs, rep.failures[:3])
+    assert rep.excused_accept_ties + rep.excused_cdf_ties <= 1, (desc, rep.summary())
