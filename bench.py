@@ -53,8 +53,8 @@ def main() -> int:
                     help="also compute the acceptance rates of Eq. (7) (an optional output, not the headline step)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on one GPU only (rows of the batch shard without any exchange; "
-              "see DESIGN.md). Re-run with --gpus 1.", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (rows of the batch are independent, so several GPUs "
+              "would each take a slice of the batch without any exchange). Re-run with --gpus 1.", file=sys.stderr)
         return 2
 
     import numpy as np
