@@ -144,6 +144,17 @@ void cos_oracle_softmax(const double *l, int V, double *s) {
   for (x = 0; x < V; ++x) s[x] /= Z;
 }
 
+/* ---- the same at temperature 0 (Sec. 4.1 runs T = 0 and T = 1) ----------- */
+/* softmax(l / T) for T -> 0: all mass on the largest entry, ties to the lowest
+ * index.                                                                     */
+void cos_oracle_softmax_t0(const double *l, int V, double *s) {
+  int x, arg = 0;
+  for (x = 1; x < V; ++x)
+    if (l[x] > l[arg]) arg = x;
+  for (x = 0; x < V; ++x) s[x] = 0.0;
+  s[arg] = 1.0;
+}
+
 /* ---- Eq. (4), n models: r(x) = sum_m w_m s_m(x) ------------------------ */
 /* s is [n][V] row-major.                                                   */
 void cos_oracle_combine_ensemble(const double *s, const double *w, int n, int V,
@@ -402,6 +413,12 @@ static int check_weights(int mode, int n, const double *w) {
  *                  extra token): out_tokens[b][num_drafts[b]] = -1 and the logits of
  *                  that position are not read; sample_mass, cdf edges and flags of
  *                  such a row are 0
+ *   greedy         != 0: temperature 0 for the ensemble of Eq. (4): every model's
+ *                  softmax is one-hot at its largest logit (cos_oracle_softmax_t0),
+ *                  so r = sum_m w_m e_{a_m} has at most n tokens and q = e_{a_pi};
+ *                  every later step (Eq. (6), residual, inverse CDF) is unchanged and
+ *                  still consumes the uniforms; `temperature` is not used.  Ensemble
+ *                  mode only (the logit-level modes: cos_oracle_verify_greedy_mode)
  */
 typedef struct cos_oracle_options {
   double temperature;
@@ -410,6 +427,7 @@ typedef struct cos_oracle_options {
   double *alpha;
   const int32_t *num_drafts;
   int no_bonus;
+  int greedy;
 } cos_oracle_options;
 
 int cos_oracle_verify_ex(const void *logits, int dtype, int n, int B, int gamma,
@@ -430,6 +448,7 @@ int cos_oracle_verify_ex(const void *logits, int dtype, int n, int B, int gamma,
   double *alpha = opt ? opt->alpha : NULL;
   const int32_t *num_drafts = opt ? opt->num_drafts : NULL;
   const int no_bonus = opt ? opt->no_bonus : 0;
+  const int greedy = opt ? opt->greedy : 0;
   if (!logits || !draft_tokens || !proposer_idx || !weights || !u_accept ||
       !u_resample || !accepted_len || !out_tokens)
     return ORACLE_ERR_NULL;
@@ -438,6 +457,7 @@ int cos_oracle_verify_ex(const void *logits, int dtype, int n, int B, int gamma,
     return ORACLE_ERR_DTYPE;
   status = check_weights(mode, n, weights);
   if (status != ORACLE_OK) return status;
+  if (greedy && mode != ORACLE_ENSEMBLE) return ORACLE_ERR_MODE;
   esize = dtype == ORACLE_DTYPE_F32 ? 4 : 2;
   if (opt && !(opt->temperature >= 0.0) ) return ORACLE_ERR_WEIGHTS;
   for (b = 0; b < B; ++b) {
@@ -505,6 +525,10 @@ int cos_oracle_verify_ex(const void *logits, int dtype, int n, int B, int gamma,
           const char *src = (const char *)logits + row * (size_t)V * esize;
           if (verifier_bonus && m != bonus_from) continue; /* not needed, not read */
           cos_oracle_row_to_f64(src, dtype, V, l + (size_t)m * V);
+          if (greedy) {
+            cos_oracle_softmax_t0(l + (size_t)m * V, V, s + (size_t)m * V);
+            continue;
+          }
           if (T != 1.0) cos_oracle_apply_temperature(l + (size_t)m * V, V, T);
           cos_oracle_softmax(l + (size_t)m * V, V, s + (size_t)m * V);
         }

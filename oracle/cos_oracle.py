@@ -40,7 +40,7 @@ def build(force: bool = True) -> str:
 class _Options(ctypes.Structure):
     _fields_ = [("temperature", ctypes.c_double), ("bonus_idx", ctypes.POINTER(ctypes.c_int32)),
                 ("proposer_pos", ctypes.POINTER(ctypes.c_int32)), ("alpha", ctypes.POINTER(ctypes.c_double)),
-                ("num_drafts", ctypes.POINTER(ctypes.c_int32)), ("no_bonus", ctypes.c_int)]
+                ("num_drafts", ctypes.POINTER(ctypes.c_int32)), ("no_bonus", ctypes.c_int), ("greedy", ctypes.c_int)]
 
 
 _lib = None
@@ -57,6 +57,8 @@ def _load():
         ci = ctypes.c_int
         lib.cos_oracle_row_to_f64.argtypes = [vp, ci, ci, dp]
         lib.cos_oracle_row_to_f64.restype = None
+        lib.cos_oracle_softmax_t0.argtypes = [dp, ci, dp]
+        lib.cos_oracle_softmax_t0.restype = None
         lib.cos_oracle_softmax.argtypes = [dp, ci, dp]
         lib.cos_oracle_softmax.restype = None
         lib.cos_oracle_combine_ensemble.argtypes = [dp, dp, ci, ci, dp]
@@ -137,6 +139,14 @@ def softmax(l) -> np.ndarray:
     return s
 
 
+def softmax_t0(l) -> np.ndarray:
+    """softmax(l / T) for T -> 0: one-hot at the largest entry (ties to the lowest index)."""
+    l = _f64(l)
+    s = np.empty_like(l)
+    _load().cos_oracle_softmax_t0(_dp(l), l.shape[0], _dp(s))
+    return s
+
+
 def combine_ensemble(s, w) -> np.ndarray:
     s = _f64(s)
     w = _f64(w)
@@ -200,7 +210,7 @@ class OracleResult:
 def verify(logits: np.ndarray, dtype: int, draft_tokens, proposer_idx, mode: int, weights,
            u_accept, u_resample, all_positions: bool = False, num_threads: int = 0,
            temperature: float = 1.0, bonus_idx=None, proposer_pos=None,
-           want_alpha: bool = False, num_drafts=None, no_bonus: bool = False) -> OracleResult:
+           want_alpha: bool = False, num_drafts=None, no_bonus: bool = False, greedy: bool = False) -> OracleResult:
     """Run ``cos_oracle_verify_ex`` (the base step when no extension is given).
 
     ``logits`` is a host array of shape [n][B][gamma+1][V]: float32, or uint16
@@ -242,6 +252,7 @@ def verify(logits: np.ndarray, dtype: int, draft_tokens, proposer_idx, mode: int
         keep.append(nd)
         opt.num_drafts = _ip(nd)
     opt.no_bonus = int(bool(no_bonus))
+    opt.greedy = int(bool(greedy))     # temperature 0, ensemble mode: every softmax one-hot at its largest logit
     res.status = _load().cos_oracle_verify_ex(
         logits.ctypes.data_as(ctypes.c_void_p), dtype, n, B, gamma, V,
         _ip(draft_tokens), _ip(proposer_idx), mode, _dp(weights), _dp(u_accept), _dp(u_resample),

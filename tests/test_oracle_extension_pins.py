@@ -518,3 +518,81 @@ def test_greedy_logit_mix_brute_force_with_verifier_bonus_ragged_rows_and_no_bon
     assert O.verify_greedy(logits, O.DTYPE_F32, drafts, beta, mode=O.ENSEMBLE)[0] == -4
     assert O.verify_greedy(logits, O.DTYPE_F32, drafts, [0.5, 0.1], mode=O.CONTRASTIVE)[0] == -4   # contrastive needs n == 2
     assert O.verify_greedy(logits, O.DTYPE_F32, drafts, beta, bonus_idx=np.full(B, n), mode=O.LOGIT_MIX)[0] == -2
+
+
+# ---- temperature 0 (greedy), ensemble ---------------------------------------------
+
+def test_softmax_t0_is_the_limit_of_the_softmax():
+    rng = _rng(50)
+    for V in (1, 5, 300):
+        l = rng.standard_normal(V) * 3
+        s = O.softmax_t0(l)
+        assert s.sum() == 1.0 and s[np.argmax(l)] == 1.0
+        assert np.array_equal(s, np.round(O.softmax(l / 1e-9)))          # numerically one-hot already at T = 1e-9
+    assert np.array_equal(O.softmax_t0(np.array([1.0, 4.0, 4.0, -np.inf])), [0.0, 1.0, 0.0, 0.0])   # tie: lowest index
+
+
+def test_greedy_ensemble_is_the_small_temperature_limit_of_the_step():
+    """The whole step at temperature 0 equals the step at T = 1e-9 with the same uniforms (the softmaxes are
+    one-hot there already): a pin against the sampler that is pinned elsewhere, with per-position proposers,
+    verifier bonus tokens, ragged rows and the no-bonus variant."""
+    rng = _rng(51)
+    n, B, gamma, V = 3, 400, 3, 12                         # a small vocabulary: the models often agree
+    w = [0.5, 0.3, 0.2]
+    logits = (rng.standard_normal((n, B, gamma + 1, V)) * 2).astype(np.float32)
+    logits[1, ::3] = logits[0, ::3]                         # ... and sometimes fully
+    proposer = rng.integers(0, n, B).astype(np.int32)
+    ppos = rng.integers(0, n, (B, gamma)).astype(np.int32)
+    top = logits.argmax(-1)                                 # [n][B][gamma+1]
+    drafts = rng.integers(0, V, (B, gamma)).astype(np.int32)
+    for b in range(B):                                      # drafts as the paper has them: the proposer's own token
+        for j in range(gamma):
+            if rng.random() < 0.8:
+                drafts[b, j] = top[ppos[b, j], b, j]
+    ua, ur = rng.random((B, gamma)), rng.random(B)
+    bonus = rng.integers(-1, n, B).astype(np.int32)
+    nd = rng.integers(0, gamma + 1, B).astype(np.int32)
+    for kw in ({}, {"proposer_pos": ppos}, {"bonus_idx": bonus}, {"num_drafts": nd}, {"num_drafts": nd, "no_bonus": True},
+               {"proposer_pos": ppos, "bonus_idx": bonus, "num_drafts": nd}):
+        g = O.verify(logits, O.DTYPE_F32, drafts, proposer, O.ENSEMBLE, w, ua, ur, greedy=True, all_positions=True, **kw)
+        lim = O.verify(logits, O.DTYPE_F32, drafts, proposer, O.ENSEMBLE, w, ua, ur, temperature=1e-9, all_positions=True, **kw)
+        assert g.status == 0 and lim.status == 0
+        assert np.array_equal(g.accepted_len, lim.accepted_len) and np.array_equal(g.out_tokens, lim.out_tokens), kw
+        assert np.array_equal(g.flags, lim.flags)
+        assert len(set(g.accepted_len.tolist())) >= 3
+
+
+def test_greedy_ensemble_by_cases():
+    """Eq. (6) at temperature 0 by hand: q is one-hot at the proposer's token a_pi and r(x) is the weight of the
+    models whose token is x.  A draft equal to a_pi is accepted with probability r(a_pi); any other draft is
+    accepted iff some model votes for it; after a rejection the token is one of the other models' tokens, in
+    proportion to their weights (by inverse CDF in token order); when every model agrees with the proposer a
+    foreign draft is rejected and replaced by that token (residual without mass: the fall-back to r)."""
+    V, gamma = 10, 1
+    w = [0.5, 0.3, 0.2]
+
+    def run(tokens, d, pi, u, ur=0.5):
+        logits = np.zeros((3, 1, gamma + 1, V), dtype=np.float32)
+        for m, t in enumerate(tokens):
+            logits[m, 0, :, t] = 5.0
+        return O.verify(logits, O.DTYPE_F32, [[d]], [pi], O.ENSEMBLE, w, [[u]], [ur], greedy=True)
+
+    res = run((4, 4, 7), d=4, pi=0, u=0.79)                 # r(4) = 0.8
+    assert res.accepted_len[0] == 1 and res.r_at_draft[0, 0] == 0.8 and res.q_at_draft[0, 0] == 1.0
+    res = run((4, 4, 7), d=4, pi=0, u=0.81)                 # rejected: the residual is all on token 7
+    assert res.accepted_len[0] == 0 and res.out_tokens[0, 0] == 7 and abs(res.sample_mass[0] - 0.2) < 1e-15
+    res = run((4, 4, 7), d=7, pi=0, u=0.999)                # q(7) = 0 < r(7): always accepted
+    assert res.accepted_len[0] == 1 and np.isinf(res.ratio[0, 0])
+    res = run((4, 4, 7), d=2, pi=0, u=0.0)                  # nobody votes for 2: rejected even at u = 0
+    assert res.accepted_len[0] == 0 and res.out_tokens[0, 0] == 7
+    res = run((4, 6, 2), d=4, pi=0, u=0.6, ur=0.39)         # residual: token 2 (0.2) before token 6 (0.3): u*F = 0.195
+    assert res.accepted_len[0] == 0 and res.out_tokens[0, 0] == 2
+    res = run((4, 6, 2), d=4, pi=0, u=0.6, ur=0.41)         # 0.205 > 0.2: token 6
+    assert res.out_tokens[0, 0] == 6
+    res = run((4, 4, 4), d=9, pi=1, u=0.0)                  # all agree; a foreign draft: r = q, fall back to r
+    assert res.accepted_len[0] == 0 and res.out_tokens[0, 0] == 4 and res.flags[0] & O.FLAG_RESIDUAL_FALLBACK
+    res = run((4, 6, 2), d=4, pi=0, u=0.1, ur=0.75)         # accepted; bonus from r in token order: 2 (.2), 4 (.5), 6 (.3)
+    assert res.accepted_len[0] == 1 and res.out_tokens[0, 1] == 6
+    # only the ensemble is combined at the probability level; the logit-level modes have their own step
+    lg = np.zeros((2, 1, 2, V), dtype=np.float32)
+    assert O.verify(lg, O.DTYPE_F32, [[1]], [0], O.CONTRASTIVE, [0.5, 0.1], [[0.5]], [0.5], greedy=True).status == -4
