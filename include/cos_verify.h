@@ -159,18 +159,24 @@ cos_status_t cos_verify(const void *logits, cos_dtype_t dt, int n, int B, int ga
  *               are identical; diag.r_at_draft / q_at_draft are written only
  *               for positions that were read; alpha must be NULL
  *               (COS_ERR_UNSUPPORTED).  Fewer bytes, more launches.
- * greedy        non-zero: temperature 0 (the T = 0 runs of Sec. 4.1), logit-level
- *               modes only (contrastive, logit mix).  Every softmax is one-hot,
- *               so r of Eq. (5) is one-hot at a_j = argmax over the mask of
- *               l_0 - mu l_1 (ties to the lowest index; the mask stays the
- *               temperature-1 one, l_0 - max l_0 >= ln alpha_cd), and r of the
- *               logit mix at a_j = argmax of sum_m beta_m l_m: draft d_j is
- *               accepted iff d_j == a_j, the token at the first mismatch -- or
- *               the bonus token -- is a_j (with bonus_idx[b] = v >= 0: the argmax
- *               of l_v alone).  u_accept, u_resample, proposer_idx and temperature
- *               are not used; diag is not written.  Bit-exact against a float64
- *               reference.  Not combinable with alpha, proposer_pos or
- *               stop_window; ensemble mode: COS_ERR_UNSUPPORTED.
+ * greedy        non-zero: temperature 0 (the T = 0 runs of Sec. 4.1): every softmax
+ *               is one-hot at its largest entry, ties to the lowest index.
+ *               Logit-level modes: r of Eq. (5) is one-hot at a_j = argmax over
+ *               the mask of l_0 - mu l_1 (the mask stays the temperature-1 one,
+ *               l_0 - max l_0 >= ln alpha_cd), r of the logit mix at a_j = argmax
+ *               of sum_m beta_m l_m: draft d_j is accepted iff d_j == a_j, the
+ *               token at the first mismatch -- or the bonus token -- is a_j (with
+ *               bonus_idx[b] = v >= 0: the argmax of l_v alone); u_accept,
+ *               u_resample, proposer_idx and temperature are not used.
+ *               Ensemble mode: r = sum_m w_m e_{a_m} over the models' own tokens
+ *               a_m = argmax l_m and q = e_{a_pi}; Eq. (6), the residual and the
+ *               draw are taken as always, on those at most n tokens, with
+ *               u_accept and u_resample (a draft equal to the proposer's token
+ *               is accepted with probability r(d); another model's token
+ *               always; any other token never); proposer_pos may be given.
+ *               diag is not written.  Bit-exact against a float64 reference.
+ *               Not combinable with alpha or stop_window, nor (logit-level
+ *               modes) with proposer_pos.
  * num_drafts    DEVICE [B] int32 or NULL.  Row b carries only num_drafts[b]
  *               drafts, in [0, gamma] (caller's contract): the rows of a batch,
  *               and the windows Alg. 2 verifies, differ in length.  Position

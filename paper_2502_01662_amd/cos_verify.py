@@ -188,7 +188,7 @@ def cos_verify(logits: torch.Tensor, draft_tokens: torch.Tensor, proposer_idx: t
     Extensions (``cos_verify_ex``): ``temperature``, ``bonus_idx`` [B] int32,
     ``proposer_pos`` [B][gamma] int32, ``alpha`` [B][gamma] float64 (output: acceptance rates),
     ``stop_window`` (positions per streaming launch; later positions of a rejected sequence are not read),
-    ``greedy`` (temperature 0, contrastive mode or logit mix), ``num_drafts`` [B] int32 (drafts per row, each in
+    ``greedy`` (temperature 0), ``num_drafts`` [B] int32 (drafts per row, each in
     [0, gamma]), ``no_bonus`` (no extra token when every draft of a row is accepted), ``refine_residual``
     (residuals of little mass are evaluated once more in their difference form).
     """

@@ -109,7 +109,7 @@ struct Params {
 struct LaunchPlan {
   int mode;         // kEns, kCd or kMix
   int window;       // positions per streaming launch
-  int greedy;       // temperature 0 (logit-level modes): one argmax kernel instead
+  int greedy;       // temperature 0: one argmax kernel instead
   int aligned;      // every row starts on a 16-byte boundary and V is a multiple of the vector width
   int counters;     // arrival counters (ints, with their stride) the fill kernel clears
   size_t lds;       // dynamic LDS of the sampling kernel (one double per tile)

@@ -111,18 +111,19 @@ cos_status_t launch_all(Params p, int mode, int window, size_t lds, hipStream_t 
                         : launch_acceptance_rate<T, ALIGNED, kCd>(p, st);
 }
 
-// Temperature 0, logit-level modes: the expert maxima (contrastive with a mask only), then one
-// argmax kernel.
+// Temperature 0: the expert maxima (contrastive with a mask only), then one argmax kernel.
 template <typename T, bool ALIGNED>
 cos_status_t launch_greedy(Params p, const LaunchPlan& lp) {
   p.j0 = 0;
   p.nj = p.gamma + 1;
   p.win = 0;
-  const long blocks = stream_blocks(p, p.gamma + 1);
+  const long blocks = stream_blocks(p, (p.gamma + 1) * (lp.mode == kEns ? p.n : 1));
   if (blocks <= 0 || blocks > 0x7fffffffL) return COS_ERR_SHAPE;
   const dim3 grid((unsigned)blocks), block(kThreads);
   if (lp.ev_start) (void)hipEventRecord(lp.ev_start, lp.stream);
-  if (lp.mode == kMix) {
+  if (lp.mode == kEns) {
+    hipLaunchKernelGGL((greedy_ensemble_kernel<T, ALIGNED>), grid, block, 0, lp.stream, p);
+  } else if (lp.mode == kMix) {
     switch (p.n) {
       case 1: hipLaunchKernelGGL((greedy_mix_kernel<T, ALIGNED, 1>), grid, block, 0, lp.stream, p); break;
       case 2: hipLaunchKernelGGL((greedy_mix_kernel<T, ALIGNED, 2>), grid, block, 0, lp.stream, p); break;

@@ -790,13 +790,11 @@ __device__ __forceinline__ bool arg_plain_ok(const ArgBest& best, double val) {
   return val > -INFINITY || (best.idx < 0 && val == -INFINITY);
 }
 
-// Lanes -> wavefront -> workgroup -> the chunk's partial, then the arrival.  The
-// workgroup that completes the sequence takes the argmax of every position, finds
-// the first mismatch and writes the outputs.
-__device__ __forceinline__ void greedy_finish(const Params& p, int b, int gb, ArgBest best, Partial* out,
-                                              int per_b, ArgBest* wbest, int* s_flag, int* s_arg) {
+// Lanes -> wavefront -> workgroup -> the chunk's partial, then the arrival: true in the workgroup
+// that completes the sequence.
+__device__ __forceinline__ bool greedy_arrive(const Params& p, int b, ArgBest best, Partial* out, int per_b,
+                                              ArgBest* wbest, int* s_flag) {
   const int tid = threadIdx.x;
-  const int g1 = p.gamma + 1;
 #pragma unroll
   for (int d = 32; d >= 1; d >>= 1) {
     const double ov = __shfl_xor(best.val, d, 64);
@@ -812,17 +810,25 @@ __device__ __forceinline__ void greedy_finish(const Params& p, int b, int gb, Ar
     store_agent(&out->o, bb.idx);
     wait_stores();
   }
-  if (!arrive_last(p.counters + (size_t)b * kCtrStride, per_b, s_flag)) return;
+  return arrive_last(p.counters + (size_t)b * kCtrStride, per_b, s_flag);
+}
 
-  if (tid < g1) {
-    const Partial* pp = p.partials + (((size_t)b * g1 + tid) * p.nstat) * p.S;
-    const int Sb = splits_of(p, b);
-    ArgBest bb;
-    bb.val = 0.0;
-    bb.idx = -1;
-    for (int i = 0; i < Sb; ++i) arg_better(bb, load_agent(&pp[i].Z), load_agent(&pp[i].o));
-    s_arg[tid] = bb.idx;
-  }
+// The argmax of statistic `stat` from its chunk partials (read by one thread).
+__device__ __forceinline__ int greedy_combine(const Params& p, int b, int stat) {
+  const Partial* pp = p.partials + ((size_t)b * (p.gamma + 1) * p.nstat + stat) * p.S;
+  const int Sb = splits_of(p, b);
+  ArgBest bb;
+  bb.val = 0.0;
+  bb.idx = -1;
+  for (int i = 0; i < Sb; ++i) arg_better(bb, load_agent(&pp[i].Z), load_agent(&pp[i].o));
+  return bb.idx;
+}
+
+// r is one-hot at the argmax of every position: first mismatch, outputs.
+__device__ __forceinline__ void greedy_decide_one_hot(const Params& p, int b, int gb, int* s_arg) {
+  const int tid = threadIdx.x;
+  const int g1 = p.gamma + 1;
+  if (tid < g1) s_arg[tid] = greedy_combine(p, b, tid * p.nstat);
   __syncthreads();
   int jstar = gb;
   for (int jj = gb - 1; jj >= 0; --jj)
@@ -832,6 +838,11 @@ __device__ __forceinline__ void greedy_finish(const Params& p, int b, int gb, Ar
   if (tid < g1)
     p.out_tokens[(size_t)b * g1 + tid] =
         tid < jstar ? p.draft[(size_t)b * p.gamma + tid] : ((tid == jstar && !skip) ? s_arg[jstar] : -1);
+}
+
+__device__ __forceinline__ void greedy_finish(const Params& p, int b, int gb, ArgBest best, Partial* out,
+                                              int per_b, ArgBest* wbest, int* s_flag, int* s_arg) {
+  if (greedy_arrive(p, b, best, out, per_b, wbest, s_flag)) greedy_decide_one_hot(p, b, gb, s_arg);
 }
 
 template <typename T, bool ALIGNED>
@@ -976,6 +987,160 @@ __global__ void __launch_bounds__(kThreads) greedy_mix_kernel(Params p) {
   }
   Partial* out = p.partials + (((size_t)b * g1 + j) * p.nstat) * p.S + s;
   greedy_finish(p, b, gb, best, out, per_b, wbest, &s_flag, s_arg);
+}
+
+// ---------------------------------------------------------------------------
+// Temperature 0, ensemble.  Every model's softmax is one-hot at its largest logit
+// a_m (ties to the lowest index), so r = sum_m w_m e_{a_m} (Eq. (4)) lives on at
+// most n tokens and q = e_{a_pi}.  One streaming argmax per row; the workgroup that
+// completes the sequence then takes Eq. (6), the first rejection and the draw in
+// float64 on those few tokens, with exactly the operations a float64 reference
+// makes on the full vocabulary (sums in model order, then in token order; terms
+// that are zero there are left out here), so the outputs are bit-exact.
+// ---------------------------------------------------------------------------
+
+// r(x) = sum of the weights of the models whose token is x, in model order.
+__device__ __forceinline__ double t0_mass(const Params& p, const int* a, int x) {
+  double r = 0.0;
+  for (int m = 0; m < p.n; ++m)
+    if (a[m] == x) r += p.w[m];
+  return r;
+}
+
+__device__ void greedy_decide_ensemble(const Params& p, int b, int gb, int* s_arg, int* s_accept) {
+  const int tid = threadIdx.x;
+  const int g1 = p.gamma + 1, n = p.n;
+  for (int i = tid; i < g1 * n; i += kThreads) s_arg[i] = greedy_combine(p, b, i);  // (position, model)
+  __syncthreads();
+  if (tid < gb) {  // Eq. (6) at draft position tid
+    const size_t k = (size_t)b * p.gamma + tid;
+    const int d = p.draft[k];
+    const int pi = p.proposer_pos ? p.proposer_pos[k] : p.proposer[b];
+    const int* a = s_arg + tid * n;
+    const double rd = t0_mass(p, a, d);
+    const double qd = (a[pi] == d) ? 1.0 : 0.0;
+    double ratio;
+    if (!(rd > 0.0))
+      ratio = 0.0;
+    else if (!(qd > 0.0))
+      ratio = INFINITY;
+    else
+      ratio = rd / qd;
+    const double bound = ratio < 1.0 ? ratio : 1.0;
+    s_accept[tid] = p.u_accept[k] < bound;
+  }
+  __syncthreads();
+  int jstar = gb;
+  for (int jj = gb - 1; jj >= 0; --jj)
+    if (!s_accept[jj]) jstar = jj;
+  const bool skip = p.no_bonus && jstar == gb;  // every draft accepted, no extra token
+  if (tid == 0) p.accepted_len[b] = jstar;
+  if (tid < g1 && (tid != jstar || skip))
+    p.out_tokens[(size_t)b * g1 + tid] = tid < jstar ? p.draft[(size_t)b * p.gamma + tid] : -1;
+  if (tid != 0 || skip) return;
+
+  // the draw at jstar: from norm(max(0, r - q)) after a rejection, else from r (or from the
+  // verifier's own one-hot softmax), by inverse CDF in ascending token order
+  const int* a = s_arg + jstar * n;
+  const bool residual = jstar < gb;
+  const int v = (!residual && p.bonus_idx) ? p.bonus_idx[b] : -1;
+  int token = -1;
+  if (v >= 0) {
+    token = a[v];
+  } else {
+    const int pi = (residual && p.proposer_pos) ? p.proposer_pos[(size_t)b * p.gamma + jstar] : p.proposer[b];
+    int tok[COS_MAX_MODELS];
+    double rr[COS_MAX_MODELS], f[COS_MAX_MODELS];
+    int cnt = 0;
+    for (int m = 0; m < n; ++m) {  // the distinct tokens, ascending
+      const int x = a[m];
+      bool seen = x < 0;
+      for (int i = 0; i < cnt; ++i) seen = seen || tok[i] == x;
+      if (seen) continue;
+      int at = cnt++;
+      while (at > 0 && tok[at - 1] > x) {
+        tok[at] = tok[at - 1];
+        --at;
+      }
+      tok[at] = x;
+    }
+    double F = 0.0;
+    for (int i = 0; i < cnt; ++i) {
+      rr[i] = t0_mass(p, a, tok[i]);
+      const double val = residual ? rr[i] - ((tok[i] == a[pi]) ? 1.0 : 0.0) : rr[i];
+      f[i] = val > 0.0 ? val : 0.0;
+      F += f[i];
+    }
+    if (!(F > 0.0) || !(F < INFINITY)) {  // r == q although a draft was rejected: draw from r
+      F = 0.0;
+      for (int i = 0; i < cnt; ++i) {
+        f[i] = rr[i] > 0.0 ? rr[i] : 0.0;
+        F += f[i];
+      }
+    }
+    const double t = p.u_resample[b] * F;
+    double cum = 0.0;
+    int last = -1;
+    for (int i = 0; i < cnt && token < 0; ++i) {
+      cum += f[i];
+      if (f[i] > 0.0) last = tok[i];
+      if (cum > t) token = tok[i];
+    }
+    if (token < 0) token = last;  // rounding left no prefix above t: the last token with mass
+  }
+  p.out_tokens[(size_t)b * g1 + jstar] = token;
+}
+
+// Workgroup index -> (b, j, m, s): the argmax of one chunk of one row.
+template <typename T, bool ALIGNED>
+__global__ void __launch_bounds__(kThreads) greedy_ensemble_kernel(Params p) {
+  constexpr int N = VecOf<T>::N;
+  constexpr int U = kUnroll;
+  constexpr int kStep = kThreads * U;
+  __shared__ ArgBest wbest[kWaves];
+  __shared__ int s_flag;
+  __shared__ int s_arg[kMaxStatsPerSeq];
+  __shared__ int s_accept[COS_MAX_GAMMA + 1];
+
+  const int g1 = p.gamma + 1;
+  const Place pl = place_of(p, g1 * p.n);
+  const int b = pl.b;
+  int rem = pl.rem;
+  const int j = rem / (p.n * pl.S);
+  rem -= j * p.n * pl.S;
+  const int m = rem / pl.S;
+  const int s = rem - m * pl.S;
+  const int tid = threadIdx.x;
+  const int gb = drafts_of(p, b);
+  // a verifier bonus needs that model's row only; rows of positions never read are skipped
+  const int only = (p.bonus_idx && j == gb) ? p.bonus_idx[b] : -1;
+  const bool unread = position_unread(p, gb, j) || (only >= 0 && m != only);
+
+  const T* row = row_ptr<T>(p, m, b, j);
+  const int v0 = s * pl.cv;
+  const int v1 = min(v0 + pl.cv, p.nvec);
+  ArgBest best;
+  best.val = 0.0;
+  best.idx = -1;
+  for (int base = v0; base < v1 && !unread; base += kStep) {
+    float x[U][N];
+    if (base + kStep <= v1)
+      load_group<T, ALIGNED, false, U>(row, base, v1, p.V, x);
+    else
+      load_group<T, ALIGNED, true, U>(row, base, v1, p.V, x);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int first = (base + u * kThreads + tid) * N;  // element index of x[u][0]
+      const bool inside = base + u * kThreads + tid < v1;
+#pragma unroll
+      for (int k = 0; k < N; ++k) {
+        const double val = (double)x[u][k];
+        arg_take(best, val, first + k, arg_plain_ok(best, val) && inside && first + k < p.V);
+      }
+    }
+  }
+  Partial* out = p.partials + (((size_t)b * g1 + j) * p.n + m) * p.S + s;
+  if (greedy_arrive(p, b, best, out, pl.per_b, wbest, &s_flag)) greedy_decide_ensemble(p, b, gb, s_arg, s_accept);
 }
 
 }  // namespace

@@ -263,10 +263,8 @@ cos_status_t cos_verify_ex(const void* logits, cos_dtype_t dt, int n, int B, int
     if (options->temperature > 0.0) temperature = options->temperature;
     if (options->stop_window < 0) return COS_ERR_SHAPE;
     if (options->greedy) {
-      // temperature 0: built for the logit-level modes (the paper's T = 0 runs are contrastive), whole
-      // step in one launch
-      if ((combine_mode != COS_COMBINE_CONTRASTIVE && combine_mode != COS_COMBINE_LOGIT_MIX) || options->alpha ||
-          options->proposer_pos ||
+      // temperature 0: the whole step in one launch; only the ensemble's step looks at the proposers
+      if (options->alpha || (options->proposer_pos && combine_mode != COS_COMBINE_ENSEMBLE) ||
           (options->stop_window > 0 && options->stop_window <= gamma))
         return COS_ERR_UNSUPPORTED;
     }

@@ -114,7 +114,9 @@ def test_option_validation_needs_no_gpu():
     assert _call_ex(C.CosOptions(size, -1.0, None, None, None, 0, 0, None, 0)) == -5         # temperature < 0
     assert _call_ex(C.CosOptions(size, float("nan"), None, None, None, 0, 0, None, 0)) == -5
     assert _call_ex(C.CosOptions(size, 0.0, None, None, None, -1, 0, None, 0)) == -2         # stop_window < 0
-    assert _call_ex(C.CosOptions(size, 0.0, None, None, None, 0, 1, None, 0)) == -9          # greedy ensemble
+    assert _call_ex(C.CosOptions(size, 0.0, None, None, None, 0, 1, None, 0)) == -6          # greedy ensemble: built
+    assert _call_ex(C.CosOptions(size, 0.0, None, 0x1000, None, 0, 1, None, 0)) == -6        # ... with per-position proposers
+    assert _call_ex(C.CosOptions(size, 0.0, None, None, 0x1000, 0, 1, None, 0)) == -9        # ... but not with acceptance rates
     assert _call_ex(C.CosOptions(size, 0.0, None, None, None, 0, 1, None, 0), mode=2) == -6  # greedy logit mix: built
     assert _call_ex(C.CosOptions(size, 0.0, None, 0x1000, None, 0, 1, None, 0), mode=2) == -9  # ... not per-position proposers
     assert _call_ex(C.CosOptions(size, 0.0, None, None, None, 0, 1, None, 0), mode=1, weights=(0.5, 0.1)) == -6

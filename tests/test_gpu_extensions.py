@@ -4,6 +4,7 @@ import numpy as np
 import pytest
 import torch
 
+from oracle import cos_oracle as O
 from paper_2502_01662_amd import cos_verify as C
 from paper_2502_01662_amd import workloads as W
 from tests import parity as P
@@ -264,9 +265,10 @@ def test_greedy_ties_go_to_the_lowest_index_and_unsupported_combinations():
     st, want_len, want_toks = O.verify_greedy(W.host_logits(inp["logits"]), O.DTYPE_BF16,
                                               inp["draft_tokens"].cpu().numpy(), [0.5, 0.0])
     assert np.array_equal(toks.cpu().numpy(), want_toks)
-    with pytest.raises(C.CosVerifyError):                    # greedy ensembles are not built
-        C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], C.COS_COMBINE_ENSEMBLE, [0.5, 0.5],
-                     inp["u_accept"], inp["u_resample"], greedy=True)
+    with pytest.raises(C.CosVerifyError):                    # the one-hot r of Eq. (5) has no use for per-position proposers
+        C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], C.COS_COMBINE_CONTRASTIVE, [0.5, 0.0],
+                     inp["u_accept"], inp["u_resample"], greedy=True,
+                     proposer_pos=torch.zeros((B, gamma), dtype=torch.int32, device="cuda"))
     with pytest.raises(C.CosVerifyError):
         C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], C.COS_COMBINE_CONTRASTIVE, [0.5, 0.0],
                      inp["u_accept"], inp["u_resample"], greedy=True, stop_window=1)
@@ -444,3 +446,79 @@ def test_refine_residual_changes_nothing_when_the_residual_has_mass():
                               inp["u_accept"], inp["u_resample"], refine_residual=True)
     torch.cuda.synchronize()
     assert np.array_equal(a[0], alen.cpu().numpy()) and np.array_equal(a[1], toks.cpu().numpy())
+
+
+# ---------------------------------------------------------------------------
+# temperature 0 (greedy), ensemble: r lives on the models' own tokens; bit-exact, nothing excused
+# ---------------------------------------------------------------------------
+
+def _greedy_ensemble_inputs(n, B, gamma, V, dtype, seed):
+    """Models that often agree (a shared base plus a little noise); drafts are mostly the proposer's own
+    token, sometimes another model's, sometimes a token nobody votes for."""
+    g = torch.Generator().manual_seed(seed)
+    tdt = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[dtype]
+    base = torch.randn((1, B, gamma + 1, V), generator=g, dtype=torch.float64) * 2.0
+    logits = (base + 0.7 * torch.randn((n, B, gamma + 1, V), generator=g, dtype=torch.float64)).to(tdt)
+    inp = {"logits": logits.cuda(),
+           "proposer_idx": torch.randint(0, n, (B,), generator=g, dtype=torch.int32).cuda(),
+           "u_accept": torch.rand((B, gamma), generator=g, dtype=torch.float64).cuda(),
+           "u_resample": torch.rand((B,), generator=g, dtype=torch.float64).cuda()}
+    ppos = torch.randint(0, n, (B, gamma), generator=g, dtype=torch.int32)
+    top = logits.double().argmax(-1)                              # [n][B][gamma+1], first maximum
+    kind = torch.randint(0, 10, (B, gamma), generator=g)
+    drafts = torch.randint(0, V, (B, gamma), generator=g, dtype=torch.int32)
+    for b in range(B):
+        for j in range(gamma):
+            if kind[b, j] < 7:
+                drafts[b, j] = top[ppos[b, j], b, j]              # the proposer's token
+            elif kind[b, j] < 9:
+                drafts[b, j] = top[(ppos[b, j] + 1) % n, b, j]    # another model's token
+    inp["draft_tokens"] = drafts.cuda()
+    inp["proposer_pos"] = ppos.cuda()
+    return inp
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32", "f16"])
+@pytest.mark.parametrize("n,B,gamma,V", [(1, 6, 2, 9), (2, 12, 3, 1000), (3, 9, 2, 4099), (4, 10, 4, 33000), (5, 7, 3, 70001),
+                                         (8, 5, 2, 20000), (2, 16, 5, 128256)])
+def test_greedy_ensemble_is_bit_exact(dtype, n, B, gamma, V):
+    inp = _greedy_ensemble_inputs(n, B, gamma, V, dtype, seed=31 * V + n)
+    w = np.random.default_rng(V + n).dirichlet(np.ones(n)).tolist()
+    host, odt = W.host_logits(inp["logits"]), P.oracle_dtype(inp["logits"])
+    common = (inp["draft_tokens"].cpu().numpy(), inp["proposer_idx"].cpu().numpy(), C.COS_COMBINE_ENSEMBLE, w,
+              inp["u_accept"].cpu().numpy(), inp["u_resample"].cpu().numpy())
+    bonus = torch.tensor([(b % (n + 1)) - 1 for b in range(B)], dtype=torch.int32).cuda()
+    lens = set()
+    for kw in ({}, {"proposer_pos": inp["proposer_pos"]}, {"bonus_idx": bonus}, {"proposer_pos": inp["proposer_pos"], "bonus_idx": bonus}):
+        alen, toks = C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], C.COS_COMBINE_ENSEMBLE, w,
+                                  inp["u_accept"], inp["u_resample"], greedy=True, **kw)
+        torch.cuda.synchronize()
+        ora = O.verify(host, odt, *common, greedy=True, **{k: v.cpu().numpy() for k, v in kw.items()})
+        assert ora.status == 0
+        assert np.array_equal(alen.cpu().numpy(), ora.accepted_len), kw.keys()
+        assert np.array_equal(toks.cpu().numpy(), ora.out_tokens), kw.keys()
+        lens |= set(ora.accepted_len.tolist())
+    assert n == 1 or len(lens) >= min(3, gamma + 1)
+
+
+@pytest.mark.parametrize("no_bonus", [False, True])
+def test_greedy_ensemble_ragged_rows_odd_vocabulary_agreeing_models_and_zero_weights(no_bonus):
+    n, B, gamma, V = 3, 24, 4, 33001
+    inp = _greedy_ensemble_inputs(n, B, gamma, V, "bf16", seed=99)
+    inp["logits"][1, ::2] = inp["logits"][0, ::2]              # two models agree on every other row
+    inp["logits"][2, ::4] = inp["logits"][0, ::4]              # ... all three on every fourth: r == q, the fall-back
+    w = [0.7, 0.3, 0.0]                                         # a model without weight still proposes
+    nd = np.array([(b * 2) % (gamma + 1) for b in range(B)], dtype=np.int32)
+    for b in range(B):
+        inp["logits"][:, b, int(nd[b]) + (0 if no_bonus else 1):] = float("nan")
+    host = W.host_logits(inp["logits"])
+    alen, toks = C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], C.COS_COMBINE_ENSEMBLE, w,
+                              inp["u_accept"], inp["u_resample"], greedy=True, proposer_pos=inp["proposer_pos"],
+                              num_drafts=torch.from_numpy(nd).cuda(), no_bonus=no_bonus)
+    torch.cuda.synchronize()
+    ora = O.verify(host, O.DTYPE_BF16, inp["draft_tokens"].cpu().numpy(), inp["proposer_idx"].cpu().numpy(),
+                   C.COS_COMBINE_ENSEMBLE, w, inp["u_accept"].cpu().numpy(), inp["u_resample"].cpu().numpy(), greedy=True,
+                   proposer_pos=inp["proposer_pos"].cpu().numpy(), num_drafts=nd, no_bonus=no_bonus)
+    assert ora.status == 0
+    assert np.array_equal(alen.cpu().numpy(), ora.accepted_len) and np.array_equal(toks.cpu().numpy(), ora.out_tokens)
+    assert (ora.flags & O.FLAG_RESIDUAL_FALLBACK).any()         # the degenerate case did occur

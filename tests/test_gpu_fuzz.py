@@ -108,15 +108,15 @@ def test_random_float16_configuration(seed):
     assert rep.excused_accept_ties + rep.excused_cdf_ties <= 1, (desc, rep.summary())
 
 
-@pytest.mark.parametrize("seed", range(40))
+@pytest.mark.parametrize("seed", range(60))
 def test_random_greedy_configuration(seed):
-    """Temperature 0 of the logit-level modes on the same random shapes: bit-exact, nothing excused."""
+    """Temperature 0 on the same random shapes, every combine mode: bit-exact, nothing excused."""
     from oracle import cos_oracle as O
     from paper_2502_01662_amd import workloads as W
     inp, mode, weights, desc = _case(11000 + seed)
     rng = np.random.default_rng(12000 + seed)
     n, B, gamma, V = desc["n"], desc["B"], desc["gamma"], desc["V"]
-    if mode != C.COS_COMBINE_CONTRASTIVE:                         # an ensemble case: take its shape for a logit mix
+    if mode == C.COS_COMBINE_ENSEMBLE and seed % 2:               # every other ensemble case: its shape for a logit mix
         mode = C.COS_COMBINE_LOGIT_MIX
         weights = rng.normal(0.0, 0.8, n)
         weights[rng.integers(0, n)] = 1.0
@@ -125,23 +125,35 @@ def test_random_greedy_configuration(seed):
         weights = weights.tolist()
     host, odt = W.host_logits(inp["logits"]), P.oracle_dtype(inp["logits"])
     drafts = inp["draft_tokens"].cpu().numpy().copy()
-    for b in range(B):                                            # an accepted prefix of random length
+    ppos = inp.get("proposer_pos")
+    prop = inp["proposer_idx"].cpu().numpy()
+    for b in range(B):                                            # a likely prefix of random length
         for j in range(int(rng.integers(0, gamma + 1))):
             rows = [O.row_to_f64(host[m, b, j], odt) for m in range(n)]
             if np.isnan(rows[0]).any():
                 break                                             # poisoned: beyond this row's drafts
-            drafts[b, j] = (O.argmax_contrastive(rows[0], rows[1], weights[0], weights[1])
-                            if mode == C.COS_COMBINE_CONTRASTIVE else O.argmax_logit_mix(np.stack(rows), weights))
+            if mode == C.COS_COMBINE_CONTRASTIVE:
+                drafts[b, j] = O.argmax_contrastive(rows[0], rows[1], weights[0], weights[1])
+            elif mode == C.COS_COMBINE_LOGIT_MIX:
+                drafts[b, j] = O.argmax_logit_mix(np.stack(rows), weights)
+            else:                                                 # the proposer's own token, or another model's
+                pi = int(prop[b]) if ppos is None else int(ppos[b, j])
+                drafts[b, j] = int(np.argmax(rows[(pi + int(rng.integers(0, 2))) % n]))
     inp["draft_tokens"] = torch.from_numpy(drafts).cuda()
     nd, bonus = inp.get("num_drafts"), inp.get("bonus_idx")
+    ens = mode == C.COS_COMBINE_ENSEMBLE
     alen, toks = C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], mode, weights, inp["u_accept"],
                               inp["u_resample"], greedy=True, bonus_idx=bonus, num_drafts=nd,
-                              no_bonus=bool(inp.get("no_bonus", False)))
+                              proposer_pos=ppos if ens else None, no_bonus=bool(inp.get("no_bonus", False)))
     torch.cuda.synchronize()
-    st, want_len, want_toks = O.verify_greedy(host, odt, drafts, weights, mode=mode,
-                                              bonus_idx=None if bonus is None else bonus.cpu().numpy(),
-                                              num_drafts=None if nd is None else nd.cpu().numpy(),
-                                              no_bonus=bool(inp.get("no_bonus", False)))
+    opts = dict(bonus_idx=None if bonus is None else bonus.cpu().numpy(), num_drafts=None if nd is None else nd.cpu().numpy(),
+                no_bonus=bool(inp.get("no_bonus", False)))
+    if ens:
+        ora = O.verify(host, odt, drafts, prop, mode, weights, inp["u_accept"].cpu().numpy(), inp["u_resample"].cpu().numpy(),
+                       greedy=True, proposer_pos=None if ppos is None else ppos.cpu().numpy(), **opts)
+        st, want_len, want_toks = ora.status, ora.accepted_len, ora.out_tokens
+    else:
+        st, want_len, want_toks = O.verify_greedy(host, odt, drafts, weights, mode=mode, **opts)
     desc["mode"] = mode
     print(f"[fuzz] greedy {desc}: accepted lengths {np.bincount(want_len, minlength=gamma + 1).tolist()}", flush=True)
     assert st == 0
