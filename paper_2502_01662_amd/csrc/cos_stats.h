@@ -1119,26 +1119,47 @@ __global__ void __launch_bounds__(kThreads) greedy_ensemble_kernel(Params p) {
   const T* row = row_ptr<T>(p, m, b, j);
   const int v0 = s * pl.cv;
   const int v1 = min(v0 + pl.cv, p.nvec);
-  ArgBest best;
-  best.val = 0.0;
-  best.idx = -1;
+  // The wavefront keeps its largest value so far and where it first occurred.  Per element this is
+  // one maximum; the search for the place runs only when a group of loads raises the wavefront's
+  // maximum (a handful of times per chunk).  Groups come in ascending order of index, so a strict
+  // comparison keeps the lowest index among equal values; elements past the row's or the chunk's
+  // end read as -inf, NaN never wins a maximum.
+  float wave_val = -INFINITY;
+  int wave_idx = -1;
   for (int base = v0; base < v1 && !unread; base += kStep) {
     float x[U][N];
     if (base + kStep <= v1)
       load_group<T, ALIGNED, false, U>(row, base, v1, p.V, x);
     else
       load_group<T, ALIGNED, true, U>(row, base, v1, p.V, x);
+    float lm = -INFINITY;
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int first = (base + u * kThreads + tid) * N;  // element index of x[u][0]
-      const bool inside = base + u * kThreads + tid < v1;
+    for (int u = 0; u < U; ++u)
 #pragma unroll
-      for (int k = 0; k < N; ++k) {
-        const double val = (double)x[u][k];
-        arg_take(best, val, first + k, arg_plain_ok(best, val) && inside && first + k < p.V);
+      for (int k = 0; k < N; ++k) lm = fmaxf(lm, x[u][k]);
+    const float wm = wave_max(lm);
+    if (wm > wave_val) {  // wave-uniform
+      int cand = 0x7fffffff;
+      if (lm == wm) {
+#pragma unroll
+        for (int u = U - 1; u >= 0; --u)
+#pragma unroll
+          for (int k = N - 1; k >= 0; --k)
+            if (x[u][k] == wm) cand = (base + u * kThreads + tid) * N + k;  // descending: the first one stays
       }
+      wave_idx = -wave_max_i32(-cand);
+      wave_val = wm;
     }
   }
+  if (wave_idx < 0 && !unread) {
+    // nothing above -inf in this wavefront's share: its first element stands for it (a row of
+    // -inf still has an argmax, its first element)
+    const int first_vec = v0 + (tid & ~63);
+    if (first_vec < v1) wave_idx = first_vec * N;
+  }
+  ArgBest best;
+  best.val = (double)wave_val;
+  best.idx = wave_idx;
   Partial* out = p.partials + (((size_t)b * g1 + j) * p.n + m) * p.S + s;
   if (greedy_arrive(p, b, best, out, pl.per_b, wbest, &s_flag)) greedy_decide_ensemble(p, b, gb, s_arg, s_accept);
 }
