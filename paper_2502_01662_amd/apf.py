@@ -59,6 +59,13 @@ def sample_from_logits(logits: torch.Tensor, u: torch.Tensor) -> torch.Tensor:
     return torch.searchsorted(cdf, t, right=True).squeeze(1).clamp_(max=logits.shape[1] - 1).to(torch.int32)
 
 
+def first_argmax(logits: torch.Tensor) -> torch.Tensor:
+    """Temperature 0: the index of each row's largest logit, the lowest one among equals."""
+    top = logits.max(dim=-1, keepdim=True).values
+    index = torch.arange(logits.shape[-1], device=logits.device).expand_as(logits)
+    return torch.where(logits == top, index, logits.shape[-1]).min(dim=-1).values.to(torch.int32)
+
+
 @dataclass
 class APFStats:
     cycles: int = 0
@@ -74,7 +81,7 @@ VerifyFn = Callable[..., tuple]
 def alternate_proposal_decode(lm, prefix: torch.Tensor, cycles: int, gamma: int, combine_mode: int,
                               weights: Sequence[float], verify: VerifyFn, seed: int = 0,
                               default_proposer: int = 0, temperature: float = 1.0,
-                              use_bonus: bool = True):
+                              use_bonus: bool = True, greedy: bool = False):
     """Run ``cycles`` propose/score/verify cycles of Alg. 1 for a batch of sequences.
 
     prefix  [B, L0] int32 (L0 >= 2), on the device of ``lm``.
@@ -82,6 +89,8 @@ def alternate_proposal_decode(lm, prefix: torch.Tensor, cycles: int, gamma: int,
             ``bonus_idx`` and ``temperature`` included) returning (accepted_len, out_tokens).
     use_bonus = False gives Naive-CoS (Sec. 3.2): the verifier's extra token is discarded and the
             default proposer proposes every cycle.
+    greedy  temperature 0 (the T = 0 runs of Sec. 4.1): the proposer drafts its largest logit and
+            ``verify`` is called with ``greedy=True`` instead of ``temperature``.
     Returns (list of per-row token lists, APFStats).
     """
     dev = prefix.device
@@ -115,7 +124,7 @@ def alternate_proposal_decode(lm, prefix: torch.Tensor, cycles: int, gamma: int,
             both = torch.stack([lm.logits(0, ctx), lm.logits(1, ctx)])          # [2, B, V]
             prow = both[p_dev.long(), rows]
             u = torch.rand((B,), generator=gen, dtype=torch.float64)
-            tok = sample_from_logits(prow.float() / temperature, u)
+            tok = first_argmax(prow) if greedy else sample_from_logits(prow.float() / temperature, u)
             if j == 0 and bool(has_cache.any()):
                 hc = has_cache.to(dev)
                 tok = torch.where(hc, cache_tok.to(dev), tok)
@@ -130,8 +139,9 @@ def alternate_proposal_decode(lm, prefix: torch.Tensor, cycles: int, gamma: int,
         # ---- VERIFY ----
         u_acc = torch.rand((B, gamma), generator=gen, dtype=torch.float64).to(dev)
         u_res = torch.rand((B,), generator=gen, dtype=torch.float64).to(dev)
+        how = {"greedy": True} if greedy else {"temperature": temperature}
         alen, toks = verify(logits, drafts, p_dev, combine_mode, list(weights), u_acc, u_res,
-                            bonus_idx=v_dev.contiguous(), temperature=temperature)
+                            bonus_idx=v_dev.contiguous(), **how)
         alen_h, toks_h = alen.cpu(), toks.cpu()
         # ---- state update (Alg. 1) ----
         for b in range(B):

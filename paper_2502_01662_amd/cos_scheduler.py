@@ -27,7 +27,7 @@ from typing import Callable, List, Sequence
 
 import torch
 
-from .apf import sample_from_logits
+from .apf import first_argmax, sample_from_logits
 
 
 @dataclass
@@ -49,7 +49,7 @@ class SchedulerStats:
 
 def collaborative_speculation_decode(lm, prefix: torch.Tensor, iterations: int, gammas: Sequence[int],
                                      combine_mode: int, weights: Sequence[float], verify: Callable[..., tuple],
-                                     seed: int = 0, temperature: float = 1.0):
+                                     seed: int = 0, temperature: float = 1.0, greedy: bool = False):
     """Run ``iterations`` model invocations per sequence of Alg. 2.
 
     lm       object with ``n_models``, ``V``, ``tables`` and ``logits_multi(models [R], contexts [R, 2])``
@@ -58,6 +58,9 @@ def collaborative_speculation_decode(lm, prefix: torch.Tensor, iterations: int, 
     gammas   proposal length of every model (each >= 1).
     verify   callable with the signature of ``cos_verify.cos_verify``; it is called with the keyword
              arguments ``proposer_pos``, ``num_drafts``, ``no_bonus`` and ``temperature``.
+    greedy   temperature 0: every model drafts its largest logit and ``verify`` is called with
+             ``greedy=True`` instead of ``temperature`` (with ``proposer_pos`` only where the
+             verification looks at the proposers: the ensemble).
     Returns (list of per-row token lists, SchedulerStats).
     """
     n = lm.n_models
@@ -108,7 +111,7 @@ def collaborative_speculation_decode(lm, prefix: torch.Tensor, iterations: int, 
             if int(pos.max()) >= cap - 1:
                 raise RuntimeError("pending window outgrew the cache")
             out = distributions(model, pos, active)
-            tok = sample_from_logits(out.float() / temperature, u[:, t])
+            tok = first_argmax(out) if greedy else sample_from_logits(out.float() / temperature, u[:, t])
             sel = active.nonzero(as_tuple=True)[0]
             window[sel, pos[sel]] = tok[sel]
             proposer[sel, pos[sel]] = model[sel].to(torch.int32)
@@ -138,10 +141,14 @@ def collaborative_speculation_decode(lm, prefix: torch.Tensor, iterations: int, 
         stats.max_window = max(stats.max_window, int(win_len.max()) if B else 0)
         # ---- VERIFY every leading token that all models have scored ----
         K = have.min(dim=1).values
+        how = {"temperature": temperature}
+        if greedy:
+            how = {"greedy": True}
+        if not greedy or combine_mode == 0:              # at temperature 0 only the ensemble looks at the proposers
+            how["proposer_pos"] = proposer[:, :g_call].contiguous()
         alen, toks = verify(cache, window[:, :g_call].contiguous(), torch.zeros(B, dtype=torch.int32, device=dev),
-                            combine_mode, list(weights), u_acc, u_res,
-                            proposer_pos=proposer[:, :g_call].contiguous(), num_drafts=K.to(torch.int32),
-                            no_bonus=True, temperature=temperature)
+                            combine_mode, list(weights), u_acc, u_res, num_drafts=K.to(torch.int32),
+                            no_bonus=True, **how)
         alen = alen.to(dev).to(torch.int64)
         toks = toks.to(dev)
         rejected = alen < K

@@ -15,10 +15,16 @@ from paper_2502_01662_amd import workloads as W
 
 
 def oracle_verify(logits, drafts, proposer, mode, weights, u_acc, u_res, proposer_pos=None, num_drafts=None,
-                  no_bonus=False, temperature=1.0):
+                  no_bonus=False, temperature=1.0, greedy=False):
     dt = O.DTYPE_F32 if logits.dtype == torch.float32 else O.DTYPE_BF16
+    if greedy and mode != O.ENSEMBLE:                       # temperature 0, logit-level modes: their own oracle step
+        st, alen, toks = O.verify_greedy(W.host_logits(logits), dt, drafts.cpu().numpy(), weights, mode=mode,
+                                         num_drafts=None if num_drafts is None else num_drafts.cpu().numpy(),
+                                         no_bonus=no_bonus)
+        assert st == 0
+        return torch.from_numpy(alen), torch.from_numpy(toks)
     res = O.verify(W.host_logits(logits), dt, drafts.cpu().numpy(), proposer.cpu().numpy(), mode, weights,
-                   u_acc.cpu().numpy(), u_res.cpu().numpy(), temperature=temperature,
+                   u_acc.cpu().numpy(), u_res.cpu().numpy(), temperature=temperature, greedy=greedy,
                    proposer_pos=None if proposer_pos is None else proposer_pos.cpu().numpy(),
                    num_drafts=None if num_drafts is None else num_drafts.cpu().numpy(), no_bonus=no_bonus)
     assert res.status == 0
@@ -152,3 +158,38 @@ def test_gpu_driver_matches_oracle_driver_token_for_token(n, gammas, mode, weigh
     got, st_g = S.collaborative_speculation_decode(lm_gpu, prefix.cuda(), 14, gammas, mode, weights, C.cos_verify, seed=21)
     assert got == want
     assert st_g == st_o and st_g.rejections > 0 and st_g.accepted > 100
+
+
+@pytest.mark.parametrize("n,gammas,beta", [(2, (2, 1), [1.3, -0.3]), (3, (3, 2, 1), [0.8, 0.5, -0.3]), (4, (1, 1, 1, 1), [0.4, 0.3, 0.2, 0.1])])
+def test_greedy_scheduler_is_lossless(n, gammas, beta):
+    """Temperature 0 with a logit mix of n models: whatever the schedule, the text is the one that
+    one-token-at-a-time greedy decoding of the mix writes."""
+    V, B, iterations = 40, 48, 12
+    lm = apf.HashedBigramLM(n, V, buckets=128, base_std=2.0, noise_std=0.5, seed=17, device="cpu", dtype=torch.float32)
+    prefix = torch.randint(0, V, (B, 3), dtype=torch.int32, generator=torch.Generator().manual_seed(3))
+    seqs, st = S.collaborative_speculation_decode(lm, prefix, iterations, gammas, O.LOGIT_MIX, beta, oracle_verify,
+                                                  seed=7, greedy=True)
+    for row, got in zip(prefix.tolist(), seqs):
+        seq = list(row)
+        while len(seq) < len(got):
+            ctx = torch.tensor([seq[-2:]], dtype=torch.int32)
+            rows = np.stack([lm.logits(m, ctx)[0].to(torch.float64).numpy() for m in range(n)])
+            seq.append(O.argmax_logit_mix(rows, beta))
+        assert got == seq
+    assert st.accepted > 0 and st.rejections > 0 and st.tokens_out > B
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("mode,weights,n", [(O.ENSEMBLE, [0.5, 0.3, 0.2], 3), (O.LOGIT_MIX, [0.8, 0.5, -0.3], 3),
+                                            (O.CONTRASTIVE, [0.5, 0.1], 2)])
+def test_gpu_greedy_scheduler_matches_oracle_scheduler_token_for_token(mode, weights, n):
+    from paper_2502_01662_amd import cos_verify as C
+    V, B = 2048, 24
+    gammas = (3, 2, 1)[:n]
+    lm_gpu = apf.HashedBigramLM(n, V, buckets=256, base_std=2.0, noise_std=0.6, seed=19, device="cuda")
+    lm_cpu = apf.HashedBigramLM(n, V, buckets=256, base_std=2.0, noise_std=0.6, seed=19, device="cpu")
+    prefix = torch.randint(0, V, (B, 4), dtype=torch.int32, generator=torch.Generator().manual_seed(6))
+    want, st_o = S.collaborative_speculation_decode(lm_cpu, prefix, 10, gammas, mode, weights, oracle_verify, seed=23, greedy=True)
+    got, st_g = S.collaborative_speculation_decode(lm_gpu, prefix.cuda(), 10, gammas, mode, weights, C.cos_verify, seed=23, greedy=True)
+    assert got == want and st_g == st_o
+    assert st_g.accepted > 0
