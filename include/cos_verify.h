@@ -226,6 +226,24 @@ cos_status_t cos_verify_ex(const void *logits, cos_dtype_t dt, int n, int B, int
                            size_t workspace_bytes, const cos_diag_t *diag,
                            const cos_options_t *options, void *hip_stream);
 
+/*
+ * Debugging aid for the caller's side of the contract (cos_verify itself does not
+ * look at these values before using them): counts, on the device, the entries
+ * that are out of range -- draft tokens outside [0, V), proposer indices (and
+ * options->proposer_pos) outside [0, n), options->bonus_idx outside [-1, n),
+ * options->num_drafts outside [0, gamma], uniforms outside [0, 1) or NaN; with
+ * num_drafts given, only the drafts, proposers and uniforms of positions that
+ * carry a draft are looked at.  Waits for the stream, writes the count to
+ * *bad_entries (HOST) and returns COS_OK if it is zero, COS_ERR_SHAPE otherwise.
+ * Allocates nothing: the count lives in the first bytes of the workspace
+ * (256-byte aligned, at least 256 bytes).  options may be NULL.
+ */
+cos_status_t cos_verify_check_inputs(int n, int B, int gamma, int V, const int32_t *draft_tokens,
+                                     const int32_t *proposer_idx, const double *u_accept,
+                                     const double *u_resample, const cos_options_t *options,
+                                     void *workspace, size_t workspace_bytes, int *bad_entries,
+                                     void *hip_stream);
+
 /* Static, NUL-terminated description of a status code. */
 const char *cos_status_string(cos_status_t status);
 

@@ -86,6 +86,9 @@ def load_library() -> ctypes.CDLL:
         lib.cos_tune_set_chunk_vectors.restype = None
         lib.cos_tune_set_sample_blocks.argtypes = [ci]
         lib.cos_tune_set_sample_blocks.restype = None
+        lib.cos_verify_check_inputs.argtypes = [ci, ci, ci, ci, vp, vp, vp, vp, ctypes.POINTER(CosOptions), vp, sz,
+                                                ctypes.POINTER(ci), vp]
+        lib.cos_verify_check_inputs.restype = ci
         lib.cos_tune_set_tail.argtypes = [ci, ci]
         lib.cos_tune_set_tail.restype = None
         _lib = lib
@@ -259,3 +262,33 @@ def cos_verify(logits: torch.Tensor, draft_tokens: torch.Tensor, proposer_idx: t
     if st != COS_OK:
         raise CosVerifyError(st, cos_status_string(st))
     return accepted_len, out_tokens
+
+
+def cos_verify_check_inputs(n: int, V: int, draft_tokens: torch.Tensor, proposer_idx: torch.Tensor, u_accept: torch.Tensor,
+                            u_resample: torch.Tensor, bonus_idx: Optional[torch.Tensor] = None,
+                            proposer_pos: Optional[torch.Tensor] = None, num_drafts: Optional[torch.Tensor] = None) -> int:
+    """Debugging aid: the number of out-of-range entries in the side arrays of a call (0 = the caller's
+    contract holds).  Counted on the GPU; waits for the current stream."""
+    lib = load_library()
+    B, gamma = draft_tokens.shape
+    dev = draft_tokens.device
+    if not draft_tokens.is_cuda:
+        raise CosVerifyError(-8, "the arrays must live on the GPU: there is no CPU path")
+    for name, t, dtype, shape in (("draft_tokens", draft_tokens, torch.int32, (B, gamma)), ("proposer_idx", proposer_idx, torch.int32, (B,)),
+                                  ("u_accept", u_accept, torch.float64, (B, gamma)), ("u_resample", u_resample, torch.float64, (B,)),
+                                  ("bonus_idx", bonus_idx, torch.int32, (B,)), ("proposer_pos", proposer_pos, torch.int32, (B, gamma)),
+                                  ("num_drafts", num_drafts, torch.int32, (B,))):
+        if t is not None and (t.dtype != dtype or tuple(t.shape) != shape or not t.is_contiguous() or t.device != dev):
+            raise TypeError(f"{name}: want contiguous {dtype} {shape} on {dev}")
+    opt = CosOptions(ctypes.sizeof(CosOptions), 0.0, bonus_idx.data_ptr() if bonus_idx is not None else None,
+                     proposer_pos.data_ptr() if proposer_pos is not None else None, None, 0, 0,
+                     num_drafts.data_ptr() if num_drafts is not None else None, 0, 0)
+    ws = torch.empty(256, dtype=torch.uint8, device=dev)
+    bad = ctypes.c_int(0)
+    with torch.cuda.device(dev):
+        st = lib.cos_verify_check_inputs(n, B, gamma, V, draft_tokens.data_ptr(), proposer_idx.data_ptr(), u_accept.data_ptr(),
+                                         u_resample.data_ptr(), ctypes.byref(opt), ws.data_ptr(), ws.numel(), ctypes.byref(bad),
+                                         torch.cuda.current_stream(dev).cuda_stream)
+    if st not in (COS_OK, -2):
+        raise CosVerifyError(st, cos_status_string(st))
+    return bad.value

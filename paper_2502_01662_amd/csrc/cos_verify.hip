@@ -214,6 +214,34 @@ void choose_sampling(int B, int ntiles, int* C_out, int* tpc_out) {
   *tpc_out = tpc;
 }
 
+__global__ void zero_int_kernel(int* dst) { *dst = 0; }
+
+// Counts the entries of the side arrays that break the caller's contract (one thread per entry of
+// the [B][gamma] arrays; the first B threads also look at the per-sequence arrays).
+__global__ void check_inputs_kernel(int n, int B, int gamma, int V, const int* draft, const int* proposer,
+                                    const int* proposer_pos, const int* bonus_idx, const int* num_drafts,
+                                    const double* u_accept, const double* u_resample, int* bad) {
+  const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  int wrong = 0;
+  if (i < (long)B * gamma) {
+    const int b = (int)(i / gamma), j = (int)(i - (long)b * gamma);
+    int nd = num_drafts ? num_drafts[b] : gamma;
+    if (nd < 0 || nd > gamma) nd = 0;  // counted below, once per sequence
+    if (j < nd) {
+      wrong += draft[i] < 0 || draft[i] >= V;
+      wrong += !(u_accept[i] >= 0.0 && u_accept[i] < 1.0);
+      if (proposer_pos) wrong += proposer_pos[i] < 0 || proposer_pos[i] >= n;
+    }
+  }
+  if (i < B) {
+    wrong += proposer[i] < 0 || proposer[i] >= n;
+    wrong += !(u_resample[i] >= 0.0 && u_resample[i] < 1.0);
+    if (bonus_idx) wrong += bonus_idx[i] < -1 || bonus_idx[i] >= n;
+    if (num_drafts) wrong += num_drafts[i] < 0 || num_drafts[i] > gamma;
+  }
+  if (wrong) atomicAdd(bad, wrong);
+}
+
 }  // namespace
 
 extern "C" {
@@ -413,6 +441,32 @@ cos_status_t cos_verify_ex(const void* logits, cos_dtype_t dt, int n, int B, int
                                                 : run_bf16(p, lp);
   if (profile) ++g_ev_recorded;
   return rc;
+}
+
+cos_status_t cos_verify_check_inputs(int n, int B, int gamma, int V, const int32_t* draft_tokens,
+                                     const int32_t* proposer_idx, const double* u_accept,
+                                     const double* u_resample, const cos_options_t* options,
+                                     void* workspace, size_t workspace_bytes, int* bad_entries,
+                                     void* hip_stream) {
+  if (options && options->struct_bytes != sizeof(cos_options_t)) return COS_ERR_UNSUPPORTED;
+  if (!shape_ok(n, B, gamma, V)) return COS_ERR_SHAPE;
+  if (!bad_entries) return COS_ERR_NULL;
+  *bad_entries = 0;
+  if (B == 0) return COS_OK;
+  if (!draft_tokens || !proposer_idx || !u_accept || !u_resample) return COS_ERR_NULL;
+  if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256 || workspace_bytes < 256) return COS_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  int* bad = static_cast<int*>(workspace);
+  hipLaunchKernelGGL(zero_int_kernel, dim3(1), dim3(1), 0, st, bad);
+  const long entries = (long)B * gamma;
+  hipLaunchKernelGGL(check_inputs_kernel, dim3((unsigned)((entries + 255) / 256)), dim3(256), 0, st, n, B, gamma, V,
+                     draft_tokens, proposer_idx, options ? options->proposer_pos : nullptr,
+                     options ? options->bonus_idx : nullptr, options ? options->num_drafts : nullptr, u_accept,
+                     u_resample, bad);
+  if (hipGetLastError() != hipSuccess) return COS_ERR_LAUNCH;
+  if (hipMemcpyAsync(bad_entries, bad, sizeof(int), hipMemcpyDeviceToHost, st) != hipSuccess) return COS_ERR_LAUNCH;
+  if (hipStreamSynchronize(st) != hipSuccess) return COS_ERR_LAUNCH;
+  return *bad_entries == 0 ? COS_OK : COS_ERR_SHAPE;
 }
 
 const char* cos_status_string(cos_status_t status) {

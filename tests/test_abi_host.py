@@ -154,3 +154,15 @@ def test_workspace_bytes_follow_the_tail_knob():
     finally:
         C.cos_tune_set_tail(-1, 4)
     assert C.cos_verify_workspace_bytes(*shape) >= plain
+
+
+def test_input_checker_validates_its_own_arguments_on_the_host():
+    lib = C.load_library()
+    bad = ctypes.c_int(-1)
+    call = lambda n, B, ws, ws_bytes, draft=0x1000: lib.cos_verify_check_inputs(
+        n, B, 2, 16, draft, 0x1000, 0x1000, 0x1000, None, ws, ws_bytes, ctypes.byref(bad), None)
+    assert call(0, 1, 0x1000, 256) == -2                          # n out of range
+    assert call(2, 1, 0x1000, 256, draft=0) == -1                 # a required array is missing
+    assert call(2, 1, 0, 256) == -6 and call(2, 1, 0x1010, 256) == -6 and call(2, 1, 0x1000, 16) == -6
+    assert call(2, 0, 0, 0) == 0 and bad.value == 0               # empty batch: nothing to check
+    assert lib.cos_verify_check_inputs(2, 1, 2, 16, 0x1000, 0x1000, 0x1000, 0x1000, None, 0x1000, 256, None, None) == -1

@@ -256,6 +256,32 @@ def test_binding_checks_what_the_library_cannot():
     assert alen.shape == (3,) and toks.shape == (3, 3)
 
 
+def test_input_checker_counts_what_breaks_the_contract():
+    n, B, gamma, V = 3, 7, 4, 100
+    inp = _random_inputs(n, B, gamma, V, "bf16", seed=5)
+    args = (inp["draft_tokens"], inp["proposer_idx"], inp["u_accept"], inp["u_resample"])
+    assert C.cos_verify_check_inputs(n, V, *args) == 0
+    inp["draft_tokens"][2, 1] = V                    # one past the vocabulary
+    inp["draft_tokens"][5, 3] = -1
+    inp["proposer_idx"][0] = n
+    inp["u_accept"][6, 0] = 1.0                      # uniforms live in [0, 1)
+    inp["u_resample"][3] = float("nan")
+    assert C.cos_verify_check_inputs(n, V, *args) == 5
+    nd = torch.tensor([4, 4, 1, 4, 4, 3, 0], dtype=torch.int32, device="cuda")   # rows 2, 5, 6: the bad entries carry no draft
+    assert C.cos_verify_check_inputs(n, V, *args, num_drafts=nd) == 2
+    nd[1] = gamma + 1
+    bonus = torch.tensor([-1, 0, 2, 3, -2, 1, 0], dtype=torch.int32, device="cuda")  # two out of [-1, n)
+    ppos = torch.zeros((B, gamma), dtype=torch.int32, device="cuda")
+    ppos[0, 0] = 7                                   # row 0 has all its drafts
+    assert C.cos_verify_check_inputs(n, V, *args, num_drafts=nd, bonus_idx=bonus, proposer_pos=ppos) == 2 + 1 + 2 + 1
+    lib = C.load_library()                           # host-side argument checks of the entry point itself
+    import ctypes
+    bad = ctypes.c_int(-1)
+    assert lib.cos_verify_check_inputs(n, B, gamma, V, 0, 0, 0, 0, None, 0, 0, ctypes.byref(bad), None) == -1
+    assert lib.cos_verify_check_inputs(0, B, gamma, V, 0, 0, 0, 0, None, 0, 0, ctypes.byref(bad), None) == -2
+    assert lib.cos_verify_check_inputs(n, 0, gamma, V, 0, 0, 0, 0, None, 0, 0, ctypes.byref(bad), None) == 0 and bad.value == 0
+
+
 def test_r_equals_q_accepts_every_draft():
     inp = _random_inputs(1, 16, 4, 5000, "bf16", seed=21)
     inp["logits"] = inp["logits"].repeat(3, 1, 1, 1).contiguous()          # three identical models
