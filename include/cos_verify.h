@@ -247,7 +247,8 @@ cos_status_t cos_verify_check_inputs(int n, int B, int gamma, int V, const int32
 /* Static, NUL-terminated description of a status code. */
 const char *cos_status_string(cos_status_t status);
 
-/* ABI version of this library (bumped on incompatible changes). */
+/* Version of this library's interface: bumped whenever an entry point, an option or a mode is added
+ * or changes meaning (5: temperature 0 for every combine mode, cos_verify_check_inputs). */
 int cos_verify_version(void);
 
 /*

@@ -485,7 +485,7 @@ const char* cos_status_string(cos_status_t status) {
   return "unknown status";
 }
 
-int cos_verify_version(void) { return 4; }
+int cos_verify_version(void) { return 5; }
 
 cos_status_t cos_profile_enable(int slots) {
   if (slots < 0 || slots > kMaxProfileSlots) return COS_ERR_SHAPE;

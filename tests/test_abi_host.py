@@ -26,7 +26,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_version_and_status_strings():
-    assert C.cos_verify_version() == 4
+    assert C.cos_verify_version() == 5
     assert C.cos_status_string(0) == "ok"
     for code in range(-9, 0):
         assert C.cos_status_string(code) not in ("ok", "unknown status")
