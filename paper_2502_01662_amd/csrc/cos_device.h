@@ -94,6 +94,8 @@ struct Params {
   int nj;             // positions in this launch's window (gamma+1: the whole step in one launch)
   int win;            // window index (selects the arrival counters)
   int nwin;           // streaming launches of the call = sets of streaming arrival counters
+  int fill_count;     // > 0: no fill kernel ran; the call's first kernel clears this many counter ints
+                      // and marks the sequences undecided itself
   double w[COS_MAX_MODELS];  // ensemble weights; contrastive: w[0] = mu, w[1] = alpha_cd
   float scale;               // log2(e) / temperature: logits times this are base-2 exponents
   float mu_hi, mu_lo;        // mu split into two floats

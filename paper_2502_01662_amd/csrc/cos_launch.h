@@ -141,10 +141,15 @@ cos_status_t launch_greedy(Params p, const LaunchPlan& lp) {
 
 // Everything one call enqueues: the fill kernel, then the kernels of the mode.
 template <typename T>
-cos_status_t run_kernels(const Params& p, const LaunchPlan& lp) {
-  hipLaunchKernelGGL(fill_zero_kernel, dim3((lp.counters + kThreads - 1) / kThreads), dim3(kThreads), 0,
-                     lp.stream, p.counters, lp.counters, p.plans, p.B);
-  if (hipGetLastError() != hipSuccess) return COS_ERR_LAUNCH;
+cos_status_t run_kernels(Params p, const LaunchPlan& lp) {
+  // The masked contrastive mode starts with a kernel that uses neither counters nor plans (the expert
+  // maxima): it clears them on its way, one launch less.
+  p.fill_count = (lp.mode == kCd && p.masked) ? lp.counters : 0;
+  if (p.fill_count == 0) {
+    hipLaunchKernelGGL(fill_zero_kernel, dim3((lp.counters + kThreads - 1) / kThreads), dim3(kThreads), 0,
+                       lp.stream, p.counters, lp.counters, p.plans, p.B);
+    if (hipGetLastError() != hipSuccess) return COS_ERR_LAUNCH;
+  }
   if (lp.greedy) return lp.aligned ? launch_greedy<T, true>(p, lp) : launch_greedy<T, false>(p, lp);
   return lp.aligned ? launch_all<T, true>(p, lp.mode, lp.window, lp.lds, lp.stream, lp.ev_start, lp.ev_stop)
                     : launch_all<T, false>(p, lp.mode, lp.window, lp.lds, lp.stream, lp.ev_start, lp.ev_stop);

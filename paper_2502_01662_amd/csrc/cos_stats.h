@@ -492,6 +492,12 @@ __global__ void __launch_bounds__(kThreads) expert_rowmax_kernel(Params p) {
   constexpr int kStep = kThreads * kUnroll;
   __shared__ float wmax[kWaves];
   const int g1 = p.gamma + 1;
+  if (p.win == 0 && p.fill_count > 0) {
+    // the first kernel of the call: nothing has used the counters or the plans yet, and the
+    // kernels that do start after this one has ended
+    for (int i = blockIdx.x * kThreads + threadIdx.x; i < p.fill_count; i += gridDim.x * kThreads) p.counters[i] = 0;
+    for (int i = blockIdx.x * kThreads + threadIdx.x; i < p.B; i += gridDim.x * kThreads) p.plans[i].jstar = -1;
+  }
   const Place pl = place_of(p, p.nj);
   const int b = pl.b;
   const int j = p.j0 + pl.rem / pl.S;
