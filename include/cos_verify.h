@@ -60,7 +60,8 @@ typedef enum {
   COS_ERR_WORKSPACE = -6,   /* workspace NULL, misaligned (256 B) or smaller than cos_verify_workspace_bytes() */
   COS_ERR_ALIGN = -7,       /* logits pointer not aligned to its element size */
   COS_ERR_LAUNCH = -8,      /* a HIP call failed (no usable GPU, launch error) */
-  COS_ERR_UNSUPPORTED = -9
+  COS_ERR_UNSUPPORTED = -9,
+  COS_ERR_SCRATCH = -10     /* cos_verify_noalloc: the shape needs more than COS_NOALLOC_SCRATCH_BYTES of scratch */
 } cos_status_t;
 
 /* Supported ranges: 1 <= n <= COS_MAX_MODELS, 1 <= gamma <= COS_MAX_GAMMA,
@@ -225,6 +226,37 @@ cos_status_t cos_verify_ex(const void *logits, cos_dtype_t dt, int n, int B, int
                            int32_t *accepted_len, int32_t *out_tokens, void *workspace,
                            size_t workspace_bytes, const cos_diag_t *diag,
                            const cos_options_t *options, void *hip_stream);
+
+/*
+ * cos_verify_ex for callers that cannot allocate device memory or hand over a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  The scratch the kernels need (arrival counters, partial
+ * statistics, plans, tile sums) lives in an array of COS_NOALLOC_SCRATCH_BYTES
+ * bytes built into the library, one copy per GPU, held until the process ends;
+ * its device address is looked up once per device, on the first call made with
+ * that device current.  Every other argument is as in cos_verify_ex, outputs
+ * included: the caller still passes them.  The call allocates nothing (no
+ * hipMalloc, no hipFree, no allocating library routine) and enqueues exactly
+ * the kernels cos_verify_ex enqueues; the outputs are identical.
+ *
+ * A shape whose cos_verify_workspace_bytes() exceeds the array is rejected with
+ * COS_ERR_SCRATCH before anything is enqueued (the largest listed workload,
+ * n = 4, B = 512, gamma = 6, V = 256000, needs 5.0 MB).  All calls on one GPU
+ * share that GPU's array: calls that overlap in time on one GPU (two streams,
+ * two threads) race and give undefined outputs -- use cos_verify_ex with one
+ * workspace per stream there.  The array keeps the last call's contents; each
+ * call clears the counters it uses itself.
+ */
+#define COS_NOALLOC_SCRATCH_BYTES (8u << 20)
+cos_status_t cos_verify_noalloc(const void *logits, cos_dtype_t dt, int n, int B, int gamma, int V,
+                                const int32_t *draft_tokens, const int32_t *proposer_idx,
+                                cos_combine_t combine_mode, const double *weights,
+                                const double *u_accept, const double *u_resample,
+                                int32_t *accepted_len, int32_t *out_tokens, const cos_diag_t *diag,
+                                const cos_options_t *options, void *hip_stream);
+
+/* COS_NOALLOC_SCRATCH_BYTES as the loaded library was built with. */
+size_t cos_verify_noalloc_capacity(void);
 
 /*
  * Debugging aid for the caller's side of the contract (cos_verify itself does not

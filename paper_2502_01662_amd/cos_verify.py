@@ -72,6 +72,11 @@ def load_library() -> ctypes.CDLL:
                                       vp, vp, vp, vp, vp, sz, ctypes.POINTER(CosDiag),
                                       ctypes.POINTER(CosOptions), vp]
         lib.cos_verify_ex.restype = ci
+        lib.cos_verify_noalloc.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp, ci, ctypes.POINTER(ctypes.c_double),
+                                           vp, vp, vp, vp, ctypes.POINTER(CosDiag), ctypes.POINTER(CosOptions), vp]
+        lib.cos_verify_noalloc.restype = ci
+        lib.cos_verify_noalloc_capacity.argtypes = []
+        lib.cos_verify_noalloc_capacity.restype = sz
         lib.cos_status_string.argtypes = [ci]
         lib.cos_status_string.restype = ctypes.c_char_p
         lib.cos_verify_version.argtypes = []
@@ -182,7 +187,8 @@ def cos_verify(logits: torch.Tensor, draft_tokens: torch.Tensor, proposer_idx: t
                diag: Optional[Diagnostics] = None, temperature: float = 1.0,
                bonus_idx: Optional[torch.Tensor] = None, proposer_pos: Optional[torch.Tensor] = None,
                alpha: Optional[torch.Tensor] = None, stop_window: int = 0, greedy: bool = False,
-               num_drafts: Optional[torch.Tensor] = None, no_bonus: bool = False, refine_residual: bool = False):
+               num_drafts: Optional[torch.Tensor] = None, no_bonus: bool = False, refine_residual: bool = False,
+               _noalloc: bool = False):
     """Enqueue one verification step on the current stream; returns (accepted_len, out_tokens).
 
     logits [n][B][gamma+1][V] (float32, bfloat16 or float16), draft_tokens [B][gamma] int32,
@@ -210,6 +216,8 @@ def cos_verify(logits: torch.Tensor, draft_tokens: torch.Tensor, proposer_idx: t
             raise TypeError(f"{name}: want contiguous {dtype} {shape} on {dev}")
     if not logits.is_contiguous():
         raise TypeError("logits must be contiguous")
+    if _noalloc and (accepted_len is None or out_tokens is None or workspace is not None):
+        raise TypeError("cos_verify_noalloc: pass accepted_len and out_tokens, and no workspace")
     if accepted_len is None:
         accepted_len = torch.empty(B, dtype=torch.int32, device=dev)
     if out_tokens is None:
@@ -217,7 +225,9 @@ def cos_verify(logits: torch.Tensor, draft_tokens: torch.Tensor, proposer_idx: t
     for name, t, shape in (("accepted_len", accepted_len, (B,)), ("out_tokens", out_tokens, (B, g1))):
         if t.dtype != torch.int32 or tuple(t.shape) != shape or not t.is_contiguous() or t.device != dev:
             raise TypeError(f"{name}: want contiguous int32 {shape} on {dev}")
-    if workspace is None:
+    if _noalloc:
+        pass
+    elif workspace is None:
         workspace = allocate_workspace(n, B, gamma, V, dt, combine_mode, dev)
     elif workspace.dtype != torch.uint8 or not workspace.is_contiguous() or workspace.device != dev:
         raise TypeError(f"workspace: want a contiguous uint8 tensor on {dev}")
@@ -253,15 +263,35 @@ def cos_verify(logits: torch.Tensor, draft_tokens: torch.Tensor, proposer_idx: t
                          int(bool(refine_residual)))
     stream = torch.cuda.current_stream(dev).cuda_stream
     with torch.cuda.device(dev):
-        st = lib.cos_verify_ex(logits.data_ptr(), dt, n, B, gamma, V, draft_tokens.data_ptr(),
-                               proposer_idx.data_ptr(), combine_mode, w, u_accept.data_ptr(),
-                               u_resample.data_ptr(), accepted_len.data_ptr(), out_tokens.data_ptr(),
-                               workspace.data_ptr(), workspace.numel(),
-                               ctypes.byref(dstruct) if dstruct is not None else None,
-                               ctypes.byref(opt) if opt is not None else None, stream)
+        if _noalloc:
+            st = lib.cos_verify_noalloc(logits.data_ptr(), dt, n, B, gamma, V, draft_tokens.data_ptr(),
+                                        proposer_idx.data_ptr(), combine_mode, w, u_accept.data_ptr(),
+                                        u_resample.data_ptr(), accepted_len.data_ptr(), out_tokens.data_ptr(),
+                                        ctypes.byref(dstruct) if dstruct is not None else None,
+                                        ctypes.byref(opt) if opt is not None else None, stream)
+        else:
+            st = lib.cos_verify_ex(logits.data_ptr(), dt, n, B, gamma, V, draft_tokens.data_ptr(),
+                                   proposer_idx.data_ptr(), combine_mode, w, u_accept.data_ptr(),
+                                   u_resample.data_ptr(), accepted_len.data_ptr(), out_tokens.data_ptr(),
+                                   workspace.data_ptr(), workspace.numel(),
+                                   ctypes.byref(dstruct) if dstruct is not None else None,
+                                   ctypes.byref(opt) if opt is not None else None, stream)
     if st != COS_OK:
         raise CosVerifyError(st, cos_status_string(st))
     return accepted_len, out_tokens
+
+
+def cos_verify_noalloc(logits: torch.Tensor, draft_tokens: torch.Tensor, proposer_idx: torch.Tensor,
+                       combine_mode: int, weights: Sequence[float], u_accept: torch.Tensor, u_resample: torch.Tensor,
+                       accepted_len: torch.Tensor, out_tokens: torch.Tensor, **extensions):
+    """``cos_verify`` on the library's built-in scratch array: no workspace, and no device allocation
+    anywhere in the call (the outputs must be passed).  Calls that overlap on one GPU race."""
+    return cos_verify(logits, draft_tokens, proposer_idx, combine_mode, weights, u_accept, u_resample,
+                      accepted_len=accepted_len, out_tokens=out_tokens, _noalloc=True, **extensions)
+
+
+def cos_verify_noalloc_capacity() -> int:
+    return load_library().cos_verify_noalloc_capacity()
 
 
 def cos_verify_check_inputs(n: int, V: int, draft_tokens: torch.Tensor, proposer_idx: torch.Tensor, u_accept: torch.Tensor,

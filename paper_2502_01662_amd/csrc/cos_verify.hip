@@ -44,10 +44,16 @@
 #include <cmath>
 #include <cstdint>
 #include <cstdlib>
+#include <mutex>
 
 #include "cos_verify.h"
 
 #include "cos_device.h"
+
+// Built-in scratch of cos_verify_noalloc: one array per GPU the library runs on, held until the
+// process ends.  In host code this name is only a handle for hipGetSymbolAddress; the device
+// address it resolves to (per device) is what kernels, and every other use, are given.
+static __device__ __align__(256) unsigned char scratch[COS_NOALLOC_SCRATCH_BYTES];
 
 namespace {
 
@@ -74,6 +80,25 @@ struct Plan {
 };
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Device address of `scratch` on the current device, resolved once per device (each GPU holds its
+// own copy of the array at its own address).
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices];
+cos_status_t scratch_on_current_device(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return COS_ERR_LAUNCH;
+  if (dev < 0 || dev >= kMaxDevices) return COS_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return COS_ERR_LAUNCH;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return COS_OK;
+}
 
 bool shape_ok(int n, int B, int gamma, int V) {
   return n >= 1 && n <= COS_MAX_MODELS && B >= 0 && gamma >= 1 && gamma <= COS_MAX_GAMMA &&
@@ -276,13 +301,18 @@ cos_status_t cos_verify(const void* logits, cos_dtype_t dt, int n, int B, int ga
                        diag, nullptr, hip_stream);
 }
 
-cos_status_t cos_verify_ex(const void* logits, cos_dtype_t dt, int n, int B, int gamma, int V,
-                           const int32_t* draft_tokens, const int32_t* proposer_idx,
-                           cos_combine_t combine_mode, const double* weights,
-                           const double* u_accept, const double* u_resample,
-                           int32_t* accepted_len, int32_t* out_tokens, void* workspace,
-                           size_t workspace_bytes, const cos_diag_t* diag,
-                           const cos_options_t* options, void* hip_stream) {
+}  // extern "C"
+
+namespace {
+
+// The step behind every entry point.  builtin_scratch: the workspace is the library's own array.
+cos_status_t verify_impl(const void* logits, cos_dtype_t dt, int n, int B, int gamma, int V,
+                         const int32_t* draft_tokens, const int32_t* proposer_idx,
+                         cos_combine_t combine_mode, const double* weights,
+                         const double* u_accept, const double* u_resample,
+                         int32_t* accepted_len, int32_t* out_tokens, void* workspace,
+                         size_t workspace_bytes, bool builtin_scratch, const cos_diag_t* diag,
+                         const cos_options_t* options, void* hip_stream) {
   // ---- host-side validation (no HIP call before it passes) ----
   double temperature = 1.0;
   if (options) {
@@ -331,9 +361,15 @@ cos_status_t cos_verify_ex(const void* logits, cos_dtype_t dt, int n, int B, int
   const size_t esize = dt == COS_DTYPE_F32 ? 4 : 2;
   if (reinterpret_cast<uintptr_t>(logits) % esize) return COS_ERR_ALIGN;
   const size_t need = cos_verify_workspace_bytes(n, B, gamma, V, dt, combine_mode);
+  if ((size_t)(gamma + 1) * (contrastive ? 3 : (mix ? 2 : n)) > kMaxStatsPerSeq) return COS_ERR_SHAPE;
+  if (builtin_scratch) {
+    if (need > (size_t)COS_NOALLOC_SCRATCH_BYTES) return COS_ERR_SCRATCH;
+    const cos_status_t rc = scratch_on_current_device(&workspace);
+    if (rc != COS_OK) return rc;
+    workspace_bytes = COS_NOALLOC_SCRATCH_BYTES;
+  }
   if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256 || workspace_bytes < need)
     return COS_ERR_WORKSPACE;
-  if ((size_t)(gamma + 1) * (contrastive ? 3 : (mix ? 2 : n)) > kMaxStatsPerSeq) return COS_ERR_SHAPE;
 
   // ---- launch plan ----
   const int N = dt == COS_DTYPE_F32 ? 4 : 8;
@@ -443,6 +479,34 @@ cos_status_t cos_verify_ex(const void* logits, cos_dtype_t dt, int n, int B, int
   return rc;
 }
 
+}  // namespace
+
+extern "C" {
+
+cos_status_t cos_verify_ex(const void* logits, cos_dtype_t dt, int n, int B, int gamma, int V,
+                           const int32_t* draft_tokens, const int32_t* proposer_idx,
+                           cos_combine_t combine_mode, const double* weights,
+                           const double* u_accept, const double* u_resample,
+                           int32_t* accepted_len, int32_t* out_tokens, void* workspace,
+                           size_t workspace_bytes, const cos_diag_t* diag,
+                           const cos_options_t* options, void* hip_stream) {
+  return verify_impl(logits, dt, n, B, gamma, V, draft_tokens, proposer_idx, combine_mode, weights, u_accept,
+                     u_resample, accepted_len, out_tokens, workspace, workspace_bytes, false, diag, options,
+                     hip_stream);
+}
+
+cos_status_t cos_verify_noalloc(const void* logits, cos_dtype_t dt, int n, int B, int gamma, int V,
+                                const int32_t* draft_tokens, const int32_t* proposer_idx,
+                                cos_combine_t combine_mode, const double* weights,
+                                const double* u_accept, const double* u_resample,
+                                int32_t* accepted_len, int32_t* out_tokens, const cos_diag_t* diag,
+                                const cos_options_t* options, void* hip_stream) {
+  return verify_impl(logits, dt, n, B, gamma, V, draft_tokens, proposer_idx, combine_mode, weights, u_accept,
+                     u_resample, accepted_len, out_tokens, nullptr, 0, true, diag, options, hip_stream);
+}
+
+size_t cos_verify_noalloc_capacity(void) { return COS_NOALLOC_SCRATCH_BYTES; }
+
 cos_status_t cos_verify_check_inputs(int n, int B, int gamma, int V, const int32_t* draft_tokens,
                                      const int32_t* proposer_idx, const double* u_accept,
                                      const double* u_resample, const cos_options_t* options,
@@ -481,6 +545,7 @@ const char* cos_status_string(cos_status_t status) {
     case COS_ERR_ALIGN: return "logits pointer not aligned to its element size";
     case COS_ERR_LAUNCH: return "a HIP call failed";
     case COS_ERR_UNSUPPORTED: return "not supported";
+    case COS_ERR_SCRATCH: return "this shape needs more scratch than the library's built-in array holds";
   }
   return "unknown status";
 }
