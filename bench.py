@@ -20,7 +20,8 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E peak
 
 
 def _traffic_from_profiles(workload: str):
-    """HBM bytes per launch measured with rocprofv3 --pmc (committed summary), or None."""
+    """HBM bytes per launch of the dominant kernel, from the committed rocprofv3 --pmc summary of this
+    workload's shape (measured through the plain C++ driver, not in this run), or None."""
     path = os.path.join(ROOT, "profiles", f"cos_verify_{workload}_hbm_traffic.txt")
     if not os.path.exists(path):
         return None
@@ -40,9 +41,9 @@ def main() -> int:
     ap.add_argument("--cpu-rows", type=int, default=-1, help="batch rows the CPU oracle is timed on (-1 = auto, 0 = skip)")
     ap.add_argument("--chunk-vectors", type=int, default=0, help="tuning knob (0 = library heuristic)")
     ap.add_argument("--sample-blocks", type=int, default=0, help="tuning knob (0 = library heuristic)")
-    ap.add_argument("--tail-sequences", type=int, default=-1,
-                    help="tuning knob: sequences at the end of the grid with shorter chunks (-1 = library heuristic)")
-    ap.add_argument("--tail-factor", type=int, default=4, help="tuning knob: how many times shorter")
+    ap.add_argument("--tail-sequences", type=int, default=0,
+                    help="tuning knob: sequences at the end of the grid with shorter chunks (0 = library heuristic, < 0 = none)")
+    ap.add_argument("--tail-factor", type=int, default=0, help="tuning knob: how many times shorter (0 = 4)")
     ap.add_argument("--stop-window", type=int, default=0,
                     help="verify this many positions per launch and never read past a sequence's first "
                          "rejection (0 = the headline step: every position read, one launch)")
@@ -71,9 +72,8 @@ def main() -> int:
     if args.batch:
         w = w.scaled(B=args.batch, name=f"{w.name}_B{args.batch}")
     C.load_library()
-    C.cos_tune_set_chunk_vectors(args.chunk_vectors)
-    C.cos_tune_set_sample_blocks(args.sample_blocks)
-    C.cos_tune_set_tail(args.tail_sequences, args.tail_factor)
+    shape = C.LaunchShape(chunk_vectors=args.chunk_vectors, sample_blocks=args.sample_blocks,
+                          tail_sequences=args.tail_sequences, tail_factor=args.tail_factor)
 
     t0 = time.time()
     # small workloads: rotate over distinct input sets so that the timed calls stream from HBM,
@@ -83,30 +83,30 @@ def main() -> int:
     torch.cuda.synchronize()
     gen_s = time.time() - t0
     dt = C.COS_DTYPE_F32 if w.dtype == "f32" else C.COS_DTYPE_BF16
-    ws = C.allocate_workspace(w.n, w.B, w.gamma, w.V, dt, w.mode, dev)
+    ws = C.allocate_workspace(w.n, w.B, w.gamma, w.V, dt, w.mode, dev, shape)
     alen = torch.empty(w.B, dtype=torch.int32, device=dev)
     toks = torch.empty((w.B, w.gamma + 1), dtype=torch.int32, device=dev)
 
     alpha = torch.empty((w.B, w.gamma), dtype=torch.float64, device=dev) if args.with_alpha else None
 
-    def step(i):
+    def step(i, events=None):
         s = sets[i % nsets]
         C.cos_verify(s["logits"], s["draft_tokens"], s["proposer_idx"], w.mode, w.weights,
                      s["u_accept"], s["u_resample"], accepted_len=alen, out_tokens=toks, workspace=ws,
-                     alpha=alpha, stop_window=args.stop_window)
+                     alpha=alpha, stop_window=args.stop_window, shape=shape, events=events)
 
     for i in range(args.warmup):
         step(i)
-    torch.cuda.synchronize()
-    C.cos_profile_enable(min(args.steps, 1024))
+    # HIP events of this program, recorded by each call on its own stream around the kernel(s) that
+    # read every logit: the dominant kernel's duration, measured live over the timed region
+    timed_events = [C.make_events(dev) for _ in range(min(args.steps, 1024))]
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     for i in range(args.steps):
-        step(i)
+        step(i, timed_events[i % len(timed_events)])
     torch.cuda.synchronize()
     t2 = time.perf_counter()
-    kernel_ms = [C.cos_profile_kernel_ms(i) for i in range(C.cos_profile_recorded())]
-    C.cos_profile_enable(0)
+    kernel_ms = [a.elapsed_time(b) for a, b in timed_events]
     ms_per_step = (t2 - t1) * 1e3 / args.steps
     kavg = float(np.mean(kernel_ms))
     value = w.positions / (ms_per_step * 1e-3)
@@ -115,6 +115,8 @@ def main() -> int:
     roofline = {"bound": "hbm", "kernel": "contrastive_stats_kernel" if w.mode == W.CONTRASTIVE else "ensemble_stats_kernel",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": _traffic_from_profiles(args.workload),
+                "traffic_source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE through the plain C++ driver on this workload's "
+                                  "shape; committed summary under profiles/, not measured in this run",
                 "algorithmic_bytes_per_launch": w.logit_bytes, "kernel_avg_ms": round(kavg, 5),
                 "kernel_min_ms": round(float(np.min(kernel_ms)), 5)}
 
@@ -139,7 +141,7 @@ def main() -> int:
             s = sets[i % nsets]
             C.cos_verify(s["logits"], s["draft_tokens"], s["proposer_idx"], w.mode, w.weights,
                          s["u_accept"], s["u_resample"], accepted_len=alen, out_tokens=toks, workspace=ws,
-                         stop_window=1)
+                         stop_window=1, shape=shape)
         for i in range(args.warmup):
             lazy_step(i)
         torch.cuda.synchronize()
@@ -159,12 +161,13 @@ def main() -> int:
     parity = None
     cpu_rows = args.cpu_rows
     if cpu_rows < 0:
-        # ~20 core-seconds: about 6 ns per logit element, of which the sequential procedure
-        # (it stops at the first rejection) touches roughly half
+        # ~20-30 core-seconds for the two oracle passes: about 6 ns per logit element read
         per_row = w.n * (w.gamma + 1) * w.V * 3e-9
         cpu_rows = int(max(1, min(w.B, round(20.0 / per_row))))
+    failed = False
     if cpu_rows > 0:
         from oracle import cos_oracle as O
+        from tests import parity as P
         s = sets[0]
         rows = np.unique(np.linspace(0, w.B - 1, cpu_rows).round().astype(int))
         sel = torch.as_tensor(rows, device=dev)
@@ -173,29 +176,47 @@ def main() -> int:
         hd, hp = s["draft_tokens"][sel].cpu().numpy(), s["proposer_idx"][sel].cpu().numpy()
         hua, hur = s["u_accept"][sel].cpu().numpy(), s["u_resample"][sel].cpu().numpy()
         threads = O.max_threads()
+        # the same work as the GPU does: every position of every row (all_positions)
         c0 = time.perf_counter()
-        res = O.verify(lg, odt, hd, hp, w.mode, list(w.weights), hua, hur, all_positions=False, num_threads=threads)
+        res = O.verify(lg, odt, hd, hp, w.mode, list(w.weights), hua, hur, all_positions=True, num_threads=threads)
         c1 = time.perf_counter()
         assert res.status == 0
+        # the sequential procedure as the paper states it: stops at each row's first rejection
+        e0 = time.perf_counter()
+        early = O.verify(lg, odt, hd, hp, w.mode, list(w.weights), hua, hur, all_positions=False, num_threads=threads)
+        e1 = time.perf_counter()
+        assert early.status == 0
         # per-core rate: the same oracle on one thread, on a few of those rows
         few = max(1, min(len(rows), 8))
         s0 = time.perf_counter()
         one = O.verify(lg[:, :few], odt, hd[:few], hp[:few], w.mode, list(w.weights), hua[:few], hur[:few],
-                       all_positions=False, num_threads=1)
+                       all_positions=True, num_threads=1)
         s1 = time.perf_counter()
         assert one.status == 0
+        read_frac = float(np.mean(np.minimum(early.accepted_len + 1, w.gamma + 1)) / (w.gamma + 1))
         cpu = {"value": round(len(rows) * w.gamma / (c1 - c0), 2), "unit": "positions/s",
+               "early_stop_value": round(len(rows) * w.gamma / (e1 - e0), 2),
                "one_core_value": round(few * w.gamma / (s1 - s0), 2),
                "cores": int(min(threads, len(rows))), "kind": "oracle",
-               "sample": f"{len(rows)} of {w.B} batch rows of {w.name} (float64 C oracle, OpenMP over rows, "
-                         f"stops at the first rejection), {c1 - c0:.2f} s wall",
+               "sample": f"{len(rows)} of {w.B} batch rows of {w.name}: float64 C oracle, OpenMP over rows; `value` reads "
+                         f"every position of every row as the GPU does ({c1 - c0:.2f} s wall), `early_stop_value` stops at "
+                         f"each row's first rejection and so reads {read_frac:.0%} of the logits ({e1 - e0:.2f} s wall)",
                "host_cpus": os.cpu_count()}
-        step(0)
+        # parity of the timed configuration on those rows: lengths, tokens, r(d), q(d), flags
+        diag = C.Diagnostics.allocate(w.B, w.gamma, dev)
+        C.cos_verify(s["logits"], s["draft_tokens"], s["proposer_idx"], w.mode, w.weights, s["u_accept"],
+                     s["u_resample"], accepted_len=alen, out_tokens=toks, workspace=ws, diag=diag,
+                     stop_window=args.stop_window, shape=shape)
         torch.cuda.synchronize()
-        ga, gt = alen.cpu().numpy()[rows], toks.cpu().numpy()[rows]
-        exact = int(np.sum((ga == res.accepted_len) & np.all(gt == res.out_tokens, axis=1)))
-        parity = {"rows": int(len(rows)), "bit_exact_rows": exact,
+        rep = P.compare(s, w.mode, w.weights, alen.cpu().numpy(), toks.cpu().numpy(), diag, rows=rows)
+        parity = {"rows": rep.rows, "bit_exact_rows": rep.exact_rows,
+                  "excused_accept_ties": rep.excused_accept_ties, "excused_cdf_ties": rep.excused_cdf_ties,
+                  "unexcused_rows": len(rep.failures), "flag_mismatches": rep.flag_mismatches,
+                  "max_rel_err_r": rep.max_rel_err_r, "max_rel_err_q": rep.max_rel_err_q,
                   "accepted_len_histogram": np.bincount(alen.cpu().numpy(), minlength=w.gamma + 1).tolist()}
+        failed = (not rep.ok) or rep.exact_rows + rep.excused_accept_ties + rep.excused_cdf_ties != rep.rows
+        for msg in rep.failures[:5]:
+            print("bench.py: GPU/oracle mismatch:", msg, file=sys.stderr)
 
     out = {
         "metric": "verified positions/sec + achieved HBM GB/s of cos_verify (bf16 logits, 1 GPU)",
@@ -214,6 +235,9 @@ def main() -> int:
         "input_generation_s": round(gen_s, 1),
     }
     print(json.dumps(out), flush=True)
+    if failed:
+        print("bench.py: the timed configuration does not match the oracle on the sampled rows", file=sys.stderr)
+        return 1
     return 0
 
 

@@ -73,8 +73,9 @@ typedef enum {
 /* Flags written to cos_diag_t.flags. */
 #define COS_FLAG_RESIDUAL_FALLBACK 1 /* residual mass was <= 0 or not finite: token drawn from r instead */
 #define COS_FLAG_TAIL_CLAMP 2        /* rounding left no prefix above u*F: last token with mass taken */
-#define COS_FLAG_RESIDUAL_REFINED 4  /* the residual had little mass (r close to q) and was re-evaluated in
-                                        its difference form q (r/q - 1); not an error */
+#define COS_FLAG_RESIDUAL_REFINED 4  /* the residual had little mass (below 1/32: r close to q, an acceptance
+                                        rate above 97 %) and was evaluated in its difference form q (r/q - 1),
+                                        whose rounding error is relative to r - q itself; not an error */
 
 /* Optional per-row diagnostics; every member is a DEVICE pointer or NULL. */
 typedef struct cos_diag_t {
@@ -193,17 +194,24 @@ cos_status_t cos_verify(const void *logits, cos_dtype_t dt, int n, int B, int ga
  *               = -1 and the logits of that position are not read, so the
  *               tensor's last position may hold anything.  diag.sample_mass,
  *               cdf_lo, cdf_hi and flags of such a row are 0.
- * refine_residual  non-zero: a residual max(0, r - q) whose mass is below 1/32 (r
- *               close to q: an acceptance rate above 97 %) is evaluated once more in
- *               its difference form q (r/q - 1) by one workgroup of the sequence
- *               (flag COS_FLAG_RESIDUAL_REFINED).  The plain float32 evaluation
- *               carries an absolute error of ~1e-7 of each probability, i.e. ~1e-7 / F
- *               of the residual distribution with mass F: statistically irrelevant (such
- *               a residual is drawn from with probability F), but with F below ~1e-2 the
- *               drawn token can differ from a float64 reference for u_resample not near
- *               any CDF edge.  With this option it agrees down to F ~ 1e-3 (then the
- *               ~1e-7 accuracy of the float32 normalisers is the limit).  Costs about
- *               1.5 % of the step (a second variant of the sampling kernel).
+ * chunk_vectors, sample_blocks, tail_sequences, tail_factor
+ *               Launch-shape overrides for experiments and tests; 0 everywhere is
+ *               the built-in heuristic.  Outputs do not depend on them beyond the
+ *               rounding order of float64 sums.  chunk_vectors: 16-byte vectors of
+ *               one logit row that one workgroup of the streaming kernel reduces.
+ *               sample_blocks: total workgroups the sampling kernel aims for.
+ *               tail_sequences / tail_factor: the rows of the last tail_sequences
+ *               sequences of a streaming launch are cut into tail_factor times more
+ *               chunks than the others (they run while the GPU drains);
+ *               tail_sequences < 0 turns that off, tail_factor 0 means 4.
+ *               The workspace a call needs depends on chunk_vectors and the tail
+ *               fields: size it with cos_verify_workspace_bytes_ex and the same
+ *               options.
+ * event_start, event_stop
+ *               hipEvent_t handles created by the caller, or NULL.  The call records
+ *               event_start on its stream just before its streaming kernel(s) -- the
+ *               kernel(s) that read every logit -- and event_stop just after, so that
+ *               a benchmark can time that part of the step alone.
  */
 typedef struct cos_options_t {
   size_t struct_bytes;
@@ -215,7 +223,12 @@ typedef struct cos_options_t {
   int greedy;
   const int32_t *num_drafts;
   int no_bonus;
-  int refine_residual;
+  int chunk_vectors;
+  int sample_blocks;
+  int tail_sequences;
+  int tail_factor;
+  void *event_start;
+  void *event_stop;
 } cos_options_t;
 
 /* cos_verify with extensions; options == NULL is exactly cos_verify. */
@@ -226,6 +239,11 @@ cos_status_t cos_verify_ex(const void *logits, cos_dtype_t dt, int n, int B, int
                            int32_t *accepted_len, int32_t *out_tokens, void *workspace,
                            size_t workspace_bytes, const cos_diag_t *diag,
                            const cos_options_t *options, void *hip_stream);
+
+/* cos_verify_workspace_bytes for a call with these options (NULL: the same value).  Only the
+ * launch-shape overrides enter; 0 on invalid arguments.  Host-only computation. */
+size_t cos_verify_workspace_bytes_ex(int n, int B, int gamma, int V, cos_dtype_t dt, cos_combine_t mode,
+                                     const cos_options_t *options);
 
 /*
  * cos_verify_ex for callers that cannot allocate device memory or hand over a
@@ -280,45 +298,9 @@ cos_status_t cos_verify_check_inputs(int n, int B, int gamma, int V, const int32
 const char *cos_status_string(cos_status_t status);
 
 /* Version of this library's interface: bumped whenever an entry point, an option or a mode is added
- * or changes meaning (5: temperature 0 for every combine mode, cos_verify_check_inputs). */
+ * or changes meaning (6: residuals of little mass are always evaluated in their difference form; launch-shape overrides and
+ * timing events are per-call options, the library keeps no settings between calls). */
 int cos_verify_version(void);
-
-/*
- * Optional timing of the streaming kernel (the one that reads every logit),
- * for benchmarks.  cos_profile_enable(slots) with 1 <= slots <= 1024 makes
- * each following cos_verify call record a HIP event pair around that kernel
- * on the call's stream, into slot (call number mod slots); slots == 0 turns
- * it off.  cos_profile_recorded() is the number of filled slots, and
- * cos_profile_kernel_ms(i, &ms) waits for slot i's stop event and returns the
- * elapsed milliseconds.  Process-wide state; not thread-safe; off by default.
- */
-cos_status_t cos_profile_enable(int slots);
-int cos_profile_recorded(void);
-cos_status_t cos_profile_kernel_ms(int index, float *ms);
-
-/*
- * Tuning knob for experiments: vectors (16-byte units) of one logit row that
- * one workgroup of the streaming kernel reduces.  0 restores the built-in
- * heuristic.  Process-wide; results do not depend on it beyond rounding order.
- * cos_verify_workspace_bytes() depends on it: size the workspace after setting it.
- */
-void cos_tune_set_chunk_vectors(int vectors);
-
-/*
- * Tuning knob for experiments: total number of workgroups the sampling kernel
- * aims for (each sequence gets ceil(blocks / B) of them, at least 4 tiles
- * each).  0 restores the built-in heuristic.  Process-wide.
- */
-void cos_tune_set_sample_blocks(int blocks);
-
-/*
- * Tuning knob for experiments: the rows of the last `sequences` sequences of a streaming
- * launch are cut into `factor` times more chunks than the others (they run while
- * the GPU drains, where short chunks finish sooner).  sequences < 0 restores the
- * built-in heuristic, 0 or factor <= 1 turns it off.  Process-wide;
- * cos_verify_workspace_bytes() depends on it.
- */
-void cos_tune_set_tail(int sequences, int factor);
 
 #ifdef __cplusplus
 }

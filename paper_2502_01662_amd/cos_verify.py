@@ -39,7 +39,10 @@ class CosOptions(ctypes.Structure):
     _fields_ = [("struct_bytes", ctypes.c_size_t), ("temperature", ctypes.c_double),
                 ("bonus_idx", ctypes.c_void_p), ("proposer_pos", ctypes.c_void_p), ("alpha", ctypes.c_void_p),
                 ("stop_window", ctypes.c_int), ("greedy", ctypes.c_int),
-                ("num_drafts", ctypes.c_void_p), ("no_bonus", ctypes.c_int), ("refine_residual", ctypes.c_int)]
+                ("num_drafts", ctypes.c_void_p), ("no_bonus", ctypes.c_int),
+                ("chunk_vectors", ctypes.c_int), ("sample_blocks", ctypes.c_int),
+                ("tail_sequences", ctypes.c_int), ("tail_factor", ctypes.c_int),
+                ("event_start", ctypes.c_void_p), ("event_stop", ctypes.c_void_p)]
 
 
 class CosVerifyError(RuntimeError):
@@ -81,21 +84,11 @@ def load_library() -> ctypes.CDLL:
         lib.cos_status_string.restype = ctypes.c_char_p
         lib.cos_verify_version.argtypes = []
         lib.cos_verify_version.restype = ci
-        lib.cos_profile_enable.argtypes = [ci]
-        lib.cos_profile_enable.restype = ci
-        lib.cos_profile_recorded.argtypes = []
-        lib.cos_profile_recorded.restype = ci
-        lib.cos_profile_kernel_ms.argtypes = [ci, ctypes.POINTER(ctypes.c_float)]
-        lib.cos_profile_kernel_ms.restype = ci
-        lib.cos_tune_set_chunk_vectors.argtypes = [ci]
-        lib.cos_tune_set_chunk_vectors.restype = None
-        lib.cos_tune_set_sample_blocks.argtypes = [ci]
-        lib.cos_tune_set_sample_blocks.restype = None
+        lib.cos_verify_workspace_bytes_ex.argtypes = [ci, ci, ci, ci, ci, ci, ctypes.POINTER(CosOptions)]
+        lib.cos_verify_workspace_bytes_ex.restype = sz
         lib.cos_verify_check_inputs.argtypes = [ci, ci, ci, ci, vp, vp, vp, vp, ctypes.POINTER(CosOptions), vp, sz,
                                                 ctypes.POINTER(ci), vp]
         lib.cos_verify_check_inputs.restype = ci
-        lib.cos_tune_set_tail.argtypes = [ci, ci]
-        lib.cos_tune_set_tail.restype = None
         _lib = lib
     return _lib
 
@@ -112,30 +105,43 @@ def cos_verify_workspace_bytes(n: int, B: int, gamma: int, V: int, dt: int, mode
     return load_library().cos_verify_workspace_bytes(n, B, gamma, V, dt, mode)
 
 
-def cos_profile_enable(slots: int) -> None:
-    st = load_library().cos_profile_enable(int(slots))
-    if st != COS_OK:
-        raise CosVerifyError(st, cos_status_string(st))
+@dataclass(frozen=True)
+class LaunchShape:
+    """Launch-shape overrides of one call (experiments and tests); zeros are the built-in heuristics."""
+    chunk_vectors: int = 0
+    sample_blocks: int = 0
+    tail_sequences: int = 0     # > 0: that many sequences at the end of the grid; < 0: none
+    tail_factor: int = 0        # 0: 4
+
+    def any(self) -> bool:
+        return bool(self.chunk_vectors or self.sample_blocks or self.tail_sequences or self.tail_factor)
 
 
-def cos_profile_recorded() -> int:
-    return load_library().cos_profile_recorded()
+def _options(temperature=0.0, bonus_idx=None, proposer_pos=None, alpha=None, stop_window=0, greedy=False,
+             num_drafts=None, no_bonus=False, shape: Optional[LaunchShape] = None, events=None) -> CosOptions:
+    shape = shape or LaunchShape()
+    ptr = lambda t: t.data_ptr() if t is not None else None
+    ev0, ev1 = (events[0].cuda_event, events[1].cuda_event) if events is not None else (None, None)
+    return CosOptions(ctypes.sizeof(CosOptions), float(temperature), ptr(bonus_idx), ptr(proposer_pos), ptr(alpha),
+                      int(stop_window), int(bool(greedy)), ptr(num_drafts), int(bool(no_bonus)),
+                      int(shape.chunk_vectors), int(shape.sample_blocks), int(shape.tail_sequences),
+                      int(shape.tail_factor), ev0, ev1)
 
 
-def cos_profile_kernel_ms(index: int) -> float:
-    ms = ctypes.c_float()
-    st = load_library().cos_profile_kernel_ms(int(index), ctypes.byref(ms))
-    if st != COS_OK:
-        raise CosVerifyError(st, cos_status_string(st))
-    return ms.value
+def cos_verify_workspace_bytes_ex(n: int, B: int, gamma: int, V: int, dt: int, mode: int,
+                                  shape: Optional[LaunchShape] = None) -> int:
+    opt = _options(shape=shape)
+    return load_library().cos_verify_workspace_bytes_ex(n, B, gamma, V, dt, mode, ctypes.byref(opt))
 
 
-def cos_tune_set_chunk_vectors(vectors: int) -> None:
-    load_library().cos_tune_set_chunk_vectors(int(vectors))
-
-
-def cos_tune_set_sample_blocks(blocks: int) -> None:
-    load_library().cos_tune_set_sample_blocks(int(blocks))
+def make_events(device=None):
+    """A (start, stop) pair of timing events whose HIP handles exist, for ``cos_verify(events=...)``;
+    ``start.elapsed_time(stop)`` after a call gives the milliseconds of its streaming kernel(s)."""
+    pair = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+    with torch.cuda.device(device):
+        for e in pair:
+            e.record()      # creates the underlying hipEvent_t (torch creates it lazily)
+    return pair
 
 
 @dataclass
@@ -159,10 +165,6 @@ class Diagnostics:
                        self.cdf_lo.data_ptr(), self.cdf_hi.data_ptr(), self.flags.data_ptr())
 
 
-def cos_tune_set_tail(sequences: int, factor: int) -> None:
-    load_library().cos_tune_set_tail(int(sequences), int(factor))
-
-
 def _dtype_code(t: torch.Tensor) -> int:
     if t.dtype == torch.float32:
         return COS_DTYPE_F32
@@ -173,8 +175,9 @@ def _dtype_code(t: torch.Tensor) -> int:
     raise TypeError(f"logits must be float32, bfloat16 or float16, got {t.dtype}")
 
 
-def allocate_workspace(n: int, B: int, gamma: int, V: int, dt: int, mode: int, device) -> torch.Tensor:
-    nbytes = cos_verify_workspace_bytes(n, B, gamma, V, dt, mode)
+def allocate_workspace(n: int, B: int, gamma: int, V: int, dt: int, mode: int, device,
+                       shape: Optional[LaunchShape] = None) -> torch.Tensor:
+    nbytes = cos_verify_workspace_bytes_ex(n, B, gamma, V, dt, mode, shape)
     if nbytes == 0:
         raise CosVerifyError(-2, "unsupported shape")
     return torch.empty(nbytes, dtype=torch.uint8, device=device)
@@ -187,8 +190,8 @@ def cos_verify(logits: torch.Tensor, draft_tokens: torch.Tensor, proposer_idx: t
                diag: Optional[Diagnostics] = None, temperature: float = 1.0,
                bonus_idx: Optional[torch.Tensor] = None, proposer_pos: Optional[torch.Tensor] = None,
                alpha: Optional[torch.Tensor] = None, stop_window: int = 0, greedy: bool = False,
-               num_drafts: Optional[torch.Tensor] = None, no_bonus: bool = False, refine_residual: bool = False,
-               _noalloc: bool = False):
+               num_drafts: Optional[torch.Tensor] = None, no_bonus: bool = False,
+               shape: Optional[LaunchShape] = None, events=None, _noalloc: bool = False):
     """Enqueue one verification step on the current stream; returns (accepted_len, out_tokens).
 
     logits [n][B][gamma+1][V] (float32, bfloat16 or float16), draft_tokens [B][gamma] int32,
@@ -198,8 +201,9 @@ def cos_verify(logits: torch.Tensor, draft_tokens: torch.Tensor, proposer_idx: t
     ``proposer_pos`` [B][gamma] int32, ``alpha`` [B][gamma] float64 (output: acceptance rates),
     ``stop_window`` (positions per streaming launch; later positions of a rejected sequence are not read),
     ``greedy`` (temperature 0), ``num_drafts`` [B] int32 (drafts per row, each in
-    [0, gamma]), ``no_bonus`` (no extra token when every draft of a row is accepted), ``refine_residual``
-    (residuals of little mass are evaluated once more in their difference form).
+    [0, gamma]), ``no_bonus`` (no extra token when every draft of a row is accepted), ``shape``
+    (launch-shape overrides; a workspace passed along must be sized for them), ``events`` (a pair from
+    ``make_events``, recorded around the streaming kernel(s)).
     """
     lib = load_library()
     if not logits.is_cuda:
@@ -208,12 +212,12 @@ def cos_verify(logits: torch.Tensor, draft_tokens: torch.Tensor, proposer_idx: t
     gamma = g1 - 1
     dev = logits.device
     dt = _dtype_code(logits)
-    for name, t, dtype, shape in (("draft_tokens", draft_tokens, torch.int32, (B, gamma)),
+    for name, t, dtype, shp in (("draft_tokens", draft_tokens, torch.int32, (B, gamma)),
                                   ("proposer_idx", proposer_idx, torch.int32, (B,)),
                                   ("u_accept", u_accept, torch.float64, (B, gamma)),
                                   ("u_resample", u_resample, torch.float64, (B,))):
-        if t.dtype != dtype or tuple(t.shape) != shape or not t.is_contiguous() or t.device != dev:
-            raise TypeError(f"{name}: want contiguous {dtype} {shape} on {dev}")
+        if t.dtype != dtype or tuple(t.shape) != shp or not t.is_contiguous() or t.device != dev:
+            raise TypeError(f"{name}: want contiguous {dtype} {shp} on {dev}")
     if not logits.is_contiguous():
         raise TypeError("logits must be contiguous")
     if _noalloc and (accepted_len is None or out_tokens is None or workspace is not None):
@@ -222,13 +226,13 @@ def cos_verify(logits: torch.Tensor, draft_tokens: torch.Tensor, proposer_idx: t
         accepted_len = torch.empty(B, dtype=torch.int32, device=dev)
     if out_tokens is None:
         out_tokens = torch.empty((B, g1), dtype=torch.int32, device=dev)
-    for name, t, shape in (("accepted_len", accepted_len, (B,)), ("out_tokens", out_tokens, (B, g1))):
-        if t.dtype != torch.int32 or tuple(t.shape) != shape or not t.is_contiguous() or t.device != dev:
-            raise TypeError(f"{name}: want contiguous int32 {shape} on {dev}")
+    for name, t, shp in (("accepted_len", accepted_len, (B,)), ("out_tokens", out_tokens, (B, g1))):
+        if t.dtype != torch.int32 or tuple(t.shape) != shp or not t.is_contiguous() or t.device != dev:
+            raise TypeError(f"{name}: want contiguous int32 {shp} on {dev}")
     if _noalloc:
         pass
     elif workspace is None:
-        workspace = allocate_workspace(n, B, gamma, V, dt, combine_mode, dev)
+        workspace = allocate_workspace(n, B, gamma, V, dt, combine_mode, dev, shape)
     elif workspace.dtype != torch.uint8 or not workspace.is_contiguous() or workspace.device != dev:
         raise TypeError(f"workspace: want a contiguous uint8 tensor on {dev}")
     # the library reads n weights (two in contrastive mode) from this host array
@@ -237,30 +241,27 @@ def cos_verify(logits: torch.Tensor, draft_tokens: torch.Tensor, proposer_idx: t
         raise CosVerifyError(-5, f"{wanted} weights wanted for this mode, got {len(weights)}")
     w = (ctypes.c_double * max(len(weights), 1))(*[float(x) for x in weights])
     if diag is not None:
-        for name, shape, dtype in (("r_at_draft", (B, gamma), torch.float64), ("q_at_draft", (B, gamma), torch.float64),
+        for name, shp, dtype in (("r_at_draft", (B, gamma), torch.float64), ("q_at_draft", (B, gamma), torch.float64),
                                    ("sample_mass", (B,), torch.float64), ("cdf_lo", (B,), torch.float64),
                                    ("cdf_hi", (B,), torch.float64), ("flags", (B,), torch.int32)):
             t = getattr(diag, name)
-            if t.dtype != dtype or tuple(t.shape) != shape or not t.is_contiguous() or t.device != dev:
-                raise TypeError(f"diag.{name}: want contiguous {dtype} {shape} on {dev}")
+            if t.dtype != dtype or tuple(t.shape) != shp or not t.is_contiguous() or t.device != dev:
+                raise TypeError(f"diag.{name}: want contiguous {dtype} {shp} on {dev}")
     dstruct = diag.as_struct() if diag is not None else None
     opt = None
     if alpha is not None and (alpha.dtype != torch.float64 or tuple(alpha.shape) != (B, gamma)
                               or not alpha.is_contiguous() or alpha.device != dev):
         raise TypeError(f"alpha: want contiguous float64 {(B, gamma)} on {dev}")
     if (temperature != 1.0 or bonus_idx is not None or proposer_pos is not None or alpha is not None
-            or stop_window or greedy or num_drafts is not None or no_bonus or refine_residual):
-        for name, t, shape in (("bonus_idx", bonus_idx, (B,)), ("proposer_pos", proposer_pos, (B, gamma)),
-                               ("num_drafts", num_drafts, (B,))):
-            if t is not None and (t.dtype != torch.int32 or tuple(t.shape) != shape or not t.is_contiguous()
+            or stop_window or greedy or num_drafts is not None or no_bonus or (shape is not None and shape.any())
+            or events is not None):
+        for name, t, shp in (("bonus_idx", bonus_idx, (B,)), ("proposer_pos", proposer_pos, (B, gamma)),
+                             ("num_drafts", num_drafts, (B,))):
+            if t is not None and (t.dtype != torch.int32 or tuple(t.shape) != shp or not t.is_contiguous()
                                   or t.device != dev):
-                raise TypeError(f"{name}: want contiguous int32 {shape} on {dev}")
-        opt = CosOptions(ctypes.sizeof(CosOptions), float(temperature),
-                         bonus_idx.data_ptr() if bonus_idx is not None else None,
-                         proposer_pos.data_ptr() if proposer_pos is not None else None,
-                         alpha.data_ptr() if alpha is not None else None, int(stop_window), int(greedy),
-                         num_drafts.data_ptr() if num_drafts is not None else None, int(bool(no_bonus)),
-                         int(bool(refine_residual)))
+                raise TypeError(f"{name}: want contiguous int32 {shp} on {dev}")
+        opt = _options(temperature, bonus_idx, proposer_pos, alpha, stop_window, greedy, num_drafts, no_bonus,
+                       shape, events)
     stream = torch.cuda.current_stream(dev).cuda_stream
     with torch.cuda.device(dev):
         if _noalloc:
@@ -310,9 +311,7 @@ def cos_verify_check_inputs(n: int, V: int, draft_tokens: torch.Tensor, proposer
                                   ("num_drafts", num_drafts, torch.int32, (B,))):
         if t is not None and (t.dtype != dtype or tuple(t.shape) != shape or not t.is_contiguous() or t.device != dev):
             raise TypeError(f"{name}: want contiguous {dtype} {shape} on {dev}")
-    opt = CosOptions(ctypes.sizeof(CosOptions), 0.0, bonus_idx.data_ptr() if bonus_idx is not None else None,
-                     proposer_pos.data_ptr() if proposer_pos is not None else None, None, 0, 0,
-                     num_drafts.data_ptr() if num_drafts is not None else None, 0, 0)
+    opt = _options(bonus_idx=bonus_idx, proposer_pos=proposer_pos, num_drafts=num_drafts)
     ws = torch.empty(256, dtype=torch.uint8, device=dev)
     bad = ctypes.c_int(0)
     with torch.cuda.device(dev):

@@ -61,7 +61,6 @@ struct Params {
   const int* bonus_idx;     // optional [B]: model the bonus token is drawn from (-1: from r)
   const int* num_drafts;    // optional [B]: drafts of each row (NULL: gamma everywhere)
   int no_bonus;             // 1: no extra token when every draft is accepted
-  int refine;               // 1: residuals of little mass are evaluated once more in their difference form
   const double* u_accept;
   const double* u_resample;
   int* accepted_len;

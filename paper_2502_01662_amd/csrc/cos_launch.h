@@ -12,29 +12,23 @@ namespace {
 
 // Kernels that hold the rows of all n models in registers are specialised for
 // n = 1..4; more models take the generic instance.
-template <typename T, bool ALIGNED, int MODE, bool REFINE>
-cos_status_t launch_sampling_variant(const Params& p, size_t lds, hipStream_t st) {
+template <typename T, bool ALIGNED, int MODE>
+cos_status_t launch_sampling(const Params& p, size_t lds, hipStream_t st) {
   const long blocks = (long)p.B * p.C;
   if (blocks <= 0 || blocks > 0x7fffffffL) return COS_ERR_SHAPE;
   const dim3 grid((unsigned)blocks), block(kThreads);
   if constexpr (MODE == kCd) {
-    hipLaunchKernelGGL((sample_kernel<T, ALIGNED, 2, kCd, REFINE>), grid, block, lds, st, p);
+    hipLaunchKernelGGL((sample_kernel<T, ALIGNED, 2, kCd>), grid, block, lds, st, p);
   } else {
     switch (p.n) {
-      case 1: hipLaunchKernelGGL((sample_kernel<T, ALIGNED, 1, MODE, REFINE>), grid, block, lds, st, p); break;
-      case 2: hipLaunchKernelGGL((sample_kernel<T, ALIGNED, 2, MODE, REFINE>), grid, block, lds, st, p); break;
-      case 3: hipLaunchKernelGGL((sample_kernel<T, ALIGNED, 3, MODE, REFINE>), grid, block, lds, st, p); break;
-      case 4: hipLaunchKernelGGL((sample_kernel<T, ALIGNED, 4, MODE, REFINE>), grid, block, lds, st, p); break;
-      default: hipLaunchKernelGGL((sample_kernel<T, ALIGNED, 0, MODE, REFINE>), grid, block, lds, st, p); break;
+      case 1: hipLaunchKernelGGL((sample_kernel<T, ALIGNED, 1, MODE>), grid, block, lds, st, p); break;
+      case 2: hipLaunchKernelGGL((sample_kernel<T, ALIGNED, 2, MODE>), grid, block, lds, st, p); break;
+      case 3: hipLaunchKernelGGL((sample_kernel<T, ALIGNED, 3, MODE>), grid, block, lds, st, p); break;
+      case 4: hipLaunchKernelGGL((sample_kernel<T, ALIGNED, 4, MODE>), grid, block, lds, st, p); break;
+      default: hipLaunchKernelGGL((sample_kernel<T, ALIGNED, 0, MODE>), grid, block, lds, st, p); break;
     }
   }
   return hipGetLastError() == hipSuccess ? COS_OK : COS_ERR_LAUNCH;
-}
-
-template <typename T, bool ALIGNED, int MODE>
-cos_status_t launch_sampling(const Params& p, size_t lds, hipStream_t st) {
-  return p.refine ? launch_sampling_variant<T, ALIGNED, MODE, true>(p, lds, st)
-                  : launch_sampling_variant<T, ALIGNED, MODE, false>(p, lds, st);
 }
 
 template <typename T, bool ALIGNED, int MODE>

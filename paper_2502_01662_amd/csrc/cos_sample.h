@@ -92,7 +92,15 @@ __device__ __forceinline__ void eval_f_mix(const float (&x)[NCAP][N], int n, int
 //   ensemble:     q(x) * sum_{m != pi} w_m (2^delta_m - 1),  delta_m = log2(s_m(x) / s_pi(x))
 //   logit level:  q(x) * (2^delta - 1),                      delta   = log2(r(x) / q(x))
 // (the ensemble form uses sum_m w_m = 1), whose error is relative to the small
-// differences themselves.
+// differences themselves.  delta needs the difference of two log-normalisers, and the
+// streaming kernel's float32 sums give each of them to ~1e-7 only -- an absolute
+// error in delta, hence a relative one of 1e-7 / F in the residual.  The workgroup
+// therefore first takes that difference itself, again in difference form: with
+// E(x) = 2^(l_pi(x)*scale - K) and one offset K for both rows,
+//   Z_m / Z_pi - 1 = sum_x E(x) (2^d0_m(x) - 1) / sum_x E(x),   d0_m = (l_m - l_pi)*scale
+// (logit level: d0 = (c - l_pi)*scale; tokens outside the mask contribute -E(x)),
+// which is what makes sum_x (r - q) vanish: the refined residual then carries a
+// relative error of ~1e-7 whatever its mass.
 
 // What the difference form needs beside the plain coefficients.
 template <int NCAP>
@@ -192,13 +200,14 @@ __device__ __forceinline__ void eval_f_refined(const Params& p, const float (&x)
         for (int m = 0; m < NCAP; ++m)
           if (m < n && (p.beta_hi[m] != 0.0f || p.beta_lo[m] != 0.0f)) {
             dead = dead || x[m][k] == -INFINITY;
-            const float dv = (x[m][k] - ref[m]) - vp;
+            // (l_m - l_pi) - (ref_m - ref_pi): both differences are exact for nearby rows
+            const float dv = (x[m][k] - lp) - (ref[m] - refq);
             cd = fmaf(p.beta_lo[m], dv, fmaf(p.beta_hi[m], dv, cd));
           }
         cd = dead ? -INFINITY : cd;
       } else {
         const float v1 = x[1][k] - ref[1];
-        cd = fmaf(-p.mu_lo, v1, fmaf(-p.mu_hi, v1, (x[0][k] - ref[0]) - vp));
+        cd = fmaf(-p.mu_lo, v1, fmaf(-p.mu_hi, v1, (x[0][k] - lp) - (ref[0] - refq)));
         cd = in_mask<T>(x[0][k], m0, p.thr32, p.thr64) ? cd : -INFINITY;
       }
       const float d = fmaf(cd, p.scale, -rf.dlse[0]);
@@ -207,6 +216,69 @@ __device__ __forceinline__ void eval_f_refined(const Params& p, const float (&x)
     }
     // (NaN in `far` -- q(x) = 0 -- fails the comparison and keeps the plain value)
     f[k] = (far <= 1.0f) ? fmaxf(q * acc, 0.0f) : plainf[k];
+  }
+}
+
+// First pass of the difference form: this lane's contributions, over one vector, to
+// Q = sum_x E(x) and A[t] = sum_x (E_t(x) - E(x)) for every term t of r (ensemble: the models with
+// weight other than the proposer; logit level: slot 0), E_t being the term's own 2^(. - K).
+template <typename T, int NCAP, int N, int MODE>
+__device__ __forceinline__ void refine_sums(const Params& p, const float (&x)[NCAP][N], int n, int pi, float m0,
+                                            const float (&ref)[NCAP], const Refine<NCAP>& rf, double& Q,
+                                            double (&A)[NCAP]) {
+  float refq = ref[0];
+#pragma unroll
+  for (int m = 1; m < NCAP; ++m) refq = (m == pi) ? ref[m] : refq;
+#pragma unroll
+  for (int k = 0; k < N; ++k) {
+    const float lp = pick_row<NCAP, N>(x, pi, k);
+    const float vp = lp - refq;
+    const float E = fast_exp2(fmaf(vp, p.scale, -rf.off_q));
+    Q += (double)E;
+    if constexpr (MODE == kEns) {
+#pragma unroll
+      for (int m = 0; m < NCAP; ++m)
+        if (m < n && rf.w[m] != 0.0f) {
+          const float d0 = (x[m][k] - lp) * p.scale;
+          // beyond a factor of two nothing cancels: the term's own value minus E (a -inf logit: -E)
+          const float t = (fabsf(d0) <= 1.0f) ? E * exp2m1(d0) : fast_exp2(fmaf(x[m][k], p.scale, -rf.off_q)) - E;
+          A[m] += (double)t;
+        }
+    } else {
+      float cd, c;  // c(x) - l_pi(x) and c(x), both on the shifted logits
+      bool in = true;
+      if constexpr (MODE == kMix) {
+        cd = rf.wsum_m1 * vp;
+        bool dead = false;
+#pragma unroll
+        for (int m = 0; m < NCAP; ++m)
+          if (m < n && (p.beta_hi[m] != 0.0f || p.beta_lo[m] != 0.0f)) {
+            dead = dead || x[m][k] == -INFINITY;
+            // (l_m - l_pi) - (ref_m - ref_pi): both differences are exact for nearby rows
+            const float dv = (x[m][k] - lp) - (ref[m] - refq);
+            cd = fmaf(p.beta_lo[m], dv, fmaf(p.beta_hi[m], dv, cd));
+          }
+        float l[NCAP];
+#pragma unroll
+        for (int m = 0; m < NCAP; ++m) l[m] = x[m][k];
+        c = mix_one<NCAP>(p, n, l, ref);
+        in = !dead;
+      } else {
+        const float v1 = x[1][k] - ref[1];
+        cd = fmaf(-p.mu_lo, v1, fmaf(-p.mu_hi, v1, (x[0][k] - lp) - (ref[0] - refq)));
+        c = contrast(x[0][k], x[1][k], p.mu_hi, p.mu_lo, ref[0], ref[1]);
+        in = in_mask<T>(x[0][k], m0, p.thr32, p.thr64);
+      }
+      const float d0 = cd * p.scale;
+      float t;
+      if (!in)
+        t = -E;
+      else if (fabsf(d0) <= 1.0f)  // false for NaN (a proposer logit of -inf)
+        t = E * exp2m1(d0);
+      else
+        t = fast_exp2(fmaf(c, p.scale, -rf.off_q)) - E;
+      A[0] += (double)t;
+    }
   }
 }
 
@@ -423,9 +495,9 @@ __device__ int draw_token(const Params& p, int b, const SeqPlan& plan, const T* 
 
 // Sampling kernel.  Workgroup index -> (b, c): tiles [c*tpc, (c+1)*tpc) of the
 // sampled position's rows -> tile sums; the last workgroup of b draws the token.
-// REFINE: the variant that can re-evaluate a residual of little mass in its difference form
-// (a kernel of its own because that rare path costs the streaming loop scalar registers).
-template <typename T, bool ALIGNED, int NM, int MODE, bool REFINE>
+// A residual of little mass (r close to q) is evaluated once more in its difference form by the last
+// workgroup of its sequence.
+template <typename T, bool ALIGNED, int NM, int MODE>
 __global__ void __launch_bounds__(kThreads) sample_kernel(Params p) {
   constexpr int N = VecOf<T>::N;
   constexpr bool CONTRASTIVE = MODE == kCd;
@@ -491,14 +563,14 @@ __global__ void __launch_bounds__(kThreads) sample_kernel(Params p) {
   int status = kDrawn;
   if (wave == 0)
     status = draw_token<T, ALIGNED, NCAP, MODE>(p, b, plan, rows, n, coef, off, ref, tile_sum, residual, 0,
-                                                (REFINE && residual) ? kRefineBelow : 0.0, false, no_refine);
+                                                residual ? kRefineBelow : 0.0, false, no_refine);
   if (threadIdx.x == 0) s_flag = status;
   __syncthreads();
   status = s_flag;
   if (status == kDrawn) return;
   __syncthreads();  // s_flag is written again below
 
-  if (REFINE && status == kLittleMass) {
+  if (status == kLittleMass) {
     // r is close to q: this one workgroup evaluates the residual of the whole row once more,
     // in its difference form, and draws from that
     if (threadIdx.x == 0) {
@@ -509,6 +581,41 @@ __global__ void __launch_bounds__(kThreads) sample_kernel(Params p) {
     }
     __syncthreads();
     const Refine<NCAP>& rf = s_rf;
+    // first pass: the differences of the log-normalisers, themselves in difference form
+    {
+      double Q = 0.0, A[NCAP];
+#pragma unroll
+      for (int m = 0; m < NCAP; ++m) A[m] = 0.0;
+      for (int t = wave; t < p.ntiles; t += kWaves) {
+        float x[NCAP][N];
+        tile_load<T, ALIGNED, NCAP>(p, rows, n, t, x);
+        if (t * 64 + lane < p.nvec) refine_sums<T, NCAP, N, MODE>(p, x, n, plan.pi, plan.m0, ref, rf, Q, A);
+      }
+      // the tile sums are not needed any more: their LDS takes the wavefronts' totals
+      __syncthreads();
+      Q = wave_sum(Q);
+      if (lane == 0) tile_sum[wave * (NCAP + 1)] = Q;
+#pragma unroll
+      for (int m = 0; m < NCAP; ++m) {
+        const double a = wave_sum(A[m]);
+        if (lane == 0) tile_sum[wave * (NCAP + 1) + 1 + m] = a;
+      }
+      __syncthreads();
+      if (threadIdx.x == 0) {
+        double q = 0.0;
+        for (int w = 0; w < kWaves; ++w) q += tile_sum[w * (NCAP + 1)];
+#pragma unroll
+        for (int m = 0; m < NCAP; ++m) {
+          double a = 0.0;
+          for (int w = 0; w < kWaves; ++w) a += tile_sum[w * (NCAP + 1) + 1 + m];
+          const double ratio = a / q;  // Z_t / Z_pi - 1
+          const bool used = MODE == kEns ? s_rf.w[m] != 0.0f : m == 0;
+          // (not finite, or not above -1: models that are not close after all; the streamed value stays)
+          if (used && ratio > -1.0 && ratio < INFINITY) s_rf.dlse[m] = (float)(log1p(ratio) * 1.4426950408889634);
+        }
+      }
+      __syncthreads();
+    }
     for (int t = wave; t < p.ntiles; t += kWaves) {
       float f[N];
       tile_weights<T, ALIGNED, NCAP, MODE>(p, rows, n, t, plan.pi, plan.bonus, plan.m0, coef, off, ref, f, true, rf);

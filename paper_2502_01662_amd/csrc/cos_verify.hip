@@ -61,17 +61,22 @@ namespace {
 // host side
 // ---------------------------------------------------------------------------
 
-int g_chunk_vectors = 0;  // 0 = heuristic
-int g_sample_blocks = 0;  // 0 = heuristic
-int g_tail_sequences = -1;  // sequences at the end of the grid with shorter chunks (-1 = heuristic, 0 = none)
-int g_tail_factor = 4;      // how many times shorter
-
-// Optional event ring around the streaming kernel (benchmarks only).
-constexpr int kMaxProfileSlots = 1024;
-hipEvent_t g_ev_start[kMaxProfileSlots], g_ev_stop[kMaxProfileSlots];
-int g_ev_created = 0;   // event pairs that exist
-int g_ev_slots = 0;     // pairs in use (0 = profiling off)
-int g_ev_recorded = 0;  // calls recorded since the last enable
+// Launch-shape overrides of one call (cos_options_t); all zero: the built-in heuristics.
+struct Tune {
+  int chunk_vectors = 0;   // 0 = heuristic
+  int sample_blocks = 0;   // 0 = heuristic
+  int tail_sequences = -1; // sequences at the end of the grid with shorter chunks (-1 = heuristic, 0 = none)
+  int tail_factor = 4;     // how many times shorter
+};
+Tune tune_of(const cos_options_t* o) {
+  Tune t;
+  if (!o) return t;
+  t.chunk_vectors = o->chunk_vectors > 0 ? o->chunk_vectors : 0;
+  t.sample_blocks = o->sample_blocks > 0 ? o->sample_blocks : 0;
+  t.tail_sequences = o->tail_sequences == 0 ? -1 : (o->tail_sequences < 0 ? 0 : o->tail_sequences);
+  t.tail_factor = o->tail_factor == 0 ? 4 : (o->tail_factor > 1 ? o->tail_factor : 1);
+  return t;
+}
 
 struct Plan {
   int nvec, ntiles, nstat;
@@ -143,10 +148,10 @@ int max_splits(int nvec) {
 // Chunks per row.  A workgroup's start-up and hand-off cost is paid per chunk,
 // so chunks are as long as possible: whole rows once there are a few thousand
 // rows, otherwise just enough chunks to fill 256 CUs several times over.
-void choose_split(int rows_total, int nvec, int* S_out, int* cv_out) {
+void choose_split(const Tune& tn, int rows_total, int nvec, int* S_out, int* cv_out) {
   int cv;
-  if (g_chunk_vectors > 0) {
-    cv = g_chunk_vectors;
+  if (tn.chunk_vectors > 0) {
+    cv = tn.chunk_vectors;
   } else {
     long s_want = (3072 + rows_total - 1) / (rows_total > 0 ? rows_total : 1);
     if (s_want < 1) s_want = 1;
@@ -176,22 +181,22 @@ void choose_split(int rows_total, int nvec, int* S_out, int* cv_out) {
 // short; everywhere else chunks stay long (a workgroup's start-up and hand-off are paid per chunk).
 // Measured: half a generation of resident workgroups, cut four times finer, is about the optimum
 // (0.6 % of the streaming kernel at 14336 rows of 512 KB, 3 % at 4608 rows of 256 KB, 5 % at 960 rows).
-void choose_tail(int B, int rows_per_b, int nvec, int Sh, int cvh, int* b_tail, int* St, int* cvt) {
+void choose_tail(const Tune& tn, int B, int rows_per_b, int nvec, int Sh, int cvh, int* b_tail, int* St, int* cvt) {
   *b_tail = B;
   *St = Sh;
   *cvt = cvh;
   constexpr long kResident = 1536;  // workgroups the streaming kernels keep resident (6 per CU)
   const long per_b = (long)rows_per_b * Sh;
-  long K = g_tail_sequences;
+  long K = tn.tail_sequences;
   if (K < 0) K = ((long)B * per_b >= 2 * kResident) ? (kResident / 2 + per_b - 1) / per_b : 0;
-  if (K <= 0 || g_tail_factor <= 1) return;
+  if (K <= 0 || tn.tail_factor <= 1) return;
   if (K > B) K = B;
   const int smax = max_splits(nvec);
-  long s_want = (long)Sh * g_tail_factor;
+  long s_want = (long)Sh * tn.tail_factor;
   if (s_want > smax) s_want = smax;
   int cv = (int)((nvec + s_want - 1) / s_want);
   // one full group of loads per thread, as everywhere (unless the chunk length is dictated)
-  const int cv_min = g_chunk_vectors > 0 ? kThreads : kThreads * kUnroll;
+  const int cv_min = tn.chunk_vectors > 0 ? kThreads : kThreads * kUnroll;
   if (cv < cv_min) cv = cv_min;
   cv = (cv + kThreads - 1) / kThreads * kThreads;
   const int S = (nvec + cv - 1) / cv;
@@ -205,11 +210,11 @@ void choose_tail(int B, int rows_per_b, int nvec, int Sh, int cvh, int* b_tail, 
 struct Split {
   int Sh, cvh, St, cvt, b_tail, stride;
 };
-Split split_for(int n, int B, int window, int nvec, bool ensemble) {
+Split split_for(const Tune& tn, int n, int B, int window, int nvec, bool ensemble) {
   Split sp;
   const int rows_per_b = (ensemble ? n : 1) * window;
-  choose_split(rows_per_b * (B > 0 ? B : 1), nvec, &sp.Sh, &sp.cvh);
-  choose_tail(B, rows_per_b, nvec, sp.Sh, sp.cvh, &sp.b_tail, &sp.St, &sp.cvt);
+  choose_split(tn, rows_per_b * (B > 0 ? B : 1), nvec, &sp.Sh, &sp.cvh);
+  choose_tail(tn, B, rows_per_b, nvec, sp.Sh, sp.cvh, &sp.b_tail, &sp.St, &sp.cvt);
   sp.stride = sp.St > sp.Sh ? sp.St : sp.Sh;
   return sp;
 }
@@ -228,8 +233,8 @@ int alpha_blocks(int B, int gamma, int ntiles) {
 // Sampling workgroups per sequence: about 2048 in total, at least 4 tiles each.  (Finer
 // workgroups at the end of this grid, as choose_tail makes them for the streaming kernels, were
 // measured and do not pay: the kernel is short and its workgroups are nearly all resident at once.)
-void choose_sampling(int B, int ntiles, int* C_out, int* tpc_out) {
-  const int target = g_sample_blocks > 0 ? g_sample_blocks : 2048;
+void choose_sampling(const Tune& tn, int B, int ntiles, int* C_out, int* tpc_out) {
+  const int target = tn.sample_blocks > 0 ? tn.sample_blocks : 2048;
   int C = (target + B - 1) / B;
   const int cmax = (ntiles + 3) / 4;
   if (C > cmax) C = cmax;
@@ -273,6 +278,13 @@ extern "C" {
 
 size_t cos_verify_workspace_bytes(int n, int B, int gamma, int V, cos_dtype_t dt,
                                   cos_combine_t mode) {
+  return cos_verify_workspace_bytes_ex(n, B, gamma, V, dt, mode, nullptr);
+}
+
+size_t cos_verify_workspace_bytes_ex(int n, int B, int gamma, int V, cos_dtype_t dt, cos_combine_t mode,
+                                     const cos_options_t* options) {
+  if (options && options->struct_bytes != sizeof(cos_options_t)) return 0;
+  const Tune tn = tune_of(options);
   if (!shape_ok(n, B, gamma, V)) return 0;
   if (dt != COS_DTYPE_F32 && dt != COS_DTYPE_BF16 && dt != COS_DTYPE_F16) return 0;
   if (mode != COS_COMBINE_ENSEMBLE && mode != COS_COMBINE_CONTRASTIVE && mode != COS_COMBINE_LOGIT_MIX)
@@ -283,7 +295,7 @@ size_t cos_verify_workspace_bytes(int n, int B, int gamma, int V, cos_dtype_t dt
   const int N = dt == COS_DTYPE_F32 ? 4 : 8;
   int S = 1;
   for (int window = 1; window <= gamma + 1; ++window) {
-    const Split sp = split_for(n, B, window, (V + N - 1) / N, mode == COS_COMBINE_ENSEMBLE);
+    const Split sp = split_for(tn, n, B, window, (V + N - 1) / N, mode == COS_COMBINE_ENSEMBLE);
     if (sp.stride > S) S = sp.stride;
   }
   plan_layout(n, B, gamma, V, dt, mode, S, &pl);
@@ -360,7 +372,7 @@ cos_status_t verify_impl(const void* logits, cos_dtype_t dt, int n, int B, int g
     return COS_ERR_NULL;
   const size_t esize = dt == COS_DTYPE_F32 ? 4 : 2;
   if (reinterpret_cast<uintptr_t>(logits) % esize) return COS_ERR_ALIGN;
-  const size_t need = cos_verify_workspace_bytes(n, B, gamma, V, dt, combine_mode);
+  const size_t need = cos_verify_workspace_bytes_ex(n, B, gamma, V, dt, combine_mode, options);
   if ((size_t)(gamma + 1) * (contrastive ? 3 : (mix ? 2 : n)) > kMaxStatsPerSeq) return COS_ERR_SHAPE;
   if (builtin_scratch) {
     if (need > (size_t)COS_NOALLOC_SCRATCH_BYTES) return COS_ERR_SCRATCH;
@@ -376,7 +388,8 @@ cos_status_t verify_impl(const void* logits, cos_dtype_t dt, int n, int B, int g
   const int nvec = (V + N - 1) / N;
   int window = gamma + 1;  // positions per streaming launch
   if (options && options->stop_window > 0 && options->stop_window < window) window = options->stop_window;
-  const Split sp = split_for(n, B, window, nvec, mode == kEns);
+  const Tune tn = tune_of(options);
+  const Split sp = split_for(tn, n, B, window, nvec, mode == kEns);
   Plan pl;
   plan_layout(n, B, gamma, V, dt, combine_mode, sp.stride, &pl);
   if (pl.bytes > workspace_bytes || pl.ntiles > kMaxTiles) return COS_ERR_WORKSPACE;
@@ -393,7 +406,6 @@ cos_status_t verify_impl(const void* logits, cos_dtype_t dt, int n, int B, int g
   p.bonus_idx = options ? options->bonus_idx : nullptr;
   p.num_drafts = options ? options->num_drafts : nullptr;
   p.no_bonus = (options && options->no_bonus) ? 1 : 0;
-  p.refine = (options && options->refine_residual) ? 1 : 0;
   p.u_accept = u_accept;
   p.u_resample = u_resample;
   p.accepted_len = accepted_len;
@@ -423,7 +435,7 @@ cos_status_t verify_impl(const void* logits, cos_dtype_t dt, int n, int B, int g
   p.nvec = pl.nvec;
   p.ntiles = pl.ntiles;
   p.nstat = pl.nstat;
-  choose_sampling(B, pl.ntiles, &p.C, &p.tpc);
+  choose_sampling(tn, B, pl.ntiles, &p.C, &p.tpc);
   for (int m = 0; m < COS_MAX_MODELS; ++m) p.w[m] = m < n ? weights[m] : 0.0;
   p.scale = (float)((double)kLog2e / temperature);
   p.mu_hi = p.mu_lo = 0.0f;
@@ -455,11 +467,10 @@ cos_status_t verify_impl(const void* logits, cos_dtype_t dt, int n, int B, int g
 
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   const bool aligned = (reinterpret_cast<uintptr_t>(logits) % 16 == 0) && (V % N == 0);
-  const size_t lds = (size_t)pl.ntiles * sizeof(double);
-  const bool profile = g_ev_slots > 0;
-  const int slot = profile ? g_ev_recorded % g_ev_slots : 0;
-  hipEvent_t ev_start = profile ? g_ev_start[slot] : nullptr;
-  hipEvent_t ev_stop = profile ? g_ev_stop[slot] : nullptr;
+  // one double per tile; the rare difference-form path also parks a few totals per wavefront there
+  const size_t lds = (size_t)(pl.ntiles > kWaves * (COS_MAX_MODELS + 1) ? pl.ntiles : kWaves * (COS_MAX_MODELS + 1)) * sizeof(double);
+  hipEvent_t ev_start = options ? static_cast<hipEvent_t>(options->event_start) : nullptr;
+  hipEvent_t ev_stop = options ? static_cast<hipEvent_t>(options->event_stop) : nullptr;
 
   // counters in use: one set per streaming launch, the sampling set, and the acceptance-rate sets if wanted
   LaunchPlan lp;
@@ -472,11 +483,7 @@ cos_status_t verify_impl(const void* logits, cos_dtype_t dt, int n, int B, int g
   lp.stream = st;
   lp.ev_start = ev_start;
   lp.ev_stop = ev_stop;
-  const cos_status_t rc = dt == COS_DTYPE_F32   ? run_f32(p, lp)
-                          : dt == COS_DTYPE_F16 ? run_f16(p, lp)
-                                                : run_bf16(p, lp);
-  if (profile) ++g_ev_recorded;
-  return rc;
+  return dt == COS_DTYPE_F32 ? run_f32(p, lp) : (dt == COS_DTYPE_F16 ? run_f16(p, lp) : run_bf16(p, lp));
 }
 
 }  // namespace
@@ -550,37 +557,6 @@ const char* cos_status_string(cos_status_t status) {
   return "unknown status";
 }
 
-int cos_verify_version(void) { return 5; }
-
-cos_status_t cos_profile_enable(int slots) {
-  if (slots < 0 || slots > kMaxProfileSlots) return COS_ERR_SHAPE;
-  while (g_ev_created < slots) {
-    if (hipEventCreate(&g_ev_start[g_ev_created]) != hipSuccess) return COS_ERR_LAUNCH;
-    if (hipEventCreate(&g_ev_stop[g_ev_created]) != hipSuccess) return COS_ERR_LAUNCH;
-    ++g_ev_created;
-  }
-  g_ev_slots = slots;
-  g_ev_recorded = 0;
-  return COS_OK;
-}
-
-int cos_profile_recorded(void) { return g_ev_recorded < g_ev_slots ? g_ev_recorded : g_ev_slots; }
-
-cos_status_t cos_profile_kernel_ms(int index, float* ms) {
-  if (!ms) return COS_ERR_NULL;
-  if (index < 0 || index >= cos_profile_recorded()) return COS_ERR_SHAPE;
-  if (hipEventSynchronize(g_ev_stop[index]) != hipSuccess) return COS_ERR_LAUNCH;
-  if (hipEventElapsedTime(ms, g_ev_start[index], g_ev_stop[index]) != hipSuccess) return COS_ERR_LAUNCH;
-  return COS_OK;
-}
-
-void cos_tune_set_chunk_vectors(int vectors) { g_chunk_vectors = vectors > 0 ? vectors : 0; }
-
-void cos_tune_set_sample_blocks(int blocks) { g_sample_blocks = blocks > 0 ? blocks : 0; }
-
-void cos_tune_set_tail(int sequences, int factor) {
-  g_tail_sequences = sequences < 0 ? -1 : sequences;
-  g_tail_factor = factor > 1 ? factor : 1;
-}
+int cos_verify_version(void) { return 6; }
 
 }  // extern "C"

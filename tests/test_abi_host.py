@@ -26,9 +26,9 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_version_and_status_strings():
-    assert C.cos_verify_version() == 5
+    assert C.cos_verify_version() == 6
     assert C.cos_status_string(0) == "ok"
-    for code in range(-9, 0):
+    for code in range(-10, 0):
         assert C.cos_status_string(code) not in ("ok", "unknown status")
 
 
@@ -136,24 +136,34 @@ def test_cpp_driver_links_the_library_and_validates_its_arguments():
     assert subprocess.run([B.DRIVER, "2", "1", "2", "16", "bf16", "vote"], capture_output=True).returncode == 2
 
 
-def test_workspace_bytes_follow_the_tail_knob():
+def test_workspace_bytes_follow_the_launch_shape_of_the_call():
     """Shorter chunks for the last sequences need more room for chunk partials: the size function and the
-    call must agree on it (the call rejects a workspace sized before the knob was turned)."""
-    shape = (2, 2048, 4, 128256, C.COS_DTYPE_BF16, C.COS_COMBINE_ENSEMBLE)   # whole rows per workgroup without the knob
-    try:
-        C.cos_tune_set_tail(0, 1)
-        plain = C.cos_verify_workspace_bytes(*shape)
-        C.cos_tune_set_tail(8, 16)
-        finer = C.cos_verify_workspace_bytes(*shape)
-        assert finer > plain > 0
-        lib = C.load_library()
-        w = (ctypes.c_double * 2)(0.5, 0.5)
-        call = lambda nbytes: lib.cos_verify(0x1000, 1, 2, 2048, 4, 128256, 0x1000, 0x1000, 0, w, 0x1000, 0x1000,
-                                             0x1000, 0x1000, 0x1000, nbytes, None, None)
-        assert call(plain) == -6                                 # too small for this setting: rejected on the host
-    finally:
-        C.cos_tune_set_tail(-1, 4)
-    assert C.cos_verify_workspace_bytes(*shape) >= plain
+    call agree on it because both take the same options (a workspace sized for other options is rejected)."""
+    shape = (2, 2048, 4, 128256, C.COS_DTYPE_BF16, C.COS_COMBINE_ENSEMBLE)   # whole rows per workgroup by default
+    plain = C.cos_verify_workspace_bytes_ex(*shape, C.LaunchShape(tail_sequences=-1))
+    finer_shape = C.LaunchShape(tail_sequences=8, tail_factor=16)
+    finer = C.cos_verify_workspace_bytes_ex(*shape, finer_shape)
+    assert finer > plain > 0
+    assert C.cos_verify_workspace_bytes_ex(*shape, None) == C.cos_verify_workspace_bytes(*shape) >= plain
+    lib = C.load_library()
+    w = (ctypes.c_double * 2)(0.5, 0.5)
+    opt = C._options(shape=finer_shape)
+    call = lambda nbytes, o: lib.cos_verify_ex(0x1000, 1, 2, 2048, 4, 128256, 0x1000, 0x1000, 0, w, 0x1000, 0x1000,
+                                               0x1000, 0x1000, 0x1000, nbytes, None, o, None)
+    assert call(plain, ctypes.byref(opt)) == -6                  # too small for these options: rejected on the host
+    bad = C._options()
+    bad.struct_bytes = 8
+    assert call(finer, ctypes.byref(bad)) == -9                  # an options struct of another size
+    assert lib.cos_verify_workspace_bytes_ex(*shape, ctypes.byref(bad)) == 0
+
+
+def test_the_library_keeps_no_settings_between_calls():
+    """Every exported function is declared in the header, and none of them sets process-wide state:
+    no cos_tune_* / cos_profile_* symbols exist any more."""
+    lib = C.load_library()
+    for name in ("cos_tune_set_chunk_vectors", "cos_tune_set_sample_blocks", "cos_tune_set_tail", "cos_profile_enable",
+                 "cos_profile_recorded", "cos_profile_kernel_ms"):
+        assert not hasattr(lib, name), name
 
 
 def test_input_checker_validates_its_own_arguments_on_the_host():

@@ -399,35 +399,40 @@ def test_ragged_rows_at_the_c5_shape():
 
 
 # ---------------------------------------------------------------------------
-# refine_residual: r close to q (acceptance rates above 97 %), rejection forced
+# r close to q (acceptance rates above 97 %), rejection forced: the default path, no option set
 # ---------------------------------------------------------------------------
 
-@pytest.mark.parametrize("mode,weights,n,noise", [(C.COS_COMBINE_ENSEMBLE, [0.5, 0.5], 2, 0.03),
-                                                  (C.COS_COMBINE_ENSEMBLE, [0.5, 0.5], 2, 0.003),
-                                                  (C.COS_COMBINE_ENSEMBLE, [0.4, 0.35, 0.25], 3, 0.03),
-                                                  (C.COS_COMBINE_ENSEMBLE, [0.4, 0.35, 0.25], 3, 0.003),
-                                                  (C.COS_COMBINE_CONTRASTIVE, [0.002, 0.0], 2, 0.03),   # mu -> 0: r -> softmax(l_0)
-                                                  (C.COS_COMBINE_LOGIT_MIX, [0.5, 0.5], 2, 0.03)])
-def test_residual_of_nearly_identical_models(mode, weights, n, noise):
-    """Models that differ by a little noise: the residual mass is 1e-2 ... 1e-4 of a probability, far
-    below what term-by-term float32 resolves; with refine_residual every drawn token must still be
-    the float64 reference's (u_accept -> 1 forces the rejections that never happen otherwise).
-    Residual masses of ~1e-2 (noise 0.03) in every mode, ~1e-3 for ensembles, whose normalisers'
-    rounding errors are correlated between nearly identical rows; below that the ~1e-7 accuracy of the
-    float32 normalisers themselves is the limit."""
-    B, gamma, V = 256, 2, 32000
-    inp = _random_inputs(1, B, gamma, V, "f32", seed=5, std=2.5)
-    g = torch.Generator().manual_seed(3)
+def _nearly_identical_models(n, B, gamma, V, noise, seed, dtype="f32", proposer=0):
+    """n models that differ from one base by Gaussian noise of the given size; every first draft is the
+    proposer's favourite token and u_accept -> 1 forces the rejections that hardly ever happen otherwise
+    (a slightly flatter r gives that token less than q does)."""
+    inp = _random_inputs(1, B, gamma, V, "f32", seed=seed, std=2.5)
+    g = torch.Generator().manual_seed(seed + 1)
     base = inp["logits"][0].double().cpu()
-    inp["logits"] = torch.stack([(base + torch.randn(base.shape, generator=g, dtype=torch.float64) * noise).float()
+    tdt = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[dtype]
+    inp["logits"] = torch.stack([(base + torch.randn(base.shape, generator=g, dtype=torch.float64) * noise).to(tdt)
                                  for _ in range(n)]).cuda()
-    inp["proposer_idx"] = torch.zeros(B, dtype=torch.int32).cuda()
+    inp["proposer_idx"] = torch.full((B,), proposer, dtype=torch.int32).cuda()
     inp["u_accept"][:] = 1.0 - 1e-12
-    # the proposer's favourite token: a slightly flatter r gives it less than q does, so it is rejected
-    inp["draft_tokens"][:, 0] = inp["logits"][0, :, 0].argmax(-1).to(torch.int32)
+    inp["draft_tokens"][:, 0] = inp["logits"][proposer, :, 0].argmax(-1).to(torch.int32)
+    return inp
+
+
+@pytest.mark.parametrize("noise", [0.03, 0.003, 0.0003])
+@pytest.mark.parametrize("mode,weights,n", [(C.COS_COMBINE_ENSEMBLE, [0.5, 0.5], 2),
+                                            (C.COS_COMBINE_ENSEMBLE, [0.4, 0.35, 0.25], 3),
+                                            (C.COS_COMBINE_CONTRASTIVE, [0.002, 0.0], 2),   # mu -> 0: r -> softmax(l_0)
+                                            (C.COS_COMBINE_CONTRASTIVE, [0.002, 1e-6], 2),  # the same behind a wide mask
+                                            (C.COS_COMBINE_LOGIT_MIX, [0.5, 0.5], 2)])
+def test_residual_of_nearly_identical_models(mode, weights, n, noise):
+    """Models that differ by a little noise: the residual mass is 1e-2 ... 1e-5 of a probability, far below
+    what term-by-term float32 resolves.  The step evaluates such residuals in their difference form by
+    itself (no option): every drawn token must be the float64 reference's, in every combine mode."""
+    B, gamma, V = 256, 2, 32000
+    inp = _nearly_identical_models(n, B, gamma, V, noise, seed=5, proposer=1 if mode != C.COS_COMBINE_ENSEMBLE else 0)
     diag = C.Diagnostics.allocate(B, gamma, "cuda")
     alen, toks = C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], mode, weights,
-                              inp["u_accept"], inp["u_resample"], diag=diag, refine_residual=True)
+                              inp["u_accept"], inp["u_resample"], diag=diag)
     torch.cuda.synchronize()
     rep = P.compare(inp, mode, weights, alen.cpu().numpy(), toks.cpu().numpy(), diag)
     flags = diag.flags.cpu().numpy()
@@ -435,17 +440,27 @@ def test_residual_of_nearly_identical_models(mode, weights, n, noise):
           f"{int((flags & C.COS_FLAG_RESIDUAL_REFINED != 0).sum())}/{B}, median F {np.median(diag.sample_mass.cpu().numpy()):.2e}", flush=True)
     assert rep.ok, rep.failures[:3]
     assert (flags & C.COS_FLAG_RESIDUAL_REFINED != 0).sum() > B // 4
-    assert rep.excused_accept_ties + rep.excused_cdf_ties <= 3
+    # the residual spreads over most of the vocabulary here, so the 1e-6 windows around its 32000 CDF edges
+    # cover several percent of [0, 1): a few draws land in one and may take the neighbouring token
+    assert rep.excused_accept_ties + rep.excused_cdf_ties <= B // 50
 
 
-def test_refine_residual_changes_nothing_when_the_residual_has_mass():
-    w = W.C3.scaled(B=16)
-    inp = W.generate(w, device="cuda")
-    a = P.run_gpu(inp, w.mode, w.weights)
-    alen, toks = C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], w.mode, w.weights,
-                              inp["u_accept"], inp["u_resample"], refine_residual=True)
-    torch.cuda.synchronize()
-    assert np.array_equal(a[0], alen.cpu().numpy()) and np.array_equal(a[1], toks.cpu().numpy())
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_residual_of_nearly_identical_models_in_16_bit_formats(dtype):
+    """The same with stored 16-bit logits, where 'nearly identical' means many logits are bit-identical and
+    the others differ by one step of the format."""
+    B, gamma, V = 128, 2, 40000
+    for mode, weights, n in ((C.COS_COMBINE_ENSEMBLE, [0.3, 0.3, 0.4], 3), (C.COS_COMBINE_LOGIT_MIX, [0.7, 0.3], 2)):
+        inp = _nearly_identical_models(n, B, gamma, V, 0.004, seed=11, dtype=dtype)
+        diag = C.Diagnostics.allocate(B, gamma, "cuda")
+        alen, toks = C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], mode, weights,
+                                  inp["u_accept"], inp["u_resample"], diag=diag)
+        torch.cuda.synchronize()
+        rep = P.compare(inp, mode, weights, alen.cpu().numpy(), toks.cpu().numpy(), diag)
+        print(f"[parity] nearly identical {dtype} models, mode {mode}: {rep.summary()}, median F "
+              f"{np.median(diag.sample_mass.cpu().numpy()):.2e}", flush=True)
+        assert rep.ok, rep.failures[:3]
+        assert rep.excused_accept_ties + rep.excused_cdf_ties <= 3, rep.summary()
 
 
 # ---------------------------------------------------------------------------

@@ -45,8 +45,8 @@ def _check(name, inp, mode, weights, rows=None):
 # ---------------------------------------------------------------------------
 
 def test_c1_ensemble_f32_alternating_proposer():
-    """B=1, gamma=5, V=32000 float32; fresh tensors and the other proposer at every step."""
-    for step in range(12):
+    """B=1, gamma=5, V=32000 float32; fresh tensors and the other proposer at every step: all 100 steps."""
+    for step in range(100):
         inp = W.generate(W.C1, device="cuda", step=step)
         assert int(inp["proposer_idx"][0]) == step % 2
         _check(f"c1 step {step}", inp, W.C1.mode, W.C1.weights)
@@ -77,31 +77,37 @@ def test_c5_four_model_reduced_batch():
     _check("c5 B=24", inp, W.C5.mode, W.C5.weights)
 
 
-def test_c4_full_size_sampled_rows():
-    """Full B=256 launch (the configuration the benchmark times); the oracle checks a sample of rows."""
-    inp = W.generate(W.C4, device="cuda")
-    rows = list(range(0, 256, 11)) + [255]
-    _check("c4 full, sampled rows", inp, W.C4.mode, W.C4.weights, rows=rows)
-
-
-def test_c5_full_size_sampled_rows():
-    inp = W.generate(W.C5, device="cuda")
-    rows = list(range(0, 512, 23)) + [511]
-    alen, toks, diag, _ = _check("c5 full, sampled rows", inp, W.C5.mode, W.C5.weights, rows=rows)
-    # properties that hold at any size, on every row
-    g = W.C5.gamma
+def _properties_on_every_row(w, inp, alen, toks, diag):
+    """What holds at any size, checked without the oracle."""
+    g = w.gamma
     assert alen.min() >= 0 and alen.max() <= g
     drafts = inp["draft_tokens"].cpu().numpy()
-    for b in range(W.C5.B):
+    for b in range(w.B):
         a = alen[b]
         assert np.array_equal(toks[b, :a], drafts[b, :a])
-        assert 0 <= toks[b, a] < W.C5.V
+        assert 0 <= toks[b, a] < w.V
         assert np.all(toks[b, a + 1:] == -1)
     lo, hi = diag.cdf_lo.cpu().numpy(), diag.cdf_hi.cpu().numpy()
     u = inp["u_resample"].cpu().numpy()
     assert np.all(lo <= u + 1e-9) and np.all(u < hi + 1e-9)
-    # Thm 3.2-style sanity on the accept statistics: mean accepted length is plausible and varied
     assert len(set(alen.tolist())) >= 3
+
+
+def test_c4_full_size_every_row():
+    """Full B=256 launch (the launch configuration the benchmark times): all 256 rows against the oracle,
+    lengths, tokens, r(d) and q(d)."""
+    inp = W.generate(W.C4, device="cuda")
+    alen, toks, diag, rep = _check("c4 full, every row", inp, W.C4.mode, W.C4.weights)
+    assert rep.rows == W.C4.B
+    _properties_on_every_row(W.C4, inp, alen, toks, diag)
+
+
+def test_c5_full_size_every_row():
+    """Full B=512 launch, 7.34 GB of logits: all 512 rows against the oracle."""
+    inp = W.generate(W.C5, device="cuda")
+    alen, toks, diag, rep = _check("c5 full, every row", inp, W.C5.mode, W.C5.weights)
+    assert rep.rows == W.C5.B
+    _properties_on_every_row(W.C5, inp, alen, toks, diag)
 
 
 # ---------------------------------------------------------------------------
@@ -155,7 +161,7 @@ def test_unaligned_base_pointer_and_odd_vocabulary_in_every_mode(dtype):
         _check(f"unaligned {dtype} n={n} mode={mode}", inp, mode, w)
         alpha = torch.empty((5, 3), dtype=torch.float64, device="cuda")
         C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], mode, w, inp["u_accept"],
-                     inp["u_resample"], alpha=alpha, refine_residual=True)
+                     inp["u_resample"], alpha=alpha)
         torch.cuda.synchronize()
         a = alpha.cpu().numpy()
         assert np.all((a > 0) & (a <= 1 + 1e-9))
@@ -327,11 +333,8 @@ def test_results_do_not_depend_on_chunking_or_repeat():
     inp = W.generate(W.C3.scaled(B=6), device="cuda")
     ref = None
     for cv in (0, 256, 1024, 8192, 0):
-        C.cos_tune_set_chunk_vectors(cv)
-        try:
-            alen, toks, diag = P.run_gpu(inp, W.C3.mode, W.C3.weights)
-        finally:
-            C.cos_tune_set_chunk_vectors(0)
+        inp["shape"] = C.LaunchShape(chunk_vectors=cv)
+        alen, toks, diag = P.run_gpu(inp, W.C3.mode, W.C3.weights)
         if ref is None:
             ref = (alen, toks)
         assert np.array_equal(alen, ref[0]) and np.array_equal(toks, ref[1]), cv
@@ -350,26 +353,22 @@ def test_shorter_chunks_for_the_last_sequences_of_the_grid(mode, weights, n):
         c = inp["logits"][0, :, :gamma].float() - (0.5 if mode == C.COS_COMBINE_CONTRASTIVE else 0.0) * inp["logits"][1, :, :gamma].float()
         inp["draft_tokens"][::2] = c.argmax(-1).to(torch.int32)[::2]
     ref = None
-    try:
-        C.cos_tune_set_chunk_vectors(1024)                      # several chunks per row at this small size
-        for seqs, factor in ((0, 1), (3, 8), (7, 2), (17, 4), (40, 3), (100, 16), (-1, 4)):
-            C.cos_tune_set_tail(seqs, factor)
-            for window in (0, 1):
-                inp["stop_window"] = window
-                alen, toks, _, _ = _check(f"tail {seqs} x{factor}, window {window}, mode {mode}", inp, mode, weights)
-                if ref is None:
-                    ref = (alen, toks)
-                assert np.array_equal(alen, ref[0]) and np.array_equal(toks, ref[1]), (seqs, factor, window)
-            if mode != C.COS_COMBINE_ENSEMBLE:
-                a, t = C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], mode, weights,
-                                    inp["u_accept"], inp["u_resample"], greedy=True)
-                torch.cuda.synchronize()
-                st, wl, wt = O.verify_greedy(W.host_logits(inp["logits"]), O.DTYPE_BF16, inp["draft_tokens"].cpu().numpy(),
-                                             weights, mode=mode)
-                assert st == 0 and np.array_equal(a.cpu().numpy(), wl) and np.array_equal(t.cpu().numpy(), wt), (seqs, factor)
-    finally:
-        C.cos_tune_set_tail(-1, 4)
-        C.cos_tune_set_chunk_vectors(0)
+    # tail_sequences: < 0 none, 0 the built-in choice; 1024 vectors: several chunks per row at this small size
+    for seqs, factor in ((-1, 0), (3, 8), (7, 2), (17, 4), (40, 3), (100, 16), (0, 0)):
+        inp["shape"] = C.LaunchShape(chunk_vectors=1024, tail_sequences=seqs, tail_factor=factor)
+        for window in (0, 1):
+            inp["stop_window"] = window
+            alen, toks, _, _ = _check(f"tail {seqs} x{factor}, window {window}, mode {mode}", inp, mode, weights)
+            if ref is None:
+                ref = (alen, toks)
+            assert np.array_equal(alen, ref[0]) and np.array_equal(toks, ref[1]), (seqs, factor, window)
+        if mode != C.COS_COMBINE_ENSEMBLE:
+            a, t = C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], mode, weights,
+                                inp["u_accept"], inp["u_resample"], greedy=True, shape=inp["shape"])
+            torch.cuda.synchronize()
+            st, wl, wt = O.verify_greedy(W.host_logits(inp["logits"]), O.DTYPE_BF16, inp["draft_tokens"].cpu().numpy(),
+                                         weights, mode=mode)
+            assert st == 0 and np.array_equal(a.cpu().numpy(), wl) and np.array_equal(t.cpu().numpy(), wt), (seqs, factor)
 
 
 def test_workspace_can_be_reused_and_holds_garbage():
