@@ -207,6 +207,10 @@ cos_status_t cos_verify(const void *logits, cos_dtype_t dt, int n, int B, int ga
  *               The workspace a call needs depends on chunk_vectors and the tail
  *               fields: size it with cos_verify_workspace_bytes_ex and the same
  *               options.
+ * two_pass_mask non-zero: the masked contrastive mode (alpha_cd > 0) takes its older
+ *               route -- one pass for the expert maxima, one for the masked statistic,
+ *               the sampling kernel -- instead of the single read with candidate lists.
+ *               Same outputs up to near-ties; kept for comparison and tests.
  * event_start, event_stop
  *               hipEvent_t handles created by the caller, or NULL.  The call records
  *               event_start on its stream just before its streaming kernel(s) -- the
@@ -227,6 +231,7 @@ typedef struct cos_options_t {
   int sample_blocks;
   int tail_sequences;
   int tail_factor;
+  int two_pass_mask;
   void *event_start;
   void *event_stop;
 } cos_options_t;

@@ -10,8 +10,6 @@ SOURCES = [os.path.join(_PKG, "csrc", f) for f in
            ("cos_verify.hip", "cos_kernels_bf16.hip", "cos_kernels_f32.hip", "cos_kernels_f16.hip")]
 INCLUDE = os.path.join(_ROOT, "include")
 LIBRARY = os.path.join(_PKG, "libcosverify.so")
-PROBE_SOURCE = os.path.join(_PKG, "csrc", "hbm_probe.hip")
-PROBE = os.path.join(_PKG, "hbm_probe")
 DRIVER_SOURCE = os.path.join(_PKG, "csrc", "cos_verify_driver.hip")
 DRIVER = os.path.join(_PKG, "cos_verify_driver")
 
@@ -59,19 +57,9 @@ def build_library(verbose: bool = False) -> str:
     return LIBRARY
 
 
-def build_probe(verbose: bool = False) -> str:
-    """The copy/read calibration program (counter scaling, achievable bandwidth)."""
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
-           "-packed-fp32-ops", "-o", PROBE, PROBE_SOURCE]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True)
-    return PROBE
-
-
 def build_driver(verbose: bool = False) -> str:
-    """The plain C++ caller of the C ABI (timing and profiler runs without Python in the process)."""
+    """The plain C++ caller of the C ABI (timing and profiler runs without Python in the process; its
+    `calibrate` mode holds the copy/read kernels that scale the profiler's byte counters)."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
            "-packed-fp32-ops", "-I", INCLUDE, "-o", DRIVER, DRIVER_SOURCE, "-L", _PKG, "-lcosverify",
@@ -84,5 +72,4 @@ def build_driver(verbose: bool = False) -> str:
 
 if __name__ == "__main__":
     print(build_library(verbose=True))
-    print(build_probe(verbose=True))
     print(build_driver(verbose=True))

@@ -34,12 +34,40 @@ constexpr int kEns = 0;  // Eq. (4): r = sum_m w_m softmax(l_m)
 constexpr int kCd = 1;   // Eq. (5) with the plausibility mask
 constexpr int kMix = 2;  // Eq. (3), logit level: r = softmax(sum_m beta_m l_m)
 
+// A value that one workgroup hands to another inside one launch.  It can only be written by
+// publish() -- an agent-scope atomic store, which gfx950 executes as a write-through store
+// (global_store ... sc1) -- and only be read by read() -- an agent-scope atomic load
+// (global_load ... sc1), which is served coherently at agent scope and never from a line another
+// compute die's writes could have made stale.  There is no other access to the member, so a plain
+// store or load of hand-off data (which the hand-off below would not cover) does not compile.
+// Protocol (see wait_stores / arrive_last): publish, wait for the stores' completion, bump the
+// counter; the workgroup that sees the last count reads.
+template <typename U>
+class HandOff {
+ public:
+#if defined(__HIPCC__)
+  __device__ __forceinline__ void publish(U v) { __hip_atomic_store(&v_, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+  __device__ __forceinline__ U read() const { return __hip_atomic_load(&v_, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+#endif
+ private:
+  U v_;
+};
+
 // One partial softmax statistic: Z = sum_x 2^(l(x)*log2e - o) over a chunk.
 struct Partial {
-  double Z;
-  int o;
+  HandOff<double> Z;
+  HandOff<int> o;
   int pad;
 };
+static_assert(sizeof(Partial) == 16, "two partials per 32 bytes");
+
+// A token that may lie in the plausibility mask of Eq. (5), with its two logits (masked contrastive
+// mode: what the streaming kernel keeps of a row beside its statistics).
+struct Cand {
+  int idx;
+  float l0, l1;
+};
+constexpr int kCandChunk = 256;  // candidates a chunk can leave in the workspace
 
 // What the streaming kernel leaves for the sampling kernel, per sequence.
 struct SeqPlan {
@@ -70,13 +98,16 @@ struct Params {
                       // arrivals, [B][gamma] acceptance-rate arrivals
   Partial* partials;  // [B][gamma+1][nstat][S]
   float* rowmax;      // contrastive: [B][gamma+1][S] partial maxima of the expert row
+  Cand* cand;         // masked contrastive, one-pass: [B][gamma+1][S][cand_cap] candidates of every chunk
+  int* cand_count;    //   [B][gamma+1][S] how many (-1: they did not fit)
+  int cand_cap;
   SeqPlan* plans;     // [B]
-  double* tile_sums;  // [B][ntiles]
+  HandOff<double>* tile_sums;  // [B][ntiles]
   // acceptance-rate output (optional)
   double* alpha;           // [B][gamma] out, or NULL
   double* lse_all;         // [B][gamma+1][nstat] log2-sum-exp2 of every position
   float* rowmax_all;       // contrastive: [B][gamma+1] expert maxima
-  double* alpha_partials;  // [B][gamma][CA]
+  HandOff<double>* alpha_partials;  // [B][gamma][CA]
   int CA;                  // acceptance-rate workgroups per (sequence, position)
   int tpa;                 // tiles per acceptance-rate workgroup
   int S;              // stride of the per-chunk arrays: the larger of Sh and St
@@ -111,6 +142,7 @@ struct LaunchPlan {
   int mode;         // kEns, kCd or kMix
   int window;       // positions per streaming launch
   int greedy;       // temperature 0: one argmax kernel instead
+  int onepass;      // masked contrastive mode in one read of the logits (candidate lists), no counters
   int aligned;      // every row starts on a 16-byte boundary and V is a multiple of the vector width
   int counters;     // arrival counters (ints, with their stride) the fill kernel clears
   size_t lds;       // dynamic LDS of the sampling kernel (one double per tile)
@@ -232,21 +264,22 @@ __device__ __forceinline__ double wave_inclusive_scan(double v) {
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-template <typename U>
-__device__ __forceinline__ void store_agent(U* p, U v) {
-  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-template <typename U>
-__device__ __forceinline__ U load_agent(const U* p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
-// Wait until this wavefront's outstanding stores have completed.
+// Wait until this wavefront's outstanding vector-memory operations have completed (vmcnt counts
+// them down as they complete; for a write-through store that is the acknowledgement from the
+// memory side it was written through to).  After a wavefront's publish() calls this is the release
+// half of the hand-off: what it published is in place, for every compute die, before the wavefront
+// goes on to the barrier and the counter bump of arrive_last().  It is the instruction sequence
+// the compiler emits for an agent-scope release minus the cache write-back (buffer_wbl2), which
+// only serves plain stores that may still sit dirty in a cache -- HandOff has none.
 __device__ __forceinline__ void wait_stores() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 // Last-arrival test.  Every wavefront must have called wait_stores() after its
 // hand-off stores.  Returns true in every thread of exactly one workgroup per
 // counter: the one that arrives after all `total` workgroups have published.
+// The counter is bumped by an agent-scope atomic add, executed where every compute die's atomics
+// on that address are executed, so exactly one workgroup sees total - 1.  That workgroup's reads
+// come after the barrier that follows the add's returned value: they cannot be issued earlier, and
+// being agent-scope loads (HandOff::read) they need no cache invalidation in front of them.
 __device__ __forceinline__ bool arrive_last(int* counter, int total, int* s_flag) {
   __syncthreads();
   if (threadIdx.x == 0) {

@@ -7,6 +7,7 @@
 #include "cos_device.h"
 #include "cos_stats.h"
 #include "cos_sample.h"
+#include "cos_cand.h"
 
 namespace {
 
@@ -105,6 +106,29 @@ cos_status_t launch_all(Params p, int mode, int window, size_t lds, hipStream_t 
                         : launch_acceptance_rate<T, ALIGNED, kCd>(p, st);
 }
 
+// Masked contrastive mode in one read of the logits: per window the streaming kernel (statistics of the
+// proposer rows, chunk maxima of the expert rows, candidates of the mask), then one finishing workgroup
+// per sequence.  No arrival counters, no fill kernel, no sampling or acceptance-rate kernel.
+template <typename T, bool ALIGNED>
+cos_status_t launch_onepass(Params p, const LaunchPlan& lp) {
+  const dim3 block(kThreads);
+  const int g1 = p.gamma + 1;
+  if (lp.ev_start) (void)hipEventRecord(lp.ev_start, lp.stream);
+  p.win = 0;
+  for (int j0 = 0; j0 < g1; j0 += lp.window, ++p.win) {
+    p.j0 = j0;
+    p.nj = (j0 + lp.window <= g1) ? lp.window : g1 - j0;
+    const long blocks = stream_blocks(p, p.nj);
+    if (blocks <= 0 || blocks > 0x7fffffffL) return COS_ERR_SHAPE;
+    hipLaunchKernelGGL((contrastive_onepass_kernel<T, ALIGNED>), dim3((unsigned)blocks), block, 0, lp.stream, p);
+    if (p.win == 0 && j0 + lp.window >= g1 && lp.ev_stop) (void)hipEventRecord(lp.ev_stop, lp.stream);
+    hipLaunchKernelGGL((contrastive_finish_kernel<T, ALIGNED>), dim3((unsigned)p.B), block, lp.lds, lp.stream, p);
+    if (hipGetLastError() != hipSuccess) return COS_ERR_LAUNCH;
+  }
+  if (p.win > 1 && lp.ev_stop) (void)hipEventRecord(lp.ev_stop, lp.stream);
+  return COS_OK;
+}
+
 // Temperature 0: the expert maxima (contrastive with a mask only), then one argmax kernel.
 template <typename T, bool ALIGNED>
 cos_status_t launch_greedy(Params p, const LaunchPlan& lp) {
@@ -136,6 +160,7 @@ cos_status_t launch_greedy(Params p, const LaunchPlan& lp) {
 // Everything one call enqueues: the fill kernel, then the kernels of the mode.
 template <typename T>
 cos_status_t run_kernels(Params p, const LaunchPlan& lp) {
+  if (lp.onepass) return lp.aligned ? launch_onepass<T, true>(p, lp) : launch_onepass<T, false>(p, lp);
   // The masked contrastive mode starts with a kernel that uses neither counters nor plans (the expert
   // maxima): it clears them on its way, one launch less.
   p.fill_count = (lp.mode == kCd && p.masked) ? lp.counters : 0;

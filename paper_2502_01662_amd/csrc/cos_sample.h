@@ -493,72 +493,18 @@ __device__ int draw_token(const Params& p, int b, const SeqPlan& plan, const T* 
   return kDrawn;
 }
 
-// Sampling kernel.  Workgroup index -> (b, c): tiles [c*tpc, (c+1)*tpc) of the
-// sampled position's rows -> tile sums; the last workgroup of b draws the token.
-// A residual of little mass (r close to q) is evaluated once more in its difference form by the last
-// workgroup of its sequence.
-template <typename T, bool ALIGNED, int NM, int MODE>
-__global__ void __launch_bounds__(kThreads) sample_kernel(Params p) {
+// With every tile sum of the sampled position in tile_sum (LDS), the whole workgroup draws the
+// sequence's token: the scan and the inverse CDF, and the two rare endings -- a residual of little
+// mass (r close to q) is evaluated once more in its difference form, a residual without mass falls
+// back to r.  Each ending recomputes every tile sum in this one workgroup.
+template <typename T, bool ALIGNED, int NCAP, int MODE>
+__device__ __forceinline__ void finish_draw(const Params& p, int b, const SeqPlan& plan, const T* const (&rows)[NCAP],
+                                            int n, float (&coef)[NCAP], float (&off)[NCAP], const float (&ref)[NCAP],
+                                            double* tile_sum, int& s_flag, Refine<NCAP>& s_rf) {
   constexpr int N = VecOf<T>::N;
-  constexpr bool CONTRASTIVE = MODE == kCd;
-  // register rows; the logit mix keeps its two coefficients in slots 0 and 1
-  constexpr int NCAP = CONTRASTIVE ? 2 : (NM ? (MODE == kMix && NM < 2 ? 2 : NM) : COS_MAX_MODELS);
-  constexpr int TU = NCAP <= 4 ? 4 : 1;  // tiles in flight per wavefront
-  extern __shared__ double tile_sum[];
-  __shared__ int s_flag;
-  // parameters of the rarely used difference form: kept in LDS, not in scalar registers, which
-  // the streaming loop below needs for itself
-  __shared__ Refine<NCAP> s_rf;
-
-  const int b = blockIdx.x / p.C;
-  const int c = blockIdx.x - b * p.C;
   const int lane = lane_id();
   const int wave = threadIdx.x >> 6;
-  const int n = CONTRASTIVE ? 2 : (NM ? NM : p.n);
-  const SeqPlan plan = p.plans[b];
-  if (plan.skip) return;  // every draft accepted, no extra token: nothing to draw
-  // A verifier bonus reads that one model's row only (the others carry a zero
-  // coefficient and may hold anything, so every slot points at the valid row).
-  const bool one_row = MODE == kEns && plan.residual == 0 && plan.bonus >= 0;
-  const T* rows[NCAP];
-#pragma unroll
-  for (int m = 0; m < NCAP; ++m)
-    rows[m] = row_ptr<T>(p, one_row ? plan.bonus : (m < n ? m : 0), b, plan.jstar);
-  float coef[NCAP], off[NCAP];
-  plan_coefficients<NCAP, MODE>(p, plan, plan.residual != 0, n, coef, off);
-  float ref[NCAP];  // per-row reference of the logit-level combinations (unused by the ensemble)
-#pragma unroll
-  for (int m = 0; m < NCAP; ++m) ref[m] = (MODE != kEns && m < n) ? row_reference<T>(rows[m]) : 0.0f;
-
   const Refine<NCAP> no_refine = {};  // the plain, term-by-term evaluation
-  double* sums = p.tile_sums + (size_t)b * p.ntiles;
-  const int tb = c * p.tpc;
-  const int te = min(tb + p.tpc, p.ntiles);
-  // wavefront w takes tiles tb + w, tb + w + kWaves, ...; TU of them are in flight at once
-  for (int t = tb + wave; t < te; t += kWaves * TU) {
-    float x[TU][NCAP][N];
-#pragma unroll
-    for (int i = 0; i < TU; ++i)
-      tile_load<T, ALIGNED, NCAP>(p, rows, n, min(t + i * kWaves, te - 1), x[i]);
-#pragma unroll
-    for (int i = 0; i < TU; ++i) {
-      const int ti = t + i * kWaves;
-      float f[N];
-      tile_eval<T, NCAP, MODE>(p, x[i], n, min(ti, te - 1), plan.pi, plan.bonus, plan.m0, coef,
-                               off, ref, f, false, no_refine);
-      const double ts = wave_sum_to_lane63(lane_mass<N>(f));
-      if (lane == 63 && ti < te) tile_sum[ti - tb] = ts;  // staged in LDS
-    }
-  }
-  __syncthreads();
-  // publish this workgroup's tile sums with coalesced write-through stores
-  for (int i = threadIdx.x; i < te - tb; i += kThreads) store_agent(sums + tb + i, tile_sum[i]);
-  wait_stores();
-  if (!arrive_last(p.counters + ((size_t)p.nwin * p.B + b) * kCtrStride, p.C, &s_flag)) return;
-
-  // last workgroup of this sequence: all tile sums are published
-  for (int t = threadIdx.x; t < p.ntiles; t += kThreads) tile_sum[t] = load_agent(sums + t);
-  __syncthreads();
   const bool residual = plan.residual != 0;
   int status = kDrawn;
   if (wave == 0)
@@ -645,6 +591,75 @@ __global__ void __launch_bounds__(kThreads) sample_kernel(Params p) {
   if (wave == 0)
     draw_token<T, ALIGNED, NCAP, MODE>(p, b, plan, rows, n, coef, off, ref, tile_sum, false,
                                        COS_FLAG_RESIDUAL_FALLBACK, 0.0, false, no_refine);
+}
+
+// Sampling kernel.  Workgroup index -> (b, c): tiles [c*tpc, (c+1)*tpc) of the
+// sampled position's rows -> tile sums; the last workgroup of b draws the token.
+// A residual of little mass (r close to q) is evaluated once more in its difference form by the last
+// workgroup of its sequence.
+template <typename T, bool ALIGNED, int NM, int MODE>
+__global__ void __launch_bounds__(kThreads) sample_kernel(Params p) {
+  constexpr int N = VecOf<T>::N;
+  constexpr bool CONTRASTIVE = MODE == kCd;
+  // register rows; the logit mix keeps its two coefficients in slots 0 and 1
+  constexpr int NCAP = CONTRASTIVE ? 2 : (NM ? (MODE == kMix && NM < 2 ? 2 : NM) : COS_MAX_MODELS);
+  constexpr int TU = NCAP <= 4 ? 4 : 1;  // tiles in flight per wavefront
+  extern __shared__ double tile_sum[];
+  __shared__ int s_flag;
+  // parameters of the rarely used difference form: kept in LDS, not in scalar registers, which
+  // the streaming loop below needs for itself
+  __shared__ Refine<NCAP> s_rf;
+
+  const int b = blockIdx.x / p.C;
+  const int c = blockIdx.x - b * p.C;
+  const int lane = lane_id();
+  const int wave = threadIdx.x >> 6;
+  const int n = CONTRASTIVE ? 2 : (NM ? NM : p.n);
+  const SeqPlan plan = p.plans[b];
+  if (plan.skip) return;  // every draft accepted, no extra token: nothing to draw
+  // A verifier bonus reads that one model's row only (the others carry a zero
+  // coefficient and may hold anything, so every slot points at the valid row).
+  const bool one_row = MODE == kEns && plan.residual == 0 && plan.bonus >= 0;
+  const T* rows[NCAP];
+#pragma unroll
+  for (int m = 0; m < NCAP; ++m)
+    rows[m] = row_ptr<T>(p, one_row ? plan.bonus : (m < n ? m : 0), b, plan.jstar);
+  float coef[NCAP], off[NCAP];
+  plan_coefficients<NCAP, MODE>(p, plan, plan.residual != 0, n, coef, off);
+  float ref[NCAP];  // per-row reference of the logit-level combinations (unused by the ensemble)
+#pragma unroll
+  for (int m = 0; m < NCAP; ++m) ref[m] = (MODE != kEns && m < n) ? row_reference<T>(rows[m]) : 0.0f;
+
+  const Refine<NCAP> no_refine = {};  // the plain, term-by-term evaluation
+  HandOff<double>* sums = p.tile_sums + (size_t)b * p.ntiles;
+  const int tb = c * p.tpc;
+  const int te = min(tb + p.tpc, p.ntiles);
+  // wavefront w takes tiles tb + w, tb + w + kWaves, ...; TU of them are in flight at once
+  for (int t = tb + wave; t < te; t += kWaves * TU) {
+    float x[TU][NCAP][N];
+#pragma unroll
+    for (int i = 0; i < TU; ++i)
+      tile_load<T, ALIGNED, NCAP>(p, rows, n, min(t + i * kWaves, te - 1), x[i]);
+#pragma unroll
+    for (int i = 0; i < TU; ++i) {
+      const int ti = t + i * kWaves;
+      float f[N];
+      tile_eval<T, NCAP, MODE>(p, x[i], n, min(ti, te - 1), plan.pi, plan.bonus, plan.m0, coef,
+                               off, ref, f, false, no_refine);
+      const double ts = wave_sum_to_lane63(lane_mass<N>(f));
+      if (lane == 63 && ti < te) tile_sum[ti - tb] = ts;  // staged in LDS
+    }
+  }
+  __syncthreads();
+  // publish this workgroup's tile sums with coalesced write-through stores
+  for (int i = threadIdx.x; i < te - tb; i += kThreads) sums[tb + i].publish(tile_sum[i]);
+  wait_stores();
+  if (!arrive_last(p.counters + ((size_t)p.nwin * p.B + b) * kCtrStride, p.C, &s_flag)) return;
+
+  // last workgroup of this sequence: all tile sums are published
+  for (int t = threadIdx.x; t < p.ntiles; t += kThreads) tile_sum[t] = sums[t].read();
+  __syncthreads();
+  finish_draw<T, ALIGNED, NCAP, MODE>(p, b, plan, rows, n, coef, off, ref, tile_sum, s_flag, s_rf);
 }
 
 // Acceptance-rate kernel (optional): alpha = sum_x min(q(x), r(x)) of Eq. (7) for
@@ -743,18 +758,18 @@ __global__ void __launch_bounds__(kThreads) acceptance_rate_kernel(Params p) {
   const double ws = wave_sum(acc);
   if (lane == 0) wsum[wave] = ws;
   __syncthreads();
-  double* parts = p.alpha_partials + ((size_t)b * p.gamma + j) * p.CA;
+  HandOff<double>* parts = p.alpha_partials + ((size_t)b * p.gamma + j) * p.CA;
   if (threadIdx.x == 0) {
     double tot = 0.0;
     for (int w = 0; w < kWaves; ++w) tot += wsum[w];
-    store_agent(parts + c, tot);
+    parts[c].publish(tot);
     wait_stores();
   }
   int* counter = p.counters + ((size_t)(p.nwin + 1) * p.B + (size_t)b * p.gamma + j) * kCtrStride;
   if (!arrive_last(counter, p.CA, &s_flag)) return;
   if (threadIdx.x == 0) {
     double tot = 0.0;
-    for (int i = 0; i < p.CA; ++i) tot += load_agent(parts + i);
+    for (int i = 0; i < p.CA; ++i) tot += parts[i].read();
     p.alpha[(size_t)b * p.gamma + j] = tot;
   }
 }

@@ -234,13 +234,13 @@ __device__ __forceinline__ void store_partial(const WaveStat* ws, int slot, Part
     const WaveStat& s = ws[slot * kWaves + w];
     if (s.z > 0.0) z += ldexp(s.z, s.o - omax);
   }
-  store_agent(&out->Z, z);
-  store_agent(&out->o, omax);
+  out->Z.publish(z);
+  out->o.publish(omax);
 }
 
 __device__ __forceinline__ void store_empty_partial(Partial* out) {
-  store_agent(&out->Z, 0.0);
-  store_agent(&out->o, kNoOffset);
+  out->Z.publish(0.0);
+  out->o.publish(kNoOffset);
 }
 
 // ---------------------------------------------------------------------------
@@ -251,100 +251,133 @@ struct DecideShared {
   double lse2[kMaxStatsPerSeq];     // log2-sum-exp2 per (position, statistic)
   float rowmax[COS_MAX_GAMMA + 1];  // contrastive: expert maximum per position
   int accept[COS_MAX_GAMMA + 1];
+  // the outcome (written by thread 0 of decide_outcome): -1 = every draft of the window accepted and the
+  // bonus position is not in it
+  int jstar, residual, pi, bonus, skip;
 };
 
-// Decides the window [j0, j0+nj) of a sequence that no earlier window has
-// decided.  The sequence stays undecided if every draft of the window is
-// accepted and the window does not contain the bonus position.
+// What one thread brings in for its draft position before the statistics are combined: the draft
+// token, its proposer, its uniform, the n logits at the token and the rows' references.
+struct DraftGather {
+  int d, pi;
+  double u_acc;
+  double lgat[COS_MAX_MODELS], rgat[COS_MAX_MODELS];
+};
+
+// Thread tid < ndraft gathers for position j0 + tid.  These loads do not depend on the statistics, so
+// they go out first and their latency (draft token, then the n logits at it) overlaps the combine.
+// Two steps, so that a caller can put other loads between them: the side arrays, then -- once the
+// draft token is there -- the logits at it.
+__device__ __forceinline__ void gather_drafts_side(const Params& p, int b, int ndraft, DraftGather& g) {
+  const int tid = threadIdx.x;
+  g.d = 0;
+  g.pi = 0;
+  g.u_acc = 0.0;
+#pragma unroll
+  for (int m = 0; m < COS_MAX_MODELS; ++m) g.lgat[m] = g.rgat[m] = 0.0;
+  if (tid < ndraft) {
+    const size_t k = (size_t)b * p.gamma + p.j0 + tid;
+    g.d = p.draft[k];
+    g.pi = p.proposer_pos ? p.proposer_pos[k] : p.proposer[b];
+    g.u_acc = p.u_accept[k];
+  }
+}
+
 template <typename T, int MODE>
-__device__ void decide_sequence(const Params& p, int b, DecideShared& sh) {
+__device__ __forceinline__ void gather_drafts_logits(const Params& p, int b, int ndraft, DraftGather& g) {
+  const int tid = threadIdx.x;
+  if (tid < ndraft) {
+    const int j = p.j0 + tid;
+#pragma unroll
+    for (int m = 0; m < COS_MAX_MODELS; ++m)
+      if (m < p.n) {
+        const T* row = row_ptr<T>(p, m, b, j);
+        g.lgat[m] = (double)widen(row[g.d]);
+        if constexpr (MODE != kEns) g.rgat[m] = (double)row_reference<T>(row);
+      }
+  }
+}
+
+template <typename T, int MODE>
+__device__ __forceinline__ void gather_drafts(const Params& p, int b, int ndraft, DraftGather& g) {
+  gather_drafts_side(p, b, ndraft, g);
+  gather_drafts_logits<T, MODE>(p, b, ndraft, g);
+}
+
+// Combine the chunk partials of every (position, statistic) of the window in float64 into sh.lse2.
+// A group of G lanes (a power of two >= S, at most a wavefront) shares the S partials of one
+// statistic, so that a row cut into many chunks (small batches) costs a few dependent loads, not S
+// of them; with whole rows (S = 1) it is one thread per statistic.
+__device__ __forceinline__ void combine_partials(const Params& p, int b, DecideShared& sh) {
+  const int tid = threadIdx.x;
+  const int g1 = p.gamma + 1;
+  const int nstat = p.nstat;
+  const int j0 = p.j0;
+  const int nrows = p.nj * nstat;  // statistics of this window
+  const int Sb = splits_of(p, b);  // chunks per row of this sequence
+  int G = 1;
+  while (G < Sb && G < 64) G <<= 1;
+  const int per_pass = kThreads / G;
+  const int gl = tid & (G - 1);
+  for (int r0 = 0; r0 < nrows; r0 += per_pass) {  // uniform trip count: every lane shuffles
+    const int r = r0 + tid / G;
+    int omax = kNoOffset;
+    double zsum = 0.0;  // sum of Z 2^(o - omax) over the partials seen by this lane
+    if (r < nrows) {
+      const Partial* pp = p.partials + (((size_t)b * g1 + j0) * nstat + r) * p.S;
+      for (int s = gl; s < Sb; s += G) {
+        const double z = pp[s].Z.read();
+        const int o = pp[s].o.read();
+        if (z > 0.0) {
+          if (o > omax) {
+            zsum = ldexp(zsum, omax - o);  // exact: a power of two
+            omax = o;
+          }
+          zsum += ldexp(z, o - omax);
+        }
+      }
+    }
+    for (int span = G >> 1; span >= 1; span >>= 1) {
+      const int oo = __shfl_xor(omax, span, 64);
+      const double zz = __shfl_xor(zsum, span, 64);
+      const int om = max(omax, oo);
+      zsum = (zsum > 0.0 ? ldexp(zsum, omax - om) : 0.0) + (zz > 0.0 ? ldexp(zz, oo - om) : 0.0);
+      omax = om;
+    }
+    if (r < nrows && gl == 0) sh.lse2[r] = (zsum > 0.0) ? (double)omax + log2(zsum) : -INFINITY;
+  }
+}
+
+// A logit minus its row's reference exactly as the streaming kernels take it: in float32.  For logits of
+// large magnitude that subtraction rounds (1e-7 of the difference), and the statistics were summed over
+// the rounded values, so what is normalised by them must be those same values: then a token that
+// holds nearly all of a row's mass gets its probability to 1e-7 of its small complement, not of itself.
+__device__ __forceinline__ double shifted(double logit, double ref) { return (double)((float)logit - (float)ref); }
+
+// Eq. (6) for every draft position of the window (float64), the first rejection (Sec. 3.1), the
+// accepted prefix and the padding, and the plan for the draw.  sh.lse2 and (contrastive) sh.rowmax
+// must be complete and visible (a barrier after they were written).  The sequence stays undecided
+// (sh.jstar = -1) if every draft of the window is accepted and the window does not contain the
+// bonus position.  The outcome is in sh after the caller's next barrier.
+template <typename T, int MODE>
+__device__ __forceinline__ void decide_outcome(const Params& p, int b, DecideShared& sh, const DraftGather& g,
+                                               int ndraft) {
   constexpr bool CONTRASTIVE = MODE == kCd;
   const int tid = threadIdx.x;
   const int g1 = p.gamma + 1;
   const int nstat = p.nstat;
   const int j0 = p.j0, nj = p.nj;
-  const int nrows = nj * nstat;  // statistics of this window
+  const int nrows = nj * nstat;
   const int n = p.n;
   const int gb = drafts_of(p, b);
-  const int Sb = splits_of(p, b);        // chunks per row of this sequence
   const double log2e = (double)p.scale;  // log2(e) / T, the same constant the streaming kernel used
-
-  // 0. The loads that do not depend on the statistics go out first, so that their latency
-  //    (draft token, then the n logits at it) overlaps the combine of step 1.
-  const int ndraft = max(min(j0 + nj, gb) - j0, 0);  // draft positions in the window
-  int d = 0, pi = 0;
-  double u_acc = 0.0;
-  double lgat[COS_MAX_MODELS], rgat[COS_MAX_MODELS];  // logits at the draft token; row references
-#pragma unroll
-  for (int m = 0; m < COS_MAX_MODELS; ++m) lgat[m] = rgat[m] = 0.0;
-  if (tid < ndraft) {
-    const int j = j0 + tid;
-    const size_t k = (size_t)b * p.gamma + j;
-    d = p.draft[k];
-    pi = p.proposer_pos ? p.proposer_pos[k] : p.proposer[b];
-    u_acc = p.u_accept[k];
-#pragma unroll
-    for (int m = 0; m < COS_MAX_MODELS; ++m)
-      if (m < n) {
-        const T* row = row_ptr<T>(p, m, b, j);
-        lgat[m] = (double)widen(row[d]);
-        if constexpr (MODE != kEns) rgat[m] = (double)row_reference<T>(row);
-      }
-  }
-
-  // 1. combine the chunk partials of every (position, statistic) of the window in float64.
-  //    A group of G lanes (a power of two >= S, at most a wavefront) shares the S partials of
-  //    one statistic, so that a row cut into many chunks (small batches) costs a few dependent
-  //    loads, not S of them; with whole rows (S = 1) it is one thread per statistic.
-  {
-    int G = 1;
-    while (G < Sb && G < 64) G <<= 1;
-    const int per_pass = kThreads / G;
-    const int gl = tid & (G - 1);
-    for (int r0 = 0; r0 < nrows; r0 += per_pass) {  // uniform trip count: every lane shuffles
-      const int r = r0 + tid / G;
-      int omax = kNoOffset;
-      double zsum = 0.0;  // sum of Z 2^(o - omax) over the partials seen by this lane
-      if (r < nrows) {
-        const Partial* pp = p.partials + (((size_t)b * g1 + j0) * nstat + r) * p.S;
-        for (int s = gl; s < Sb; s += G) {
-          const double z = load_agent(&pp[s].Z);
-          const int o = load_agent(&pp[s].o);
-          if (z > 0.0) {
-            if (o > omax) {
-              zsum = ldexp(zsum, omax - o);  // exact: a power of two
-              omax = o;
-            }
-            zsum += ldexp(z, o - omax);
-          }
-        }
-      }
-      for (int span = G >> 1; span >= 1; span >>= 1) {
-        const int oo = __shfl_xor(omax, span, 64);
-        const double zz = __shfl_xor(zsum, span, 64);
-        const int om = max(omax, oo);
-        zsum = (zsum > 0.0 ? ldexp(zsum, omax - om) : 0.0) + (zz > 0.0 ? ldexp(zz, oo - om) : 0.0);
-        omax = om;
-      }
-      if (r < nrows && gl == 0) sh.lse2[r] = (zsum > 0.0) ? (double)omax + log2(zsum) : -INFINITY;
-    }
-  }
-  if (CONTRASTIVE && tid < nj) {
-    // written by the row-max kernel, an earlier launch on the same stream
-    const float* rm = p.rowmax + ((size_t)b * g1 + j0 + tid) * p.S;
-    float m0 = -INFINITY;
-    for (int s = 0; s < Sb && p.masked; ++s) m0 = fmaxf(m0, rm[s]);
-    sh.rowmax[tid] = p.masked ? m0 : 0.0f;
-  }
-  __syncthreads();
-
-  // 2. Eq. (6) for every draft position of the window, in float64
   if (tid >= ndraft && tid < nj && j0 + tid < p.gamma) {  // no draft here
     if (p.diag.r_at_draft) p.diag.r_at_draft[(size_t)b * p.gamma + j0 + tid] = NAN;
     if (p.diag.q_at_draft) p.diag.q_at_draft[(size_t)b * p.gamma + j0 + tid] = NAN;
   }
   if (tid < ndraft) {
     const int jj = tid;
+    const int pi = g.pi;
     const size_t k = (size_t)b * p.gamma + j0 + tid;
     double rd = 0.0, qd = 0.0;
     if constexpr (MODE == kMix) {
@@ -354,7 +387,7 @@ __device__ void decide_sequence(const Params& p, int b, DecideShared& sh) {
 #pragma unroll
       for (int m = 0; m < COS_MAX_MODELS; ++m)
         if (m < n) {
-          const double v = lgat[m] - rgat[m];
+          const double v = shifted(g.lgat[m], g.rgat[m]);
           if (p.w[m] != 0.0) c += p.w[m] * v;
           lq = (m == pi) ? v : lq;
         }
@@ -364,16 +397,16 @@ __device__ void decide_sequence(const Params& p, int b, DecideShared& sh) {
 #pragma unroll
       for (int m = 0; m < COS_MAX_MODELS; ++m)
         if (m < n) {
-          const double s = exp2(lgat[m] * log2e - sh.lse2[jj * nstat + m]);
+          const double s = exp2(g.lgat[m] * log2e - sh.lse2[jj * nstat + m]);
           rd += p.w[m] * s;
           qd = (m == pi) ? s : qd;
         }
     } else {
-      const double l0 = lgat[0], l1 = lgat[1];
+      const double l0 = g.lgat[0], l1 = g.lgat[1];
       const bool in = (l0 > -INFINITY) && (l0 - (double)sh.rowmax[jj] >= p.thr64);
       // on logits shifted by the row references, as both statistics were
-      const double d0 = l0 - rgat[0];
-      const double d1 = l1 - rgat[1];
+      const double d0 = shifted(l0, g.rgat[0]);
+      const double d1 = shifted(l1, g.rgat[1]);
       const double c = d0 - p.w[0] * d1;
       rd = in ? exp2(c * log2e - sh.lse2[jj * nstat + 2]) : 0.0;
       qd = exp2((pi ? d1 : d0) * log2e - sh.lse2[jj * nstat + pi]);
@@ -386,7 +419,7 @@ __device__ void decide_sequence(const Params& p, int b, DecideShared& sh) {
     else
       ratio = rd / qd;
     const double bound = ratio < 1.0 ? ratio : 1.0;
-    sh.accept[jj] = u_acc < bound;
+    sh.accept[jj] = g.u_acc < bound;
     if (p.diag.r_at_draft) p.diag.r_at_draft[k] = rd;
     if (p.diag.q_at_draft) p.diag.q_at_draft[k] = qd;
   }
@@ -396,19 +429,25 @@ __device__ void decide_sequence(const Params& p, int b, DecideShared& sh) {
     if (CONTRASTIVE && tid < nj) p.rowmax_all[(size_t)b * g1 + j0 + tid] = sh.rowmax[tid];
   }
 
-  // 3. first rejection (Sec. 3.1) inside the window; -1: none, and the bonus position is not in it
+  // first rejection (Sec. 3.1) inside the window; -1: none, and the bonus position is not in it
   int jstar = (j0 + nj > gb) ? gb : -1;
   for (int jj = ndraft - 1; jj >= 0; --jj)
     if (!sh.accept[jj]) jstar = j0 + jj;
-  if (jstar < 0) return;  // undecided: a later window continues
+  if (jstar < 0) {  // undecided: a later window continues
+    if (tid == 0) {
+      sh.jstar = -1;
+      p.plans[b].jstar = -1;
+    }
+    return;
+  }
 
-  // the drawn token's slot is filled by the sampling kernel, unless nothing is drawn
+  // the drawn token's slot is filled by whoever draws, unless nothing is drawn
   const bool skip = p.no_bonus && jstar == gb;
   if (tid == 0) p.accepted_len[b] = jstar;
   if (tid < g1 && (tid != jstar || skip))
     p.out_tokens[(size_t)b * g1 + tid] = (tid < jstar) ? p.draft[(size_t)b * p.gamma + tid] : -1;
 
-  // 4. plan for the sampling kernel (read after this launch has ended)
+  // plan for the draw
   SeqPlan* plan = p.plans + b;
   if (tid == 0) {
     const bool residual = jstar < gb;
@@ -418,6 +457,11 @@ __device__ void decide_sequence(const Params& p, int b, DecideShared& sh) {
     plan->bonus = (!residual && p.bonus_idx) ? p.bonus_idx[b] : -1;
     plan->m0 = (CONTRASTIVE && !skip) ? sh.rowmax[jstar - j0] : 0.0f;
     plan->skip = skip;
+    sh.jstar = jstar;
+    sh.residual = residual;
+    sh.pi = plan->pi;
+    sh.bonus = plan->bonus;
+    sh.skip = skip;
     if (skip) {
       if (p.diag.sample_mass) p.diag.sample_mass[b] = 0.0;
       if (p.diag.cdf_lo) p.diag.cdf_lo[b] = 0.0;
@@ -426,6 +470,29 @@ __device__ void decide_sequence(const Params& p, int b, DecideShared& sh) {
     }
   }
   if (tid < nstat && !skip) plan->lse2[tid] = sh.lse2[(jstar - j0) * nstat + tid];
+}
+
+// Decides the window [j0, j0+nj) of a sequence that no earlier window has decided (runs in the
+// workgroup that arrived last on the sequence's counter).
+template <typename T, int MODE>
+__device__ void decide_sequence(const Params& p, int b, DecideShared& sh) {
+  const int tid = threadIdx.x;
+  const int g1 = p.gamma + 1;
+  const int gb = drafts_of(p, b);
+  const int ndraft = max(min(p.j0 + p.nj, gb) - p.j0, 0);  // draft positions in the window
+  DraftGather g;
+  gather_drafts<T, MODE>(p, b, ndraft, g);
+  combine_partials(p, b, sh);
+  if (MODE == kCd && tid < p.nj) {
+    // written by the row-max kernel, an earlier launch on the same stream
+    const int Sb = splits_of(p, b);
+    const float* rm = p.rowmax + ((size_t)b * g1 + p.j0 + tid) * p.S;
+    float m0 = -INFINITY;
+    for (int s = 0; s < Sb && p.masked; ++s) m0 = fmaxf(m0, rm[s]);
+    sh.rowmax[tid] = p.masked ? m0 : 0.0f;
+  }
+  __syncthreads();
+  decide_outcome<T, MODE>(p, b, sh, g, ndraft);
 }
 
 // ---------------------------------------------------------------------------
@@ -812,8 +879,8 @@ __device__ __forceinline__ bool greedy_arrive(const Params& p, int b, ArgBest be
   if (tid == 0) {
     ArgBest bb = wbest[0];
     for (int w = 1; w < kWaves; ++w) arg_better(bb, wbest[w].val, wbest[w].idx);
-    store_agent(&out->Z, bb.val);
-    store_agent(&out->o, bb.idx);
+    out->Z.publish(bb.val);
+    out->o.publish(bb.idx);
     wait_stores();
   }
   return arrive_last(p.counters + (size_t)b * kCtrStride, per_b, s_flag);
@@ -826,7 +893,7 @@ __device__ __forceinline__ int greedy_combine(const Params& p, int b, int stat) 
   ArgBest bb;
   bb.val = 0.0;
   bb.idx = -1;
-  for (int i = 0; i < Sb; ++i) arg_better(bb, load_agent(&pp[i].Z), load_agent(&pp[i].o));
+  for (int i = 0; i < Sb; ++i) arg_better(bb, pp[i].Z.read(), pp[i].o.read());
   return bb.idx;
 }
 

@@ -81,7 +81,7 @@ Tune tune_of(const cos_options_t* o) {
 struct Plan {
   int nvec, ntiles, nstat;
   size_t off_counters, off_partials, off_rowmax, off_plans, off_tiles, off_lse_all, off_rowmax_all,
-      off_alpha_partials, bytes;
+      off_alpha_partials, off_cand, off_cand_count, bytes;
 };
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -135,6 +135,11 @@ void plan_layout(int n, int B, int gamma, int V, cos_dtype_t dt, cos_combine_t m
   at += align_up((size_t)B * gamma * alpha_blocks(B, gamma, pl->ntiles) * sizeof(double), 256);
   pl->off_rowmax = at;
   if (mode == COS_COMBINE_CONTRASTIVE) at += align_up((size_t)B * g1 * S * sizeof(float), 256);
+  // masked contrastive mode in one pass: the candidates every chunk leaves behind
+  pl->off_cand = at;
+  if (mode == COS_COMBINE_CONTRASTIVE) at += align_up((size_t)B * g1 * S * kCandChunk * sizeof(Cand), 256);
+  pl->off_cand_count = at;
+  if (mode == COS_COMBINE_CONTRASTIVE) at += align_up((size_t)B * g1 * S * sizeof(int), 256);
   pl->off_partials = at;
   at += align_up((size_t)B * g1 * pl->nstat * S * sizeof(Partial), 256);
   pl->bytes = at;
@@ -414,12 +419,15 @@ cos_status_t verify_impl(const void* logits, cos_dtype_t dt, int n, int B, int g
   p.counters = reinterpret_cast<int*>(wsb + pl.off_counters);
   p.partials = reinterpret_cast<Partial*>(wsb + pl.off_partials);
   p.rowmax = reinterpret_cast<float*>(wsb + pl.off_rowmax);
+  p.cand = reinterpret_cast<Cand*>(wsb + pl.off_cand);
+  p.cand_count = reinterpret_cast<int*>(wsb + pl.off_cand_count);
+  p.cand_cap = kCandChunk;
   p.plans = reinterpret_cast<SeqPlan*>(wsb + pl.off_plans);
-  p.tile_sums = reinterpret_cast<double*>(wsb + pl.off_tiles);
+  p.tile_sums = reinterpret_cast<HandOff<double>*>(wsb + pl.off_tiles);
   p.alpha = options ? options->alpha : nullptr;
   p.lse_all = reinterpret_cast<double*>(wsb + pl.off_lse_all);
   p.rowmax_all = reinterpret_cast<float*>(wsb + pl.off_rowmax_all);
-  p.alpha_partials = reinterpret_cast<double*>(wsb + pl.off_alpha_partials);
+  p.alpha_partials = reinterpret_cast<HandOff<double>*>(wsb + pl.off_alpha_partials);
   {
     const int ca = alpha_blocks(B, gamma, pl.ntiles);
     p.tpa = (pl.ntiles + ca - 1) / ca;
@@ -477,6 +485,7 @@ cos_status_t verify_impl(const void* logits, cos_dtype_t dt, int n, int B, int g
   lp.mode = mode;
   lp.window = window;
   lp.greedy = (options && options->greedy) ? 1 : 0;
+  lp.onepass = (mode == kCd && p.masked && !lp.greedy && !(options && options->two_pass_mask)) ? 1 : 0;
   lp.aligned = aligned ? 1 : 0;
   lp.counters = ((p.nwin + 1 + (p.alpha ? gamma : 0)) * B) * kCtrStride;
   lp.lds = lds;

@@ -537,3 +537,73 @@ def test_greedy_ensemble_ragged_rows_odd_vocabulary_agreeing_models_and_zero_wei
     assert ora.status == 0
     assert np.array_equal(alen.cpu().numpy(), ora.accepted_len) and np.array_equal(toks.cpu().numpy(), ora.out_tokens)
     assert (ora.flags & O.FLAG_RESIDUAL_FALLBACK).any()         # the degenerate case did occur
+
+
+# ---------------------------------------------------------------------------
+# masked contrastive mode in one read of the logits: candidate lists, and what happens when they do not fit
+# ---------------------------------------------------------------------------
+
+def _masked_inputs(B, gamma, V, dtype, seed, flat=False, std=3.0):
+    inp = _random_inputs(2, B, gamma, V, dtype, seed=seed, std=std)
+    if flat:          # an expert row with very many tokens at (nearly) the same top value: the mask is not sparse
+        g = torch.Generator().manual_seed(seed + 7)
+        top = (torch.rand((B, gamma + 1, V), generator=g) < 0.4).cuda()
+        inp["logits"][0] = torch.where(top, torch.full_like(inp["logits"][0], 4.0), inp["logits"][0].clamp(max=3.0))
+    # drafts the combination likes on half of the rows, so that lengths vary
+    c = inp["logits"][0, :, :gamma].float() - 0.5 * inp["logits"][1, :, :gamma].float()
+    inp["draft_tokens"][::2] = c.argmax(-1).to(torch.int32)[::2]
+    return inp
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32", "f16"])
+@pytest.mark.parametrize("flat,alpha_cd", [(False, 0.1), (False, 1e-4), (True, 0.5), (False, 1.0)])
+def test_masked_contrastive_candidate_lists_and_their_overflow(dtype, flat, alpha_cd):
+    """alpha_cd = 0.1 on Gaussian logits keeps a few dozen tokens (the candidate lists carry the whole step);
+    alpha_cd = 1e-4, or an expert row with 40 % of its tokens at the top, keeps thousands (no list fits: the
+    finishing workgroup reads the rows again and draws from the full row); alpha_cd = 1 keeps the expert's
+    top token alone.  Same outputs as the reference either way, with acceptance rates, a verifier's bonus
+    token, per-position proposers, one-position windows -- and the same tokens as the two-pass route."""
+    B, gamma, V = 12, 3, 40000
+    inp = _masked_inputs(B, gamma, V, dtype, seed=77, flat=flat)
+    mode, weights = C.COS_COMBINE_CONTRASTIVE, [0.5, alpha_cd]
+    alen, toks, diag, rep = _check(f"masked one-pass {dtype} flat={flat} alpha_cd={alpha_cd}", inp, mode, weights)
+    # the two-pass route gives the same tokens (near-ties aside: none at these seeds)
+    a2, t2 = C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], mode, weights, inp["u_accept"],
+                          inp["u_resample"], shape=C.LaunchShape(two_pass_mask=1))
+    torch.cuda.synchronize()
+    assert np.array_equal(a2.cpu().numpy(), alen) and np.array_equal(t2.cpu().numpy(), toks)
+    # acceptance rates from the candidate lists (or the second read) against the oracle's
+    alpha = torch.full((B, gamma), -1.0, dtype=torch.float64, device="cuda")
+    C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], mode, weights, inp["u_accept"], inp["u_resample"],
+                 alpha=alpha)
+    torch.cuda.synchronize()
+    ora = O.verify(W.host_logits(inp["logits"]), P.oracle_dtype(inp["logits"]), inp["draft_tokens"].cpu().numpy(),
+                   inp["proposer_idx"].cpu().numpy(), mode, weights, inp["u_accept"].cpu().numpy(),
+                   inp["u_resample"].cpu().numpy(), all_positions=True, want_alpha=True)
+    assert np.abs(alpha.cpu().numpy() - ora.alpha).max() < 1e-6
+    # extensions on top
+    g = torch.Generator().manual_seed(5)
+    inp["proposer_pos"] = torch.randint(0, 2, (B, gamma), generator=g, dtype=torch.int32).cuda()
+    inp["bonus_idx"] = torch.randint(-1, 2, (B,), generator=g, dtype=torch.int32).cuda()
+    inp["u_accept"][B // 2:] = 0.0                               # these rows reach the bonus position
+    inp["draft_tokens"][B // 2:] = (inp["logits"][0, B // 2:, :gamma].float() - 0.5 * inp["logits"][1, B // 2:, :gamma].float()).argmax(-1).to(torch.int32)
+    for window in (0, 1, 2):
+        inp["stop_window"] = window
+        _check(f"masked one-pass {dtype} flat={flat} alpha_cd={alpha_cd} + extensions, window {window}", inp, mode, weights)
+
+
+def test_masked_contrastive_is_deterministic():
+    """Candidates are collected in whatever order the wavefronts find them and sorted by token before anything
+    is summed: two calls give the same bits, diagnostics included."""
+    inp = _masked_inputs(16, 4, 128256, "bf16", seed=3)
+    outs = []
+    for _ in range(3):
+        diag = C.Diagnostics.allocate(16, 4, "cuda")
+        a, t = C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], C.COS_COMBINE_CONTRASTIVE, [0.5, 0.1],
+                            inp["u_accept"], inp["u_resample"], diag=diag)
+        torch.cuda.synchronize()
+        outs.append((a, t, diag))
+    for a, t, d in outs[1:]:
+        assert torch.equal(a, outs[0][0]) and torch.equal(t, outs[0][1])
+        for name in ("r_at_draft", "q_at_draft", "sample_mass", "cdf_lo", "cdf_hi", "flags"):
+            assert torch.equal(getattr(d, name), getattr(outs[0][2], name)), name

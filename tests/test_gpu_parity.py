@@ -225,6 +225,45 @@ def test_two_streams_with_their_own_workspaces_overlap():
         assert np.array_equal(rb[0].cpu().numpy(), want_b[0]) and np.array_equal(rb[1].cpu().numpy(), want_b[1])
 
 
+def test_two_threads_with_their_own_streams_workspaces_and_launch_shapes():
+    """The library keeps no settings between calls: two host threads that call it at the same time, each
+    on its own stream and workspace and each with its own launch-shape overrides (which change the
+    workspace a call needs), get the outputs of their own inputs."""
+    import threading
+    w = W.C3.scaled(B=12)
+    inputs = [W.generate(w, device="cuda", step=s) for s in range(2)]
+    want = [P.run_gpu(i, w.mode, w.weights) for i in inputs]
+    shapes = [C.LaunchShape(chunk_vectors=512, tail_sequences=5, tail_factor=8), C.LaunchShape(chunk_vectors=4096, tail_sequences=-1)]
+    spaces = [C.allocate_workspace(w.n, w.B, w.gamma, w.V, C.COS_DTYPE_BF16, w.mode, "cuda", sh) for sh in shapes]
+    assert spaces[0].numel() != spaces[1].numel()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    torch.cuda.synchronize()
+    results, errors = [[], []], []
+
+    def worker(k):
+        try:
+            torch.cuda.set_device(0)
+            with torch.cuda.stream(streams[k]):
+                for _ in range(40):
+                    i = inputs[k]
+                    results[k].append(C.cos_verify(i["logits"], i["draft_tokens"], i["proposer_idx"], w.mode, w.weights,
+                                                   i["u_accept"], i["u_resample"], workspace=spaces[k], shape=shapes[k]))
+        except Exception as e:          # surfaced below: an assertion in a thread would be lost
+            errors.append(repr(e))
+
+    threads = [threading.Thread(target=worker, args=(k,)) for k in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    torch.cuda.synchronize()
+    assert not errors, errors
+    for k in range(2):
+        assert len(results[k]) == 40
+        for alen, toks in results[k]:
+            assert np.array_equal(alen.cpu().numpy(), want[k][0]) and np.array_equal(toks.cpu().numpy(), want[k][1]), k
+
+
 # ---------------------------------------------------------------------------
 # degenerate cases of the method
 # ---------------------------------------------------------------------------
