@@ -38,44 +38,78 @@ struct OnePass {
   float wm0;   // largest expert logit the wavefront has seen (wave-uniform)
 };
 
-// H vectors per lane of both rows (x0, x1; first[u] = token index of x[u][0]): the proposer row's
-// statistic, the expert row's running maximum, and the tokens that pass the mask test against it.
-template <typename T, int H>
-__device__ __forceinline__ void onepass_group(const Params& p, OnePass& st, const float (&x0)[H][VecOf<T>::N],
-                                              const float (&x1)[H][VecOf<T>::N], const int (&first)[H], int pi,
-                                              float ref0, float ref1, int* s_count, Cand* s_cand) {
+// The wavefront's largest element of U raw vectors per lane.  16-bit formats: on the raw bit patterns
+// with packed integer maxima (among non-negative values integer order is float order, and a pattern
+// with the sign bit set never wins against one without); if every element is negative, or the format
+// is float32, on the widened values.
+template <typename T, int U>
+__device__ __forceinline__ float raw_wave_max(const uint4 (&raw)[U]) {
   constexpr int N = VecOf<T>::N;
-  // on the shifted logits (as the finishing kernel evaluates q)
-  {
-    float xq[H][N];
-    const float refq = pi ? ref1 : ref0;
+  if constexpr (sizeof(T) == 2) {
+    short2_t m = __builtin_bit_cast(short2_t, raw[0].x);
 #pragma unroll
-    for (int u = 0; u < H; ++u)
-#pragma unroll
-      for (int k = 0; k < N; ++k) xq[u][k] = (pi ? x1[u][k] : x0[u][k]) - refq;
-    running_add<H, N>(st.rq, xq, p.scale);
+    for (int u = 0; u < U; ++u) {
+      m = __builtin_elementwise_max(m, __builtin_bit_cast(short2_t, raw[u].x));
+      m = __builtin_elementwise_max(m, __builtin_bit_cast(short2_t, raw[u].y));
+      m = __builtin_elementwise_max(m, __builtin_bit_cast(short2_t, raw[u].z));
+      m = __builtin_elementwise_max(m, __builtin_bit_cast(short2_t, raw[u].w));
+    }
+    const int wm16 = wave_max_i32(max((int)m.x, (int)m.y));
+    if (wm16 >= 0) return raw16_to_float<T>(wm16);
   }
   float lm = -INFINITY;
 #pragma unroll
-  for (int u = 0; u < H; ++u)
+  for (int u = 0; u < U; ++u) {
+    float x[N];
+    unpack<T>(raw[u], x);
 #pragma unroll
-    for (int k = 0; k < N; ++k) lm = fmaxf(lm, x0[u][k]);
-  st.wm0 = fmaxf(st.wm0, wave_max(lm));
-  // a lane whose best element fails has no candidate (vectors past the chunk's end and elements past
-  // the row's end read as -inf: never in)
-  if (in_mask<T>(lm, st.wm0, p.thr32, p.thr64)) {  // a few lanes per group
+    for (int k = 0; k < N; ++k) lm = fmaxf(lm, x[k]);
+  }
+  return wave_max(lm);
+}
+
+// U vectors per lane of both rows (raw; vector u holds tokens first + u * kThreads * N ...): the
+// proposer row's statistic, the expert row's running maximum, and the tokens that pass the mask test
+// against it.
+template <typename T, int U>
+__device__ __forceinline__ void onepass_group(const Params& p, OnePass& st, const uint4 (&a0)[U], const uint4 (&a1)[U],
+                                              int first, int pi, float ref0, float ref1, int* s_count, Cand* s_cand) {
+  constexpr int N = VecOf<T>::N;
+  const float m0 = raw_wave_max<T, U>(a0);
+  st.wm0 = fmaxf(st.wm0, m0);
+  // the proposer's row on the shifted logits (as the finishing kernel evaluates q); the shift is
+  // monotone, so the row's largest shifted logit is its largest logit shifted
+  const float refq = pi ? ref1 : ref0;
+  const float mq = pi ? raw_wave_max<T, U>(a1) : m0;
+  running_cover(st.rq, mq - refq, p.scale);
+  const float neg_o = -(float)st.rq.o;
+  // a cut just below the mask's edge against the running maximum: what lies above it is looked at
+  // exactly (vectors past the chunk's end and elements past the row's end read as -inf: never in)
+  const float edge = st.wm0 + p.thr32;
+  const float cut = edge - 2.0f * fabsf(edge) * 1.1920929e-7f - 1e-30f;
 #pragma unroll
-    for (int u = 0; u < H; ++u)
+  for (int u = 0; u < U; ++u) {
+    float x0[N], x1[N];
+    unpack<T>(a0[u], x0);
+    unpack<T>(a1[u], x1);
+    bool any = false;
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+      st.rq.acc[k & 3] += fast_exp2(fmaf((pi ? x1[k] : x0[k]) - refq, p.scale, neg_o));
+      any = any || x0[k] >= cut;
+    }
+    if (any) {  // a few lanes per chunk
 #pragma unroll
       for (int k = 0; k < N; ++k)
-        if (in_mask<T>(x0[u][k], st.wm0, p.thr32, p.thr64)) {
+        if (in_mask<T>(x0[k], st.wm0, p.thr32, p.thr64)) {
           const int at = atomicAdd(s_count, 1);
           if (at < kCandStage) {
-            s_cand[at].idx = first[u] + k;
-            s_cand[at].l0 = x0[u][k];
-            s_cand[at].l1 = x1[u][k];
+            s_cand[at].idx = first + u * kThreads * N + k;
+            s_cand[at].l0 = x0[k];
+            s_cand[at].l1 = x1[k];
           }
         }
+    }
   }
 }
 
@@ -83,8 +117,7 @@ __device__ __forceinline__ void onepass_group(const Params& p, OnePass& st, cons
 template <typename T, bool ALIGNED>
 __global__ void __launch_bounds__(kThreads) contrastive_onepass_kernel(Params p) {
   constexpr int N = VecOf<T>::N;
-  constexpr int U = kUnroll;  // 16-byte loads in flight per lane and row
-  constexpr int H = 4;        // vectors per row worked on at a time
+  constexpr int U = kUnroll / 2;  // 16-byte loads in flight per lane and row
   constexpr int kStep = kThreads * U;
   __shared__ WaveStat ws[kWaves];
   __shared__ float s_m0[kWaves];
@@ -145,28 +178,16 @@ __global__ void __launch_bounds__(kThreads) contrastive_onepass_kernel(Params p)
       mask_raw_group<T, U>(base, vfull, a0);
       mask_raw_group<T, U>(base, vfull, a1);
     }
-#pragma unroll
-    for (int h = 0; h < U; h += H) {
-      float x0[H][N], x1[H][N];
-      int first[H];
-#pragma unroll
-      for (int u = 0; u < H; ++u) {
-        unpack<T>(a0[h + u], x0[u]);
-        unpack<T>(a1[h + u], x1[u]);
-        first[u] = (base + (h + u) * kThreads + tid) * N;
-      }
-      onepass_group<T, H>(p, st, x0, x1, first, pi, ref0, ref1, &s_count, s_cand);
-    }
+    onepass_group<T, U>(p, st, a0, a1, (base + tid) * N, pi, ref0, ref1, &s_count, s_cand);
   }
   if (!ALIGNED && v1 > vfull && tid < 64) {
     // the partial vector belongs to this chunk: lane 0 of the first wavefront brings it in
     const uint32_t ninf = sizeof(T) == 4 ? 0xff800000u : (IsBf16<T>::value ? 0xff80ff80u : 0xfc00fc00u);
     const uint4 none = make_uint4(ninf, ninf, ninf, ninf);
-    float x0[1][N], x1[1][N];
-    int first[1] = {vfull * N};
-    unpack<T>(tid == 0 ? load_tail_raw<T>(row0, vfull * N, p.V) : none, x0[0]);
-    unpack<T>(tid == 0 ? load_tail_raw<T>(row1, vfull * N, p.V) : none, x1[0]);
-    onepass_group<T, 1>(p, st, x0, x1, first, pi, ref0, ref1, &s_count, s_cand);
+    uint4 a0[1], a1[1];
+    a0[0] = tid == 0 ? load_tail_raw<T>(row0, vfull * N, p.V) : none;
+    a1[0] = tid == 0 ? load_tail_raw<T>(row1, vfull * N, p.V) : none;
+    onepass_group<T, 1>(p, st, a0, a1, vfull * N, pi, ref0, ref1, &s_count, s_cand);
   }
   const double zq = running_total(st.rq);
   publish_wave_stat(ws, 0, st.rq.o, zq);

@@ -129,6 +129,9 @@ __global__ void __launch_bounds__(kProbeThreads) hbm_probe_read(const uint4* __r
   }
 #pragma unroll
   for (int u = 0; u < kProbePerThread; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+  // every lane's loads must matter (a store from one lane alone lets the compiler load for that lane alone)
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) acc ^= __shfl_xor(acc, d, 64);
   if ((threadIdx.x & 63) == 0) out[blockIdx.x * (kProbeThreads / 64) + (threadIdx.x >> 6)] = acc;
 }
 
