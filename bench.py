@@ -89,12 +89,19 @@ def main() -> int:
 
     alpha = torch.empty((w.B, w.gamma), dtype=torch.float64, device=dev) if args.with_alpha else None
 
-    def step(i, events=None):
+    # the serving loop's form of the call: one shape step after step on one workspace, so from the second
+    # call on the workspace is promised ready (every call leaves its arrival counters at zero) and the
+    # kernel that clears them is skipped
+    from dataclasses import replace
+    steady = replace(shape, workspace_ready=1)
+
+    def step(i, events=None, first=False):
         s = sets[i % nsets]
         C.cos_verify(s["logits"], s["draft_tokens"], s["proposer_idx"], w.mode, w.weights,
                      s["u_accept"], s["u_resample"], accepted_len=alen, out_tokens=toks, workspace=ws,
-                     alpha=alpha, stop_window=args.stop_window, shape=shape, events=events)
+                     alpha=alpha, stop_window=args.stop_window, shape=shape if first else steady, events=events)
 
+    step(0, first=True)
     for i in range(args.warmup):
         step(i)
     # HIP events of this program, recorded by each call on its own stream around the kernel(s) that
@@ -141,7 +148,7 @@ def main() -> int:
             s = sets[i % nsets]
             C.cos_verify(s["logits"], s["draft_tokens"], s["proposer_idx"], w.mode, w.weights,
                          s["u_accept"], s["u_resample"], accepted_len=alen, out_tokens=toks, workspace=ws,
-                         stop_window=1, shape=shape)
+                         stop_window=1, shape=steady if i > 0 else shape)
         for i in range(args.warmup):
             lazy_step(i)
         torch.cuda.synchronize()
@@ -206,7 +213,7 @@ def main() -> int:
         diag = C.Diagnostics.allocate(w.B, w.gamma, dev)
         C.cos_verify(s["logits"], s["draft_tokens"], s["proposer_idx"], w.mode, w.weights, s["u_accept"],
                      s["u_resample"], accepted_len=alen, out_tokens=toks, workspace=ws, diag=diag,
-                     stop_window=args.stop_window, shape=shape)
+                     stop_window=args.stop_window, shape=steady)
         torch.cuda.synchronize()
         rep = P.compare(s, w.mode, w.weights, alen.cpu().numpy(), toks.cpu().numpy(), diag, rows=rows)
         parity = {"rows": rep.rows, "bit_exact_rows": rep.exact_rows,
@@ -227,7 +234,7 @@ def main() -> int:
         "config": {"workload": w.name, "n": w.n, "B": w.B, "gamma": w.gamma, "V": w.V,
                    "combine": "contrastive" if w.mode == W.CONTRASTIVE else "ensemble", "weights": list(w.weights),
                    "input_sets_rotated": nsets, "chunk_vectors": args.chunk_vectors,
-                   "sample_blocks": args.sample_blocks, "tail_sequences": args.tail_sequences, "tail_factor": args.tail_factor, "acceptance_rate_output": bool(args.with_alpha),
+                   "sample_blocks": args.sample_blocks, "tail_sequences": args.tail_sequences, "tail_factor": args.tail_factor, "acceptance_rate_output": bool(args.with_alpha), "workspace_ready": True,
                    "stop_window": args.stop_window},
         "achieved_hbm_gbs_per_step": round(w.logit_bytes / (ms_per_step * 1e-3) / 1e9, 1),
         "roofline": roofline, "cpu_baseline": cpu, "parity_sample": parity, "stop_window_1": lazy,

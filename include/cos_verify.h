@@ -117,7 +117,8 @@ size_t cos_verify_workspace_bytes(int n, int B, int gamma, int V, cos_dtype_t dt
  *               token at index accepted_len[b], then -1.
  * workspace     DEVICE scratch, 256-byte aligned, at least
  *               cos_verify_workspace_bytes() bytes, contents arbitrary on
- *               entry; two calls that overlap in time need distinct ones.
+ *               entry (but see options->workspace_ready); two calls that overlap in
+ *               time need distinct ones.
  * diag          HOST pointer to a struct of device pointers, or NULL.
  * hip_stream    hipStream_t (NULL = the default stream).
  *
@@ -211,6 +212,13 @@ cos_status_t cos_verify(const void *logits, cos_dtype_t dt, int n, int B, int ga
  *               route -- one pass for the expert maxima, one for the masked statistic,
  *               the sampling kernel -- instead of the single read with candidate lists.
  *               Same outputs up to near-ties; kept for comparison and tests.
+ * workspace_ready  non-zero: the caller promises that every arrival counter in the
+ *               workspace is zero, which is the case if the workspace was zero-filled,
+ *               or if its last use was a completed call of this library with the same
+ *               shape, mode and options (every call leaves its counters at zero).  The
+ *               call then skips the kernel that clears them.  For loops that verify
+ *               the same shape step after step; a promise that does not hold gives
+ *               undefined outputs (never an out-of-bounds access).
  * event_start, event_stop
  *               hipEvent_t handles created by the caller, or NULL.  The call records
  *               event_start on its stream just before its streaming kernel(s) -- the
@@ -232,6 +240,7 @@ typedef struct cos_options_t {
   int tail_sequences;
   int tail_factor;
   int two_pass_mask;
+  int workspace_ready;
   void *event_start;
   void *event_stop;
 } cos_options_t;

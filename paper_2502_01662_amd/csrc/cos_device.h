@@ -143,6 +143,7 @@ struct LaunchPlan {
   int window;       // positions per streaming launch
   int greedy;       // temperature 0: one argmax kernel instead
   int onepass;      // masked contrastive mode in one read of the logits (candidate lists), no counters
+  int ready;        // the caller promises zeroed arrival counters: no clearing kernel
   int aligned;      // every row starts on a 16-byte boundary and V is a multiple of the vector width
   int counters;     // arrival counters (ints, with their stride) the fill kernel clears
   size_t lds;       // dynamic LDS of the sampling kernel (one double per tile)
@@ -276,15 +277,18 @@ __device__ __forceinline__ void wait_stores() { asm volatile("s_waitcnt vmcnt(0)
 // Last-arrival test.  Every wavefront must have called wait_stores() after its
 // hand-off stores.  Returns true in every thread of exactly one workgroup per
 // counter: the one that arrives after all `total` workgroups have published.
-// The counter is bumped by an agent-scope atomic add, executed where every compute die's atomics
+// The counter is bumped by an agent-scope atomic increment, executed where every compute die's atomics
 // on that address are executed, so exactly one workgroup sees total - 1.  That workgroup's reads
-// come after the barrier that follows the add's returned value: they cannot be issued earlier, and
+// come after the barrier that follows the increment's returned value: they cannot be issued earlier, and
 // being agent-scope loads (HandOff::read) they need no cache invalidation in front of them.
 __device__ __forceinline__ bool arrive_last(int* counter, int total, int* s_flag) {
   __syncthreads();
   if (threadIdx.x == 0) {
-    const int prev = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    *s_flag = (prev == total - 1);
+    // increment that wraps to zero at the last arrival: the counter is left as it was found, so a
+    // workspace whose counters were zero before a call has them zero after it
+    const unsigned prev = __builtin_amdgcn_atomic_inc32(reinterpret_cast<unsigned*>(counter), (unsigned)(total - 1),
+                                                        __ATOMIC_RELAXED, "agent");
+    *s_flag = (prev == (unsigned)(total - 1));
   }
   __syncthreads();
   return *s_flag != 0;

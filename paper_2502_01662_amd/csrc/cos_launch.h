@@ -163,8 +163,8 @@ cos_status_t run_kernels(Params p, const LaunchPlan& lp) {
   if (lp.onepass) return lp.aligned ? launch_onepass<T, true>(p, lp) : launch_onepass<T, false>(p, lp);
   // The masked contrastive mode starts with a kernel that uses neither counters nor plans (the expert
   // maxima): it clears them on its way, one launch less.
-  p.fill_count = (lp.mode == kCd && p.masked) ? lp.counters : 0;
-  if (p.fill_count == 0) {
+  p.fill_count = (lp.mode == kCd && p.masked && !lp.ready) ? lp.counters : 0;
+  if (p.fill_count == 0 && !lp.ready) {
     hipLaunchKernelGGL(fill_zero_kernel, dim3((lp.counters + kThreads - 1) / kThreads), dim3(kThreads), 0,
                        lp.stream, p.counters, lp.counters, p.plans, p.B);
     if (hipGetLastError() != hipSuccess) return COS_ERR_LAUNCH;

@@ -235,11 +235,13 @@ int alpha_blocks(int B, int gamma, int ntiles) {
   return (int)ca;
 }
 
-// Sampling workgroups per sequence: about 2048 in total, at least 4 tiles each.  (Finer
-// workgroups at the end of this grid, as choose_tail makes them for the streaming kernels, were
-// measured and do not pay: the kernel is short and its workgroups are nearly all resident at once.)
+// Sampling workgroups per sequence: about 1024 in total -- one generation of resident workgroups; a
+// sampling workgroup's fixed cost (the plan, the coefficients, the hand-off) is large beside its
+// streaming, so few long ones beat many short ones (measured: 1024 against 2048 saves 1.5 us at
+// B = 64 and B = 256, 10 us at B = 512) --, at least 4 tiles each.  (Finer workgroups at the end of
+// this grid, as choose_tail makes them for the streaming kernels, were measured and do not pay.)
 void choose_sampling(const Tune& tn, int B, int ntiles, int* C_out, int* tpc_out) {
-  const int target = tn.sample_blocks > 0 ? tn.sample_blocks : 2048;
+  const int target = tn.sample_blocks > 0 ? tn.sample_blocks : 1024;
   int C = (target + B - 1) / B;
   const int cmax = (ntiles + 3) / 4;
   if (C > cmax) C = cmax;
@@ -485,6 +487,7 @@ cos_status_t verify_impl(const void* logits, cos_dtype_t dt, int n, int B, int g
   lp.mode = mode;
   lp.window = window;
   lp.greedy = (options && options->greedy) ? 1 : 0;
+  lp.ready = (options && options->workspace_ready) ? 1 : 0;
   lp.onepass = (mode == kCd && p.masked && !lp.greedy && !(options && options->two_pass_mask)) ? 1 : 0;
   lp.aligned = aligned ? 1 : 0;
   lp.counters = ((p.nwin + 1 + (p.alpha ? gamma : 0)) * B) * kCtrStride;

@@ -426,6 +426,50 @@ def test_workspace_can_be_reused_and_holds_garbage():
     _report("reused workspace", rep)
 
 
+def test_workspace_ready_promise_skips_the_clearing_kernel():
+    """Every call leaves its arrival counters at zero (the last arrival wraps them), so a loop over one shape may
+    promise a ready workspace from its second call on -- or from the first on a zero-filled one -- and gets the
+    same outputs; in every mode, with windows, acceptance rates and at temperature 0."""
+    n, B, gamma, V = 3, 20, 4, 33000
+    base = _random_inputs(n, B, gamma, V, "bf16", seed=401, std=2.0)
+    c = sum(base["logits"][m, :, :gamma].float() for m in range(n))
+    base["draft_tokens"][::2] = c.argmax(-1).to(torch.int32)[::2]
+    ready = C.LaunchShape(workspace_ready=1)
+    for mode, weights, nn, ext in ((C.COS_COMBINE_ENSEMBLE, [0.5, 0.3, 0.2], 3, {}),
+                                   (C.COS_COMBINE_ENSEMBLE, [0.5, 0.3, 0.2], 3, {"stop_window": 2}),
+                                   (C.COS_COMBINE_ENSEMBLE, [0.5, 0.3, 0.2], 3, {"greedy": True}),
+                                   (C.COS_COMBINE_LOGIT_MIX, [0.7, 0.5, -0.2], 3, {"alpha": True}),
+                                   (C.COS_COMBINE_CONTRASTIVE, [0.5, 0.0], 2, {"alpha": True}),
+                                   (C.COS_COMBINE_CONTRASTIVE, [0.5, 0.1], 2, {"greedy": True}),
+                                   (C.COS_COMBINE_CONTRASTIVE, [0.5, 0.1], 2, {"stop_window": 1})):
+        inp = {k: (v[:nn].contiguous() if k == "logits" else v) for k, v in base.items()}
+        inp["proposer_idx"] = inp["proposer_idx"] % nn
+        dt = C.COS_DTYPE_BF16
+        for zero_filled in (False, True):
+            ws = C.allocate_workspace(nn, B, gamma, V, dt, mode, "cuda")
+            ws.fill_(0 if zero_filled else 0xA5)
+            outs = []
+            for call in range(4):
+                kw = dict(ext)
+                alpha = torch.full((B, gamma), -1.0, dtype=torch.float64, device="cuda") if kw.pop("alpha", False) else None
+                a, t = C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], mode, weights, inp["u_accept"],
+                                    inp["u_resample"], workspace=ws, alpha=alpha,
+                                    shape=ready if (zero_filled or call > 0) else None, **kw)
+                torch.cuda.synchronize()
+                outs.append((a.cpu().numpy(), t.cpu().numpy(), None if alpha is None else alpha.cpu().numpy()))
+            for a, t, al in outs[1:]:
+                assert np.array_equal(a, outs[0][0]) and np.array_equal(t, outs[0][1]), (mode, ext, zero_filled)
+                if al is not None:
+                    assert np.array_equal(al, outs[0][2], equal_nan=True)
+        # and they are the reference's outputs
+        if not ext.get("greedy"):
+            chk = dict(inp)
+            if "stop_window" in ext:
+                chk["stop_window"] = ext["stop_window"]
+            rep = P.compare(chk, mode, weights, outs[0][0], outs[0][1], None)
+            assert rep.ok, rep.failures[:3]
+
+
 def test_contrastive_without_mask_needs_no_expert_maxima():
     """alpha_cd = 0 (Eq. (5) as printed) runs no pass for the expert maxima: a workspace full of NaN bit
     patterns must not matter, with the acceptance rates and at temperature 0 as well."""

@@ -1,5 +1,5 @@
 """The cross-workgroup hand-off rests on which instructions gfx950 code gets for it: agent-scope
-write-through stores, a wait for their completion, an agent-scope atomic add, agent-scope loads --
+write-through stores, a wait for their completion, an agent-scope atomic increment, agent-scope loads --
 and no cache-wide write-back or invalidate.  This compiles a few lines that use the hand-off primitives
 of csrc/cos_device.h for gfx950 (no GPU needed) and checks the instruction stream."""
 import os
@@ -44,7 +44,7 @@ def _asm():
 def test_handoff_compiles_to_write_through_stores_a_wait_and_agent_scope_loads():
     ins = _asm()
     stores = [i for i, ln in enumerate(ins) if ln.startswith("global_store")]
-    atomics = [i for i, ln in enumerate(ins) if ln.startswith("global_atomic_add")]
+    atomics = [i for i, ln in enumerate(ins) if ln.startswith("global_atomic_inc")]   # wraps to zero at the last arrival
     loads = [i for i, ln in enumerate(ins) if re.match(r"global_load_dword(x2)? ", ln)]
     waits = [i for i, ln in enumerate(ins) if ln.startswith("s_waitcnt") and "vmcnt(0)" in ln]
     assert len(atomics) == 1
