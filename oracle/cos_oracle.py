@@ -17,6 +17,9 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "cos_oracle.c")
 _LIB = os.path.join(_HERE, "libcos_oracle.so")
+# The mutation test of the pins (tests/test_oracle_mutations.py) points this at a library built from a
+# deliberately wrong copy of the C file; such a library is loaded as it is, never rebuilt.
+_OVERRIDE = os.environ.get("COS_ORACLE_LIBRARY")
 
 DTYPE_F32 = 0
 DTYPE_BF16 = 1
@@ -30,6 +33,8 @@ FLAG_TAIL_CLAMP = 2
 
 def build(force: bool = True) -> str:
     """Compile the oracle with gcc (plain C99, OpenMP over batch rows)."""
+    if _OVERRIDE:
+        return _OVERRIDE
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         cmd = ["gcc", "-std=c99", "-O2", "-Wall", "-Wextra", "-fopenmp", "-shared", "-fPIC",
                "-o", _LIB, _SRC, "-lm"]
@@ -50,7 +55,7 @@ def _load():
     global _lib
     if _lib is None:
         build(force=False)
-        lib = ctypes.CDLL(_LIB)
+        lib = ctypes.CDLL(_OVERRIDE or _LIB)
         dp = ctypes.POINTER(ctypes.c_double)
         ip = ctypes.POINTER(ctypes.c_int32)
         vp = ctypes.c_void_p
