@@ -201,6 +201,54 @@ def test_maximum_gamma_and_models():
         assert np.array_equal(alen, base[0]) and np.array_equal(toks, base[1])
 
 
+def _correlated_inputs(n, B, gamma, V, seed, spread=1.0):
+    """Large bf16 tensors built on the device, one model at a time: a shared base plus noise per model."""
+    g = torch.Generator(device="cuda").manual_seed(seed)
+    g1 = gamma + 1
+    logits = torch.empty((n, B, g1, V), dtype=torch.bfloat16, device="cuda")
+    base = torch.randn((B, g1, V), generator=g, device="cuda") * 2.5
+    for m in range(n):
+        logits[m] = (base + torch.randn((B, g1, V), generator=g, device="cuda") * spread).to(torch.bfloat16)
+    del base
+    proposer = torch.randint(0, n, (B,), generator=g, device="cuda", dtype=torch.int32)
+    # drafts from the proposer's own row by the Gumbel trick (Eq. (1))
+    drafts = torch.empty((B, gamma), dtype=torch.int32, device="cuda")
+    for b0 in range(0, B, 64):
+        sl = slice(b0, min(b0 + 64, B))
+        rows = logits[proposer[sl].long(), torch.arange(sl.start, sl.stop, device="cuda"), :gamma].float()
+        gum = -torch.log(-torch.log(torch.rand(rows.shape, generator=g, device="cuda").clamp_min(1e-30)))
+        drafts[sl] = (rows + gum).argmax(-1).to(torch.int32)
+    return {"logits": logits, "draft_tokens": drafts, "proposer_idx": proposer,
+            "u_accept": torch.rand((B, gamma), generator=g, device="cuda", dtype=torch.float64),
+            "u_resample": torch.rand((B,), generator=g, device="cuda", dtype=torch.float64)}
+
+
+@pytest.mark.parametrize("name,n,B,gamma,V,mode,weights", [
+    ("ensemble of 4", 4, 640, 6, 256000, C.COS_COMBINE_ENSEMBLE, [0.25] * 4),
+    ("ensemble of 6", 6, 440, 6, 256000, C.COS_COMBINE_ENSEMBLE, [0.3, 0.2, 0.2, 0.1, 0.1, 0.1]),
+    ("contrastive", 2, 1100, 7, 256000, C.COS_COMBINE_CONTRASTIVE, [0.5, 0.1]),
+    ("logit mix of 3", 3, 860, 6, 256000, C.COS_COMBINE_LOGIT_MIX, [0.8, 0.4, -0.2]),
+])
+def test_more_than_two_to_the_32_logits(name, n, B, gamma, V, mode, weights):
+    """Tensors of more than 2^32 elements (9-11 GB): element offsets that no longer fit 32 bits, signed or
+    unsigned.  Rows from both ends and the middle of the batch -- the last ones lie past the 2^32nd element of the
+    later models -- go through the oracle; every row gets the structural checks."""
+    assert n * B * (gamma + 1) * V > 1 << 32
+    inp = _correlated_inputs(n, B, gamma, V, seed=4242 + n)
+    alen, toks, diag = P.run_gpu(inp, mode, weights)
+    rng = np.random.default_rng(n)
+    rows = sorted(set([0, 1, B // 2, B - 3, B - 2, B - 1] + rng.integers(0, B, 10).tolist()))
+    rep = P.compare(inp, mode, weights, alen, toks, diag, rows=rows)
+    _report(f"2^32+ elements, {name}", rep)
+    assert np.all((alen >= 0) & (alen <= gamma))
+    d = inp["draft_tokens"].cpu().numpy()
+    for b in range(B):
+        a = int(alen[b])
+        assert np.array_equal(toks[b, :a], d[b, :a]) and 0 <= toks[b, a] < V and np.all(toks[b, a + 1:] == -1), b
+    if mode != C.COS_COMBINE_CONTRASTIVE:
+        assert len(set(alen.tolist())) >= gamma, np.bincount(alen, minlength=gamma + 1)
+
+
 def test_two_streams_with_their_own_workspaces_overlap():
     """Calls that overlap in time need distinct workspaces, and with them they do not disturb each other."""
     w = W.C3.scaled(B=16)
