@@ -92,7 +92,10 @@ cos_status_t launch_all(Params p, int mode, int window, size_t lds, hipStream_t 
     } else {
       // alpha_cd = 0 is Eq. (5) as printed: no mask, so no pass for the expert maxima
       if (p.masked) hipLaunchKernelGGL((expert_rowmax_kernel<T, ALIGNED>), grid, block, 0, st, p);
-      hipLaunchKernelGGL((contrastive_stats_kernel<T, ALIGNED>), grid, block, 0, st, p);
+      if (p.masked)
+        hipLaunchKernelGGL((contrastive_stats_kernel<T, ALIGNED, true>), grid, block, 0, st, p);
+      else
+        hipLaunchKernelGGL((contrastive_stats_kernel<T, ALIGNED, false>), grid, block, 0, st, p);
     }
     if (hipGetLastError() != hipSuccess) return COS_ERR_LAUNCH;
   }

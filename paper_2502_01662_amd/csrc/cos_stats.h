@@ -59,6 +59,16 @@ __device__ __forceinline__ void running_add(Running& run, const float (&x)[U][N]
     for (int k = 0; k < N; ++k) run.acc[k & 3] += fast_exp2(fmaf(x[u][k], scale, neg_o));
 }
 
+// The same for row `sel` of NR rows held in registers.  `sel` is uniform over the wavefront, so the row
+// is chosen by a scalar branch around NR copies of the accumulation instead of a select per element.
+template <int NR, int U, int N>
+__device__ __forceinline__ void running_add_row(Running& run, const float (&x)[NR][U][N], int sel, float scale) {
+  sel = __builtin_amdgcn_readfirstlane(sel);
+#pragma unroll
+  for (int m = 0; m < NR; ++m)
+    if (m == sel) running_add<U, N>(run, x[m], scale);
+}
+
 // ---- raw-register variant for 16-byte aligned rows -------------------------
 //
 // For the 16-bit formats (bf16, binary16: both sign-magnitude) the maximum is taken on
@@ -603,7 +613,7 @@ __global__ void __launch_bounds__(kThreads) expert_rowmax_kernel(Params p) {
 // Contrastive, kernel 2.  Workgroup index -> (b, j, s); reads the chunk of both
 // rows once and produces the proposer row's softmax statistic and the masked
 // statistic of the contrastive logits (Eq. (5) restricted to the mask).
-template <typename T, bool ALIGNED>
+template <typename T, bool ALIGNED, bool MASKED>
 __global__ void __launch_bounds__(kThreads) contrastive_stats_kernel(Params p) {
   constexpr int N = VecOf<T>::N;
   constexpr int U = kUnroll >= 2 ? kUnroll / 2 : 1;
@@ -646,14 +656,14 @@ __global__ void __launch_bounds__(kThreads) contrastive_stats_kernel(Params p) {
   {
     const float* rm = p.rowmax + ((size_t)b * g1 + j) * p.S;
     float lm = -INFINITY;
-    for (int i = tid; i < pl.S && p.masked; i += kThreads) lm = fmaxf(lm, rm[i]);
+    for (int i = tid; i < pl.S && MASKED; i += kThreads) lm = fmaxf(lm, rm[i]);
     const float wm = wave_max(lm);
     if (lane_id() == 0) s_m0[tid >> 6] = wm;
     __syncthreads();
   }
   float m0 = s_m0[0];
   for (int w = 1; w < kWaves; ++w) m0 = fmaxf(m0, s_m0[w]);
-  if (!p.masked) m0 = 0.0f;  // no mask: every finite expert logit is in
+  if (!MASKED) m0 = 0.0f;  // no mask: every finite expert logit is in
 
   const T* row0 = row_ptr<T>(p, 0, b, j);
   const T* row1 = row_ptr<T>(p, 1, b, j);
@@ -664,37 +674,60 @@ __global__ void __launch_bounds__(kThreads) contrastive_stats_kernel(Params p) {
   running_init(rq);
   running_init(rc);
   for (int base = v0; base < v1; base += kStep) {
-    float x0[U][N], x1[U][N];
+    float x[2][U][N];
     if (base + kStep <= v1) {
-      load_group<T, ALIGNED, false, U>(row0, base, v1, p.V, x0);
-      load_group<T, ALIGNED, false, U>(row1, base, v1, p.V, x1);
+      load_group<T, ALIGNED, false, U>(row0, base, v1, p.V, x[0]);
+      load_group<T, ALIGNED, false, U>(row1, base, v1, p.V, x[1]);
     } else {
-      load_group<T, ALIGNED, true, U>(row0, base, v1, p.V, x0);
-      load_group<T, ALIGNED, true, U>(row1, base, v1, p.V, x1);
+      load_group<T, ALIGNED, true, U>(row0, base, v1, p.V, x[0]);
+      load_group<T, ALIGNED, true, U>(row1, base, v1, p.V, x[1]);
     }
-    // proposer row statistic, on the shifted logits like the contrastive one: with mu = 0 and
-    // the expert proposing, r and q then see the very same numbers and cancel exactly
-    {
+    float c[U][N];
+    if constexpr (!MASKED) {
+      // Eq. (5) as printed, no mask: the rows are shifted in place and c comes straight from them.  An
+      // expert logit of -inf gives c = -inf by itself unless the amateur's is not finite either; only a
+      // group in which some c comes out NaN or +inf pays for the explicit test.
+      bool odd = false;
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int k = 0; k < N; ++k) {
+          x[0][u][k] -= ref0;
+          x[1][u][k] -= ref1;
+          c[u][k] = fmaf(-p.mu_lo, x[1][u][k], fmaf(-p.mu_hi, x[1][u][k], x[0][u][k]));
+          odd = odd || !(c[u][k] < INFINITY);
+        }
+      if (__ballot(odd)) {
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+          for (int k = 0; k < N; ++k) c[u][k] = (x[0][u][k] > -INFINITY) ? c[u][k] : -INFINITY;
+      }
+      // the proposer's statistic on the same shifted logits: with mu = 0 and the expert proposing,
+      // r and q see the very same numbers and cancel exactly
+      running_add_row<2, U, N>(rq, x, pi, p.scale);
+      running_add<U, N>(rc, c, p.scale);
+    } else {
+      // proposer row statistic, on the shifted logits like the contrastive one
       float xq[U][N];
       const float refq = pi ? ref1 : ref0;
 #pragma unroll
       for (int u = 0; u < U; ++u)
 #pragma unroll
-        for (int k = 0; k < N; ++k) xq[u][k] = (pi ? x1[u][k] : x0[u][k]) - refq;
+        for (int k = 0; k < N; ++k) xq[u][k] = (pi ? x[1][u][k] : x[0][u][k]) - refq;
       running_add<U, N>(rq, xq, p.scale);
+      // masked contrastive statistic; the mask is sparse, so skip wave-wide when empty
+      float lmc = -INFINITY;
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int k = 0; k < N; ++k) {
+          const bool in = in_mask<T>(x[0][u][k], m0, p.thr32, p.thr64);
+          c[u][k] = in ? contrast(x[0][u][k], x[1][u][k], p.mu_hi, p.mu_lo, ref0, ref1) : -INFINITY;
+          lmc = fmaxf(lmc, c[u][k]);
+        }
+      if (__ballot(lmc > -INFINITY)) running_add<U, N>(rc, c, p.scale);
     }
-    // masked contrastive statistic; the mask is sparse, so skip wave-wide when empty
-    float c[U][N];
-    float lmc = -INFINITY;
-#pragma unroll
-    for (int u = 0; u < U; ++u)
-#pragma unroll
-      for (int k = 0; k < N; ++k) {
-        const bool in = in_mask<T>(x0[u][k], m0, p.thr32, p.thr64);
-        c[u][k] = in ? contrast(x0[u][k], x1[u][k], p.mu_hi, p.mu_lo, ref0, ref1) : -INFINITY;
-        lmc = fmaxf(lmc, c[u][k]);
-      }
-    if (__ballot(lmc > -INFINITY)) running_add<U, N>(rc, c, p.scale);
   }
   const double zq = running_total(rq);
   const double zc = running_total(rc);
@@ -780,34 +813,40 @@ __global__ void __launch_bounds__(kThreads) mix_stats_kernel(Params p) {
       for (int m = 0; m < NCAP; ++m)
         if (m < n) load_group<T, ALIGNED, true, U>(rows[m], base, v1, p.V, x[m]);
     }
-    float xq[U][N];
-    float refq = ref[0];
-#pragma unroll
-    for (int m = 1; m < NCAP; ++m) refq = (m == pi) ? ref[m] : refq;
+    // The rows are shifted in place; c = sum_m beta_m d_m in model order with the two multiply-adds per
+    // model of mix_one.  A model with beta_m = 0 adds 0 * d_m = 0 when d_m is finite; a -inf (or
+    // non-finite) logit shows as a c that is not finite, and only such a group pays for mix_one's tests.
+    float c[U][N];
+    bool odd = false;
 #pragma unroll
     for (int u = 0; u < U; ++u)
 #pragma unroll
       for (int k = 0; k < N; ++k) {
-        float v = x[0][u][k];
+        float acc = 0.0f;
 #pragma unroll
-        for (int m = 1; m < NCAP; ++m) {
-          const float xm = x[m][u][k];
-          v = (m == pi) ? xm : v;
-        }
-        xq[u][k] = v - refq;  // shifted like the mixed logits: a one-hot mix on the proposer cancels exactly
+        for (int m = 0; m < NCAP; ++m)
+          if (m < n) {
+            x[m][u][k] -= ref[m];
+            acc = fmaf(p.beta_lo[m], x[m][u][k], fmaf(p.beta_hi[m], x[m][u][k], acc));
+          }
+        c[u][k] = acc;
+        odd = odd || !(fabsf(acc) < INFINITY);
       }
-    running_add<U, N>(rq, xq, p.scale);
+    // shifted like the mixed logits: a one-hot mix on the proposer cancels exactly
+    running_add_row<NCAP, U, N>(rq, x, pi, p.scale);
     if (!plain) {
-      float c[U][N];
+      if (__ballot(odd)) {
+        const float zero[NCAP] = {};
 #pragma unroll
-      for (int u = 0; u < U; ++u)
+        for (int u = 0; u < U; ++u)
 #pragma unroll
-        for (int k = 0; k < N; ++k) {
-          float l[NCAP];
+          for (int k = 0; k < N; ++k) {
+            float l[NCAP];
 #pragma unroll
-          for (int m = 0; m < NCAP; ++m) l[m] = x[m][u][k];
-          c[u][k] = mix_one<NCAP>(p, n, l, ref);
-        }
+            for (int m = 0; m < NCAP; ++m) l[m] = x[m][u][k];
+            c[u][k] = mix_one<NCAP>(p, n, l, zero);  // -inf stays -inf under the shift
+          }
+      }
       running_add<U, N>(rc, c, p.scale);
     }
   }
