@@ -494,6 +494,39 @@ __device__ __forceinline__ float mix_one(const Params& p, int n, const float (&l
   return dead ? -INFINITY : acc;
 }
 
+// The rows of one vector shifted by their references, d_m = l_m - ref_m, and their combination
+// c = sum_m beta_m d_m, with mix_one's numbers: the same two multiply-adds per model in model
+// order; a model with beta_m = 0 adds 0 * d_m = 0 when d_m is finite.  A -inf (or non-finite) logit
+// shows as a c that is not finite; only a wavefront that sees one pays for mix_one's tests (-inf
+// stays -inf under the shift).  want_c = false (uniform): only the shifted rows are wanted.
+template <int NCAP, int N>
+__device__ __forceinline__ void mix_shifted_rows(const Params& p, int n, const float (&x)[NCAP][N],
+                                                 const float (&ref)[NCAP], bool want_c,
+                                                 float (&d)[NCAP][N], float (&c)[N]) {
+  bool odd = false;
+#pragma unroll
+  for (int k = 0; k < N; ++k) {
+    float acc = 0.0f;
+#pragma unroll
+    for (int m = 0; m < NCAP; ++m) {
+      d[m][k] = m < n ? x[m][k] - ref[m] : 0.0f;
+      if (m < n) acc = fmaf(p.beta_lo[m], d[m][k], fmaf(p.beta_hi[m], d[m][k], acc));
+    }
+    c[k] = acc;
+    odd = odd || !(fabsf(acc) < INFINITY);
+  }
+  if (want_c && __ballot(odd)) {
+    const float zero[NCAP] = {};
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+      float l[NCAP];
+#pragma unroll
+      for (int m = 0; m < NCAP; ++m) l[m] = d[m][k];
+      c[k] = mix_one<NCAP>(p, n, l, zero);
+    }
+  }
+}
+
 // Element k of the row of model `sel` (wave-uniform) out of the loaded rows.
 template <int NCAP, int N>
 __device__ __forceinline__ float pick_row(const float (&x)[NCAP][N], int sel, int k) {

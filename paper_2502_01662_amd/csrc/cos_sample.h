@@ -37,18 +37,24 @@ __device__ __forceinline__ void eval_f_contrastive(const float (&x0)[N], const f
                                                    int pi, int plain, float m0, const Params& p,
                                                    const float (&coef)[2], const float (&off)[2],
                                                    const float (&ref)[2], float (&f)[N]) {
-  const int qsel = plain >= 0 ? plain : pi;
+  const int qsel = __builtin_amdgcn_readfirstlane(plain >= 0 ? plain : pi);  // uniform: a scalar branch
+  float q[N];
+  if (qsel) {
+#pragma unroll
+    for (int k = 0; k < N; ++k) q[k] = coef[1] * fast_exp2(fmaf(x1[k] - ref[1], p.scale, -off[1]));
+  } else {
+#pragma unroll
+    for (int k = 0; k < N; ++k) q[k] = coef[1] * fast_exp2(fmaf(x0[k] - ref[0], p.scale, -off[1]));
+  }
 #pragma unroll
   for (int k = 0; k < N; ++k) {
-    const float lq = qsel ? x1[k] - ref[1] : x0[k] - ref[0];
-    const float q = coef[1] * fast_exp2(fmaf(lq, p.scale, -off[1]));
     if (plain >= 0) {
-      f[k] = q;
+      f[k] = q[k];
     } else {
       const bool in = in_mask<T>(x0[k], m0, p.thr32, p.thr64);
       const float c = contrast(x0[k], x1[k], p.mu_hi, p.mu_lo, ref[0], ref[1]);
       const float r = coef[0] * fast_exp2(fmaf(c, p.scale, -off[0]));
-      f[k] = in ? fmaxf(r - q, 0.0f) : 0.0f;
+      f[k] = in ? fmaxf(r - q[k], 0.0f) : 0.0f;
     }
   }
 }
@@ -62,21 +68,24 @@ __device__ __forceinline__ void eval_f_mix(const float (&x)[NCAP][N], int n, int
                                            const float (&off)[NCAP], const float (&ref)[NCAP],
                                            float (&f)[N]) {
   static_assert(NCAP >= 2, "two coefficients");
-  const int qsel = plain >= 0 ? plain : pi;
-  float refq = ref[0];
+  const int qsel = __builtin_amdgcn_readfirstlane(plain >= 0 ? plain : pi);  // uniform: a scalar branch
+  // the shifted rows and their combination (mix_shifted_rows: mix_one's numbers at less arithmetic)
+  float d[NCAP][N], c[N];
+  mix_shifted_rows<NCAP, N>(p, n, x, ref, plain < 0, d, c);
+  float q[N];
 #pragma unroll
-  for (int m = 1; m < NCAP; ++m) refq = (m == qsel) ? ref[m] : refq;
+  for (int m = 0; m < NCAP; ++m)
+    if (m == qsel) {
+#pragma unroll
+      for (int k = 0; k < N; ++k) q[k] = coef[1] * fast_exp2(fmaf(d[m][k], p.scale, -off[1]));
+    }
 #pragma unroll
   for (int k = 0; k < N; ++k) {
-    const float q = coef[1] * fast_exp2(fmaf(pick_row<NCAP, N>(x, qsel, k) - refq, p.scale, -off[1]));
     if (plain >= 0) {
-      f[k] = q;
+      f[k] = q[k];
     } else {
-      float l[NCAP];
-#pragma unroll
-      for (int m = 0; m < NCAP; ++m) l[m] = x[m][k];
-      const float r = coef[0] * fast_exp2(fmaf(mix_one<NCAP>(p, n, l, ref), p.scale, -off[0]));
-      f[k] = fmaxf(r - q, 0.0f);
+      const float r = coef[0] * fast_exp2(fmaf(c[k], p.scale, -off[0]));
+      f[k] = fmaxf(r - q[k], 0.0f);
     }
   }
 }
@@ -686,7 +695,7 @@ __global__ void __launch_bounds__(kThreads) acceptance_rate_kernel(Params p) {
     if (c == 0 && threadIdx.x == 0) p.alpha[(size_t)b * p.gamma + j] = NAN;
     return;
   }
-  const int pi = p.proposer_pos ? p.proposer_pos[(size_t)b * p.gamma + j] : p.proposer[b];
+  const int pi = __builtin_amdgcn_readfirstlane(p.proposer_pos ? p.proposer_pos[(size_t)b * p.gamma + j] : p.proposer[b]);
   const double* lse = p.lse_all + ((size_t)b * g1 + j) * p.nstat;
   const float m0 = CONTRASTIVE ? p.rowmax_all[(size_t)b * g1 + j] : 0.0f;
 
@@ -727,7 +736,18 @@ __global__ void __launch_bounds__(kThreads) acceptance_rate_kernel(Params p) {
   for (int t = tb + wave; t < te; t += kWaves) {
     float x[NCAP][N];
     tile_load<T, ALIGNED, NCAP>(p, rows, n, t, x);
+    [[maybe_unused]] float d[NCAP][N], cm[N];
+    if constexpr (MODE == kMix) mix_shifted_rows<NCAP, N>(p, n, x, ref, true, d, cm);
     if (t * 64 + lane < p.nvec) {
+      [[maybe_unused]] float qm[N];
+      if constexpr (MODE == kMix) {
+#pragma unroll
+        for (int m = 0; m < NCAP; ++m)
+          if (m == pi) {  // uniform over the workgroup: a scalar branch
+#pragma unroll
+            for (int k = 0; k < N; ++k) qm[k] = cq * fast_exp2(fmaf(d[m][k], p.scale, -off[1]));
+          }
+      }
 #pragma unroll
       for (int k = 0; k < N; ++k) {
         float r = 0.0f, q = 0.0f;
@@ -740,11 +760,8 @@ __global__ void __launch_bounds__(kThreads) acceptance_rate_kernel(Params p) {
               if (m == pi) q = cq * e;
             }
         } else if constexpr (MODE == kMix) {
-          float l[NCAP];
-#pragma unroll
-          for (int m = 0; m < NCAP; ++m) l[m] = x[m][k];
-          r = cr[0] * fast_exp2(fmaf(mix_one<NCAP>(p, n, l, ref), p.scale, -off[0]));
-          q = cq * fast_exp2(fmaf(pick_row<NCAP, N>(x, pi, k) - refq, p.scale, -off[1]));
+          r = cr[0] * fast_exp2(fmaf(cm[k], p.scale, -off[0]));
+          q = qm[k];
         } else {
           const bool in = in_mask<T>(x[0][k], m0, p.thr32, p.thr64);
           const float cc = contrast(x[0][k], x[1][k], p.mu_hi, p.mu_lo, ref[0], ref[1]);

@@ -161,12 +161,20 @@ void choose_split(const Tune& tn, int rows_total, int nvec, int* S_out, int* cv_
     long s_want = (3072 + rows_total - 1) / (rows_total > 0 ? rows_total : 1);
     if (s_want < 1) s_want = 1;
     cv = (int)((nvec + s_want - 1) / s_want);
-    // never less than one full group of loads per thread: shorter chunks only add hand-offs
-    if (cv < kThreads * kUnroll) cv = kThreads * kUnroll;
+    // never less than one full group of loads per thread (shorter chunks only add hand-offs), and a
+    // whole number of groups: a chunk's last, partly filled group costs a full one
+    constexpr int kGroup = kThreads * kUnroll;
+    cv = cv < kGroup ? kGroup : (cv + kGroup / 2) / kGroup * kGroup;
   }
   cv = (cv + kThreads - 1) / kThreads * kThreads;
   if (cv < kThreads) cv = kThreads;
   int S = (nvec + cv - 1) / cv;
+  if (tn.chunk_vectors <= 0 && S > 1 && nvec - (S - 1) * cv < kThreads * kUnroll / 4) {
+    // a sliver left over for the last chunk is not worth a workgroup of its own
+    --S;
+    cv = ((nvec + S - 1) / S + kThreads - 1) / kThreads * kThreads;
+    S = (nvec + cv - 1) / cv;
+  }
   const int smax = max_splits(nvec);
   if (S > smax) {
     S = smax;
