@@ -219,6 +219,16 @@ cos_status_t cos_verify(const void *logits, cos_dtype_t dt, int n, int B, int ga
  *               call then skips the kernel that clears them.  For loops that verify
  *               the same shape step after step; a promise that does not hold gives
  *               undefined outputs (never an out-of-bounds access).
+ * refine_kernels  how a residual of little mass (the models nearly agree at the rejected
+ *               position: Sec. 3.2's norm(max(0, r - q)) with r close to q) is drawn from once
+ *               more in its difference form, which takes two more passes over that
+ *               position's rows.  0: by the size of a row-set (n * V * element size) --
+ *               up to 256 KiB the sequence's last sampling workgroup does it alone, above
+ *               that two more launches do it with many workgroups per such sequence
+ *               (a few microseconds when no sequence needs them, against a stall of the
+ *               whole call on one workgroup's two passes over a large row-set).
+ *               > 0: always the two launches; < 0: never.  Same outputs either way.  The
+ *               workspace does not depend on it.
  * event_start, event_stop
  *               hipEvent_t handles created by the caller, or NULL.  The call records
  *               event_start on its stream just before its streaming kernel(s) -- the
@@ -241,6 +251,7 @@ typedef struct cos_options_t {
   int tail_factor;
   int two_pass_mask;
   int workspace_ready;
+  int refine_kernels;
   void *event_start;
   void *event_stop;
 } cos_options_t;

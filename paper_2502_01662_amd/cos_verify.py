@@ -42,7 +42,8 @@ class CosOptions(ctypes.Structure):
                 ("num_drafts", ctypes.c_void_p), ("no_bonus", ctypes.c_int),
                 ("chunk_vectors", ctypes.c_int), ("sample_blocks", ctypes.c_int),
                 ("tail_sequences", ctypes.c_int), ("tail_factor", ctypes.c_int), ("two_pass_mask", ctypes.c_int),
-                ("workspace_ready", ctypes.c_int), ("event_start", ctypes.c_void_p), ("event_stop", ctypes.c_void_p)]
+                ("workspace_ready", ctypes.c_int), ("refine_kernels", ctypes.c_int),
+                ("event_start", ctypes.c_void_p), ("event_stop", ctypes.c_void_p)]
 
 
 class CosVerifyError(RuntimeError):
@@ -114,10 +115,11 @@ class LaunchShape:
     tail_factor: int = 0        # 0: 4
     two_pass_mask: int = 0      # 1: masked contrastive mode by its older two-pass route
     workspace_ready: int = 0    # 1: promise that the workspace's arrival counters are zero (skips the clearing kernel)
+    refine_kernels: int = 0     # residuals of little mass: > 0 the two refinement launches, < 0 the lone workgroup, 0 by size
 
     def any(self) -> bool:
         return bool(self.chunk_vectors or self.sample_blocks or self.tail_sequences or self.tail_factor
-                    or self.two_pass_mask or self.workspace_ready)
+                    or self.two_pass_mask or self.workspace_ready or self.refine_kernels)
 
 
 def _options(temperature=0.0, bonus_idx=None, proposer_pos=None, alpha=None, stop_window=0, greedy=False,
@@ -128,7 +130,7 @@ def _options(temperature=0.0, bonus_idx=None, proposer_pos=None, alpha=None, sto
     return CosOptions(ctypes.sizeof(CosOptions), float(temperature), ptr(bonus_idx), ptr(proposer_pos), ptr(alpha),
                       int(stop_window), int(bool(greedy)), ptr(num_drafts), int(bool(no_bonus)),
                       int(shape.chunk_vectors), int(shape.sample_blocks), int(shape.tail_sequences),
-                      int(shape.tail_factor), int(shape.two_pass_mask), int(shape.workspace_ready), ev0, ev1)
+                      int(shape.tail_factor), int(shape.two_pass_mask), int(shape.workspace_ready), int(shape.refine_kernels), ev0, ev1)
 
 
 def cos_verify_workspace_bytes_ex(n: int, B: int, gamma: int, V: int, dt: int, mode: int,

@@ -77,8 +77,12 @@ struct SeqPlan {
   int bonus;     // >= 0: the bonus token is drawn from this model's softmax alone (jstar == gamma)
   float m0;      // contrastive: expert maximum at jstar
   int skip;      // 1: every draft accepted and no extra token wanted: nothing is sampled
+  int redo;      // left by the sampling kernel for the refinement kernels: 0 the token is drawn,
+                 // kLittleMass: draw from the residual in its difference form, kNoMass: draw from r
+  int pad;
   double lse2[COS_MAX_MODELS];  // log2-sum-exp2 of the statistics at jstar
 };
+constexpr int kDrawn = 0, kNoMass = 1, kLittleMass = 2;  // what a draw reports (cos_sample.h)
 
 struct Params {
   const void* logits;
@@ -95,7 +99,8 @@ struct Params {
   int* out_tokens;
   // workspace
   int* counters;      // (stride kCtrStride) [nwin windows][B] streaming arrivals, [B] sampling
-                      // arrivals, [B][gamma] acceptance-rate arrivals
+                      // arrivals, 2 x [B] arrivals of the refinement kernels and their two control
+                      // counters, [B][gamma] acceptance-rate arrivals
   Partial* partials;  // [B][gamma+1][nstat][S]
   float* rowmax;      // contrastive: [B][gamma+1][S] partial maxima of the expert row
   Cand* cand;         // masked contrastive, one-pass: [B][gamma+1][S][cand_cap] candidates of every chunk
@@ -103,6 +108,13 @@ struct Params {
   int cand_cap;
   SeqPlan* plans;     // [B]
   HandOff<double>* tile_sums;  // [B][ntiles]
+  // refinement kernels (a residual of little or no mass drawn from once more, by many workgroups)
+  int* refine_ctl;                   // two counters (stride kCtrStride): marked sequences; those finished
+  int* refine_list;                  // [B]: the marked sequences, in the order they were marked
+  HandOff<double>* refine_partials;  // [refine_grid][COS_MAX_MODELS + 1]: every workgroup's sums of the first pass
+  float* refine_dlse;                // [B][COS_MAX_MODELS]: differences of the log-normalisers it gives
+  int refine_grid;                   // workgroups of a refinement launch (>= B)
+  int refine_cmax;                   // most workgroups one sequence is split over (>= 8 tiles each)
   // acceptance-rate output (optional)
   double* alpha;           // [B][gamma] out, or NULL
   double* lse_all;         // [B][gamma+1][nstat] log2-sum-exp2 of every position
@@ -144,6 +156,8 @@ struct LaunchPlan {
   int greedy;       // temperature 0: one argmax kernel instead
   int onepass;      // masked contrastive mode in one read of the logits (candidate lists), no counters
   int ready;        // the caller promises zeroed arrival counters: no clearing kernel
+  int refine_kernels;  // residuals of little mass are drawn from by two more launches of the sampling
+                       // grid (which do nothing when no sequence needs them) instead of by one workgroup
   int aligned;      // every row starts on a 16-byte boundary and V is a multiple of the vector width
   int counters;     // arrival counters (ints, with their stride) the fill kernel clears
   size_t lds;       // dynamic LDS of the sampling kernel (one double per tile)

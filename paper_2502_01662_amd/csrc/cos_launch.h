@@ -13,20 +13,35 @@ namespace {
 
 // Kernels that hold the rows of all n models in registers are specialised for
 // n = 1..4; more models take the generic instance.
+template <typename T, bool ALIGNED, int NM, int MODE>
+void launch_sampling_kernels(const Params& p, bool refine_kernels, dim3 grid, size_t lds, hipStream_t st) {
+  const dim3 block(kThreads);
+  if (!refine_kernels) {
+    hipLaunchKernelGGL((sample_kernel<T, ALIGNED, NM, MODE, true>), grid, block, lds, st, p);
+    return;
+  }
+  // The sampling kernel only marks a sequence whose residual has little or no mass; the two launches
+  // after it split the marked sequences between their workgroups (which return at once when there is none).
+  hipLaunchKernelGGL((sample_kernel<T, ALIGNED, NM, MODE, false>), grid, block, lds, st, p);
+  const dim3 rgrid((unsigned)p.refine_grid);
+  hipLaunchKernelGGL((refine_sums_kernel<T, ALIGNED, NM, MODE>), rgrid, block, 0, st, p);
+  hipLaunchKernelGGL((refine_draw_kernel<T, ALIGNED, NM, MODE>), rgrid, block, lds, st, p);
+}
+
 template <typename T, bool ALIGNED, int MODE>
-cos_status_t launch_sampling(const Params& p, size_t lds, hipStream_t st) {
+cos_status_t launch_sampling(const Params& p, bool refine_kernels, size_t lds, hipStream_t st) {
   const long blocks = (long)p.B * p.C;
   if (blocks <= 0 || blocks > 0x7fffffffL) return COS_ERR_SHAPE;
-  const dim3 grid((unsigned)blocks), block(kThreads);
+  const dim3 grid((unsigned)blocks);
   if constexpr (MODE == kCd) {
-    hipLaunchKernelGGL((sample_kernel<T, ALIGNED, 2, kCd>), grid, block, lds, st, p);
+    launch_sampling_kernels<T, ALIGNED, 2, kCd>(p, refine_kernels, grid, lds, st);
   } else {
     switch (p.n) {
-      case 1: hipLaunchKernelGGL((sample_kernel<T, ALIGNED, 1, MODE>), grid, block, lds, st, p); break;
-      case 2: hipLaunchKernelGGL((sample_kernel<T, ALIGNED, 2, MODE>), grid, block, lds, st, p); break;
-      case 3: hipLaunchKernelGGL((sample_kernel<T, ALIGNED, 3, MODE>), grid, block, lds, st, p); break;
-      case 4: hipLaunchKernelGGL((sample_kernel<T, ALIGNED, 4, MODE>), grid, block, lds, st, p); break;
-      default: hipLaunchKernelGGL((sample_kernel<T, ALIGNED, 0, MODE>), grid, block, lds, st, p); break;
+      case 1: launch_sampling_kernels<T, ALIGNED, 1, MODE>(p, refine_kernels, grid, lds, st); break;
+      case 2: launch_sampling_kernels<T, ALIGNED, 2, MODE>(p, refine_kernels, grid, lds, st); break;
+      case 3: launch_sampling_kernels<T, ALIGNED, 3, MODE>(p, refine_kernels, grid, lds, st); break;
+      case 4: launch_sampling_kernels<T, ALIGNED, 4, MODE>(p, refine_kernels, grid, lds, st); break;
+      default: launch_sampling_kernels<T, ALIGNED, 0, MODE>(p, refine_kernels, grid, lds, st); break;
     }
   }
   return hipGetLastError() == hipSuccess ? COS_OK : COS_ERR_LAUNCH;
@@ -73,7 +88,7 @@ inline long stream_blocks(const Params& p, int rows_per_b) {
 // verified per streaming launch; sequences decided by an earlier window are
 // skipped by every later one (their workgroups return at once).
 template <typename T, bool ALIGNED>
-cos_status_t launch_all(Params p, int mode, int window, size_t lds, hipStream_t st,
+cos_status_t launch_all(Params p, int mode, int window, bool refine_kernels, size_t lds, hipStream_t st,
                         hipEvent_t ev_start, hipEvent_t ev_stop) {
   const dim3 block(kThreads);
   const int g1 = p.gamma + 1;
@@ -100,9 +115,9 @@ cos_status_t launch_all(Params p, int mode, int window, size_t lds, hipStream_t 
     if (hipGetLastError() != hipSuccess) return COS_ERR_LAUNCH;
   }
   if (ev_stop) (void)hipEventRecord(ev_stop, st);
-  cos_status_t rc = mode == kEns   ? launch_sampling<T, ALIGNED, kEns>(p, lds, st)
-                    : mode == kMix ? launch_sampling<T, ALIGNED, kMix>(p, lds, st)
-                                   : launch_sampling<T, ALIGNED, kCd>(p, lds, st);
+  cos_status_t rc = mode == kEns   ? launch_sampling<T, ALIGNED, kEns>(p, refine_kernels, lds, st)
+                    : mode == kMix ? launch_sampling<T, ALIGNED, kMix>(p, refine_kernels, lds, st)
+                                   : launch_sampling<T, ALIGNED, kCd>(p, refine_kernels, lds, st);
   if (rc != COS_OK || !p.alpha) return rc;
   return mode == kEns   ? launch_acceptance_rate<T, ALIGNED, kEns>(p, st)
          : mode == kMix ? launch_acceptance_rate<T, ALIGNED, kMix>(p, st)
@@ -173,8 +188,9 @@ cos_status_t run_kernels(Params p, const LaunchPlan& lp) {
     if (hipGetLastError() != hipSuccess) return COS_ERR_LAUNCH;
   }
   if (lp.greedy) return lp.aligned ? launch_greedy<T, true>(p, lp) : launch_greedy<T, false>(p, lp);
-  return lp.aligned ? launch_all<T, true>(p, lp.mode, lp.window, lp.lds, lp.stream, lp.ev_start, lp.ev_stop)
-                    : launch_all<T, false>(p, lp.mode, lp.window, lp.lds, lp.stream, lp.ev_start, lp.ev_stop);
+  const bool rk = lp.refine_kernels != 0;
+  return lp.aligned ? launch_all<T, true>(p, lp.mode, lp.window, rk, lp.lds, lp.stream, lp.ev_start, lp.ev_stop)
+                    : launch_all<T, false>(p, lp.mode, lp.window, rk, lp.lds, lp.stream, lp.ev_start, lp.ev_stop);
 }
 
 }  // namespace

@@ -388,7 +388,6 @@ __device__ __forceinline__ double lane_mass(const float (&f)[N]) {
 // Returns kDrawn, or without drawing: kNoMass if the weights have no mass and
 // may_retry is set, kLittleMass if their mass is below refine_below.
 // ---------------------------------------------------------------------------
-constexpr int kDrawn = 0, kNoMass = 1, kLittleMass = 2;
 constexpr double kRefineBelow = 1.0 / 32.0;  // residual mass under which the difference form is used
 
 template <typename T, bool ALIGNED, int NCAP, int MODE>
@@ -506,11 +505,28 @@ __device__ int draw_token(const Params& p, int b, const SeqPlan& plan, const T* 
 // sequence's token: the scan and the inverse CDF, and the two rare endings -- a residual of little
 // mass (r close to q) is evaluated once more in its difference form, a residual without mass falls
 // back to r.  Each ending recomputes every tile sum in this one workgroup.
+// One workgroup over every tile of a row-set, TB tiles per wavefront in flight (all loads issued before
+// the first is used): body(t, x) for this wavefront's tiles t = wave, wave + kWaves, ...
+template <typename T, bool ALIGNED, int NCAP, int TB, class Body>
+__device__ __forceinline__ void for_each_tile(const Params& p, const T* const (&rows)[NCAP], int n, Body&& body) {
+  constexpr int N = VecOf<T>::N;
+  const int wave = threadIdx.x >> 6;
+  for (int t0 = wave; t0 < p.ntiles; t0 += kWaves * TB) {
+    float x[TB][NCAP][N];
+#pragma unroll
+    for (int i = 0; i < TB; ++i) tile_load<T, ALIGNED, NCAP>(p, rows, n, min(t0 + i * kWaves, p.ntiles - 1), x[i]);
+#pragma unroll
+    for (int i = 0; i < TB; ++i)
+      if (t0 + i * kWaves < p.ntiles) body(t0 + i * kWaves, x[i]);
+  }
+}
+
 template <typename T, bool ALIGNED, int NCAP, int MODE>
 __device__ __forceinline__ void finish_draw(const Params& p, int b, const SeqPlan& plan, const T* const (&rows)[NCAP],
                                             int n, float (&coef)[NCAP], float (&off)[NCAP], const float (&ref)[NCAP],
                                             double* tile_sum, int& s_flag, Refine<NCAP>& s_rf) {
   constexpr int N = VecOf<T>::N;
+    constexpr int TB = 1;  // (the passes are bound by this one workgroup's arithmetic, not by its loads in flight)
   const int lane = lane_id();
   const int wave = threadIdx.x >> 6;
   const Refine<NCAP> no_refine = {};  // the plain, term-by-term evaluation
@@ -541,11 +557,9 @@ __device__ __forceinline__ void finish_draw(const Params& p, int b, const SeqPla
       double Q = 0.0, A[NCAP];
 #pragma unroll
       for (int m = 0; m < NCAP; ++m) A[m] = 0.0;
-      for (int t = wave; t < p.ntiles; t += kWaves) {
-        float x[NCAP][N];
-        tile_load<T, ALIGNED, NCAP>(p, rows, n, t, x);
+      for_each_tile<T, ALIGNED, NCAP, TB>(p, rows, n, [&](int t, const float (&x)[NCAP][N]) {
         if (t * 64 + lane < p.nvec) refine_sums<T, NCAP, N, MODE>(p, x, n, plan.pi, plan.m0, ref, rf, Q, A);
-      }
+      });
       // the tile sums are not needed any more: their LDS takes the wavefronts' totals
       __syncthreads();
       Q = wave_sum(Q);
@@ -571,12 +585,12 @@ __device__ __forceinline__ void finish_draw(const Params& p, int b, const SeqPla
       }
       __syncthreads();
     }
-    for (int t = wave; t < p.ntiles; t += kWaves) {
+    for_each_tile<T, ALIGNED, NCAP, TB>(p, rows, n, [&](int t, const float (&x)[NCAP][N]) {
       float f[N];
-      tile_weights<T, ALIGNED, NCAP, MODE>(p, rows, n, t, plan.pi, plan.bonus, plan.m0, coef, off, ref, f, true, rf);
+      tile_eval<T, NCAP, MODE>(p, x, n, t, plan.pi, plan.bonus, plan.m0, coef, off, ref, f, true, rf);
       const double ts = wave_sum(lane_mass<N>(f));
       if (lane == 0) tile_sum[t] = ts;
-    }
+    });
     __syncthreads();
     if (wave == 0)
       status = draw_token<T, ALIGNED, NCAP, MODE>(p, b, plan, rows, n, coef, off, ref, tile_sum, true,
@@ -589,13 +603,12 @@ __device__ __forceinline__ void finish_draw(const Params& p, int b, const SeqPla
   // The residual has no mass (cannot happen in exact arithmetic): draw from r
   // itself.  Rare, so this one workgroup recomputes every tile sum.
   plan_coefficients<NCAP, MODE>(p, plan, false, n, coef, off);
-  for (int t = wave; t < p.ntiles; t += kWaves) {
+  for_each_tile<T, ALIGNED, NCAP, TB>(p, rows, n, [&](int t, const float (&x)[NCAP][N]) {
     float f[N];
-    tile_weights<T, ALIGNED, NCAP, MODE>(p, rows, n, t, plan.pi, plan.bonus, plan.m0, coef, off, ref, f, false,
-                                         no_refine);
+    tile_eval<T, NCAP, MODE>(p, x, n, t, plan.pi, plan.bonus, plan.m0, coef, off, ref, f, false, no_refine);
     const double ts = wave_sum(lane_mass<N>(f));
     if (lane == 0) tile_sum[t] = ts;
-  }
+  });
   __syncthreads();
   if (wave == 0)
     draw_token<T, ALIGNED, NCAP, MODE>(p, b, plan, rows, n, coef, off, ref, tile_sum, false,
@@ -604,9 +617,11 @@ __device__ __forceinline__ void finish_draw(const Params& p, int b, const SeqPla
 
 // Sampling kernel.  Workgroup index -> (b, c): tiles [c*tpc, (c+1)*tpc) of the
 // sampled position's rows -> tile sums; the last workgroup of b draws the token.
-// A residual of little mass (r close to q) is evaluated once more in its difference form by the last
-// workgroup of its sequence.
-template <typename T, bool ALIGNED, int NM, int MODE>
+// A residual of little mass (r close to q) is evaluated once more in its difference form: by the last
+// workgroup of its sequence alone (LONE; two more passes over the row-set at the rate of one
+// workgroup, which is fine for small row-sets), or -- the sequence only marked here -- by the two
+// refinement kernels below, which every sampling workgroup of the sequence takes part in.
+template <typename T, bool ALIGNED, int NM, int MODE, bool LONE>
 __global__ void __launch_bounds__(kThreads) sample_kernel(Params p) {
   constexpr int N = VecOf<T>::N;
   constexpr bool CONTRASTIVE = MODE == kCd;
@@ -668,7 +683,227 @@ __global__ void __launch_bounds__(kThreads) sample_kernel(Params p) {
   // last workgroup of this sequence: all tile sums are published
   for (int t = threadIdx.x; t < p.ntiles; t += kThreads) tile_sum[t] = sums[t].read();
   __syncthreads();
-  finish_draw<T, ALIGNED, NCAP, MODE>(p, b, plan, rows, n, coef, off, ref, tile_sum, s_flag, s_rf);
+  if constexpr (LONE) {
+    finish_draw<T, ALIGNED, NCAP, MODE>(p, b, plan, rows, n, coef, off, ref, tile_sum, s_flag, s_rf);
+  } else {
+    if (wave == 0) {
+      const bool residual = plan.residual != 0;
+      const int status = draw_token<T, ALIGNED, NCAP, MODE>(p, b, plan, rows, n, coef, off, ref, tile_sum, residual,
+                                                            0, residual ? kRefineBelow : 0.0, false, no_refine);
+      if (lane == 0 && status != kDrawn) {  // for the refinement kernels: mark the sequence, add it to their list
+        p.plans[b].redo = status;
+        const int slot = __hip_atomic_fetch_add(p.refine_ctl, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        p.refine_list[slot] = b;
+      }
+    }
+  }
+}
+
+// The refinement kernels' work: the sequences the sampling kernel marked (refine_list), each split over
+// as many workgroups as the launch has to spare -- with few marked sequences each gets many, so that its
+// two extra passes over the row-set take microseconds instead of one workgroup's hundreds.  All
+// workgroups see the same final count, hence the same split.
+struct RefineTask {
+  int count;  // marked sequences
+  int cr;     // workgroups per marked sequence
+  int b;      // this workgroup's sequence (-1: none)
+  int c;      // its part of that sequence
+  int slot;   // cr * (index in the list) + c
+  int tb, te; // its tiles
+};
+__device__ __forceinline__ RefineTask refine_task(const Params& p) {
+  RefineTask t;
+  t.count = __hip_atomic_load(p.refine_ctl, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  t.b = -1;
+  if (t.count <= 0) return t;
+  t.cr = min(p.refine_cmax, max(1, p.refine_grid / t.count));
+  const int i = blockIdx.x / t.cr;
+  if (i >= t.count) return t;
+  t.c = blockIdx.x - i * t.cr;
+  t.slot = blockIdx.x;
+  t.b = p.refine_list[i];
+  const int per = (p.ntiles + t.cr - 1) / t.cr;
+  t.tb = min(t.c * per, p.ntiles);
+  t.te = min(t.tb + per, p.ntiles);
+  return t;
+}
+
+// Refinement, first kernel (a launch of refine_grid workgroups that return at once when no sequence is
+// marked): the sums that give the differences of the log-normalisers in difference form (refine_sums),
+// every workgroup over its own tiles; the last one of the sequence combines them.
+template <typename T, bool ALIGNED, int NM, int MODE>
+__global__ void __launch_bounds__(kThreads) refine_sums_kernel(Params p) {
+  constexpr int N = VecOf<T>::N;
+  constexpr bool CONTRASTIVE = MODE == kCd;
+  constexpr int NCAP = CONTRASTIVE ? 2 : (NM ? (MODE == kMix && NM < 2 ? 2 : NM) : COS_MAX_MODELS);
+  constexpr int TU = NCAP <= 4 ? 2 : 1;  // tiles in flight per wavefront
+  constexpr int NS = COS_MAX_MODELS + 1;
+  __shared__ double s_part[kWaves][NCAP + 1];
+  __shared__ int s_flag;
+  __shared__ Refine<NCAP> s_rf;
+
+  const RefineTask task = refine_task(p);
+  if (task.b < 0) return;
+  const int b = task.b;
+  const SeqPlan plan = p.plans[b];
+  if (plan.redo != kLittleMass) return;  // (no mass: nothing to refine, the second kernel draws from r)
+  const int lane = lane_id();
+  const int wave = threadIdx.x >> 6;
+  const int n = CONTRASTIVE ? 2 : (NM ? NM : p.n);
+  const T* rows[NCAP];
+#pragma unroll
+  for (int m = 0; m < NCAP; ++m) rows[m] = row_ptr<T>(p, m < n ? m : 0, b, plan.jstar);
+  float ref[NCAP];
+#pragma unroll
+  for (int m = 0; m < NCAP; ++m) ref[m] = (MODE != kEns && m < n) ? row_reference<T>(rows[m]) : 0.0f;
+  if (threadIdx.x == 0) plan_refine<NCAP, MODE>(p, plan, n, s_rf);
+  __syncthreads();
+  const Refine<NCAP>& rf = s_rf;
+
+  double Q = 0.0, A[NCAP];
+#pragma unroll
+  for (int m = 0; m < NCAP; ++m) A[m] = 0.0;
+  const int tb = task.tb, te = task.te;
+  for (int t = tb + wave; t < te; t += kWaves * TU) {
+    float x[TU][NCAP][N];
+#pragma unroll
+    for (int i = 0; i < TU; ++i) tile_load<T, ALIGNED, NCAP>(p, rows, n, min(t + i * kWaves, te - 1), x[i]);
+#pragma unroll
+    for (int i = 0; i < TU; ++i) {
+      const int ti = t + i * kWaves;
+      if (ti < te && ti * 64 + lane < p.nvec)
+        refine_sums<T, NCAP, N, MODE>(p, x[i], n, plan.pi, plan.m0, ref, rf, Q, A);
+    }
+  }
+  Q = wave_sum(Q);
+  if (lane == 0) s_part[wave][0] = Q;
+#pragma unroll
+  for (int m = 0; m < NCAP; ++m) {
+    const double a = wave_sum(A[m]);
+    if (lane == 0) s_part[wave][1 + m] = a;
+  }
+  __syncthreads();
+  HandOff<double>* parts = p.refine_partials + (size_t)(task.slot - task.c) * NS;  // of this sequence
+  if (threadIdx.x <= NCAP) {
+    double v = 0.0;
+    for (int w = 0; w < kWaves; ++w) v += s_part[w][threadIdx.x];
+    parts[(size_t)task.c * NS + threadIdx.x].publish(v);
+  }
+  wait_stores();
+  if (!arrive_last(p.counters + ((size_t)(p.nwin + 1) * p.B + b) * kCtrStride, task.cr, &s_flag)) return;
+
+  // last workgroup of the sequence: Z_t / Z_pi - 1 for every term, then the log-normaliser differences
+  if (threadIdx.x < NCAP) {
+    const int m = threadIdx.x;
+    double q = 0.0, a = 0.0;
+    for (int i = 0; i < task.cr; ++i) {
+      q += parts[(size_t)i * NS].read();
+      a += parts[(size_t)i * NS + 1 + m].read();
+    }
+    const double ratio = a / q;
+    const bool used = MODE == kEns ? rf.w[m] != 0.0f : m == 0;
+    float d = rf.dlse[m];
+    // (not finite, or not above -1: models that are not close after all; the streamed value stays)
+    if (used && ratio > -1.0 && ratio < INFINITY) d = (float)(log1p(ratio) * 1.4426950408889634);
+    p.refine_dlse[(size_t)b * COS_MAX_MODELS + m] = d;
+  }
+}
+
+// Refinement, second kernel (the same launch shape and split): the tile sums of a marked sequence once
+// more -- the residual in its difference form with the first kernel's normaliser differences, or r itself
+// where the residual had no mass -- and the draw by the sequence's last workgroup.  The workgroup that
+// finishes the last marked sequence empties the list for the next call.
+template <typename T, bool ALIGNED, int NM, int MODE>
+__global__ void __launch_bounds__(kThreads) refine_draw_kernel(Params p) {
+  constexpr int N = VecOf<T>::N;
+  constexpr bool CONTRASTIVE = MODE == kCd;
+  constexpr int NCAP = CONTRASTIVE ? 2 : (NM ? (MODE == kMix && NM < 2 ? 2 : NM) : COS_MAX_MODELS);
+  constexpr int TU = NCAP <= 4 ? 2 : 1;  // tiles in flight per wavefront
+  extern __shared__ double tile_sum[];
+  __shared__ int s_flag;
+  __shared__ Refine<NCAP> s_rf;
+
+  const RefineTask task = refine_task(p);
+  if (task.b < 0) return;
+  const int b = task.b;
+  const SeqPlan plan = p.plans[b];
+  const bool little = plan.redo == kLittleMass;
+  const int lane = lane_id();
+  const int wave = threadIdx.x >> 6;
+  const int n = CONTRASTIVE ? 2 : (NM ? NM : p.n);
+  const T* rows[NCAP];
+#pragma unroll
+  for (int m = 0; m < NCAP; ++m) rows[m] = row_ptr<T>(p, m < n ? m : 0, b, plan.jstar);
+  float ref[NCAP];
+#pragma unroll
+  for (int m = 0; m < NCAP; ++m) ref[m] = (MODE != kEns && m < n) ? row_reference<T>(rows[m]) : 0.0f;
+  float coef[NCAP], off[NCAP];
+  plan_coefficients<NCAP, MODE>(p, plan, little, n, coef, off);  // no mass: the weights of r itself
+  if (threadIdx.x == 0) {
+    plan_refine<NCAP, MODE>(p, plan, n, s_rf);
+    if (little) {
+#pragma unroll
+      for (int m = 0; m < NCAP; ++m) s_rf.dlse[m] = p.refine_dlse[(size_t)b * COS_MAX_MODELS + m];
+    }
+  }
+  __syncthreads();
+  const Refine<NCAP>& rf = s_rf;
+
+  HandOff<double>* sums = p.tile_sums + (size_t)b * p.ntiles;
+  const int tb = task.tb, te = task.te;
+  for (int t = tb + wave; t < te; t += kWaves * TU) {
+    float x[TU][NCAP][N];
+#pragma unroll
+    for (int i = 0; i < TU; ++i) tile_load<T, ALIGNED, NCAP>(p, rows, n, min(t + i * kWaves, te - 1), x[i]);
+#pragma unroll
+    for (int i = 0; i < TU; ++i) {
+      const int ti = t + i * kWaves;
+      float f[N];
+      tile_eval<T, NCAP, MODE>(p, x[i], n, min(ti, te - 1), plan.pi, plan.bonus, plan.m0, coef, off, ref, f, little, rf);
+      const double ts = wave_sum_to_lane63(lane_mass<N>(f));
+      if (lane == 63 && ti < te) tile_sum[ti - tb] = ts;
+    }
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < te - tb; i += kThreads) sums[tb + i].publish(tile_sum[i]);
+  wait_stores();
+  if (!arrive_last(p.counters + ((size_t)(p.nwin + 2) * p.B + b) * kCtrStride, task.cr, &s_flag)) return;
+
+  for (int t = threadIdx.x; t < p.ntiles; t += kThreads) tile_sum[t] = sums[t].read();
+  __syncthreads();
+  int status = kDrawn;
+  if (wave == 0)
+    status = draw_token<T, ALIGNED, NCAP, MODE>(p, b, plan, rows, n, coef, off, ref, tile_sum, little,
+                                                little ? COS_FLAG_RESIDUAL_REFINED : COS_FLAG_RESIDUAL_FALLBACK,
+                                                0.0, little, rf);
+  if (threadIdx.x == 0) s_flag = status;
+  __syncthreads();
+  if (s_flag != kDrawn) {
+    __syncthreads();
+    // The refined residual has no mass either (cannot happen in exact arithmetic): this one workgroup
+    // recomputes every tile sum of r itself and draws from that.
+    const Refine<NCAP> no_refine = {};
+    plan_coefficients<NCAP, MODE>(p, plan, false, n, coef, off);
+    for (int t = wave; t < p.ntiles; t += kWaves) {
+      float f[N];
+      tile_weights<T, ALIGNED, NCAP, MODE>(p, rows, n, t, plan.pi, plan.bonus, plan.m0, coef, off, ref, f, false,
+                                           no_refine);
+      const double ts = wave_sum(lane_mass<N>(f));
+      if (lane == 0) tile_sum[t] = ts;
+    }
+    __syncthreads();
+    if (wave == 0)
+      draw_token<T, ALIGNED, NCAP, MODE>(p, b, plan, rows, n, coef, off, ref, tile_sum, false,
+                                         COS_FLAG_RESIDUAL_FALLBACK, 0.0, false, no_refine);
+  }
+  // this sequence is done; whoever finishes the last one leaves the list empty (both control counters at
+  // zero, as every arrival counter is left)
+  if (threadIdx.x == 0) {
+    const unsigned prev = __builtin_amdgcn_atomic_inc32(reinterpret_cast<unsigned*>(p.refine_ctl + kCtrStride),
+                                                        (unsigned)(task.count - 1), __ATOMIC_RELAXED, "agent");
+    if (prev == (unsigned)(task.count - 1))
+      __hip_atomic_store(p.refine_ctl, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
 }
 
 // Acceptance-rate kernel (optional): alpha = sum_x min(q(x), r(x)) of Eq. (7) for
@@ -782,7 +1017,7 @@ __global__ void __launch_bounds__(kThreads) acceptance_rate_kernel(Params p) {
     parts[c].publish(tot);
     wait_stores();
   }
-  int* counter = p.counters + ((size_t)(p.nwin + 1) * p.B + (size_t)b * p.gamma + j) * kCtrStride;
+  int* counter = p.counters + ((size_t)(p.nwin + 3) * p.B + 2 + (size_t)b * p.gamma + j) * kCtrStride;
   if (!arrive_last(counter, p.CA, &s_flag)) return;
   if (threadIdx.x == 0) {
     double tot = 0.0;

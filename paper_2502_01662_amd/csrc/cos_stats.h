@@ -467,6 +467,7 @@ __device__ __forceinline__ void decide_outcome(const Params& p, int b, DecideSha
     plan->bonus = (!residual && p.bonus_idx) ? p.bonus_idx[b] : -1;
     plan->m0 = (CONTRASTIVE && !skip) ? sh.rowmax[jstar - j0] : 0.0f;
     plan->skip = skip;
+    plan->redo = 0;
     sh.jstar = jstar;
     sh.residual = residual;
     sh.pi = plan->pi;

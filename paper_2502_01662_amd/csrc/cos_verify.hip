@@ -67,6 +67,7 @@ struct Tune {
   int sample_blocks = 0;   // 0 = heuristic
   int tail_sequences = -1; // sequences at the end of the grid with shorter chunks (-1 = heuristic, 0 = none)
   int tail_factor = 4;     // how many times shorter
+  int refine_kernels = 0;  // 0 = by the size of a row-set, > 0 = the two refinement launches, < 0 = never
 };
 Tune tune_of(const cos_options_t* o) {
   Tune t;
@@ -75,13 +76,14 @@ Tune tune_of(const cos_options_t* o) {
   t.sample_blocks = o->sample_blocks > 0 ? o->sample_blocks : 0;
   t.tail_sequences = o->tail_sequences == 0 ? -1 : (o->tail_sequences < 0 ? 0 : o->tail_sequences);
   t.tail_factor = o->tail_factor == 0 ? 4 : (o->tail_factor > 1 ? o->tail_factor : 1);
+  t.refine_kernels = o->refine_kernels;
   return t;
 }
 
 struct Plan {
   int nvec, ntiles, nstat;
   size_t off_counters, off_partials, off_rowmax, off_plans, off_tiles, off_lse_all, off_rowmax_all,
-      off_alpha_partials, off_cand, off_cand_count, bytes;
+      off_alpha_partials, off_cand, off_cand_count, off_refine_partials, off_refine_dlse, off_refine_list, bytes;
 };
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -113,6 +115,17 @@ bool shape_ok(int n, int B, int gamma, int V) {
 int alpha_blocks(int B, int gamma, int ntiles);
 
 // Workspace layout for S chunks per row.
+// Launch shape of the refinement kernels: a sequence is split over at most cmax workgroups (eight tiles
+// each at least), the launch has about a thousand workgroups and never fewer than sequences.
+void refine_shape(int B, int ntiles, int* grid, int* cmax) {
+  const int cm = ntiles / 8 > 1 ? ntiles / 8 : 1;
+  const long want = (long)(B > 0 ? B : 1) * cm;
+  int g = (int)(want < 1024 ? want : 1024);
+  if (g < B) g = B;
+  *grid = g;
+  *cmax = cm;
+}
+
 void plan_layout(int n, int B, int gamma, int V, cos_dtype_t dt, cos_combine_t mode, int S,
                  Plan* pl) {
   const int N = dt == COS_DTYPE_F32 ? 4 : 8;
@@ -122,11 +135,19 @@ void plan_layout(int n, int B, int gamma, int V, cos_dtype_t dt, cos_combine_t m
   const size_t g1 = (size_t)gamma + 1;
   size_t at = 0;
   pl->off_counters = at;
-  at += align_up(((size_t)(gamma + 2) * B + (size_t)B * gamma) * kCtrStride * sizeof(int), 256);
+  at += align_up(((size_t)(gamma + 4) * B + 2 + (size_t)B * gamma) * kCtrStride * sizeof(int), 256);
   pl->off_plans = at;
   at += align_up((size_t)B * sizeof(SeqPlan), 256);
   pl->off_tiles = at;
   at += align_up((size_t)B * pl->ntiles * sizeof(double), 256);
+  int rgrid, rcmax;
+  refine_shape(B, pl->ntiles, &rgrid, &rcmax);
+  pl->off_refine_partials = at;
+  at += align_up((size_t)rgrid * (COS_MAX_MODELS + 1) * sizeof(double), 256);
+  pl->off_refine_dlse = at;
+  at += align_up((size_t)B * COS_MAX_MODELS * sizeof(float), 256);
+  pl->off_refine_list = at;
+  at += align_up((size_t)B * sizeof(int), 256);
   pl->off_lse_all = at;
   at += align_up((size_t)B * g1 * pl->nstat * sizeof(double), 256);
   pl->off_rowmax_all = at;
@@ -250,6 +271,7 @@ int alpha_blocks(int B, int gamma, int ntiles) {
 // this grid, as choose_tail makes them for the streaming kernels, were measured and do not pay.)
 void choose_sampling(const Tune& tn, int B, int ntiles, int* C_out, int* tpc_out) {
   const int target = tn.sample_blocks > 0 ? tn.sample_blocks : 1024;
+  if (B < 1) B = 1;  // an empty batch: sized like one sequence, nothing is launched
   int C = (target + B - 1) / B;
   const int cmax = (ntiles + 3) / 4;
   if (C > cmax) C = cmax;
@@ -434,6 +456,10 @@ cos_status_t verify_impl(const void* logits, cos_dtype_t dt, int n, int B, int g
   p.cand_cap = kCandChunk;
   p.plans = reinterpret_cast<SeqPlan*>(wsb + pl.off_plans);
   p.tile_sums = reinterpret_cast<HandOff<double>*>(wsb + pl.off_tiles);
+  p.refine_partials = reinterpret_cast<HandOff<double>*>(wsb + pl.off_refine_partials);
+  p.refine_dlse = reinterpret_cast<float*>(wsb + pl.off_refine_dlse);
+  p.refine_list = reinterpret_cast<int*>(wsb + pl.off_refine_list);
+  refine_shape(B, pl.ntiles, &p.refine_grid, &p.refine_cmax);
   p.alpha = options ? options->alpha : nullptr;
   p.lse_all = reinterpret_cast<double*>(wsb + pl.off_lse_all);
   p.rowmax_all = reinterpret_cast<float*>(wsb + pl.off_rowmax_all);
@@ -444,6 +470,7 @@ cos_status_t verify_impl(const void* logits, cos_dtype_t dt, int n, int B, int g
     p.CA = (pl.ntiles + p.tpa - 1) / p.tpa;  // <= ca
   }
   p.nwin = (gamma + 1 + window - 1) / window;
+  p.refine_ctl = p.counters + (size_t)(p.nwin + 3) * B * kCtrStride;
   p.S = sp.stride;
   p.Sh = sp.Sh;
   p.cvh = sp.cvh;
@@ -498,7 +525,13 @@ cos_status_t verify_impl(const void* logits, cos_dtype_t dt, int n, int B, int g
   lp.ready = (options && options->workspace_ready) ? 1 : 0;
   lp.onepass = (mode == kCd && p.masked && !lp.greedy && !(options && options->two_pass_mask)) ? 1 : 0;
   lp.aligned = aligned ? 1 : 0;
-  lp.counters = ((p.nwin + 1 + (p.alpha ? gamma : 0)) * B) * kCtrStride;
+  // A residual of little mass is drawn from once more in its difference form -- two more passes over the
+  // row-set.  One workgroup alone does that at the rate of one compute unit's arithmetic: fine for a small
+  // row-set, but a stall of the whole call for a large one, and in a large batch some sequence needs it in most calls (a rejection where
+  // the models nearly agree).  Above 256 KiB per row-set two more launches do it with many workgroups per
+  // marked sequence; they cost a few microseconds when no sequence is marked.
+  lp.refine_kernels = tn.refine_kernels > 0 || (tn.refine_kernels == 0 && (size_t)n * V * esize > ((size_t)256 << 10));
+  lp.counters = ((p.nwin + 3 + (p.alpha ? gamma : 0)) * B + 2) * kCtrStride;
   lp.lds = lds;
   lp.stream = st;
   lp.ev_start = ev_start;
@@ -577,6 +610,6 @@ const char* cos_status_string(cos_status_t status) {
   return "unknown status";
 }
 
-int cos_verify_version(void) { return 6; }
+int cos_verify_version(void) { return 7; }
 
 }  // extern "C"

@@ -26,7 +26,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_version_and_status_strings():
-    assert C.cos_verify_version() == 6
+    assert C.cos_verify_version() == 7
     assert C.cos_status_string(0) == "ok"
     for code in range(-10, 0):
         assert C.cos_status_string(code) not in ("ok", "unknown status")
@@ -176,3 +176,12 @@ def test_input_checker_validates_its_own_arguments_on_the_host():
     assert call(2, 1, 0, 256) == -6 and call(2, 1, 0x1010, 256) == -6 and call(2, 1, 0x1000, 16) == -6
     assert call(2, 0, 0, 0) == 0 and bad.value == 0               # empty batch: nothing to check
     assert lib.cos_verify_check_inputs(2, 1, 2, 16, 0x1000, 0x1000, 0x1000, 0x1000, None, 0x1000, 256, None, None) == -1
+
+
+def test_workspace_of_an_empty_batch_and_of_every_refinement_route():
+    """Sizing never divides by the batch size, and does not depend on how residuals of little mass are refined."""
+    for mode, n in ((C.COS_COMBINE_ENSEMBLE, 3), (C.COS_COMBINE_CONTRASTIVE, 2), (C.COS_COMBINE_LOGIT_MIX, 3)):
+        assert C.cos_verify_workspace_bytes(n, 0, 4, 1000, C.COS_DTYPE_BF16, mode) >= 256
+        sizes = {C.cos_verify_workspace_bytes_ex(n, 17, 4, 70000, C.COS_DTYPE_BF16, mode, C.LaunchShape(refine_kernels=r))
+                 for r in (-1, 0, 1)}
+        assert len(sizes) == 1 and min(sizes) > 256

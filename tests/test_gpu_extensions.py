@@ -424,19 +424,23 @@ def _nearly_identical_models(n, B, gamma, V, noise, seed, dtype="f32", proposer=
                                             (C.COS_COMBINE_CONTRASTIVE, [0.002, 0.0], 2),   # mu -> 0: r -> softmax(l_0)
                                             (C.COS_COMBINE_CONTRASTIVE, [0.002, 1e-6], 2),  # the same behind a wide mask
                                             (C.COS_COMBINE_LOGIT_MIX, [0.5, 0.5], 2)])
-def test_residual_of_nearly_identical_models(mode, weights, n, noise):
+@pytest.mark.parametrize("refine_kernels", [0, 1])
+def test_residual_of_nearly_identical_models(mode, weights, n, noise, refine_kernels):
     """Models that differ by a little noise: the residual mass is 1e-2 ... 1e-5 of a probability, far below
     what term-by-term float32 resolves.  The step evaluates such residuals in their difference form by
-    itself (no option): every drawn token must be the float64 reference's, in every combine mode."""
+    itself (no option): every drawn token must be the float64 reference's, in every combine mode -- by the
+    route a row-set of this size takes by default (the sequence's last sampling workgroup alone) and by the
+    two refinement launches that large row-sets take."""
     B, gamma, V = 256, 2, 32000
     inp = _nearly_identical_models(n, B, gamma, V, noise, seed=5, proposer=1 if mode != C.COS_COMBINE_ENSEMBLE else 0)
     diag = C.Diagnostics.allocate(B, gamma, "cuda")
     alen, toks = C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], mode, weights,
-                              inp["u_accept"], inp["u_resample"], diag=diag)
+                              inp["u_accept"], inp["u_resample"], diag=diag,
+                              shape=C.LaunchShape(refine_kernels=refine_kernels) if refine_kernels else None)
     torch.cuda.synchronize()
     rep = P.compare(inp, mode, weights, alen.cpu().numpy(), toks.cpu().numpy(), diag)
     flags = diag.flags.cpu().numpy()
-    print(f"[parity] nearly identical models, noise {noise}, mode {mode}: {rep.summary()}, refined "
+    print(f"[parity] nearly identical models, noise {noise}, mode {mode}, refinement launches {refine_kernels}: {rep.summary()}, refined "
           f"{int((flags & C.COS_FLAG_RESIDUAL_REFINED != 0).sum())}/{B}, median F {np.median(diag.sample_mass.cpu().numpy()):.2e}", flush=True)
     assert rep.ok, rep.failures[:3]
     assert (flags & C.COS_FLAG_RESIDUAL_REFINED != 0).sum() > B // 4
@@ -461,6 +465,78 @@ def test_residual_of_nearly_identical_models_in_16_bit_formats(dtype):
               f"{np.median(diag.sample_mass.cpu().numpy()):.2e}", flush=True)
         assert rep.ok, rep.failures[:3]
         assert rep.excused_accept_ties + rep.excused_cdf_ties <= 3, rep.summary()
+
+
+@pytest.mark.parametrize("mode,weights,n,B,V,dtype", [
+    (C.COS_COMBINE_ENSEMBLE, [0.25, 0.25, 0.25, 0.25], 4, 24, 262144, "bf16"),   # 2 MiB per row-set
+    (C.COS_COMBINE_ENSEMBLE, [0.2] * 5, 5, 12, 150000, "bf16"),                  # the general model count
+    (C.COS_COMBINE_LOGIT_MIX, [0.6, 0.4], 2, 24, 140000, "f32"),
+    (C.COS_COMBINE_CONTRASTIVE, [0.002, 0.0], 2, 24, 300001, "f16"),             # unaligned rows
+])
+def test_large_row_sets_take_the_refinement_launches_by_default(mode, weights, n, B, V, dtype):
+    """Above 256 KiB per row-set the default route is the two refinement launches; both routes must give the
+    reference's tokens and the same outputs as each other (the tile sums do not depend on who computes them)."""
+    gamma = 2
+    inp = _nearly_identical_models(n, B, gamma, V, 0.004, seed=23, dtype=dtype,
+                                   proposer=1 if mode != C.COS_COMBINE_ENSEMBLE else 0)
+    assert n * V * inp["logits"].element_size() > 256 << 10
+    outs = {}
+    for route in (0, -1, 1):
+        diag = C.Diagnostics.allocate(B, gamma, "cuda")
+        alen, toks = C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], mode, weights,
+                                  inp["u_accept"], inp["u_resample"], diag=diag,
+                                  shape=C.LaunchShape(refine_kernels=route) if route else None)
+        torch.cuda.synchronize()
+        outs[route] = (alen.cpu().numpy(), toks.cpu().numpy(), diag.flags.cpu().numpy(), diag.sample_mass.cpu().numpy())
+        rep = P.compare(inp, mode, weights, outs[route][0], outs[route][1], diag)
+        print(f"[parity] large row-set, mode {mode}, n {n}, route {route}: {rep.summary()}, refined "
+              f"{int((outs[route][2] & C.COS_FLAG_RESIDUAL_REFINED != 0).sum())}/{B}", flush=True)
+        assert rep.ok, rep.failures[:3]
+        assert rep.excused_accept_ties + rep.excused_cdf_ties <= 2, rep.summary()
+    assert (outs[0][2] & C.COS_FLAG_RESIDUAL_REFINED != 0).sum() > B // 4
+    for route in (-1, 1):
+        assert np.array_equal(outs[route][0], outs[0][0]) and np.array_equal(outs[route][1], outs[0][1])
+        assert np.array_equal(outs[route][2], outs[0][2])
+        np.testing.assert_allclose(outs[route][3], outs[0][3], rtol=1e-12)
+
+
+def test_refinement_launches_with_more_marked_sequences_than_a_thousand():
+    """Every sequence of a batch of 3000 is marked: the refinement launches then have one workgroup per sequence."""
+    n, B, gamma, V = 2, 3000, 1, 2000
+    inp = _nearly_identical_models(n, B, gamma, V, 0.003, seed=91)
+    inp["shape"] = C.LaunchShape(refine_kernels=1)
+    alen, toks, diag = P.run_gpu(inp, C.COS_COMBINE_ENSEMBLE, [0.5, 0.5])
+    rep = P.compare(inp, C.COS_COMBINE_ENSEMBLE, [0.5, 0.5], alen, toks, diag)
+    flags = diag.flags.cpu().numpy()
+    print(f"[parity] 3000 marked sequences: {rep.summary()}, refined {int((flags & C.COS_FLAG_RESIDUAL_REFINED != 0).sum())}", flush=True)
+    assert rep.ok, rep.failures[:3]
+    assert (flags & C.COS_FLAG_RESIDUAL_REFINED != 0).sum() > 1100          # more than the launch's usual thousand workgroups
+    assert rep.excused_accept_ties + rep.excused_cdf_ties <= B // 50
+
+
+def test_refinement_launches_leave_their_counters_at_zero():
+    """The refinement kernels' arrival counters wrap like the others: a loop that promises a ready workspace
+    gets the same outputs call after call, also when the set of marked sequences changes between calls."""
+    n, B, gamma, V = 3, 40, 2, 20000
+    inp = _nearly_identical_models(n, B, gamma, V, 0.003, seed=77)
+    other = dict(inp)
+    other["u_accept"] = inp["u_accept"].clone()
+    other["u_accept"][::3] = 0.0                     # every third sequence accepts everything: no residual there
+    ws = C.allocate_workspace(n, B, gamma, V, C.COS_DTYPE_F32, C.COS_COMBINE_ENSEMBLE, "cuda")
+    ws.fill_(0xA5)
+    want = {}
+    for name, x in (("all", inp), ("some", other)):
+        a, t = C.cos_verify(x["logits"], x["draft_tokens"], x["proposer_idx"], C.COS_COMBINE_ENSEMBLE, [0.5, 0.3, 0.2],
+                            x["u_accept"], x["u_resample"], shape=C.LaunchShape(refine_kernels=-1))
+        torch.cuda.synchronize()
+        want[name] = (a.cpu().numpy(), t.cpu().numpy())
+    for call, name in enumerate(("all", "some", "all", "all", "some")):
+        x = inp if name == "all" else other
+        a, t = C.cos_verify(x["logits"], x["draft_tokens"], x["proposer_idx"], C.COS_COMBINE_ENSEMBLE, [0.5, 0.3, 0.2],
+                            x["u_accept"], x["u_resample"], workspace=ws,
+                            shape=C.LaunchShape(refine_kernels=1, workspace_ready=1 if call else 0))
+        torch.cuda.synchronize()
+        assert np.array_equal(a.cpu().numpy(), want[name][0]) and np.array_equal(t.cpu().numpy(), want[name][1]), (call, name)
 
 
 # ---------------------------------------------------------------------------

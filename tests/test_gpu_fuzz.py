@@ -213,7 +213,11 @@ def test_random_nearly_identical_models(seed):
         weights = [float(rng.choice([0.0, 0.001, 0.01])), float(rng.choice([0.0, 1e-7, 1e-3]))]
     else:
         weights = rng.dirichlet(np.ones(n) * 3).tolist()                         # a logit-level average of the models
-    desc = dict(noise=noise, mode=mode, n=n, B=B, gamma=gamma, V=V, dtype=dtype, weights=np.round(weights, 4).tolist())
+    route = int(rng.integers(-1, 2))      # the lone workgroup, by size, or the two refinement launches
+    if route:
+        inp["shape"] = C.LaunchShape(refine_kernels=route)
+    desc = dict(noise=noise, mode=mode, n=n, B=B, gamma=gamma, V=V, dtype=dtype, weights=np.round(weights, 4).tolist(),
+                refine_kernels=route)
     alen, toks, diag = P.run_gpu(inp, mode, weights)
     rep = P.compare(inp, mode, weights, alen, toks, diag)
     flags = diag.flags.cpu().numpy()

@@ -397,10 +397,13 @@ def test_residual_without_mass_falls_back_to_r():
     inp["logits"] = inp["logits"].repeat(2, 1, 1, 1).contiguous()
     inp["draft_tokens"][:, 0] = 7
     inp["logits"][:, :, 0, 7] = float("-inf")
-    alen, toks, diag, rep = _check("zero residual mass", inp, C.COS_COMBINE_ENSEMBLE, [0.5, 0.5])
-    assert np.all(alen == 0)
-    assert np.all(diag.flags.cpu().numpy() & C.COS_FLAG_RESIDUAL_FALLBACK)
-    assert rep.flag_mismatches == 0
+    for route in (0, 1):   # by the sequence's last sampling workgroup, by the refinement launches
+        if route:
+            inp["shape"] = C.LaunchShape(refine_kernels=route)
+        alen, toks, diag, rep = _check(f"zero residual mass, refinement launches {route}", inp, C.COS_COMBINE_ENSEMBLE, [0.5, 0.5])
+        assert np.all(alen == 0)
+        assert np.all(diag.flags.cpu().numpy() & C.COS_FLAG_RESIDUAL_FALLBACK)
+        assert rep.flag_mismatches == 0
 
 
 def test_minus_inf_logits_and_extreme_uniforms():
