@@ -208,10 +208,15 @@ cos_status_t cos_verify(const void *logits, cos_dtype_t dt, int n, int B, int ga
  *               The workspace a call needs depends on chunk_vectors and the tail
  *               fields: size it with cos_verify_workspace_bytes_ex and the same
  *               options.
- * two_pass_mask non-zero: the masked contrastive mode (alpha_cd > 0) takes its older
- *               route -- one pass for the expert maxima, one for the masked statistic,
- *               the sampling kernel -- instead of the single read with candidate lists.
- *               Same outputs up to near-ties; kept for comparison and tests.
+ * two_pass_mask the route of the masked contrastive mode (alpha_cd > 0).  0: chosen by
+ *               the width of the mask -- a single read of the logits with candidate lists
+ *               when T ln(1/alpha_cd) <= ln 50 (the usual alpha_cd = 0.1 keeps a few dozen
+ *               tokens of a peaked expert row), else one pass for the expert maxima, one
+ *               for the masked statistic and the sampling kernel, whose cost does not
+ *               depend on how many tokens pass.  > 0: always the two passes; < 0: always
+ *               the single read (a position whose candidates do not fit its lists -- a few
+ *               hundred tokens in the mask -- is then read again by one workgroup alone).
+ *               Same outputs up to near-ties.
  * workspace_ready  non-zero: the caller promises that every arrival counter in the
  *               workspace is zero, which is the case if the workspace was zero-filled,
  *               or if its last use was a completed call of this library with the same

@@ -113,7 +113,7 @@ class LaunchShape:
     sample_blocks: int = 0
     tail_sequences: int = 0     # > 0: that many sequences at the end of the grid; < 0: none
     tail_factor: int = 0        # 0: 4
-    two_pass_mask: int = 0      # 1: masked contrastive mode by its older two-pass route
+    two_pass_mask: int = 0      # masked contrastive mode: > 0 the two-pass route, < 0 the single read, 0 by the mask's width
     workspace_ready: int = 0    # 1: promise that the workspace's arrival counters are zero (skips the clearing kernel)
     refine_kernels: int = 0     # residuals of little mass: > 0 the two refinement launches, < 0 the lone workgroup, 0 by size
 

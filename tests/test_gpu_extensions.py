@@ -642,7 +642,11 @@ def test_masked_contrastive_candidate_lists_and_their_overflow(dtype, flat, alph
     B, gamma, V = 12, 3, 40000
     inp = _masked_inputs(B, gamma, V, dtype, seed=77, flat=flat)
     mode, weights = C.COS_COMBINE_CONTRASTIVE, [0.5, alpha_cd]
+    auto = _check(f"masked {dtype} flat={flat} alpha_cd={alpha_cd}, route by the mask's width", inp, mode, weights)
+    one_read = C.LaunchShape(two_pass_mask=-1)       # (a wide mask takes the two passes by itself)
+    inp["shape"] = one_read
     alen, toks, diag, rep = _check(f"masked one-pass {dtype} flat={flat} alpha_cd={alpha_cd}", inp, mode, weights)
+    assert np.array_equal(auto[0], alen) and np.array_equal(auto[1], toks)
     # the two-pass route gives the same tokens (near-ties aside: none at these seeds)
     a2, t2 = C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], mode, weights, inp["u_accept"],
                           inp["u_resample"], shape=C.LaunchShape(two_pass_mask=1))
@@ -651,7 +655,7 @@ def test_masked_contrastive_candidate_lists_and_their_overflow(dtype, flat, alph
     # acceptance rates from the candidate lists (or the second read) against the oracle's
     alpha = torch.full((B, gamma), -1.0, dtype=torch.float64, device="cuda")
     C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], mode, weights, inp["u_accept"], inp["u_resample"],
-                 alpha=alpha)
+                 alpha=alpha, shape=one_read)
     torch.cuda.synchronize()
     ora = O.verify(W.host_logits(inp["logits"]), P.oracle_dtype(inp["logits"]), inp["draft_tokens"].cpu().numpy(),
                    inp["proposer_idx"].cpu().numpy(), mode, weights, inp["u_accept"].cpu().numpy(),
