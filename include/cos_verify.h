@@ -324,12 +324,36 @@ cos_status_t cos_verify_check_inputs(int n, int B, int gamma, int V, const int32
                                      void *workspace, size_t workspace_bytes, int *bad_entries,
                                      void *hip_stream);
 
+/*
+ * What a call with these arguments would enqueue (host-only; nothing is launched, no pointer
+ * to device memory is needed): for tools, tests and whoever tunes the launch-shape options.
+ * weights as in cos_verify (the contrastive mode's alpha_cd chooses its route); options may be
+ * NULL.  Returns the status cos_verify_ex would return for these arguments, as far as it
+ * depends on them alone.
+ */
+typedef struct cos_launch_info_t {
+  size_t struct_bytes;          /* sizeof(cos_launch_info_t), set by the caller */
+  int streaming_launches;       /* launches that read the logits (more than one: stop_window) */
+  int chunks_per_row;           /* workgroups a row is cut into ... */
+  int chunk_vectors;            /* ... of this many 16-byte vectors each */
+  int tail_sequences;           /* sequences at the end of the grid cut finer ... */
+  int tail_chunks_per_row;      /* ... into this many chunks per row */
+  int sample_workgroups;        /* sampling workgroups per sequence (0: no sampling kernel) */
+  int refine_launches;          /* 1: residuals of little mass go to the two refinement launches */
+  int one_read_mask;            /* 1: masked contrastive mode in one read with candidate lists */
+  int greedy;                   /* 1: temperature 0, one argmax kernel */
+  size_t workspace_bytes;       /* cos_verify_workspace_bytes_ex for these options */
+} cos_launch_info_t;
+cos_status_t cos_verify_launch_info(int n, int B, int gamma, int V, cos_dtype_t dt, cos_combine_t combine_mode,
+                                    const double *weights, const cos_options_t *options,
+                                    cos_launch_info_t *info);
+
 /* Static, NUL-terminated description of a status code. */
 const char *cos_status_string(cos_status_t status);
 
 /* Version of this library's interface: bumped whenever an entry point, an option or a mode is added
- * or changes meaning (6: residuals of little mass are always evaluated in their difference form; launch-shape overrides and
- * timing events are per-call options, the library keeps no settings between calls). */
+ * or changes meaning (7: refine_kernels option and the refinement launches, two_pass_mask with three values,
+ * cos_verify_launch_info). */
 int cos_verify_version(void);
 
 #ifdef __cplusplus

@@ -46,6 +46,13 @@ class CosOptions(ctypes.Structure):
                 ("event_start", ctypes.c_void_p), ("event_stop", ctypes.c_void_p)]
 
 
+class CosLaunchInfo(ctypes.Structure):
+    _fields_ = [("struct_bytes", ctypes.c_size_t), ("streaming_launches", ctypes.c_int), ("chunks_per_row", ctypes.c_int),
+                ("chunk_vectors", ctypes.c_int), ("tail_sequences", ctypes.c_int), ("tail_chunks_per_row", ctypes.c_int),
+                ("sample_workgroups", ctypes.c_int), ("refine_launches", ctypes.c_int), ("one_read_mask", ctypes.c_int),
+                ("greedy", ctypes.c_int), ("workspace_bytes", ctypes.c_size_t)]
+
+
 class CosVerifyError(RuntimeError):
     def __init__(self, status: int, message: str):
         super().__init__(f"cos_verify failed: {message} (status {status})")
@@ -90,6 +97,9 @@ def load_library() -> ctypes.CDLL:
         lib.cos_verify_check_inputs.argtypes = [ci, ci, ci, ci, vp, vp, vp, vp, ctypes.POINTER(CosOptions), vp, sz,
                                                 ctypes.POINTER(ci), vp]
         lib.cos_verify_check_inputs.restype = ci
+        lib.cos_verify_launch_info.argtypes = [ci, ci, ci, ci, ci, ci, ctypes.POINTER(ctypes.c_double),
+                                               ctypes.POINTER(CosOptions), ctypes.POINTER(CosLaunchInfo)]
+        lib.cos_verify_launch_info.restype = ci
         _lib = lib
     return _lib
 
@@ -137,6 +147,19 @@ def cos_verify_workspace_bytes_ex(n: int, B: int, gamma: int, V: int, dt: int, m
                                   shape: Optional[LaunchShape] = None) -> int:
     opt = _options(shape=shape)
     return load_library().cos_verify_workspace_bytes_ex(n, B, gamma, V, dt, mode, ctypes.byref(opt))
+
+
+def cos_verify_launch_info(n: int, B: int, gamma: int, V: int, dt: int, mode: int, weights: Sequence[float],
+                           shape: Optional[LaunchShape] = None, **ext) -> dict:
+    """What a call with these arguments would enqueue (host-only): chunks per row, sampling workgroups, the
+    routes taken.  ``ext``: temperature, stop_window, greedy as for ``cos_verify``."""
+    opt = _options(shape=shape, **ext)
+    info = CosLaunchInfo(ctypes.sizeof(CosLaunchInfo))
+    w = (ctypes.c_double * len(weights))(*[float(x) for x in weights])
+    status = load_library().cos_verify_launch_info(n, B, gamma, V, dt, mode, w, ctypes.byref(opt), ctypes.byref(info))
+    if status != COS_OK:
+        raise CosVerifyError(status, cos_status_string(status))
+    return {name: getattr(info, name) for name, _ in CosLaunchInfo._fields_ if name != "struct_bytes"}
 
 
 def make_events(device=None):

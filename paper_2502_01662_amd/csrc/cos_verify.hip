@@ -182,20 +182,12 @@ void choose_split(const Tune& tn, int rows_total, int nvec, int* S_out, int* cv_
     long s_want = (3072 + rows_total - 1) / (rows_total > 0 ? rows_total : 1);
     if (s_want < 1) s_want = 1;
     cv = (int)((nvec + s_want - 1) / s_want);
-    // never less than one full group of loads per thread (shorter chunks only add hand-offs), and a
-    // whole number of groups: a chunk's last, partly filled group costs a full one
-    constexpr int kGroup = kThreads * kUnroll;
-    cv = cv < kGroup ? kGroup : (cv + kGroup / 2) / kGroup * kGroup;
+    // never less than one full group of loads per thread: shorter chunks only add hand-offs
+    if (cv < kThreads * kUnroll) cv = kThreads * kUnroll;
   }
   cv = (cv + kThreads - 1) / kThreads * kThreads;
   if (cv < kThreads) cv = kThreads;
   int S = (nvec + cv - 1) / cv;
-  if (tn.chunk_vectors <= 0 && S > 1 && nvec - (S - 1) * cv < kThreads * kUnroll / 4) {
-    // a sliver left over for the last chunk is not worth a workgroup of its own
-    --S;
-    cv = ((nvec + S - 1) / S + kThreads - 1) / kThreads * kThreads;
-    S = (nvec + cv - 1) / cv;
-  }
   const int smax = max_splits(nvec);
   if (S > smax) {
     S = smax;
@@ -361,7 +353,9 @@ cos_status_t verify_impl(const void* logits, cos_dtype_t dt, int n, int B, int g
                          const double* u_accept, const double* u_resample,
                          int32_t* accepted_len, int32_t* out_tokens, void* workspace,
                          size_t workspace_bytes, bool builtin_scratch, const cos_diag_t* diag,
-                         const cos_options_t* options, void* hip_stream) {
+                         const cos_options_t* options, void* hip_stream, cos_launch_info_t* info = nullptr) {
+  // info: fill in what the call would enqueue and return before anything touches a device (the
+  // device pointers and the workspace are then not looked at).
   // ---- host-side validation (no HIP call before it passes) ----
   double temperature = 1.0;
   if (options) {
@@ -404,20 +398,22 @@ cos_status_t verify_impl(const void* logits, cos_dtype_t dt, int n, int B, int g
     if (!(weights[1] >= 0.0 && weights[1] <= 1.0)) return COS_ERR_WEIGHTS;
   }
   if (B == 0) return COS_OK;
-  if (!logits || !draft_tokens || !proposer_idx || !u_accept || !u_resample || !accepted_len ||
-      !out_tokens)
+  if (!info && (!logits || !draft_tokens || !proposer_idx || !u_accept || !u_resample || !accepted_len ||
+                !out_tokens))
     return COS_ERR_NULL;
   const size_t esize = dt == COS_DTYPE_F32 ? 4 : 2;
-  if (reinterpret_cast<uintptr_t>(logits) % esize) return COS_ERR_ALIGN;
+  if (!info && reinterpret_cast<uintptr_t>(logits) % esize) return COS_ERR_ALIGN;
   const size_t need = cos_verify_workspace_bytes_ex(n, B, gamma, V, dt, combine_mode, options);
   if ((size_t)(gamma + 1) * (contrastive ? 3 : (mix ? 2 : n)) > kMaxStatsPerSeq) return COS_ERR_SHAPE;
-  if (builtin_scratch) {
+  if (info) {
+    workspace_bytes = need;  // planned as with a workspace of exactly the needed size
+  } else if (builtin_scratch) {
     if (need > (size_t)COS_NOALLOC_SCRATCH_BYTES) return COS_ERR_SCRATCH;
     const cos_status_t rc = scratch_on_current_device(&workspace);
     if (rc != COS_OK) return rc;
     workspace_bytes = COS_NOALLOC_SCRATCH_BYTES;
   }
-  if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256 || workspace_bytes < need)
+  if (!info && (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256 || workspace_bytes < need))
     return COS_ERR_WORKSPACE;
 
   // ---- launch plan ----
@@ -542,6 +538,20 @@ cos_status_t verify_impl(const void* logits, cos_dtype_t dt, int n, int B, int g
   lp.stream = st;
   lp.ev_start = ev_start;
   lp.ev_stop = ev_stop;
+  if (info) {
+    const bool samples = !lp.greedy && !lp.onepass;
+    info->streaming_launches = lp.greedy ? 1 : p.nwin;
+    info->chunks_per_row = p.Sh;
+    info->chunk_vectors = p.cvh;
+    info->tail_sequences = B - p.b_tail;
+    info->tail_chunks_per_row = p.St;
+    info->sample_workgroups = samples ? p.C : 0;
+    info->refine_launches = (samples && lp.refine_kernels) ? 1 : 0;
+    info->one_read_mask = lp.onepass;
+    info->greedy = lp.greedy;
+    info->workspace_bytes = need;
+    return COS_OK;
+  }
   return dt == COS_DTYPE_F32 ? run_f32(p, lp) : (dt == COS_DTYPE_F16 ? run_f16(p, lp) : run_bf16(p, lp));
 }
 
@@ -572,6 +582,16 @@ cos_status_t cos_verify_noalloc(const void* logits, cos_dtype_t dt, int n, int B
 }
 
 size_t cos_verify_noalloc_capacity(void) { return COS_NOALLOC_SCRATCH_BYTES; }
+
+cos_status_t cos_verify_launch_info(int n, int B, int gamma, int V, cos_dtype_t dt, cos_combine_t combine_mode,
+                                    const double* weights, const cos_options_t* options, cos_launch_info_t* info) {
+  if (!info) return COS_ERR_NULL;
+  if (info->struct_bytes != sizeof(cos_launch_info_t)) return COS_ERR_UNSUPPORTED;
+  *info = cos_launch_info_t{};
+  info->struct_bytes = sizeof(cos_launch_info_t);
+  return verify_impl(nullptr, dt, n, B, gamma, V, nullptr, nullptr, combine_mode, weights, nullptr, nullptr, nullptr,
+                     nullptr, nullptr, 0, false, nullptr, options, nullptr, info);
+}
 
 cos_status_t cos_verify_check_inputs(int n, int B, int gamma, int V, const int32_t* draft_tokens,
                                      const int32_t* proposer_idx, const double* u_accept,

@@ -185,3 +185,37 @@ def test_workspace_of_an_empty_batch_and_of_every_refinement_route():
         sizes = {C.cos_verify_workspace_bytes_ex(n, 17, 4, 70000, C.COS_DTYPE_BF16, mode, C.LaunchShape(refine_kernels=r))
                  for r in (-1, 0, 1)}
         assert len(sizes) == 1 and min(sizes) > 256
+
+
+def test_launch_info_whole_rows_routes_and_windows():
+    """What a call would enqueue, without a GPU.  Once a call has thousands of rows a workgroup takes a whole
+    row -- never a long chunk and a sliver (float32 rows of 64000 vectors were once cut into 63488 + 512)."""
+    ens, cd, mix = C.COS_COMBINE_ENSEMBLE, C.COS_COMBINE_CONTRASTIVE, C.COS_COMBINE_LOGIT_MIX
+    for dt, V in ((C.COS_DTYPE_F32, 256000), (C.COS_DTYPE_BF16, 256000), (C.COS_DTYPE_F32, 128256), (C.COS_DTYPE_F16, 152064)):
+        info = C.cos_verify_launch_info(4, 512, 6, V, dt, ens, [0.25] * 4)
+        nvec = -(-V // (4 if dt == C.COS_DTYPE_F32 else 8))
+        assert info["chunks_per_row"] == 1 and info["chunk_vectors"] >= nvec, info
+        assert info["tail_sequences"] > 0 and info["tail_chunks_per_row"] == 4
+        assert info["streaming_launches"] == 1 and info["sample_workgroups"] == 2 and info["refine_launches"] == 1
+        assert info["workspace_bytes"] == C.cos_verify_workspace_bytes(4, 512, 6, V, dt, ens)
+    # a cut row: chunks of at least one full group of loads (2048 vectors), the last one not empty
+    for n, B, gamma, V in ((3, 64, 4, 152064), (2, 16, 5, 128256), (2, 1, 5, 32000), (4, 8, 6, 256000), (2, 40, 3, 50257)):
+        info = C.cos_verify_launch_info(n, B, gamma, V, C.COS_DTYPE_BF16, ens, [1.0 / n] * n)
+        nvec = -(-V // 8)
+        last = nvec - (info["chunks_per_row"] - 1) * info["chunk_vectors"]
+        assert info["chunks_per_row"] > 1 and info["chunk_vectors"] >= 2048 and 0 < last <= info["chunk_vectors"], info
+    # small row-sets keep the lone refinement, windows multiply the streaming launches
+    small = C.cos_verify_launch_info(2, 1, 5, 32000, C.COS_DTYPE_F32, ens, [0.5, 0.5])
+    assert small["refine_launches"] == 0 and small["sample_workgroups"] > 1
+    assert C.cos_verify_launch_info(2, 1, 5, 32000, C.COS_DTYPE_F32, ens, [0.5, 0.5],
+                                    shape=C.LaunchShape(refine_kernels=1))["refine_launches"] == 1
+    assert C.cos_verify_launch_info(2, 8, 5, 32000, C.COS_DTYPE_F32, ens, [0.5, 0.5], stop_window=2)["streaming_launches"] == 3
+    # masked contrastive mode: one read while the mask can be expected to be sparse
+    for alpha_cd, T, one in ((0.1, 1.0, 1), (0.02, 1.0, 1), (0.01, 1.0, 0), (0.1, 2.0, 0), (0.001, 0.5, 1), (0.0, 1.0, 0)):
+        info = C.cos_verify_launch_info(2, 16, 5, 128256, C.COS_DTYPE_BF16, cd, [0.5, alpha_cd], temperature=T)
+        assert info["one_read_mask"] == one and (info["sample_workgroups"] == 0) == bool(one), (alpha_cd, T, info)
+    forced = C.cos_verify_launch_info(2, 16, 5, 128256, C.COS_DTYPE_BF16, cd, [0.5, 0.001], shape=C.LaunchShape(two_pass_mask=-1))
+    assert forced["one_read_mask"] == 1
+    assert C.cos_verify_launch_info(3, 16, 5, 128256, C.COS_DTYPE_BF16, mix, [0.5, 0.3, 0.2], greedy=True)["greedy"] == 1
+    with pytest.raises(C.CosVerifyError):
+        C.cos_verify_launch_info(3, 16, 5, 128256, C.COS_DTYPE_BF16, cd, [0.5, 0.1])
