@@ -671,6 +671,16 @@ __global__ void __launch_bounds__(kThreads) contrastive_finish_kernel(Params p) 
     return;
   }
 
+  if (p.whole_row_bonus && sh.bonus >= 0 && !residual) {
+    // a verifier's own bonus token, large rows: left to refine_draw_kernel, which splits the marked
+    // sequences' rows between a thousand workgroups (this one alone would take tens of microseconds)
+    if (tid == 0) {
+      p.plans[b].redo = kWholeRow;
+      const int slot = __hip_atomic_fetch_add(p.refine_ctl, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      p.refine_list[slot] = b;
+    }
+    return;
+  }
   // general draw: every tile sum of the sampled position by this one workgroup, then as the sampling kernel
   const SeqPlan plan = p.plans[b];  // written by this workgroup in decide_outcome (a barrier since)
   const T* rows[2];

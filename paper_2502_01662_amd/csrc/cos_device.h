@@ -78,11 +78,14 @@ struct SeqPlan {
   float m0;      // contrastive: expert maximum at jstar
   int skip;      // 1: every draft accepted and no extra token wanted: nothing is sampled
   int redo;      // left by the sampling kernel for the refinement kernels: 0 the token is drawn,
-                 // kLittleMass: draw from the residual in its difference form, kNoMass: draw from r
+                 // kLittleMass: draw from the residual in its difference form, kNoMass: draw from r;
+                 // kWholeRow (left by the one-read contrastive mode's finishing kernel): draw a
+                 // verifier's own bonus token from its whole row
   int pad;
   double lse2[COS_MAX_MODELS];  // log2-sum-exp2 of the statistics at jstar
 };
 constexpr int kDrawn = 0, kNoMass = 1, kLittleMass = 2;  // what a draw reports (cos_sample.h)
+constexpr int kWholeRow = 3;  // SeqPlan::redo only: nothing drawn yet, the weights of the plan as they are
 
 struct Params {
   const void* logits;
@@ -113,6 +116,8 @@ struct Params {
   int* refine_list;                  // [B]: the marked sequences, in the order they were marked
   HandOff<double>* refine_partials;  // [refine_grid][COS_MAX_MODELS + 1]: every workgroup's sums of the first pass
   float* refine_dlse;                // [B][COS_MAX_MODELS]: differences of the log-normalisers it gives
+  int whole_row_bonus;               // one-read contrastive mode: a verifier's own bonus token is left to
+                                     // refine_draw_kernel (else the finishing workgroup draws it alone)
   int refine_grid;                   // workgroups of a refinement launch (>= B)
   int refine_cmax;                   // most workgroups one sequence is split over (>= 8 tiles each)
   // acceptance-rate output (optional)

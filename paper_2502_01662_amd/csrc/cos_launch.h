@@ -131,6 +131,12 @@ template <typename T, bool ALIGNED>
 cos_status_t launch_onepass(Params p, const LaunchPlan& lp) {
   const dim3 block(kThreads);
   const int g1 = p.gamma + 1;
+  // Verifier bonus tokens of large rows are drawn by refine_draw_kernel, the only user of counters in this mode.
+  if (p.whole_row_bonus && !lp.ready) {
+    hipLaunchKernelGGL(fill_zero_kernel, dim3((lp.counters + kThreads - 1) / kThreads), block, 0, lp.stream,
+                       p.counters, lp.counters, p.plans, 0);
+    if (hipGetLastError() != hipSuccess) return COS_ERR_LAUNCH;
+  }
   if (lp.ev_start) (void)hipEventRecord(lp.ev_start, lp.stream);
   p.win = 0;
   for (int j0 = 0; j0 < g1; j0 += lp.window, ++p.win) {
@@ -144,6 +150,11 @@ cos_status_t launch_onepass(Params p, const LaunchPlan& lp) {
     if (hipGetLastError() != hipSuccess) return COS_ERR_LAUNCH;
   }
   if (p.win > 1 && lp.ev_stop) (void)hipEventRecord(lp.ev_stop, lp.stream);
+  if (p.whole_row_bonus) {  // (a sequence is decided, hence marked, in one window only: one launch for all)
+    hipLaunchKernelGGL((refine_draw_kernel<T, ALIGNED, 2, kCd>), dim3((unsigned)p.refine_grid), block, lp.lds,
+                       lp.stream, p);
+    if (hipGetLastError() != hipSuccess) return COS_ERR_LAUNCH;
+  }
   return COS_OK;
 }
 

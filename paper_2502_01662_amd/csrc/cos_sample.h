@@ -811,8 +811,9 @@ __global__ void __launch_bounds__(kThreads) refine_sums_kernel(Params p) {
 
 // Refinement, second kernel (the same launch shape and split): the tile sums of a marked sequence once
 // more -- the residual in its difference form with the first kernel's normaliser differences, or r itself
-// where the residual had no mass -- and the draw by the sequence's last workgroup.  The workgroup that
-// finishes the last marked sequence empties the list for the next call.
+// where the residual had no mass, or a verifier's own bonus token that the one-read contrastive mode left
+// undrawn -- and the draw by the sequence's last workgroup.  The workgroup that finishes the last marked
+// sequence empties the list for the next call.
 template <typename T, bool ALIGNED, int NM, int MODE>
 __global__ void __launch_bounds__(kThreads) refine_draw_kernel(Params p) {
   constexpr int N = VecOf<T>::N;
@@ -874,7 +875,8 @@ __global__ void __launch_bounds__(kThreads) refine_draw_kernel(Params p) {
   int status = kDrawn;
   if (wave == 0)
     status = draw_token<T, ALIGNED, NCAP, MODE>(p, b, plan, rows, n, coef, off, ref, tile_sum, little,
-                                                little ? COS_FLAG_RESIDUAL_REFINED : COS_FLAG_RESIDUAL_FALLBACK,
+                                                little ? COS_FLAG_RESIDUAL_REFINED
+                                                       : (plan.redo == kWholeRow ? 0 : COS_FLAG_RESIDUAL_FALLBACK),
                                                 0.0, little, rf);
   if (threadIdx.x == 0) s_flag = status;
   __syncthreads();

@@ -534,6 +534,7 @@ cos_status_t verify_impl(const void* logits, cos_dtype_t dt, int n, int B, int g
   // marked sequence; they cost a few microseconds when no sequence is marked.
   lp.refine_kernels = tn.refine_kernels > 0 || (tn.refine_kernels == 0 && (size_t)n * V * esize > ((size_t)256 << 10));
   lp.counters = ((p.nwin + 3 + (p.alpha ? gamma : 0)) * B + 2) * kCtrStride;
+  p.whole_row_bonus = (lp.onepass && lp.refine_kernels && p.bonus_idx) ? 1 : 0;
   lp.lds = lds;
   lp.stream = st;
   lp.ev_start = ev_start;

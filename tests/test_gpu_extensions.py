@@ -669,7 +669,14 @@ def test_masked_contrastive_candidate_lists_and_their_overflow(dtype, flat, alph
     inp["draft_tokens"][B // 2:] = (inp["logits"][0, B // 2:, :gamma].float() - 0.5 * inp["logits"][1, B // 2:, :gamma].float()).argmax(-1).to(torch.int32)
     for window in (0, 1, 2):
         inp["stop_window"] = window
-        _check(f"masked one-pass {dtype} flat={flat} alpha_cd={alpha_cd} + extensions, window {window}", inp, mode, weights)
+        base = _check(f"masked one-pass {dtype} flat={flat} alpha_cd={alpha_cd} + extensions, window {window}", inp, mode, weights)
+        # a verifier's own bonus token by the finishing workgroup alone, and by the cooperative draw kernel
+        for route in (-1, 1):
+            inp["shape"] = C.LaunchShape(two_pass_mask=-1, refine_kernels=route)
+            other = _check(f"masked one-pass {dtype} flat={flat} alpha_cd={alpha_cd} + extensions, window {window}, "
+                           f"refinement launches {route}", inp, mode, weights)
+            assert np.array_equal(other[0], base[0]) and np.array_equal(other[1], base[1])
+        inp["shape"] = one_read
 
 
 def test_masked_contrastive_is_deterministic():
