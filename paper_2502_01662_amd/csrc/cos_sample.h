@@ -792,13 +792,23 @@ __global__ void __launch_bounds__(kThreads) refine_sums_kernel(Params p) {
   wait_stores();
   if (!arrive_last(p.counters + ((size_t)(p.nwin + 1) * p.B + b) * kCtrStride, task.cr, &s_flag)) return;
 
-  // last workgroup of the sequence: Z_t / Z_pi - 1 for every term, then the log-normaliser differences
+  // last workgroup of the sequence: the workgroups' sums added up (one partial per thread, so that the
+  // reads are in flight together; wave_sum adds in a fixed order), Z_t / Z_pi - 1 for every term, then the
+  // log-normaliser differences
+#pragma unroll
+  for (int k = 0; k <= NCAP; ++k) {
+    double v = 0.0;
+    for (int i = threadIdx.x; i < task.cr; i += kThreads) v += parts[(size_t)i * NS + k].read();
+    v = wave_sum(v);
+    if (lane == 0) s_part[wave][k] = v;
+  }
+  __syncthreads();
   if (threadIdx.x < NCAP) {
     const int m = threadIdx.x;
     double q = 0.0, a = 0.0;
-    for (int i = 0; i < task.cr; ++i) {
-      q += parts[(size_t)i * NS].read();
-      a += parts[(size_t)i * NS + 1 + m].read();
+    for (int w = 0; w < kWaves; ++w) {
+      q += s_part[w][0];
+      a += s_part[w][1 + m];
     }
     const double ratio = a / q;
     const bool used = MODE == kEns ? rf.w[m] != 0.0f : m == 0;
