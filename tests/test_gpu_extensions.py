@@ -514,6 +514,47 @@ def test_refinement_launches_with_more_marked_sequences_than_a_thousand():
     assert rep.excused_accept_ties + rep.excused_cdf_ties <= B // 50
 
 
+def test_refinement_launches_in_a_captured_graph():
+    """The refinement route under HIP graph capture: the list of marked sequences is built by atomics and
+    emptied by the last workgroup, so every replay (eager work and garbage in the workspace in between) must
+    reproduce the eager result."""
+    n, B, gamma, V = 2, 24, 2, 70000
+    inp = _nearly_identical_models(n, B, gamma, V, 0.003, seed=61)
+    ws = C.allocate_workspace(n, B, gamma, V, C.COS_DTYPE_F32, C.COS_COMBINE_ENSEMBLE, "cuda")
+    alen = torch.empty(B, dtype=torch.int32, device="cuda")
+    toks = torch.empty((B, gamma + 1), dtype=torch.int32, device="cuda")
+    diag = C.Diagnostics.allocate(B, gamma, "cuda")
+
+    def call():
+        C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], C.COS_COMBINE_ENSEMBLE, [0.5, 0.5],
+                     inp["u_accept"], inp["u_resample"], accepted_len=alen, out_tokens=toks, workspace=ws, diag=diag)
+
+    assert C.cos_verify_launch_info(n, B, gamma, V, C.COS_DTYPE_F32, C.COS_COMBINE_ENSEMBLE, [0.5, 0.5])["refine_launches"] == 1
+    call()
+    torch.cuda.synchronize()
+    want = (alen.cpu().numpy().copy(), toks.cpu().numpy().copy())
+    assert (diag.flags.cpu().numpy() & C.COS_FLAG_RESIDUAL_REFINED != 0).sum() > B // 4
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        call()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        call()
+    for i in range(4):
+        alen.fill_(-5)
+        toks.fill_(-5)
+        ws.fill_(i + 1)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(alen.cpu().numpy(), want[0]) and np.array_equal(toks.cpu().numpy(), want[1]), i
+    rep = P.compare(inp, C.COS_COMBINE_ENSEMBLE, [0.5, 0.5], want[0], want[1], None)
+    assert rep.ok, rep.failures[:3]
+
+
 def test_refinement_launches_leave_their_counters_at_zero():
     """The refinement kernels' arrival counters wrap like the others: a loop that promises a ready workspace
     gets the same outputs call after call, also when the set of marked sequences changes between calls."""
