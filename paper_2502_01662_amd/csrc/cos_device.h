@@ -161,8 +161,8 @@ struct LaunchPlan {
   int greedy;       // temperature 0: one argmax kernel instead
   int onepass;      // masked contrastive mode in one read of the logits (candidate lists), no counters
   int ready;        // the caller promises zeroed arrival counters: no clearing kernel
-  int refine_kernels;  // residuals of little mass are drawn from by two more launches of the sampling
-                       // grid (which do nothing when no sequence needs them) instead of by one workgroup
+  int refine_kernels;  // residuals of little mass are drawn from by two more launches (which do nothing
+                       // when no sequence needs them) instead of by one workgroup
   int aligned;      // every row starts on a 16-byte boundary and V is a multiple of the vector width
   int counters;     // arrival counters (ints, with their stride) the fill kernel clears
   size_t lds;       // dynamic LDS of the sampling kernel (one double per tile)

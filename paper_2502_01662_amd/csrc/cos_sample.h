@@ -501,32 +501,29 @@ __device__ int draw_token(const Params& p, int b, const SeqPlan& plan, const T* 
   return kDrawn;
 }
 
-// With every tile sum of the sampled position in tile_sum (LDS), the whole workgroup draws the
-// sequence's token: the scan and the inverse CDF, and the two rare endings -- a residual of little
-// mass (r close to q) is evaluated once more in its difference form, a residual without mass falls
-// back to r.  Each ending recomputes every tile sum in this one workgroup.
-// One workgroup over every tile of a row-set, TB tiles per wavefront in flight (all loads issued before
-// the first is used): body(t, x) for this wavefront's tiles t = wave, wave + kWaves, ...
-template <typename T, bool ALIGNED, int NCAP, int TB, class Body>
+// One workgroup over every tile of a row-set: body(t, x) for this wavefront's tiles t = wave,
+// wave + kWaves, ...  (One tile per wavefront in flight: these passes are bound by the one workgroup's
+// arithmetic, not by its loads; more in flight only cost the sampling kernel registers.)
+template <typename T, bool ALIGNED, int NCAP, class Body>
 __device__ __forceinline__ void for_each_tile(const Params& p, const T* const (&rows)[NCAP], int n, Body&& body) {
   constexpr int N = VecOf<T>::N;
-  const int wave = threadIdx.x >> 6;
-  for (int t0 = wave; t0 < p.ntiles; t0 += kWaves * TB) {
-    float x[TB][NCAP][N];
-#pragma unroll
-    for (int i = 0; i < TB; ++i) tile_load<T, ALIGNED, NCAP>(p, rows, n, min(t0 + i * kWaves, p.ntiles - 1), x[i]);
-#pragma unroll
-    for (int i = 0; i < TB; ++i)
-      if (t0 + i * kWaves < p.ntiles) body(t0 + i * kWaves, x[i]);
+  for (int t = threadIdx.x >> 6; t < p.ntiles; t += kWaves) {
+    float x[NCAP][N];
+    tile_load<T, ALIGNED, NCAP>(p, rows, n, t, x);
+    body(t, x);
   }
 }
 
+// With every tile sum of the sampled position in tile_sum (LDS), the whole workgroup draws the
+// sequence's token: the scan and the inverse CDF, and the two rare endings -- a residual of little
+// mass (r close to q) is evaluated once more in its difference form, a residual without mass falls
+// back to r.  Each ending recomputes every tile sum in this one workgroup (small row-sets, and the
+// finishing kernel of the one-read contrastive mode; large row-sets: the refinement kernels below).
 template <typename T, bool ALIGNED, int NCAP, int MODE>
 __device__ __forceinline__ void finish_draw(const Params& p, int b, const SeqPlan& plan, const T* const (&rows)[NCAP],
                                             int n, float (&coef)[NCAP], float (&off)[NCAP], const float (&ref)[NCAP],
                                             double* tile_sum, int& s_flag, Refine<NCAP>& s_rf) {
   constexpr int N = VecOf<T>::N;
-    constexpr int TB = 1;  // (the passes are bound by this one workgroup's arithmetic, not by its loads in flight)
   const int lane = lane_id();
   const int wave = threadIdx.x >> 6;
   const Refine<NCAP> no_refine = {};  // the plain, term-by-term evaluation
@@ -557,7 +554,7 @@ __device__ __forceinline__ void finish_draw(const Params& p, int b, const SeqPla
       double Q = 0.0, A[NCAP];
 #pragma unroll
       for (int m = 0; m < NCAP; ++m) A[m] = 0.0;
-      for_each_tile<T, ALIGNED, NCAP, TB>(p, rows, n, [&](int t, const float (&x)[NCAP][N]) {
+      for_each_tile<T, ALIGNED, NCAP>(p, rows, n, [&](int t, const float (&x)[NCAP][N]) {
         if (t * 64 + lane < p.nvec) refine_sums<T, NCAP, N, MODE>(p, x, n, plan.pi, plan.m0, ref, rf, Q, A);
       });
       // the tile sums are not needed any more: their LDS takes the wavefronts' totals
@@ -585,7 +582,7 @@ __device__ __forceinline__ void finish_draw(const Params& p, int b, const SeqPla
       }
       __syncthreads();
     }
-    for_each_tile<T, ALIGNED, NCAP, TB>(p, rows, n, [&](int t, const float (&x)[NCAP][N]) {
+    for_each_tile<T, ALIGNED, NCAP>(p, rows, n, [&](int t, const float (&x)[NCAP][N]) {
       float f[N];
       tile_eval<T, NCAP, MODE>(p, x, n, t, plan.pi, plan.bonus, plan.m0, coef, off, ref, f, true, rf);
       const double ts = wave_sum(lane_mass<N>(f));
@@ -603,7 +600,7 @@ __device__ __forceinline__ void finish_draw(const Params& p, int b, const SeqPla
   // The residual has no mass (cannot happen in exact arithmetic): draw from r
   // itself.  Rare, so this one workgroup recomputes every tile sum.
   plan_coefficients<NCAP, MODE>(p, plan, false, n, coef, off);
-  for_each_tile<T, ALIGNED, NCAP, TB>(p, rows, n, [&](int t, const float (&x)[NCAP][N]) {
+  for_each_tile<T, ALIGNED, NCAP>(p, rows, n, [&](int t, const float (&x)[NCAP][N]) {
     float f[N];
     tile_eval<T, NCAP, MODE>(p, x, n, t, plan.pi, plan.bonus, plan.m0, coef, off, ref, f, false, no_refine);
     const double ts = wave_sum(lane_mass<N>(f));
@@ -620,7 +617,7 @@ __device__ __forceinline__ void finish_draw(const Params& p, int b, const SeqPla
 // A residual of little mass (r close to q) is evaluated once more in its difference form: by the last
 // workgroup of its sequence alone (LONE; two more passes over the row-set at the rate of one
 // workgroup, which is fine for small row-sets), or -- the sequence only marked here -- by the two
-// refinement kernels below, which every sampling workgroup of the sequence takes part in.
+// refinement kernels below, which split the marked sequences between about a thousand workgroups.
 template <typename T, bool ALIGNED, int NM, int MODE, bool LONE>
 __global__ void __launch_bounds__(kThreads) sample_kernel(Params p) {
   constexpr int N = VecOf<T>::N;
