@@ -163,14 +163,17 @@ def test_random_greedy_configuration(seed):
 
 @pytest.mark.parametrize("seed", range(40))
 def test_random_configuration_with_random_chunking(seed):
-    """The same random cases with the launch shape drawn at random as well: chunk length, and how many
-    of the last sequences of the grid get how much shorter chunks.  Outputs must not depend on it."""
+    """The same random cases with the launch shape drawn at random as well: chunk length, how many of the last
+    sequences of the grid get how much shorter chunks, the route of the masked contrastive mode and who refines
+    residuals of little mass.  Outputs must not depend on it."""
     inp, mode, weights, desc = _case(15000 + seed)
     rng = np.random.default_rng(16000 + seed)
     if mode == C.COS_COMBINE_ENSEMBLE and rng.integers(0, 2):
         mode, weights = C.COS_COMBINE_LOGIT_MIX, np.abs(rng.normal(0.5, 0.5, desc["n"])).tolist()
-    knobs = (int(rng.choice([0, 256, 512, 1024, 2048])), int(rng.integers(0, desc["B"] + 2)), int(rng.choice([1, 2, 3, 4, 8, 16])))
-    inp["shape"] = C.LaunchShape(chunk_vectors=knobs[0], tail_sequences=knobs[1] if knobs[1] else -1, tail_factor=knobs[2])
+    knobs = (int(rng.choice([0, 256, 512, 1024, 2048])), int(rng.integers(0, desc["B"] + 2)), int(rng.choice([1, 2, 3, 4, 8, 16])),
+             int(rng.integers(-1, 2)), int(rng.integers(-1, 2)))      # ... and the routes of a wide mask and of small residuals
+    inp["shape"] = C.LaunchShape(chunk_vectors=knobs[0], tail_sequences=knobs[1] if knobs[1] else -1, tail_factor=knobs[2],
+                                 two_pass_mask=knobs[3], refine_kernels=knobs[4])
     alen, toks, diag = P.run_gpu(inp, mode, weights)
     rep = P.compare(inp, mode, weights, alen, toks, diag)
     print(f"[fuzz] chunking {knobs} {desc}: {rep.summary()}", flush=True)
