@@ -232,6 +232,8 @@ struct FinishShared {
   float ref[kWin][2];    // row references per position
   int total[kWin];       // candidates per position before the test against the true maximum
   int off[kWin + 1];     // segment of each position in list
+  int toff[kWin + 1];    // prefix of `total`: where each position's candidates start among all the window's
+  int recount;           // 1: the totals do not fit the list; the segments are sized by the masked tokens
   int n[kWin];           // masked tokens per position
   int slow[kWin];        // 1: the position's candidates did not fit
   int flag;
@@ -460,25 +462,24 @@ __global__ void __launch_bounds__(kThreads) contrastive_finish_kernel(Params p) 
     }
   }
   __syncthreads();
-  // 2. a segment of the list for every position (those that do not fit any more take the slow route)
+  // 2. a segment of the list for every position.  What the chunks left passes the test against their own
+  //    maxima, the segments need only hold what passes against the position's: when the former do not fit
+  //    (many chunks of a huge vocabulary, many positions), the sweep below first only counts.
   if (tid == 0) {
     int at = 0;
     for (int jj = 0; jj < nj; ++jj) {
-      fs.off[jj] = at;
-      if (at + fs.total[jj] > kCandRow) {
-        fs.slow[jj] = 1;
-        fs.total[jj] = 0;
-      }
+      fs.toff[jj] = fs.off[jj] = at;
       at += fs.total[jj];
     }
-    fs.off[nj] = at;
+    fs.toff[nj] = fs.off[nj] = at;
+    fs.recount = at > kCandRow;
   }
   __syncthreads();
   // 3. every chunk's candidates, tested against the position's true maximum, into the segments: entry
-  //    e of the window's candidates belongs to the position whose segment holds e and to the chunk
-  //    whose prefix holds the rest; four entries per thread at a time, their loads independent.
-  {
-    const int all = fs.off[nj];
+  //    e of the window's candidates belongs to the position whose stretch of the totals holds e and to
+  //    the chunk whose prefix holds the rest; four entries per thread at a time, their loads independent.
+  auto sweep = [&](bool count_only) {
+    const int all = fs.toff[nj];
     constexpr int R = 4;
     for (int e0 = tid; e0 < all; e0 += kThreads * R) {
       Cand c[R];
@@ -491,8 +492,8 @@ __global__ void __launch_bounds__(kThreads) contrastive_finish_kernel(Params p) 
         c[r].l0 = c[r].l1 = 0.0f;
         if (e < all) {
           int jj = 0;
-          while (fs.off[jj + 1] <= e) ++jj;  // (empty segments are skipped: their end is not above e)
-          const int within = e - fs.off[jj];
+          while (fs.toff[jj + 1] <= e) ++jj;  // (empty stretches are skipped: their end is not above e)
+          const int within = e - fs.toff[jj];
           const int* pre = fs.pre + jj * Sb;
           int lo = 0, hi = Sb - 1;  // last chunk whose prefix is <= within
           while (lo < hi) {
@@ -506,10 +507,27 @@ __global__ void __launch_bounds__(kThreads) contrastive_finish_kernel(Params p) 
       }
 #pragma unroll
       for (int r = 0; r < R; ++r)
-        if (seg[r] >= 0 && in_mask<T>(c[r].l0, fs.m0[seg[r]], p.thr32, p.thr64))
-          fs.list[fs.off[seg[r]] + atomicAdd(&fs.n[seg[r]], 1)] = c[r];
+        if (seg[r] >= 0 && !fs.slow[seg[r]] && in_mask<T>(c[r].l0, fs.m0[seg[r]], p.thr32, p.thr64)) {
+          const int at = atomicAdd(&fs.n[seg[r]], 1);
+          if (!count_only) fs.list[fs.off[seg[r]] + at] = c[r];
+        }
     }
+  };
+  if (fs.recount) {  // uniform over the workgroup
+    sweep(true);
+    __syncthreads();
+    if (tid == 0) {  // segments by the masked tokens; a position that still does not fit takes the slow route
+      int at = 0;
+      for (int jj = 0; jj < nj; ++jj) {
+        fs.off[jj] = at;
+        if (at + fs.n[jj] > kCandRow) fs.slow[jj] = 1; else at += fs.n[jj];
+        fs.n[jj] = 0;
+      }
+      fs.off[nj] = at;
+    }
+    __syncthreads();
   }
+  sweep(false);
   __syncthreads();
   // 4. per position (a wavefront each): the masked normaliser and the acceptance rate
   for (int jj = wave; jj < nj; jj += kWaves) {

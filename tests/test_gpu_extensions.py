@@ -720,6 +720,33 @@ def test_masked_contrastive_candidate_lists_and_their_overflow(dtype, flat, alph
         inp["shape"] = one_read
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_masked_contrastive_with_many_chunks_of_a_huge_vocabulary(dtype):
+    """Eight positions of 600 000 tokens in 37 chunks each: what the chunks leave (every token within reach of its
+    own chunk's maximum: thousands per sequence) does not fit the finishing workgroup's list, what passes against
+    the rows' true maxima (a few dozen per position) does -- the list is sized by a first counting sweep."""
+    B, gamma, V = 4, 7, 600000
+    inp = _masked_inputs(B, gamma, V, dtype, seed=131)
+    inp["shape"] = C.LaunchShape(two_pass_mask=-1)
+    mode, weights = C.COS_COMBINE_CONTRASTIVE, [0.5, 0.1]
+    info = C.cos_verify_launch_info(2, B, gamma, V, {"bf16": C.COS_DTYPE_BF16, "f32": C.COS_DTYPE_F32}[dtype], mode, weights,
+                                    shape=inp["shape"])
+    assert info["one_read_mask"] == 1 and info["chunks_per_row"] >= 30
+    alen, toks, diag, rep = _check(f"masked one-pass {dtype}, 600k tokens in {info['chunks_per_row']} chunks", inp, mode, weights)
+    alpha = torch.full((B, gamma), -1.0, dtype=torch.float64, device="cuda")
+    C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], mode, weights, inp["u_accept"], inp["u_resample"],
+                 alpha=alpha, shape=inp["shape"])
+    torch.cuda.synchronize()
+    ora = O.verify(W.host_logits(inp["logits"]), P.oracle_dtype(inp["logits"]), inp["draft_tokens"].cpu().numpy(),
+                   inp["proposer_idx"].cpu().numpy(), mode, weights, inp["u_accept"].cpu().numpy(),
+                   inp["u_resample"].cpu().numpy(), all_positions=True, want_alpha=True)
+    assert np.abs(alpha.cpu().numpy() - ora.alpha).max() < 1e-6
+    two = C.cos_verify(inp["logits"], inp["draft_tokens"], inp["proposer_idx"], mode, weights, inp["u_accept"],
+                       inp["u_resample"], shape=C.LaunchShape(two_pass_mask=1))
+    torch.cuda.synchronize()
+    assert np.array_equal(two[0].cpu().numpy(), alen) and np.array_equal(two[1].cpu().numpy(), toks)
+
+
 def test_masked_contrastive_is_deterministic():
     """Candidates are collected in whatever order the wavefronts find them and sorted by token before anything
     is summed: two calls give the same bits, diagnostics included."""
