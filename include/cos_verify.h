@@ -210,7 +210,7 @@ cos_status_t cos_verify(const void *logits, cos_dtype_t dt, int n, int B, int ga
  *               options.
  * two_pass_mask the route of the masked contrastive mode (alpha_cd > 0).  0: chosen by
  *               the width of the mask -- a single read of the logits with candidate lists
- *               when T ln(1/alpha_cd) <= ln 50 (the usual alpha_cd = 0.1 keeps a few dozen
+ *               when T ln(1/alpha_cd) <= ln 25 (the usual alpha_cd = 0.1 keeps a few dozen
  *               tokens of a peaked expert row), else one pass for the expert maxima, one
  *               for the masked statistic and the sampling kernel, whose cost does not
  *               depend on how many tokens pass.  > 0: always the two passes; < 0: always

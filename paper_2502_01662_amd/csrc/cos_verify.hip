@@ -520,11 +520,12 @@ cos_status_t verify_impl(const void* logits, cos_dtype_t dt, int n, int B, int g
   lp.greedy = (options && options->greedy) ? 1 : 0;
   lp.ready = (options && options->workspace_ready) ? 1 : 0;
   // Masked contrastive mode: one read with candidate lists while the mask can be expected to be sparse --
-  // tokens within T ln(1/alpha_cd) <= ln 50 of the expert's maximum; the usual alpha_cd = 0.1 keeps a few
+  // tokens within T ln(1/alpha_cd) <= ln 25 of the expert's maximum; the usual alpha_cd = 0.1 keeps a few
   // dozen -- else the two-pass route, whose cost does not depend on how many tokens pass (a position whose
-  // candidates do not fit is read again by one workgroup alone in the one-read route).
+  // candidates do not fit is read again by one workgroup alone in the one-read route; measured on Gaussian
+  // logits the routes cross at alpha_cd = 0.03, some 80 tokens per position).
   const int route = options ? options->two_pass_mask : 0;
-  const bool sparse_mask = p.thr64 >= -3.912023005428146;
+  const bool sparse_mask = p.thr64 >= -3.21888;  // ln 25, a hair wider so that alpha_cd = 0.04 is in
   lp.onepass = (mode == kCd && p.masked && !lp.greedy && (route < 0 || (route == 0 && sparse_mask))) ? 1 : 0;
   lp.aligned = aligned ? 1 : 0;
   // A residual of little mass is drawn from once more in its difference form -- two more passes over the

@@ -211,7 +211,7 @@ def test_launch_info_whole_rows_routes_and_windows():
                                     shape=C.LaunchShape(refine_kernels=1))["refine_launches"] == 1
     assert C.cos_verify_launch_info(2, 8, 5, 32000, C.COS_DTYPE_F32, ens, [0.5, 0.5], stop_window=2)["streaming_launches"] == 3
     # masked contrastive mode: one read while the mask can be expected to be sparse
-    for alpha_cd, T, one in ((0.1, 1.0, 1), (0.02, 1.0, 1), (0.01, 1.0, 0), (0.1, 2.0, 0), (0.001, 0.5, 1), (0.0, 1.0, 0)):
+    for alpha_cd, T, one in ((0.1, 1.0, 1), (0.05, 1.0, 1), (0.03, 1.0, 0), (0.1, 2.0, 0), (0.002, 0.5, 1), (0.0, 1.0, 0)):
         info = C.cos_verify_launch_info(2, 16, 5, 128256, C.COS_DTYPE_BF16, cd, [0.5, alpha_cd], temperature=T)
         assert info["one_read_mask"] == one and (info["sample_workgroups"] == 0) == bool(one), (alpha_cd, T, info)
     forced = C.cos_verify_launch_info(2, 16, 5, 128256, C.COS_DTYPE_BF16, cd, [0.5, 0.001], shape=C.LaunchShape(two_pass_mask=-1))
