@@ -139,7 +139,11 @@ cos_status_t cos_verify(const void *logits, cos_dtype_t dt, int n, int B, int ga
  * temperature   T > 0 divides every logit before every softmax (Sec. 4.1 runs
  *               T = 1; how T enters Eq. (5) is not stated: it divides both l^p
  *               and l^q, so the mask reads s_0 >= alpha_cd max s_0 at that T).
- *               0 means 1.  Negative or non-finite: COS_ERR_WEIGHTS.
+ *               0 means 1.  Negative or non-finite: COS_ERR_WEIGHTS.  The ensemble
+ *               keeps its accuracy (r(d), q(d) to 1e-7) at every T; the logit-level
+ *               modes round their combination to float32 before it is divided by
+ *               T, so their relative error is about 1e-6 / T: inside 1e-5 for
+ *               T >= 0.15 (for T -> 0 there is `greedy`, which is exact).
  * bonus_idx     DEVICE [B] int32 or NULL.  bonus_idx[b] = v >= 0: when every
  *               draft of the row is accepted, the extra token is drawn from
  *               the verifier's own distribution s_v (Sec. 3.1, Sec. 3.3:
